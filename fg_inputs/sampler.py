@@ -1,0 +1,88 @@
+"""Uniform neighbour sampler producing the layered mini-batch both sides consume.
+
+Layout of a sampled L-layer mini-batch (layer L = seeds, layer 0 = input nodes):
+
+* `ids[l]`, l = 0..L: distinct node ids of layer l (int32). Layer l-1 starts
+  with the nodes of layer l in the same order (a node needs its own previous
+  embedding), followed by newly sampled neighbours in order of first occurrence.
+* block l, l = 1..L, connects layer l-1 (sources) to layer l (rows) with two
+  row arrays: the neighbours of row j are `col[l][start[l][j] : end[l][j]]`,
+  each a position into `ids[l-1]`. Setting `end[j] = start[j]` removes the
+  neighbours of row j without touching `col`.
+
+Per row, min(degree, fanout) neighbour slots are chosen (all of them when the
+degree does not exceed the fan-out, otherwise one slot from each of `fanout`
+equal strata of the slot range, which gives every slot the same inclusion
+probability); self loops and repeated neighbours within the row are dropped.
+`fanouts` lists the fan-out from the input side to the seed side: block l uses
+`fanouts[l - 1]`.
+
+This is input generation only; it contains none of the cache or model logic.
+"""
+from dataclasses import dataclass, field
+from typing import List, Optional
+
+import numpy as np
+
+from . import rng
+
+
+@dataclass
+class MiniBatch:
+    num_layers: int
+    ids: List[np.ndarray]                      # index 0..L
+    start: List[Optional[np.ndarray]]          # index 1..L (0 unused)
+    end: List[Optional[np.ndarray]]
+    col: List[Optional[np.ndarray]]
+    meta: dict = field(default_factory=dict)
+
+    def copy(self):
+        cp = lambda xs: [None if x is None else x.copy() for x in xs]
+        return MiniBatch(self.num_layers, cp(self.ids), cp(self.start), cp(self.end), cp(self.col), dict(self.meta))
+
+
+def sample_minibatch(graph, seeds, fanouts, key):
+    L = len(fanouts)
+    ids = [None] * (L + 1)
+    start = [None] * (L + 1)
+    end = [None] * (L + 1)
+    col = [None] * (L + 1)
+    cur = np.asarray(seeds, dtype=np.int64)
+    assert np.unique(cur).shape[0] == cur.shape[0], "seed nodes must be distinct"
+    ids[L] = cur
+    for l in range(L, 0, -1):
+        f = int(fanouts[l - 1])
+        n = cur.shape[0]
+        deg = graph.degree(cur)
+        j = np.arange(f, dtype=np.int64)[None, :]
+        u = rng.uniform(rng.u64_2(rng.make_key(key, l), cur[:, None], j))
+        strat = np.floor((j + u) * (deg[:, None].astype(np.float64) / f)).astype(np.int64)
+        slot = np.where(deg[:, None] <= f, j, strat)
+        valid = j < np.minimum(deg, f)[:, None]
+        slot = np.where(valid, np.minimum(slot, np.maximum(deg[:, None] - 1, 0)), 0)
+        nb = np.where(valid, graph.neighbour(np.broadcast_to(cur[:, None], slot.shape), slot), -1)
+        valid &= nb != cur[:, None]
+        for a in range(1, f):
+            for b in range(a):
+                valid[:, a] &= ~(valid[:, b] & (nb[:, a] == nb[:, b]))
+        cnt = valid.sum(axis=1)
+        st = np.zeros(n, dtype=np.int64)
+        if n:
+            st[1:] = np.cumsum(cnt)[:-1]
+        cand = nb[valid]
+        allv = np.concatenate([cur, cand])
+        uniq, first, inv = np.unique(allv, return_index=True, return_inverse=True)
+        order = np.argsort(first, kind="stable")
+        pos_of_uniq = np.empty(uniq.shape[0], dtype=np.int64)
+        pos_of_uniq[order] = np.arange(uniq.shape[0], dtype=np.int64)
+        pos = pos_of_uniq[inv]
+        prev = uniq[order]
+        assert prev.shape[0] < 2 ** 31 and cand.shape[0] < 2 ** 31
+        start[l] = st.astype(np.int32)
+        end[l] = (st + cnt).astype(np.int32)
+        col[l] = pos[n:].astype(np.int32)
+        ids[l - 1] = prev
+        cur = prev
+    ids = [x.astype(np.int32) for x in ids]
+    return MiniBatch(L, ids, start, end, col)
+

@@ -1,0 +1,336 @@
+"""Plain CPU statement of one training iteration's data path with a selective
+historical-embedding cache (Algorithm 1 of the paper), used ONLY to check the
+GPU library: test infrastructure, never part of the product path. Nothing here
+is imported by the library or its Python binding, and nothing here imports them.
+
+The method is an approximation scheme (Eq. 2: cached embeddings stand in for
+recomputed ones), so this file is the algorithm itself, step by step, in the
+paper's order and notation, with floating point carried in float64 and rounded
+once to the storage type:
+
+  top-down   (Alg. 1, the lookup / remove_subgraph / V_normal lines): `lookup_prune`
+  loader     (Alg. 1, Load_feature line; Section 6, one-sided reads): `gather`
+  bottom-up  (Alg. 1, the cache fetch line and the f_W line; Eq. 1): `gather`,
+             `aggregate`, `linear`
+  update     (Alg. 1, Update line; Sections 4.1.1, 4.1.2, 4.2): `cache_update`
+
+Where the paper leaves something open (the Update procedure has no printed body;
+mini-batch layout; percentile ties; slot capacity) the reading taken is stated in
+the docstring of the function concerned.
+
+Pins (tests marked "not gpu"): dense whole-graph recursion of Eq. 1 on small
+graphs with full neighbourhoods; closed forms of the mean; identity-panel
+weights; a depth-first "needed set" for the pruning; a dictionary model of the
+cache; hand-worked admit/evict/staleness/ring traces; the degenerate settings of
+Section 4.1.3. The I/O-saving percentages the paper reports depend on its
+datasets and real gradients: parity unpinned for those, they are not reproduced.
+"""
+import numpy as np
+
+FLOAT_TYPES = ("f32", "f16", "bf16")
+
+
+# --------------------------------------------------------------------------- storage types
+
+def round_bf16(x):
+    """Round to the nearest bfloat16 (ties to even); result held in float32."""
+    x32 = np.asarray(x, dtype=np.float64).astype(np.float32)
+    b = x32.view(np.uint32).astype(np.uint64)
+    r = (b + 0x7FFF + ((b >> 16) & 1)) & 0xFFFF0000
+    return r.astype(np.uint32).view(np.float32).reshape(x32.shape)
+
+
+def round_to(x, dtype):
+    """Round float64 values once to storage type `dtype`; bf16 is held as float32 values."""
+    if dtype == "f32":
+        return np.asarray(x, dtype=np.float64).astype(np.float32)
+    if dtype == "f16":
+        return np.asarray(x, dtype=np.float64).astype(np.float16)
+    if dtype == "bf16":
+        # float64 -> float32 -> bf16 double rounding matches a device that converts an fp32 result
+        return round_bf16(x)
+    raise ValueError(dtype)
+
+
+def storage_numpy_dtype(dtype):
+    return {"f32": np.float32, "f16": np.float16, "bf16": np.float32}[dtype]
+
+
+# --------------------------------------------------------------------------- the cache C^(l)
+
+class HistoricalCache:
+    """Historical embedding cache of one layer (Section 4.2, embedding side).
+
+    State, following the paper's description: a node-id mapping array of length |V| whose
+    entry is the slot holding that node's embedding (or -1), a slot table of embeddings, and a
+    ring header that moves forward as embeddings are admitted. Per slot this model also keeps
+    the owning node and the iteration that admitted it ("auxiliary data related to staleness").
+
+    Reading taken for staleness (Section 4.1.2): an embedding admitted by the update of
+    iteration a has staleness i - a when looked up in iteration i; it is usable while
+    1 <= i - a <= t_stale, so t_stale = 0 disables the cache (Section 4.1.3). The paper's
+    implementation note that the header is reset every t_stale iterations is replaced by a
+    per-slot stamp with a modulo ring: the oldest slots are overwritten first and the bound
+    is exact.
+    """
+
+    def __init__(self, num_nodes, capacity, dim, t_stale, dtype="f32"):
+        self.num_nodes = int(num_nodes)
+        self.capacity = int(capacity)
+        self.dim = int(dim)
+        self.t_stale = int(t_stale)
+        self.dtype = dtype
+        self.map = np.full(self.num_nodes, -1, dtype=np.int32)
+        self.slot_node = np.full(self.capacity, -1, dtype=np.int32)
+        self.slot_stamp = np.zeros(self.capacity, dtype=np.int32)
+        self.table = np.zeros((self.capacity, self.dim), dtype=storage_numpy_dtype(dtype))
+        self.head = 0
+
+    def slot_of(self, v, i):
+        """Slot holding a usable embedding of node v at iteration i, or -1 (the set C^(l) is {v: slot_of >= 0})."""
+        s = int(self.map[v])
+        if s < 0:
+            return -1
+        if int(self.slot_node[s]) != int(v):
+            return -1          # the slot has been recycled for another node
+        age = int(i) - int(self.slot_stamp[s])
+        if age < 1 or age > self.t_stale:
+            return -1
+        return s
+
+    def valid_entries(self, i):
+        """{node: (slot, stamp)} of everything a lookup at iteration i would hit."""
+        out = {}
+        for s in range(self.capacity):
+            v = int(self.slot_node[s])
+            if v >= 0 and self.slot_of(v, i) == s:
+                out[v] = (s, int(self.slot_stamp[s]))
+        return out
+
+
+# --------------------------------------------------------------------------- top-down pass
+
+def lookup_prune(cache, i, ids, live, start, end, col, n_src):
+    """One layer of the top-down pass (Alg. 1: V_cache = V ∩ C, remove_subgraph, V_normal = V \\ V_cache).
+
+    ids     node ids of layer l, by position
+    live    bool per position: still needed after pruning the layers above (None: all)
+    start, end, col   block l in the two-row-array format of Section 5 (None for layer 0);
+            `end` is modified in place: rows that are not normal get end = start
+    n_src   number of positions in layer l-1
+
+    A node is looked up only if it is live (a pruned node is no longer part of G_b). Hits form
+    V_cache; live non-hits form V_normal. The neighbours that remain needed in layer l-1 are
+    the normal rows themselves (their own previous embedding) and their sampled neighbours:
+    that is what removing the subgraph below every hit leaves.
+
+    Returns hit (bool[n]), hit_pos, hit_slot, normal_pos (ascending positions) and
+    live_src (bool[n_src], None without a block).
+    """
+    n = len(ids)
+    live = np.ones(n, dtype=bool) if live is None else np.asarray(live, dtype=bool)
+    hit = np.zeros(n, dtype=bool)
+    hit_pos, hit_slot, normal_pos = [], [], []
+    for j in range(n):
+        if not live[j]:
+            continue
+        s = cache.slot_of(int(ids[j]), i) if cache is not None else -1
+        if s >= 0:
+            hit[j] = True
+            hit_pos.append(j)
+            hit_slot.append(s)
+        else:
+            normal_pos.append(j)
+    live_src = None
+    if start is not None:
+        live_src = np.zeros(n_src, dtype=bool)
+        normal = live & ~hit
+        for j in range(n):
+            if normal[j]:
+                live_src[j] = True
+                live_src[col[start[j]:end[j]]] = True
+            else:
+                end[j] = start[j]
+    return dict(hit=hit, hit_pos=np.asarray(hit_pos, dtype=np.int32), hit_slot=np.asarray(hit_slot, dtype=np.int32),
+                normal_pos=np.asarray(normal_pos, dtype=np.int32), live_src=live_src,
+                counts=(int(live.sum()), len(hit_pos), len(normal_pos)))
+
+
+# --------------------------------------------------------------------------- loader / cache fetch
+
+def gather(table_rows, index, dst, dst_pos=None):
+    """dst[dst_pos[k], :] = table[index[k], :], a bit copy (Load_feature, and the C^(l)[v] fetch).
+
+    `table_rows(index_array)` returns the rows; dst_pos None means k itself.
+    """
+    index = np.asarray(index)
+    rows = table_rows(index)
+    if dst_pos is None:
+        dst[:len(index)] = rows
+    else:
+        dst[np.asarray(dst_pos)] = rows
+    return dst
+
+
+# --------------------------------------------------------------------------- one GNN layer (Eq. 1, GraphSAGE mean)
+
+def aggregate(start, end, col, rows, h_src):
+    """Mean of the sampled neighbours' previous-layer rows, per row in `rows`: float64 [len(rows), d].
+
+    AGG of Eq. 1 with the mean aggregator; a row without neighbours gets the zero vector.
+    """
+    h = np.asarray(h_src)
+    out = np.zeros((len(rows), h.shape[1]), dtype=np.float64)
+    for k, r in enumerate(rows):
+        nb = col[start[r]:end[r]]
+        if len(nb):
+            out[k] = h[nb].astype(np.float64).sum(axis=0) / float(len(nb))
+    return out
+
+
+def linear(h_self, agg, W, b, relu):
+    """phi of Eq. 1 for GraphSAGE-mean: act([h_self ‖ agg] · W + b) in float64.
+
+    W is [2*d_in, d_out]; its first d_in rows multiply the node's own previous embedding, the
+    last d_in rows the neighbour mean. ReLU between layers, identity after the last.
+    """
+    d_in = h_self.shape[1]
+    W = np.asarray(W, dtype=np.float64)
+    z = (np.asarray(h_self, dtype=np.float64) @ W[:d_in] + np.asarray(agg, dtype=np.float64) @ W[d_in:]
+         + np.asarray(b, dtype=np.float64))
+    return np.maximum(z, 0.0) if relu else z
+
+
+# --------------------------------------------------------------------------- Update(C, V_normal, V, h, i, t_stale, p_grad)
+
+def admission_threshold(g_live, p_grad):
+    """Threshold tau such that "g < tau" selects the p_grad fraction with the smallest gradient norms.
+
+    k = floor(p_grad * m) with m the number of live nodes (p_grad taken as the float32 the caller
+    passes, the product in float64); tau is the value of rank k (0-based, ascending), +inf when
+    k >= m, -inf when k = 0. Ties at tau are not admitted, so the result does not depend on order.
+    """
+    m = len(g_live)
+    k = int(np.floor(np.float64(np.float32(p_grad)) * np.float64(m)))
+    if k <= 0:
+        return -np.inf, k
+    if k >= m:
+        return np.inf, k
+    return float(np.sort(np.asarray(g_live, dtype=np.float32))[k]), k
+
+
+def cache_update(cache, i, ids, live, hit, gnorm, p_grad, h):
+    """Update of one layer's cache after iteration i (Sections 4.1.1, 4.1.2, ring of 4.2).
+
+    Population: all live nodes of the layer, computed or fetched (the paper's example compares the
+    gradient norm of a fetched node with that of a computed one). With tau from
+    `admission_threshold`:
+      * a hit whose norm is not below tau is checked out: its mapping entry is invalidated;
+      * a hit whose norm is below tau stays as it is (its stamp is not refreshed: it was not recomputed);
+      * normal nodes with norm below tau are admitted in ascending position order into the slots
+        head, head+1, ... (mod capacity): row copied from h, slot owner and stamp = i written, mapping
+        entry set. A recycled slot's previous owner stops hitting because the slot no longer names it.
+        If more are admissible than there are slots, the first `capacity` in position order get in.
+      * the header advances by the number admitted.
+    Staleness needs no pass of its own: `HistoricalCache.slot_of` enforces the bound.
+    Returns counts (admitted, evicted_by_gradient, overwritten_valid, dropped_overflow) and tau.
+    """
+    n = len(ids)
+    live = np.ones(n, dtype=bool) if live is None else np.asarray(live, dtype=bool)
+    hit = np.asarray(hit, dtype=bool)
+    g = np.asarray(gnorm, dtype=np.float32)
+    tau, _ = admission_threshold(g[live], p_grad)
+    admitted = evicted = overwritten = dropped = 0
+    for j in range(n):
+        if live[j] and hit[j] and not (g[j] < tau):
+            cache.map[ids[j]] = -1
+            evicted += 1
+    head = cache.head
+    for j in range(n):
+        if live[j] and not hit[j] and g[j] < tau:
+            if admitted >= cache.capacity:
+                dropped += 1
+                continue
+            s = (head + admitted) % cache.capacity
+            old = int(cache.slot_node[s])
+            if old >= 0 and cache.slot_of(old, i + 1) == s:
+                overwritten += 1
+            cache.slot_node[s] = ids[j]
+            cache.slot_stamp[s] = i
+            cache.table[s] = h[j]
+            cache.map[ids[j]] = s
+            admitted += 1
+    cache.head = (head + admitted) % cache.capacity if cache.capacity else 0
+    return dict(admitted=admitted, evicted_by_gradient=evicted, overwritten=overwritten, dropped_overflow=dropped, tau=tau)
+
+
+# --------------------------------------------------------------------------- the whole iteration
+
+def check_minibatch(mb):
+    """Structural checks of a sampled mini-batch (layout described in the sampler): raises on violation."""
+    L = mb.num_layers
+    for l in range(L + 1):
+        assert len(np.unique(mb.ids[l])) == len(mb.ids[l]), "node ids repeat within a layer"
+    for l in range(1, L + 1):
+        n = len(mb.ids[l])
+        assert len(mb.start[l]) == n and len(mb.end[l]) == n
+        assert np.array_equal(mb.ids[l - 1][:n], mb.ids[l]), "layer l-1 must begin with layer l"
+        assert np.all(mb.start[l] <= mb.end[l]) and (n == 0 or mb.end[l].max() <= len(mb.col[l]))
+        assert n == 0 or np.all(mb.start[l][1:] >= mb.end[l][:-1])
+        if len(mb.col[l]):
+            assert mb.col[l].min() >= 0 and mb.col[l].max() < len(mb.ids[l - 1])
+
+
+def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_dtype="f32", compute_dtype="f32",
+              update=True):
+    """One pass of Algorithm 1 without loss/backward (gradient norms are given).
+
+    mb        sampled mini-batch (its `end` arrays are modified: pruning)
+    caches    {l: HistoricalCache} for l = 1..L-1 (missing or None: that layer is never looked up)
+    feature_rows(ids) -> raw feature rows; weights[l] = (W_l, b_l); gnorms[l] = norms by position
+    dims      [d_0..d_L]
+    Types: H(0) in feat_dtype; H(l), AGG(l) for l >= 1 in compute_dtype except H(L) which is fp32.
+    In the bf16 setting the own rows and the mean are rounded to bf16 before the product and W is bf16.
+    Returns a record of every intermediate the GPU path exposes.
+    """
+    L = mb.num_layers
+    rec = dict(layers={})
+    live = [None] * (L + 1)
+    look = [None] * (L + 1)
+    live[L] = np.ones(len(mb.ids[L]), dtype=bool)
+    for l in range(L, -1, -1):
+        cache = caches.get(l) if (1 <= l <= L - 1) else None
+        if l >= 1:
+            look[l] = lookup_prune(cache, i, mb.ids[l], live[l], mb.start[l], mb.end[l], mb.col[l], len(mb.ids[l - 1]))
+            live[l - 1] = look[l]["live_src"]
+        else:
+            look[0] = lookup_prune(None, i, mb.ids[0], live[0], None, None, None, 0)
+    H = [None] * (L + 1)
+    AGG = [None] * (L + 1)
+    H[0] = np.zeros((len(mb.ids[0]), dims[0]), dtype=storage_numpy_dtype(feat_dtype))
+    input_pos = look[0]["normal_pos"]
+    gather(feature_rows, mb.ids[0][input_pos], H[0], input_pos)
+    for l in range(1, L + 1):
+        out_dtype = "f32" if l == L else compute_dtype
+        H[l] = np.zeros((len(mb.ids[l]), dims[l]), dtype=storage_numpy_dtype(out_dtype))
+        if 1 <= l <= L - 1 and caches.get(l) is not None and len(look[l]["hit_pos"]):
+            c = caches[l]
+            gather(lambda s: c.table[s], look[l]["hit_slot"], H[l], look[l]["hit_pos"])
+        rows = look[l]["normal_pos"]
+        agg64 = aggregate(mb.start[l], mb.end[l], mb.col[l], rows, H[l - 1])
+        W, b = weights[l]
+        if compute_dtype == "bf16":
+            AGG[l] = round_bf16(agg64)
+            h_self = round_bf16(H[l - 1][rows].astype(np.float64))
+        else:
+            AGG[l] = round_to(agg64, "f32")
+            h_self = H[l - 1][rows]
+        z = linear(h_self, AGG[l], W, b, relu=(l < L))
+        H[l][rows] = round_to(z, out_dtype)
+    stats = {}
+    if update:
+        for l in range(1, L):
+            if caches.get(l) is not None:
+                stats[l] = cache_update(caches[l], i, mb.ids[l], live[l], look[l]["hit"], gnorms[l], p_grad, H[l])
+    rec.update(live=live, look=look, H=H, AGG=AGG, stats=stats)
+    return rec
