@@ -1,0 +1,204 @@
+/*
+ * freshgnn.h - C ABI of the MI355X (gfx950) hot path of mini-batch GNN training with a
+ * selective historical-embedding cache (Algorithm 1 of the paper).
+ *
+ * One training iteration calls, in this order:
+ *   top-down   fg_lookup_prune  for layers L, L-1, ..., 1, 0   (cache lookup, pruning, V_normal)
+ *   loader     fg_gather        raw features of the surviving input nodes
+ *   bottom-up  for l = 1..L:    fg_gather (cached rows of V_cache), fg_aggregate, fg_linear
+ *   update     fg_cache_update  for l = 1..L-1
+ *
+ * Conventions
+ *   - Every pointer named *_dev or documented "device" is device memory owned by the caller
+ *     (a pointer to host memory mapped into the device address space works wherever a table
+ *     is only read; it is named where that is intended). "host" pointers are ordinary host memory.
+ *   - All calls are asynchronous on the caller's stream (a hipStream_t passed as void*), never
+ *     synchronise the device and never copy a count back to the host: element counts that are
+ *     only known on the device are read from device memory by the kernels, and the host passes
+ *     an upper bound (max_*) that sizes the launch.
+ *   - Node ids, positions and slot indices are int32; byte strides are int64; counts on the
+ *     device are int64.
+ *   - A mini-batch layer l holds n_l distinct node ids by position. Block l (l >= 1) connects
+ *     layer l-1 to layer l in the two-row-array format of Section 5: the sampled neighbours of
+ *     row j are col[row_start[j] .. row_end[j]), each a position in layer l-1, and layer l-1
+ *     begins with the nodes of layer l in the same order (row j's own previous embedding is at
+ *     position j).
+ *   - Return value: FG_OK or an error code; fg_last_error() gives the message for the calling
+ *     thread. Arguments are validated on the host before anything is launched; a call that
+ *     returns an error has launched nothing. Indices read from device memory are range-checked
+ *     inside the kernels: an out-of-range entry is skipped, never dereferenced.
+ *   - Calls on one cache must be ordered by the caller (same stream, or events); the library
+ *     keeps no locks.
+ */
+#ifndef FRESHGNN_H
+#define FRESHGNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t fg_status_t;
+enum {
+    FG_OK = 0,
+    FG_ERR_INVALID_ARG = 1, /* NULL where a pointer is required, negative size, bad enum, bad alignment */
+    FG_ERR_SHAPE = 2,       /* sizes that do not fit together (layer index, dim, strides, workspace too small) */
+    FG_ERR_DTYPE = 3,       /* element type not supported by this call */
+    FG_ERR_STATE = 4,       /* call not valid in the cache's current state (e.g. iteration going backwards) */
+    FG_ERR_OOM = 5,         /* device allocation failed */
+    FG_ERR_HIP = 6          /* the HIP runtime reported an error (message in fg_last_error) */
+};
+
+typedef enum { FG_F32 = 0, FG_F16 = 1, FG_BF16 = 2 } fg_dtype_t;
+
+typedef struct fg_cache fg_cache_t; /* opaque: the historical embedding caches C^(1..L-1) of one model */
+
+/* Message of the last error on this thread ("" if none). The pointer stays valid until the next failing call. */
+const char* fg_last_error(void);
+/* Library version, major * 10000 + minor * 100 + patch. */
+int32_t fg_version(void);
+
+/*
+ * Historical embedding cache (Section 4.2, embedding side): per cached layer a node-id mapping
+ * array of length num_nodes (entry = slot or -1), a slot table [capacity x dim] of `dtype`, and a
+ * ring header; per slot also the owning node and the iteration that admitted it.
+ * A cached embedding admitted by the update of iteration a is usable by the lookups of
+ * iterations a+1 .. a+t_stale (Section 4.1.2); t_stale = 0 therefore disables the cache.
+ *
+ * n_layers: number of cached layers; layer indices 1..n_layers are valid in the calls below
+ * (for an L-layer model pass L-1). capacity[k], dim[k]: slots and row width of layer k+1 (host arrays).
+ * The library allocates (hipMalloc) and owns all cache memory:
+ *   num_nodes*4 + capacity*(dim*sizeof(dtype) + 8) bytes per layer.
+ * The initialisation is queued on `stream`. *out is NULL on error.
+ */
+fg_status_t fg_cache_create(fg_cache_t** out, int64_t num_nodes, int32_t n_layers, const int64_t* capacity,
+                            const int32_t* dim, fg_dtype_t dtype, int32_t t_stale, void* stream);
+/* Frees everything the cache owns. Synchronises the device first. NULL is accepted. */
+fg_status_t fg_cache_destroy(fg_cache_t* cache);
+/* Empties all layers (as after create), queued on `stream`. */
+fg_status_t fg_cache_clear(fg_cache_t* cache, void* stream);
+/* Device pointer to the slot table of `layer` ([capacity x dim], row stride dim*sizeof(dtype)); NULL on error. */
+const void* fg_cache_table(const fg_cache_t* cache, int32_t layer);
+/* Changes the staleness bound for subsequent lookups. */
+fg_status_t fg_cache_set_t_stale(fg_cache_t* cache, int32_t t_stale);
+
+/*
+ * Snapshot for tests and monitoring: every entry a lookup at iteration `iter` would hit, in slot
+ * order: nodes_dev[k], slots_dev[k], stamps_dev[k] (each int32[capacity] device, may be NULL),
+ * *count_dev (int64 device) = number of entries, *head_dev (int64 device, may be NULL) = ring header.
+ * ws_dev: device workspace of at least fg_workspace_bytes(FG_WS_EXPORT, capacity, 0) bytes.
+ */
+fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, int64_t iter, int32_t* nodes_dev,
+                            int32_t* slots_dev, int32_t* stamps_dev, int64_t* count_dev, int64_t* head_dev,
+                            void* ws_dev, size_t ws_bytes, void* stream);
+
+typedef enum { FG_WS_LOOKUP_PRUNE = 0, FG_WS_CACHE_UPDATE = 1, FG_WS_EXPORT = 2 } fg_ws_kind_t;
+/* Bytes of device workspace the named call needs for a layer of n nodes (0 on a bad argument). */
+size_t fg_workspace_bytes(fg_ws_kind_t kind, int64_t n, int64_t reserved);
+
+/*
+ * One layer of the top-down pass (Algorithm 1: V_cache = V ∩ C, remove_subgraph(root = V_cache),
+ * V_normal = V \ V_cache; Section 5, GPU graph pruning).
+ *
+ *   cache, layer, iter  cache to look layer `layer` up in at iteration `iter`; cache == NULL: no lookup
+ *                       (the seed layer L, the input layer 0, or a run with the cache disabled)
+ *   ids_dev[n]          node ids of the layer by position
+ *   live_dev[n]         uint8, 1 = still needed after pruning the layers above; NULL = all live.
+ *                       Only live nodes are looked up or listed.
+ *   row_start_dev[n], row_end_dev[n], col_dev[nnz], n_src
+ *                       block `layer` (device); all three NULL for the input layer. row_end is
+ *                       MODIFIED: every row that is not normal gets row_end = row_start. col is read only.
+ *                       nnz = entries of col (a row whose range leaves [0, nnz] is treated as empty);
+ *                       n_src = number of positions of layer-1 (n_src >= n).
+ *   live_src_dev[n_src] out, uint8: set to 0 by the call, then 1 at position j of every normal row j and at
+ *                       every neighbour position of a normal row (what survives below). NULL iff no block.
+ *   hit_dev[n]          out, uint8 per position: 1 = live and found in the cache (may be NULL if cache == NULL)
+ *   hit_pos_dev, hit_slot_dev   out, int32[n]: positions of the hits in ascending order and their cache slots
+ *                       (may be NULL if cache == NULL)
+ *   normal_pos_dev      out, int32[n]: positions of V_normal (live, not hit) in ascending order
+ *   normal_ids_dev      out, int32[n] or NULL: ids_dev[normal_pos[k]] (what the loader needs for layer 0)
+ *   counts_dev          out, int64[3] device: n_live, n_hit, n_normal
+ *   ws_dev, ws_bytes    device workspace, >= fg_workspace_bytes(FG_WS_LOOKUP_PRUNE, n, 0)
+ */
+fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, int64_t iter, const int32_t* ids_dev, int32_t n,
+                            const uint8_t* live_dev, const int32_t* row_start_dev, int32_t* row_end_dev,
+                            const int32_t* col_dev, int64_t nnz, int32_t n_src, uint8_t* live_src_dev, uint8_t* hit_dev,
+                            int32_t* hit_pos_dev, int32_t* hit_slot_dev, int32_t* normal_pos_dev,
+                            int32_t* normal_ids_dev, int64_t* counts_dev, void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * Row gather, a bit copy: for k < *count_dev: dst[dst_pos[k], :] = table[src_index[k], :].
+ * Serves Load_feature(V_normal^(0)) (Algorithm 1; Section 6, one-sided reads by node id: `table` may be
+ * pinned host memory mapped into the device address space) and the cache fetch h_v = C^(l)[v].
+ *
+ *   table, table_rows, src_stride   source table (device or mapped host), rows, bytes between rows
+ *   row_bytes                       bytes copied per row (multiple of 2)
+ *   src_index_dev[max_count]        int32 row numbers in the table (node ids or cache slots)
+ *   dst_pos_dev[max_count]          int32 destination rows, or NULL for k itself
+ *   count_dev, max_count            int64 device count (NULL = max_count) and its host-known upper bound
+ *   dst, dst_rows, dst_stride       destination (device), rows, bytes between rows
+ *   table_on_host                   0 = table in HBM, 1 = table in mapped host memory (tuning hint only)
+ * Entries with src_index or dst_pos out of range are skipped. Pointers and strides must be aligned to
+ * the largest power of two <= 16 that divides row_bytes.
+ */
+fg_status_t fg_gather(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
+                      const int32_t* src_index_dev, const int32_t* dst_pos_dev, const int64_t* count_dev,
+                      int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride, int32_t table_on_host,
+                      void* stream);
+
+/*
+ * Mean aggregation over sampled neighbours (AGG of Eq. 1 with the mean aggregator), for the rows listed:
+ *   agg[k, :] = (1/deg) * sum_{e in [row_start[r], row_end[r])} h_src[col[e], :],  r = rows[k], k < *n_rows_dev;
+ *   a row without neighbours gives zeros.
+ * Sums are carried in fp64 and rounded once to out_dtype.
+ *   row_start_dev, row_end_dev [n_block_rows], col_dev[nnz]   the (pruned) block
+ *   rows_dev[max_rows]       int32 positions (V_normal, ascending); NULL = 0..count-1
+ *   h_src, n_src, src_stride previous-layer embeddings by position (device), rows, byte stride; in_dtype
+ *   agg, agg_stride          output [max_rows x dim] compact (row k for rows[k]), any out_dtype; 16-byte aligned
+ *   dim * sizeof(in_dtype) must be a multiple of 16.
+ */
+fg_status_t fg_aggregate(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
+                         int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                         const void* h_src, int32_t n_src, int64_t src_stride, int32_t dim, fg_dtype_t in_dtype,
+                         void* agg, int64_t agg_stride, fg_dtype_t out_dtype, void* stream);
+
+/*
+ * Dense update of a GraphSAGE-mean layer (phi of Eq. 1; the f_W line of Algorithm 1), for the rows listed:
+ *   h_out[r, :] = act( h_src[r, :] . W[0:d_in, :] + agg[k, :] . W[d_in:2*d_in, :] + bias ),  r = rows[k]
+ *   act = ReLU if relu != 0, identity otherwise.
+ *   h_src (in_dtype; F16 rows are converted to BF16 when w_dtype is BF16), agg (F32 when w_dtype is F32, BF16 when BF16)
+ *   W [2*d_in x d_out] row-major, w_dtype F32 (fp32 MFMA, fp32 accumulate) or BF16 (bf16 MFMA, fp32 accumulate)
+ *   bias float[d_out] (device); h_out rows of out_dtype (F32 or BF16) written at position rows[k]
+ *   d_in must be a multiple of 4 (8 for 16-bit inputs), d_out a multiple of 4.
+ */
+fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype, const void* agg,
+                      int64_t agg_stride, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                      int32_t d_in, int32_t d_out, const void* W, fg_dtype_t w_dtype, const float* bias, int32_t relu,
+                      void* h_out, int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, void* stream);
+
+/*
+ * Update(C^(l), V_normal^(l), V^(l), h^(l), i, t_stale, p_grad) of Algorithm 1 (Sections 4.1.1, 4.1.2, 4.2).
+ * Over the live nodes of the layer (m of them): k = floor(p_grad * m), tau = the gradient norm of rank k
+ * (ascending, 0-based; every norm is below tau if k >= m, none if k == 0). Live hits whose norm is not below
+ * tau are checked out (mapping entry invalidated); normal nodes (live, not hit) whose norm is below tau are
+ * admitted in ascending position order into ring slots head, head+1, ... (mod capacity): their row of h is
+ * copied into the table and stamped with `iter`; at most `capacity` per call, the rest are counted as dropped.
+ *
+ *   ids_dev[n], live_dev[n] (NULL = all live), hit_dev[n]   as given to / produced by fg_lookup_prune
+ *   gnorm_dev[n]        float, L2 norm of the loss gradient w.r.t. each node's embedding; finite and >= 0
+ *   h_dev, h_stride     embeddings of the layer by position (type = the cache's dtype, width = its dim)
+ *   stats_dev           out, int64[4] device or NULL: admitted, evicted_by_gradient, overwritten, dropped_overflow
+ *   ws_dev, ws_bytes    device workspace, >= fg_workspace_bytes(FG_WS_CACHE_UPDATE, n, 0)
+ * `iter` must not decrease between updates of a layer (FG_ERR_STATE).
+ */
+fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t iter, const int32_t* ids_dev, int32_t n,
+                            const uint8_t* live_dev, const uint8_t* hit_dev, const float* gnorm_dev, float p_grad,
+                            const void* h_dev, int64_t h_stride, int64_t* stats_dev, void* ws_dev, size_t ws_bytes,
+                            void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FRESHGNN_H */

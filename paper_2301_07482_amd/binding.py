@@ -1,0 +1,135 @@
+"""Thin ctypes binding of libfreshgnn.so: same names as the C ABI, argument marshalling only.
+
+Tensors are passed as raw device pointers (torch is used for device memory and streams, nothing
+else); every step runs in the library's HIP kernels. There is no fallback: if the shared library is
+missing, importing this module raises.
+"""
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libfreshgnn.so")
+
+FG_OK, FG_ERR_INVALID_ARG, FG_ERR_SHAPE, FG_ERR_DTYPE, FG_ERR_STATE, FG_ERR_OOM, FG_ERR_HIP = range(7)
+FG_F32, FG_F16, FG_BF16 = 0, 1, 2
+FG_WS_LOOKUP_PRUNE, FG_WS_CACHE_UPDATE, FG_WS_EXPORT = 0, 1, 2
+DTYPE_SIZE = {FG_F32: 4, FG_F16: 2, FG_BF16: 2}
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2301_07482_amd.build` (needs hipcc); "
+                      "there is no fallback implementation")
+_lib = C.CDLL(LIB_PATH)
+
+_p, _i32, _i64, _sz, _f = C.c_void_p, C.c_int32, C.c_int64, C.c_size_t, C.c_float
+
+SIGNATURES = {
+    "fg_last_error": (C.c_char_p, []),
+    "fg_version": (_i32, []),
+    "fg_cache_create": (_i32, [C.POINTER(_p), _i64, _i32, C.POINTER(_i64), C.POINTER(_i32), _i32, _i32, _p]),
+    "fg_cache_destroy": (_i32, [_p]),
+    "fg_cache_clear": (_i32, [_p, _p]),
+    "fg_cache_table": (_p, [_p, _i32]),
+    "fg_cache_set_t_stale": (_i32, [_p, _i32]),
+    "fg_cache_export": (_i32, [_p, _i32, _i64, _p, _p, _p, _p, _p, _p, _sz, _p]),
+    "fg_workspace_bytes": (_sz, [_i32, _i64, _i64]),
+    "fg_lookup_prune": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _p, _i64, _i32, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
+    "fg_gather": (_i32, [_p, _i64, _i64, _i64, _p, _p, _p, _i64, _p, _i64, _i64, _i32, _p]),
+    "fg_aggregate": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _i32, _p, _i64, _i32, _p]),
+    "fg_linear": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _p, _i64, _i32, _i32, _p, _i32, _p, _i32, _p, _i32, _i64, _i32, _p]),
+    "fg_cache_update": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _f, _p, _i64, _p, _p, _sz, _p]),
+}
+for _name, (_res, _args) in SIGNATURES.items():
+    _fn = getattr(_lib, _name)
+    _fn.restype, _fn.argtypes = _res, _args
+
+
+class FgError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"freshgnn error {code}: {message}")
+        self.code = code
+
+
+def _check(rc):
+    if rc != FG_OK:
+        raise FgError(rc, _lib.fg_last_error().decode())
+
+
+def ptr(t):
+    """Raw address of a torch tensor (or None); an int is passed through."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def fg_version():
+    return _lib.fg_version()
+
+
+def fg_last_error():
+    return _lib.fg_last_error().decode()
+
+
+def fg_workspace_bytes(kind, n):
+    return _lib.fg_workspace_bytes(kind, n, 0)
+
+
+def fg_cache_create(num_nodes, capacity, dim, dtype, t_stale, stream=None):
+    n = len(capacity)
+    handle = _p()
+    cap = (_i64 * max(n, 1))(*capacity)
+    dm = (_i32 * max(n, 1))(*dim)
+    _check(_lib.fg_cache_create(C.byref(handle), num_nodes, n, cap, dm, dtype, t_stale, stream))
+    return handle
+
+
+def fg_cache_destroy(cache):
+    _check(_lib.fg_cache_destroy(cache))
+
+
+def fg_cache_clear(cache, stream=None):
+    _check(_lib.fg_cache_clear(cache, stream))
+
+
+def fg_cache_table(cache, layer):
+    return _lib.fg_cache_table(cache, layer)
+
+
+def fg_cache_set_t_stale(cache, t_stale):
+    _check(_lib.fg_cache_set_t_stale(cache, t_stale))
+
+
+def fg_cache_export(cache, layer, it, nodes, slots, stamps, count, head, ws, ws_bytes, stream=None):
+    _check(_lib.fg_cache_export(cache, layer, it, ptr(nodes), ptr(slots), ptr(stamps), ptr(count), ptr(head), ptr(ws),
+                                ws_bytes, stream))
+
+
+def fg_lookup_prune(cache, layer, it, ids, n, live, row_start, row_end, col, nnz, n_src, live_src, hit, hit_pos, hit_slot,
+                    normal_pos, normal_ids, counts, ws, ws_bytes, stream=None):
+    _check(_lib.fg_lookup_prune(cache, layer, it, ptr(ids), n, ptr(live), ptr(row_start), ptr(row_end), ptr(col), nnz, n_src,
+                                ptr(live_src), ptr(hit), ptr(hit_pos), ptr(hit_slot), ptr(normal_pos), ptr(normal_ids),
+                                ptr(counts), ptr(ws), ws_bytes, stream))
+
+
+def fg_gather(table, table_rows, src_stride, row_bytes, src_index, dst_pos, count, max_count, dst, dst_rows, dst_stride,
+              table_on_host=0, stream=None):
+    _check(_lib.fg_gather(ptr(table), table_rows, src_stride, row_bytes, ptr(src_index), ptr(dst_pos), ptr(count), max_count,
+                          ptr(dst), dst_rows, dst_stride, table_on_host, stream))
+
+
+def fg_aggregate(row_start, row_end, col, nnz, n_block_rows, rows, n_rows, max_rows, h_src, n_src, src_stride, dim, in_dtype,
+                 agg, agg_stride, out_dtype, stream=None):
+    _check(_lib.fg_aggregate(ptr(row_start), ptr(row_end), ptr(col), nnz, n_block_rows, ptr(rows), ptr(n_rows), max_rows,
+                             ptr(h_src), n_src, src_stride, dim, in_dtype, ptr(agg), agg_stride, out_dtype, stream))
+
+
+def fg_linear(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows, n_rows, max_rows, d_in, d_out, W, w_dtype, bias, relu,
+              h_out, n_out, out_stride, out_dtype, stream=None):
+    _check(_lib.fg_linear(ptr(h_src), n_src, src_stride, in_dtype, ptr(agg), agg_stride, ptr(rows), ptr(n_rows), max_rows,
+                          d_in, d_out, ptr(W), w_dtype, ptr(bias), relu, ptr(h_out), n_out, out_stride, out_dtype, stream))
+
+
+def fg_cache_update(cache, layer, it, ids, n, live, hit, gnorm, p_grad, h, h_stride, stats, ws, ws_bytes, stream=None):
+    _check(_lib.fg_cache_update(cache, layer, it, ptr(ids), n, ptr(live), ptr(hit), ptr(gnorm), p_grad, ptr(h), h_stride,
+                                ptr(stats), ptr(ws), ws_bytes, stream))

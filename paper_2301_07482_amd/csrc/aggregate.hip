@@ -1,0 +1,226 @@
+// fg_aggregate: mean of the sampled neighbours' previous-layer rows (AGG of Eq. 1, mean aggregator) for the
+// rows of V_normal, over the pruned two-row-array block.
+//
+// HBM/L2-bound: nnz rows of d elements are read, one row of d per output written. A group of 2^g lanes owns
+// one output row and holds 16 bytes of it per lane (4 fp32 or 8 16-bit elements); the neighbour indices of
+// the rows a workgroup works on are staged in LDS by a coalesced load and then read back as broadcasts,
+// and the neighbour rows are fetched UNROLL at a time. Sums are carried in fp64 (the arithmetic is free
+// next to the memory traffic) and rounded once, so the result does not depend on the neighbour order
+// beyond fp64 rounding.
+#include <hip/hip_bf16.h>
+#include <hip/hip_fp16.h>
+
+#include "common.h"
+
+namespace {
+
+constexpr int AGG_THREADS = 256;
+constexpr int AGG_MAX_STAGE = 64;  // neighbour indices staged per row and pass
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+template <int DT>
+struct Elem;
+template <>
+struct Elem<FG_F32> {
+    static constexpr int PER16 = 4;
+    __device__ static void unpack(const u32x4& raw, double* acc) {
+        acc[0] += (double)__uint_as_float(raw.x);
+        acc[1] += (double)__uint_as_float(raw.y);
+        acc[2] += (double)__uint_as_float(raw.z);
+        acc[3] += (double)__uint_as_float(raw.w);
+    }
+};
+template <>
+struct Elem<FG_F16> {
+    static constexpr int PER16 = 8;
+    __device__ static void unpack(const u32x4& raw, double* acc) {
+        const unsigned int w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += (double)__half2float(__ushort_as_half((unsigned short)(w[i] & 0xFFFF)));
+            acc[2 * i + 1] += (double)__half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
+        }
+    }
+};
+template <>
+struct Elem<FG_BF16> {
+    static constexpr int PER16 = 8;
+    __device__ static void unpack(const u32x4& raw, double* acc) {
+        const unsigned int w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            acc[2 * i] += (double)__uint_as_float(w[i] << 16);
+            acc[2 * i + 1] += (double)__uint_as_float(w[i] & 0xFFFF0000u);
+        }
+    }
+};
+
+// round an fp32 value to bf16 bits, nearest even (finite inputs)
+__device__ __forceinline__ unsigned int bf16_bits(float f) {
+    const unsigned int b = __float_as_uint(f);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ unsigned int half_bits(float f) { return (unsigned int)__half_as_ushort(__float2half_rn(f)); }
+
+// acc / deg rounded once to OUT and written as aligned vector stores (N = 4 or 8 elements)
+template <int OUT, int N>
+__device__ __forceinline__ void store_row_piece(char* dst, const double* acc, double deg) {
+    float v[N];
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = deg > 0.0 ? (float)(acc[i] / deg) : 0.0f;
+    if constexpr (OUT == FG_F32) {
+#pragma unroll
+        for (int i = 0; i < N; i += 4) {
+            f32x4 o = {v[i], v[i + 1], v[i + 2], v[i + 3]};
+            *(f32x4*)(dst + 4 * i) = o;
+        }
+    } else {
+        unsigned int w[N / 2];
+#pragma unroll
+        for (int i = 0; i < N / 2; ++i) {
+            if constexpr (OUT == FG_BF16)
+                w[i] = bf16_bits(v[2 * i]) | (bf16_bits(v[2 * i + 1]) << 16);
+            else
+                w[i] = half_bits(v[2 * i]) | (half_bits(v[2 * i + 1]) << 16);
+        }
+        if constexpr (N == 4) {
+            u32x2 o = {w[0], w[1]};
+            *(u32x2*)dst = o;
+        } else {
+            u32x4 o = {w[0], w[1], w[2], w[3]};
+            *(u32x4*)dst = o;
+        }
+    }
+}
+
+// IN: element type of h_src; OUT: element type of agg. One group of `lanes` lanes per output row;
+// pieces = 16-byte pieces per row (may exceed `lanes`, then a lane loops).
+template <int IN, int OUT>
+__global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
+    const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ col,
+    int64_t nnz, int n_block_rows, const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev,
+    int64_t max_rows, const char* __restrict__ h_src, int n_src, int64_t src_stride, int pieces, char* __restrict__ agg,
+    int64_t agg_stride, int lanes_log2) {
+    constexpr int PER = Elem<IN>::PER16;
+    constexpr int OUT_BYTES = (OUT == FG_F32 ? 4 : 2) * PER;
+    extern __shared__ int32_t nb_lds[];  // [groups_per_block][AGG_MAX_STAGE]
+    int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
+    if (n_rows > max_rows) n_rows = max_rows;
+    const int lanes = 1 << lanes_log2;
+    const int gpb = AGG_THREADS >> lanes_log2;
+    const int g_in_block = threadIdx.x >> lanes_log2;
+    const int lane = threadIdx.x & (lanes - 1);
+    int32_t* my_nb = nb_lds + g_in_block * AGG_MAX_STAGE;
+    for (int64_t k = (int64_t)blockIdx.x * gpb + g_in_block; k < n_rows; k += (int64_t)gridDim.x * gpb) {
+        const int32_t r = rows ? rows[k] : (int32_t)k;
+        int32_t s0 = 0, e0 = 0;
+        if (r >= 0 && r < n_block_rows) {
+            s0 = row_start[r];
+            e0 = row_end[r];
+            if (s0 < 0 || e0 < s0 || (int64_t)e0 > nnz) e0 = s0 = 0;
+        }
+        const int deg = e0 - s0;
+        for (int p0 = 0; p0 < pieces; p0 += lanes) {
+            const int piece = p0 + lane;
+            const bool active = piece < pieces;
+            double acc[PER];
+#pragma unroll
+            for (int i = 0; i < PER; ++i) acc[i] = 0.0;
+            for (int base = 0; base < deg; base += AGG_MAX_STAGE) {
+                const int cnt = min(deg - base, AGG_MAX_STAGE);
+                // stage this row's neighbour positions: coalesced read, broadcast reads afterwards
+                for (int t = lane; t < cnt; t += lanes) my_nb[t] = col[s0 + base + t];
+                // lanes of a group sit in one wavefront when lanes <= 64, so LDS writes above are visible
+                // to the group after a wavefront-level fence
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                int t = 0;
+                for (; t + 4 <= cnt; t += 4) {
+                    u32x4 raw[4];
+                    bool ok[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int32_t c = my_nb[t + u];
+                        ok[u] = active && c >= 0 && c < n_src;
+                        if (ok[u]) raw[u] = *(const u32x4*)(h_src + (int64_t)c * src_stride + (int64_t)piece * 16);
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (ok[u]) Elem<IN>::unpack(raw[u], acc);
+                }
+                for (; t < cnt; ++t) {
+                    const int32_t c = my_nb[t];
+                    if (active && c >= 0 && c < n_src) {
+                        const u32x4 raw = *(const u32x4*)(h_src + (int64_t)c * src_stride + (int64_t)piece * 16);
+                        Elem<IN>::unpack(raw, acc);
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();  // the stage is rewritten by the next pass
+            }
+            if (active) store_row_piece<OUT, PER>(agg + k * agg_stride + (int64_t)piece * OUT_BYTES, acc, (double)deg);
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" fg_status_t fg_aggregate(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
+                                    int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev,
+                                    const int64_t* n_rows_dev, int64_t max_rows, const void* h_src, int32_t n_src,
+                                    int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
+                                    fg_dtype_t out_dtype, void* stream) {
+    if (max_rows < 0 || n_block_rows < 0 || n_src < 0 || dim <= 0 || nnz < 0)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_aggregate: bad size (max_rows %lld, n_block_rows %d, n_src %d, dim %d, nnz %lld)",
+                (long long)max_rows, n_block_rows, n_src, dim, (long long)nnz);
+    const int isz = fg_dtype_size(in_dtype), osz = fg_dtype_size(out_dtype);
+    if (!isz || !osz) FG_FAIL(FG_ERR_DTYPE, "fg_aggregate: unknown element type");
+    if (max_rows > 0 && (!row_start_dev || !row_end_dev || !h_src || !agg || (nnz > 0 && !col_dev)))
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_aggregate: NULL pointer");
+    const int per16 = 16 / isz;
+    if (dim % per16) FG_FAIL(FG_ERR_SHAPE, "fg_aggregate: dim = %d must be a multiple of %d for this type", dim, per16);
+    if (src_stride < (int64_t)dim * isz || agg_stride < (int64_t)dim * osz)
+        FG_FAIL(FG_ERR_SHAPE, "fg_aggregate: row stride smaller than a row");
+    if (((uintptr_t)h_src | (uintptr_t)src_stride) & 15)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_aggregate: h_src and its stride must be 16-byte aligned");
+    if (((uintptr_t)agg | (uintptr_t)agg_stride) & 15)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_aggregate: agg and its stride must be 16-byte aligned");
+    fg_clear_error();
+    if (max_rows == 0) return FG_OK;
+    const int pieces = dim / per16;
+    int lg = 0;
+    while ((1 << lg) < pieces && lg < 6) ++lg;
+    const int gpb = AGG_THREADS >> lg;
+    int64_t blocks = fg_ceil_div(max_rows, gpb);
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    const size_t lds = (size_t)gpb * AGG_MAX_STAGE * sizeof(int32_t);
+    hipStream_t st = (hipStream_t)stream;
+#define FG_AGG_LAUNCH(IN, OUT)                                                                                        \
+    hipLaunchKernelGGL((aggregate_mean_kernel<IN, OUT>), dim3((unsigned)blocks), dim3(AGG_THREADS), lds, st,           \
+                       row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,         \
+                       (const char*)h_src, n_src, src_stride, pieces, (char*)agg, agg_stride, lg)
+#define FG_AGG_IN(IN)                                  \
+    do {                                               \
+        if (out_dtype == FG_F32)                       \
+            FG_AGG_LAUNCH(IN, FG_F32);                 \
+        else if (out_dtype == FG_F16)                  \
+            FG_AGG_LAUNCH(IN, FG_F16);                 \
+        else                                           \
+            FG_AGG_LAUNCH(IN, FG_BF16);                \
+    } while (0)
+    if (in_dtype == FG_F32)
+        FG_AGG_IN(FG_F32);
+    else if (in_dtype == FG_F16)
+        FG_AGG_IN(FG_F16);
+    else
+        FG_AGG_IN(FG_BF16);
+#undef FG_AGG_IN
+#undef FG_AGG_LAUNCH
+    FG_LAUNCH_CHECK("aggregate_mean_kernel");
+    return FG_OK;
+}

@@ -1,0 +1,421 @@
+// The historical embedding cache (Section 4.2, embedding side) and its Update (Algorithm 1, last loop;
+// admission and check-out by gradient norm, Section 4.1.1; staleness bound, Section 4.1.2).
+//
+// State per cached layer, all in HBM: map[num_nodes] (slot of a node or -1), table[capacity x dim],
+// slot_node[capacity], slot_stamp[capacity], head. A node v is usable at iteration i iff
+//   s = map[v] >= 0, slot_node[s] == v and 1 <= i - slot_stamp[s] <= t_stale.
+// The back-pointer test makes every location single-writer during an update: admitting into a slot never
+// touches the previous owner's map entry, a check-out only writes the node's own map entry, and the slots
+// handed out in one update are distinct. The result is therefore the same as the sequential procedure.
+//
+// Update = 4 launches, no host synchronisation:
+//   1. select_tau    one workgroup: m = live count, k = floor(p_grad*m), radix select (4 x 8 bits on the
+//                    order-preserving integer image of the fp32 norms) of the norm with rank k
+//   2. classify      check out hits that are not below tau; flag admissible normal nodes; count per workgroup
+//   3. assign_slots  rank admissible nodes in position order (ballot ranks + preceding workgroups' counts),
+//                    hand out ring slots head + rank, write slot_node / slot_stamp / map, list (position, slot)
+//   4. row copy      table[slot] = h[position] (the gather kernel), then the header moves
+#include "common.h"
+#include "scan.h"
+
+namespace {
+
+struct UpdHeader {        // lives at the start of the update workspace
+    uint32_t tau_key;     // order-preserving key of tau
+    int32_t mode;         // 0: nothing is below tau, 1: compare with tau_key, 2: everything is below tau
+    int64_t n_admit;      // rows to copy (<= capacity)
+    int64_t m_live;
+};
+
+__device__ __forceinline__ uint32_t order_key(float f) {
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+
+__global__ __launch_bounds__(1024) void select_tau_kernel(const uint8_t* __restrict__ live,
+                                                          const float* __restrict__ gnorm, int n, float p_grad,
+                                                          UpdHeader* __restrict__ hdr, int64_t* __restrict__ stats) {
+    __shared__ unsigned int hist[256];
+    __shared__ long long red[16];
+    __shared__ uint32_t s_prefix;
+    __shared__ long long s_rank;
+    long long c = 0;
+    for (int j = threadIdx.x; j < n; j += blockDim.x) c += (live ? live[j] != 0 : true) ? 1 : 0;
+    const long long m = fg_block_sum(c, red);
+    const long long k = (long long)floor((double)p_grad * (double)m);
+    if (threadIdx.x == 0) {
+        hdr->m_live = m;
+        hdr->n_admit = 0;
+        if (stats) stats[0] = stats[1] = stats[2] = stats[3] = 0;
+    }
+    if (k <= 0 || k >= m) {
+        if (threadIdx.x == 0) {
+            hdr->mode = k <= 0 ? 0 : 2;
+            hdr->tau_key = 0;
+        }
+        return;
+    }
+    if (threadIdx.x == 0) {
+        s_prefix = 0;
+        s_rank = k;
+    }
+    for (int pass = 0; pass < 4; ++pass) {
+        const int shift = 24 - 8 * pass;
+        if (threadIdx.x < 256) hist[threadIdx.x] = 0;
+        __syncthreads();
+        const uint32_t prefix = s_prefix;
+        const uint32_t mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
+        for (int j = threadIdx.x; j < n; j += blockDim.x) {
+            if (live && !live[j]) continue;
+            const uint32_t key = order_key(gnorm[j]);
+            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            long long rank = s_rank;
+            int b = 0;
+            for (; b < 255; ++b) {
+                if (rank < (long long)hist[b]) break;
+                rank -= hist[b];
+            }
+            s_rank = rank;
+            s_prefix = prefix | ((uint32_t)b << shift);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        hdr->mode = 1;
+        hdr->tau_key = s_prefix;
+    }
+}
+
+struct CacheRW {
+    int32_t* map;
+    int32_t* slot_node;
+    int32_t* slot_stamp;
+    int64_t* head;
+    int64_t capacity;
+    int64_t num_nodes;
+    int64_t iter;
+    int32_t t_stale;
+};
+
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void classify_update_kernel(
+    CacheRW c, const int32_t* __restrict__ ids, int n, const uint8_t* __restrict__ live,
+    const uint8_t* __restrict__ hit, const float* __restrict__ gnorm, const UpdHeader* __restrict__ hdr,
+    uint8_t* __restrict__ admit_flag, int32_t* __restrict__ blk_counts, int64_t* __restrict__ stats) {
+    const int j = blockIdx.x * FG_SCAN_BLOCK + threadIdx.x;
+    bool admit = false, evict = false;
+    if (j < n && (live ? live[j] != 0 : true)) {
+        const int mode = hdr->mode;
+        const bool low = mode == 2 || (mode == 1 && order_key(gnorm[j]) < hdr->tau_key);
+        const bool is_hit = hit[j] != 0;
+        const int32_t v = ids[j];
+        const bool v_ok = v >= 0 && v < c.num_nodes;
+        if (is_hit && !low && v_ok) {
+            c.map[v] = -1;
+            evict = true;
+        }
+        admit = !is_hit && low && v_ok;
+    }
+    if (j < n) admit_flag[j] = admit ? 1 : 0;
+    const int n_admit = __syncthreads_count(admit);
+    const int n_evict = __syncthreads_count(evict);
+    if (threadIdx.x == 0) {
+        blk_counts[blockIdx.x] = n_admit;
+        if (stats && n_evict) atomicAdd((unsigned long long*)&stats[1], (unsigned long long)n_evict);
+    }
+}
+
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(
+    CacheRW c, const int32_t* __restrict__ ids, int n, const uint8_t* __restrict__ admit_flag,
+    const int32_t* __restrict__ blk_counts, UpdHeader* __restrict__ hdr, int32_t* __restrict__ admit_pos,
+    int32_t* __restrict__ admit_slot, int64_t* __restrict__ stats) {
+    __shared__ long long red[16];
+    __shared__ int sc[17];
+    long long before = 0;
+    for (int b = threadIdx.x; b < (int)blockIdx.x; b += FG_SCAN_BLOCK) before += blk_counts[b];
+    before = fg_block_sum(before, red);
+    const int j = blockIdx.x * FG_SCAN_BLOCK + threadIdx.x;
+    const bool admit = j < n && admit_flag[j] != 0;
+    int total;
+    const long long rank = before + fg_block_rank(admit, total, sc);
+    bool overwrote = false;
+    if (admit && rank < c.capacity) {
+        const int64_t head = *c.head;
+        const int32_t s = (int32_t)((head + rank) % c.capacity);
+        const int32_t v = ids[j];
+        const int32_t old = c.slot_node[s];
+        if (old >= 0 && old < c.num_nodes && c.map[old] == s) {
+            const int64_t age = c.iter + 1 - (int64_t)c.slot_stamp[s];
+            overwrote = age >= 1 && age <= (int64_t)c.t_stale;
+        }
+        c.slot_node[s] = v;
+        c.slot_stamp[s] = (int32_t)c.iter;
+        c.map[v] = s;
+        admit_pos[rank] = j;
+        admit_slot[rank] = s;
+    }
+    const int n_over = __syncthreads_count(overwrote);
+    if (threadIdx.x == 0) {
+        if (stats && n_over) atomicAdd((unsigned long long*)&stats[2], (unsigned long long)n_over);
+        if (blockIdx.x == gridDim.x - 1) {
+            const long long all = before + total;
+            const long long in = all < c.capacity ? all : c.capacity;
+            hdr->n_admit = in;
+            if (stats) {
+                stats[0] = in;
+                stats[3] = all - in;
+            }
+        }
+    }
+}
+
+__global__ void advance_head_kernel(int64_t* head, const UpdHeader* hdr, int64_t capacity) {
+    if (threadIdx.x == 0 && blockIdx.x == 0) *head = (*head + hdr->n_admit) % capacity;
+}
+
+struct UpdWs {
+    size_t hdr, flag, blk, pos, slot, total;
+};
+UpdWs upd_layout(int64_t n) {
+    UpdWs w;
+    const int64_t nb = fg_ceil_div(n > 0 ? n : 1, FG_SCAN_BLOCK);
+    w.hdr = 0;
+    w.flag = 256;
+    w.blk = w.flag + fg_align_up((size_t)n, 256);
+    w.pos = w.blk + fg_align_up((size_t)nb * 4, 256);
+    w.slot = w.pos + fg_align_up((size_t)n * 4, 256);
+    w.total = w.slot + fg_align_up((size_t)n * 4, 256);
+    return w;
+}
+
+// ---- export -----------------------------------------------------------------------------------------------
+
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void export_flag_kernel(CacheRW c, uint8_t* __restrict__ flag,
+                                                                    int32_t* __restrict__ blk_counts) {
+    const int64_t s = (int64_t)blockIdx.x * FG_SCAN_BLOCK + threadIdx.x;
+    bool valid = false;
+    if (s < c.capacity) {
+        const int32_t v = c.slot_node[s];
+        if (v >= 0 && v < c.num_nodes && c.map[v] == (int32_t)s) {
+            const int64_t age = c.iter - (int64_t)c.slot_stamp[s];
+            valid = age >= 1 && age <= (int64_t)c.t_stale;
+        }
+        flag[s] = valid ? 1 : 0;
+    }
+    const int cnt = __syncthreads_count(valid);
+    if (threadIdx.x == 0) blk_counts[blockIdx.x] = cnt;
+}
+
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void export_write_kernel(CacheRW c, const uint8_t* __restrict__ flag,
+                                                                     const int32_t* __restrict__ blk_counts,
+                                                                     int32_t* __restrict__ nodes,
+                                                                     int32_t* __restrict__ slots,
+                                                                     int32_t* __restrict__ stamps,
+                                                                     int64_t* __restrict__ count_out,
+                                                                     int64_t* __restrict__ head_out) {
+    __shared__ long long red[16];
+    __shared__ int sc[17];
+    long long before = 0;
+    for (int b = threadIdx.x; b < (int)blockIdx.x; b += FG_SCAN_BLOCK) before += blk_counts[b];
+    before = fg_block_sum(before, red);
+    const int64_t s = (int64_t)blockIdx.x * FG_SCAN_BLOCK + threadIdx.x;
+    const bool valid = s < c.capacity && flag[s] != 0;
+    int total;
+    const long long rank = before + fg_block_rank(valid, total, sc);
+    if (valid) {
+        if (nodes) nodes[rank] = c.slot_node[s];
+        if (slots) slots[rank] = (int32_t)s;
+        if (stamps) stamps[rank] = c.slot_stamp[s];
+    }
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        *count_out = before + total;
+        if (head_out) *head_out = *c.head;
+    }
+}
+
+fg_status_t layer_of(const fg_cache_t* cache, int32_t layer, const char* who, const fg_layer** out) {
+    if (!cache) FG_FAIL(FG_ERR_INVALID_ARG, "%s: cache is NULL", who);
+    if (layer < 1 || layer > cache->n_layers)
+        FG_FAIL(FG_ERR_SHAPE, "%s: layer %d outside the cached layers 1..%d", who, layer, cache->n_layers);
+    *out = &cache->layers[layer - 1];
+    return FG_OK;
+}
+
+void free_layers(fg_cache_t* c) {
+    if (!c) return;
+    if (c->layers) {
+        for (int i = 0; i < c->n_layers; ++i) {
+            fg_layer& l = c->layers[i];
+            if (l.map) (void)hipFree(l.map);
+            if (l.slot_node) (void)hipFree(l.slot_node);
+            if (l.slot_stamp) (void)hipFree(l.slot_stamp);
+            if (l.table) (void)hipFree(l.table);
+            if (l.head) (void)hipFree(l.head);
+        }
+        delete[] c->layers;
+    }
+    delete c;
+}
+
+}  // namespace
+
+size_t fg_ws_cache_update_bytes(int64_t n) { return upd_layout(n).total; }
+size_t fg_ws_export_bytes(int64_t capacity) {
+    return fg_align_up((size_t)capacity, 256) + fg_align_up((size_t)fg_ceil_div(capacity > 0 ? capacity : 1, FG_SCAN_BLOCK) * 4, 256);
+}
+
+extern "C" fg_status_t fg_cache_clear(fg_cache_t* cache, void* stream) {
+    if (!cache) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_clear: cache is NULL");
+    hipStream_t st = (hipStream_t)stream;
+    for (int i = 0; i < cache->n_layers; ++i) {
+        fg_layer& l = cache->layers[i];
+        fg_status_t rc;
+        if ((rc = fg_launch_fill_i32(l.map, cache->num_nodes, -1, st)) != FG_OK) return rc;
+        if ((rc = fg_launch_fill_i32(l.slot_node, l.capacity, -1, st)) != FG_OK) return rc;
+        if ((rc = fg_launch_fill_i32(l.slot_stamp, l.capacity, 0, st)) != FG_OK) return rc;
+        if ((rc = fg_launch_fill_i32((int32_t*)l.head, 2, 0, st)) != FG_OK) return rc;
+        l.last_iter = INT64_MIN;
+    }
+    fg_clear_error();
+    return FG_OK;
+}
+
+extern "C" fg_status_t fg_cache_create(fg_cache_t** out, int64_t num_nodes, int32_t n_layers, const int64_t* capacity,
+                                       const int32_t* dim, fg_dtype_t dtype, int32_t t_stale, void* stream) {
+    if (!out) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create: out is NULL");
+    *out = nullptr;
+    if (num_nodes <= 0 || num_nodes > INT32_MAX)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create: num_nodes = %lld must be in 1..2^31-1", (long long)num_nodes);
+    if (n_layers < 0 || (n_layers > 0 && (!capacity || !dim)))
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create: n_layers = %d needs capacity and dim arrays", n_layers);
+    if (t_stale < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create: t_stale = %d is negative", t_stale);
+    const int esz = fg_dtype_size(dtype);
+    if (!esz) FG_FAIL(FG_ERR_DTYPE, "fg_cache_create: unknown element type %d", (int)dtype);
+    for (int i = 0; i < n_layers; ++i) {
+        if (capacity[i] <= 0 || capacity[i] > INT32_MAX)
+            FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create: capacity[%d] = %lld must be in 1..2^31-1", i, (long long)capacity[i]);
+        if (dim[i] <= 0 || ((int64_t)dim[i] * esz) % 16)
+            FG_FAIL(FG_ERR_SHAPE, "fg_cache_create: dim[%d] = %d must give rows that are a multiple of 16 bytes", i, dim[i]);
+    }
+    fg_cache_t* c = new fg_cache_t();
+    c->num_nodes = num_nodes;
+    c->n_layers = n_layers;
+    c->dtype = dtype;
+    c->t_stale = t_stale;
+    c->layers = n_layers ? new fg_layer[n_layers]() : nullptr;
+    for (int i = 0; i < n_layers; ++i) {
+        fg_layer& l = c->layers[i];
+        l.capacity = capacity[i];
+        l.dim = dim[i];
+        hipError_t e = hipMalloc((void**)&l.map, (size_t)num_nodes * 4);
+        if (e == hipSuccess) e = hipMalloc((void**)&l.slot_node, (size_t)l.capacity * 4);
+        if (e == hipSuccess) e = hipMalloc((void**)&l.slot_stamp, (size_t)l.capacity * 4);
+        if (e == hipSuccess) e = hipMalloc(&l.table, (size_t)l.capacity * l.dim * esz);
+        if (e == hipSuccess) e = hipMalloc((void**)&l.head, 16);
+        if (e != hipSuccess) {
+            free_layers(c);
+            (void)hipGetLastError();
+            FG_FAIL(e == hipErrorOutOfMemory ? FG_ERR_OOM : FG_ERR_HIP, "fg_cache_create: allocation for layer %d failed: %s",
+                    i + 1, hipGetErrorString(e));
+        }
+    }
+    fg_status_t rc = fg_cache_clear(c, stream);
+    if (rc != FG_OK) {
+        free_layers(c);
+        return rc;
+    }
+    *out = c;
+    return FG_OK;
+}
+
+extern "C" fg_status_t fg_cache_destroy(fg_cache_t* cache) {
+    if (!cache) return FG_OK;
+    (void)hipDeviceSynchronize();
+    free_layers(cache);
+    return FG_OK;
+}
+
+extern "C" const void* fg_cache_table(const fg_cache_t* cache, int32_t layer) {
+    const fg_layer* l;
+    if (layer_of(cache, layer, "fg_cache_table", &l) != FG_OK) return nullptr;
+    return l->table;
+}
+
+extern "C" fg_status_t fg_cache_set_t_stale(fg_cache_t* cache, int32_t t_stale) {
+    if (!cache) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_set_t_stale: cache is NULL");
+    if (t_stale < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_set_t_stale: t_stale = %d is negative", t_stale);
+    cache->t_stale = t_stale;
+    return FG_OK;
+}
+
+extern "C" fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, int64_t iter, int32_t* nodes_dev,
+                                       int32_t* slots_dev, int32_t* stamps_dev, int64_t* count_dev, int64_t* head_dev,
+                                       void* ws_dev, size_t ws_bytes, void* stream) {
+    const fg_layer* l;
+    fg_status_t rc = layer_of(cache, layer, "fg_cache_export", &l);
+    if (rc != FG_OK) return rc;
+    if (!count_dev) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_export: count_dev is NULL");
+    const size_t need = fg_ws_export_bytes(l->capacity);
+    if (!ws_dev || ws_bytes < need) FG_FAIL(FG_ERR_SHAPE, "fg_cache_export: workspace of %zu bytes given, %zu needed", ws_bytes, need);
+    fg_clear_error();
+    CacheRW c{l->map, l->slot_node, l->slot_stamp, l->head, l->capacity, cache->num_nodes, iter, cache->t_stale};
+    uint8_t* flag = (uint8_t*)ws_dev;
+    int32_t* blk = (int32_t*)((char*)ws_dev + fg_align_up((size_t)l->capacity, 256));
+    const int nb = (int)fg_ceil_div(l->capacity, FG_SCAN_BLOCK);
+    hipStream_t st = (hipStream_t)stream;
+    hipLaunchKernelGGL(export_flag_kernel, dim3(nb), dim3(FG_SCAN_BLOCK), 0, st, c, flag, blk);
+    FG_LAUNCH_CHECK("export_flag_kernel");
+    hipLaunchKernelGGL(export_write_kernel, dim3(nb), dim3(FG_SCAN_BLOCK), 0, st, c, flag, blk, nodes_dev, slots_dev,
+                       stamps_dev, count_dev, head_dev);
+    FG_LAUNCH_CHECK("export_write_kernel");
+    return FG_OK;
+}
+
+extern "C" fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t iter, const int32_t* ids_dev,
+                                       int32_t n, const uint8_t* live_dev, const uint8_t* hit_dev,
+                                       const float* gnorm_dev, float p_grad, const void* h_dev, int64_t h_stride,
+                                       int64_t* stats_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+    const fg_layer* lc;
+    fg_status_t rc = layer_of(cache, layer, "fg_cache_update", &lc);
+    if (rc != FG_OK) return rc;
+    fg_layer* l = &cache->layers[layer - 1];
+    if (n < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: n = %d is negative", n);
+    if (!(p_grad >= 0.0f && p_grad <= 1.0f)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: p_grad = %g outside [0, 1]", (double)p_grad);
+    if (n > 0 && (!ids_dev || !hit_dev || !gnorm_dev || !h_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: NULL pointer");
+    const int64_t row_bytes = (int64_t)l->dim * fg_dtype_size(cache->dtype);
+    if (h_stride < row_bytes) FG_FAIL(FG_ERR_SHAPE, "fg_cache_update: h_stride = %lld smaller than a cache row of %lld bytes", (long long)h_stride, (long long)row_bytes);
+    if (((uintptr_t)h_dev | (uintptr_t)h_stride) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: h_dev and h_stride must be 16-byte aligned");
+    if (iter < l->last_iter) FG_FAIL(FG_ERR_STATE, "fg_cache_update: iteration %lld after %lld: the counter must not go backwards", (long long)iter, (long long)l->last_iter);
+    if (iter < 0 || iter > INT32_MAX - 1) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: iteration %lld out of range", (long long)iter);
+    const UpdWs w = upd_layout(n);
+    if (!ws_dev || ws_bytes < w.total) FG_FAIL(FG_ERR_SHAPE, "fg_cache_update: workspace of %zu bytes given, %zu needed", ws_bytes, w.total);
+    if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: workspace must be 16-byte aligned");
+    fg_clear_error();
+    l->last_iter = iter;
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)ws_dev;
+    UpdHeader* hdr = (UpdHeader*)(ws + w.hdr);
+    uint8_t* flag = (uint8_t*)(ws + w.flag);
+    int32_t* blk = (int32_t*)(ws + w.blk);
+    int32_t* apos = (int32_t*)(ws + w.pos);
+    int32_t* aslot = (int32_t*)(ws + w.slot);
+    CacheRW c{l->map, l->slot_node, l->slot_stamp, l->head, l->capacity, cache->num_nodes, iter, cache->t_stale};
+    hipLaunchKernelGGL(select_tau_kernel, dim3(1), dim3(1024), 0, st, live_dev, gnorm_dev, n, p_grad, hdr, stats_dev);
+    FG_LAUNCH_CHECK("select_tau_kernel");
+    if (n == 0) return FG_OK;
+    const int nb = (int)fg_ceil_div(n, FG_SCAN_BLOCK);
+    hipLaunchKernelGGL(classify_update_kernel, dim3(nb), dim3(FG_SCAN_BLOCK), 0, st, c, ids_dev, n, live_dev, hit_dev,
+                       gnorm_dev, hdr, flag, blk, stats_dev);
+    FG_LAUNCH_CHECK("classify_update_kernel");
+    hipLaunchKernelGGL(assign_slots_kernel, dim3(nb), dim3(FG_SCAN_BLOCK), 0, st, c, ids_dev, n, flag, blk, hdr, apos,
+                       aslot, stats_dev);
+    FG_LAUNCH_CHECK("assign_slots_kernel");
+    rc = fg_launch_gather(h_dev, n, h_stride, row_bytes, apos, aslot, &hdr->n_admit, n < l->capacity ? n : l->capacity,
+                          l->table, l->capacity, row_bytes, 0, st);
+    if (rc != FG_OK) return rc;
+    hipLaunchKernelGGL(advance_head_kernel, dim3(1), dim3(64), 0, st, l->head, hdr, l->capacity);
+    FG_LAUNCH_CHECK("advance_head_kernel");
+    return FG_OK;
+}

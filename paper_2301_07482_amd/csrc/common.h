@@ -1,0 +1,63 @@
+// Internal declarations shared by the translation units of libfreshgnn (not part of the C ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "freshgnn.h"
+
+struct fg_layer {
+    int64_t capacity = 0;
+    int32_t dim = 0;
+    int32_t* map = nullptr;         // [num_nodes] slot of each node or -1
+    int32_t* slot_node = nullptr;   // [capacity] owner of each slot or -1
+    int32_t* slot_stamp = nullptr;  // [capacity] iteration whose update filled the slot
+    void* table = nullptr;          // [capacity x dim]
+    int64_t* head = nullptr;        // device scalar: ring header
+    int64_t last_iter = INT64_MIN;  // host: iteration of the last update
+};
+
+struct fg_cache {
+    int64_t num_nodes = 0;
+    int32_t n_layers = 0;
+    fg_dtype_t dtype = FG_F32;
+    int32_t t_stale = 0;
+    fg_layer* layers = nullptr;  // host array [n_layers], layer l at index l-1
+};
+
+void fg_set_error(const char* fmt, ...);
+void fg_clear_error();
+
+static inline int fg_dtype_size(fg_dtype_t t) { return t == FG_F32 ? 4 : (t == FG_F16 || t == FG_BF16) ? 2 : 0; }
+
+#define FG_FAIL(code, ...)         \
+    do {                           \
+        fg_set_error(__VA_ARGS__); \
+        return (code);             \
+    } while (0)
+
+#define FG_HIP(expr)                                                                       \
+    do {                                                                                   \
+        hipError_t e_ = (expr);                                                            \
+        if (e_ != hipSuccess) FG_FAIL(FG_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// Returns FG_ERR_HIP if the launch just queued was rejected.
+#define FG_LAUNCH_CHECK(name)                                                                          \
+    do {                                                                                               \
+        hipError_t e_ = hipGetLastError();                                                             \
+        if (e_ != hipSuccess) FG_FAIL(FG_ERR_HIP, "launch of %s failed: %s", name, hipGetErrorString(e_)); \
+    } while (0)
+
+constexpr int FG_SCAN_BLOCK = 1024;  // elements (= threads) per block in the compaction kernels
+
+static inline int64_t fg_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t fg_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// internal row copy used by fg_gather and by the cache update
+fg_status_t fg_launch_gather(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
+                             const int32_t* src_index, const int32_t* dst_pos, const int64_t* count_dev,
+                             int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride, int on_host,
+                             hipStream_t stream);
+// fill n bytes with a value (a kernel, so that callers may capture it into a graph)
+fg_status_t fg_launch_fill_u8(uint8_t* p, int64_t n, uint8_t value, hipStream_t stream);
+fg_status_t fg_launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t stream);

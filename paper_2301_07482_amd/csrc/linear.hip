@@ -1,0 +1,192 @@
+// fg_linear: h_out[r,:] = act([h_src[r,:] ‖ agg[k,:]] . W + bias) for r = rows[k]: the dense update phi of
+// Eq. 1 for GraphSAGE-mean, the only dense contraction on the path, on the matrix cores.
+//
+// fp32 path: v_mfma_f32_32x32x2_f32, fp32 accumulate. A workgroup of four wavefronts owns a 128 x 128 output
+// tile, each wavefront a 64 x 64 quadrant (2 x 2 MFMA blocks, 64 accumulator registers). The A operand is
+// never materialised: its first d_in columns are read from h_src at the listed positions and the last d_in
+// from the compact agg array, 16 bytes at a time, through LDS. K is walked in steps of 32; inside a step the
+// two half-wavefronts of an MFMA take k = s and k = 16 + s (s = 0..15), which lets every lane fetch its 16
+// A values as four 16-byte LDS reads (the sum over k does not care about the order).
+// Global loads of the next step are issued before the MFMAs of the current one.
+#include "common.h"
+
+namespace {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int LDA = BK + 4;  // floats; keeps 16-byte alignment and spreads rows over banks
+constexpr int LDB = BN + 4;
+constexpr int LIN_THREADS = 256;
+
+__global__ __launch_bounds__(LIN_THREADS) void linear_f32_kernel(
+    const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
+    const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
+    const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
+    int64_t out_stride) {
+    __shared__ __attribute__((aligned(16))) float As[BM * LDA];
+    __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
+    __shared__ int32_t row_of[BM];
+
+    int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
+    if (n_rows > max_rows) n_rows = max_rows;
+    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    if (m0 >= n_rows) return;
+    const int n0 = blockIdx.y * BN;
+    const int t = threadIdx.x;
+    const int K = 2 * d_in;
+
+    if (t < BM) {
+        const int64_t g = m0 + t;
+        int32_t r = -1;
+        if (g < n_rows) {
+            r = rows ? rows[g] : (int32_t)g;
+            if (r < 0 || r >= n_src || r >= n_out) r = -1;
+        }
+        row_of[t] = r;
+    }
+    __syncthreads();
+
+    // this thread's share of the global -> LDS traffic
+    const int a_kc = t & 7;   // which 16-byte piece of the 32-wide k step
+    const int a_m = t >> 3;   // rows a_m, a_m + 32, a_m + 64, a_m + 96
+    const int b_nc = t & 31;  // which 16-byte piece of the 128-wide n tile
+    const int b_k = t >> 5;   // k rows b_k, b_k + 8, b_k + 16, b_k + 24
+    const float* a_self[4];
+    const float* a_agg[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int m = a_m + 32 * i;
+        const int32_t r = row_of[m];
+        a_self[i] = r >= 0 ? (const float*)(h_src + (int64_t)r * src_stride) : nullptr;
+        a_agg[i] = r >= 0 ? (const float*)(agg + (m0 + m) * agg_stride) : nullptr;
+    }
+    const bool b_col_ok = (n0 + 4 * b_nc) < d_out;
+
+    f32x4 ra[4], rb[4];
+    auto load_step = [&](int k0) {
+        const int ka = k0 + 4 * a_kc;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (a_self[i] && ka < K) v = ka < d_in ? *(const f32x4*)(a_self[i] + ka) : *(const f32x4*)(a_agg[i] + (ka - d_in));
+            ra[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int kb = k0 + b_k + 8 * i;
+            f32x4 v = {0.f, 0.f, 0.f, 0.f};
+            if (b_col_ok && kb < K) v = *(const f32x4*)(W + (int64_t)kb * d_out + n0 + 4 * b_nc);
+            rb[i] = v;
+        }
+    };
+    auto store_step = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *(f32x4*)(As + (a_m + 32 * i) * LDA + 4 * a_kc) = ra[i];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) *(f32x4*)(Bs + (b_k + 8 * i) * LDB + 4 * b_nc) = rb[i];
+    };
+
+    const int lane = t & 63, wave = t >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    const int nk = (K + BK - 1) / BK;
+    load_step(0);
+    for (int step = 0; step < nk; ++step) {
+        store_step();
+        __syncthreads();
+        if (step + 1 < nk) load_step((step + 1) * BK);
+        f32x4 av[2][4];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) av[mb][q] = *(const f32x4*)(As + (wm + mb * 32 + l32) * LDA + 16 * half + 4 * q);
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const float b0 = Bs[(16 * half + s) * LDB + wn + l32];
+            const float b1 = Bs[(16 * half + s) * LDB + wn + 32 + l32];
+            const float a0 = av[0][s >> 2][s & 3];
+            const float a1 = av[1][s >> 2][s & 3];
+            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // epilogue: accumulator register i of a 32x32 block holds row 8*(i/4) + 4*half + i%4, column l32
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int c = n0 + wn + nb * 32 + l32;
+        if (c >= d_out) continue;
+        const float bv = bias ? bias[c] : 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = wm + mb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                const int32_t r = row_of[m];
+                if (r < 0) continue;
+                float v = acc[mb][nb][i] + bv;
+                if (relu) v = v > 0.f ? v : 0.f;
+                *(float*)(h_out + (int64_t)r * out_stride + (int64_t)c * 4) = v;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype,
+                                  const void* agg, int64_t agg_stride, const int32_t* rows_dev,
+                                  const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
+                                  const float* bias, int32_t relu, void* h_out, int32_t n_out, int64_t out_stride,
+                                  fg_dtype_t out_dtype, hipStream_t st);
+
+extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype,
+                                 const void* agg, int64_t agg_stride, const int32_t* rows_dev,
+                                 const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
+                                 fg_dtype_t w_dtype, const float* bias, int32_t relu, void* h_out, int32_t n_out,
+                                 int64_t out_stride, fg_dtype_t out_dtype, void* stream) {
+    if (max_rows < 0 || n_src < 0 || n_out < 0 || d_in <= 0 || d_out <= 0)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: bad size (max_rows %lld, n_src %d, n_out %d, d_in %d, d_out %d)",
+                (long long)max_rows, n_src, n_out, d_in, d_out);
+    if (!fg_dtype_size(in_dtype) || !fg_dtype_size(w_dtype) || !fg_dtype_size(out_dtype))
+        FG_FAIL(FG_ERR_DTYPE, "fg_linear: unknown element type");
+    if (max_rows > 0 && (!h_src || !agg || !W || !h_out)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: NULL pointer");
+    hipStream_t st = (hipStream_t)stream;
+    if (w_dtype == FG_F32) {
+        if (in_dtype != FG_F32 || out_dtype != FG_F32)
+            FG_FAIL(FG_ERR_DTYPE, "fg_linear: fp32 weights need fp32 inputs and outputs");
+        if (d_in % 4 || d_out % 4) FG_FAIL(FG_ERR_SHAPE, "fg_linear: d_in = %d and d_out = %d must be multiples of 4", d_in, d_out);
+        if (src_stride < (int64_t)d_in * 4 || agg_stride < (int64_t)d_in * 4 || out_stride < (int64_t)d_out * 4)
+            FG_FAIL(FG_ERR_SHAPE, "fg_linear: a row stride is smaller than its row");
+        if (((uintptr_t)h_src | (uintptr_t)agg | (uintptr_t)W | (uintptr_t)src_stride | (uintptr_t)agg_stride) & 15)
+            FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: h_src, agg, W and the input strides must be 16-byte aligned");
+        if (((uintptr_t)h_out | (uintptr_t)out_stride | (uintptr_t)bias) & 3)
+            FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: h_out, its stride and bias must be 4-byte aligned");
+        fg_clear_error();
+        if (max_rows == 0) return FG_OK;
+        dim3 grid((unsigned)fg_ceil_div(max_rows, BM), (unsigned)fg_ceil_div(d_out, BN));
+        hipLaunchKernelGGL(linear_f32_kernel, grid, dim3(LIN_THREADS), 0, st, (const char*)h_src, n_src, src_stride,
+                           (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, (const float*)W,
+                           bias, relu, (char*)h_out, n_out, out_stride);
+        FG_LAUNCH_CHECK("linear_f32_kernel");
+        return FG_OK;
+    }
+    if (w_dtype == FG_BF16)
+        return fg_launch_linear_bf16(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows_dev, n_rows_dev, max_rows,
+                                     d_in, d_out, W, bias, relu, h_out, n_out, out_stride, out_dtype, st);
+    FG_FAIL(FG_ERR_DTYPE, "fg_linear: weights must be F32 or BF16");
+}

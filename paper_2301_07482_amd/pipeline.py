@@ -1,0 +1,200 @@
+"""One training iteration's data path (Algorithm 1 without loss/backward) as a sequence of C-ABI calls.
+
+This module only owns device buffers (torch tensors) and the order of the calls; every computation is
+done by the HIP kernels behind `binding`. Nothing is copied back to the host between calls: element
+counts stay in device memory and each call is launched over a static upper bound.
+"""
+import numpy as np
+import torch
+
+from . import binding as B
+
+TORCH_DTYPE = {B.FG_F32: torch.float32, B.FG_F16: torch.float16, B.FG_BF16: torch.bfloat16}
+DTYPE_CODE = {"f32": B.FG_F32, "f16": B.FG_F16, "bf16": B.FG_BF16}
+
+
+def layer_bounds(batch, fanouts, num_nodes):
+    """Static upper bounds n_L..n_0 (index l) and nnz_l of a sampled mini-batch."""
+    L = len(fanouts)
+    n = [0] * (L + 1)
+    nnz = [0] * (L + 1)
+    n[L] = batch
+    for l in range(L, 0, -1):
+        nnz[l] = n[l] * fanouts[l - 1]
+        n[l - 1] = min(n[l] + nnz[l], num_nodes)
+    return n, nnz
+
+
+class DeviceBatch:
+    """A sampled mini-batch resident in device memory (ids, two-row-array blocks, gradient norms)."""
+
+    def __init__(self, mb, gnorms, device="cuda"):
+        L = mb.num_layers
+        self.num_layers = L
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
+        self.n = [len(x) for x in mb.ids]
+        self.ids = [up(x) for x in mb.ids]
+        self.start = [None] + [up(mb.start[l]) for l in range(1, L + 1)]
+        self.end = [None] + [up(mb.end[l]) for l in range(1, L + 1)]
+        self.col = [None] + [up(mb.col[l]) if len(mb.col[l]) else torch.zeros(1, dtype=torch.int32, device=device)
+                             for l in range(1, L + 1)]
+        self.nnz = [0] + [len(mb.col[l]) for l in range(1, L + 1)]
+        self.gnorm = {l: up(np.asarray(g, dtype=np.float32)) for l, g in (gnorms or {}).items()}
+
+
+class HotPath:
+    """Work buffers, cache and weights of one model; `run(batch, it)` executes one iteration."""
+
+    def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
+                 weights, features_on_host=False, device="cuda", use_cache=True):
+        self.device = device
+        self.L = L = len(fanouts)
+        self.dims = list(dims)
+        self.num_nodes = num_nodes
+        self.p_grad = float(p_grad)
+        self.feat = features
+        self.feat_code = DTYPE_CODE[feat_dtype]
+        self.comp_code = DTYPE_CODE[compute_dtype]
+        self.on_host = 1 if features_on_host else 0
+        self.use_cache = use_cache
+        self.n_max, self.nnz_max = layer_bounds(batch, fanouts, num_nodes)
+        n = self.n_max
+        dev = device
+        # embeddings by position: H[0] in the feature type, H[l] in the compute type, H[L] fp32
+        self.h_code = [self.feat_code] + [self.comp_code] * (L - 1) + [B.FG_F32]
+        self.H = [torch.zeros((n[l], dims[l]), dtype=TORCH_DTYPE[self.h_code[l]], device=dev) for l in range(L + 1)]
+        self.agg_code = B.FG_F32 if self.comp_code == B.FG_F32 else B.FG_BF16
+        agg_elems = max(n[l] * dims[l - 1] for l in range(1, L + 1))
+        self.AGG = torch.zeros(agg_elems, dtype=TORCH_DTYPE[self.agg_code], device=dev)
+        self.live = [torch.zeros(n[l], dtype=torch.uint8, device=dev) for l in range(L + 1)]
+        self.hit = [torch.zeros(n[l], dtype=torch.uint8, device=dev) for l in range(L + 1)]
+        self.hit_pos = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
+        self.hit_slot = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
+        self.normal_pos = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
+        self.input_ids = torch.zeros(n[0], dtype=torch.int32, device=dev)
+        self.counts = torch.zeros((L + 1, 3), dtype=torch.int64, device=dev)
+        self.stats = torch.zeros((L + 1, 4), dtype=torch.int64, device=dev)
+        ws_bytes = max(max(B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, n[l]) for l in range(L + 1)),
+                       max([B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L)] or [0]))
+        self.ws = torch.zeros(ws_bytes + 256, dtype=torch.uint8, device=dev)
+        self.ws_bytes = ws_bytes
+        self.W = {}
+        self.bias = {}
+        wt = TORCH_DTYPE[self.comp_code]
+        for l in range(1, L + 1):
+            W, b = weights[l]
+            self.W[l] = torch.from_numpy(np.ascontiguousarray(W)).to(dev).to(wt).contiguous()
+            self.bias[l] = torch.from_numpy(np.ascontiguousarray(b)).to(dev)
+        self.cache = None
+        if L > 1:
+            caps = [capacity] * (L - 1) if np.isscalar(capacity) else list(capacity)
+            self.capacity = caps
+            self.cache = B.fg_cache_create(num_nodes, caps, [dims[l] for l in range(1, L)], self.comp_code, t_stale,
+                                           self._stream())
+
+    def _stream(self):
+        return torch.cuda.current_stream().cuda_stream
+
+    def close(self):
+        if self.cache is not None:
+            B.fg_cache_destroy(self.cache)
+            self.cache = None
+
+    def _cnt(self, l, k):
+        return self.counts.data_ptr() + (l * 3 + k) * 8
+
+    def run(self, bt, it, update=True, stream=None):
+        L = self.L
+        st = self._stream() if stream is None else stream
+        esz = B.DTYPE_SIZE
+        assert all(bt.n[l] <= self.n_max[l] for l in range(L + 1)), "mini-batch larger than the static bounds"
+        # ---- top-down: lookup, prune, V_normal (layers L .. 0)
+        for l in range(L, -1, -1):
+            cache = self.cache if (self.use_cache and 1 <= l <= L - 1) else None
+            has_block = l >= 1
+            B.fg_lookup_prune(cache, l, it, bt.ids[l], bt.n[l], None if l == L else self.live[l],
+                              bt.start[l] if has_block else None, bt.end[l] if has_block else None,
+                              bt.col[l] if has_block else None, bt.nnz[l] if has_block else 0,
+                              bt.n[l - 1] if has_block else 0, self.live[l - 1] if has_block else None,
+                              self.hit[l], self.hit_pos[l], self.hit_slot[l], self.normal_pos[l],
+                              self.input_ids if l == 0 else None, self._cnt(l, 0), self.ws, self.ws_bytes, st)
+        # ---- loader: raw features of the surviving input nodes
+        d0b = self.dims[0] * esz[self.feat_code]
+        B.fg_gather(self.feat, self.num_nodes, d0b, d0b, self.input_ids, self.normal_pos[0], self._cnt(0, 2), bt.n[0],
+                    self.H[0], bt.n[0], d0b, self.on_host, st)
+        # ---- bottom-up: cached rows, mean aggregation, dense update
+        for l in range(1, L + 1):
+            in_code, out_code = self.h_code[l - 1], self.h_code[l]
+            in_b = self.dims[l - 1] * esz[in_code]
+            out_b = self.dims[l] * esz[out_code]
+            if self.use_cache and self.cache is not None and 1 <= l <= L - 1:
+                B.fg_gather(B.fg_cache_table(self.cache, l), self.capacity[l - 1], out_b, out_b, self.hit_slot[l],
+                            self.hit_pos[l], self._cnt(l, 1), bt.n[l], self.H[l], bt.n[l], out_b, 0, st)
+            agg_b = self.dims[l - 1] * esz[self.agg_code]
+            B.fg_aggregate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),
+                           bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], in_code, self.AGG, agg_b,
+                           self.agg_code, st)
+            B.fg_linear(self.H[l - 1], bt.n[l - 1], in_b, in_code, self.AGG, agg_b, self.normal_pos[l], self._cnt(l, 2),
+                        bt.n[l], self.dims[l - 1], self.dims[l], self.W[l], self.comp_code, self.bias[l],
+                        1 if l < L else 0, self.H[l], bt.n[l], out_b, out_code, st)
+        # ---- update of the caches
+        if update and self.use_cache and self.cache is not None:
+            for l in range(1, L):
+                out_b = self.dims[l] * esz[self.h_code[l]]
+                B.fg_cache_update(self.cache, l, it, bt.ids[l], bt.n[l], self.live[l], self.hit[l], bt.gnorm[l],
+                                  self.p_grad, self.H[l], out_b, self.stats.data_ptr() + l * 32, self.ws, self.ws_bytes, st)
+
+    # ---- read-back helpers for tests and reports (synchronising) -------------------------------------------
+    def snapshot(self, bt):
+        """Host copies of what one `run` produced (lists cut to their device-side counts)."""
+        L = self.L
+        torch.cuda.synchronize()
+        counts = self.counts.cpu().numpy()
+        out = dict(counts=counts, stats=self.stats.cpu().numpy(), layers={})
+        for l in range(L + 1):
+            n = bt.n[l]
+            n_hit, n_norm = int(counts[l, 1]), int(counts[l, 2])
+            out["layers"][l] = dict(
+                live=(self.live[l][:n].cpu().numpy().astype(bool) if l < L else np.ones(n, dtype=bool)),
+                hit=self.hit[l][:n].cpu().numpy().astype(bool),
+                hit_pos=self.hit_pos[l][:n_hit].cpu().numpy(), hit_slot=self.hit_slot[l][:n_hit].cpu().numpy(),
+                normal_pos=self.normal_pos[l][:n_norm].cpu().numpy(),
+                end=None if l == 0 else bt.end[l].cpu().numpy())
+        out["input_ids"] = self.input_ids[:int(counts[0, 2])].cpu().numpy()
+        return out
+
+    def export_cache(self, layer, it):
+        cap = self.capacity[layer - 1]
+        dev = self.device
+        nodes = torch.zeros(cap, dtype=torch.int32, device=dev)
+        slots = torch.zeros(cap, dtype=torch.int32, device=dev)
+        stamps = torch.zeros(cap, dtype=torch.int32, device=dev)
+        cnt = torch.zeros(2, dtype=torch.int64, device=dev)
+        wsb = B.fg_workspace_bytes(B.FG_WS_EXPORT, cap)
+        ws = torch.zeros(wsb, dtype=torch.uint8, device=dev)
+        B.fg_cache_export(self.cache, layer, it, nodes, slots, stamps, cnt.data_ptr(), cnt.data_ptr() + 8, ws, wsb,
+                          self._stream())
+        torch.cuda.synchronize()
+        c = int(cnt[0].item())
+        return dict(nodes=nodes[:c].cpu().numpy(), slots=slots[:c].cpu().numpy(), stamps=stamps[:c].cpu().numpy(),
+                    head=int(cnt[1].item()))
+
+    def cache_rows(self, layer, slots):
+        """Rows of the cache table at the given slots, as a host array (bf16 widened to fp32)."""
+        cap, d = self.capacity[layer - 1], self.dims[layer]
+        nbytes = cap * d * B.DTYPE_SIZE[self.comp_code]
+        tab = _tensor_from_ptr(B.fg_cache_table(self.cache, layer), (cap, d), TORCH_DTYPE[self.comp_code], nbytes, self.device)
+        idx = torch.as_tensor(np.asarray(slots, dtype=np.int64), device=self.device)
+        return tab[idx].float().cpu().numpy()
+
+
+class _Ext:
+    """Minimal __cuda_array_interface__ holder so torch can view library-owned device memory."""
+
+    def __init__(self, ptr, nbytes):
+        self.__cuda_array_interface__ = dict(shape=(nbytes,), typestr="|u1", data=(ptr, False), version=2)
+
+
+def _tensor_from_ptr(ptr, shape, dtype, nbytes, device):
+    raw = torch.as_tensor(_Ext(ptr, nbytes), device=device)
+    return raw.view(dtype).view(shape)

@@ -1,0 +1,37 @@
+"""Helpers of the GPU parity tests: build the HIP path and the oracle on the same seeded inputs."""
+import numpy as np
+
+from fg_inputs import features, workload as wl
+from oracle import freshgnn_oracle as O
+
+
+def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None, p_grad=None):
+    """HotPath for workload `w` with its feature table resident where the workload says."""
+    from fg_inputs import device as fdev
+    from paper_2301_07482_amd.pipeline import HotPath
+    dims = wl.layer_dims(w)
+    weights = {l: wl.layer_weights(w, l) for l in range(1, w.num_layers + 1)}
+    if feat_table is None:
+        feat_table = fdev.feature_table(w.seed, w.num_nodes, w.feat_dim, w.feat_dtype, w.feat_location)
+    hp = HotPath(w.num_nodes, dims, w.fanouts, w.batch, w.cache_capacity if capacity is None else capacity,
+                 w.t_stale if t_stale is None else t_stale, w.p_grad if p_grad is None else p_grad, feat_table,
+                 w.feat_dtype, w.compute_dtype, weights, features_on_host=(w.feat_location == "host"),
+                 use_cache=use_cache)
+    return hp, weights, feat_table
+
+
+def make_oracle_caches(w, capacity=None, t_stale=None):
+    dims = wl.layer_dims(w)
+    return {l: O.HistoricalCache(w.num_nodes, w.cache_capacity if capacity is None else capacity, dims[l],
+                                 w.t_stale if t_stale is None else t_stale, w.compute_dtype)
+            for l in range(1, w.num_layers)}
+
+
+def feature_accessor(w):
+    dt = np.float32 if w.feat_dtype == "f32" else np.float16
+    return lambda ids: features.feature_rows(w.seed, ids, w.feat_dim, dt)
+
+
+def to_f32(t):
+    """Host float32 copy of a device tensor of any float type."""
+    return t.float().cpu().numpy()

@@ -1,0 +1,405 @@
+"""GPU parity: every C-ABI call, and the whole iteration, against the CPU oracle on the same seeded inputs.
+
+Bars: bit-exact for flags, index lists, counts, pruned row ends, gathered rows and cache state;
+REL_TOL_F32 for aggregation and linear outputs (relative error as defined in helpers.rel_err_rows).
+"""
+import numpy as np
+import pytest
+
+from fg_inputs import features, workload as wl
+from oracle import freshgnn_oracle as O
+from tests import helpers as T
+from tests import gpu_common as G
+
+pytestmark = pytest.mark.gpu
+
+REL_TOL_F32 = 1e-5
+
+
+@pytest.fixture(scope="module")
+def env():
+    import torch
+    from paper_2301_07482_amd import binding as B
+    assert torch.cuda.is_available()
+    return torch, B
+
+
+def dev(torch, a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+# ------------------------------------------------------------------------------------------------ fg_gather
+
+@pytest.mark.parametrize("row_bytes,dtype", [(256, np.float32), (400, np.float32), (512, np.float32), (1024, np.float32),
+                                             (1536, np.float16), (2048, np.float16), (24, np.float32), (6, np.float16)])
+def test_gather_bit_exact(env, row_bytes, dtype):
+    torch, B = env
+    r = np.random.default_rng(row_bytes)
+    elems = row_bytes // np.dtype(dtype).itemsize
+    table_rows, n_dst, max_count = 5000, 3000, 2500
+    table = r.standard_normal((table_rows, elems)).astype(dtype)
+    for count, use_pos in [(max_count, True), (1733, True), (1, False), (0, True), (1733, False)]:
+        src = r.integers(0, table_rows, max_count).astype(np.int32)
+        pos = r.permutation(n_dst)[:max_count].astype(np.int32)
+        dst0 = r.standard_normal((n_dst, elems)).astype(dtype)
+        t_tab, t_src, t_pos, t_dst = dev(torch, table), dev(torch, src), dev(torch, pos), dev(torch, dst0)
+        t_cnt = torch.tensor([count], dtype=torch.int64, device="cuda")
+        B.fg_gather(t_tab, table_rows, row_bytes, row_bytes, t_src, t_pos if use_pos else None, t_cnt, max_count, t_dst,
+                    n_dst, row_bytes, 0, torch.cuda.current_stream().cuda_stream)
+        want = dst0.copy()
+        O.gather(lambda idx: table[idx], src[:count], want, pos[:count] if use_pos else None)
+        got = t_dst.cpu().numpy()
+        assert np.array_equal(got.view(np.uint8), want.view(np.uint8)), (row_bytes, count, use_pos)
+
+
+def test_gather_skips_out_of_range_and_strided_rows(env):
+    torch, B = env
+    r = np.random.default_rng(0)
+    table = r.standard_normal((100, 40)).astype(np.float32)        # 32 floats copied out of rows of 40
+    src = np.array([5, -1, 100, 7, 99, 0], dtype=np.int32)
+    pos = np.array([0, 1, 2, 50, 3, -4], dtype=np.int32)
+    dst0 = np.zeros((10, 36), dtype=np.float32)
+    t_dst = dev(torch, dst0)
+    B.fg_gather(dev(torch, table), 100, 160, 128, dev(torch, src), dev(torch, pos), None, 6, t_dst, 10, 144, 0, None)
+    want = dst0.copy()
+    want[0, :32] = table[5, :32]
+    want[3, :32] = table[99, :32]
+    assert np.array_equal(t_dst.cpu().numpy(), want)
+
+
+# ------------------------------------------------------------------------------------------------ fg_lookup_prune
+
+def _random_block(r, n, n_src, max_deg):
+    deg = r.integers(0, max_deg + 1, n)
+    gap = r.integers(0, 2, n)                                    # unused col entries between rows are allowed
+    start = np.cumsum(np.concatenate([[0], (deg + gap)[:-1]])).astype(np.int32)
+    end = (start + deg).astype(np.int32)
+    nnz = int(end[-1] + gap[-1]) if n else 0
+    col = r.integers(0, n_src, max(nnz, 1)).astype(np.int32)
+    return start, end, col, nnz
+
+
+@pytest.mark.parametrize("n,n_src,max_deg,seed", [(1, 5, 3, 0), (1000, 4000, 6, 1), (1024, 1024, 0, 2), (5000, 30000, 25, 3),
+                                                   (70001, 200000, 4, 4)])
+def test_lookup_prune_matches_oracle(env, n, n_src, max_deg, seed):
+    torch, B = env
+    r = np.random.default_rng(seed)
+    N, cap, t_stale, it = 300000, 4096, 5, 9
+    ids = r.permutation(N)[:n].astype(np.int32)
+    live = (r.random(n) < 0.7)
+    start, end, col, nnz = _random_block(r, n, n_src, max_deg)
+    # a cache state with valid, stale, recycled and checked-out entries: the same updates on both sides
+    oc = O.HistoricalCache(N, cap, 4, t_stale)
+    cache = B.fg_cache_create(N, [cap], [4], B.FG_F32, t_stale, None)
+    try:
+        for a in range(2, 9):
+            sub = r.permutation(n)[:min(n, 900)]
+            ids_a = np.concatenate([ids[sub], r.permutation(N)[:300].astype(np.int32)])
+            ids_a = ids_a[np.sort(np.unique(ids_a, return_index=True)[1])]
+            gn_a = np.exp(r.standard_normal(len(ids_a))).astype(np.float32)
+            rows_a = np.zeros((len(ids_a), 4), np.float32)
+            look = O.lookup_prune(oc, a, ids_a, None, None, None, None, 0)
+            O.cache_update(oc, a, ids_a, None, look["hit"], gn_a, 0.6, rows_a)
+            hit_dev, _, _ = _device_update(torch, B, cache, a, ids_a, None, gn_a, 0.6, rows_a)
+            assert np.array_equal(hit_dev, look["hit"])
+        for use_cache, use_live in [(True, True), (True, False), (False, True)]:
+            want_end = end.copy()
+            want = O.lookup_prune(oc if use_cache else None, it, ids, live if use_live else None, start, want_end, col, n_src)
+            t_end = dev(torch, end)
+            t_live_src = torch.full((n_src,), 7, dtype=torch.uint8, device="cuda")
+            t_hit = torch.full((n,), 9, dtype=torch.uint8, device="cuda")
+            t_hp, t_hs, t_np, t_ni = (torch.full((n,), -7, dtype=torch.int32, device="cuda") for _ in range(4))
+            t_cnt = torch.zeros(3, dtype=torch.int64, device="cuda")
+            wsb = B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, n)
+            ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+            B.fg_lookup_prune(cache if use_cache else None, 1, it, dev(torch, ids), n,
+                              dev(torch, live.astype(np.uint8)) if use_live else None, dev(torch, start), t_end,
+                              dev(torch, col), nnz, n_src, t_live_src, t_hit, t_hp, t_hs, t_np, t_ni, t_cnt, ws, wsb, None)
+            cnt = t_cnt.cpu().numpy()
+            assert tuple(cnt) == want["counts"]
+            assert np.array_equal(t_hit.cpu().numpy().astype(bool), want["hit"])
+            assert np.array_equal(t_hp.cpu().numpy()[:cnt[1]], want["hit_pos"])
+            assert np.array_equal(t_hs.cpu().numpy()[:cnt[1]], want["hit_slot"])
+            assert np.array_equal(t_np.cpu().numpy()[:cnt[2]], want["normal_pos"])
+            assert np.array_equal(t_ni.cpu().numpy()[:cnt[2]], ids[want["normal_pos"]])
+            assert np.array_equal(t_end.cpu().numpy(), want_end)
+            assert np.array_equal(t_live_src.cpu().numpy().astype(bool), want["live_src"])
+            if use_cache and n >= 1000:
+                assert cnt[1] > 0
+    finally:
+        B.fg_cache_destroy(cache)
+
+
+def _device_update(torch, B, cache, i, ids, live, gn, p, rows):
+    """Lookup (no block) followed by the update on the device; returns the hit flags."""
+    n = len(ids)
+    wsb = max(B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, n), B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n))
+    ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+    t_ids = dev(torch, ids)
+    t_live = None if live is None else dev(torch, live.astype(np.uint8))
+    t_hit = torch.zeros(max(n, 1), dtype=torch.uint8, device="cuda")
+    t_l = [torch.zeros(max(n, 1), dtype=torch.int32, device="cuda") for _ in range(3)]
+    t_cnt = torch.zeros(3, dtype=torch.int64, device="cuda")
+    B.fg_lookup_prune(cache, 1, i, t_ids, n, t_live, None, None, None, 0, 0, None, t_hit, t_l[0], t_l[1], t_l[2], None,
+                      t_cnt, ws, wsb, None)
+    t_stats = torch.zeros(4, dtype=torch.int64, device="cuda")
+    B.fg_cache_update(cache, 1, i, t_ids, n, t_live, t_hit, dev(torch, gn), p, dev(torch, rows), rows.shape[1] * 4, t_stats,
+                      ws, wsb, None)
+    return t_hit.cpu().numpy()[:n].astype(bool), t_l[1].cpu().numpy(), t_stats.cpu().numpy().tolist()
+
+
+# ------------------------------------------------------------------------------------------------ fg_aggregate
+
+@pytest.mark.parametrize("dim,dtype,max_deg,n", [(64, "f32", 10, 700), (100, "f32", 15, 3000), (128, "f32", 15, 5000),
+                                                 (256, "f32", 10, 900), (128, "f32", 150, 300), (768, "f16", 25, 400),
+                                                 (1024, "bf16", 15, 300), (4, "f32", 3, 50)])
+def test_aggregate_matches_oracle(env, dim, dtype, max_deg, n):
+    torch, B = env
+    r = np.random.default_rng(dim + max_deg)
+    n_src = 4 * n
+    start, end, col, nnz = _random_block(r, n, n_src, max_deg)
+    rows = np.sort(r.permutation(n)[: int(0.8 * n)]).astype(np.int32)
+    h64 = r.standard_normal((n_src, dim))
+    code = {"f32": B.FG_F32, "f16": B.FG_F16, "bf16": B.FG_BF16}[dtype]
+    tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[dtype]
+    h = O.round_to(h64, dtype)
+    t_h = torch.from_numpy(h.astype(np.float32)).cuda().to(tdt) if dtype == "bf16" else dev(torch, h)
+    esz = 2 if dtype != "f32" else 4
+    for out_dtype in (["f32"] if dtype == "f32" else ["f32", "bf16"]):
+        ocode = {"f32": B.FG_F32, "bf16": B.FG_BF16}[out_dtype]
+        otd = {"f32": torch.float32, "bf16": torch.bfloat16}[out_dtype]
+        t_out = torch.full((len(rows) + 3, dim), 5.0, dtype=otd, device="cuda")
+        t_cnt = torch.tensor([len(rows)], dtype=torch.int64, device="cuda")
+        B.fg_aggregate(dev(torch, start), dev(torch, end), dev(torch, col), nnz, n, dev(torch, rows), t_cnt, len(rows) + 3,
+                       t_h, n_src, dim * esz, dim, code, t_out, dim * (4 if out_dtype == "f32" else 2), ocode, None)
+        want = O.round_to(O.aggregate(start, end, col, rows, h), out_dtype).astype(np.float32)
+        got = G.to_f32(t_out)
+        assert np.all(got[len(rows):] == 5.0)                       # rows past the device-side count are untouched
+        tol = REL_TOL_F32 if out_dtype == "f32" else 2e-2
+        assert T.rel_err_rows(got[:len(rows)], want) <= tol
+        # fp64 accumulation and one rounding: in fact (almost) every element is the correctly rounded mean
+        assert (got[:len(rows)] == want).mean() > 0.999
+        empty = (end[rows] == start[rows])
+        assert empty.any() and np.all(got[:len(rows)][empty] == 0)
+
+
+# ------------------------------------------------------------------------------------------------ fg_linear
+
+def _linear_case(torch, B, r, n_src, n_rows, max_rows, d_in, d_out, relu, W=None, bias=None):
+    h = r.standard_normal((n_src, d_in)).astype(np.float32)
+    agg = r.standard_normal((max_rows, d_in)).astype(np.float32) * 0.3
+    rows = np.sort(r.permutation(n_src)[:max_rows]).astype(np.int32)
+    if W is None:
+        W = (r.standard_normal((2 * d_in, d_out)) / np.sqrt(2 * d_in)).astype(np.float32)
+    if bias is None:
+        bias = (0.1 * r.standard_normal(d_out)).astype(np.float32)
+    t_out = torch.full((n_src, d_out), -3.0, dtype=torch.float32, device="cuda")
+    t_cnt = torch.tensor([n_rows], dtype=torch.int64, device="cuda")
+    B.fg_linear(dev(torch, h), n_src, d_in * 4, B.FG_F32, dev(torch, agg), d_in * 4, dev(torch, rows), t_cnt, max_rows, d_in,
+                d_out, dev(torch, W), B.FG_F32, dev(torch, bias), 1 if relu else 0, t_out, n_src, d_out * 4, B.FG_F32, None)
+    got = t_out.cpu().numpy()
+    want = O.round_to(O.linear(h[rows[:n_rows]], agg[:n_rows], W, bias, relu), "f32")
+    untouched = np.ones(n_src, bool)
+    untouched[rows[:n_rows]] = False
+    assert np.all(got[untouched] == -3.0)
+    return got[rows[:n_rows]], want, h[rows[:n_rows]], agg[:n_rows]
+
+
+def test_linear_identity_panels_pin_operand_layout(env):
+    """W = [I;0] returns the node's own rows, W = [0;I] the neighbour means: exact in any accumulation order,
+    and wrong for any mistake in the matrix-core operand or accumulator layout."""
+    torch, B = env
+    r = np.random.default_rng(0)
+    for d in (64, 128, 100):
+        I, Z = np.eye(d, dtype=np.float32), np.zeros((d, d), np.float32)
+        zero = np.zeros(d, np.float32)
+        got, want, hs, ag = _linear_case(torch, B, r, 700, 333, 400, d, d, False, np.vstack([I, Z]), zero)
+        assert np.array_equal(got, hs)
+        got, want, hs, ag = _linear_case(torch, B, r, 700, 333, 400, d, d, False, np.vstack([Z, I]), zero)
+        assert np.array_equal(got, ag)
+        perm = r.permutation(d)
+        got, want, hs, ag = _linear_case(torch, B, r, 700, 333, 400, d, d, True, np.vstack([I[perm], Z]), zero)
+        assert np.array_equal(got, np.maximum(hs[:, np.argsort(perm)], 0))
+
+
+@pytest.mark.parametrize("d_in,d_out,n_rows,max_rows,relu", [(64, 64, 1000, 1200, True), (100, 256, 777, 777, True),
+                                                             (128, 256, 4097, 5000, True), (256, 256, 129, 200, False),
+                                                             (256, 256, 1, 128, True), (64, 64, 0, 128, True),
+                                                             (4, 4, 130, 130, False), (128, 260, 300, 300, True)])
+def test_linear_matches_oracle(env, d_in, d_out, n_rows, max_rows, relu):
+    torch, B = env
+    r = np.random.default_rng(d_in * 7 + d_out)
+    got, want, _, _ = _linear_case(torch, B, r, max_rows + 500, n_rows, max_rows, d_in, d_out, relu)
+    assert got.shape == want.shape
+    err = T.rel_err_rows(got, want)
+    print(f"linear {d_in}x{d_out} rows {n_rows}: rel err {err:.3e}")
+    assert err <= REL_TOL_F32
+
+
+# ------------------------------------------------------------------------------------------------ fg_cache_update
+
+@pytest.mark.parametrize("cap,t_stale,p,nmax", [(5, 2, 0.5, 12), (64, 4, 0.9, 40), (3, 1, 1.0, 9), (1000, 50, 0.3, 3000),
+                                                (4096, 3, 0.7, 5000)])
+def test_cache_update_sequences_match_oracle(env, cap, t_stale, p, nmax):
+    torch, B = env
+    r = np.random.default_rng(cap + nmax)
+    N, d = 20000 if nmax > 100 else 40, 8
+    oc = O.HistoricalCache(N, cap, d, t_stale)
+    cache = B.fg_cache_create(N, [cap], [d], B.FG_F32, t_stale, None)
+    from paper_2301_07482_amd.pipeline import _tensor_from_ptr
+    try:
+        for i in range(25):
+            n = int(r.integers(0, nmax + 1))
+            ids = r.permutation(N)[:n].astype(np.int32)
+            live = r.random(n) < 0.8
+            gn = np.round(np.exp(r.standard_normal(n)), 1 if nmax < 100 else 3).astype(np.float32)   # ties occur
+            rows = r.standard_normal((n, d)).astype(np.float32)
+            look = O.lookup_prune(oc, i, ids, live, None, None, None, 0)
+            hit_dev, slots_dev, stats_dev = _device_update(torch, B, cache, i, ids, live, gn, p, rows)
+            assert np.array_equal(hit_dev, look["hit"])                       # the device lookup sees the same hits
+            assert np.array_equal(slots_dev[:len(look["hit_slot"])], look["hit_slot"])
+            st = O.cache_update(oc, i, ids, live, look["hit"], gn, p, rows)
+            assert stats_dev == [st["admitted"], st["evicted_by_gradient"], st["overwritten"], st["dropped_overflow"]], \
+                f"stats at iteration {i}"
+            exp = _export(torch, B, cache, cap, i + 1)
+            valid = oc.valid_entries(i + 1) if cap <= 5000 else None
+            assert exp["head"] == oc.head
+            assert dict(zip(exp["nodes"].tolist(), zip(exp["slots"].tolist(), exp["stamps"].tolist()))) == valid
+            tab = _tensor_from_ptr(B.fg_cache_table(cache, 1), (cap, d), torch.float32, cap * d * 4, "cuda").cpu().numpy()
+            for v, (s, _) in valid.items():
+                assert np.array_equal(tab[s], oc.table[s])
+    finally:
+        B.fg_cache_destroy(cache)
+
+
+def _export(torch, B, cache, cap, it, layer=1):
+    t = [torch.zeros(cap, dtype=torch.int32, device="cuda") for _ in range(3)]
+    cnt = torch.zeros(2, dtype=torch.int64, device="cuda")
+    wsb = B.fg_workspace_bytes(B.FG_WS_EXPORT, cap)
+    ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+    B.fg_cache_export(cache, layer, it, t[0], t[1], t[2], cnt.data_ptr(), cnt.data_ptr() + 8, ws, wsb, None)
+    c = int(cnt[0].item())
+    return dict(nodes=t[0][:c].cpu().numpy(), slots=t[1][:c].cpu().numpy(), stamps=t[2][:c].cpu().numpy(), head=int(cnt[1].item()))
+
+
+def test_iteration_counter_must_not_go_backwards(env):
+    torch, B = env
+    cache = B.fg_cache_create(100, [10], [4], B.FG_F32, 3, None)
+    try:
+        z = lambda dt, n=4: torch.zeros(n, dtype=dt, device="cuda")
+        ws = torch.zeros(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, 4), dtype=torch.uint8, device="cuda")
+        args = lambda it: (cache, 1, it, dev(torch, np.arange(4, dtype=np.int32)), 4, None, z(torch.uint8), z(torch.float32),
+                           0.5, torch.zeros((4, 4), device="cuda"), 16, None, ws, ws.numel(), None)
+        B.fg_cache_update(*args(5))
+        with pytest.raises(B.FgError) as e:
+            B.fg_cache_update(*args(4))
+        assert e.value.code == B.FG_ERR_STATE
+    finally:
+        B.fg_cache_destroy(cache)
+
+
+# ------------------------------------------------------------------------------------------------ whole iterations
+
+def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
+                        sample_rows=None, feat_table=None):
+    """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence."""
+    g = wl.make_graph(w)
+    hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity)
+    caches = G.make_oracle_caches(w, capacity=capacity, t_stale=t_stale)
+    from paper_2301_07482_amd.pipeline import DeviceBatch
+    frows = G.feature_accessor(w)
+    dims = wl.layer_dims(w)
+    L = w.num_layers
+    p = w.p_grad if p_grad is None else p_grad
+    total_hits = 0
+    worst = 0.0
+    try:
+        for it in range(iterations):
+            mb = wl.minibatch(w, g, it)
+            gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
+            bt = DeviceBatch(mb, gn)
+            hp.run(bt, it)
+            snap = hp.snapshot(bt)
+            rec = O.iteration(mb, it, caches, frows, weights, gn, p, dims, w.feat_dtype, w.compute_dtype)
+            for l in range(L, -1, -1):
+                s, lk = snap["layers"][l], rec["look"][l]
+                assert tuple(snap["counts"][l]) == lk["counts"], f"counts, iteration {it} layer {l}"
+                assert np.array_equal(s["live"], rec["live"][l] if rec["live"][l] is not None else np.ones(len(mb.ids[l]), bool))
+                assert np.array_equal(s["hit"], lk["hit"])
+                assert np.array_equal(s["hit_pos"], lk["hit_pos"]) and np.array_equal(s["hit_slot"], lk["hit_slot"])
+                assert np.array_equal(s["normal_pos"], lk["normal_pos"])
+                if l >= 1:
+                    assert np.array_equal(s["end"], mb.end[l]), f"pruned row ends, iteration {it} layer {l}"
+                total_hits += len(lk["hit_pos"])
+            ipos = rec["look"][0]["normal_pos"]
+            assert np.array_equal(snap["input_ids"], mb.ids[0][ipos])
+            # gathered raw features: bit-exact
+            rows_chk = ipos if sample_rows is None or len(ipos) <= sample_rows else np.sort(
+                np.random.default_rng(it).choice(ipos, sample_rows, replace=False))
+            got0 = hp.H[0][torch.as_tensor(rows_chk.astype(np.int64), device="cuda")].cpu().numpy()
+            want0 = rec["H"][0][rows_chk]
+            assert np.array_equal(got0.view(np.uint8), want0.view(np.uint8)), f"gathered features, iteration {it}"
+            if it % check_numeric_every == 0 or it == iterations - 1:
+                tol = REL_TOL_F32 if w.compute_dtype == "f32" else 2e-2
+                for l in range(1, L + 1):
+                    npos = rec["look"][l]["normal_pos"]
+                    if len(npos):
+                        got = G.to_f32(hp.H[l][torch.as_tensor(npos.astype(np.int64), device="cuda")])
+                        err = T.rel_err_rows(got, rec["H"][l][npos].astype(np.float32))
+                        worst = max(worst, err)
+                        assert err <= tol, f"H[{l}] iteration {it}: rel err {err:.3e}"
+                    hpos = rec["look"][l]["hit_pos"]
+                    if len(hpos):
+                        # fetched rows are bit copies of the device cache, and match the oracle's cached rows within tolerance
+                        got = G.to_f32(hp.H[l][torch.as_tensor(hpos.astype(np.int64), device="cuda")])
+                        assert np.array_equal(got, hp.cache_rows(l, rec["look"][l]["hit_slot"]))
+                        assert T.rel_err_rows(got, rec["H"][l][hpos].astype(np.float32)) <= tol
+            for l in range(1, L):
+                st = rec["stats"][l]
+                assert snap["stats"][l].tolist() == [st["admitted"], st["evicted_by_gradient"], st["overwritten"],
+                                                     st["dropped_overflow"]], f"update stats, iteration {it} layer {l}"
+        for l in range(1, L):
+            exp = hp.export_cache(l, iterations)
+            oc = caches[l]
+            assert exp["head"] == oc.head
+            # compare the valid set through the oracle's predicate, node by node
+            for v, s, a in zip(exp["nodes"].tolist(), exp["slots"].tolist(), exp["stamps"].tolist()):
+                assert oc.slot_of(v, iterations) == s and int(oc.slot_stamp[s]) == a
+            filled = np.flatnonzero(oc.slot_node >= 0)
+            n_valid = sum(1 for s in filled if oc.slot_of(int(oc.slot_node[s]), iterations) == s)
+            assert n_valid == len(exp["nodes"])
+    finally:
+        hp.close()
+    return total_hits, worst
+
+
+def test_iterations_tiny(env):
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    hits, worst = run_workload_parity(torch, w, w.iterations)
+    print(f"tiny: {hits} hits over {w.iterations} iterations, worst rel err {worst:.3e}")
+    assert hits > 100
+
+
+def test_iterations_tiny_degenerate_settings(env):
+    """t_stale = 0 and p_grad = 0: no hit ever (Section 4.1.3), on the device as in the oracle."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    assert run_workload_parity(torch, w, 6, t_stale=0)[0] == 0
+    assert run_workload_parity(torch, w, 6, p_grad=0.0)[0] == 0
+
+
+def test_iterations_tiny_small_ring(env):
+    """A cache much smaller than a layer: wrap-around and overflow every iteration."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    hits, _ = run_workload_parity(torch, w, 10, capacity=97, p_grad=0.9)
+    assert hits > 0
+
+
+def test_iterations_medium(env):
+    torch, B = env
+    w = wl.WORKLOADS["medium"]
+    hits, worst = run_workload_parity(torch, w, 8, check_numeric_every=4, sample_rows=20000)
+    print(f"medium: {hits} hits, worst rel err {worst:.3e}")
+    assert hits > 0
