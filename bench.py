@@ -1,0 +1,217 @@
+#!/usr/bin/env python3
+"""Throughput of the whole hot path (lookup+prune, gather, cache fetch, aggregate, linear, cache update) on one MI355X.
+
+A step is one pass over one sampled mini-batch of the named workload; mini-batches, gradient norms and the
+feature table are resident in HBM before the timed region starts. Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large_hbm] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
+
+
+def _sample_one(args):
+    name, it = args
+    from fg_inputs import workload as wl
+    w = wl.WORKLOADS[name]
+    g = wl.make_graph(w)
+    mb = wl.minibatch(w, g, it)
+    gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, w.num_layers)}
+    return mb, gn
+
+
+def sample_batches(name, count, workers):
+    """Sample `count` mini-batches on host cores (before the GPU is touched: the pool forks)."""
+    from concurrent.futures import ProcessPoolExecutor
+    jobs = [(name, it) for it in range(count)]
+    if workers <= 1:
+        return [_sample_one(j) for j in jobs]
+    with ProcessPoolExecutor(max_workers=workers) as ex:
+        return list(ex.map(_sample_one, jobs, chunksize=1))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="large_hbm")
+    ap.add_argument("--scale", type=int, default=1, help="divide node/edge/cache counts (debugging on small boxes)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-cache", action="store_true", help="run with the historical cache disabled (plain neighbour sampling)")
+    ap.add_argument("--sample-workers", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build measures one GPU only (the path has no collectives); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    from fg_inputs import workload as wl
+    w = wl.WORKLOADS[args.workload]
+    if args.scale > 1:
+        w = w.scaled(args.scale)
+        wl.WORKLOADS[w.name] = w
+    total = args.warmup + args.steps
+    t0 = time.time()
+    sampled = sample_batches(w.name, total, args.sample_workers)
+    t_sample = time.time() - t0
+
+    import numpy as np
+    import torch
+    from paper_2301_07482_amd.pipeline import DeviceBatch
+    from tests import gpu_common as G
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    t0 = time.time()
+    hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache)
+    batches = [DeviceBatch(mb, gn) for mb, gn in sampled]
+    torch.cuda.synchronize()
+    t_setup = time.time() - t0
+    L = hp.L
+    assert total <= hp.ring
+
+    for it in range(args.warmup):
+        hp.run(batches[it], it)
+    torch.cuda.synchronize()
+
+    # timed region: exactly `steps` iterations; HIP events on the launch stream around every C-ABI call
+    ev = []
+
+    def timer_for(step_events):
+        def tick(name):
+            e = torch.cuda.Event(enable_timing=True)
+            e.record()
+            step_events.append((name, e))
+        return tick
+
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(args.steps):
+        it = args.warmup + k
+        step_events = []
+        hp.run(batches[it], it, timer=timer_for(step_events))
+        ev.append(step_events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    ms_per_step = 1e3 * elapsed / args.steps
+    value = args.steps / elapsed
+
+    # per-call device time from the events (each call's span runs to the next call's start event)
+    call_ms = {}
+    for step_events in ev:
+        for (name, e0), (_, e1) in zip(step_events[:-1], step_events[1:]):
+            call_ms.setdefault(name, []).append(e0.elapsed_time(e1))
+    call_avg_ms = {k: float(np.mean(v)) for k, v in call_ms.items()}
+
+    counts_log = hp.counts_log.cpu().numpy()
+    stats_log = hp.stats_log.cpu().numpy()
+    steps_it = [args.warmup + k for k in range(args.steps)]
+    counts = [counts_log[it % hp.ring] for it in steps_it]
+    esz = {"f32": 4, "f16": 2, "bf16": 2}
+    # algorithmic bytes / flops per step, averaged over the timed steps
+    feat_row = w.feat_dim * esz[w.feat_dtype]
+    gather_bytes = float(np.mean([c[0][2] * (4 + 2 * feat_row) for c in counts]))
+    # edges under normal rows of block 1 (host copy of the block and the device-side normal list are both known)
+    agg_bytes = {}
+    lin_flops = {}
+    lin_bytes = {}
+    for l in range(1, L + 1):
+        d_in, d_out = hp.dims[l - 1], hp.dims[l]
+        e_in = 4 if (l == 1 and w.feat_dtype == "f32") or w.compute_dtype == "f32" else 2
+        nn = float(np.mean([c[l][2] for c in counts]))
+        lin_flops[l] = 2.0 * nn * 2 * d_in * d_out
+        lin_bytes[l] = nn * (2 * d_in * e_in + d_out * 4) + 2 * d_in * d_out * 4
+    dom = max(call_avg_ms, key=call_avg_ms.get)
+    gather_ms = call_avg_ms["gather_features"]
+    roofline = dict(bound="hbm", kernel="gather_rows_kernel (fg_gather of raw features)",
+                    achieved=gather_bytes / (gather_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=gather_bytes / (gather_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, traffic=None,
+                    bytes_per_launch=gather_bytes, ms_per_launch=gather_ms)
+    lin1_ms = call_avg_ms.get("linear[1]")
+    linear_roof = dict(bound="mfma", kernel="linear_f32_kernel (layer 1)", achieved=lin_flops[1] / (lin1_ms * 1e-3) / 1e12,
+                       peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_flops[1] / (lin1_ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS,
+                       ms_per_launch=lin1_ms)
+
+    hits = {l: float(np.mean([c[l][1] for c in counts])) for l in range(1, L)}
+    n_input = float(np.mean([c[0][2] for c in counts]))
+    n0_all = float(np.mean([batches[it].n[0] for it in steps_it]))
+
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        cpu_baseline = time_oracle(w, sampled, weights)
+
+    hp.close()
+    out = {
+        "metric": "sampled mini-batches/sec (lookup+gather+aggregate+update); achieved GB/s vs roofline",
+        "value": value, "unit": "mini-batches/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.compute_dtype == "f32" else "bf16", "data": "synthetic",
+        "config": {"workload": w.name, "num_nodes": w.num_nodes, "num_edges": w.num_edges, "feat_dim": w.feat_dim,
+                   "feat_dtype": w.feat_dtype, "features": w.feat_location, "layers": L, "hidden": w.hidden,
+                   "fanouts": list(w.fanouts), "batch": w.batch, "cache_slots_per_layer": w.cache_capacity,
+                   "t_stale": w.t_stale, "p_grad": w.p_grad, "cache": not args.no_cache, "seed": w.seed},
+        "roofline": roofline,
+        "roofline_linear": linear_roof,
+        "cpu_baseline": cpu_baseline,
+        "per_call_ms": {k: round(v, 5) for k, v in sorted(call_avg_ms.items())},
+        "dominant_call": dom,
+        "per_step": {"input_rows_gathered": n_input, "input_rows_sampled": n0_all,
+                     "io_saving_vs_no_cache": 1.0 - n_input / n0_all if n0_all else 0.0,
+                     "hits": hits, "gather_bytes": gather_bytes, "linear_flops": lin_flops},
+        "host": {"sampling_s": t_sample, "setup_s": t_setup},
+    }
+    print(json.dumps(out))
+
+
+def time_oracle(w, sampled, weights, iterations=10):
+    """The CPU oracle timed on the first `iterations` mini-batches of the same workload (from an empty cache),
+    single-threaded; feature rows are regenerated beforehand and not timed."""
+    import numpy as np
+    from fg_inputs import features, workload as wl
+    from oracle import freshgnn_oracle as O
+    from tests import gpu_common as G
+    try:
+        from threadpoolctl import threadpool_limits
+        limiter = threadpool_limits(limits=1)
+    except Exception:  # pragma: no cover
+        limiter = None
+    caches = G.make_oracle_caches(w)
+    dims = wl.layer_dims(w)
+    dt = np.float32 if w.feat_dtype == "f32" else np.float16
+    secs = 0.0
+    done = 0
+    for it in range(min(iterations, len(sampled))):
+        mb, gn = sampled[it]
+        mb = mb.copy()
+        rows = features.feature_rows(w.seed, mb.ids[0], w.feat_dim, dt)      # not timed: input generation
+        order = np.argsort(mb.ids[0], kind="stable")
+        sorted_ids = mb.ids[0][order]
+
+        def frows(ids, rows=rows, order=order, sorted_ids=sorted_ids):
+            return rows[order[np.searchsorted(sorted_ids, ids)]]
+
+        t0 = time.perf_counter()
+        O.iteration(mb, it, caches, frows, weights, gn, w.p_grad, dims, w.feat_dtype, w.compute_dtype)
+        secs += time.perf_counter() - t0
+        done += 1
+        if secs > 20.0:
+            break
+    if limiter is not None:
+        limiter.restore_original_limits()
+    return {"value": done / secs, "unit": "mini-batches/s", "cores": 1, "kind": "oracle",
+            "sample": f"iterations 0..{done - 1} of the same workload from an empty cache, {secs:.1f} s of CPU time, "
+                      "feature-row generation excluded"}
+
+
+if __name__ == "__main__":
+    main()

@@ -1,13 +1,19 @@
 // fg_linear: h_out[r,:] = act([h_src[r,:] ‖ agg[k,:]] . W + bias) for r = rows[k]: the dense update phi of
 // Eq. 1 for GraphSAGE-mean, the only dense contraction on the path, on the matrix cores.
 //
-// fp32 path: v_mfma_f32_32x32x2_f32, fp32 accumulate. A workgroup of four wavefronts owns a 128 x 128 output
-// tile, each wavefront a 64 x 64 quadrant (2 x 2 MFMA blocks, 64 accumulator registers). The A operand is
-// never materialised: its first d_in columns are read from h_src at the listed positions and the last d_in
-// from the compact agg array, 16 bytes at a time, through LDS. K is walked in steps of 32; inside a step the
-// two half-wavefronts of an MFMA take k = s and k = 16 + s (s = 0..15), which lets every lane fetch its 16
-// A values as four 16-byte LDS reads (the sum over k does not care about the order).
-// Global loads of the next step are issued before the MFMAs of the current one.
+// fp32 path: v_mfma_f32_32x32x2_f32. A workgroup of eight wavefronts owns a 128 x 128 output tile, each
+// wavefront a 32 x 64 piece (two 32x32 MFMA blocks). The A operand is never materialised: its first d_in
+// columns are read from h_src at the listed positions and the last d_in from the compact agg array, 16 bytes
+// at a time, through LDS. K is walked in steps of 32; inside a step the two half-wavefronts of an MFMA take
+// k = s and k = 16 + s (s = 0..15), which lets every lane fetch its 16 A values as four 16-byte LDS reads
+// (the sum over k does not care about the order). Global loads of the next step are issued before the MFMAs
+// of the current one.
+//
+// Accuracy: a single fp32 accumulator over K = 512 products drifts by a few 1e-6 of the row scale, which is
+// the whole error budget of the path (1e-5). Each 32-wide K step therefore starts from a zero fp32
+// accumulator (small partial sums, small rounding steps) and is folded into an fp64 running sum on the
+// vector ALU, two instructions per output element and step next to 32 matrix instructions; bias, ReLU and
+// the single rounding to fp32 happen from the fp64 sum.
 #include "common.h"
 
 namespace {
@@ -18,7 +24,7 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int BM = 128, BN = 128, BK = 32;
 constexpr int LDA = BK + 4;  // floats; keeps 16-byte alignment and spreads rows over banks
 constexpr int LDB = BN + 4;
-constexpr int LIN_THREADS = 256;
+constexpr int LIN_THREADS = 512;
 
 __global__ __launch_bounds__(LIN_THREADS) void linear_f32_kernel(
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
@@ -48,34 +54,34 @@ __global__ __launch_bounds__(LIN_THREADS) void linear_f32_kernel(
     }
     __syncthreads();
 
-    // this thread's share of the global -> LDS traffic
+    // this thread's share of the global -> LDS traffic: two 16-byte pieces of A and two of W per step
     const int a_kc = t & 7;   // which 16-byte piece of the 32-wide k step
-    const int a_m = t >> 3;   // rows a_m, a_m + 32, a_m + 64, a_m + 96
+    const int a_m = t >> 3;   // rows a_m and a_m + 64
     const int b_nc = t & 31;  // which 16-byte piece of the 128-wide n tile
-    const int b_k = t >> 5;   // k rows b_k, b_k + 8, b_k + 16, b_k + 24
-    const float* a_self[4];
-    const float* a_agg[4];
+    const int b_k = t >> 5;   // k rows b_k and b_k + 16
+    const float* a_self[2];
+    const float* a_agg[2];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int m = a_m + 32 * i;
+    for (int i = 0; i < 2; ++i) {
+        const int m = a_m + 64 * i;
         const int32_t r = row_of[m];
         a_self[i] = r >= 0 ? (const float*)(h_src + (int64_t)r * src_stride) : nullptr;
         a_agg[i] = r >= 0 ? (const float*)(agg + (m0 + m) * agg_stride) : nullptr;
     }
     const bool b_col_ok = (n0 + 4 * b_nc) < d_out;
 
-    f32x4 ra[4], rb[4];
+    f32x4 ra[2], rb[2];
     auto load_step = [&](int k0) {
         const int ka = k0 + 4 * a_kc;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < 2; ++i) {
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
             if (a_self[i] && ka < K) v = ka < d_in ? *(const f32x4*)(a_self[i] + ka) : *(const f32x4*)(a_agg[i] + (ka - d_in));
             ra[i] = v;
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int kb = k0 + b_k + 8 * i;
+        for (int i = 0; i < 2; ++i) {
+            const int kb = k0 + b_k + 16 * i;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
             if (b_col_ok && kb < K) v = *(const f32x4*)(W + (int64_t)kb * d_out + n0 + 4 * b_nc);
             rb[i] = v;
@@ -83,22 +89,20 @@ __global__ __launch_bounds__(LIN_THREADS) void linear_f32_kernel(
     };
     auto store_step = [&]() {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *(f32x4*)(As + (a_m + 32 * i) * LDA + 4 * a_kc) = ra[i];
+        for (int i = 0; i < 2; ++i) *(f32x4*)(As + (a_m + 64 * i) * LDA + 4 * a_kc) = ra[i];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) *(f32x4*)(Bs + (b_k + 8 * i) * LDB + 4 * b_nc) = rb[i];
+        for (int i = 0; i < 2; ++i) *(f32x4*)(Bs + (b_k + 16 * i) * LDB + 4 * b_nc) = rb[i];
     };
 
     const int lane = t & 63, wave = t >> 6;
-    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 64;
     const int l32 = lane & 31, half = lane >> 5;
 
-    f32x16 acc[2][2];
+    double sum[2][16];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int b = 0; b < 2; ++b)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+        for (int i = 0; i < 16; ++i) sum[b][i] = 0.0;
 
     const int nk = (K + BK - 1) / BK;
     load_step(0);
@@ -106,42 +110,42 @@ __global__ __launch_bounds__(LIN_THREADS) void linear_f32_kernel(
         store_step();
         __syncthreads();
         if (step + 1 < nk) load_step((step + 1) * BK);
-        f32x4 av[2][4];
+        f32x4 av[4];
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb)
+        for (int q = 0; q < 4; ++q) av[q] = *(const f32x4*)(As + (wm + l32) * LDA + 16 * half + 4 * q);
+        f32x16 acc0, acc1;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) av[mb][q] = *(const f32x4*)(As + (wm + mb * 32 + l32) * LDA + 16 * half + 4 * q);
+        for (int i = 0; i < 16; ++i) acc0[i] = acc1[i] = 0.f;
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
             const float b0 = Bs[(16 * half + s) * LDB + wn + l32];
             const float b1 = Bs[(16 * half + s) * LDB + wn + 32 + l32];
-            const float a0 = av[0][s >> 2][s & 3];
-            const float a1 = av[1][s >> 2][s & 3];
-            acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-            acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-            acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-            acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+            const float a = av[s >> 2][s & 3];
+            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
+            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            sum[0][i] += (double)acc0[i];
+            sum[1][i] += (double)acc1[i];
         }
         __syncthreads();
     }
 
-    // epilogue: accumulator register i of a 32x32 block holds row 8*(i/4) + 4*half + i%4, column l32
+    // epilogue: accumulator element i of a 32x32 block is row 8*(i/4) + 4*half + i%4, column l32
 #pragma unroll
     for (int nb = 0; nb < 2; ++nb) {
         const int c = n0 + wn + nb * 32 + l32;
         if (c >= d_out) continue;
-        const float bv = bias ? bias[c] : 0.f;
+        const double bv = bias ? (double)bias[c] : 0.0;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int m = wm + mb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
-                const int32_t r = row_of[m];
-                if (r < 0) continue;
-                float v = acc[mb][nb][i] + bv;
-                if (relu) v = v > 0.f ? v : 0.f;
-                *(float*)(h_out + (int64_t)r * out_stride + (int64_t)c * 4) = v;
-            }
+        for (int i = 0; i < 16; ++i) {
+            const int m = wm + 8 * (i >> 2) + 4 * half + (i & 3);
+            const int32_t r = row_of[m];
+            if (r < 0) continue;
+            float v = (float)(sum[nb][i] + bv);
+            if (relu) v = v > 0.f ? v : 0.f;
+            *(float*)(h_out + (int64_t)r * out_stride + (int64_t)c * 4) = v;
         }
     }
 }

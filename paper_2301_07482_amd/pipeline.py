@@ -72,8 +72,12 @@ class HotPath:
         self.hit_slot = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
         self.normal_pos = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
         self.input_ids = torch.zeros(n[0], dtype=torch.int32, device=dev)
-        self.counts = torch.zeros((L + 1, 3), dtype=torch.int64, device=dev)
-        self.stats = torch.zeros((L + 1, 4), dtype=torch.int64, device=dev)
+        # device-side counts/stats are kept per iteration in a ring, so a timed loop can be read back afterwards
+        self.ring = 256
+        self.counts_log = torch.zeros((self.ring, L + 1, 3), dtype=torch.int64, device=dev)
+        self.stats_log = torch.zeros((self.ring, L + 1, 4), dtype=torch.int64, device=dev)
+        self.counts = self.counts_log[0]
+        self.stats = self.stats_log[0]
         ws_bytes = max(max(B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, n[l]) for l in range(L + 1)),
                        max([B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L)] or [0]))
         self.ws = torch.zeros(ws_bytes + 256, dtype=torch.uint8, device=dev)
@@ -103,15 +107,20 @@ class HotPath:
     def _cnt(self, l, k):
         return self.counts.data_ptr() + (l * 3 + k) * 8
 
-    def run(self, bt, it, update=True, stream=None):
+    def run(self, bt, it, update=True, stream=None, timer=None):
+        """One iteration. `timer(name)` (optional) is called before each C-ABI call and once at the end with None."""
         L = self.L
         st = self._stream() if stream is None else stream
+        self.counts = self.counts_log[it % self.ring]
+        self.stats = self.stats_log[it % self.ring]
+        tick = timer if timer is not None else (lambda name: None)
         esz = B.DTYPE_SIZE
         assert all(bt.n[l] <= self.n_max[l] for l in range(L + 1)), "mini-batch larger than the static bounds"
         # ---- top-down: lookup, prune, V_normal (layers L .. 0)
         for l in range(L, -1, -1):
             cache = self.cache if (self.use_cache and 1 <= l <= L - 1) else None
             has_block = l >= 1
+            tick(f"lookup_prune[{l}]")
             B.fg_lookup_prune(cache, l, it, bt.ids[l], bt.n[l], None if l == L else self.live[l],
                               bt.start[l] if has_block else None, bt.end[l] if has_block else None,
                               bt.col[l] if has_block else None, bt.nnz[l] if has_block else 0,
@@ -120,6 +129,7 @@ class HotPath:
                               self.input_ids if l == 0 else None, self._cnt(l, 0), self.ws, self.ws_bytes, st)
         # ---- loader: raw features of the surviving input nodes
         d0b = self.dims[0] * esz[self.feat_code]
+        tick("gather_features")
         B.fg_gather(self.feat, self.num_nodes, d0b, d0b, self.input_ids, self.normal_pos[0], self._cnt(0, 2), bt.n[0],
                     self.H[0], bt.n[0], d0b, self.on_host, st)
         # ---- bottom-up: cached rows, mean aggregation, dense update
@@ -128,12 +138,15 @@ class HotPath:
             in_b = self.dims[l - 1] * esz[in_code]
             out_b = self.dims[l] * esz[out_code]
             if self.use_cache and self.cache is not None and 1 <= l <= L - 1:
+                tick(f"cache_fetch[{l}]")
                 B.fg_gather(B.fg_cache_table(self.cache, l), self.capacity[l - 1], out_b, out_b, self.hit_slot[l],
                             self.hit_pos[l], self._cnt(l, 1), bt.n[l], self.H[l], bt.n[l], out_b, 0, st)
             agg_b = self.dims[l - 1] * esz[self.agg_code]
+            tick(f"aggregate[{l}]")
             B.fg_aggregate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),
                            bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], in_code, self.AGG, agg_b,
                            self.agg_code, st)
+            tick(f"linear[{l}]")
             B.fg_linear(self.H[l - 1], bt.n[l - 1], in_b, in_code, self.AGG, agg_b, self.normal_pos[l], self._cnt(l, 2),
                         bt.n[l], self.dims[l - 1], self.dims[l], self.W[l], self.comp_code, self.bias[l],
                         1 if l < L else 0, self.H[l], bt.n[l], out_b, out_code, st)
@@ -141,8 +154,10 @@ class HotPath:
         if update and self.use_cache and self.cache is not None:
             for l in range(1, L):
                 out_b = self.dims[l] * esz[self.h_code[l]]
+                tick(f"cache_update[{l}]")
                 B.fg_cache_update(self.cache, l, it, bt.ids[l], bt.n[l], self.live[l], self.hit[l], bt.gnorm[l],
                                   self.p_grad, self.H[l], out_b, self.stats.data_ptr() + l * 32, self.ws, self.ws_bytes, st)
+        tick(None)
 
     # ---- read-back helpers for tests and reports (synchronising) -------------------------------------------
     def snapshot(self, bt):
