@@ -9,12 +9,13 @@
 // handed out in one update are distinct. The result is therefore the same as the sequential procedure.
 //
 // Update = 4 launches, no host synchronisation:
-//   1. select_tau    one workgroup: m = live count, k = floor(p_grad*m), radix select (4 x 8 bits on the
-//                    order-preserving integer image of the fp32 norms) of the norm with rank k
+//   1. select_tau    one workgroup: m = live count, k = floor(p_grad*m), radix select (11+11+10 bits on the
+//                    order-preserving integer image of the fp32 norms, keys held in registers) of the norm with rank k
 //   2. classify      check out hits that are not below tau; flag admissible normal nodes; count per workgroup
 //   3. assign_slots  rank admissible nodes in position order (ballot ranks + preceding workgroups' counts),
-//                    hand out ring slots head + rank, write slot_node / slot_stamp / map, list (position, slot)
-//   4. row copy      table[slot] = h[position] (the gather kernel), then the header moves
+//                    hand out ring slots head + rank, write slot_node / slot_stamp / map, list (position, slot);
+//                    the last workgroup leaves the advanced header in the spare header cell
+//   4. row copy      table[slot] = h[position] (the gather kernel)
 #include "common.h"
 #include "scan.h"
 
@@ -32,60 +33,126 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-__global__ __launch_bounds__(1024) void select_tau_kernel(const uint8_t* __restrict__ live,
-                                                          const float* __restrict__ gnorm, int n, float p_grad,
-                                                          UpdHeader* __restrict__ hdr, int64_t* __restrict__ stats) {
-    __shared__ unsigned int hist[256];
+// Exact rank-k selection by one workgroup: three radix passes (11, 11 and 10 bits, most significant first)
+// over the order-preserving keys. A pass builds a histogram of the keys that match the digits found so far
+// with LDS atomics and finds the bin that contains the wanted rank with a workgroup scan. The first two passes
+// stream the norms from memory (a few hundred KB, L2-resident after the first); the keys that survive the
+// first digit are parked in LDS for the last pass (if they do not fit, the last pass streams as well).
+constexpr int SEL_THREADS = 1024;
+constexpr int SEL_BINS = 2048;
+constexpr int SEL_BPT = SEL_BINS / SEL_THREADS;  // bins owned by a thread in the scan
+constexpr int SEL_PARK = 8192;                   // survivors kept in LDS
+
+// Finds the bin holding rank *s_rank in hist[] (counts), stores it in *s_bin and rebases *s_rank to that bin.
+__device__ __forceinline__ void select_bin(const unsigned int* hist, long long* red, uint32_t* s_bin, long long* s_rank) {
+    const int t = threadIdx.x;
+    unsigned int h[SEL_BPT];
+    long long mine = 0;
+#pragma unroll
+    for (int q = 0; q < SEL_BPT; ++q) {
+        h[q] = hist[SEL_BPT * t + q];
+        mine += h[q];
+    }
+    long long incl = mine;  // inclusive scan over the wavefront, then wavefront totals through LDS
+    for (int off = 1; off < FG_WAVE; off <<= 1) {
+        const long long v = __shfl_up(incl, off, FG_WAVE);
+        if (fg_lane() >= off) incl += v;
+    }
+    __syncthreads();
+    if (fg_lane() == FG_WAVE - 1) red[fg_wave()] = incl;
+    __syncthreads();
+    long long before = incl - mine;
+    for (int w = 0; w < fg_wave(); ++w) before += red[w];
+    const long long rank = *s_rank;
+    __syncthreads();
+    if (rank >= before && rank < before + mine) {  // true for exactly one thread
+        long long lo = before;
+#pragma unroll
+        for (int q = 0; q < SEL_BPT; ++q) {
+            if (rank >= lo && rank < lo + h[q]) {
+                *s_bin = SEL_BPT * t + q;
+                *s_rank = rank - lo;
+            }
+            lo += h[q];
+        }
+    }
+    __syncthreads();
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void select_tau_kernel(const uint8_t* __restrict__ live,
+                                                                 const float* __restrict__ gnorm, int n, float p_grad,
+                                                                 UpdHeader* __restrict__ hdr, int64_t* __restrict__ stats) {
+    __shared__ unsigned int hist[SEL_BINS];
+    __shared__ uint32_t park[SEL_PARK];
     __shared__ long long red[16];
-    __shared__ uint32_t s_prefix;
+    __shared__ uint32_t s_bin;
     __shared__ long long s_rank;
+    __shared__ unsigned int s_parked;
+    const int t = threadIdx.x;
+    // pass 0: top 11 bits of every live key; the histogram total is the live count m
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
+    if (t == 0) s_parked = 0;
+    __syncthreads();
+    for (int j = t; j < n; j += SEL_THREADS)
+        if (live ? live[j] != 0 : true) atomicAdd(&hist[order_key(gnorm[j]) >> 21], 1u);
+    __syncthreads();
     long long c = 0;
-    for (int j = threadIdx.x; j < n; j += blockDim.x) c += (live ? live[j] != 0 : true) ? 1 : 0;
+#pragma unroll
+    for (int q = 0; q < SEL_BPT; ++q) c += hist[SEL_BPT * t + q];
     const long long m = fg_block_sum(c, red);
     const long long k = (long long)floor((double)p_grad * (double)m);
-    if (threadIdx.x == 0) {
+    if (t == 0) {
         hdr->m_live = m;
         hdr->n_admit = 0;
         if (stats) stats[0] = stats[1] = stats[2] = stats[3] = 0;
     }
     if (k <= 0 || k >= m) {
-        if (threadIdx.x == 0) {
+        if (t == 0) {
             hdr->mode = k <= 0 ? 0 : 2;
             hdr->tau_key = 0;
         }
         return;
     }
-    if (threadIdx.x == 0) {
-        s_prefix = 0;
-        s_rank = k;
+    if (t == 0) s_rank = k;
+    __syncthreads();
+    select_bin(hist, red, &s_bin, &s_rank);
+    const uint32_t d0 = s_bin;
+    // pass 1: middle 11 bits of the keys whose top digit is d0; park those keys in LDS
+    __syncthreads();
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
+    __syncthreads();
+    for (int j = t; j < n; j += SEL_THREADS) {
+        if (live && !live[j]) continue;
+        const uint32_t kj = order_key(gnorm[j]);
+        if ((kj >> 21) != d0) continue;
+        atomicAdd(&hist[(kj >> 10) & 2047u], 1u);
+        const unsigned int at = atomicAdd(&s_parked, 1u);
+        if (at < SEL_PARK) park[at] = kj;
     }
-    for (int pass = 0; pass < 4; ++pass) {
-        const int shift = 24 - 8 * pass;
-        if (threadIdx.x < 256) hist[threadIdx.x] = 0;
-        __syncthreads();
-        const uint32_t prefix = s_prefix;
-        const uint32_t mask = pass == 0 ? 0u : (0xFFFFFFFFu << (shift + 8));
-        for (int j = threadIdx.x; j < n; j += blockDim.x) {
+    __syncthreads();
+    select_bin(hist, red, &s_bin, &s_rank);
+    const uint32_t d1 = s_bin;
+    const uint32_t hi = (d0 << 21) | (d1 << 10);
+    const unsigned int parked = s_parked;
+    // pass 2: low 10 bits of the keys whose upper 22 bits are (d0, d1)
+    __syncthreads();
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
+    __syncthreads();
+    if (parked <= SEL_PARK) {
+        for (unsigned int i = t; i < parked; i += SEL_THREADS)
+            if ((park[i] & 0xFFFFFC00u) == hi) atomicAdd(&hist[park[i] & 1023u], 1u);
+    } else {
+        for (int j = t; j < n; j += SEL_THREADS) {
             if (live && !live[j]) continue;
-            const uint32_t key = order_key(gnorm[j]);
-            if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1u);
+            const uint32_t kj = order_key(gnorm[j]);
+            if ((kj & 0xFFFFFC00u) == hi) atomicAdd(&hist[kj & 1023u], 1u);
         }
-        __syncthreads();
-        if (threadIdx.x == 0) {
-            long long rank = s_rank;
-            int b = 0;
-            for (; b < 255; ++b) {
-                if (rank < (long long)hist[b]) break;
-                rank -= hist[b];
-            }
-            s_rank = rank;
-            s_prefix = prefix | ((uint32_t)b << shift);
-        }
-        __syncthreads();
     }
-    if (threadIdx.x == 0) {
+    __syncthreads();
+    select_bin(hist, red, &s_bin, &s_rank);
+    if (t == 0) {
         hdr->mode = 1;
-        hdr->tau_key = s_prefix;
+        hdr->tau_key = hi | s_bin;
     }
 }
 
@@ -93,7 +160,8 @@ struct CacheRW {
     int32_t* map;
     int32_t* slot_node;
     int32_t* slot_stamp;
-    int64_t* head;
+    const int64_t* head;  // current ring header
+    int64_t* head_next;   // where an update leaves the advanced header (the two swap roles after every update)
     int64_t capacity;
     int64_t num_nodes;
     int64_t iter;
@@ -163,16 +231,13 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(
             const long long all = before + total;
             const long long in = all < c.capacity ? all : c.capacity;
             hdr->n_admit = in;
+            *c.head_next = (*c.head + in) % c.capacity;
             if (stats) {
                 stats[0] = in;
                 stats[3] = all - in;
             }
         }
     }
-}
-
-__global__ void advance_head_kernel(int64_t* head, const UpdHeader* hdr, int64_t capacity) {
-    if (threadIdx.x == 0 && blockIdx.x == 0) *head = (*head + hdr->n_admit) % capacity;
 }
 
 struct UpdWs {
@@ -275,7 +340,8 @@ extern "C" fg_status_t fg_cache_clear(fg_cache_t* cache, void* stream) {
         if ((rc = fg_launch_fill_i32(l.map, cache->num_nodes, -1, st)) != FG_OK) return rc;
         if ((rc = fg_launch_fill_i32(l.slot_node, l.capacity, -1, st)) != FG_OK) return rc;
         if ((rc = fg_launch_fill_i32(l.slot_stamp, l.capacity, 0, st)) != FG_OK) return rc;
-        if ((rc = fg_launch_fill_i32((int32_t*)l.head, 2, 0, st)) != FG_OK) return rc;
+        if ((rc = fg_launch_fill_i32((int32_t*)l.head, 4, 0, st)) != FG_OK) return rc;
+        l.head_cur = 0;
         l.last_iter = INT64_MIN;
     }
     fg_clear_error();
@@ -360,7 +426,7 @@ extern "C" fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, i
     const size_t need = fg_ws_export_bytes(l->capacity);
     if (!ws_dev || ws_bytes < need) FG_FAIL(FG_ERR_SHAPE, "fg_cache_export: workspace of %zu bytes given, %zu needed", ws_bytes, need);
     fg_clear_error();
-    CacheRW c{l->map, l->slot_node, l->slot_stamp, l->head, l->capacity, cache->num_nodes, iter, cache->t_stale};
+    CacheRW c{l->map, l->slot_node, l->slot_stamp, l->head + l->head_cur, nullptr, l->capacity, cache->num_nodes, iter, cache->t_stale};
     uint8_t* flag = (uint8_t*)ws_dev;
     int32_t* blk = (int32_t*)((char*)ws_dev + fg_align_up((size_t)l->capacity, 256));
     const int nb = (int)fg_ceil_div(l->capacity, FG_SCAN_BLOCK);
@@ -401,8 +467,8 @@ extern "C" fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t
     int32_t* blk = (int32_t*)(ws + w.blk);
     int32_t* apos = (int32_t*)(ws + w.pos);
     int32_t* aslot = (int32_t*)(ws + w.slot);
-    CacheRW c{l->map, l->slot_node, l->slot_stamp, l->head, l->capacity, cache->num_nodes, iter, cache->t_stale};
-    hipLaunchKernelGGL(select_tau_kernel, dim3(1), dim3(1024), 0, st, live_dev, gnorm_dev, n, p_grad, hdr, stats_dev);
+    CacheRW c{l->map, l->slot_node, l->slot_stamp, l->head + l->head_cur, l->head + (l->head_cur ^ 1), l->capacity, cache->num_nodes, iter, cache->t_stale};
+    hipLaunchKernelGGL(select_tau_kernel, dim3(1), dim3(SEL_THREADS), 0, st, live_dev, gnorm_dev, n, p_grad, hdr, stats_dev);
     FG_LAUNCH_CHECK("select_tau_kernel");
     if (n == 0) return FG_OK;
     const int nb = (int)fg_ceil_div(n, FG_SCAN_BLOCK);
@@ -415,7 +481,6 @@ extern "C" fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t
     rc = fg_launch_gather(h_dev, n, h_stride, row_bytes, apos, aslot, &hdr->n_admit, n < l->capacity ? n : l->capacity,
                           l->table, l->capacity, row_bytes, 0, st);
     if (rc != FG_OK) return rc;
-    hipLaunchKernelGGL(advance_head_kernel, dim3(1), dim3(64), 0, st, l->head, hdr, l->capacity);
-    FG_LAUNCH_CHECK("advance_head_kernel");
+    l->head_cur ^= 1;  // the advanced header written by assign_slots is the current one from here on
     return FG_OK;
 }

@@ -12,7 +12,8 @@ struct fg_layer {
     int32_t* slot_node = nullptr;   // [capacity] owner of each slot or -1
     int32_t* slot_stamp = nullptr;  // [capacity] iteration whose update filled the slot
     void* table = nullptr;          // [capacity x dim]
-    int64_t* head = nullptr;        // device scalar: ring header
+    int64_t* head = nullptr;        // device int64[2]: ring header, double-buffered (head_cur indexes the current one)
+    int head_cur = 0;
     int64_t last_iter = INT64_MIN;  // host: iteration of the last update
 };
 
