@@ -50,6 +50,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-cache", action="store_true", help="run with the historical cache disabled (plain neighbour sampling)")
     ap.add_argument("--sample-workers", type=int, default=8)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device-to-device copy before the warm-up, as the known-size "
+                         "reference for scaling hardware traffic counters")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build measures one GPU only (the path has no collectives); run with --gpus 1", file=sys.stderr)
@@ -78,6 +81,14 @@ def main():
     t_setup = time.time() - t0
     L = hp.L
     assert total <= hp.ring
+
+    if args.calibration_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        b.copy_(a)                     # reads 2**30 bytes, writes 2**30 bytes
+        torch.cuda.synchronize()
+        del a, b
 
     for it in range(args.warmup):
         hp.run(batches[it], it)

@@ -94,6 +94,13 @@ fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, int64_t iter
                             int32_t* slots_dev, int32_t* stamps_dev, int64_t* count_dev, int64_t* head_dev,
                             void* ws_dev, size_t ws_bytes, void* stream);
 
+/*
+ * Launch-shape overrides for measurements (defaults are tuned for MI355X and need no call). Keys:
+ * "gather_wg_per_cu", "gather_host_wg_per_cu", "gather_unroll" (1, 2, 4, 8), "gather_nontemporal" (0/1),
+ * "aggregate_wg_per_cu". Process-wide, not thread-safe against concurrent launches. Results never depend on them.
+ */
+fg_status_t fg_set_tuning(const char* key, int64_t value);
+
 typedef enum { FG_WS_LOOKUP_PRUNE = 0, FG_WS_CACHE_UPDATE = 1, FG_WS_EXPORT = 2 } fg_ws_kind_t;
 /* Bytes of device workspace the named call needs for a layer of n nodes (0 on a bad argument). */
 size_t fg_workspace_bytes(fg_ws_kind_t kind, int64_t n, int64_t reserved);
@@ -139,13 +146,20 @@ fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, int64_t iter
  *   dst_pos_dev[max_count]          int32 destination rows, or NULL for k itself
  *   count_dev, max_count            int64 device count (NULL = max_count) and its host-known upper bound
  *   dst, dst_rows, dst_stride       destination (device), rows, bytes between rows
- *   table_on_host                   0 = table in HBM, 1 = table in mapped host memory (tuning hint only)
+ *   table_kind                      FG_TABLE_* below: where the rows live and whether they are read once (a hint
+ *                                   for the load policy and launch shape only; results do not depend on it)
  * Entries with src_index or dst_pos out of range are skipped. Pointers and strides must be aligned to
  * the largest power of two <= 16 that divides row_bytes.
  */
+typedef enum {
+    FG_TABLE_HBM_STREAMED = 0, /* big table in HBM, each row read once per call (raw features) */
+    FG_TABLE_HOST_MAPPED = 1,  /* table in pinned host memory mapped into the device address space */
+    FG_TABLE_HBM_REUSED = 2    /* rows recently written or read again soon (cached embeddings, layer outputs) */
+} fg_table_kind_t;
+
 fg_status_t fg_gather(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
                       const int32_t* src_index_dev, const int32_t* dst_pos_dev, const int64_t* count_dev,
-                      int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride, int32_t table_on_host,
+                      int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride, int32_t table_kind,
                       void* stream);
 
 /*

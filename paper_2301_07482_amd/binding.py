@@ -13,6 +13,7 @@ LIB_PATH = os.path.join(_HERE, "libfreshgnn.so")
 FG_OK, FG_ERR_INVALID_ARG, FG_ERR_SHAPE, FG_ERR_DTYPE, FG_ERR_STATE, FG_ERR_OOM, FG_ERR_HIP = range(7)
 FG_F32, FG_F16, FG_BF16 = 0, 1, 2
 FG_WS_LOOKUP_PRUNE, FG_WS_CACHE_UPDATE, FG_WS_EXPORT = 0, 1, 2
+FG_TABLE_HBM_STREAMED, FG_TABLE_HOST_MAPPED, FG_TABLE_HBM_REUSED = 0, 1, 2
 DTYPE_SIZE = {FG_F32: 4, FG_F16: 2, FG_BF16: 2}
 
 if not os.path.exists(LIB_PATH):
@@ -32,6 +33,7 @@ SIGNATURES = {
     "fg_cache_set_t_stale": (_i32, [_p, _i32]),
     "fg_cache_export": (_i32, [_p, _i32, _i64, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "fg_workspace_bytes": (_sz, [_i32, _i64, _i64]),
+    "fg_set_tuning": (_i32, [C.c_char_p, _i64]),
     "fg_lookup_prune": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _p, _i64, _i32, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "fg_gather": (_i32, [_p, _i64, _i64, _i64, _p, _p, _p, _i64, _p, _i64, _i64, _i32, _p]),
     "fg_aggregate": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _i32, _p, _i64, _i32, _p]),
@@ -69,6 +71,10 @@ def fg_version():
 
 def fg_last_error():
     return _lib.fg_last_error().decode()
+
+
+def fg_set_tuning(key, value):
+    _check(_lib.fg_set_tuning(key.encode(), value))
 
 
 def fg_workspace_bytes(kind, n):
@@ -113,9 +119,9 @@ def fg_lookup_prune(cache, layer, it, ids, n, live, row_start, row_end, col, nnz
 
 
 def fg_gather(table, table_rows, src_stride, row_bytes, src_index, dst_pos, count, max_count, dst, dst_rows, dst_stride,
-              table_on_host=0, stream=None):
+              table_kind=0, stream=None):
     _check(_lib.fg_gather(ptr(table), table_rows, src_stride, row_bytes, ptr(src_index), ptr(dst_pos), ptr(count), max_count,
-                          ptr(dst), dst_rows, dst_stride, table_on_host, stream))
+                          ptr(dst), dst_rows, dst_stride, table_kind, stream))
 
 
 def fg_aggregate(row_start, row_end, col, nnz, n_block_rows, rows, n_rows, max_rows, h_src, n_src, src_stride, dim, in_dtype,

@@ -197,7 +197,8 @@ extern "C" fg_status_t fg_aggregate(const int32_t* row_start_dev, const int32_t*
     while ((1 << lg) < pieces && lg < 6) ++lg;
     const int gpb = AGG_THREADS >> lg;
     int64_t blocks = fg_ceil_div(max_rows, gpb);
-    if (blocks > 256 * 16) blocks = 256 * 16;
+    const int64_t cap = 256 * fg_tuning(FG_TUNE_AGG_WG_PER_CU);
+    if (blocks > cap) blocks = cap;
     const size_t lds = (size_t)gpb * AGG_MAX_STAGE * sizeof(int32_t);
     hipStream_t st = (hipStream_t)stream;
 #define FG_AGG_LAUNCH(IN, OUT)                                                                                        \

@@ -1,6 +1,7 @@
 // Error reporting, version and workspace sizing of the C ABI.
 #include <stdarg.h>
 #include <stdio.h>
+#include <string.h>
 
 #include "common.h"
 
@@ -18,6 +19,25 @@ void fg_clear_error() { g_err[0] = 0; }
 size_t fg_ws_lookup_prune_bytes(int64_t n);
 size_t fg_ws_cache_update_bytes(int64_t n);
 size_t fg_ws_export_bytes(int64_t capacity);
+
+static int64_t g_tune[FG_TUNE_COUNT] = {16, 4, 1, 1, 16};
+static const char* const g_tune_names[FG_TUNE_COUNT] = {"gather_wg_per_cu", "gather_host_wg_per_cu", "gather_unroll",
+                                                        "gather_nontemporal", "aggregate_wg_per_cu"};
+
+int64_t fg_tuning(fg_tune_id id) { return g_tune[id]; }
+
+extern "C" fg_status_t fg_set_tuning(const char* key, int64_t value) {
+    if (!key) FG_FAIL(FG_ERR_INVALID_ARG, "fg_set_tuning: key is NULL");
+    if (value < 0 || value > 4096) FG_FAIL(FG_ERR_INVALID_ARG, "fg_set_tuning: value %lld out of range", (long long)value);
+    for (int i = 0; i < FG_TUNE_COUNT; ++i) {
+        if (strcmp(key, g_tune_names[i]) == 0) {
+            if (value == 0 && i != FG_TUNE_GATHER_NONTEMPORAL) FG_FAIL(FG_ERR_INVALID_ARG, "fg_set_tuning: %s must be positive", key);
+            g_tune[i] = value;
+            return FG_OK;
+        }
+    }
+    FG_FAIL(FG_ERR_INVALID_ARG, "fg_set_tuning: unknown key '%s'", key);
+}
 
 extern "C" const char* fg_last_error(void) { return g_err; }
 

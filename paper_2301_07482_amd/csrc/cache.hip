@@ -79,6 +79,36 @@ __device__ __forceinline__ void select_bin(const unsigned int* hist, long long* 
     __syncthreads();
 }
 
+// Calls f(key) for every live element, reading the norms 4 at a time (8 loads in flight per thread) when the
+// arrays are suitably aligned; element order is irrelevant to the callers (they only count).
+template <typename F>
+__device__ __forceinline__ void for_each_live_key(const uint8_t* __restrict__ live, const float* __restrict__ gnorm, int n, F f) {
+    const int t = threadIdx.x;
+    const bool vec = (((uintptr_t)gnorm & 15) == 0) && (!live || ((uintptr_t)live & 3) == 0);
+    int done = 0;
+    if (vec) {
+        typedef float f4 __attribute__((ext_vector_type(4)));
+        const int n4 = n >> 2;
+        for (int q0 = t; q0 < n4; q0 += 2 * SEL_THREADS) {
+            const int q1 = q0 + SEL_THREADS;
+            const bool has1 = q1 < n4;
+            const f4 g0 = ((const f4*)gnorm)[q0];
+            const f4 g1 = has1 ? ((const f4*)gnorm)[q1] : g0;
+            const uint32_t l0 = live ? ((const uint32_t*)live)[q0] : 0x01010101u;
+            const uint32_t l1 = live ? (has1 ? ((const uint32_t*)live)[q1] : 0u) : (has1 ? 0x01010101u : 0u);
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if ((l0 >> (8 * e)) & 0xFFu) f(order_key(g0[e]));
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                if ((l1 >> (8 * e)) & 0xFFu) f(order_key(g1[e]));
+        }
+        done = n4 << 2;
+    }
+    for (int j = done + t; j < n; j += SEL_THREADS)
+        if (live ? live[j] != 0 : true) f(order_key(gnorm[j]));
+}
+
 __global__ __launch_bounds__(SEL_THREADS) void select_tau_kernel(const uint8_t* __restrict__ live,
                                                                  const float* __restrict__ gnorm, int n, float p_grad,
                                                                  UpdHeader* __restrict__ hdr, int64_t* __restrict__ stats) {
@@ -93,8 +123,7 @@ __global__ __launch_bounds__(SEL_THREADS) void select_tau_kernel(const uint8_t* 
     for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
     if (t == 0) s_parked = 0;
     __syncthreads();
-    for (int j = t; j < n; j += SEL_THREADS)
-        if (live ? live[j] != 0 : true) atomicAdd(&hist[order_key(gnorm[j]) >> 21], 1u);
+    for_each_live_key(live, gnorm, n, [&](uint32_t kj) { atomicAdd(&hist[kj >> 21], 1u); });
     __syncthreads();
     long long c = 0;
 #pragma unroll
@@ -121,14 +150,12 @@ __global__ __launch_bounds__(SEL_THREADS) void select_tau_kernel(const uint8_t* 
     __syncthreads();
     for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
     __syncthreads();
-    for (int j = t; j < n; j += SEL_THREADS) {
-        if (live && !live[j]) continue;
-        const uint32_t kj = order_key(gnorm[j]);
-        if ((kj >> 21) != d0) continue;
+    for_each_live_key(live, gnorm, n, [&](uint32_t kj) {
+        if ((kj >> 21) != d0) return;
         atomicAdd(&hist[(kj >> 10) & 2047u], 1u);
         const unsigned int at = atomicAdd(&s_parked, 1u);
         if (at < SEL_PARK) park[at] = kj;
-    }
+    });
     __syncthreads();
     select_bin(hist, red, &s_bin, &s_rank);
     const uint32_t d1 = s_bin;
@@ -142,11 +169,9 @@ __global__ __launch_bounds__(SEL_THREADS) void select_tau_kernel(const uint8_t* 
         for (unsigned int i = t; i < parked; i += SEL_THREADS)
             if ((park[i] & 0xFFFFFC00u) == hi) atomicAdd(&hist[park[i] & 1023u], 1u);
     } else {
-        for (int j = t; j < n; j += SEL_THREADS) {
-            if (live && !live[j]) continue;
-            const uint32_t kj = order_key(gnorm[j]);
+        for_each_live_key(live, gnorm, n, [&](uint32_t kj) {
             if ((kj & 0xFFFFFC00u) == hi) atomicAdd(&hist[kj & 1023u], 1u);
-        }
+        });
     }
     __syncthreads();
     select_bin(hist, red, &s_bin, &s_rank);
@@ -479,7 +504,7 @@ extern "C" fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t
                        aslot, stats_dev);
     FG_LAUNCH_CHECK("assign_slots_kernel");
     rc = fg_launch_gather(h_dev, n, h_stride, row_bytes, apos, aslot, &hdr->n_admit, n < l->capacity ? n : l->capacity,
-                          l->table, l->capacity, row_bytes, 0, st);
+                          l->table, l->capacity, row_bytes, FG_TABLE_HBM_REUSED, st);
     if (rc != FG_OK) return rc;
     l->head_cur ^= 1;  // the advanced header written by assign_slots is the current one from here on
     return FG_OK;

@@ -54,6 +54,17 @@ constexpr int FG_SCAN_BLOCK = 1024;  // elements (= threads) per block in the co
 static inline int64_t fg_ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline size_t fg_align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
+// launch-shape parameters (defaults tuned on MI355X; fg_set_tuning overrides them for measurements)
+enum fg_tune_id {
+    FG_TUNE_GATHER_WG_PER_CU = 0,
+    FG_TUNE_GATHER_HOST_WG_PER_CU,
+    FG_TUNE_GATHER_UNROLL,
+    FG_TUNE_GATHER_NONTEMPORAL,
+    FG_TUNE_AGG_WG_PER_CU,
+    FG_TUNE_COUNT
+};
+int64_t fg_tuning(fg_tune_id id);
+
 // internal row copy used by fg_gather and by the cache update
 fg_status_t fg_launch_gather(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
                              const int32_t* src_index, const int32_t* dst_pos, const int64_t* count_dev,

@@ -11,12 +11,15 @@
 
 namespace {
 
-template <typename V>
-__device__ __forceinline__ V load_stream(const V* p) {
-    return __builtin_nontemporal_load(p);
+template <typename V, bool NT>
+__device__ __forceinline__ V load_row_piece(const V* p) {
+    if constexpr (NT)
+        return __builtin_nontemporal_load(p);  // table rows are read once: do not displace what the next stages reuse
+    else
+        return *p;
 }
 
-template <typename V, int UNROLL>
+template <typename V, int UNROLL, bool NT>
 __global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict__ table, int64_t table_rows,
                                                           int64_t src_stride, int chunks,
                                                           const int32_t* __restrict__ src_index,
@@ -52,7 +55,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict
             V v[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u)
-                if (src[u] && lane < chunks) v[u] = load_stream(src[u] + lane);
+                if (src[u] && lane < chunks) v[u] = load_row_piece<V, NT>(src[u] + lane);
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u)
                 if (src[u] && lane < chunks) out[u][lane] = v[u];
@@ -61,7 +64,7 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict
                 V v[UNROLL];
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u)
-                    if (src[u]) v[u] = load_stream(src[u] + c);
+                    if (src[u]) v[u] = load_row_piece<V, NT>(src[u] + c);
 #pragma unroll
                 for (int u = 0; u < UNROLL; ++u)
                     if (src[u]) out[u][c] = v[u];
@@ -79,23 +82,41 @@ __global__ void fill_kernel(T* p, int64_t n, T value) {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-template <typename V>
-void launch_gather_t(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
+template <typename V, int UNROLL, bool NT>
+void launch_gather_u(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
                      const int32_t* src_index, const int32_t* dst_pos, const int64_t* count_dev, int64_t max_count,
                      void* dst, int64_t dst_rows, int64_t dst_stride, int on_host, hipStream_t st) {
     const int chunks = (int)(row_bytes / (int64_t)sizeof(V));
     int lg = 0;
     while ((1 << lg) < chunks && lg < 6) ++lg;
     const int lanes = 1 << lg;
-    constexpr int UNROLL = 4;
     const int groups_per_block = 256 / lanes;
     int64_t blocks = fg_ceil_div(max_count, (int64_t)groups_per_block * UNROLL);
-    const int64_t cap = on_host ? 256 * 4 : 256 * 8;  // a few workgroups per compute unit; the grid loops
+    // a few workgroups per compute unit; the grid loops over the list
+    const int64_t cap = 256 * fg_tuning(on_host == 1 ? FG_TUNE_GATHER_HOST_WG_PER_CU : FG_TUNE_GATHER_WG_PER_CU);
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL((gather_rows_kernel<V, UNROLL>), dim3((unsigned)blocks), dim3(256), 0, st, (const char*)table,
+    hipLaunchKernelGGL((gather_rows_kernel<V, UNROLL, NT>), dim3((unsigned)blocks), dim3(256), 0, st, (const char*)table,
                        table_rows, src_stride, chunks, src_index, dst_pos, count_dev, max_count, (char*)dst, dst_rows,
                        dst_stride, lg);
+}
+
+template <typename V>
+void launch_gather_t(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
+                     const int32_t* src_index, const int32_t* dst_pos, const int64_t* count_dev, int64_t max_count,
+                     void* dst, int64_t dst_rows, int64_t dst_stride, int on_host, hipStream_t st) {
+    const int unroll = (int)fg_tuning(FG_TUNE_GATHER_UNROLL);
+    // rows of a big table are read once (streaming loads); rows that were just written or will be read again
+    // (cached embeddings, layer outputs) go through the caches normally
+    const bool nt = on_host != 2 && fg_tuning(FG_TUNE_GATHER_NONTEMPORAL) != 0;
+#define FG_G(U, N)                                                                                                      \
+    launch_gather_u<V, U, N>(table, table_rows, src_stride, row_bytes, src_index, dst_pos, count_dev, max_count, dst, \
+                             dst_rows, dst_stride, on_host, st)
+    if (unroll <= 1) { if (nt) FG_G(1, true); else FG_G(1, false); }
+    else if (unroll == 2) { if (nt) FG_G(2, true); else FG_G(2, false); }
+    else if (unroll <= 4) { if (nt) FG_G(4, true); else FG_G(4, false); }
+    else { if (nt) FG_G(8, true); else FG_G(8, false); }
+#undef FG_G
 }
 
 }  // namespace
@@ -148,7 +169,7 @@ fg_status_t fg_launch_gather(const void* table, int64_t table_rows, int64_t src_
 extern "C" fg_status_t fg_gather(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
                                  const int32_t* src_index_dev, const int32_t* dst_pos_dev, const int64_t* count_dev,
                                  int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride,
-                                 int32_t table_on_host, void* stream) {
+                                 int32_t table_kind, void* stream) {
     if (max_count < 0 || table_rows < 0 || dst_rows < 0 || row_bytes < 0)
         FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather: negative size (max_count %lld, table_rows %lld, dst_rows %lld, row_bytes %lld)",
                 (long long)max_count, (long long)table_rows, (long long)dst_rows, (long long)row_bytes);
@@ -164,7 +185,8 @@ extern "C" fg_status_t fg_gather(const void* table, int64_t table_rows, int64_t 
     if (bits & (uintptr_t)(need - 1))
         FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather: pointers and strides must be %lld-byte aligned for rows of %lld bytes",
                 (long long)need, (long long)row_bytes);
+    if (table_kind < 0 || table_kind > 2) FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather: table_kind = %d is not FG_TABLE_*", table_kind);
     fg_clear_error();
     return fg_launch_gather(table, table_rows, src_stride, row_bytes, src_index_dev, dst_pos_dev, count_dev, max_count,
-                            dst, dst_rows, dst_stride, table_on_host, (hipStream_t)stream);
+                            dst, dst_rows, dst_stride, table_kind, (hipStream_t)stream);
 }

@@ -1,18 +1,20 @@
 // fg_linear: h_out[r,:] = act([h_src[r,:] ‖ agg[k,:]] . W + bias) for r = rows[k]: the dense update phi of
 // Eq. 1 for GraphSAGE-mean, the only dense contraction on the path, on the matrix cores.
 //
-// fp32 path: v_mfma_f32_32x32x2_f32. A workgroup of eight wavefronts owns a 128 x 128 output tile, each
-// wavefront a 32 x 64 piece (two 32x32 MFMA blocks). The A operand is never materialised: its first d_in
-// columns are read from h_src at the listed positions and the last d_in from the compact agg array, 16 bytes
-// at a time, through LDS. K is walked in steps of 32; inside a step the two half-wavefronts of an MFMA take
-// k = s and k = 16 + s (s = 0..15), which lets every lane fetch its 16 A values as four 16-byte LDS reads
-// (the sum over k does not care about the order). Global loads of the next step are issued before the MFMAs
-// of the current one.
+// fp32 path: v_mfma_f32_32x32x2_f32. A workgroup of four wavefronts owns a (32*WM) x 64 output tile: WM = 4
+// stacks the wavefronts along M (each 32 x 64, two MFMA blocks), WM = 2 arranges them 2 x 2 (each 32 x 32) for
+// layers with few rows. Register use is kept low enough for three workgroups per compute unit, so that one
+// workgroup's matrix instructions overlap another's loads. The A operand is never materialised: its first
+// d_in columns are read from h_src at the listed positions and the last d_in from the compact agg array,
+// 16 bytes at a time, through LDS. K is walked in steps of 32; inside a step the two half-wavefronts of an
+// MFMA take k = s and k = 16 + s (s = 0..15), which lets every lane fetch its 16 A values as four 16-byte
+// LDS reads (the sum over k does not care about the order). Global loads of the next step are issued
+// before the MFMAs of the current one.
 //
 // Accuracy: a single fp32 accumulator over K = 512 products drifts by a few 1e-6 of the row scale, which is
 // the whole error budget of the path (1e-5). Each 32-wide K step therefore starts from a zero fp32
 // accumulator (small partial sums, small rounding steps) and is folded into an fp64 running sum on the
-// vector ALU, two instructions per output element and step next to 32 matrix instructions; bias, ReLU and
+// vector ALU, two instructions per output element and step next to 16 matrix instructions; bias, ReLU and
 // the single rounding to fp32 happen from the fp64 sum.
 #include "common.h"
 
@@ -21,25 +23,36 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BM = 128, BN = 128, BK = 32;
+constexpr int BN = 64, BK = 32;
 constexpr int LDA = BK + 4;  // floats; keeps 16-byte alignment and spreads rows over banks
 constexpr int LDB = BN + 4;
-constexpr int LIN_THREADS = 512;
+constexpr int LIN_THREADS = 256;
 
-__global__ __launch_bounds__(LIN_THREADS) void linear_f32_kernel(
+template <int WM>
+__global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
-    int64_t out_stride) {
+    int64_t out_stride, int n_tiles) {
+    constexpr int BM = 32 * WM;
+    constexpr int WN = 4 / WM;          // wavefronts along N
+    constexpr int NB = BN / (32 * WN);  // 32-wide MFMA blocks per wavefront
+    constexpr int A_LOADS = BM * BK / 4 / LIN_THREADS;
+    constexpr int B_LOADS = BK * BN / 4 / LIN_THREADS;
     __shared__ __attribute__((aligned(16))) float As[BM * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
     __shared__ int32_t row_of[BM];
 
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
     if (n_rows > max_rows) n_rows = max_rows;
-    const int64_t m0 = (int64_t)blockIdx.x * BM;
+    // Workgroup ids are dealt round-robin to the 8 XCDs, each with its own L2. The column tiles of one row
+    // tile read the same A rows, so they are given consecutive slots of ONE XCD: id -> (xcd, j), row tile
+    // (j / n_tiles) * 8 + xcd, column tile j % n_tiles. A then comes from HBM once instead of once per column tile.
+    const int xcd = blockIdx.x & 7;
+    const int j = blockIdx.x >> 3;
+    const int64_t m0 = ((int64_t)(j / n_tiles) * 8 + xcd) * BM;
     if (m0 >= n_rows) return;
-    const int n0 = blockIdx.y * BN;
+    const int n0 = (j % n_tiles) * BN;
     const int t = threadIdx.x;
     const int K = 2 * d_in;
 
@@ -54,33 +67,33 @@ __global__ __launch_bounds__(LIN_THREADS) void linear_f32_kernel(
     }
     __syncthreads();
 
-    // this thread's share of the global -> LDS traffic: two 16-byte pieces of A and two of W per step
+    // this thread's share of the global -> LDS traffic per step
     const int a_kc = t & 7;   // which 16-byte piece of the 32-wide k step
-    const int a_m = t >> 3;   // rows a_m and a_m + 64
-    const int b_nc = t & 31;  // which 16-byte piece of the 128-wide n tile
-    const int b_k = t >> 5;   // k rows b_k and b_k + 16
-    const float* a_self[2];
-    const float* a_agg[2];
+    const int a_m = t >> 3;   // rows a_m + 32 i
+    const int b_nc = t & 15;  // which 16-byte piece of the 64-wide n tile
+    const int b_k = t >> 4;   // k rows b_k + 16 i
+    const float* a_self[A_LOADS];
+    const float* a_agg[A_LOADS];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int m = a_m + 64 * i;
+    for (int i = 0; i < A_LOADS; ++i) {
+        const int m = a_m + 32 * i;
         const int32_t r = row_of[m];
         a_self[i] = r >= 0 ? (const float*)(h_src + (int64_t)r * src_stride) : nullptr;
         a_agg[i] = r >= 0 ? (const float*)(agg + (m0 + m) * agg_stride) : nullptr;
     }
     const bool b_col_ok = (n0 + 4 * b_nc) < d_out;
 
-    f32x4 ra[2], rb[2];
+    f32x4 ra[A_LOADS], rb[B_LOADS];
     auto load_step = [&](int k0) {
         const int ka = k0 + 4 * a_kc;
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < A_LOADS; ++i) {
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
             if (a_self[i] && ka < K) v = ka < d_in ? *(const f32x4*)(a_self[i] + ka) : *(const f32x4*)(a_agg[i] + (ka - d_in));
             ra[i] = v;
         }
 #pragma unroll
-        for (int i = 0; i < 2; ++i) {
+        for (int i = 0; i < B_LOADS; ++i) {
             const int kb = k0 + b_k + 16 * i;
             f32x4 v = {0.f, 0.f, 0.f, 0.f};
             if (b_col_ok && kb < K) v = *(const f32x4*)(W + (int64_t)kb * d_out + n0 + 4 * b_nc);
@@ -89,18 +102,18 @@ __global__ __launch_bounds__(LIN_THREADS) void linear_f32_kernel(
     };
     auto store_step = [&]() {
 #pragma unroll
-        for (int i = 0; i < 2; ++i) *(f32x4*)(As + (a_m + 64 * i) * LDA + 4 * a_kc) = ra[i];
+        for (int i = 0; i < A_LOADS; ++i) *(f32x4*)(As + (a_m + 32 * i) * LDA + 4 * a_kc) = ra[i];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) *(f32x4*)(Bs + (b_k + 16 * i) * LDB + 4 * b_nc) = rb[i];
+        for (int i = 0; i < B_LOADS; ++i) *(f32x4*)(Bs + (b_k + 16 * i) * LDB + 4 * b_nc) = rb[i];
     };
 
     const int lane = t & 63, wave = t >> 6;
-    const int wm = (wave >> 1) * 32, wn = (wave & 1) * 64;
+    const int wm = (wave / WN) * 32, wn = (wave % WN) * 32 * NB;
     const int l32 = lane & 31, half = lane >> 5;
 
-    double sum[2][16];
+    double sum[NB][16];
 #pragma unroll
-    for (int b = 0; b < 2; ++b)
+    for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int i = 0; i < 16; ++i) sum[b][i] = 0.0;
 
@@ -113,28 +126,30 @@ __global__ __launch_bounds__(LIN_THREADS) void linear_f32_kernel(
         f32x4 av[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) av[q] = *(const f32x4*)(As + (wm + l32) * LDA + 16 * half + 4 * q);
-        f32x16 acc0, acc1;
+        f32x16 acc[NB];
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc0[i] = acc1[i] = 0.f;
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
-            const float b0 = Bs[(16 * half + s) * LDB + wn + l32];
-            const float b1 = Bs[(16 * half + s) * LDB + wn + 32 + l32];
             const float a = av[s >> 2][s & 3];
-            acc0 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b0, acc0, 0, 0, 0);
-            acc1 = __builtin_amdgcn_mfma_f32_32x32x2f32(a, b1, acc1, 0, 0, 0);
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const float bv = Bs[(16 * half + s) * LDB + wn + 32 * b + l32];
+                acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc[b], 0, 0, 0);
+            }
         }
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            sum[0][i] += (double)acc0[i];
-            sum[1][i] += (double)acc1[i];
-        }
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum[b][i] += (double)acc[b][i];
         __syncthreads();
     }
 
     // epilogue: accumulator element i of a 32x32 block is row 8*(i/4) + 4*half + i%4, column l32
 #pragma unroll
-    for (int nb = 0; nb < 2; ++nb) {
+    for (int nb = 0; nb < NB; ++nb) {
         const int c = n0 + wn + nb * 32 + l32;
         if (c >= d_out) continue;
         const double bv = bias ? (double)bias[c] : 0.0;
@@ -182,10 +197,19 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
             FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: h_out, its stride and bias must be 4-byte aligned");
         fg_clear_error();
         if (max_rows == 0) return FG_OK;
-        dim3 grid((unsigned)fg_ceil_div(max_rows, BM), (unsigned)fg_ceil_div(d_out, BN));
-        hipLaunchKernelGGL(linear_f32_kernel, grid, dim3(LIN_THREADS), 0, st, (const char*)h_src, n_src, src_stride,
-                           (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, (const float*)W,
-                           bias, relu, (char*)h_out, n_out, out_stride);
+        const int ny = (int)fg_ceil_div(d_out, BN);
+        // few rows: 64-row tiles give twice the workgroups to spread over the compute units
+        const bool big = fg_ceil_div(max_rows, 128) * ny >= 512;
+        const int64_t m_tiles = fg_ceil_div(max_rows, big ? 128 : 64);
+        const unsigned grid = (unsigned)(fg_ceil_div(m_tiles, 8) * 8 * ny);
+        if (big)
+            hipLaunchKernelGGL(linear_f32_kernel<4>, dim3(grid), dim3(LIN_THREADS), 0, st, (const char*)h_src, n_src, src_stride,
+                               (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, (const float*)W,
+                               bias, relu, (char*)h_out, n_out, out_stride, ny);
+        else
+            hipLaunchKernelGGL(linear_f32_kernel<2>, dim3(grid), dim3(LIN_THREADS), 0, st, (const char*)h_src, n_src, src_stride,
+                               (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, (const float*)W,
+                               bias, relu, (char*)h_out, n_out, out_stride, ny);
         FG_LAUNCH_CHECK("linear_f32_kernel");
         return FG_OK;
     }

@@ -140,7 +140,7 @@ class HotPath:
             if self.use_cache and self.cache is not None and 1 <= l <= L - 1:
                 tick(f"cache_fetch[{l}]")
                 B.fg_gather(B.fg_cache_table(self.cache, l), self.capacity[l - 1], out_b, out_b, self.hit_slot[l],
-                            self.hit_pos[l], self._cnt(l, 1), bt.n[l], self.H[l], bt.n[l], out_b, 0, st)
+                            self.hit_pos[l], self._cnt(l, 1), bt.n[l], self.H[l], bt.n[l], out_b, B.FG_TABLE_HBM_REUSED, st)
             agg_b = self.dims[l - 1] * esz[self.agg_code]
             tick(f"aggregate[{l}]")
             B.fg_aggregate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),

@@ -1,0 +1,83 @@
+"""The C-ABI library: loads, exports everything the header declares, and rejects bad arguments on the host
+before anything is launched (so these run without a GPU)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "freshgnn.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2301_07482_amd import binding
+    return binding
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(fg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(B):
+    names = declared_functions()
+    assert {"fg_cache_create", "fg_lookup_prune", "fg_gather", "fg_aggregate", "fg_linear", "fg_cache_update"} <= set(names)
+    lib = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} declared in freshgnn.h but not exported"
+    assert set(B.SIGNATURES) == set(names), "binding and header list different calls"
+    assert B.fg_version() >= 100
+
+
+def test_argument_validation_needs_no_gpu(B):
+    def code(fn, *a, **k):
+        with pytest.raises(B.FgError) as e:
+            fn(*a, **k)
+        assert B.fg_last_error() != ""
+        return e.value.code
+
+    assert code(B.fg_gather, None, 10, 16, 16, None, None, None, 4, None, 4, 16) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_gather, 4096, 10, 16, 15, 4096, None, None, 4, 4096, 4, 16) == B.FG_ERR_SHAPE          # odd row
+    assert code(B.fg_gather, 4096, 10, 8, 16, 4096, None, None, 4, 4096, 4, 16) == B.FG_ERR_SHAPE           # stride < row
+    assert code(B.fg_gather, 4100, 10, 16, 16, 4096, None, None, 4, 4096, 4, 16) == B.FG_ERR_INVALID_ARG    # alignment
+    assert code(B.fg_gather, 4096, 10, 16, 16, 4096, None, None, -1, 4096, 4, 16) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_gather, 4096, 10, 16, 16, 4096, None, None, 4, 4096, 4, 16, 7) == B.FG_ERR_INVALID_ARG  # table kind
+    assert code(B.fg_lookup_prune, None, 0, 0, None, 5, None, None, None, None, 0, 0, None, None, None, None, None, None,
+                None, None, 0) == B.FG_ERR_INVALID_ARG                                                      # no counts
+    assert code(B.fg_lookup_prune, None, 0, 0, 4096, 5, None, 4096, None, None, 0, 9, None, None, None, None, 4096, None,
+                4096, None, 0) == B.FG_ERR_INVALID_ARG                                                      # half a block
+    assert code(B.fg_lookup_prune, None, 0, 0, 4096, 5, None, 4096, 4096, 4096, 3, 2, 4096, None, None, None, 4096, None,
+                4096, 4096, 1 << 20) == B.FG_ERR_SHAPE                                                      # n_src < n
+    assert code(B.fg_lookup_prune, None, 0, 0, 4096, 5, None, None, None, None, 0, 0, None, None, None, None, 4096, None,
+                4096, 4096, 8) == B.FG_ERR_SHAPE                                                            # workspace
+    assert code(B.fg_aggregate, 4096, 4096, 4096, 5, 5, None, None, 5, 4096, 9, 512, 130, B.FG_F32, 4096, 520, B.FG_F32) \
+        == B.FG_ERR_SHAPE                                                                                   # dim % 4
+    assert code(B.fg_aggregate, 4096, 4096, 4096, 5, 5, None, None, 5, 4096, 9, 256, 128, B.FG_F32, 4096, 512, B.FG_F32) \
+        == B.FG_ERR_SHAPE                                                                                   # stride
+    assert code(B.fg_aggregate, 4096, 4096, 4096, 5, 5, None, None, 5, 4096, 9, 512, 128, 9, 4096, 512, B.FG_F32) \
+        == B.FG_ERR_DTYPE
+    assert code(B.fg_linear, 4096, 9, 512, B.FG_F32, 4096, 512, None, None, 5, 126, 64, 4096, B.FG_F32, None, 1, 4096, 9, 256,
+                B.FG_F32) == B.FG_ERR_SHAPE
+    assert code(B.fg_linear, 4096, 9, 512, B.FG_F16, 4096, 512, None, None, 5, 128, 64, 4096, B.FG_F32, None, 1, 4096, 9, 256,
+                B.FG_F32) == B.FG_ERR_DTYPE
+    assert code(B.fg_linear, None, 9, 512, B.FG_F32, 4096, 512, None, None, 5, 128, 64, 4096, B.FG_F32, None, 1, 4096, 9, 256,
+                B.FG_F32) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_cache_update, None, 1, 0, None, 0, None, None, None, 0.5, None, 0, None, None, 0) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_cache_create, 0, [4], [4], B.FG_F32, 3) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_cache_create, 100, [0], [4], B.FG_F32, 3) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_cache_create, 100, [4], [3], B.FG_F32, 3) == B.FG_ERR_SHAPE
+    assert code(B.fg_cache_create, 100, [4], [4], 5, 3) == B.FG_ERR_DTYPE
+    assert code(B.fg_cache_create, 100, [4], [4], B.FG_F32, -1) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_set_tuning, "gather_unroll", -3) == B.FG_ERR_INVALID_ARG
+    assert B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, 1000) >= 1000 * 5
+    assert B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, 1000) >= 1000 * 9
+    assert B.fg_workspace_bytes(7, 1000) == 0
+
+
+def test_zero_sized_calls_are_noops_without_gpu(B):
+    B.fg_gather(None, 0, 16, 16, None, None, None, 0, None, 0, 16)
+    B.fg_aggregate(None, None, None, 0, 0, None, None, 0, None, 0, 16, 4, B.FG_F32, None, 16, B.FG_F32)
+    B.fg_cache_destroy(None)
