@@ -1,8 +1,220 @@
-// bf16 variant of the dense layer update (bf16 MFMA, fp32 accumulate).
+// bf16 variant of the dense layer update (phi of Eq. 1): bf16 operands on v_mfma_f32_32x32x16_bf16, fp32
+// accumulation, bias and ReLU in fp32, output rounded once to bf16 (hidden layers) or kept in fp32 (last layer).
+// Used by the workload whose raw features are fp16 and whose embeddings, weights and cache rows are bf16.
+//
+// A workgroup of four wavefronts owns a 128 x 128 output tile, each wavefront a 64 x 64 quadrant (2 x 2 MFMA
+// blocks). K is walked in steps of 32 = two 16-deep MFMA sub-steps. Both operands sit in LDS with k contiguous
+// (rows of 40 halfwords: 16-byte aligned, conflict-free for the 16-byte operand reads): a lane's MFMA operand
+// is one 16-byte LDS read. A is gathered on the fly (own rows from h_src at the listed positions, converted
+// from fp16 to bf16 if needed; mean rows from the compact agg array). W is row-major [K x N] in memory, so each
+// thread reads two adjacent k rows x 8 columns and writes the eight (k, k+1) pairs transposed as 32-bit words.
+#include <hip/hip_fp16.h>
+
 #include "common.h"
 
-fg_status_t fg_launch_linear_bf16(const void*, int32_t, int64_t, fg_dtype_t, const void*, int64_t, const int32_t*,
-                                  const int64_t*, int64_t, int32_t, int32_t, const void*, const float*, int32_t, void*,
-                                  int32_t, int64_t, fg_dtype_t, hipStream_t) {
-    FG_FAIL(FG_ERR_DTYPE, "fg_linear: the bf16 path is not built yet");
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int HB_M = 128, HB_N = 128, HB_K = 32;
+constexpr int LDH = HB_K + 8;  // halfwords per LDS row
+constexpr int HB_THREADS = 256;
+
+__device__ __forceinline__ unsigned int f32_to_bf16_bits(float f) {
+    const unsigned int b = __float_as_uint(f);
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+
+__device__ __forceinline__ float f16_bits_to_f32(unsigned int h) {
+    return __half2float(__ushort_as_half((unsigned short)h));
+}
+
+// eight fp16 values (packed in 4 words) -> eight bf16 values, each rounded to nearest even
+__device__ __forceinline__ u32x4 f16x8_to_bf16x8(u32x4 v) {
+    u32x4 o;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const unsigned int w = v[i];
+        o[i] = f32_to_bf16_bits(f16_bits_to_f32(w & 0xFFFFu)) | (f32_to_bf16_bits(f16_bits_to_f32(w >> 16)) << 16);
+    }
+    return o;
+}
+
+template <bool SRC_F16, bool OUT_BF16>
+__global__ __launch_bounds__(HB_THREADS, 2) void linear_bf16_kernel(
+    const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
+    const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
+    const unsigned short* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
+    int64_t out_stride, int n_tiles) {
+    __shared__ __attribute__((aligned(16))) unsigned short As[HB_M * LDH];
+    __shared__ __attribute__((aligned(16))) unsigned short Bt[HB_N * LDH];
+    __shared__ int32_t row_of[HB_M];
+
+    int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
+    if (n_rows > max_rows) n_rows = max_rows;
+    // column tiles of one row tile share an XCD (and its L2), as in the fp32 kernel
+    const int xcd = blockIdx.x & 7;
+    const int j = blockIdx.x >> 3;
+    const int64_t m0 = ((int64_t)(j / n_tiles) * 8 + xcd) * HB_M;
+    if (m0 >= n_rows) return;
+    const int n0 = (j % n_tiles) * HB_N;
+    const int t = threadIdx.x;
+    const int K = 2 * d_in;
+
+    if (t < HB_M) {
+        const int64_t g = m0 + t;
+        int32_t r = -1;
+        if (g < n_rows) {
+            r = rows ? rows[g] : (int32_t)g;
+            if (r < 0 || r >= n_src || r >= n_out) r = -1;
+        }
+        row_of[t] = r;
+    }
+    __syncthreads();
+
+    const int a_kc = t & 3;   // which 8-element piece of the 32-deep k step
+    const int a_m = t >> 2;   // rows a_m and a_m + 64
+    const int b_kp = t & 15;  // k pair (2 b_kp, 2 b_kp + 1)
+    const int b_nc = t >> 4;  // columns 8 b_nc .. 8 b_nc + 7
+    const char* a_self[2];
+    const char* a_agg[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int m = a_m + 64 * i;
+        const int32_t r = row_of[m];
+        a_self[i] = r >= 0 ? h_src + (int64_t)r * src_stride : nullptr;
+        a_agg[i] = r >= 0 ? agg + (m0 + m) * agg_stride : nullptr;
+    }
+    const bool b_col_ok = (n0 + 8 * b_nc) < d_out;
+
+    u32x4 ra[2], rb[2];
+    auto load_step = [&](int k0) {
+        const int ka = k0 + 8 * a_kc;
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (a_self[i] && ka < K) {
+                if (ka < d_in) {
+                    v = *(const u32x4*)(a_self[i] + (int64_t)ka * 2);
+                    if (SRC_F16) v = f16x8_to_bf16x8(v);
+                } else {
+                    v = *(const u32x4*)(a_agg[i] + (int64_t)(ka - d_in) * 2);
+                }
+            }
+            ra[i] = v;
+        }
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+            const int kb = k0 + 2 * b_kp + i;
+            u32x4 v = {0u, 0u, 0u, 0u};
+            if (b_col_ok && kb < K) v = *(const u32x4*)(W + (int64_t)kb * d_out + n0 + 8 * b_nc);
+            rb[i] = v;
+        }
+    };
+    auto store_step = [&]() {
+#pragma unroll
+        for (int i = 0; i < 2; ++i) *(u32x4*)(As + (a_m + 64 * i) * LDH + 8 * a_kc) = ra[i];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            // word q of each row holds columns 2q (low half) and 2q + 1 (high half)
+            const unsigned int lo = rb[0][q], hi = rb[1][q];
+            *(unsigned int*)(Bt + (8 * b_nc + 2 * q) * LDH + 2 * b_kp) = (lo & 0xFFFFu) | (hi << 16);
+            *(unsigned int*)(Bt + (8 * b_nc + 2 * q + 1) * LDH + 2 * b_kp) = (lo >> 16) | (hi & 0xFFFF0000u);
+        }
+    };
+
+    const int lane = t & 63, wave = t >> 6;
+    const int wm = (wave >> 1) * 64, wn = (wave & 1) * 64;
+    const int l32 = lane & 31, half = lane >> 5;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+
+    const int nk = (K + HB_K - 1) / HB_K;
+    load_step(0);
+    for (int step = 0; step < nk; ++step) {
+        store_step();
+        __syncthreads();
+        if (step + 1 < nk) load_step((step + 1) * HB_K);
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk) {
+            bf16x8 av[2], bv[2];
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb) av[mb] = *(const bf16x8*)(As + (wm + mb * 32 + l32) * LDH + 16 * kk + 8 * half);
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) bv[nb] = *(const bf16x8*)(Bt + (wn + nb * 32 + l32) * LDH + 16 * kk + 8 * half);
+#pragma unroll
+            for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                for (int nb = 0; nb < 2; ++nb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[mb], bv[nb], acc[mb][nb], 0, 0, 0);
+        }
+        __syncthreads();
+    }
+
+    // accumulator element i of a 32x32 block is row 8*(i/4) + 4*half + i%4, column l32
+#pragma unroll
+    for (int nb = 0; nb < 2; ++nb) {
+        const int c = n0 + wn + nb * 32 + l32;
+        if (c >= d_out) continue;
+        const float bvv = bias ? bias[c] : 0.f;
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = wm + mb * 32 + 8 * (i >> 2) + 4 * half + (i & 3);
+                const int32_t r = row_of[m];
+                if (r < 0) continue;
+                float v = acc[mb][nb][i] + bvv;
+                if (relu) v = v > 0.f ? v : 0.f;
+                if (OUT_BF16)
+                    *(unsigned short*)(h_out + (int64_t)r * out_stride + (int64_t)c * 2) = (unsigned short)f32_to_bf16_bits(v);
+                else
+                    *(float*)(h_out + (int64_t)r * out_stride + (int64_t)c * 4) = v;
+            }
+        }
+    }
+}
+
+}  // namespace
+
+fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype,
+                                  const void* agg, int64_t agg_stride, const int32_t* rows_dev,
+                                  const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
+                                  const float* bias, int32_t relu, void* h_out, int32_t n_out, int64_t out_stride,
+                                  fg_dtype_t out_dtype, hipStream_t st) {
+    if (in_dtype != FG_F16 && in_dtype != FG_BF16) FG_FAIL(FG_ERR_DTYPE, "fg_linear: bf16 weights need fp16 or bf16 inputs");
+    if (out_dtype != FG_BF16 && out_dtype != FG_F32) FG_FAIL(FG_ERR_DTYPE, "fg_linear: bf16 weights give bf16 or fp32 outputs");
+    if (d_in % 8 || d_out % 8) FG_FAIL(FG_ERR_SHAPE, "fg_linear: d_in = %d and d_out = %d must be multiples of 8 for 16-bit types", d_in, d_out);
+    const int osz = out_dtype == FG_F32 ? 4 : 2;
+    if (src_stride < (int64_t)d_in * 2 || agg_stride < (int64_t)d_in * 2 || out_stride < (int64_t)d_out * osz)
+        FG_FAIL(FG_ERR_SHAPE, "fg_linear: a row stride is smaller than its row");
+    if (((uintptr_t)h_src | (uintptr_t)agg | (uintptr_t)W | (uintptr_t)src_stride | (uintptr_t)agg_stride) & 15)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: h_src, agg, W and the input strides must be 16-byte aligned");
+    if (((uintptr_t)h_out | (uintptr_t)out_stride) & (uintptr_t)(osz - 1) || ((uintptr_t)bias & 3))
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: h_out, its stride and bias must be aligned to their element size");
+    fg_clear_error();
+    if (max_rows == 0) return FG_OK;
+    const int ny = (int)fg_ceil_div(d_out, HB_N);
+    const int64_t m_tiles = fg_ceil_div(max_rows, HB_M);
+    const unsigned grid = (unsigned)(fg_ceil_div(m_tiles, 8) * 8 * ny);
+#define FG_LB(F16, OBF)                                                                                                  \
+    hipLaunchKernelGGL((linear_bf16_kernel<F16, OBF>), dim3(grid), dim3(HB_THREADS), 0, st, (const char*)h_src, n_src,    \
+                       src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out,              \
+                       (const unsigned short*)W, bias, relu, (char*)h_out, n_out, out_stride, ny)
+    if (in_dtype == FG_F16) {
+        if (out_dtype == FG_BF16) FG_LB(true, true); else FG_LB(true, false);
+    } else {
+        if (out_dtype == FG_BF16) FG_LB(false, true); else FG_LB(false, false);
+    }
+#undef FG_LB
+    FG_LAUNCH_CHECK("linear_bf16_kernel");
+    return FG_OK;
 }

@@ -425,3 +425,76 @@ def test_iterations_medium(env):
     hits, worst = run_workload_parity(torch, w, 8, check_numeric_every=4, sample_rows=20000)
     print(f"medium: {hits} hits, worst rel err {worst:.3e}")
     assert hits > 0
+
+
+def test_iterations_large_hbm_full_size(env):
+    """The benchmarked workload at its full size (111 M nodes, 57 GB table in HBM, 2 x 11.1 M cache slots), more
+    iterations than the staleness bound so that entries age out; index work compared in full every iteration,
+    gathered rows on a sample, numerics every 8th iteration."""
+    torch, B = env
+    w = wl.WORKLOADS["large_hbm"]
+    hits, worst = run_workload_parity(torch, w, 24, check_numeric_every=8, sample_rows=20000)
+    print(f"large_hbm: {hits} hits, worst rel err {worst:.3e}")
+    assert hits > 1000
+
+
+def test_iterations_large_host_resident(env):
+    """Same graph with the feature table in pinned host memory, gathered zero-copy over the host link."""
+    torch, B = env
+    w = wl.WORKLOADS["large_host"]
+    hits, worst = run_workload_parity(torch, w, 6, check_numeric_every=5, sample_rows=20000)
+    print(f"large_host: {hits} hits, worst rel err {worst:.3e}")
+    assert hits > 0
+
+
+# ------------------------------------------------------------------------------------------------ bf16 path
+
+@pytest.mark.parametrize("src,d_in,d_out,n_rows,max_rows,relu,out", [("f16", 768, 1024, 700, 900, True, "bf16"),
+                                                                     ("bf16", 1024, 1024, 300, 300, False, "f32"),
+                                                                     ("bf16", 64, 72, 129, 200, True, "bf16"),
+                                                                     ("f16", 8, 8, 5, 130, False, "f32")])
+def test_linear_bf16_matches_oracle(env, src, d_in, d_out, n_rows, max_rows, relu, out):
+    torch, B = env
+    r = np.random.default_rng(d_in + d_out)
+    n_src = max_rows + 300
+    code = {"f16": B.FG_F16, "bf16": B.FG_BF16, "f32": B.FG_F32}
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}
+    h = O.round_to(r.standard_normal((n_src, d_in)), src).astype(np.float32)
+    agg = O.round_bf16(r.standard_normal((max_rows, d_in)) * 0.3)
+    W = O.round_bf16(r.standard_normal((2 * d_in, d_out)) / np.sqrt(2 * d_in))
+    bias = (0.1 * r.standard_normal(d_out)).astype(np.float32)
+    rows = np.sort(r.permutation(n_src)[:max_rows]).astype(np.int32)
+    up = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(tdt[dt])
+    t_out = torch.full((n_src, d_out), -3.0, dtype=tdt[out], device="cuda")
+    t_cnt = torch.tensor([n_rows], dtype=torch.int64, device="cuda")
+    osz = 2 if out == "bf16" else 4
+    B.fg_linear(up(h, src), n_src, d_in * 2, code[src], up(agg, "bf16"), d_in * 2, dev(torch, rows), t_cnt, max_rows, d_in,
+                d_out, up(W, "bf16"), B.FG_BF16, dev(torch, bias), 1 if relu else 0, t_out, n_src, d_out * osz, code[out], None)
+    got = G.to_f32(t_out)
+    sel = rows[:n_rows]
+    want = O.round_to(O.linear(O.round_bf16(h[sel]), agg[:n_rows], W, bias, relu), out).astype(np.float32)
+    untouched = np.ones(n_src, bool)
+    untouched[sel] = False
+    assert np.all(got[untouched] == -3.0)
+    err = T.rel_err_rows(got[sel], want)
+    print(f"linear bf16 {src} {d_in}x{d_out}: rel err {err:.3e}")
+    assert err <= 2e-2
+    # identity panels: exact, and wrong for any operand-layout mistake
+    if d_in == d_out:
+        I, Z = np.eye(d_in, dtype=np.float32), np.zeros((d_in, d_in), np.float32)
+        for Wp, ref in [(np.vstack([I, Z]), O.round_bf16(h[sel])), (np.vstack([Z, I]), agg[:n_rows])]:
+            t2 = torch.zeros((n_src, d_out), dtype=torch.float32, device="cuda")
+            B.fg_linear(up(h, src), n_src, d_in * 2, code[src], up(agg, "bf16"), d_in * 2, dev(torch, rows), t_cnt, max_rows,
+                        d_in, d_out, up(Wp, "bf16"), B.FG_BF16, None, 0, t2, n_src, d_out * 4, B.FG_F32, None)
+            assert np.array_equal(t2.cpu().numpy()[sel], ref)
+
+
+def test_iterations_very_large_bf16(env):
+    """fp16 features in pinned host memory, bf16 embeddings/weights/cache, bf16 MFMA linear. The node count (and
+    with it edges, training subset and cache slots) is divided by 8 so that the table (47 GB instead of 375 GB)
+    fits the host memory a job may pin here (94 GB was refused); row width, fan-outs, batch and cache fraction
+    are those of the workload."""
+    torch, B = env
+    w = wl.WORKLOADS["very_large"].scaled(8)
+    hits, worst = run_workload_parity(torch, w, 8, check_numeric_every=3, sample_rows=20000)
+    print(f"{w.name}: {hits} hits, worst rel err {worst:.3e}")
