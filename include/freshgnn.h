@@ -97,7 +97,7 @@ fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, int64_t iter
 /*
  * Launch-shape overrides for measurements (defaults are tuned for MI355X and need no call). Keys:
  * "gather_wg_per_cu", "gather_host_wg_per_cu", "gather_unroll" (1, 2, 4, 8), "gather_nontemporal" (0/1),
- * "aggregate_wg_per_cu". Process-wide, not thread-safe against concurrent launches. Results never depend on them.
+ * "aggregate_wg_per_cu", "linear_tile" (rows per workgroup of the fp32 GEMM: 0 = default (64), 64, 128). Process-wide, not thread-safe against concurrent launches. Results never depend on them.
  */
 fg_status_t fg_set_tuning(const char* key, int64_t value);
 
@@ -120,7 +120,8 @@ size_t fg_workspace_bytes(fg_ws_kind_t kind, int64_t n, int64_t reserved);
  *                       nnz = entries of col (a row whose range leaves [0, nnz] is treated as empty);
  *                       n_src = number of positions of layer-1 (n_src >= n).
  *   live_src_dev[n_src] out, uint8: set to 0 by the call, then 1 at position j of every normal row j and at
- *                       every neighbour position of a normal row (what survives below). NULL iff no block.
+ *                       every neighbour position of a normal row (what survives below). NULL without a block;
+ *                       NULL with a block = prune only, liveness of the layer below not wanted.
  *   hit_dev[n]          out, uint8 per position: 1 = live and found in the cache (may be NULL if cache == NULL)
  *   hit_pos_dev, hit_slot_dev   out, int32[n]: positions of the hits in ascending order and their cache slots
  *                       (may be NULL if cache == NULL)
@@ -177,6 +178,24 @@ fg_status_t fg_aggregate(const int32_t* row_start_dev, const int32_t* row_end_de
                          int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
                          const void* h_src, int32_t n_src, int64_t src_stride, int32_t dim, fg_dtype_t in_dtype,
                          void* agg, int64_t agg_stride, fg_dtype_t out_dtype, void* stream);
+
+/*
+ * Loader fused with the first layer's aggregation: the same mean, taken straight from the feature table without
+ * materialising the neighbours' rows (Load_feature and the AGG of Eq. 1 in one pass; every needed table row is
+ * still read exactly once per referencing edge, nothing is written but the means):
+ *   agg[k, :] = (1/deg) * sum_{e in [row_start[r], row_end[r])} table[src_ids[col[e]], :],  r = rows[k]
+ * Arguments as for fg_aggregate, with h_src replaced by
+ *   src_ids_dev[n_src]              node id of every position of the input layer
+ *   table, table_rows, src_stride   the feature table (device, or host memory mapped into the device address space)
+ * Equal, up to fp64 rounding of the sums, to fg_gather of the input rows followed by fg_aggregate. The caller
+ * still gathers the rows of the layer-1 nodes themselves (fg_gather with normal_ids/normal_pos of layer 1), which
+ * fg_linear needs; it does not need the top-down call for layer 0.
+ */
+fg_status_t fg_gather_aggregate(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
+                                int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                int64_t max_rows, const int32_t* src_ids_dev, int32_t n_src, const void* table,
+                                int64_t table_rows, int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg,
+                                int64_t agg_stride, fg_dtype_t out_dtype, void* stream);
 
 /*
  * Dense update of a GraphSAGE-mean layer (phi of Eq. 1; the f_W line of Algorithm 1), for the rows listed:

@@ -98,14 +98,24 @@ __device__ __forceinline__ void store_row_piece(char* dst, const double* acc, do
     }
 }
 
+template <bool STREAM>
+__device__ __forceinline__ u32x4 load_piece(const char* p) {
+    if constexpr (STREAM)
+        return __builtin_nontemporal_load((const u32x4*)p);
+    else
+        return *(const u32x4*)p;
+}
+
 // IN: element type of h_src; OUT: element type of agg. One group of `lanes` lanes per output row;
 // pieces = 16-byte pieces per row (may exceed `lanes`, then a lane loops).
-template <int IN, int OUT>
+// INDIRECT: h_src is a table indexed by node id and src_ids[] maps a neighbour position to its id (the fused
+// loader + first-layer aggregation); table rows are then read with streaming loads, once each.
+template <int IN, int OUT, bool INDIRECT>
 __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
     const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ col,
     int64_t nnz, int n_block_rows, const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev,
-    int64_t max_rows, const char* __restrict__ h_src, int n_src, int64_t src_stride, int pieces, char* __restrict__ agg,
-    int64_t agg_stride, int lanes_log2) {
+    int64_t max_rows, const char* __restrict__ h_src, int64_t n_src, int64_t src_stride, int pieces, char* __restrict__ agg,
+    int64_t agg_stride, int lanes_log2, const int32_t* __restrict__ src_ids, int n_ids) {
     constexpr int PER = Elem<IN>::PER16;
     constexpr int OUT_BYTES = (OUT == FG_F32 ? 4 : 2) * PER;
     extern __shared__ int32_t nb_lds[];  // [groups_per_block][AGG_MAX_STAGE]
@@ -134,7 +144,11 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
             for (int base = 0; base < deg; base += AGG_MAX_STAGE) {
                 const int cnt = min(deg - base, AGG_MAX_STAGE);
                 // stage this row's neighbour positions: coalesced read, broadcast reads afterwards
-                for (int t = lane; t < cnt; t += lanes) my_nb[t] = col[s0 + base + t];
+                for (int t = lane; t < cnt; t += lanes) {
+                    int32_t c = col[s0 + base + t];
+                    if (INDIRECT) c = (c >= 0 && c < n_ids) ? src_ids[c] : -1;
+                    my_nb[t] = c;
+                }
                 // lanes of a group sit in one wavefront when lanes <= 64, so LDS writes above are visible
                 // to the group after a wavefront-level fence
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -148,7 +162,7 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
                     for (int u = 0; u < 4; ++u) {
                         const int32_t c = my_nb[t + u];
                         ok[u] = active && c >= 0 && c < n_src;
-                        if (ok[u]) raw[u] = *(const u32x4*)(h_src + (int64_t)c * src_stride + (int64_t)piece * 16);
+                        if (ok[u]) raw[u] = load_piece<INDIRECT>(h_src + (int64_t)c * src_stride + (int64_t)piece * 16);
                     }
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
@@ -157,7 +171,7 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
                 for (; t < cnt; ++t) {
                     const int32_t c = my_nb[t];
                     if (active && c >= 0 && c < n_src) {
-                        const u32x4 raw = *(const u32x4*)(h_src + (int64_t)c * src_stride + (int64_t)piece * 16);
+                        const u32x4 raw = load_piece<INDIRECT>(h_src + (int64_t)c * src_stride + (int64_t)piece * 16);
                         Elem<IN>::unpack(raw, acc);
                     }
                 }
@@ -170,26 +184,26 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
 
 }  // namespace
 
-extern "C" fg_status_t fg_aggregate(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
-                                    int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev,
-                                    const int64_t* n_rows_dev, int64_t max_rows, const void* h_src, int32_t n_src,
+static fg_status_t aggregate_common(const char* who, const int32_t* row_start_dev, const int32_t* row_end_dev,
+                                    const int32_t* col_dev, int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev,
+                                    const int64_t* n_rows_dev, int64_t max_rows, const void* h_src, int64_t n_src,
                                     int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
-                                    fg_dtype_t out_dtype, void* stream) {
-    if (max_rows < 0 || n_block_rows < 0 || n_src < 0 || dim <= 0 || nnz < 0)
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_aggregate: bad size (max_rows %lld, n_block_rows %d, n_src %d, dim %d, nnz %lld)",
-                (long long)max_rows, n_block_rows, n_src, dim, (long long)nnz);
+                                    fg_dtype_t out_dtype, const int32_t* src_ids, int32_t n_ids, void* stream) {
+    if (max_rows < 0 || n_block_rows < 0 || n_src < 0 || dim <= 0 || nnz < 0 || n_ids < 0)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (max_rows %lld, n_block_rows %d, n_src %lld, dim %d, nnz %lld)", who,
+                (long long)max_rows, n_block_rows, (long long)n_src, dim, (long long)nnz);
     const int isz = fg_dtype_size(in_dtype), osz = fg_dtype_size(out_dtype);
-    if (!isz || !osz) FG_FAIL(FG_ERR_DTYPE, "fg_aggregate: unknown element type");
+    if (!isz || !osz) FG_FAIL(FG_ERR_DTYPE, "%s: unknown element type", who);
     if (max_rows > 0 && (!row_start_dev || !row_end_dev || !h_src || !agg || (nnz > 0 && !col_dev)))
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_aggregate: NULL pointer");
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
     const int per16 = 16 / isz;
-    if (dim % per16) FG_FAIL(FG_ERR_SHAPE, "fg_aggregate: dim = %d must be a multiple of %d for this type", dim, per16);
+    if (dim % per16) FG_FAIL(FG_ERR_SHAPE, "%s: dim = %d must be a multiple of %d for this type", who, dim, per16);
     if (src_stride < (int64_t)dim * isz || agg_stride < (int64_t)dim * osz)
-        FG_FAIL(FG_ERR_SHAPE, "fg_aggregate: row stride smaller than a row");
+        FG_FAIL(FG_ERR_SHAPE, "%s: row stride smaller than a row", who);
     if (((uintptr_t)h_src | (uintptr_t)src_stride) & 15)
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_aggregate: h_src and its stride must be 16-byte aligned");
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: the source rows and their stride must be 16-byte aligned", who);
     if (((uintptr_t)agg | (uintptr_t)agg_stride) & 15)
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_aggregate: agg and its stride must be 16-byte aligned");
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: agg and its stride must be 16-byte aligned", who);
     fg_clear_error();
     if (max_rows == 0) return FG_OK;
     const int pieces = dim / per16;
@@ -201,27 +215,56 @@ extern "C" fg_status_t fg_aggregate(const int32_t* row_start_dev, const int32_t*
     if (blocks > cap) blocks = cap;
     const size_t lds = (size_t)gpb * AGG_MAX_STAGE * sizeof(int32_t);
     hipStream_t st = (hipStream_t)stream;
-#define FG_AGG_LAUNCH(IN, OUT)                                                                                        \
-    hipLaunchKernelGGL((aggregate_mean_kernel<IN, OUT>), dim3((unsigned)blocks), dim3(AGG_THREADS), lds, st,           \
-                       row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,         \
-                       (const char*)h_src, n_src, src_stride, pieces, (char*)agg, agg_stride, lg)
-#define FG_AGG_IN(IN)                                  \
+#define FG_AGG_LAUNCH(IN, OUT, IND)                                                                                    \
+    hipLaunchKernelGGL((aggregate_mean_kernel<IN, OUT, IND>), dim3((unsigned)blocks), dim3(AGG_THREADS), lds, st,       \
+                       row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,          \
+                       (const char*)h_src, n_src, src_stride, pieces, (char*)agg, agg_stride, lg, src_ids, n_ids)
+#define FG_AGG_OUT(IN, IND)                            \
     do {                                               \
         if (out_dtype == FG_F32)                       \
-            FG_AGG_LAUNCH(IN, FG_F32);                 \
+            FG_AGG_LAUNCH(IN, FG_F32, IND);            \
         else if (out_dtype == FG_F16)                  \
-            FG_AGG_LAUNCH(IN, FG_F16);                 \
+            FG_AGG_LAUNCH(IN, FG_F16, IND);            \
         else                                           \
-            FG_AGG_LAUNCH(IN, FG_BF16);                \
+            FG_AGG_LAUNCH(IN, FG_BF16, IND);           \
     } while (0)
-    if (in_dtype == FG_F32)
-        FG_AGG_IN(FG_F32);
-    else if (in_dtype == FG_F16)
-        FG_AGG_IN(FG_F16);
+#define FG_AGG_IN(IND)                                 \
+    do {                                               \
+        if (in_dtype == FG_F32)                        \
+            FG_AGG_OUT(FG_F32, IND);                   \
+        else if (in_dtype == FG_F16)                   \
+            FG_AGG_OUT(FG_F16, IND);                   \
+        else                                           \
+            FG_AGG_OUT(FG_BF16, IND);                  \
+    } while (0)
+    if (src_ids)
+        FG_AGG_IN(true);
     else
-        FG_AGG_IN(FG_BF16);
+        FG_AGG_IN(false);
 #undef FG_AGG_IN
+#undef FG_AGG_OUT
 #undef FG_AGG_LAUNCH
     FG_LAUNCH_CHECK("aggregate_mean_kernel");
     return FG_OK;
+}
+
+extern "C" fg_status_t fg_aggregate(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
+                                    int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev,
+                                    const int64_t* n_rows_dev, int64_t max_rows, const void* h_src, int32_t n_src,
+                                    int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
+                                    fg_dtype_t out_dtype, void* stream) {
+    return aggregate_common("fg_aggregate", row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev,
+                            max_rows, h_src, n_src, src_stride, dim, in_dtype, agg, agg_stride, out_dtype, nullptr, 0, stream);
+}
+
+extern "C" fg_status_t fg_gather_aggregate(const int32_t* row_start_dev, const int32_t* row_end_dev,
+                                           const int32_t* col_dev, int64_t nnz, int32_t n_block_rows,
+                                           const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                                           const int32_t* src_ids_dev, int32_t n_src, const void* table, int64_t table_rows,
+                                           int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg,
+                                           int64_t agg_stride, fg_dtype_t out_dtype, void* stream) {
+    if (max_rows > 0 && !src_ids_dev) FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather_aggregate: src_ids_dev is NULL");
+    return aggregate_common("fg_gather_aggregate", row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev,
+                            n_rows_dev, max_rows, table, table_rows, src_stride, dim, in_dtype, agg, agg_stride, out_dtype,
+                            src_ids_dev, n_src, stream);
 }

@@ -72,39 +72,46 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
     const int a_m = t >> 3;   // rows a_m + 32 i
     const int b_nc = t & 15;  // which 16-byte piece of the 64-wide n tile
     const int b_k = t >> 4;   // k rows b_k + 16 i
+    // loads are unconditional (dummy address + select) so that the compiler can count the outstanding prefetch
     const float* a_self[A_LOADS];
     const float* a_agg[A_LOADS];
+    bool a_ok[A_LOADS];
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) {
         const int m = a_m + 32 * i;
         const int32_t r = row_of[m];
-        a_self[i] = r >= 0 ? (const float*)(h_src + (int64_t)r * src_stride) : nullptr;
-        a_agg[i] = r >= 0 ? (const float*)(agg + (m0 + m) * agg_stride) : nullptr;
+        a_ok[i] = r >= 0;
+        a_self[i] = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0));
+        a_agg[i] = (const float*)(agg + (r >= 0 ? (m0 + m) * agg_stride : 0));
     }
     const bool b_col_ok = (n0 + 4 * b_nc) < d_out;
+    const int b_col = b_col_ok ? n0 + 4 * b_nc : 0;
 
     f32x4 ra[A_LOADS], rb[B_LOADS];
     auto load_step = [&](int k0) {
         const int ka = k0 + 4 * a_kc;
+        // nothing here may touch the loaded values (a select would make the wavefront wait for the load on the
+        // spot and undo the prefetch): out-of-range pieces are zeroed when they are written to LDS
+        const int kac = ka < K ? ka : 0;
 #pragma unroll
         for (int i = 0; i < A_LOADS; ++i) {
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (a_self[i] && ka < K) v = ka < d_in ? *(const f32x4*)(a_self[i] + ka) : *(const f32x4*)(a_agg[i] + (ka - d_in));
-            ra[i] = v;
+            const float* p = kac < d_in ? a_self[i] + kac : a_agg[i] + (kac - d_in);
+            ra[i] = *(const f32x4*)p;
         }
 #pragma unroll
         for (int i = 0; i < B_LOADS; ++i) {
             const int kb = k0 + b_k + 16 * i;
-            f32x4 v = {0.f, 0.f, 0.f, 0.f};
-            if (b_col_ok && kb < K) v = *(const f32x4*)(W + (int64_t)kb * d_out + n0 + 4 * b_nc);
-            rb[i] = v;
+            rb[i] = *(const f32x4*)(W + (int64_t)(kb < K ? kb : 0) * d_out + b_col);
         }
     };
-    auto store_step = [&]() {
+    auto store_step = [&](int k0) {
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        const bool ka_ok = k0 + 4 * a_kc < K;
 #pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) *(f32x4*)(As + (a_m + 32 * i) * LDA + 4 * a_kc) = ra[i];
+        for (int i = 0; i < A_LOADS; ++i) *(f32x4*)(As + (a_m + 32 * i) * LDA + 4 * a_kc) = (a_ok[i] && ka_ok) ? ra[i] : z;
 #pragma unroll
-        for (int i = 0; i < B_LOADS; ++i) *(f32x4*)(Bs + (b_k + 16 * i) * LDB + 4 * b_nc) = rb[i];
+        for (int i = 0; i < B_LOADS; ++i)
+            *(f32x4*)(Bs + (b_k + 16 * i) * LDB + 4 * b_nc) = (b_col_ok && k0 + b_k + 16 * i < K) ? rb[i] : z;
     };
 
     const int lane = t & 63, wave = t >> 6;
@@ -120,9 +127,11 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
     const int nk = (K + BK - 1) / BK;
     load_step(0);
     for (int step = 0; step < nk; ++step) {
-        store_step();
+        store_step(step * BK);
         __syncthreads();
-        if (step + 1 < nk) load_step((step + 1) * BK);
+        load_step((step + 1) * BK);  // beyond K: reads a valid dummy address, zeroed at the LDS store
+        // keep the prefetch ahead of the matrix instructions (the scheduler would otherwise sink it next to its use)
+        __builtin_amdgcn_sched_barrier(0);
         f32x4 av[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) av[q] = *(const f32x4*)(As + (wm + l32) * LDA + 16 * half + 4 * q);
@@ -197,9 +206,10 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
             FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: h_out, its stride and bias must be 4-byte aligned");
         fg_clear_error();
         if (max_rows == 0) return FG_OK;
+        const int64_t forced = fg_tuning(FG_TUNE_LINEAR_TILE);
         const int ny = (int)fg_ceil_div(d_out, BN);
-        // few rows: 64-row tiles give twice the workgroups to spread over the compute units
-        const bool big = fg_ceil_div(max_rows, 128) * ny >= 512;
+        // 64-row tiles (four workgroups per compute unit) measured faster than 128-row tiles at every layer size
+        const bool big = forced >= 128;
         const int64_t m_tiles = fg_ceil_div(max_rows, big ? 128 : 64);
         const unsigned grid = (unsigned)(fg_ceil_div(m_tiles, 8) * 8 * ny);
         if (big)

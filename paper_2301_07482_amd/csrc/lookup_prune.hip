@@ -59,8 +59,8 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void classify_mark_kernel(
                 row_end[j] = s0;
             } else {
                 const int32_t e0 = row_end[j];
-                if (j < n_src) live_src[j] = 1;
-                if (s0 >= 0 && s0 <= e0 && (int64_t)e0 <= nnz) {
+                if (live_src && j < n_src) live_src[j] = 1;
+                if (live_src && s0 >= 0 && s0 <= e0 && (int64_t)e0 <= nnz) {
                     for (int32_t e = s0; e < e0; ++e) {
                         const int32_t c = col[e];
                         if (c >= 0 && c < n_src) live_src[c] = 1;  // many writers, one value
@@ -147,9 +147,8 @@ extern "C" fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, i
         FG_FAIL(FG_ERR_INVALID_ARG, "fg_lookup_prune: ids_dev and normal_pos_dev are required");
     const bool has_block = row_start_dev || row_end_dev || col_dev || live_src_dev;
     if (has_block) {
-        if (!row_start_dev || !row_end_dev || !live_src_dev || (nnz > 0 && !col_dev))
-            FG_FAIL(FG_ERR_INVALID_ARG,
-                    "fg_lookup_prune: a block needs row_start_dev, row_end_dev, col_dev and live_src_dev together");
+        if (!row_start_dev || !row_end_dev || (nnz > 0 && !col_dev && live_src_dev))
+            FG_FAIL(FG_ERR_INVALID_ARG, "fg_lookup_prune: a block needs row_start_dev, row_end_dev and col_dev together");
         if (nnz < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_lookup_prune: nnz = %lld is negative", (long long)nnz);
         if (n_src < n) FG_FAIL(FG_ERR_SHAPE, "fg_lookup_prune: n_src = %d is smaller than n = %d", n_src, n);
     }
@@ -168,7 +167,7 @@ extern "C" fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, i
     if (ws_dev && ((uintptr_t)ws_dev & 15)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_lookup_prune: workspace must be 16-byte aligned");
     fg_clear_error();
     hipStream_t st = (hipStream_t)stream;
-    if (has_block && n_src > 0) {
+    if (has_block && live_src_dev && n_src > 0) {
         fg_status_t rc = fg_launch_fill_u8(live_src_dev, n_src, 0, st);
         if (rc != FG_OK) return rc;
     }

@@ -46,7 +46,7 @@ class HotPath:
     """Work buffers, cache and weights of one model; `run(batch, it)` executes one iteration."""
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
-                 weights, features_on_host=False, device="cuda", use_cache=True):
+                 weights, features_on_host=False, device="cuda", use_cache=True, overlap_update=True, fused_input=False):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -57,6 +57,9 @@ class HotPath:
         self.comp_code = DTYPE_CODE[compute_dtype]
         self.on_host = 1 if features_on_host else 0
         self.use_cache = use_cache
+        # fused_input: layer 1 aggregates straight from the feature table (fg_gather_aggregate); only the layer-1
+        # nodes' own rows are gathered into H[0] and the top-down pass stops at layer 1
+        self.fused_input = fused_input
         self.n_max, self.nnz_max = layer_bounds(batch, fanouts, num_nodes)
         n = self.n_max
         dev = device
@@ -72,6 +75,7 @@ class HotPath:
         self.hit_slot = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
         self.normal_pos = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
         self.input_ids = torch.zeros(n[0], dtype=torch.int32, device=dev)
+        self.self_ids = torch.zeros(n[1], dtype=torch.int32, device=dev)
         # device-side counts/stats are kept per iteration in a ring, so a timed loop can be read back afterwards
         self.ring = 256
         self.counts_log = torch.zeros((self.ring, L + 1, 3), dtype=torch.int64, device=dev)
@@ -82,6 +86,13 @@ class HotPath:
                        max([B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L)] or [0]))
         self.ws = torch.zeros(ws_bytes + 256, dtype=torch.uint8, device=dev)
         self.ws_bytes = ws_bytes
+        # The update of layer l only needs H[l], which is final once its linear has run: it is queued on a second
+        # stream (default priority) and overlaps the layers above; the next iteration waits for it before it
+        # touches the flags and embeddings again.
+        self.overlap_update = overlap_update and L > 1
+        self.side = torch.cuda.Stream(device=dev) if self.overlap_update else None
+        self.ws_upd = [torch.zeros(ws_bytes + 256, dtype=torch.uint8, device=dev) for _ in range(L)] if self.overlap_update else None
+        self.upd_done = []
         self.W = {}
         self.bias = {}
         wt = TORCH_DTYPE[self.comp_code]
@@ -107,31 +118,45 @@ class HotPath:
     def _cnt(self, l, k):
         return self.counts.data_ptr() + (l * 3 + k) * 8
 
-    def run(self, bt, it, update=True, stream=None, timer=None):
-        """One iteration. `timer(name)` (optional) is called before each C-ABI call and once at the end with None."""
+    def run(self, bt, it, update=True, timer=None):
+        """One iteration on torch's current stream. `timer(name, stream)` (optional) is called before each C-ABI call
+        and with name None after the last call of a stream (stream None = the current stream)."""
         L = self.L
-        st = self._stream() if stream is None else stream
         self.counts = self.counts_log[it % self.ring]
         self.stats = self.stats_log[it % self.ring]
-        tick = timer if timer is not None else (lambda name: None)
+        tick = timer if timer is not None else (lambda name, stream=None: None)
         esz = B.DTYPE_SIZE
+        main = torch.cuda.current_stream()
+        st = main.cuda_stream
+        for ev in self.upd_done:        # updates of the previous iteration still read live/hit/H
+            main.wait_event(ev)
+        self.upd_done = []
+        do_update = update and self.use_cache and self.cache is not None
         assert all(bt.n[l] <= self.n_max[l] for l in range(L + 1)), "mini-batch larger than the static bounds"
         # ---- top-down: lookup, prune, V_normal (layers L .. 0)
-        for l in range(L, -1, -1):
+        fused = self.fused_input
+        for l in range(L, 0 if fused else -1, -1):
             cache = self.cache if (self.use_cache and 1 <= l <= L - 1) else None
             has_block = l >= 1
+            want_live_below = has_block and not (fused and l == 1)
             tick(f"lookup_prune[{l}]")
             B.fg_lookup_prune(cache, l, it, bt.ids[l], bt.n[l], None if l == L else self.live[l],
                               bt.start[l] if has_block else None, bt.end[l] if has_block else None,
                               bt.col[l] if has_block else None, bt.nnz[l] if has_block else 0,
-                              bt.n[l - 1] if has_block else 0, self.live[l - 1] if has_block else None,
+                              bt.n[l - 1] if has_block else 0, self.live[l - 1] if want_live_below else None,
                               self.hit[l], self.hit_pos[l], self.hit_slot[l], self.normal_pos[l],
-                              self.input_ids if l == 0 else None, self._cnt(l, 0), self.ws, self.ws_bytes, st)
-        # ---- loader: raw features of the surviving input nodes
+                              self.input_ids if l == 0 else (self.self_ids if (fused and l == 1) else None),
+                              self._cnt(l, 0), self.ws, self.ws_bytes, st)
+        # ---- loader: raw features of the surviving input nodes (fused: only the layer-1 nodes' own rows)
         d0b = self.dims[0] * esz[self.feat_code]
-        tick("gather_features")
-        B.fg_gather(self.feat, self.num_nodes, d0b, d0b, self.input_ids, self.normal_pos[0], self._cnt(0, 2), bt.n[0],
-                    self.H[0], bt.n[0], d0b, self.on_host, st)
+        if fused:
+            tick("gather_self_rows")
+            B.fg_gather(self.feat, self.num_nodes, d0b, d0b, self.self_ids, self.normal_pos[1], self._cnt(1, 2), bt.n[1],
+                        self.H[0], bt.n[0], d0b, self.on_host, st)
+        else:
+            tick("gather_features")
+            B.fg_gather(self.feat, self.num_nodes, d0b, d0b, self.input_ids, self.normal_pos[0], self._cnt(0, 2), bt.n[0],
+                        self.H[0], bt.n[0], d0b, self.on_host, st)
         # ---- bottom-up: cached rows, mean aggregation, dense update
         for l in range(1, L + 1):
             in_code, out_code = self.h_code[l - 1], self.h_code[l]
@@ -142,16 +167,34 @@ class HotPath:
                 B.fg_gather(B.fg_cache_table(self.cache, l), self.capacity[l - 1], out_b, out_b, self.hit_slot[l],
                             self.hit_pos[l], self._cnt(l, 1), bt.n[l], self.H[l], bt.n[l], out_b, B.FG_TABLE_HBM_REUSED, st)
             agg_b = self.dims[l - 1] * esz[self.agg_code]
-            tick(f"aggregate[{l}]")
-            B.fg_aggregate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),
-                           bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], in_code, self.AGG, agg_b,
-                           self.agg_code, st)
+            if fused and l == 1:
+                tick("gather_aggregate[1]")
+                B.fg_gather_aggregate(bt.start[1], bt.end[1], bt.col[1], bt.nnz[1], bt.n[1], self.normal_pos[1],
+                                      self._cnt(1, 2), bt.n[1], bt.ids[0], bt.n[0], self.feat, self.num_nodes, d0b,
+                                      self.dims[0], in_code, self.AGG, agg_b, self.agg_code, st)
+            else:
+                tick(f"aggregate[{l}]")
+                B.fg_aggregate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),
+                               bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], in_code, self.AGG, agg_b,
+                               self.agg_code, st)
             tick(f"linear[{l}]")
             B.fg_linear(self.H[l - 1], bt.n[l - 1], in_b, in_code, self.AGG, agg_b, self.normal_pos[l], self._cnt(l, 2),
                         bt.n[l], self.dims[l - 1], self.dims[l], self.W[l], self.comp_code, self.bias[l],
                         1 if l < L else 0, self.H[l], bt.n[l], out_b, out_code, st)
+            if do_update and self.overlap_update and l < L:
+                ready = torch.cuda.Event()
+                ready.record(main)
+                self.side.wait_event(ready)
+                tick(f"cache_update[{l}]", self.side)
+                B.fg_cache_update(self.cache, l, it, bt.ids[l], bt.n[l], self.live[l], self.hit[l], bt.gnorm[l],
+                                  self.p_grad, self.H[l], out_b, self.stats.data_ptr() + l * 32, self.ws_upd[l],
+                                  self.ws_bytes, self.side.cuda_stream)
+                tick(None, self.side)
+                done = torch.cuda.Event()
+                done.record(self.side)
+                self.upd_done.append(done)
         # ---- update of the caches
-        if update and self.use_cache and self.cache is not None:
+        if do_update and not self.overlap_update:
             for l in range(1, L):
                 out_b = self.dims[l] * esz[self.h_code[l]]
                 tick(f"cache_update[{l}]")
@@ -166,7 +209,7 @@ class HotPath:
         torch.cuda.synchronize()
         counts = self.counts.cpu().numpy()
         out = dict(counts=counts, stats=self.stats.cpu().numpy(), layers={})
-        for l in range(L + 1):
+        for l in range(1 if self.fused_input else 0, L + 1):
             n = bt.n[l]
             n_hit, n_norm = int(counts[l, 1]), int(counts[l, 2])
             out["layers"][l] = dict(
@@ -175,7 +218,8 @@ class HotPath:
                 hit_pos=self.hit_pos[l][:n_hit].cpu().numpy(), hit_slot=self.hit_slot[l][:n_hit].cpu().numpy(),
                 normal_pos=self.normal_pos[l][:n_norm].cpu().numpy(),
                 end=None if l == 0 else bt.end[l].cpu().numpy())
-        out["input_ids"] = self.input_ids[:int(counts[0, 2])].cpu().numpy()
+        if not self.fused_input:
+            out["input_ids"] = self.input_ids[:int(counts[0, 2])].cpu().numpy()
         return out
 
     def export_cache(self, layer, it):

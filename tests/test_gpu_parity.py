@@ -183,6 +183,33 @@ def test_aggregate_matches_oracle(env, dim, dtype, max_deg, n):
         assert empty.any() and np.all(got[:len(rows)][empty] == 0)
 
 
+@pytest.mark.parametrize("dim,dtype,max_deg,n", [(128, "f32", 15, 3000), (100, "f32", 70, 500), (768, "f16", 25, 300)])
+def test_gather_aggregate_equals_gather_then_aggregate(env, dim, dtype, max_deg, n):
+    torch, B = env
+    r = np.random.default_rng(dim + n)
+    n_src, table_rows = 4 * n, 50000
+    start, end, col, nnz = _random_block(r, n, n_src, max_deg)
+    rows = np.sort(r.permutation(n)[: int(0.7 * n)]).astype(np.int32)
+    src_ids = r.permutation(table_rows)[:n_src].astype(np.int32)
+    code = {"f32": B.FG_F32, "f16": B.FG_F16}[dtype]
+    esz = 4 if dtype == "f32" else 2
+    table = O.round_to(r.standard_normal((table_rows, dim)), dtype)
+    out_dtype = "f32" if dtype == "f32" else "bf16"
+    ocode = {"f32": B.FG_F32, "bf16": B.FG_BF16}[out_dtype]
+    t_out = torch.zeros((len(rows), dim), dtype={"f32": torch.float32, "bf16": torch.bfloat16}[out_dtype], device="cuda")
+    t_cnt = torch.tensor([len(rows)], dtype=torch.int64, device="cuda")
+    B.fg_gather_aggregate(dev(torch, start), dev(torch, end), dev(torch, col), nnz, n, dev(torch, rows), t_cnt, len(rows),
+                          dev(torch, src_ids), n_src, dev(torch, table), table_rows, dim * esz, dim, code, t_out,
+                          dim * (4 if out_dtype == "f32" else 2), ocode, None)
+    # oracle: gather the input rows, then aggregate
+    h0 = np.zeros((n_src, dim), dtype=table.dtype)
+    O.gather(lambda idx: table[idx], src_ids, h0, None)
+    want = O.round_to(O.aggregate(start, end, col, rows, h0), out_dtype).astype(np.float32)
+    got = G.to_f32(t_out)
+    assert T.rel_err_rows(got, want) <= (REL_TOL_F32 if out_dtype == "f32" else 2e-2)
+    assert (got == want).mean() > 0.999
+
+
 # ------------------------------------------------------------------------------------------------ fg_linear
 
 def _linear_case(torch, B, r, n_src, n_rows, max_rows, d_in, d_out, relu, W=None, bias=None):
@@ -301,10 +328,11 @@ def test_iteration_counter_must_not_go_backwards(env):
 # ------------------------------------------------------------------------------------------------ whole iterations
 
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
-                        sample_rows=None, feat_table=None):
+                        sample_rows=None, feat_table=None, fused=False):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence."""
     g = wl.make_graph(w)
-    hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity)
+    hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity,
+                                             fused_input=fused)
     caches = G.make_oracle_caches(w, capacity=capacity, t_stale=t_stale)
     from paper_2301_07482_amd.pipeline import DeviceBatch
     frows = G.feature_accessor(w)
@@ -323,18 +351,22 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
             pre_rows = {l: hp.cache_rows(l, rec["look"][l]["hit_slot"]) for l in range(1, L) if len(rec["look"][l]["hit_pos"])}
             hp.run(bt, it)
             snap = hp.snapshot(bt)
-            for l in range(L, -1, -1):
+            for l in range(L, 0 if fused else -1, -1):
                 s, lk = snap["layers"][l], rec["look"][l]
                 assert tuple(snap["counts"][l]) == lk["counts"], f"counts, iteration {it} layer {l}"
                 assert np.array_equal(s["live"], rec["live"][l] if rec["live"][l] is not None else np.ones(len(mb.ids[l]), bool))
+                if fused and l == 1:     # the ids of the layer-1 nodes whose own rows are gathered
+                    assert np.array_equal(hp.self_ids[:len(lk["normal_pos"])].cpu().numpy(), mb.ids[1][lk["normal_pos"]])
                 assert np.array_equal(s["hit"], lk["hit"])
                 assert np.array_equal(s["hit_pos"], lk["hit_pos"]) and np.array_equal(s["hit_slot"], lk["hit_slot"])
                 assert np.array_equal(s["normal_pos"], lk["normal_pos"])
                 if l >= 1:
                     assert np.array_equal(s["end"], mb.end[l]), f"pruned row ends, iteration {it} layer {l}"
                 total_hits += len(lk["hit_pos"])
-            ipos = rec["look"][0]["normal_pos"]
-            assert np.array_equal(snap["input_ids"], mb.ids[0][ipos])
+            # fused input: only the layer-1 nodes' own rows exist in H[0]
+            ipos = rec["look"][1]["normal_pos"] if fused else rec["look"][0]["normal_pos"]
+            if not fused:
+                assert np.array_equal(snap["input_ids"], mb.ids[0][ipos])
             # gathered raw features: bit-exact
             rows_chk = ipos if sample_rows is None or len(ipos) <= sample_rows else np.sort(
                 np.random.default_rng(it).choice(ipos, sample_rows, replace=False))
@@ -351,7 +383,9 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                         got = G.to_f32(hp.H[l][idx])
                         # (a) each call against the oracle on the SAME inputs: the layer recomputed by the oracle from
                         #     the device's own previous-layer rows (bf16/fp16 values are exact in fp32)
-                        h_prev = G.to_f32(hp.H[l - 1][:len(mb.ids[l - 1])])
+                        # (fused input: the neighbours' rows were never materialised on the device; the oracle's
+                        #  bit-identical feature rows take their place)
+                        h_prev = rec["H"][0].astype(np.float32) if (fused and l == 1) else G.to_f32(hp.H[l - 1][:len(mb.ids[l - 1])])
                         agg64 = O.aggregate(mb.start[l], mb.end[l], mb.col[l], npos, h_prev)
                         agg_dtype = "f32" if w.compute_dtype == "f32" else "bf16"
                         agg_want = O.round_to(agg64, agg_dtype).astype(np.float32)
@@ -416,6 +450,21 @@ def test_iterations_tiny_small_ring(env):
     torch, B = env
     w = wl.WORKLOADS["tiny"]
     hits, _ = run_workload_parity(torch, w, 10, capacity=97, p_grad=0.9)
+    assert hits > 0
+
+
+def test_iterations_tiny_fused_input(env):
+    """Layer 1 aggregated straight from the feature table (fg_gather_aggregate): same lists, same outputs."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    hits, worst = run_workload_parity(torch, w, w.iterations, fused=True)
+    assert hits > 100
+
+
+def test_iterations_medium_fused_input(env):
+    torch, B = env
+    w = wl.WORKLOADS["medium"]
+    hits, worst = run_workload_parity(torch, w, 6, check_numeric_every=2, sample_rows=20000, fused=True)
     assert hits > 0
 
 
