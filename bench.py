@@ -104,16 +104,17 @@ def main():
     ev = []
 
     def timer_for(step_events, only=None):
-        state = {"open": False}
+        is_open = {}
 
         def tick(name, stream=None):
+            key = id(stream) if stream is not None else 0
             if only is not None:
-                if not (name in only or state["open"]):
+                if not (name in only or is_open.get(key, False)):
                     return
-                state["open"] = name in only
+                is_open[key] = name in only
             e = torch.cuda.Event(enable_timing=True)
             e.record(stream) if stream is not None else e.record()
-            step_events.setdefault(id(stream) if stream is not None else 0, []).append((name, e))
+            step_events.setdefault(key, []).append((name, e))
         return tick
 
     torch.cuda.synchronize()
