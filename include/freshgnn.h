@@ -137,6 +137,40 @@ fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, int64_t iter
                             int32_t* normal_ids_dev, int64_t* counts_dev, void* ws_dev, size_t ws_bytes, void* stream);
 
 /*
+ * The whole top-down pass (fg_lookup_prune for every layer from the seeds down) in one call. Layer by layer the
+ * pass is a chain of dependent random reads; here the cache lookups of all layers, which do not depend on
+ * liveness, are done up front in one launch and the per-layer steps only combine flags and walk the rows.
+ * Same results as calling fg_lookup_prune layer by layer.
+ *
+ * layers[0] is the seed layer, layers[i+1] the layer below layers[i]; each entry carries the arguments of
+ * fg_lookup_prune for its layer (same meaning, same NULL rules). cache_layer = 0: no lookup for this layer;
+ * otherwise the layer of `cache` to look up (1..n_layers of the cache). layers[i].live_src_dev, when given,
+ * must be layers[i+1].live_dev. At most 8 layers.
+ * ws_dev: >= fg_top_down_workspace_bytes(n_layers, layers) bytes, 16-byte aligned.
+ */
+typedef struct fg_top_down_layer {
+    int32_t cache_layer;
+    int32_t n;
+    const int32_t* ids_dev;
+    const uint8_t* live_dev;
+    const int32_t* row_start_dev;
+    int32_t* row_end_dev;
+    const int32_t* col_dev;
+    int64_t nnz;
+    int32_t n_src;
+    uint8_t* live_src_dev;
+    uint8_t* hit_dev;
+    int32_t* hit_pos_dev;
+    int32_t* hit_slot_dev;
+    int32_t* normal_pos_dev;
+    int32_t* normal_ids_dev;
+    int64_t* counts_dev;
+} fg_top_down_layer_t;
+size_t fg_top_down_workspace_bytes(int32_t n_layers, const fg_top_down_layer_t* layers);
+fg_status_t fg_top_down(const fg_cache_t* cache, int64_t iter, int32_t n_layers, const fg_top_down_layer_t* layers,
+                        void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
  * Row gather, a bit copy: for k < *count_dev: dst[dst_pos[k], :] = table[src_index[k], :].
  * Serves Load_feature(V_normal^(0)) (Algorithm 1; Section 6, one-sided reads by node id: `table` may be
  * pinned host memory mapped into the device address space) and the cache fetch h_v = C^(l)[v].

@@ -41,6 +41,18 @@ SIGNATURES = {
     "fg_linear": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _p, _i64, _i32, _i32, _p, _i32, _p, _i32, _p, _i32, _i64, _i32, _p]),
     "fg_cache_update": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _f, _p, _i64, _p, _p, _sz, _p]),
 }
+
+
+class TopDownLayer(C.Structure):
+    """fg_top_down_layer_t"""
+    _fields_ = [("cache_layer", _i32), ("n", _i32), ("ids_dev", _p), ("live_dev", _p), ("row_start_dev", _p),
+                ("row_end_dev", _p), ("col_dev", _p), ("nnz", _i64), ("n_src", _i32), ("live_src_dev", _p), ("hit_dev", _p),
+                ("hit_pos_dev", _p), ("hit_slot_dev", _p), ("normal_pos_dev", _p), ("normal_ids_dev", _p), ("counts_dev", _p)]
+
+
+SIGNATURES["fg_top_down_workspace_bytes"] = (_sz, [_i32, C.POINTER(TopDownLayer)])
+SIGNATURES["fg_top_down"] = (_i32, [_p, _i64, _i32, C.POINTER(TopDownLayer), _p, _sz, _p])
+
 for _name, (_res, _args) in SIGNATURES.items():
     _fn = getattr(_lib, _name)
     _fn.restype, _fn.argtypes = _res, _args
@@ -117,6 +129,24 @@ def fg_lookup_prune(cache, layer, it, ids, n, live, row_start, row_end, col, nnz
     _check(_lib.fg_lookup_prune(cache, layer, it, ptr(ids), n, ptr(live), ptr(row_start), ptr(row_end), ptr(col), nnz, n_src,
                                 ptr(live_src), ptr(hit), ptr(hit_pos), ptr(hit_slot), ptr(normal_pos), ptr(normal_ids),
                                 ptr(counts), ptr(ws), ws_bytes, stream))
+
+
+def top_down_layers(specs):
+    """ctypes array of fg_top_down_layer_t from dicts (tensors or addresses; missing keys are NULL / 0)."""
+    arr = (TopDownLayer * len(specs))()
+    for e, d in zip(arr, specs):
+        for name, ctype in TopDownLayer._fields_:
+            v = d.get(name)
+            setattr(e, name, (ptr(v) if ctype is _p else (v or 0)))
+    return arr
+
+
+def fg_top_down_workspace_bytes(layers):
+    return _lib.fg_top_down_workspace_bytes(len(layers), layers)
+
+
+def fg_top_down(cache, it, layers, ws, ws_bytes, stream=None):
+    _check(_lib.fg_top_down(cache, it, len(layers), layers, ptr(ws), ws_bytes, stream))
 
 
 def fg_gather(table, table_rows, src_stride, row_bytes, src_index, dst_pos, count, max_count, dst, dst_rows, dst_stride,

@@ -16,6 +16,7 @@ namespace {
 
 constexpr int AGG_THREADS = 256;
 constexpr int AGG_MAX_STAGE = 64;  // neighbour indices staged per row and pass
+constexpr int AGG_UNROLL = 8;      // neighbour rows in flight per lane
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -141,8 +142,9 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
             double acc[PER];
 #pragma unroll
             for (int i = 0; i < PER; ++i) acc[i] = 0.0;
-            for (int base = 0; base < deg; base += AGG_MAX_STAGE) {
-                const int cnt = min(deg - base, AGG_MAX_STAGE);
+            const int deg_ld = n_src > 0 ? deg : 0;  // an empty source has no row to read (the means are then zero)
+            for (int base = 0; base < deg_ld; base += AGG_MAX_STAGE) {
+                const int cnt = min(deg_ld - base, AGG_MAX_STAGE);
                 // stage this row's neighbour positions: coalesced read, broadcast reads afterwards
                 for (int t = lane; t < cnt; t += lanes) {
                     int32_t c = col[s0 + base + t];
@@ -154,26 +156,25 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
                 __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
                 __builtin_amdgcn_wave_barrier();
                 __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-                int t = 0;
-                for (; t + 4 <= cnt; t += 4) {
-                    u32x4 raw[4];
-                    bool ok[4];
+                // AGG_UNROLL neighbour rows in flight per lane, issued back to back without branches: a slot past the
+                // end of the row (or an out-of-range index) re-reads the batch's first row, which is in cache by
+                // then, and is dropped when the values are added up. Nothing touches a loaded value before the
+                // whole batch has been issued.
+                for (int t = 0; t < cnt; t += AGG_UNROLL) {
+                    u32x4 raw[AGG_UNROLL];
+                    bool ok[AGG_UNROLL];
+                    const int32_t c_first = my_nb[t];
+                    const int64_t safe = (c_first >= 0 && c_first < n_src) ? (int64_t)c_first : 0;
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {
-                        const int32_t c = my_nb[t + u];
-                        ok[u] = active && c >= 0 && c < n_src;
-                        if (ok[u]) raw[u] = load_piece<INDIRECT>(h_src + (int64_t)c * src_stride + (int64_t)piece * 16);
+                    for (int u = 0; u < AGG_UNROLL; ++u) {
+                        const int32_t c = (t + u < cnt) ? my_nb[t + u] : -1;
+                        ok[u] = c >= 0 && c < n_src;
+                        const int64_t row = ok[u] ? (int64_t)c : safe;
+                        raw[u] = load_piece<INDIRECT>(h_src + row * src_stride + (int64_t)(active ? piece : 0) * 16);
                     }
 #pragma unroll
-                    for (int u = 0; u < 4; ++u)
+                    for (int u = 0; u < AGG_UNROLL; ++u)
                         if (ok[u]) Elem<IN>::unpack(raw[u], acc);
-                }
-                for (; t < cnt; ++t) {
-                    const int32_t c = my_nb[t];
-                    if (active && c >= 0 && c < n_src) {
-                        const u32x4 raw = load_piece<INDIRECT>(h_src + (int64_t)c * src_stride + (int64_t)piece * 16);
-                        Elem<IN>::unpack(raw, acc);
-                    }
                 }
                 __builtin_amdgcn_wave_barrier();  // the stage is rewritten by the next pass
             }

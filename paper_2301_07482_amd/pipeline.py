@@ -46,7 +46,8 @@ class HotPath:
     """Work buffers, cache and weights of one model; `run(batch, it)` executes one iteration."""
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
-                 weights, features_on_host=False, device="cuda", use_cache=True, overlap_update=True, fused_input=False):
+                 weights, features_on_host=False, device="cuda", use_cache=True, overlap_update=True, fused_input=False,
+                 one_launch_top_down=True):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -60,6 +61,9 @@ class HotPath:
         # fused_input: layer 1 aggregates straight from the feature table (fg_gather_aggregate); only the layer-1
         # nodes' own rows are gathered into H[0] and the top-down pass stops at layer 1
         self.fused_input = fused_input
+        # one_launch_top_down: the whole top-down pass as one cooperative launch (fg_top_down) instead of one
+        # fg_lookup_prune call per layer
+        self.one_launch_top_down = one_launch_top_down
         self.n_max, self.nnz_max = layer_bounds(batch, fanouts, num_nodes)
         n = self.n_max
         dev = device
@@ -86,6 +90,8 @@ class HotPath:
                        max([B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L)] or [0]))
         self.ws = torch.zeros(ws_bytes + 256, dtype=torch.uint8, device=dev)
         self.ws_bytes = ws_bytes
+        self.ws_td_bytes = sum(B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, n[l]) for l in range(L + 1))
+        self.ws_td = torch.zeros(self.ws_td_bytes + 256, dtype=torch.uint8, device=dev)
         # The update of layer l only needs H[l], which is final once its linear has run: it is queued on a second
         # stream (default priority) and overlaps the layers above; the next iteration waits for it before it
         # touches the flags and embeddings again.
@@ -135,18 +141,33 @@ class HotPath:
         assert all(bt.n[l] <= self.n_max[l] for l in range(L + 1)), "mini-batch larger than the static bounds"
         # ---- top-down: lookup, prune, V_normal (layers L .. 0)
         fused = self.fused_input
-        for l in range(L, 0 if fused else -1, -1):
-            cache = self.cache if (self.use_cache and 1 <= l <= L - 1) else None
+        lowest = 1 if fused else 0
+
+        def layer_args(l):
             has_block = l >= 1
             want_live_below = has_block and not (fused and l == 1)
-            tick(f"lookup_prune[{l}]")
-            B.fg_lookup_prune(cache, l, it, bt.ids[l], bt.n[l], None if l == L else self.live[l],
-                              bt.start[l] if has_block else None, bt.end[l] if has_block else None,
-                              bt.col[l] if has_block else None, bt.nnz[l] if has_block else 0,
-                              bt.n[l - 1] if has_block else 0, self.live[l - 1] if want_live_below else None,
-                              self.hit[l], self.hit_pos[l], self.hit_slot[l], self.normal_pos[l],
-                              self.input_ids if l == 0 else (self.self_ids if (fused and l == 1) else None),
-                              self._cnt(l, 0), self.ws, self.ws_bytes, st)
+            return dict(cache_layer=l if (self.use_cache and self.cache is not None and 1 <= l <= L - 1) else 0,
+                        ids_dev=bt.ids[l], n=bt.n[l], live_dev=None if l == L else self.live[l],
+                        row_start_dev=bt.start[l] if has_block else None, row_end_dev=bt.end[l] if has_block else None,
+                        col_dev=bt.col[l] if has_block else None, nnz=bt.nnz[l] if has_block else 0,
+                        n_src=bt.n[l - 1] if has_block else 0, live_src_dev=self.live[l - 1] if want_live_below else None,
+                        hit_dev=self.hit[l], hit_pos_dev=self.hit_pos[l], hit_slot_dev=self.hit_slot[l],
+                        normal_pos_dev=self.normal_pos[l],
+                        normal_ids_dev=self.input_ids if l == 0 else (self.self_ids if (fused and l == 1) else None),
+                        counts_dev=self._cnt(l, 0))
+
+        if self.one_launch_top_down:
+            tick("top_down")
+            layers = B.top_down_layers([layer_args(l) for l in range(L, lowest - 1, -1)])
+            B.fg_top_down(self.cache if self.use_cache else None, it, layers, self.ws_td, self.ws_td_bytes, st)
+        else:
+            for l in range(L, lowest - 1, -1):
+                a = layer_args(l)
+                tick(f"lookup_prune[{l}]")
+                B.fg_lookup_prune(self.cache if a["cache_layer"] else None, l, it, a["ids_dev"], a["n"], a["live_dev"],
+                                  a["row_start_dev"], a["row_end_dev"], a["col_dev"], a["nnz"], a["n_src"], a["live_src_dev"],
+                                  a["hit_dev"], a["hit_pos_dev"], a["hit_slot_dev"], a["normal_pos_dev"], a["normal_ids_dev"],
+                                  a["counts_dev"], self.ws, self.ws_bytes, st)
         # ---- loader: raw features of the surviving input nodes (fused: only the layer-1 nodes' own rows)
         d0b = self.dims[0] * esz[self.feat_code]
         if fused:

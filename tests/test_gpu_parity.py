@@ -328,11 +328,11 @@ def test_iteration_counter_must_not_go_backwards(env):
 # ------------------------------------------------------------------------------------------------ whole iterations
 
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
-                        sample_rows=None, feat_table=None, fused=False):
+                        sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence."""
     g = wl.make_graph(w)
     hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity,
-                                             fused_input=fused)
+                                             fused_input=fused, one_launch_top_down=one_launch_top_down)
     caches = G.make_oracle_caches(w, capacity=capacity, t_stale=t_stale)
     from paper_2301_07482_amd.pipeline import DeviceBatch
     frows = G.feature_accessor(w)
@@ -435,6 +435,14 @@ def test_iterations_tiny(env):
     hits, worst = run_workload_parity(torch, w, w.iterations)
     print(f"tiny: {hits} hits over {w.iterations} iterations, worst rel err {worst:.3e}")
     assert hits > 100
+
+
+def test_iterations_tiny_layer_by_layer_top_down(env):
+    """The same iterations with one fg_lookup_prune call per layer instead of the single cooperative fg_top_down launch."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    assert run_workload_parity(torch, w, 8, one_launch_top_down=False)[0] > 0
+    assert run_workload_parity(torch, w, 8, one_launch_top_down=False, fused=True)[0] > 0
 
 
 def test_iterations_tiny_degenerate_settings(env):
