@@ -221,15 +221,18 @@ fg_status_t fg_aggregate(const int32_t* row_start_dev, const int32_t* row_end_de
  * Arguments as for fg_aggregate, with h_src replaced by
  *   src_ids_dev[n_src]              node id of every position of the input layer
  *   table, table_rows, src_stride   the feature table (device, or host memory mapped into the device address space)
- * Equal, up to fp64 rounding of the sums, to fg_gather of the input rows followed by fg_aggregate. The caller
- * still gathers the rows of the layer-1 nodes themselves (fg_gather with normal_ids/normal_pos of layer 1), which
- * fg_linear needs; it does not need the top-down call for layer 0.
+ *   h_self_out, h_self_stride, n_self_rows   optional (NULL to skip): the listed rows' own features, which fg_linear
+ *                                   needs, are copied as well: h_self_out[r, :] = table[src_ids[r], :] for r = rows[k]
+ *                                   (position r of the input layer is the same node as position r of layer 1)
+ * Equal, up to fp64 rounding of the sums, to fg_gather of the input rows followed by fg_aggregate. The top-down
+ * call for layer 0 is not needed with it.
  */
 fg_status_t fg_gather_aggregate(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
                                 int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev,
                                 int64_t max_rows, const int32_t* src_ids_dev, int32_t n_src, const void* table,
                                 int64_t table_rows, int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg,
-                                int64_t agg_stride, fg_dtype_t out_dtype, void* stream);
+                                int64_t agg_stride, fg_dtype_t out_dtype, void* h_self_out, int64_t h_self_stride,
+                                int32_t n_self_rows, void* stream);
 
 /*
  * Dense update of a GraphSAGE-mean layer (phi of Eq. 1; the f_W line of Algorithm 1), for the rows listed:

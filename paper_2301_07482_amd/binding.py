@@ -37,7 +37,8 @@ SIGNATURES = {
     "fg_lookup_prune": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _p, _i64, _i32, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "fg_gather": (_i32, [_p, _i64, _i64, _i64, _p, _p, _p, _i64, _p, _i64, _i64, _i32, _p]),
     "fg_aggregate": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _i32, _p, _i64, _i32, _p]),
-    "fg_gather_aggregate": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _p, _i64, _i64, _i32, _i32, _p, _i64, _i32, _p]),
+    "fg_gather_aggregate": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _p, _i64, _i64, _i32, _i32, _p, _i64, _i32,
+                                   _p, _i64, _i32, _p]),
     "fg_linear": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _p, _i64, _i32, _i32, _p, _i32, _p, _i32, _p, _i32, _i64, _i32, _p]),
     "fg_cache_update": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _f, _p, _i64, _p, _p, _sz, _p]),
 }
@@ -162,10 +163,11 @@ def fg_aggregate(row_start, row_end, col, nnz, n_block_rows, rows, n_rows, max_r
 
 
 def fg_gather_aggregate(row_start, row_end, col, nnz, n_block_rows, rows, n_rows, max_rows, src_ids, n_src, table, table_rows,
-                        src_stride, dim, in_dtype, agg, agg_stride, out_dtype, stream=None):
+                        src_stride, dim, in_dtype, agg, agg_stride, out_dtype, h_self_out=None, h_self_stride=0, n_self_rows=0,
+                        stream=None):
     _check(_lib.fg_gather_aggregate(ptr(row_start), ptr(row_end), ptr(col), nnz, n_block_rows, ptr(rows), ptr(n_rows), max_rows,
                                     ptr(src_ids), n_src, ptr(table), table_rows, src_stride, dim, in_dtype, ptr(agg),
-                                    agg_stride, out_dtype, stream))
+                                    agg_stride, out_dtype, ptr(h_self_out), h_self_stride, n_self_rows, stream))
 
 
 def fg_linear(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows, n_rows, max_rows, d_in, d_out, W, w_dtype, bias, relu,

@@ -116,7 +116,8 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
     const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ col,
     int64_t nnz, int n_block_rows, const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev,
     int64_t max_rows, const char* __restrict__ h_src, int64_t n_src, int64_t src_stride, int pieces, char* __restrict__ agg,
-    int64_t agg_stride, int lanes_log2, const int32_t* __restrict__ src_ids, int n_ids) {
+    int64_t agg_stride, int lanes_log2, const int32_t* __restrict__ src_ids, int n_ids, char* __restrict__ self_out,
+    int64_t self_stride, int n_self) {
     constexpr int PER = Elem<IN>::PER16;
     constexpr int OUT_BYTES = (OUT == FG_F32 ? 4 : 2) * PER;
     extern __shared__ int32_t nb_lds[];  // [groups_per_block][AGG_MAX_STAGE]
@@ -136,9 +137,17 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
             if (s0 < 0 || e0 < s0 || (int64_t)e0 > nnz) e0 = s0 = 0;
         }
         const int deg = e0 - s0;
+        // fused loader: the row's own features (position r of the input layer is the same node) go to self_out[r]
+        const char* self_row = nullptr;
+        if (INDIRECT && self_out && r >= 0 && r < n_ids && r < n_self) {
+            const int32_t v = src_ids[r];
+            if (v >= 0 && v < n_src) self_row = h_src + (int64_t)v * src_stride;
+        }
         for (int p0 = 0; p0 < pieces; p0 += lanes) {
             const int piece = p0 + lane;
             const bool active = piece < pieces;
+            u32x4 self_piece;
+            if (INDIRECT && self_row && active) self_piece = load_piece<true>(self_row + (int64_t)piece * 16);
             double acc[PER];
 #pragma unroll
             for (int i = 0; i < PER; ++i) acc[i] = 0.0;
@@ -179,6 +188,7 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
                 __builtin_amdgcn_wave_barrier();  // the stage is rewritten by the next pass
             }
             if (active) store_row_piece<OUT, PER>(agg + k * agg_stride + (int64_t)piece * OUT_BYTES, acc, (double)deg);
+            if (INDIRECT && self_row && active) *(u32x4*)(self_out + (int64_t)r * self_stride + (int64_t)piece * 16) = self_piece;
         }
     }
 }
@@ -189,7 +199,8 @@ static fg_status_t aggregate_common(const char* who, const int32_t* row_start_de
                                     const int32_t* col_dev, int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev,
                                     const int64_t* n_rows_dev, int64_t max_rows, const void* h_src, int64_t n_src,
                                     int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
-                                    fg_dtype_t out_dtype, const int32_t* src_ids, int32_t n_ids, void* stream) {
+                                    fg_dtype_t out_dtype, const int32_t* src_ids, int32_t n_ids, void* self_out,
+                                    int64_t self_stride, int32_t n_self, void* stream) {
     if (max_rows < 0 || n_block_rows < 0 || n_src < 0 || dim <= 0 || nnz < 0 || n_ids < 0)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (max_rows %lld, n_block_rows %d, n_src %lld, dim %d, nnz %lld)", who,
                 (long long)max_rows, n_block_rows, (long long)n_src, dim, (long long)nnz);
@@ -219,7 +230,8 @@ static fg_status_t aggregate_common(const char* who, const int32_t* row_start_de
 #define FG_AGG_LAUNCH(IN, OUT, IND)                                                                                    \
     hipLaunchKernelGGL((aggregate_mean_kernel<IN, OUT, IND>), dim3((unsigned)blocks), dim3(AGG_THREADS), lds, st,       \
                        row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,          \
-                       (const char*)h_src, n_src, src_stride, pieces, (char*)agg, agg_stride, lg, src_ids, n_ids)
+                       (const char*)h_src, n_src, src_stride, pieces, (char*)agg, agg_stride, lg, src_ids, n_ids,          \
+                       (char*)self_out, self_stride, n_self)
 #define FG_AGG_OUT(IN, IND)                            \
     do {                                               \
         if (out_dtype == FG_F32)                       \
@@ -255,7 +267,8 @@ extern "C" fg_status_t fg_aggregate(const int32_t* row_start_dev, const int32_t*
                                     int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
                                     fg_dtype_t out_dtype, void* stream) {
     return aggregate_common("fg_aggregate", row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev,
-                            max_rows, h_src, n_src, src_stride, dim, in_dtype, agg, agg_stride, out_dtype, nullptr, 0, stream);
+                            max_rows, h_src, n_src, src_stride, dim, in_dtype, agg, agg_stride, out_dtype, nullptr, 0, nullptr, 0,
+                            0, stream);
 }
 
 extern "C" fg_status_t fg_gather_aggregate(const int32_t* row_start_dev, const int32_t* row_end_dev,
@@ -263,9 +276,16 @@ extern "C" fg_status_t fg_gather_aggregate(const int32_t* row_start_dev, const i
                                            const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
                                            const int32_t* src_ids_dev, int32_t n_src, const void* table, int64_t table_rows,
                                            int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg,
-                                           int64_t agg_stride, fg_dtype_t out_dtype, void* stream) {
+                                           int64_t agg_stride, fg_dtype_t out_dtype, void* h_self_out,
+                                           int64_t h_self_stride, int32_t n_self_rows, void* stream) {
     if (max_rows > 0 && !src_ids_dev) FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather_aggregate: src_ids_dev is NULL");
+    if (h_self_out) {
+        if (n_self_rows < 0 || h_self_stride < (int64_t)dim * fg_dtype_size(in_dtype))
+            FG_FAIL(FG_ERR_SHAPE, "fg_gather_aggregate: h_self_out needs n_self_rows >= 0 and a stride of at least one row");
+        if (((uintptr_t)h_self_out | (uintptr_t)h_self_stride) & 15)
+            FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather_aggregate: h_self_out and its stride must be 16-byte aligned");
+    }
     return aggregate_common("fg_gather_aggregate", row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev,
                             n_rows_dev, max_rows, table, table_rows, src_stride, dim, in_dtype, agg, agg_stride, out_dtype,
-                            src_ids_dev, n_src, stream);
+                            src_ids_dev, n_src, h_self_out, h_self_stride, n_self_rows, stream);
 }

@@ -23,12 +23,12 @@ namespace {
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int BN = 64, BK = 32;
-constexpr int LDA = BK + 4;  // floats; keeps 16-byte alignment and spreads rows over banks
+constexpr int BN = 64;
+constexpr int KC = 32;  // k values per fp32 accumulation chunk (one fp64 fold per chunk)
 constexpr int LDB = BN + 4;
 constexpr int LIN_THREADS = 256;
 
-template <int WM>
+template <int WM, int BK>
 __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
@@ -37,8 +37,12 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
     constexpr int BM = 32 * WM;
     constexpr int WN = 4 / WM;          // wavefronts along N
     constexpr int NB = BN / (32 * WN);  // 32-wide MFMA blocks per wavefront
+    constexpr int LDA = BK + 4;  // floats; keeps 16-byte alignment and spreads rows over banks
     constexpr int A_LOADS = BM * BK / 4 / LIN_THREADS;
     constexpr int B_LOADS = BK * BN / 4 / LIN_THREADS;
+    constexpr int A_CHUNKS = BK / 4;                 // 16-byte pieces per A row and step
+    constexpr int A_ROWS = LIN_THREADS / A_CHUNKS;   // rows covered by one pass of the workgroup
+    constexpr int B_ROWS = LIN_THREADS / 16;         // k rows covered by one pass of the workgroup
     __shared__ __attribute__((aligned(16))) float As[BM * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
     __shared__ int32_t row_of[BM];
@@ -68,17 +72,17 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
     __syncthreads();
 
     // this thread's share of the global -> LDS traffic per step
-    const int a_kc = t & 7;   // which 16-byte piece of the 32-wide k step
-    const int a_m = t >> 3;   // rows a_m + 32 i
-    const int b_nc = t & 15;  // which 16-byte piece of the 64-wide n tile
-    const int b_k = t >> 4;   // k rows b_k + 16 i
+    const int a_kc = t % A_CHUNKS;  // which 16-byte piece of the BK-wide k step
+    const int a_m = t / A_CHUNKS;   // rows a_m + A_ROWS i
+    const int b_nc = t & 15;        // which 16-byte piece of the 64-wide n tile
+    const int b_k = t >> 4;         // k rows b_k + B_ROWS i
     // loads are unconditional (dummy address + select) so that the compiler can count the outstanding prefetch
     const float* a_self[A_LOADS];
     const float* a_agg[A_LOADS];
     bool a_ok[A_LOADS];
 #pragma unroll
     for (int i = 0; i < A_LOADS; ++i) {
-        const int m = a_m + 32 * i;
+        const int m = a_m + A_ROWS * i;
         const int32_t r = row_of[m];
         a_ok[i] = r >= 0;
         a_self[i] = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0));
@@ -100,7 +104,7 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
         }
 #pragma unroll
         for (int i = 0; i < B_LOADS; ++i) {
-            const int kb = k0 + b_k + 16 * i;
+            const int kb = k0 + b_k + B_ROWS * i;
             rb[i] = *(const f32x4*)(W + (int64_t)(kb < K ? kb : 0) * d_out + b_col);
         }
     };
@@ -108,10 +112,10 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         const bool ka_ok = k0 + 4 * a_kc < K;
 #pragma unroll
-        for (int i = 0; i < A_LOADS; ++i) *(f32x4*)(As + (a_m + 32 * i) * LDA + 4 * a_kc) = (a_ok[i] && ka_ok) ? ra[i] : z;
+        for (int i = 0; i < A_LOADS; ++i) *(f32x4*)(As + (a_m + A_ROWS * i) * LDA + 4 * a_kc) = (a_ok[i] && ka_ok) ? ra[i] : z;
 #pragma unroll
         for (int i = 0; i < B_LOADS; ++i)
-            *(f32x4*)(Bs + (b_k + 16 * i) * LDB + 4 * b_nc) = (b_col_ok && k0 + b_k + 16 * i < K) ? rb[i] : z;
+            *(f32x4*)(Bs + (b_k + B_ROWS * i) * LDB + 4 * b_nc) = (b_col_ok && k0 + b_k + B_ROWS * i < K) ? rb[i] : z;
     };
 
     const int lane = t & 63, wave = t >> 6;
@@ -132,27 +136,30 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
         load_step((step + 1) * BK);  // beyond K: reads a valid dummy address, zeroed at the LDS store
         // keep the prefetch ahead of the matrix instructions (the scheduler would otherwise sink it next to its use)
         __builtin_amdgcn_sched_barrier(0);
-        f32x4 av[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) av[q] = *(const f32x4*)(As + (wm + l32) * LDA + 16 * half + 4 * q);
-        f32x16 acc[NB];
+        for (int hs = 0; hs < BK / KC; ++hs) {  // one fp32 accumulation chunk of 32 k values at a time
+            f32x4 av[4];
 #pragma unroll
-        for (int b = 0; b < NB; ++b)
+            for (int q = 0; q < 4; ++q) av[q] = *(const f32x4*)(As + (wm + l32) * LDA + KC * hs + 16 * half + 4 * q);
+            f32x16 acc[NB];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
+            for (int b = 0; b < NB; ++b)
 #pragma unroll
-        for (int s = 0; s < 16; ++s) {
-            const float a = av[s >> 2][s & 3];
+                for (int i = 0; i < 16; ++i) acc[b][i] = 0.f;
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                const float bv = Bs[(16 * half + s) * LDB + wn + 32 * b + l32];
-                acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc[b], 0, 0, 0);
+            for (int s = 0; s < 16; ++s) {
+                const float a = av[s >> 2][s & 3];
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    const float bv = Bs[(KC * hs + 16 * half + s) * LDB + wn + 32 * b + l32];
+                    acc[b] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, bv, acc[b], 0, 0, 0);
+                }
             }
+#pragma unroll
+            for (int b = 0; b < NB; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum[b][i] += (double)acc[b][i];
         }
-#pragma unroll
-        for (int b = 0; b < NB; ++b)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sum[b][i] += (double)acc[b][i];
         __syncthreads();
     }
 
@@ -213,11 +220,11 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
         const int64_t m_tiles = fg_ceil_div(max_rows, big ? 128 : 64);
         const unsigned grid = (unsigned)(fg_ceil_div(m_tiles, 8) * 8 * ny);
         if (big)
-            hipLaunchKernelGGL(linear_f32_kernel<4>, dim3(grid), dim3(LIN_THREADS), 0, st, (const char*)h_src, n_src, src_stride,
+            hipLaunchKernelGGL((linear_f32_kernel<4, 32>), dim3(grid), dim3(LIN_THREADS), 0, st, (const char*)h_src, n_src, src_stride,
                                (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, (const float*)W,
                                bias, relu, (char*)h_out, n_out, out_stride, ny);
         else
-            hipLaunchKernelGGL(linear_f32_kernel<2>, dim3(grid), dim3(LIN_THREADS), 0, st, (const char*)h_src, n_src, src_stride,
+            hipLaunchKernelGGL((linear_f32_kernel<2, 32>), dim3(grid), dim3(LIN_THREADS), 0, st, (const char*)h_src, n_src, src_stride,
                                (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, (const float*)W,
                                bias, relu, (char*)h_out, n_out, out_stride, ny);
         FG_LAUNCH_CHECK("linear_f32_kernel");

@@ -168,13 +168,10 @@ class HotPath:
                                   a["row_start_dev"], a["row_end_dev"], a["col_dev"], a["nnz"], a["n_src"], a["live_src_dev"],
                                   a["hit_dev"], a["hit_pos_dev"], a["hit_slot_dev"], a["normal_pos_dev"], a["normal_ids_dev"],
                                   a["counts_dev"], self.ws, self.ws_bytes, st)
-        # ---- loader: raw features of the surviving input nodes (fused: only the layer-1 nodes' own rows)
+        # ---- loader: raw features of the surviving input nodes (fused: done by fg_gather_aggregate below, which also
+        #      copies the layer-1 nodes' own rows into H[0])
         d0b = self.dims[0] * esz[self.feat_code]
-        if fused:
-            tick("gather_self_rows")
-            B.fg_gather(self.feat, self.num_nodes, d0b, d0b, self.self_ids, self.normal_pos[1], self._cnt(1, 2), bt.n[1],
-                        self.H[0], bt.n[0], d0b, self.on_host, st)
-        else:
+        if not fused:
             tick("gather_features")
             B.fg_gather(self.feat, self.num_nodes, d0b, d0b, self.input_ids, self.normal_pos[0], self._cnt(0, 2), bt.n[0],
                         self.H[0], bt.n[0], d0b, self.on_host, st)
@@ -192,7 +189,7 @@ class HotPath:
                 tick("gather_aggregate[1]")
                 B.fg_gather_aggregate(bt.start[1], bt.end[1], bt.col[1], bt.nnz[1], bt.n[1], self.normal_pos[1],
                                       self._cnt(1, 2), bt.n[1], bt.ids[0], bt.n[0], self.feat, self.num_nodes, d0b,
-                                      self.dims[0], in_code, self.AGG, agg_b, self.agg_code, st)
+                                      self.dims[0], in_code, self.AGG, agg_b, self.agg_code, self.H[0], d0b, bt.n[0], st)
             else:
                 tick(f"aggregate[{l}]")
                 B.fg_aggregate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),
