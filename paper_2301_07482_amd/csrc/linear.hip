@@ -181,6 +181,134 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
     }
 }
 
+// ---- panel variant: no barrier and no LDS on the A side (d_in a multiple of 32, a 32-column panel of W <= 64 KB) ------
+//
+//   * a workgroup (8 wavefronts) owns one 32-column panel of W, copies it to LDS once and synchronises once;
+//   * a task is a 32-row block of the output times that panel; the wavefronts of the workgroups that own the
+//     panel take row blocks round-robin and run them independently of each other;
+//   * the A operand needs no LDS: with the k order used here (half-wavefront h takes k = 16h + s) a lane's 16
+//     values of a K step are 64 contiguous bytes of its own row, loaded straight from memory one step ahead into
+//     one of two register buffers. The loads are unconditional, their values are not touched before the matrix
+//     instructions use them, and a scheduling barrier pins them ahead of the current step's matrix instructions:
+//     a branch around a load, a select on its value, or the scheduler sinking it next to its use each turn the
+//     prefetch into a full memory round trip per step. A row past the end reads row 0 instead (rows of a product
+//     are independent and its results are never stored);
+//   * B values are LDS broadcasts of one row of the panel per half-wavefront.
+// Workgroups of the panels that share a row block have ids congruent mod 8 (same XCD): A comes from HBM once and
+// from that XCD's L2 for the other panels.
+constexpr int PL_THREADS = 512;
+constexpr int PL_WAVES = PL_THREADS / 64;
+constexpr int PL_BN = 32;
+
+__global__ __launch_bounds__(PL_THREADS, 4) void linear_f32_panel_kernel(
+    const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
+    const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
+    const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
+    int64_t out_stride, int n_panels, int n_groups) {
+    extern __shared__ __attribute__((aligned(16))) float panel[];  // [K][32]
+    int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
+    if (n_rows > max_rows) n_rows = max_rows;
+    const int K = 2 * d_in;
+    const int nk = K / KC, nk_self = d_in / KC;
+    const int t = threadIdx.x;
+    const int xcd = blockIdx.x & 7;
+    const int j = blockIdx.x >> 3;
+    const int n0 = (j % n_panels) * PL_BN;
+    const int group = (j / n_panels) * 8 + xcd;
+    const int64_t n_blocks = (n_rows + 31) >> 5;
+    if (group >= n_blocks) return;  // uniform over the workgroup, before the barrier
+
+    for (int q = t; q < K * 8; q += PL_THREADS) {
+        const int k = q >> 3, c4 = (q & 7) * 4;
+        const f32x4 v = *(const f32x4*)(W + (int64_t)k * d_out + (n0 + c4 < d_out ? n0 + c4 : 0));
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        *(f32x4*)(panel + k * PL_BN + c4) = n0 + c4 < d_out ? v : z;
+    }
+    __syncthreads();
+
+    const int lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int c = n0 + l32;
+    const double bv = (bias && c < d_out) ? (double)bias[c] : 0.0;
+    const float* bcol = panel + 16 * half * PL_BN + l32;
+
+    // destination / source row of this lane in row block rb (-1: past the end or out of range)
+    auto row_of_block = [&](int64_t rb) -> int32_t {
+        const int64_t g = rb * 32 + l32;
+        int32_t r = -1;
+        if (rb < n_blocks && g < n_rows) {
+            r = rows ? rows[g] : (int32_t)g;
+            if (r < 0 || r >= n_src || r >= n_out) r = -1;
+        }
+        return r;
+    };
+    const int64_t stride = (int64_t)n_groups * PL_WAVES;
+    int64_t rb = group + (int64_t)n_groups * wave;
+    if (rb >= n_blocks) return;
+    int32_t r = row_of_block(rb);
+    int32_t r_next = row_of_block(rb + stride);
+    const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+    const float* a_agg = (const float*)(agg + (r >= 0 ? (rb * 32 + l32) * agg_stride : 0)) + 16 * half;
+    f32x4 a0[4], a1[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(a_self + 4 * q);  // step 0 of the first task
+    for (; rb < n_blocks; rb += stride) {
+        // the row of the task after next is fetched now, and the next task's first K step during this task's last
+        // one, so that the matrix instructions of consecutive tasks follow each other without a memory round trip
+        const int32_t r_after = row_of_block(rb + 2 * stride);
+        double sum[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum[i] = 0.0;
+        auto compute = [&](int step, const f32x4* a) {
+            f32x16 acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+            const float* brow = bcol + step * KC * PL_BN;
+#pragma unroll
+            for (int s = 0; s < 16; ++s)
+                acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[s >> 2][s & 3], brow[s * PL_BN], acc, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum[i] += (double)acc[i];
+        };
+        // nk = 2 * (d_in / 32) is even: both halves of the loop body run unconditionally (a condition around the
+        // second one lets the compiler sink its loads into the conditional block, next to their use)
+        for (int step = 0; step < nk; step += 2) {
+            {
+                const int s1 = step + 1;
+                const float* p = s1 < nk_self ? a_self + s1 * KC : a_agg + (s1 - nk_self) * KC;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a1[q] = *(const f32x4*)(p + 4 * q);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            compute(step, a0);
+            {
+                const int s2 = step + 2;
+                const float* nxt = (const float*)(h_src + (r_next >= 0 ? (int64_t)r_next * src_stride : 0)) + 16 * half;
+                const float* cur = s2 < nk_self ? a_self + s2 * KC : a_agg + (s2 < nk ? s2 - nk_self : 0) * KC;
+                const float* p = s2 < nk ? cur : nxt;  // after the last step: step 0 of the next task (or a valid dummy)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(p + 4 * q);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            compute(step + 1, a1);
+        }
+        // accumulator element i is row 8*(i/4) + 4*half + i%4 of the block, column l32 of the panel
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int m = 8 * (i >> 2) + 4 * half + (i & 3);
+            const int32_t rr = __shfl(r, m, 64);  // lane m (< 32) holds the destination row of block row m; all lanes active
+            if (rr < 0 || c >= d_out) continue;
+            float v = (float)(sum[i] + bv);
+            if (relu) v = v > 0.f ? v : 0.f;
+            *(float*)(h_out + (int64_t)rr * out_stride + (int64_t)c * 4) = v;
+        }
+        r = r_next;
+        r_next = r_after;
+        a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+        a_agg = (const float*)(agg + (r >= 0 ? ((rb + stride) * 32 + l32) * agg_stride : 0)) + 16 * half;
+    }
+}
+
 }  // namespace
 
 fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype,
@@ -214,6 +342,22 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
         fg_clear_error();
         if (max_rows == 0) return FG_OK;
         const int64_t forced = fg_tuning(FG_TUNE_LINEAR_TILE);
+        const size_t panel_bytes = (size_t)2 * d_in * PL_BN * sizeof(float);
+        if (d_in % KC == 0 && panel_bytes <= 64 * 1024 && (forced == 0 || forced == 32)) {
+            const int n_panels = (int)fg_ceil_div(d_out, PL_BN);
+            // two workgroups (of eight wavefronts) per compute unit; 8 * q groups of workgroups, each group holding all panels
+            int q = (2 * 256) / (8 * n_panels);
+            if (q < 1) q = 1;
+            const int64_t blocks32 = fg_ceil_div(max_rows, 32);
+            while (q > 1 && (int64_t)8 * (q - 1) >= blocks32) --q;  // no more groups than row blocks
+            const int n_groups = 8 * q;
+            hipLaunchKernelGGL(linear_f32_panel_kernel, dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), panel_bytes, st,
+                               (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev,
+                               max_rows, d_in, d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels,
+                               n_groups);
+            FG_LAUNCH_CHECK("linear_f32_panel_kernel");
+            return FG_OK;
+        }
         const int ny = (int)fg_ceil_div(d_out, BN);
         // 64-row tiles (four workgroups per compute unit) measured faster than 128-row tiles at every layer size
         const bool big = forced >= 128;
