@@ -167,11 +167,13 @@ def main():
         n_input = float(np.mean([c[0][2] for c in counts]))
         dom_kernel = "gather_rows_kernel<.., true> (fg_gather of the raw features)"
     else:
-        # fused loader + layer-1 mean: per edge of a normal row 4 (col) + 4 (id) + one table row; per normal row
-        # 4 (position) + 8 (start, end) + one mean row written. The edges under normal rows are what is left in the
-        # pruned blocks (rows that are not normal have end = start).
+        # fused loader + layer-1 mean: per edge of a normal row 4 (col) + 4 (id) + one table row read; per normal row
+        # 4 (position) + 8 (start, end) + one mean row written + its own row: 4 (id) + one table row read + one row
+        # written. The edges under normal rows are what is left in the pruned blocks (rows that are not normal have
+        # end = start).
         edges = [float((batches[it].end[1] - batches[it].start[1]).sum().item()) for it in steps_it]
-        gather_bytes = float(np.mean([e * (8 + feat_row) + c[1][2] * (12 + agg_row) for e, c in zip(edges, counts)]))
+        gather_bytes = float(np.mean([e * (8 + feat_row) + c[1][2] * (12 + agg_row + 4 + 2 * feat_row)
+                                      for e, c in zip(edges, counts)]))
         n_input = float(np.mean(edges)) + float(np.mean([c[1][2] for c in counts]))   # table rows read (edges + own rows)
         dom_kernel = "aggregate_mean_kernel<.., true> (fg_gather_aggregate: loader fused with the layer-1 mean)"
     # edges under normal rows of block 1 (host copy of the block and the device-side normal list are both known)
