@@ -193,7 +193,7 @@ def main():
                        frac=gather_bytes / (gather_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, traffic=None,
                        bytes_per_launch=gather_bytes, ms_per_launch=gather_ms)
     lin1_ms = timed_ms["linear[1]"]
-    linear_roof = dict(bound="mfma", kernel="linear_f32_kernel<2> (fg_linear, layer 1, fp32 MFMA)",
+    linear_roof = dict(bound="mfma", kernel="linear_f32_panel_kernel (fg_linear, layer 1, fp32 MFMA)",
                        achieved=lin_flops[1] / (lin1_ms * 1e-3) / 1e12, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
                        frac=lin_flops[1] / (lin1_ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS, traffic=None,
                        flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms)

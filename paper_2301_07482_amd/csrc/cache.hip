@@ -10,7 +10,8 @@
 //
 // Update = 4 launches, no host synchronisation:
 //   1. select_tau    one workgroup: m = live count, k = floor(p_grad*m), radix select (11+11+10 bits on the
-//                    order-preserving integer image of the fp32 norms, keys held in registers) of the norm with rank k
+//                    order-preserving integer image of the fp32 norms) of the norm with rank k; up to 65536
+//                    elements are held in registers after one round of loads, longer lists are streamed per pass
 //   2. classify      check out hits that are not below tau; flag admissible normal nodes; count per workgroup
 //   3. assign_slots  rank admissible nodes in position order (ballot ranks + preceding workgroups' counts),
 //                    hand out ring slots head + rank, write slot_node / slot_stamp / map, list (position, slot);
@@ -173,6 +174,106 @@ __global__ __launch_bounds__(SEL_THREADS) void select_tau_kernel(const uint8_t* 
             if ((kj & 0xFFFFFC00u) == hi) atomicAdd(&hist[kj & 1023u], 1u);
         });
     }
+    __syncthreads();
+    select_bin(hist, red, &s_bin, &s_rank);
+    if (t == 0) {
+        hdr->mode = 1;
+        hdr->tau_key = hi | s_bin;
+    }
+}
+
+// The same selection for up to 4096 * V elements with every key held in registers: one round of loads, all in
+// flight at once, then the three digit passes run from registers. V = 4-key vectors per thread. Needs n >= 4,
+// gnorm aligned to 16 bytes and live (if given) to 4.
+template <int V>
+__global__ __launch_bounds__(SEL_THREADS) void select_tau_reg_kernel(const uint8_t* __restrict__ live,
+                                                                     const float* __restrict__ gnorm, int n, float p_grad,
+                                                                     UpdHeader* __restrict__ hdr, int64_t* __restrict__ stats) {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    __shared__ unsigned int hist[SEL_BINS];
+    __shared__ long long red[16];
+    __shared__ uint32_t s_bin;
+    __shared__ long long s_rank;
+    const int t = threadIdx.x;
+    const int nfull = n >> 2;
+    f4 g[V];
+    uint32_t lv[V];
+#pragma unroll
+    for (int v = 0; v < V; ++v) {  // a vector past the end re-reads vector 0 and is masked below
+        const int q = t + v * SEL_THREADS;
+        const int qc = q < nfull ? q : 0;
+        g[v] = ((const f4*)gnorm)[qc];
+        lv[v] = live ? ((const uint32_t*)live)[qc] : 0x01010101u;
+    }
+    const int jt = (nfull << 2) + t;  // the up to three elements after the last whole vector
+    const bool has_tail = t < 3 && jt < n;
+    const uint32_t tail_key = has_tail ? order_key(gnorm[jt]) : 0u;
+    const bool tail_live = has_tail && (live ? live[jt] != 0 : true);
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
+    uint32_t key[V][4];
+    uint64_t alive = 0;
+#pragma unroll
+    for (int v = 0; v < V; ++v) {
+        const bool in = t + v * SEL_THREADS < nfull;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            key[v][e] = order_key(g[v][e]);
+            if (in && ((lv[v] >> (8 * e)) & 0xFFu)) alive |= 1ull << (4 * v + e);
+        }
+    }
+    __syncthreads();
+    // pass 0: top 11 bits; the histogram total is the live count m
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if ((alive >> (4 * v + e)) & 1ull) atomicAdd(&hist[key[v][e] >> 21], 1u);
+    if (tail_live) atomicAdd(&hist[tail_key >> 21], 1u);
+    __syncthreads();
+    long long c = 0;
+#pragma unroll
+    for (int q = 0; q < SEL_BPT; ++q) c += hist[SEL_BPT * t + q];
+    const long long m = fg_block_sum(c, red);
+    const long long k = (long long)floor((double)p_grad * (double)m);
+    if (t == 0) {
+        hdr->m_live = m;
+        hdr->n_admit = 0;
+        if (stats) stats[0] = stats[1] = stats[2] = stats[3] = 0;
+    }
+    if (k <= 0 || k >= m) {
+        if (t == 0) {
+            hdr->mode = k <= 0 ? 0 : 2;
+            hdr->tau_key = 0;
+        }
+        return;
+    }
+    if (t == 0) s_rank = k;
+    __syncthreads();
+    select_bin(hist, red, &s_bin, &s_rank);
+    const uint32_t d0 = s_bin;
+    // pass 1: middle 11 bits of the keys whose top digit is d0
+    __syncthreads();
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (((alive >> (4 * v + e)) & 1ull) && (key[v][e] >> 21) == d0) atomicAdd(&hist[(key[v][e] >> 10) & 2047u], 1u);
+    if (tail_live && (tail_key >> 21) == d0) atomicAdd(&hist[(tail_key >> 10) & 2047u], 1u);
+    __syncthreads();
+    select_bin(hist, red, &s_bin, &s_rank);
+    const uint32_t hi = (d0 << 21) | (s_bin << 10);
+    // pass 2: low 10 bits of the keys whose upper 22 bits are fixed by now
+    __syncthreads();
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
+    __syncthreads();
+#pragma unroll
+    for (int v = 0; v < V; ++v)
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (((alive >> (4 * v + e)) & 1ull) && (key[v][e] & 0xFFFFFC00u) == hi) atomicAdd(&hist[key[v][e] & 1023u], 1u);
+    if (tail_live && (tail_key & 0xFFFFFC00u) == hi) atomicAdd(&hist[tail_key & 1023u], 1u);
     __syncthreads();
     select_bin(hist, red, &s_bin, &s_rank);
     if (t == 0) {
@@ -493,7 +594,16 @@ extern "C" fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t
     int32_t* apos = (int32_t*)(ws + w.pos);
     int32_t* aslot = (int32_t*)(ws + w.slot);
     CacheRW c{l->map, l->slot_node, l->slot_stamp, l->head + l->head_cur, l->head + (l->head_cur ^ 1), l->capacity, cache->num_nodes, iter, cache->t_stale};
-    hipLaunchKernelGGL(select_tau_kernel, dim3(1), dim3(SEL_THREADS), 0, st, live_dev, gnorm_dev, n, p_grad, hdr, stats_dev);
+    const bool aligned = (((uintptr_t)gnorm_dev & 15) == 0) && (((uintptr_t)live_dev & 3) == 0);
+#define FG_SEL_REG(V) hipLaunchKernelGGL(select_tau_reg_kernel<V>, dim3(1), dim3(SEL_THREADS), 0, st, live_dev, gnorm_dev, n, p_grad, hdr, stats_dev)
+    if (!aligned || n < 4 || n > 16 * 4 * SEL_THREADS)
+        hipLaunchKernelGGL(select_tau_kernel, dim3(1), dim3(SEL_THREADS), 0, st, live_dev, gnorm_dev, n, p_grad, hdr, stats_dev);
+    else if (n <= 1 * 4 * SEL_THREADS) FG_SEL_REG(1);
+    else if (n <= 2 * 4 * SEL_THREADS) FG_SEL_REG(2);
+    else if (n <= 4 * 4 * SEL_THREADS) FG_SEL_REG(4);
+    else if (n <= 8 * 4 * SEL_THREADS) FG_SEL_REG(8);
+    else FG_SEL_REG(16);
+#undef FG_SEL_REG
     FG_LAUNCH_CHECK("select_tau_kernel");
     if (n == 0) return FG_OK;
     const int nb = (int)fg_ceil_div(n, FG_SCAN_BLOCK);

@@ -92,11 +92,11 @@ class HotPath:
         self.ws_bytes = ws_bytes
         self.ws_td_bytes = sum(B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, n[l]) for l in range(L + 1))
         self.ws_td = torch.zeros(self.ws_td_bytes + 256, dtype=torch.uint8, device=dev)
-        # The update of layer l only needs H[l], which is final once its linear has run: it is queued on a second
-        # stream (default priority) and overlaps the layers above; the next iteration waits for it before it
-        # touches the flags and embeddings again.
+        # The update of layer l only needs H[l], which is final once its linear has run: it is queued on a stream
+        # of its own (default priority; the layers' caches are independent) and overlaps the layers above; the
+        # next iteration waits for it before it touches the flags and embeddings again.
         self.overlap_update = overlap_update and L > 1
-        self.side = torch.cuda.Stream(device=dev) if self.overlap_update else None
+        self.side = [torch.cuda.Stream(device=dev) for _ in range(L)] if self.overlap_update else None
         self.ws_upd = [torch.zeros(ws_bytes + 256, dtype=torch.uint8, device=dev) for _ in range(L)] if self.overlap_update else None
         self.upd_done = []
         self.W = {}
@@ -202,14 +202,15 @@ class HotPath:
             if do_update and self.overlap_update and l < L:
                 ready = torch.cuda.Event()
                 ready.record(main)
-                self.side.wait_event(ready)
-                tick(f"cache_update[{l}]", self.side)
+                side = self.side[l]
+                side.wait_event(ready)
+                tick(f"cache_update[{l}]", side)
                 B.fg_cache_update(self.cache, l, it, bt.ids[l], bt.n[l], self.live[l], self.hit[l], bt.gnorm[l],
                                   self.p_grad, self.H[l], out_b, self.stats.data_ptr() + l * 32, self.ws_upd[l],
-                                  self.ws_bytes, self.side.cuda_stream)
-                tick(None, self.side)
+                                  self.ws_bytes, side.cuda_stream)
+                tick(None, side)
                 done = torch.cuda.Event()
-                done.record(self.side)
+                done.record(side)
                 self.upd_done.append(done)
         # ---- update of the caches
         if do_update and not self.overlap_update:

@@ -130,20 +130,26 @@ def test_lookup_prune_matches_oracle(env, n, n_src, max_deg, seed):
         B.fg_cache_destroy(cache)
 
 
-def _device_update(torch, B, cache, i, ids, live, gn, p, rows):
-    """Lookup (no block) followed by the update on the device; returns the hit flags."""
+def _device_update(torch, B, cache, i, ids, live, gn, p, rows, misalign=False):
+    """Lookup (no block) followed by the update on the device; returns the hit flags. `misalign` puts the norms
+    and the liveness flags at addresses that are not multiples of 16 and 4 bytes."""
     n = len(ids)
     wsb = max(B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, n), B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n))
     ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
     t_ids = dev(torch, ids)
     t_live = None if live is None else dev(torch, live.astype(np.uint8))
+    t_gn = dev(torch, gn)
+    if misalign:
+        t_gn = torch.cat([t_gn[:1], t_gn])[1:]
+        t_live = None if t_live is None else torch.cat([t_live[:1], t_live])[1:]
+        assert n == 0 or t_gn.data_ptr() % 16 != 0
     t_hit = torch.zeros(max(n, 1), dtype=torch.uint8, device="cuda")
     t_l = [torch.zeros(max(n, 1), dtype=torch.int32, device="cuda") for _ in range(3)]
     t_cnt = torch.zeros(3, dtype=torch.int64, device="cuda")
     B.fg_lookup_prune(cache, 1, i, t_ids, n, t_live, None, None, None, 0, 0, None, t_hit, t_l[0], t_l[1], t_l[2], None,
                       t_cnt, ws, wsb, None)
     t_stats = torch.zeros(4, dtype=torch.int64, device="cuda")
-    B.fg_cache_update(cache, 1, i, t_ids, n, t_live, t_hit, dev(torch, gn), p, dev(torch, rows), rows.shape[1] * 4, t_stats,
+    B.fg_cache_update(cache, 1, i, t_ids, n, t_live, t_hit, t_gn, p, dev(torch, rows), rows.shape[1] * 4, t_stats,
                       ws, wsb, None)
     return t_hit.cpu().numpy()[:n].astype(bool), t_l[1].cpu().numpy(), t_stats.cpu().numpy().tolist()
 
@@ -271,23 +277,26 @@ def test_linear_matches_oracle(env, d_in, d_out, n_rows, max_rows, relu):
 # ------------------------------------------------------------------------------------------------ fg_cache_update
 
 @pytest.mark.parametrize("cap,t_stale,p,nmax", [(5, 2, 0.5, 12), (64, 4, 0.9, 40), (3, 1, 1.0, 9), (1000, 50, 0.3, 3000),
-                                                (4096, 3, 0.7, 5000)])
+                                                (4096, 3, 0.7, 5000), (5000, 3, 0.3, 16000), (5000, 2, 0.5, 32000),
+                                                (4000, 3, 0.2, 65536), (4500, 2, 0.6, 80000)])
 def test_cache_update_sequences_match_oracle(env, cap, t_stale, p, nmax):
+    # the list lengths span every variant of the threshold selection (registers: 4096 .. 65536 elements, streamed
+    # above that), with a ragged tail, and every fourth update passes misaligned norm and liveness arrays
     torch, B = env
     r = np.random.default_rng(cap + nmax)
-    N, d = 20000 if nmax > 100 else 40, 8
+    N, d = max(20000, 2 * nmax) if nmax > 100 else 40, 8
     oc = O.HistoricalCache(N, cap, d, t_stale)
     cache = B.fg_cache_create(N, [cap], [d], B.FG_F32, t_stale, None)
     from paper_2301_07482_amd.pipeline import _tensor_from_ptr
     try:
         for i in range(25):
-            n = int(r.integers(0, nmax + 1))
+            n = nmax if i == 0 else int(r.integers(nmax // 3 if nmax > 5000 else 0, nmax + 1))
             ids = r.permutation(N)[:n].astype(np.int32)
             live = r.random(n) < 0.8
             gn = np.round(np.exp(r.standard_normal(n)), 1 if nmax < 100 else 3).astype(np.float32)   # ties occur
             rows = r.standard_normal((n, d)).astype(np.float32)
             look = O.lookup_prune(oc, i, ids, live, None, None, None, 0)
-            hit_dev, slots_dev, stats_dev = _device_update(torch, B, cache, i, ids, live, gn, p, rows)
+            hit_dev, slots_dev, stats_dev = _device_update(torch, B, cache, i, ids, live, gn, p, rows, misalign=i % 4 == 3)
             assert np.array_equal(hit_dev, look["hit"])                       # the device lookup sees the same hits
             assert np.array_equal(slots_dev[:len(look["hit_slot"])], look["hit_slot"])
             st = O.cache_update(oc, i, ids, live, look["hit"], gn, p, rows)
