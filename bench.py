@@ -53,6 +53,10 @@ def main():
                     help="materialise every input row with fg_gather and aggregate layer 1 from H0 (separate calls) instead "
                          "of aggregating layer 1 straight from the feature table (fg_gather_aggregate)")
     ap.add_argument("--sample-workers", type=int, default=8)
+    ap.add_argument("--per-layer-update", action="store_true",
+                    help="one fg_cache_update per layer instead of one fg_cache_update_all")
+    ap.add_argument("--bracket-every", type=int, default=5,
+                    help="time the two longest calls with HIP events on every k-th step of the timed region")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy before the warm-up, as the known-size "
                          "reference for scaling hardware traffic counters")
@@ -79,6 +83,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     t0 = time.time()
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse)
+    if args.per_layer_update:
+        hp.update_all = False
     batches = [DeviceBatch(mb, gn) for mb, gn in sampled]
     torch.cuda.synchronize()
     t_setup = time.time() - t0
@@ -97,8 +103,9 @@ def main():
         hp.run(batches[it], it)
     torch.cuda.synchronize()
 
-    # timed region: exactly `steps` iterations. HIP events on the launch stream bracket only the dominant call (the
-    # feature gather) so that the region is not perturbed; the other calls are timed in a separate pass below.
+    # timed region: exactly `steps` iterations. HIP events on the launch stream bracket only the two longest calls,
+    # and only on every `--bracket-every`-th step, so that the region is not perturbed (an event record costs about
+    # 3 us of stream time); the other calls are timed in a separate pass below.
     LOADER = "gather_features" if args.no_fuse else "gather_aggregate[1]"
     BRACKETED = (LOADER, "linear[1]")   # the two longest calls; whichever is longer is reported as `roofline`
     ev = []
@@ -122,7 +129,7 @@ def main():
     for k in range(args.steps):
         it = args.warmup + k
         step_events = {}
-        hp.run(batches[it], it, timer=timer_for(step_events, only=BRACKETED))
+        hp.run(batches[it], it, timer=timer_for(step_events, only=BRACKETED) if k % args.bracket_every == 0 else None)
         ev.append(step_events)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
@@ -156,7 +163,10 @@ def main():
     counts_log = hp.counts_log.cpu().numpy()
     stats_log = hp.stats_log.cpu().numpy()
     steps_it = [args.warmup + k for k in range(args.steps)]
-    counts = [counts_log[it % hp.ring] for it in steps_it]
+    # the roofline figures price the launches that were bracketed: the same steps' counts
+    roof_it = [args.warmup + k for k in range(args.steps) if k % args.bracket_every == 0]
+    counts = [counts_log[it % hp.ring] for it in roof_it]
+    counts_all = [counts_log[it % hp.ring] for it in steps_it]
     esz = {"f32": 4, "f16": 2, "bf16": 2}
     # algorithmic bytes / flops per step, averaged over the timed steps
     feat_row = w.feat_dim * esz[w.feat_dtype]
@@ -171,7 +181,7 @@ def main():
         # 4 (position) + 8 (start, end) + one mean row written + its own row: 4 (id) + one table row read + one row
         # written. The edges under normal rows are what is left in the pruned blocks (rows that are not normal have
         # end = start).
-        edges = [float((batches[it].end[1] - batches[it].start[1]).sum().item()) for it in steps_it]
+        edges = [float((batches[it].end[1] - batches[it].start[1]).sum().item()) for it in roof_it]
         gather_bytes = float(np.mean([e * (8 + feat_row) + c[1][2] * (12 + agg_row + 4 + 2 * feat_row)
                                       for e, c in zip(edges, counts)]))
         n_input = float(np.mean(edges)) + float(np.mean([c[1][2] for c in counts]))   # table rows read (edges + own rows)
@@ -200,7 +210,7 @@ def main():
     # `roofline` is the kernel with the longest launches in the timed region; the other one follows as `roofline_2`
     roofline, roofline_2 = (loader_roof, linear_roof) if gather_ms >= lin1_ms else (linear_roof, loader_roof)
 
-    hits = {l: float(np.mean([c[l][1] for c in counts])) for l in range(1, L)}
+    hits = {l: float(np.mean([c[l][1] for c in counts_all])) for l in range(1, L)}
     n0_all = float(np.mean([batches[it].n[0] for it in steps_it]))
 
     cpu_baseline = None

@@ -6,7 +6,7 @@
  *   top-down   fg_lookup_prune  for layers L, L-1, ..., 1, 0   (cache lookup, pruning, V_normal)
  *   loader     fg_gather        raw features of the surviving input nodes
  *   bottom-up  for l = 1..L:    fg_gather (cached rows of V_cache), fg_aggregate, fg_linear
- *   update     fg_cache_update  for l = 1..L-1
+ *   update     fg_cache_update  for l = 1..L-1   (or fg_cache_update_all once)
  *
  * Conventions
  *   - Every pointer named *_dev or documented "device" is device memory owned by the caller
@@ -267,6 +267,28 @@ fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t iter, cons
                             const uint8_t* live_dev, const uint8_t* hit_dev, const float* gnorm_dev, float p_grad,
                             const void* h_dev, int64_t h_stride, int64_t* stats_dev, void* ws_dev, size_t ws_bytes,
                             void* stream);
+
+/*
+ * The whole last loop of Algorithm 1 ("for l: Update(C^(l), ...)") in one call: the same result as
+ * fg_cache_update for each listed layer (each layer at most once, at most 8), with the launches shared by the
+ * layers. Fields of a layer as in fg_cache_update; p_grad and iter are common.
+ *   ws_dev, ws_bytes    device workspace, >= the sum over the listed layers of
+ *                       fg_workspace_bytes(FG_WS_CACHE_UPDATE, layers[i].n, 0); 16-byte aligned
+ * Nothing is launched if any layer's arguments are rejected.
+ */
+typedef struct fg_update_layer {
+    int32_t layer;
+    int32_t n;
+    const int32_t* ids_dev;
+    const uint8_t* live_dev;
+    const uint8_t* hit_dev;
+    const float* gnorm_dev;
+    const void* h_dev;
+    int64_t h_stride;
+    int64_t* stats_dev;
+} fg_update_layer_t;
+fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, float p_grad, int32_t n_layers,
+                                const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -54,6 +54,16 @@ class TopDownLayer(C.Structure):
 SIGNATURES["fg_top_down_workspace_bytes"] = (_sz, [_i32, C.POINTER(TopDownLayer)])
 SIGNATURES["fg_top_down"] = (_i32, [_p, _i64, _i32, C.POINTER(TopDownLayer), _p, _sz, _p])
 
+
+
+class UpdateLayer(C.Structure):
+    """fg_update_layer_t"""
+    _fields_ = [("layer", _i32), ("n", _i32), ("ids_dev", _p), ("live_dev", _p), ("hit_dev", _p), ("gnorm_dev", _p),
+                ("h_dev", _p), ("h_stride", _i64), ("stats_dev", _p)]
+
+
+SIGNATURES["fg_cache_update_all"] = (_i32, [_p, _i64, _f, _i32, C.POINTER(UpdateLayer), _p, _sz, _p])
+
 for _name, (_res, _args) in SIGNATURES.items():
     _fn = getattr(_lib, _name)
     _fn.restype, _fn.argtypes = _res, _args
@@ -179,3 +189,17 @@ def fg_linear(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows, n_rows,
 def fg_cache_update(cache, layer, it, ids, n, live, hit, gnorm, p_grad, h, h_stride, stats, ws, ws_bytes, stream=None):
     _check(_lib.fg_cache_update(cache, layer, it, ptr(ids), n, ptr(live), ptr(hit), ptr(gnorm), p_grad, ptr(h), h_stride,
                                 ptr(stats), ptr(ws), ws_bytes, stream))
+
+
+def update_layers(specs):
+    """ctypes array of fg_update_layer_t from dicts keyed by the field names (tensors or addresses for pointers)."""
+    arr = (UpdateLayer * len(specs))()
+    for a, spec in zip(arr, specs):
+        for name, ctype in UpdateLayer._fields_:
+            v = spec.get(name)
+            setattr(a, name, ptr(v) if ctype is _p else (0 if v is None else v))
+    return arr
+
+
+def fg_cache_update_all(cache, it, p_grad, layers, ws, ws_bytes, stream=None):
+    _check(_lib.fg_cache_update_all(cache, it, p_grad, len(layers), layers, ptr(ws), ws_bytes, stream))

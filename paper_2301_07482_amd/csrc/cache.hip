@@ -2,27 +2,32 @@
 // admission and check-out by gradient norm, Section 4.1.1; staleness bound, Section 4.1.2).
 //
 // State per cached layer, all in HBM: map[num_nodes] (slot of a node or -1), table[capacity x dim],
-// slot_node[capacity], slot_stamp[capacity], head. A node v is usable at iteration i iff
+// slot_node[capacity], slot_stamp[capacity], head, and 16 KB of selection scratch. A node v is usable at
+// iteration i iff
 //   s = map[v] >= 0, slot_node[s] == v and 1 <= i - slot_stamp[s] <= t_stale.
 // The back-pointer test makes every location single-writer during an update: admitting into a slot never
 // touches the previous owner's map entry, a check-out only writes the node's own map entry, and the slots
 // handed out in one update are distinct. The result is therefore the same as the sequential procedure.
 //
-// Update = 4 launches, no host synchronisation:
-//   1. select_tau    one workgroup: m = live count, k = floor(p_grad*m), radix select (11+11+10 bits on the
-//                    order-preserving integer image of the fp32 norms) of the norm with rank k; up to 65536
-//                    elements are held in registers after one round of loads, longer lists are streamed per pass
-//   2. classify      check out hits that are not below tau; flag admissible normal nodes; count per workgroup
-//   3. assign_slots  rank admissible nodes in position order (ballot ranks + preceding workgroups' counts),
+// Update = 5 launches for any number of layers (a workgroup finds its layer from its index), no host
+// synchronisation and no waiting between workgroups:
+//   1. digit 0       histogram of the top 11 bits of the order-preserving integer image of the live nodes' norms
+//   2. digit 1       every workgroup derives m, k = floor(p_grad*m) and the first digit of the norm of rank k from
+//                    the finished histogram, then histograms the next 11 bits of its keys that carry that digit
+//                    and appends those keys to the layer's survivor list
+//   3. classify      every workgroup finishes the selection (second digit from the histogram, last 10 bits from
+//                    the survivor list): tau, exactly. Then: check out hits that are not below tau; flag
+//                    admissible normal nodes; count per workgroup
+//   4. assign_slots  rank admissible nodes in position order (ballot ranks + preceding workgroups' counts),
 //                    hand out ring slots head + rank, write slot_node / slot_stamp / map, list (position, slot);
 //                    the last workgroup leaves the advanced header in the spare header cell
-//   4. row copy      table[slot] = h[position] (the gather kernel)
+//   5. row copy      table[slot] = h[position]
 #include "common.h"
 #include "scan.h"
 
 namespace {
 
-struct UpdHeader {        // lives at the start of the update workspace
+struct UpdHeader {        // lives at the start of a layer's update workspace
     uint32_t tau_key;     // order-preserving key of tau
     int32_t mode;         // 0: nothing is below tau, 1: compare with tau_key, 2: everything is below tau
     int64_t n_admit;      // rows to copy (<= capacity)
@@ -34,15 +39,66 @@ __device__ __forceinline__ uint32_t order_key(float f) {
     return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-// Exact rank-k selection by one workgroup: three radix passes (11, 11 and 10 bits, most significant first)
-// over the order-preserving keys. A pass builds a histogram of the keys that match the digits found so far
-// with LDS atomics and finds the bin that contains the wanted rank with a workgroup scan. The first two passes
-// stream the norms from memory (a few hundred KB, L2-resident after the first); the keys that survive the
-// first digit are parked in LDS for the last pass (if they do not fit, the last pass streams as well).
 constexpr int SEL_THREADS = 1024;
 constexpr int SEL_BINS = 2048;
 constexpr int SEL_BPT = SEL_BINS / SEL_THREADS;  // bins owned by a thread in the scan
-constexpr int SEL_PARK = 8192;                   // survivors kept in LDS
+constexpr int SEL_CHUNK = 4 * SEL_THREADS;       // keys per workgroup in the histogram launches
+constexpr int FG_MAX_UPD_LAYERS = 8;
+
+// Selection scratch of a layer, owned by the cache. All-zero between updates: launch 4 clears it again.
+struct SelState {
+    unsigned int hist0[SEL_BINS];
+    unsigned int hist1[SEL_BINS];
+    unsigned int n_surv;
+    unsigned int pad[3];
+};
+
+struct CacheRW {
+    int32_t* map;
+    int32_t* slot_node;
+    int32_t* slot_stamp;
+    const int64_t* head;  // current ring header
+    int64_t* head_next;   // where an update leaves the advanced header (the two swap roles after every update)
+    int64_t capacity;
+    int64_t num_nodes;
+    int64_t iter;
+    int32_t t_stale;
+};
+
+struct UpdLayer {
+    CacheRW c;
+    const int32_t* ids;
+    const uint8_t* live;
+    const uint8_t* hit;
+    const float* gnorm;
+    int64_t* stats;
+    SelState* sel;
+    UpdHeader* hdr;
+    uint8_t* flag;       // admissible or not, per position
+    int32_t* blk;        // admissible per workgroup of launch 3
+    int32_t* apos;       // admitted positions; before launch 4 the same memory holds the survivor keys
+    int32_t* aslot;      // their slots
+    const char* h;
+    int64_t h_stride;
+    char* table;
+    int64_t row_bytes;
+    int32_t n;
+    float p_grad;
+};
+
+struct UpdBatch {
+    int32_t n_layers;
+    int32_t sel_first[FG_MAX_UPD_LAYERS + 1];   // first workgroup of each layer in launches 1 and 2
+    int32_t scan_first[FG_MAX_UPD_LAYERS + 1];  // the same for launches 3 and 4
+    UpdLayer l[FG_MAX_UPD_LAYERS];
+};
+
+__device__ __forceinline__ int layer_of_block(const int32_t* first, int n_layers, int b, int& local) {
+    int l = 0;
+    while (l + 1 < n_layers && b >= first[l + 1]) ++l;
+    local = b - first[l];
+    return l;
+}
 
 // Finds the bin holding rank *s_rank in hist[] (counts), stores it in *s_bin and rebases *s_rank to that bin.
 __device__ __forceinline__ void select_bin(const unsigned int* hist, long long* red, uint32_t* s_bin, long long* s_rank) {
@@ -80,231 +136,148 @@ __device__ __forceinline__ void select_bin(const unsigned int* hist, long long* 
     __syncthreads();
 }
 
-// Calls f(key) for every live element, reading the norms 4 at a time (8 loads in flight per thread) when the
-// arrays are suitably aligned; element order is irrelevant to the callers (they only count).
+// Calls f(key) for every live element of chunk `chunk` (SEL_CHUNK elements), reading the norms 4 at a time when
+// the arrays are suitably aligned; element order is irrelevant to the callers (they only count).
 template <typename F>
-__device__ __forceinline__ void for_each_live_key(const uint8_t* __restrict__ live, const float* __restrict__ gnorm, int n, F f) {
+__device__ __forceinline__ void for_each_live_key(const uint8_t* __restrict__ live, const float* __restrict__ gnorm, int n,
+                                                  int chunk, F f) {
     const int t = threadIdx.x;
+    const int begin = chunk * SEL_CHUNK;
+    const int len = n - begin < SEL_CHUNK ? n - begin : SEL_CHUNK;
+    if (len <= 0) return;
+    gnorm += begin;
+    if (live) live += begin;
     const bool vec = (((uintptr_t)gnorm & 15) == 0) && (!live || ((uintptr_t)live & 3) == 0);
     int done = 0;
     if (vec) {
         typedef float f4 __attribute__((ext_vector_type(4)));
-        const int n4 = n >> 2;
-        for (int q0 = t; q0 < n4; q0 += 2 * SEL_THREADS) {
-            const int q1 = q0 + SEL_THREADS;
-            const bool has1 = q1 < n4;
-            const f4 g0 = ((const f4*)gnorm)[q0];
-            const f4 g1 = has1 ? ((const f4*)gnorm)[q1] : g0;
-            const uint32_t l0 = live ? ((const uint32_t*)live)[q0] : 0x01010101u;
-            const uint32_t l1 = live ? (has1 ? ((const uint32_t*)live)[q1] : 0u) : (has1 ? 0x01010101u : 0u);
+        const int n4 = len >> 2;
+        if (t < n4) {  // SEL_CHUNK = 4 * SEL_THREADS: one vector per thread
+            const f4 g = ((const f4*)gnorm)[t];
+            const uint32_t l4 = live ? ((const uint32_t*)live)[t] : 0x01010101u;
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                if ((l0 >> (8 * e)) & 0xFFu) f(order_key(g0[e]));
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                if ((l1 >> (8 * e)) & 0xFFu) f(order_key(g1[e]));
+                if ((l4 >> (8 * e)) & 0xFFu) f(order_key(g[e]));
         }
         done = n4 << 2;
     }
-    for (int j = done + t; j < n; j += SEL_THREADS)
+    for (int j = done + t; j < len; j += SEL_THREADS)
         if (live ? live[j] != 0 : true) f(order_key(gnorm[j]));
 }
 
-__global__ __launch_bounds__(SEL_THREADS) void select_tau_kernel(const uint8_t* __restrict__ live,
-                                                                 const float* __restrict__ gnorm, int n, float p_grad,
-                                                                 UpdHeader* __restrict__ hdr, int64_t* __restrict__ stats) {
+// From the finished first histogram: m (live count), k = floor(p_grad * m) and, unless k is degenerate, the first
+// digit d0 of the key of rank k; *s_rank is left holding the rank among the keys with that digit. Returns the
+// mode (0: nothing is below tau, 2: everything is, 1: tau has to be found). Every thread gets the same values.
+__device__ __forceinline__ int first_digit(const SelState* __restrict__ S, float p_grad, unsigned int* hist, long long* red,
+                                           uint32_t* s_bin, long long* s_rank, uint32_t& d0, long long& m) {
+    const int t = threadIdx.x;
+    __syncthreads();
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = S->hist0[b];
+    __syncthreads();
+    long long c = 0;
+#pragma unroll
+    for (int q = 0; q < SEL_BPT; ++q) c += hist[SEL_BPT * t + q];
+    m = fg_block_sum(c, red);
+    const long long k = (long long)floor((double)p_grad * (double)m);
+    d0 = 0;
+    if (k <= 0) return 0;
+    if (k >= m) return 2;
+    if (t == 0) *s_rank = k;
+    __syncthreads();
+    select_bin(hist, red, s_bin, s_rank);
+    d0 = *s_bin;
+    return 1;
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void update_digit0_kernel(UpdBatch B) {
     __shared__ unsigned int hist[SEL_BINS];
-    __shared__ uint32_t park[SEL_PARK];
+    int chunk;
+    const UpdLayer& L = B.l[layer_of_block(B.sel_first, B.n_layers, blockIdx.x, chunk)];
+    const int t = threadIdx.x;
+    if (chunk == 0 && t == 0 && L.stats) L.stats[0] = L.stats[1] = L.stats[2] = L.stats[3] = 0;
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
+    __syncthreads();
+    for_each_live_key(L.live, L.gnorm, L.n, chunk, [&](uint32_t kj) { atomicAdd(&hist[kj >> 21], 1u); });
+    __syncthreads();
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS)
+        if (hist[b]) atomicAdd(&L.sel->hist0[b], hist[b]);
+}
+
+__global__ __launch_bounds__(SEL_THREADS) void update_digit1_kernel(UpdBatch B) {
+    __shared__ unsigned int hist[SEL_BINS];
+    __shared__ uint32_t park[SEL_CHUNK];
     __shared__ long long red[16];
     __shared__ uint32_t s_bin;
     __shared__ long long s_rank;
-    __shared__ unsigned int s_parked;
+    __shared__ unsigned int s_parked, s_base;
+    int chunk;
+    const UpdLayer& L = B.l[layer_of_block(B.sel_first, B.n_layers, blockIdx.x, chunk)];
     const int t = threadIdx.x;
-    // pass 0: top 11 bits of every live key; the histogram total is the live count m
+    uint32_t d0;
+    long long m;
+    if (first_digit(L.sel, L.p_grad, hist, red, &s_bin, &s_rank, d0, m) != 1) return;  // uniform over the layer
     for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
     if (t == 0) s_parked = 0;
     __syncthreads();
-    for_each_live_key(live, gnorm, n, [&](uint32_t kj) { atomicAdd(&hist[kj >> 21], 1u); });
-    __syncthreads();
-    long long c = 0;
-#pragma unroll
-    for (int q = 0; q < SEL_BPT; ++q) c += hist[SEL_BPT * t + q];
-    const long long m = fg_block_sum(c, red);
-    const long long k = (long long)floor((double)p_grad * (double)m);
-    if (t == 0) {
-        hdr->m_live = m;
-        hdr->n_admit = 0;
-        if (stats) stats[0] = stats[1] = stats[2] = stats[3] = 0;
-    }
-    if (k <= 0 || k >= m) {
-        if (t == 0) {
-            hdr->mode = k <= 0 ? 0 : 2;
-            hdr->tau_key = 0;
-        }
-        return;
-    }
-    if (t == 0) s_rank = k;
-    __syncthreads();
-    select_bin(hist, red, &s_bin, &s_rank);
-    const uint32_t d0 = s_bin;
-    // pass 1: middle 11 bits of the keys whose top digit is d0; park those keys in LDS
-    __syncthreads();
-    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
-    __syncthreads();
-    for_each_live_key(live, gnorm, n, [&](uint32_t kj) {
+    for_each_live_key(L.live, L.gnorm, L.n, chunk, [&](uint32_t kj) {
         if ((kj >> 21) != d0) return;
         atomicAdd(&hist[(kj >> 10) & 2047u], 1u);
-        const unsigned int at = atomicAdd(&s_parked, 1u);
-        if (at < SEL_PARK) park[at] = kj;
+        park[atomicAdd(&s_parked, 1u)] = kj;  // a workgroup sees at most SEL_CHUNK keys
     });
     __syncthreads();
-    select_bin(hist, red, &s_bin, &s_rank);
-    const uint32_t d1 = s_bin;
-    const uint32_t hi = (d0 << 21) | (d1 << 10);
     const unsigned int parked = s_parked;
-    // pass 2: low 10 bits of the keys whose upper 22 bits are (d0, d1)
+    if (t == 0 && parked) s_base = atomicAdd(&L.sel->n_surv, parked);
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS)
+        if (hist[b]) atomicAdd(&L.sel->hist1[b], hist[b]);
     __syncthreads();
-    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
-    __syncthreads();
-    if (parked <= SEL_PARK) {
-        for (unsigned int i = t; i < parked; i += SEL_THREADS)
-            if ((park[i] & 0xFFFFFC00u) == hi) atomicAdd(&hist[park[i] & 1023u], 1u);
-    } else {
-        for_each_live_key(live, gnorm, n, [&](uint32_t kj) {
-            if ((kj & 0xFFFFFC00u) == hi) atomicAdd(&hist[kj & 1023u], 1u);
-        });
-    }
-    __syncthreads();
-    select_bin(hist, red, &s_bin, &s_rank);
-    if (t == 0) {
-        hdr->mode = 1;
-        hdr->tau_key = hi | s_bin;
-    }
+    uint32_t* survivors = (uint32_t*)L.apos;  // at most n keys in all
+    for (unsigned int i = t; i < parked; i += SEL_THREADS) survivors[s_base + i] = park[i];
 }
 
-// The same selection for up to 4096 * V elements with every key held in registers: one round of loads, all in
-// flight at once, then the three digit passes run from registers. V = 4-key vectors per thread. Needs n >= 4,
-// gnorm aligned to 16 bytes and live (if given) to 4.
-template <int V>
-__global__ __launch_bounds__(SEL_THREADS) void select_tau_reg_kernel(const uint8_t* __restrict__ live,
-                                                                     const float* __restrict__ gnorm, int n, float p_grad,
-                                                                     UpdHeader* __restrict__ hdr, int64_t* __restrict__ stats) {
-    typedef float f4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void classify_update_kernel(UpdBatch B) {
+    static_assert(FG_SCAN_BLOCK == SEL_THREADS, "the selection helpers assume this workgroup size");
     __shared__ unsigned int hist[SEL_BINS];
     __shared__ long long red[16];
     __shared__ uint32_t s_bin;
     __shared__ long long s_rank;
+    int local;
+    const UpdLayer& L = B.l[layer_of_block(B.scan_first, B.n_layers, blockIdx.x, local)];
+    const CacheRW& c = L.c;
     const int t = threadIdx.x;
-    const int nfull = n >> 2;
-    f4 g[V];
-    uint32_t lv[V];
-#pragma unroll
-    for (int v = 0; v < V; ++v) {  // a vector past the end re-reads vector 0 and is masked below
-        const int q = t + v * SEL_THREADS;
-        const int qc = q < nfull ? q : 0;
-        g[v] = ((const f4*)gnorm)[qc];
-        lv[v] = live ? ((const uint32_t*)live)[qc] : 0x01010101u;
-    }
-    const int jt = (nfull << 2) + t;  // the up to three elements after the last whole vector
-    const bool has_tail = t < 3 && jt < n;
-    const uint32_t tail_key = has_tail ? order_key(gnorm[jt]) : 0u;
-    const bool tail_live = has_tail && (live ? live[jt] != 0 : true);
-    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
-    uint32_t key[V][4];
-    uint64_t alive = 0;
-#pragma unroll
-    for (int v = 0; v < V; ++v) {
-        const bool in = t + v * SEL_THREADS < nfull;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            key[v][e] = order_key(g[v][e]);
-            if (in && ((lv[v] >> (8 * e)) & 0xFFu)) alive |= 1ull << (4 * v + e);
+    // the rest of the selection, the same in every workgroup of the layer
+    uint32_t d0, tau_key = 0;
+    long long m;
+    const int mode = first_digit(L.sel, L.p_grad, hist, red, &s_bin, &s_rank, d0, m);
+    if (mode == 1) {
+        __syncthreads();
+        for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = L.sel->hist1[b];
+        __syncthreads();
+        select_bin(hist, red, &s_bin, &s_rank);
+        const uint32_t hi = (d0 << 21) | (s_bin << 10);
+        __syncthreads();
+        for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
+        __syncthreads();
+        const unsigned int n_surv = L.sel->n_surv;
+        const uint32_t* survivors = (const uint32_t*)L.apos;
+        for (unsigned int i = t; i < n_surv; i += SEL_THREADS) {
+            const uint32_t kj = survivors[i];
+            if ((kj & 0xFFFFFC00u) == hi) atomicAdd(&hist[kj & 1023u], 1u);
         }
+        __syncthreads();
+        select_bin(hist, red, &s_bin, &s_rank);
+        tau_key = hi | s_bin;
     }
-    __syncthreads();
-    // pass 0: top 11 bits; the histogram total is the live count m
-#pragma unroll
-    for (int v = 0; v < V; ++v)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if ((alive >> (4 * v + e)) & 1ull) atomicAdd(&hist[key[v][e] >> 21], 1u);
-    if (tail_live) atomicAdd(&hist[tail_key >> 21], 1u);
-    __syncthreads();
-    long long c = 0;
-#pragma unroll
-    for (int q = 0; q < SEL_BPT; ++q) c += hist[SEL_BPT * t + q];
-    const long long m = fg_block_sum(c, red);
-    const long long k = (long long)floor((double)p_grad * (double)m);
-    if (t == 0) {
-        hdr->m_live = m;
-        hdr->n_admit = 0;
-        if (stats) stats[0] = stats[1] = stats[2] = stats[3] = 0;
+    if (local == 0 && t == 0) {
+        L.hdr->mode = mode;
+        L.hdr->tau_key = tau_key;
+        L.hdr->m_live = m;
     }
-    if (k <= 0 || k >= m) {
-        if (t == 0) {
-            hdr->mode = k <= 0 ? 0 : 2;
-            hdr->tau_key = 0;
-        }
-        return;
-    }
-    if (t == 0) s_rank = k;
-    __syncthreads();
-    select_bin(hist, red, &s_bin, &s_rank);
-    const uint32_t d0 = s_bin;
-    // pass 1: middle 11 bits of the keys whose top digit is d0
-    __syncthreads();
-    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
-    __syncthreads();
-#pragma unroll
-    for (int v = 0; v < V; ++v)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (((alive >> (4 * v + e)) & 1ull) && (key[v][e] >> 21) == d0) atomicAdd(&hist[(key[v][e] >> 10) & 2047u], 1u);
-    if (tail_live && (tail_key >> 21) == d0) atomicAdd(&hist[(tail_key >> 10) & 2047u], 1u);
-    __syncthreads();
-    select_bin(hist, red, &s_bin, &s_rank);
-    const uint32_t hi = (d0 << 21) | (s_bin << 10);
-    // pass 2: low 10 bits of the keys whose upper 22 bits are fixed by now
-    __syncthreads();
-    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
-    __syncthreads();
-#pragma unroll
-    for (int v = 0; v < V; ++v)
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (((alive >> (4 * v + e)) & 1ull) && (key[v][e] & 0xFFFFFC00u) == hi) atomicAdd(&hist[key[v][e] & 1023u], 1u);
-    if (tail_live && (tail_key & 0xFFFFFC00u) == hi) atomicAdd(&hist[tail_key & 1023u], 1u);
-    __syncthreads();
-    select_bin(hist, red, &s_bin, &s_rank);
-    if (t == 0) {
-        hdr->mode = 1;
-        hdr->tau_key = hi | s_bin;
-    }
-}
-
-struct CacheRW {
-    int32_t* map;
-    int32_t* slot_node;
-    int32_t* slot_stamp;
-    const int64_t* head;  // current ring header
-    int64_t* head_next;   // where an update leaves the advanced header (the two swap roles after every update)
-    int64_t capacity;
-    int64_t num_nodes;
-    int64_t iter;
-    int32_t t_stale;
-};
-
-__global__ __launch_bounds__(FG_SCAN_BLOCK) void classify_update_kernel(
-    CacheRW c, const int32_t* __restrict__ ids, int n, const uint8_t* __restrict__ live,
-    const uint8_t* __restrict__ hit, const float* __restrict__ gnorm, const UpdHeader* __restrict__ hdr,
-    uint8_t* __restrict__ admit_flag, int32_t* __restrict__ blk_counts, int64_t* __restrict__ stats) {
-    const int j = blockIdx.x * FG_SCAN_BLOCK + threadIdx.x;
+    const int j = local * FG_SCAN_BLOCK + t;
     bool admit = false, evict = false;
-    if (j < n && (live ? live[j] != 0 : true)) {
-        const int mode = hdr->mode;
-        const bool low = mode == 2 || (mode == 1 && order_key(gnorm[j]) < hdr->tau_key);
-        const bool is_hit = hit[j] != 0;
-        const int32_t v = ids[j];
+    if (j < L.n && (L.live ? L.live[j] != 0 : true)) {
+        const bool low = mode == 2 || (mode == 1 && order_key(L.gnorm[j]) < tau_key);
+        const bool is_hit = L.hit[j] != 0;
+        const int32_t v = L.ids[j];
         const bool v_ok = v >= 0 && v < c.num_nodes;
         if (is_hit && !low && v_ok) {
             c.map[v] = -1;
@@ -312,33 +285,37 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void classify_update_kernel(
         }
         admit = !is_hit && low && v_ok;
     }
-    if (j < n) admit_flag[j] = admit ? 1 : 0;
+    if (j < L.n) L.flag[j] = admit ? 1 : 0;
     const int n_admit = __syncthreads_count(admit);
     const int n_evict = __syncthreads_count(evict);
-    if (threadIdx.x == 0) {
-        blk_counts[blockIdx.x] = n_admit;
-        if (stats && n_evict) atomicAdd((unsigned long long*)&stats[1], (unsigned long long)n_evict);
+    if (t == 0) {
+        L.blk[local] = n_admit;
+        if (L.stats && n_evict) atomicAdd((unsigned long long*)&L.stats[1], (unsigned long long)n_evict);
     }
 }
 
-__global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(
-    CacheRW c, const int32_t* __restrict__ ids, int n, const uint8_t* __restrict__ admit_flag,
-    const int32_t* __restrict__ blk_counts, UpdHeader* __restrict__ hdr, int32_t* __restrict__ admit_pos,
-    int32_t* __restrict__ admit_slot, int64_t* __restrict__ stats) {
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(UpdBatch B) {
     __shared__ long long red[16];
     __shared__ int sc[17];
+    int local;
+    const int layer = layer_of_block(B.scan_first, B.n_layers, blockIdx.x, local);
+    const UpdLayer& L = B.l[layer];
+    const CacheRW& c = L.c;
+    const int n_local = B.scan_first[layer + 1] - B.scan_first[layer];
+    if (local == 0)  // every workgroup of the layer has used the selection scratch in the previous launch
+        for (int i = threadIdx.x; i < (int)(sizeof(SelState) / 4); i += FG_SCAN_BLOCK) ((unsigned int*)L.sel)[i] = 0;
     long long before = 0;
-    for (int b = threadIdx.x; b < (int)blockIdx.x; b += FG_SCAN_BLOCK) before += blk_counts[b];
+    for (int b = threadIdx.x; b < local; b += FG_SCAN_BLOCK) before += L.blk[b];
     before = fg_block_sum(before, red);
-    const int j = blockIdx.x * FG_SCAN_BLOCK + threadIdx.x;
-    const bool admit = j < n && admit_flag[j] != 0;
+    const int j = local * FG_SCAN_BLOCK + threadIdx.x;
+    const bool admit = j < L.n && L.flag[j] != 0;
     int total;
     const long long rank = before + fg_block_rank(admit, total, sc);
     bool overwrote = false;
     if (admit && rank < c.capacity) {
         const int64_t head = *c.head;
         const int32_t s = (int32_t)((head + rank) % c.capacity);
-        const int32_t v = ids[j];
+        const int32_t v = L.ids[j];
         const int32_t old = c.slot_node[s];
         if (old >= 0 && old < c.num_nodes && c.map[old] == s) {
             const int64_t age = c.iter + 1 - (int64_t)c.slot_stamp[s];
@@ -347,21 +324,52 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(
         c.slot_node[s] = v;
         c.slot_stamp[s] = (int32_t)c.iter;
         c.map[v] = s;
-        admit_pos[rank] = j;
-        admit_slot[rank] = s;
+        L.apos[rank] = j;
+        L.aslot[rank] = s;
     }
     const int n_over = __syncthreads_count(overwrote);
     if (threadIdx.x == 0) {
-        if (stats && n_over) atomicAdd((unsigned long long*)&stats[2], (unsigned long long)n_over);
-        if (blockIdx.x == gridDim.x - 1) {
+        if (L.stats && n_over) atomicAdd((unsigned long long*)&L.stats[2], (unsigned long long)n_over);
+        if (local == n_local - 1) {
             const long long all = before + total;
             const long long in = all < c.capacity ? all : c.capacity;
-            hdr->n_admit = in;
+            L.hdr->n_admit = in;
             *c.head_next = (*c.head + in) % c.capacity;
-            if (stats) {
-                stats[0] = in;
-                stats[3] = all - in;
+            if (L.stats) {
+                L.stats[0] = in;
+                L.stats[3] = all - in;
             }
+        }
+    }
+}
+
+// table[aslot[k], :] = h[apos[k], :] for the admitted rows of every layer: blockIdx.y is the layer, a wavefront
+// copies a row in 16-byte pieces, two rows in flight.
+constexpr int COPY_THREADS = 256;
+__global__ __launch_bounds__(COPY_THREADS) void copy_admitted_rows_kernel(UpdBatch B) {
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const UpdLayer& L = B.l[blockIdx.y];
+    const int64_t count = L.hdr->n_admit;
+    const int chunks = (int)(L.row_bytes >> 4);
+    const int lane = threadIdx.x & 63;
+    const int64_t wave = ((int64_t)blockIdx.x * COPY_THREADS + threadIdx.x) >> 6;
+    const int64_t n_waves = ((int64_t)gridDim.x * COPY_THREADS) >> 6;
+    for (int64_t k0 = wave; k0 < count; k0 += 2 * n_waves) {
+        const int64_t k1 = k0 + n_waves;
+        const bool has1 = k1 < count;
+        const int32_t p0 = L.apos[k0], s0 = L.aslot[k0];
+        const int32_t p1 = has1 ? L.apos[k1] : p0, s1 = has1 ? L.aslot[k1] : s0;
+        const bool ok0 = p0 >= 0 && p0 < L.n && s0 >= 0 && s0 < L.c.capacity;
+        const bool ok1 = has1 && p1 >= 0 && p1 < L.n && s1 >= 0 && s1 < L.c.capacity;
+        const u32x4* a0 = (const u32x4*)(L.h + (int64_t)(ok0 ? p0 : 0) * L.h_stride);
+        const u32x4* a1 = (const u32x4*)(L.h + (int64_t)(ok1 ? p1 : 0) * L.h_stride);
+        u32x4* d0 = (u32x4*)(L.table + (int64_t)(ok0 ? s0 : 0) * L.row_bytes);
+        u32x4* d1 = (u32x4*)(L.table + (int64_t)(ok1 ? s1 : 0) * L.row_bytes);
+        for (int cidx = lane; cidx < chunks; cidx += 64) {
+            const u32x4 v0 = a0[cidx];
+            const u32x4 v1 = a1[cidx];
+            if (ok0) d0[cidx] = v0;
+            if (ok1) d1[cidx] = v1;
         }
     }
 }
@@ -444,6 +452,7 @@ void free_layers(fg_cache_t* c) {
             if (l.slot_stamp) (void)hipFree(l.slot_stamp);
             if (l.table) (void)hipFree(l.table);
             if (l.head) (void)hipFree(l.head);
+            if (l.sel) (void)hipFree(l.sel);
         }
         delete[] c->layers;
     }
@@ -467,6 +476,7 @@ extern "C" fg_status_t fg_cache_clear(fg_cache_t* cache, void* stream) {
         if ((rc = fg_launch_fill_i32(l.slot_node, l.capacity, -1, st)) != FG_OK) return rc;
         if ((rc = fg_launch_fill_i32(l.slot_stamp, l.capacity, 0, st)) != FG_OK) return rc;
         if ((rc = fg_launch_fill_i32((int32_t*)l.head, 4, 0, st)) != FG_OK) return rc;
+        if ((rc = fg_launch_fill_i32((int32_t*)l.sel, sizeof(SelState) / 4, 0, st)) != FG_OK) return rc;
         l.head_cur = 0;
         l.last_iter = INT64_MIN;
     }
@@ -506,6 +516,7 @@ extern "C" fg_status_t fg_cache_create(fg_cache_t** out, int64_t num_nodes, int3
         if (e == hipSuccess) e = hipMalloc((void**)&l.slot_stamp, (size_t)l.capacity * 4);
         if (e == hipSuccess) e = hipMalloc(&l.table, (size_t)l.capacity * l.dim * esz);
         if (e == hipSuccess) e = hipMalloc((void**)&l.head, 16);
+        if (e == hipSuccess) e = hipMalloc(&l.sel, sizeof(SelState));
         if (e != hipSuccess) {
             free_layers(c);
             (void)hipGetLastError();
@@ -565,57 +576,129 @@ extern "C" fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, i
     return FG_OK;
 }
 
+namespace {
+
+// Checks one layer's arguments and fills its descriptor; `ws` is the layer's share of the workspace.
+fg_status_t prepare_update_layer(fg_cache_t* cache, const char* who, int32_t layer, int64_t iter, const int32_t* ids_dev,
+                                 int32_t n, const uint8_t* live_dev, const uint8_t* hit_dev, const float* gnorm_dev,
+                                 float p_grad, const void* h_dev, int64_t h_stride, int64_t* stats_dev, char* ws,
+                                 UpdLayer* out) {
+    const fg_layer* lc;
+    fg_status_t rc = layer_of(cache, layer, who, &lc);
+    if (rc != FG_OK) return rc;
+    const fg_layer* l = &cache->layers[layer - 1];
+    if (n < 0) FG_FAIL(FG_ERR_INVALID_ARG, "%s: n = %d is negative", who, n);
+    if (!(p_grad >= 0.0f && p_grad <= 1.0f)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: p_grad = %g outside [0, 1]", who, (double)p_grad);
+    if (n > 0 && (!ids_dev || !hit_dev || !gnorm_dev || !h_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
+    const int64_t row_bytes = (int64_t)l->dim * fg_dtype_size(cache->dtype);
+    if (h_stride < row_bytes) FG_FAIL(FG_ERR_SHAPE, "%s: h_stride = %lld smaller than a cache row of %lld bytes", who, (long long)h_stride, (long long)row_bytes);
+    if (((uintptr_t)h_dev | (uintptr_t)h_stride) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_dev and h_stride must be 16-byte aligned", who);
+    if (iter < l->last_iter) FG_FAIL(FG_ERR_STATE, "%s: iteration %lld after %lld: the counter must not go backwards", who, (long long)iter, (long long)l->last_iter);
+    if (iter < 0 || iter > INT32_MAX - 1) FG_FAIL(FG_ERR_INVALID_ARG, "%s: iteration %lld out of range", who, (long long)iter);
+    const UpdWs w = upd_layout(n);
+    UpdLayer& u = *out;
+    u.c = CacheRW{l->map, l->slot_node, l->slot_stamp, l->head + l->head_cur, l->head + (l->head_cur ^ 1), l->capacity, cache->num_nodes, iter, cache->t_stale};
+    u.ids = ids_dev;
+    u.live = live_dev;
+    u.hit = hit_dev;
+    u.gnorm = gnorm_dev;
+    u.stats = stats_dev;
+    u.sel = (SelState*)l->sel;
+    u.hdr = (UpdHeader*)(ws + w.hdr);
+    u.flag = (uint8_t*)(ws + w.flag);
+    u.blk = (int32_t*)(ws + w.blk);
+    u.apos = (int32_t*)(ws + w.pos);
+    u.aslot = (int32_t*)(ws + w.slot);
+    u.h = (const char*)h_dev;
+    u.h_stride = h_stride;
+    u.table = (char*)l->table;
+    u.row_bytes = row_bytes;
+    u.n = n;
+    u.p_grad = p_grad;
+    return FG_OK;
+}
+
+// The five launches for the layers described in B (descriptors complete, first-workgroup tables not yet).
+fg_status_t launch_update(UpdBatch& B, hipStream_t st) {
+    int64_t max_copy = 0;
+    B.sel_first[0] = B.scan_first[0] = 0;
+    for (int i = 0; i < B.n_layers; ++i) {  // at least one workgroup per layer: it resets the statistics and writes the header
+        const int64_t n = B.l[i].n > 0 ? B.l[i].n : 1;
+        B.sel_first[i + 1] = B.sel_first[i] + (int)fg_ceil_div(n, SEL_CHUNK);
+        B.scan_first[i + 1] = B.scan_first[i] + (int)fg_ceil_div(n, FG_SCAN_BLOCK);
+        const int64_t cap = B.l[i].n < B.l[i].c.capacity ? B.l[i].n : B.l[i].c.capacity;
+        if (cap > max_copy) max_copy = cap;
+    }
+    const unsigned n_sel = (unsigned)B.sel_first[B.n_layers], n_scan = (unsigned)B.scan_first[B.n_layers];
+    hipLaunchKernelGGL(update_digit0_kernel, dim3(n_sel), dim3(SEL_THREADS), 0, st, B);
+    FG_LAUNCH_CHECK("update_digit0_kernel");
+    hipLaunchKernelGGL(update_digit1_kernel, dim3(n_sel), dim3(SEL_THREADS), 0, st, B);
+    FG_LAUNCH_CHECK("update_digit1_kernel");
+    hipLaunchKernelGGL(classify_update_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
+    FG_LAUNCH_CHECK("classify_update_kernel");
+    hipLaunchKernelGGL(assign_slots_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
+    FG_LAUNCH_CHECK("assign_slots_kernel");
+    if (max_copy > 0) {
+        int64_t gx = fg_ceil_div(max_copy, 2 * (COPY_THREADS / 64));
+        if (gx > 2048) gx = 2048;
+        hipLaunchKernelGGL(copy_admitted_rows_kernel, dim3((unsigned)gx, (unsigned)B.n_layers), dim3(COPY_THREADS), 0, st, B);
+        FG_LAUNCH_CHECK("copy_admitted_rows_kernel");
+    }
+    return FG_OK;
+}
+
+}  // namespace
+
 extern "C" fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t iter, const int32_t* ids_dev,
                                        int32_t n, const uint8_t* live_dev, const uint8_t* hit_dev,
                                        const float* gnorm_dev, float p_grad, const void* h_dev, int64_t h_stride,
                                        int64_t* stats_dev, void* ws_dev, size_t ws_bytes, void* stream) {
-    const fg_layer* lc;
-    fg_status_t rc = layer_of(cache, layer, "fg_cache_update", &lc);
+    UpdBatch B;
+    B.n_layers = 1;
+    fg_status_t rc = prepare_update_layer(cache, "fg_cache_update", layer, iter, ids_dev, n, live_dev, hit_dev, gnorm_dev,
+                                          p_grad, h_dev, h_stride, stats_dev, (char*)ws_dev, &B.l[0]);
     if (rc != FG_OK) return rc;
-    fg_layer* l = &cache->layers[layer - 1];
-    if (n < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: n = %d is negative", n);
-    if (!(p_grad >= 0.0f && p_grad <= 1.0f)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: p_grad = %g outside [0, 1]", (double)p_grad);
-    if (n > 0 && (!ids_dev || !hit_dev || !gnorm_dev || !h_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: NULL pointer");
-    const int64_t row_bytes = (int64_t)l->dim * fg_dtype_size(cache->dtype);
-    if (h_stride < row_bytes) FG_FAIL(FG_ERR_SHAPE, "fg_cache_update: h_stride = %lld smaller than a cache row of %lld bytes", (long long)h_stride, (long long)row_bytes);
-    if (((uintptr_t)h_dev | (uintptr_t)h_stride) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: h_dev and h_stride must be 16-byte aligned");
-    if (iter < l->last_iter) FG_FAIL(FG_ERR_STATE, "fg_cache_update: iteration %lld after %lld: the counter must not go backwards", (long long)iter, (long long)l->last_iter);
-    if (iter < 0 || iter > INT32_MAX - 1) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: iteration %lld out of range", (long long)iter);
-    const UpdWs w = upd_layout(n);
-    if (!ws_dev || ws_bytes < w.total) FG_FAIL(FG_ERR_SHAPE, "fg_cache_update: workspace of %zu bytes given, %zu needed", ws_bytes, w.total);
+    const size_t need = upd_layout(n).total;
+    if (!ws_dev || ws_bytes < need) FG_FAIL(FG_ERR_SHAPE, "fg_cache_update: workspace of %zu bytes given, %zu needed", ws_bytes, need);
     if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update: workspace must be 16-byte aligned");
     fg_clear_error();
-    l->last_iter = iter;
-    hipStream_t st = (hipStream_t)stream;
-    char* ws = (char*)ws_dev;
-    UpdHeader* hdr = (UpdHeader*)(ws + w.hdr);
-    uint8_t* flag = (uint8_t*)(ws + w.flag);
-    int32_t* blk = (int32_t*)(ws + w.blk);
-    int32_t* apos = (int32_t*)(ws + w.pos);
-    int32_t* aslot = (int32_t*)(ws + w.slot);
-    CacheRW c{l->map, l->slot_node, l->slot_stamp, l->head + l->head_cur, l->head + (l->head_cur ^ 1), l->capacity, cache->num_nodes, iter, cache->t_stale};
-    const bool aligned = (((uintptr_t)gnorm_dev & 15) == 0) && (((uintptr_t)live_dev & 3) == 0);
-#define FG_SEL_REG(V) hipLaunchKernelGGL(select_tau_reg_kernel<V>, dim3(1), dim3(SEL_THREADS), 0, st, live_dev, gnorm_dev, n, p_grad, hdr, stats_dev)
-    if (!aligned || n < 4 || n > 16 * 4 * SEL_THREADS)
-        hipLaunchKernelGGL(select_tau_kernel, dim3(1), dim3(SEL_THREADS), 0, st, live_dev, gnorm_dev, n, p_grad, hdr, stats_dev);
-    else if (n <= 1 * 4 * SEL_THREADS) FG_SEL_REG(1);
-    else if (n <= 2 * 4 * SEL_THREADS) FG_SEL_REG(2);
-    else if (n <= 4 * 4 * SEL_THREADS) FG_SEL_REG(4);
-    else if (n <= 8 * 4 * SEL_THREADS) FG_SEL_REG(8);
-    else FG_SEL_REG(16);
-#undef FG_SEL_REG
-    FG_LAUNCH_CHECK("select_tau_kernel");
-    if (n == 0) return FG_OK;
-    const int nb = (int)fg_ceil_div(n, FG_SCAN_BLOCK);
-    hipLaunchKernelGGL(classify_update_kernel, dim3(nb), dim3(FG_SCAN_BLOCK), 0, st, c, ids_dev, n, live_dev, hit_dev,
-                       gnorm_dev, hdr, flag, blk, stats_dev);
-    FG_LAUNCH_CHECK("classify_update_kernel");
-    hipLaunchKernelGGL(assign_slots_kernel, dim3(nb), dim3(FG_SCAN_BLOCK), 0, st, c, ids_dev, n, flag, blk, hdr, apos,
-                       aslot, stats_dev);
-    FG_LAUNCH_CHECK("assign_slots_kernel");
-    rc = fg_launch_gather(h_dev, n, h_stride, row_bytes, apos, aslot, &hdr->n_admit, n < l->capacity ? n : l->capacity,
-                          l->table, l->capacity, row_bytes, FG_TABLE_HBM_REUSED, st);
+    rc = launch_update(B, (hipStream_t)stream);
     if (rc != FG_OK) return rc;
+    fg_layer* l = &cache->layers[layer - 1];
+    l->last_iter = iter;
     l->head_cur ^= 1;  // the advanced header written by assign_slots is the current one from here on
+    return FG_OK;
+}
+
+extern "C" fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, float p_grad, int32_t n_layers,
+                                           const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (n_layers < 0 || n_layers > FG_MAX_UPD_LAYERS)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update_all: n_layers = %d outside 0..%d", n_layers, FG_MAX_UPD_LAYERS);
+    if (n_layers > 0 && !layers) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update_all: layers is NULL");
+    if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update_all: workspace must be 16-byte aligned");
+    UpdBatch B;
+    B.n_layers = n_layers;
+    size_t off = 0;
+    for (int i = 0; i < n_layers; ++i) {
+        for (int k = 0; k < i; ++k)
+            if (layers[k].layer == layers[i].layer)
+                FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update_all: layer %d is listed twice", layers[i].layer);
+        const fg_update_layer_t& a = layers[i];
+        fg_status_t rc = prepare_update_layer(cache, "fg_cache_update_all", a.layer, iter, a.ids_dev, a.n, a.live_dev, a.hit_dev,
+                                              a.gnorm_dev, p_grad, a.h_dev, a.h_stride, a.stats_dev, (char*)ws_dev + off, &B.l[i]);
+        if (rc != FG_OK) return rc;
+        off += upd_layout(a.n).total;
+    }
+    if (n_layers > 0 && (!ws_dev || ws_bytes < off))
+        FG_FAIL(FG_ERR_SHAPE, "fg_cache_update_all: workspace of %zu bytes given, %zu needed", ws_bytes, off);
+    fg_clear_error();
+    if (n_layers == 0) return FG_OK;
+    fg_status_t rc = launch_update(B, (hipStream_t)stream);
+    if (rc != FG_OK) return rc;
+    for (int i = 0; i < n_layers; ++i) {
+        fg_layer* l = &cache->layers[layers[i].layer - 1];
+        l->last_iter = iter;
+        l->head_cur ^= 1;
+    }
     return FG_OK;
 }

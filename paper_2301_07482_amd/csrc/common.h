@@ -14,6 +14,7 @@ struct fg_layer {
     void* table = nullptr;          // [capacity x dim]
     int64_t* head = nullptr;        // device int64[2]: ring header, double-buffered (head_cur indexes the current one)
     int head_cur = 0;
+    void* sel = nullptr;            // selection scratch of the update (two histograms and a count), all-zero between updates
     int64_t last_iter = INT64_MIN;  // host: iteration of the last update
 };
 

@@ -46,7 +46,7 @@ class HotPath:
     """Work buffers, cache and weights of one model; `run(batch, it)` executes one iteration."""
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
-                 weights, features_on_host=False, device="cuda", use_cache=True, overlap_update=True, fused_input=False,
+                 weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fused_input=False,
                  one_launch_top_down=True):
         self.device = device
         self.L = L = len(fanouts)
@@ -92,13 +92,10 @@ class HotPath:
         self.ws_bytes = ws_bytes
         self.ws_td_bytes = sum(B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, n[l]) for l in range(L + 1))
         self.ws_td = torch.zeros(self.ws_td_bytes + 256, dtype=torch.uint8, device=dev)
-        # The update of layer l only needs H[l], which is final once its linear has run: it is queued on a stream
-        # of its own (default priority; the layers' caches are independent) and overlaps the layers above; the
-        # next iteration waits for it before it touches the flags and embeddings again.
-        self.overlap_update = overlap_update and L > 1
-        self.side = [torch.cuda.Stream(device=dev) for _ in range(L)] if self.overlap_update else None
-        self.ws_upd = [torch.zeros(ws_bytes + 256, dtype=torch.uint8, device=dev) for _ in range(L)] if self.overlap_update else None
-        self.upd_done = []
+        # all caches are updated by one call after the last layer (the last loop of Algorithm 1)
+        self.update_all = update_all
+        self.ws_upd_bytes = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L))
+        self.ws_upd = torch.zeros(self.ws_upd_bytes + 256, dtype=torch.uint8, device=dev)
         self.W = {}
         self.bias = {}
         wt = TORCH_DTYPE[self.comp_code]
@@ -132,11 +129,7 @@ class HotPath:
         self.stats = self.stats_log[it % self.ring]
         tick = timer if timer is not None else (lambda name, stream=None: None)
         esz = B.DTYPE_SIZE
-        main = torch.cuda.current_stream()
-        st = main.cuda_stream
-        for ev in self.upd_done:        # updates of the previous iteration still read live/hit/H
-            main.wait_event(ev)
-        self.upd_done = []
+        st = torch.cuda.current_stream().cuda_stream
         do_update = update and self.use_cache and self.cache is not None
         assert all(bt.n[l] <= self.n_max[l] for l in range(L + 1)), "mini-batch larger than the static bounds"
         # ---- top-down: lookup, prune, V_normal (layers L .. 0)
@@ -199,21 +192,14 @@ class HotPath:
             B.fg_linear(self.H[l - 1], bt.n[l - 1], in_b, in_code, self.AGG, agg_b, self.normal_pos[l], self._cnt(l, 2),
                         bt.n[l], self.dims[l - 1], self.dims[l], self.W[l], self.comp_code, self.bias[l],
                         1 if l < L else 0, self.H[l], bt.n[l], out_b, out_code, st)
-            if do_update and self.overlap_update and l < L:
-                ready = torch.cuda.Event()
-                ready.record(main)
-                side = self.side[l]
-                side.wait_event(ready)
-                tick(f"cache_update[{l}]", side)
-                B.fg_cache_update(self.cache, l, it, bt.ids[l], bt.n[l], self.live[l], self.hit[l], bt.gnorm[l],
-                                  self.p_grad, self.H[l], out_b, self.stats.data_ptr() + l * 32, self.ws_upd[l],
-                                  self.ws_bytes, side.cuda_stream)
-                tick(None, side)
-                done = torch.cuda.Event()
-                done.record(side)
-                self.upd_done.append(done)
         # ---- update of the caches
-        if do_update and not self.overlap_update:
+        if do_update and self.update_all:
+            tick("cache_update_all")
+            specs = [dict(layer=l, n=bt.n[l], ids_dev=bt.ids[l], live_dev=self.live[l], hit_dev=self.hit[l],
+                          gnorm_dev=bt.gnorm[l], h_dev=self.H[l], h_stride=self.dims[l] * esz[self.h_code[l]],
+                          stats_dev=self.stats.data_ptr() + l * 32) for l in range(1, L)]
+            B.fg_cache_update_all(self.cache, it, self.p_grad, B.update_layers(specs), self.ws_upd, self.ws_upd_bytes, st)
+        elif do_update:
             for l in range(1, L):
                 out_b = self.dims[l] * esz[self.h_code[l]]
                 tick(f"cache_update[{l}]")

@@ -346,7 +346,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence."""
     g = wl.make_graph(w)
     hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity,
-                                             fused_input=fused, one_launch_top_down=one_launch_top_down)
+                                             fused_input=fused, one_launch_top_down=one_launch_top_down,
+                                             update_all=one_launch_top_down)
     caches = G.make_oracle_caches(w, capacity=capacity, t_stale=t_stale)
     from paper_2301_07482_amd.pipeline import DeviceBatch
     frows = G.feature_accessor(w)
@@ -450,7 +451,8 @@ def test_iterations_tiny(env):
 
 
 def test_iterations_tiny_layer_by_layer_top_down(env):
-    """The same iterations with one fg_lookup_prune call per layer instead of the single cooperative fg_top_down launch."""
+    """The same iterations with one fg_lookup_prune and one fg_cache_update call per layer instead of fg_top_down and
+    fg_cache_update_all."""
     torch, B = env
     w = wl.WORKLOADS["tiny"]
     assert run_workload_parity(torch, w, 8, one_launch_top_down=False)[0] > 0
