@@ -53,6 +53,8 @@ def main():
                     help="materialise every input row with fg_gather and aggregate layer 1 from H0 (separate calls) instead "
                          "of aggregating layer 1 straight from the feature table (fg_gather_aggregate)")
     ap.add_argument("--sample-workers", type=int, default=8)
+    ap.add_argument("--t-stale", type=int, default=None, help="override the workload's staleness bound (not the headline configuration)")
+    ap.add_argument("--p-grad", type=float, default=None, help="override the workload's admission fraction (not the headline configuration)")
     ap.add_argument("--per-layer-update", action="store_true",
                     help="one fg_cache_update per layer instead of one fg_cache_update_all")
     ap.add_argument("--bracket-every", type=int, default=5,
@@ -70,6 +72,11 @@ def main():
     if args.scale > 1:
         w = w.scaled(args.scale)
         wl.WORKLOADS[w.name] = w
+    if args.t_stale is not None or args.p_grad is not None:
+        import dataclasses
+        w = dataclasses.replace(w, name=w.name + "/policy", t_stale=w.t_stale if args.t_stale is None else args.t_stale,
+                                p_grad=w.p_grad if args.p_grad is None else args.p_grad)
+        wl.WORKLOADS[w.name] = w
     total = args.warmup + args.steps
     t0 = time.time()
     sampled = sample_batches(w.name, total, args.sample_workers)
@@ -82,14 +89,13 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     t0 = time.time()
-    hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse)
+    hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + 32)
     if args.per_layer_update:
         hp.update_all = False
     batches = [DeviceBatch(mb, gn) for mb, gn in sampled]
     torch.cuda.synchronize()
     t_setup = time.time() - t0
     L = hp.L
-    assert total + 20 <= hp.ring
 
     if args.calibration_copy:
         a = torch.ones(1 << 28, dtype=torch.float32, device="cuda")

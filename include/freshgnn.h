@@ -97,7 +97,7 @@ fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, int64_t iter
 /*
  * Launch-shape overrides for measurements (defaults are tuned for MI355X and need no call). Keys:
  * "gather_wg_per_cu", "gather_host_wg_per_cu", "gather_unroll" (1, 2, 4, 8), "gather_nontemporal" (0/1),
- * "aggregate_wg_per_cu", "linear_tile" (fp32 GEMM variant: 0 = default, 32 = panel kernel, 64 / 128 = LDS-tiled kernel with that many rows). Process-wide, not thread-safe against concurrent launches. Results never depend on them.
+ * "aggregate_wg_per_cu", "linear_tile" (fp32 GEMM variant: 0 = default, 8 = one task per workgroup with K split over its wavefronts, 32 = panel kernel, 64 / 128 = LDS-tiled kernel with that many rows). Process-wide, not thread-safe against concurrent launches. Results never depend on them.
  */
 fg_status_t fg_set_tuning(const char* key, int64_t value);
 

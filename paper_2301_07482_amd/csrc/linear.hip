@@ -309,6 +309,293 @@ __global__ __launch_bounds__(PL_THREADS, 4) void linear_f32_panel_kernel(
     }
 }
 
+// The panel kernel with every fp32 product formed on the bf16 matrix cores. An fp32 value is the exact sum of three
+// bf16 values (8 + 8 + 8 significand bits: x1 = bf16(x), x2 = bf16(x - x1), x3 = bf16(x - x1 - x2), each rounded to
+// nearest even), so a*w = sum of a_i*w_j; the six terms with i + j <= 4 are kept (each exact in fp32), the three
+// dropped ones are below 2^-26 |a*w|. Twelve v_mfma_f32_32x32x16_bf16 (six terms, two groups of 16 k) replace the
+// sixteen v_mfma_f32_32x32x2_f32 of a 32-wide K chunk at 3/8 of their matrix-core time; accumulation is unchanged
+// (fp32 inside a chunk, chunks folded into fp64). W is split once per workgroup while its panel is copied to
+// LDS, stored as ready-made 16-byte B fragments; A is split in registers by the wavefront that loaded it, and a
+// wavefront of the NB = 2 variant uses its split for two 32-column blocks.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// v[0..7] -> three fragments of eight bf16 (element j in half j % 2 of word j / 2)
+__device__ __forceinline__ void split8(const float* v, u32x4& t1, u32x4& t2, u32x4& t3) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const f32x2 x = {v[2 * p], v[2 * p + 1]};
+        const bf16x2 b1 = __builtin_convertvector(x, bf16x2);
+        const unsigned int u1 = __builtin_bit_cast(unsigned int, b1);
+        const f32x2 r1 = {x[0] - __uint_as_float(u1 << 16), x[1] - __uint_as_float(u1 & 0xFFFF0000u)};
+        const bf16x2 b2 = __builtin_convertvector(r1, bf16x2);
+        const unsigned int u2 = __builtin_bit_cast(unsigned int, b2);
+        const f32x2 r2 = {r1[0] - __uint_as_float(u2 << 16), r1[1] - __uint_as_float(u2 & 0xFFFF0000u)};
+        const bf16x2 b3 = __builtin_convertvector(r2, bf16x2);
+        t1[p] = u1;
+        t2[p] = u2;
+        t3[p] = __builtin_bit_cast(unsigned int, b3);
+    }
+}
+
+template <int NB>
+__global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
+    const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
+    const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
+    const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
+    int64_t out_stride, int n_panels, int n_groups) {
+    constexpr int BNW = PL_BN * NB;
+    extern __shared__ __attribute__((aligned(16))) u32x4 bfrag[];  // [3 terms][K / 8 groups of k][BNW columns]
+    int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
+    if (n_rows > max_rows) n_rows = max_rows;
+    const int K = 2 * d_in;
+    const int nk = K / KC, nk_self = d_in / KC;
+    const int ngr = K / 8;
+    const int t = threadIdx.x;
+    const int xcd = blockIdx.x & 7;
+    const int j = blockIdx.x >> 3;
+    const int n0 = (j % n_panels) * BNW;
+    const int group = (j / n_panels) * 8 + xcd;
+    const int64_t n_blocks = (n_rows + 31) >> 5;
+    if (group >= n_blocks) return;  // uniform over the workgroup, before the barrier
+
+    // group gi = (chunk * 2 + m) * 2 + half holds k = 32 * chunk + 16 * half + 8 * m + (0..7): the eight k values that
+    // half-wavefront `half` feeds to matrix instruction m of the chunk
+    for (int q = t; q < ngr * BNW; q += PL_THREADS) {
+        const int col = q % BNW, gi = q / BNW;
+        const int k0 = 32 * (gi >> 2) + 16 * (gi & 1) + 8 * ((gi >> 1) & 1);
+        const bool in = n0 + col < d_out;
+        const float* wp = W + (int64_t)k0 * d_out + (in ? n0 + col : 0);
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = wp[(int64_t)e * d_out];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = in ? v[e] : 0.f;
+        u32x4 t1, t2, t3;
+        split8(v, t1, t2, t3);
+        bfrag[(0 * ngr + gi) * BNW + col] = t1;
+        bfrag[(1 * ngr + gi) * BNW + col] = t2;
+        bfrag[(2 * ngr + gi) * BNW + col] = t3;
+    }
+    __syncthreads();
+
+    const int lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    double bv[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int c = n0 + nb * 32 + l32;
+        bv[nb] = (bias && c < d_out) ? (double)bias[c] : 0.0;
+    }
+    auto row_of_block = [&](int64_t rb) -> int32_t {
+        const int64_t g = rb * 32 + l32;
+        int32_t r = -1;
+        if (rb < n_blocks && g < n_rows) {
+            r = rows ? rows[g] : (int32_t)g;
+            if (r < 0 || r >= n_src || r >= n_out) r = -1;
+        }
+        return r;
+    };
+    const int64_t stride = (int64_t)n_groups * PL_WAVES;
+    int64_t rb = group + (int64_t)n_groups * wave;
+    if (rb >= n_blocks) return;
+    int32_t r = row_of_block(rb);
+    int32_t r_next = row_of_block(rb + stride);
+    const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+    const float* a_agg = (const float*)(agg + (r >= 0 ? (rb * 32 + l32) * agg_stride : 0)) + 16 * half;
+    f32x4 a0[4], a1[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(a_self + 4 * q);  // step 0 of the first task
+    for (; rb < n_blocks; rb += stride) {
+        const int32_t r_after = row_of_block(rb + 2 * stride);
+        double sum[NB][16];
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sum[nb][i] = 0.0;
+        auto compute = [&](int step, const f32x4* a) {
+            float av[16];
+#pragma unroll
+            for (int q = 0; q < 16; ++q) av[q] = a[q >> 2][q & 3];
+            u32x4 A[3][2];  // [term][m]
+            split8(av, A[0][0], A[1][0], A[2][0]);
+            split8(av + 8, A[0][1], A[1][1], A[2][1]);
+            // (A term, W term) pairs, smallest products first
+            constexpr int TA[6] = {2, 0, 1, 1, 0, 0};
+            constexpr int TW[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                f32x16 acc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+                for (int m = 0; m < 2; ++m) {
+                    const int base = ((step * 2 + m) * 2 + half) * BNW + nb * 32 + l32;
+                    u32x4 f[3];
+#pragma unroll
+                    for (int term = 0; term < 3; ++term) f[term] = bfrag[term * ngr * BNW + base];
+#pragma unroll
+                    for (int e = 0; e < 6; ++e)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[TA[e]][m]),
+                                                                      __builtin_bit_cast(bf16x8, f[TW[e]]), acc, 0, 0, 0);
+                }
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sum[nb][i] += (double)acc[i];
+            }
+        };
+        for (int step = 0; step < nk; step += 2) {
+            {
+                const int s1 = step + 1;
+                const float* p = s1 < nk_self ? a_self + s1 * KC : a_agg + (s1 - nk_self) * KC;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a1[q] = *(const f32x4*)(p + 4 * q);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            compute(step, a0);
+            {
+                const int s2 = step + 2;
+                const float* nxt = (const float*)(h_src + (r_next >= 0 ? (int64_t)r_next * src_stride : 0)) + 16 * half;
+                const float* cur = s2 < nk_self ? a_self + s2 * KC : a_agg + (s2 < nk ? s2 - nk_self : 0) * KC;
+                const float* p = s2 < nk ? cur : nxt;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(p + 4 * q);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            compute(step + 1, a1);
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+            const int c = n0 + nb * 32 + l32;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int m = 8 * (i >> 2) + 4 * half + (i & 3);
+                const int32_t rr = __shfl(r, m, 64);
+                if (rr < 0 || c >= d_out) continue;
+                float v = (float)(sum[nb][i] + bv[nb]);
+                if (relu) v = v > 0.f ? v : 0.f;
+                *(float*)(h_out + (int64_t)rr * out_stride + (int64_t)c * 4) = v;
+            }
+        }
+        r = r_next;
+        r_next = r_after;
+        a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+        a_agg = (const float*)(agg + (r >= 0 ? ((rb + stride) * 32 + l32) * agg_stride : 0)) + 16 * half;
+    }
+}
+
+// Few rows (up to 768 tasks, about three per compute unit; measured crossover with the panel kernel near 1000):
+// one workgroup per task, the K range split over its
+// 8 wavefronts. A wavefront copies only its own rows of the W panel to LDS, fetches its A values in one round of
+// loads, runs its one or two K chunks and leaves a 32 x 32 partial sum in fp64; the partial sums meet in LDS (in the
+// space of the panel) and are added in wavefront order, so the result does not depend on timing. This removes the
+// two costs that dominate a small layer in the panel kernel: a full pass over K by a single wavefront and the
+// copy of a whole panel for a single task.
+constexpr int SK_PART_BYTES = PL_WAVES * 16 * 64 * 8;  // partial sums: [wavefront][accumulator element][lane] doubles
+
+__global__ __launch_bounds__(PL_THREADS, 2) void linear_f32_splitk_kernel(
+    const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
+    const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
+    const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
+    int64_t out_stride, int n_panels) {
+    extern __shared__ __attribute__((aligned(16))) float panel[];  // [K][32], later the partial sums
+    int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
+    if (n_rows > max_rows) n_rows = max_rows;
+    const int K = 2 * d_in;
+    const int nk = K / KC, nk_self = d_in / KC;
+    const int xcd = blockIdx.x & 7;
+    const int j = blockIdx.x >> 3;
+    const int n0 = (j % n_panels) * PL_BN;
+    const int64_t rb = (int64_t)(j / n_panels) * 8 + xcd;  // the panels of a row block run on one XCD
+    if (rb * 32 >= n_rows) return;                         // uniform over the workgroup, before any barrier
+    const int t = threadIdx.x;
+    const int lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int per = (nk + PL_WAVES - 1) / PL_WAVES;
+    const int c0 = wave * per < nk ? wave * per : nk;
+    const int c1 = c0 + per < nk ? c0 + per : nk;
+
+    // destination / source row of this lane (-1: past the end or out of range; such a lane reads row 0)
+    const int64_t g = rb * 32 + l32;
+    int32_t r = -1;
+    if (g < n_rows) {
+        r = rows ? rows[g] : (int32_t)g;
+        if (r < 0 || r >= n_src || r >= n_out) r = -1;
+    }
+    const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+    const float* a_agg = (const float*)(agg + (r >= 0 ? g * agg_stride : 0)) + 16 * half;
+    auto a_ptr = [&](int s) { return s < nk_self ? a_self + s * KC : a_agg + (s - nk_self) * KC; };
+
+    // the first round of A loads goes out before anything else waits on memory
+    f32x4 a0[4], a1[4];
+    {
+        const float* p0 = a_ptr(c0 < nk ? c0 : 0);
+        const float* p1 = a_ptr(c0 + 1 < c1 ? c0 + 1 : (c0 < nk ? c0 : 0));
+#pragma unroll
+        for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(p0 + 4 * q);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) a1[q] = *(const f32x4*)(p1 + 4 * q);
+    }
+    // this wavefront's rows of the panel
+    for (int q = lane; q < (c1 - c0) * KC * 8; q += 64) {
+        const int k = c0 * KC + (q >> 3), c4 = (q & 7) * 4;
+        const f32x4 v = *(const f32x4*)(W + (int64_t)k * d_out + (n0 + c4 < d_out ? n0 + c4 : 0));
+        const f32x4 z = {0.f, 0.f, 0.f, 0.f};
+        *(f32x4*)(panel + k * PL_BN + c4) = n0 + c4 < d_out ? v : z;
+    }
+    double sum[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sum[i] = 0.0;
+    __syncthreads();
+    const float* bcol = panel + 16 * half * PL_BN + l32;
+    auto compute = [&](int s, const f32x4* a) {
+        f32x16 acc;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+        const float* brow = bcol + s * KC * PL_BN;
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+            acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a[q >> 2][q & 3], brow[q * PL_BN], acc, 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum[i] += (double)acc[i];
+    };
+    for (int s = c0; s < c1; s += 2) {  // two chunks per round of loads (a chunk past the end re-reads chunk s)
+        const bool two = s + 1 < c1;
+        if (s > c0) {
+            const float* p0 = a_ptr(s);
+            const float* p1 = a_ptr(two ? s + 1 : s);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(p0 + 4 * q);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) a1[q] = *(const f32x4*)(p1 + 4 * q);
+        }
+        compute(s, a0);
+        if (two) compute(s + 1, a1);
+    }
+    __syncthreads();  // every wavefront is done with the panel: its space now takes the partial sums
+    double* part = (double*)panel;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) part[(wave * 16 + i) * 64 + lane] = sum[i];
+    __syncthreads();
+    const int c = n0 + l32;
+    const double bv = (bias && c < d_out) ? (double)bias[c] : 0.0;
+    // wavefront w finishes accumulator elements 2w and 2w+1: element i is row 8*(i/4) + 4*half + i%4 of the block
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int i = 2 * wave + e;
+        double v = bv;
+#pragma unroll
+        for (int w = 0; w < PL_WAVES; ++w) v += part[(w * 16 + i) * 64 + lane];
+        const int m = 8 * (i >> 2) + 4 * half + (i & 3);
+        const int32_t rr = __shfl(r, m, 64);  // lane m (< 32) holds the destination row of block row m; all lanes active
+        if (rr < 0 || c >= d_out) continue;
+        float o = (float)v;
+        if (relu) o = o > 0.f ? o : 0.f;
+        *(float*)(h_out + (int64_t)rr * out_stride + (int64_t)c * 4) = o;
+    }
+}
+
 }  // namespace
 
 fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype,
@@ -343,7 +630,43 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
         if (max_rows == 0) return FG_OK;
         const int64_t forced = fg_tuning(FG_TUNE_LINEAR_TILE);
         const size_t panel_bytes = (size_t)2 * d_in * PL_BN * sizeof(float);
-        if (d_in % KC == 0 && panel_bytes <= 64 * 1024 && (forced == 0 || forced == 32)) {
+        if (n_src == 0 || n_out == 0) return FG_OK;  // no row can be in range
+        const int64_t n_tasks = fg_ceil_div(max_rows, 32) * fg_ceil_div(d_out, PL_BN);
+        if (d_in % KC == 0 && panel_bytes <= 64 * 1024 && (forced == 8 || (forced == 0 && n_tasks <= 768))) {
+            const int n_panels = (int)fg_ceil_div(d_out, PL_BN);
+            const size_t lds = panel_bytes > (size_t)SK_PART_BYTES ? panel_bytes : (size_t)SK_PART_BYTES;
+            const unsigned grid = (unsigned)(fg_ceil_div(fg_ceil_div(max_rows, 32), 8) * 8 * n_panels);
+            hipLaunchKernelGGL(linear_f32_splitk_kernel, dim3(grid), dim3(PL_THREADS), lds, st, (const char*)h_src, n_src,
+                               src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out,
+                               (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels);
+            FG_LAUNCH_CHECK("linear_f32_splitk_kernel");
+            return FG_OK;
+        }
+        // bf16 x 3 panel kernel: two 32-column blocks per wavefront if the split panel fits in LDS, else one
+        const size_t x3_bytes = (size_t)2 * d_in * 192;
+        if (d_in % KC == 0 && x3_bytes <= 144 * 1024 && (forced == 0 || forced == 301 || forced == 302)) {
+            const int nb = (forced != 301 && 2 * x3_bytes <= 144 * 1024) ? 2 : 1;
+            const size_t lds = x3_bytes * nb;
+            const int n_panels = (int)fg_ceil_div(d_out, PL_BN * nb);
+            int q = 256 / (8 * n_panels);  // register use allows one workgroup per compute unit
+            if (q < 1) q = 1;
+            const int64_t blocks32 = fg_ceil_div(max_rows, 32);
+            while (q > 1 && (int64_t)8 * (q - 1) >= blocks32) --q;
+            const int n_groups = 8 * q;
+            if (nb == 2)
+                hipLaunchKernelGGL(linear_f32x3_panel_kernel<2>, dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), lds, st,
+                                   (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev,
+                                   max_rows, d_in, d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels,
+                                   n_groups);
+            else
+                hipLaunchKernelGGL(linear_f32x3_panel_kernel<1>, dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), lds, st,
+                                   (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev,
+                                   max_rows, d_in, d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels,
+                                   n_groups);
+            FG_LAUNCH_CHECK("linear_f32x3_panel_kernel");
+            return FG_OK;
+        }
+        if (d_in % KC == 0 && panel_bytes <= 64 * 1024 && (forced == 0 || forced == 32)) {  // fp32 matrix instructions
             const int n_panels = (int)fg_ceil_div(d_out, PL_BN);
             // two workgroups (of eight wavefronts) per compute unit; 8 * q groups of workgroups, each group holding all panels
             int q = (2 * 256) / (8 * n_panels);

@@ -47,7 +47,7 @@ class HotPath:
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fused_input=False,
-                 one_launch_top_down=True):
+                 one_launch_top_down=True, log_ring=256):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -81,7 +81,7 @@ class HotPath:
         self.input_ids = torch.zeros(n[0], dtype=torch.int32, device=dev)
         self.self_ids = torch.zeros(n[1], dtype=torch.int32, device=dev)
         # device-side counts/stats are kept per iteration in a ring, so a timed loop can be read back afterwards
-        self.ring = 256
+        self.ring = int(log_ring)
         self.counts_log = torch.zeros((self.ring, L + 1, 3), dtype=torch.int64, device=dev)
         self.stats_log = torch.zeros((self.ring, L + 1, 4), dtype=torch.int64, device=dev)
         self.counts = self.counts_log[0]

@@ -248,7 +248,8 @@ def test_linear_identity_panels_pin_operand_layout(env):
     and wrong for any mistake in the matrix-core operand or accumulator layout."""
     torch, B = env
     r = np.random.default_rng(0)
-    for d in (64, 128, 100):
+    for d, variant in ((64, 0), (128, 0), (100, 0), (64, 8), (128, 32), (96, 8), (128, 301), (64, 302)):
+        B.fg_set_tuning("linear_tile", variant)
         I, Z = np.eye(d, dtype=np.float32), np.zeros((d, d), np.float32)
         zero = np.zeros(d, np.float32)
         got, want, hs, ag = _linear_case(torch, B, r, 700, 333, 400, d, d, False, np.vstack([I, Z]), zero)
@@ -258,19 +259,29 @@ def test_linear_identity_panels_pin_operand_layout(env):
         perm = r.permutation(d)
         got, want, hs, ag = _linear_case(torch, B, r, 700, 333, 400, d, d, True, np.vstack([I[perm], Z]), zero)
         assert np.array_equal(got, np.maximum(hs[:, np.argsort(perm)], 0))
+    B.fg_set_tuning("linear_tile", 0)
 
 
 @pytest.mark.parametrize("d_in,d_out,n_rows,max_rows,relu", [(64, 64, 1000, 1200, True), (100, 256, 777, 777, True),
                                                              (128, 256, 4097, 5000, True), (256, 256, 129, 200, False),
                                                              (256, 256, 1, 128, True), (64, 64, 0, 128, True),
-                                                             (4, 4, 130, 130, False), (128, 260, 300, 300, True)])
-def test_linear_matches_oracle(env, d_in, d_out, n_rows, max_rows, relu):
+                                                             (4, 4, 130, 130, False), (128, 260, 300, 300, True),
+                                                             (96, 96, 500, 600, True), (160, 72, 900, 900, False),
+                                                             (128, 256, 20000, 20000, True)])
+@pytest.mark.parametrize("variant", [0, 8, 32, 64, 301, 302])
+def test_linear_matches_oracle(env, d_in, d_out, n_rows, max_rows, relu, variant):
+    """variant: the fp32 kernel forced through the tuning key (0 = the library's own choice by problem size; a
+    variant that does not support the shape falls back to the LDS-tiled kernel)."""
     torch, B = env
     r = np.random.default_rng(d_in * 7 + d_out)
-    got, want, _, _ = _linear_case(torch, B, r, max_rows + 500, n_rows, max_rows, d_in, d_out, relu)
+    B.fg_set_tuning("linear_tile", variant)
+    try:
+        got, want, _, _ = _linear_case(torch, B, r, max_rows + 500, n_rows, max_rows, d_in, d_out, relu)
+    finally:
+        B.fg_set_tuning("linear_tile", 0)
     assert got.shape == want.shape
     err = T.rel_err_rows(got, want)
-    print(f"linear {d_in}x{d_out} rows {n_rows}: rel err {err:.3e}")
+    print(f"linear {d_in}x{d_out} rows {n_rows} variant {variant}: rel err {err:.3e}")
     assert err <= REL_TOL_F32
 
 
