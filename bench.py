@@ -18,6 +18,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
+BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 
 
 def _sample_one(args):
@@ -209,10 +210,17 @@ def main():
                        frac=gather_bytes / (gather_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, traffic=None,
                        bytes_per_launch=gather_bytes, ms_per_launch=gather_ms)
     lin1_ms = timed_ms["linear[1]"]
-    linear_roof = dict(bound="mfma", kernel="linear_f32_panel_kernel (fg_linear, layer 1, fp32 MFMA)",
-                       achieved=lin_flops[1] / (lin1_ms * 1e-3) / 1e12, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s",
-                       frac=lin_flops[1] / (lin1_ms * 1e-3) / 1e12 / FP32_MFMA_PEAK_TFLOPS, traffic=None,
-                       flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms)
+    # The layer-1 dense update is an fp32 contraction (fp32 operands and result, fp32/fp64 accumulation) priced against
+    # the fp32 matrix peak on its algorithmic flops 2*M*K*N. Its default kernel forms every fp32 product exactly from
+    # three bf16 pieces per operand (6 partial products on v_mfma_f32_32x32x16_bf16), so the matrix cores execute 6x
+    # the algorithmic flops at the bf16 rate: that figure is given as well.
+    lin_tf = lin_flops[1] / (lin1_ms * 1e-3) / 1e12
+    linear_roof = dict(bound="mfma", kernel="linear_f32x3_panel_kernel<2> (fg_linear, layer 1: fp32 products from 3-way bf16 "
+                                            "splits on the bf16 matrix cores)",
+                       achieved=lin_tf, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_tf / FP32_MFMA_PEAK_TFLOPS,
+                       traffic=None, flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms,
+                       executed=dict(tflops=6 * lin_tf, peak=BF16_MFMA_PEAK_TFLOPS, frac=6 * lin_tf / BF16_MFMA_PEAK_TFLOPS,
+                                     note="bf16 MFMA flops issued (6 partial products per fp32 product)"))
     # `roofline` is the kernel with the longest launches in the timed region; the other one follows as `roofline_2`
     roofline, roofline_2 = (loader_roof, linear_roof) if gather_ms >= lin1_ms else (linear_roof, loader_roof)
 

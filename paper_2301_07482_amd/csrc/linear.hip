@@ -389,27 +389,34 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
         const int c = n0 + nb * 32 + l32;
         bv[nb] = (bias && c < d_out) ? (double)bias[c] : 0.0;
     }
-    auto row_of_block = [&](int64_t rb) -> int32_t {
-        const int64_t g = rb * 32 + l32;
-        int32_t r = -1;
-        if (rb < n_blocks && g < n_rows) {
-            r = rows ? rows[g] : (int32_t)g;
-            if (r < 0 || r >= n_src || r >= n_out) r = -1;
-        }
+    // Destination / source row of this lane in row block rbx (-1: past the end or out of range), in two steps: the
+    // load is issued unconditionally (clamped index; a valid dummy address if there is no row list) and its value is
+    // looked at a whole task later. A branch around the load, or any use of the value next to it, would make the
+    // wavefront wait for everything it has in flight: the prefetched A values and the previous task's stores.
+    auto row_raw = [&](int64_t rbx) -> int32_t {
+        int64_t g = rbx * 32 + l32;
+        g = g < n_rows ? g : n_rows - 1;  // n_rows >= 1 here
+        const int32_t* src = rows ? rows + g : (const int32_t*)h_src;
+        return *src;
+    };
+    auto row_decode = [&](int32_t raw, int64_t rbx) -> int32_t {
+        const int64_t g = rbx * 32 + l32;
+        int32_t r = rows ? raw : (int32_t)g;
+        if (rbx >= n_blocks || g >= n_rows || r < 0 || r >= n_src || r >= n_out) r = -1;
         return r;
     };
     const int64_t stride = (int64_t)n_groups * PL_WAVES;
     int64_t rb = group + (int64_t)n_groups * wave;
     if (rb >= n_blocks) return;
-    int32_t r = row_of_block(rb);
-    int32_t r_next = row_of_block(rb + stride);
+    int32_t r = row_decode(row_raw(rb), rb);
+    int32_t r_next = row_decode(row_raw(rb + stride), rb + stride);
     const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
     const float* a_agg = (const float*)(agg + (r >= 0 ? (rb * 32 + l32) * agg_stride : 0)) + 16 * half;
     f32x4 a0[4], a1[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(a_self + 4 * q);  // step 0 of the first task
     for (; rb < n_blocks; rb += stride) {
-        const int32_t r_after = row_of_block(rb + 2 * stride);
+        const int32_t raw_after = row_raw(rb + 2 * stride);  // looked at when this task is done
         double sum[NB][16];
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -465,17 +472,20 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
             __builtin_amdgcn_sched_barrier(0);
             compute(step + 1, a1);
         }
+        const int32_t r_after = row_decode(raw_after, rb + 2 * stride);  // before the stores below are in flight
+        // accumulator element i is row 8*(i/4) + 4*half + i%4 of the block, column l32 of its column block. Lane m
+        // (< 32) holds the destination row of block row m: all 16 exchanges are issued before the first one is used.
+        int32_t rr[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) rr[i] = __shfl(r, 8 * (i >> 2) + 4 * half + (i & 3), 64);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
             const int c = n0 + nb * 32 + l32;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                const int m = 8 * (i >> 2) + 4 * half + (i & 3);
-                const int32_t rr = __shfl(r, m, 64);
-                if (rr < 0 || c >= d_out) continue;
                 float v = (float)(sum[nb][i] + bv[nb]);
                 if (relu) v = v > 0.f ? v : 0.f;
-                *(float*)(h_out + (int64_t)rr * out_stride + (int64_t)c * 4) = v;
+                if (rr[i] >= 0 && c < d_out) *(float*)(h_out + (int64_t)rr[i] * out_stride + (int64_t)c * 4) = v;
             }
         }
         r = r_next;
