@@ -19,6 +19,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
+PCIE5_X16_GBS = 64.0            # PCIe Gen5 x16, one direction (workloads whose feature table stays in host memory)
 
 
 def _sample_one(args):
@@ -205,10 +206,17 @@ def main():
         lin_bytes[l] = nn * (2 * d_in * e_in + d_out * 4) + 2 * d_in * d_out * 4
     dom = max(call_avg_ms, key=call_avg_ms.get)
     gather_ms = timed_ms[LOADER]
-    loader_roof = dict(bound="hbm", kernel=dom_kernel,
-                       achieved=gather_bytes / (gather_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
-                       frac=gather_bytes / (gather_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, traffic=None,
-                       bytes_per_launch=gather_bytes, ms_per_launch=gather_ms)
+    if w.feat_location == "host":
+        # host-resident table: the loader is bound by the host link, priced on the table bytes that cross it
+        link_bytes = n_input * feat_row
+        loader_roof = dict(bound="host_link", kernel=dom_kernel, achieved=link_bytes / (gather_ms * 1e-3) / 1e9,
+                           peak=PCIE5_X16_GBS, unit="GB/s", frac=link_bytes / (gather_ms * 1e-3) / 1e9 / PCIE5_X16_GBS,
+                           traffic=None, bytes_per_launch=link_bytes, ms_per_launch=gather_ms)
+    else:
+        loader_roof = dict(bound="hbm", kernel=dom_kernel,
+                           achieved=gather_bytes / (gather_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+                           frac=gather_bytes / (gather_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, traffic=None,
+                           bytes_per_launch=gather_bytes, ms_per_launch=gather_ms)
     lin1_ms = timed_ms["linear[1]"]
     # The layer-1 dense update is an fp32 contraction (fp32 operands and result, fp32/fp64 accumulation) priced against
     # the fp32 matrix peak on its algorithmic flops 2*M*K*N. Its default kernel forms every fp32 product exactly from
@@ -221,6 +229,9 @@ def main():
                        traffic=None, flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms,
                        executed=dict(tflops=6 * lin_tf, peak=BF16_MFMA_PEAK_TFLOPS, frac=6 * lin_tf / BF16_MFMA_PEAK_TFLOPS,
                                      note="bf16 MFMA flops issued (6 partial products per fp32 product)"))
+    if w.name == "large_hbm" and not (args.no_cache or args.no_fuse):   # the configuration the counter runs were made on
+        loader_roof["traffic"] = profiled_traffic("aggregate_mean_kernel<0, 0, true>")
+        linear_roof["traffic"] = profiled_traffic("linear_f32x3_panel_kernel<2>")
     # `roofline` is the kernel with the longest launches in the timed region; the other one follows as `roofline_2`
     roofline, roofline_2 = (loader_roof, linear_roof) if gather_ms >= lin1_ms else (linear_roof, loader_roof)
 
@@ -252,6 +263,20 @@ def main():
         "host": {"sampling_s": t_sample, "setup_s": t_setup},
     }
     print(json.dumps(out))
+
+
+def profiled_traffic(kernel_prefix):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 counter summary (FETCH_SIZE and WRITE_SIZE runs of
+    this same command, scaled by the plain-copy calibration stated there); None if the summary has no such row."""
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "bench_large_hbm_hbm_traffic.md")
+    try:
+        for line in open(path):
+            cells = [c.strip() for c in line.strip().strip("|").split("|")]
+            if len(cells) == 5 and cells[0].startswith(kernel_prefix):
+                return (float(cells[3]) + float(cells[4])) * 1e6
+    except (OSError, ValueError):
+        pass
+    return None
 
 
 def time_oracle(w, sampled, weights, iterations=10):
