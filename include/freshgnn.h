@@ -5,7 +5,8 @@
  * One training iteration calls, in this order:
  *   top-down   fg_lookup_prune  for layers L, L-1, ..., 1, 0   (cache lookup, pruning, V_normal)
  *   loader     fg_gather        raw features of the surviving input nodes
- *   bottom-up  for l = 1..L:    fg_gather (cached rows of V_cache), fg_aggregate, fg_linear
+ *   bottom-up  for l = 1..L:    fg_gather (cached rows of V_cache; or fg_cache_fetch_all once for all layers),
+ *                               fg_aggregate, fg_linear
  *   update     fg_cache_update  for l = 1..L-1   (or fg_cache_update_all once)
  *
  * Conventions
@@ -289,6 +290,28 @@ typedef struct fg_update_layer {
 } fg_update_layer_t;
 fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, float p_grad, int32_t n_layers,
                                 const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * The fetch of cached embeddings (h_v = C^(l)[v], Algorithm 1) for every hit of every listed layer in one launch:
+ * the same result as fg_gather(fg_cache_table(cache, layer), capacity, ..., hit_slot, hit_pos, n_hit, ..., h) per
+ * layer. At most 8 layers.
+ *   hit_slot_dev, hit_pos_dev [max_hits], n_hit_dev   the hit lists and their device-side count (NULL = max_hits)
+ *                                                     as produced by fg_lookup_prune / fg_top_down
+ *   h_dev, h_rows, h_stride                           embeddings of the layer by position (the cache's dtype and width),
+ *                                                     rows, byte stride; 16-byte aligned
+ * Entries with a slot or position out of range are skipped.
+ */
+typedef struct fg_fetch_layer {
+    int32_t layer;
+    const int32_t* hit_slot_dev;
+    const int32_t* hit_pos_dev;
+    const int64_t* n_hit_dev;
+    int64_t max_hits;
+    void* h_dev;
+    int64_t h_rows;
+    int64_t h_stride;
+} fg_fetch_layer_t;
+fg_status_t fg_cache_fetch_all(const fg_cache_t* cache, int32_t n_layers, const fg_fetch_layer_t* layers, void* stream);
 
 #ifdef __cplusplus
 }

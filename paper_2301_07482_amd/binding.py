@@ -62,6 +62,13 @@ class UpdateLayer(C.Structure):
                 ("h_dev", _p), ("h_stride", _i64), ("stats_dev", _p)]
 
 
+class FetchLayer(C.Structure):
+    """fg_fetch_layer_t"""
+    _fields_ = [("layer", _i32), ("hit_slot_dev", _p), ("hit_pos_dev", _p), ("n_hit_dev", _p), ("max_hits", _i64),
+                ("h_dev", _p), ("h_rows", _i64), ("h_stride", _i64)]
+
+
+SIGNATURES["fg_cache_fetch_all"] = (_i32, [_p, _i32, C.POINTER(FetchLayer), _p])
 SIGNATURES["fg_cache_update_all"] = (_i32, [_p, _i64, _f, _i32, C.POINTER(UpdateLayer), _p, _sz, _p])
 
 for _name, (_res, _args) in SIGNATURES.items():
@@ -191,14 +198,27 @@ def fg_cache_update(cache, layer, it, ids, n, live, hit, gnorm, p_grad, h, h_str
                                 ptr(stats), ptr(ws), ws_bytes, stream))
 
 
-def update_layers(specs):
-    """ctypes array of fg_update_layer_t from dicts keyed by the field names (tensors or addresses for pointers)."""
-    arr = (UpdateLayer * len(specs))()
+def _struct_array(struct, specs):
+    arr = (struct * len(specs))()
     for a, spec in zip(arr, specs):
-        for name, ctype in UpdateLayer._fields_:
+        for name, ctype in struct._fields_:
             v = spec.get(name)
             setattr(a, name, ptr(v) if ctype is _p else (0 if v is None else v))
     return arr
+
+
+def update_layers(specs):
+    """ctypes array of fg_update_layer_t from dicts keyed by the field names (tensors or addresses for pointers)."""
+    return _struct_array(UpdateLayer, specs)
+
+
+def fetch_layers(specs):
+    """ctypes array of fg_fetch_layer_t from dicts keyed by the field names."""
+    return _struct_array(FetchLayer, specs)
+
+
+def fg_cache_fetch_all(cache, layers, stream=None):
+    _check(_lib.fg_cache_fetch_all(cache, len(layers), layers, stream))
 
 
 def fg_cache_update_all(cache, it, p_grad, layers, ws, ws_bytes, stream=None):

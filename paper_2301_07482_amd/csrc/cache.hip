@@ -343,37 +343,6 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(UpdBatch B)
     }
 }
 
-// table[aslot[k], :] = h[apos[k], :] for the admitted rows of every layer: blockIdx.y is the layer, a wavefront
-// copies a row in 16-byte pieces, two rows in flight.
-constexpr int COPY_THREADS = 256;
-__global__ __launch_bounds__(COPY_THREADS) void copy_admitted_rows_kernel(UpdBatch B) {
-    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-    const UpdLayer& L = B.l[blockIdx.y];
-    const int64_t count = L.hdr->n_admit;
-    const int chunks = (int)(L.row_bytes >> 4);
-    const int lane = threadIdx.x & 63;
-    const int64_t wave = ((int64_t)blockIdx.x * COPY_THREADS + threadIdx.x) >> 6;
-    const int64_t n_waves = ((int64_t)gridDim.x * COPY_THREADS) >> 6;
-    for (int64_t k0 = wave; k0 < count; k0 += 2 * n_waves) {
-        const int64_t k1 = k0 + n_waves;
-        const bool has1 = k1 < count;
-        const int32_t p0 = L.apos[k0], s0 = L.aslot[k0];
-        const int32_t p1 = has1 ? L.apos[k1] : p0, s1 = has1 ? L.aslot[k1] : s0;
-        const bool ok0 = p0 >= 0 && p0 < L.n && s0 >= 0 && s0 < L.c.capacity;
-        const bool ok1 = has1 && p1 >= 0 && p1 < L.n && s1 >= 0 && s1 < L.c.capacity;
-        const u32x4* a0 = (const u32x4*)(L.h + (int64_t)(ok0 ? p0 : 0) * L.h_stride);
-        const u32x4* a1 = (const u32x4*)(L.h + (int64_t)(ok1 ? p1 : 0) * L.h_stride);
-        u32x4* d0 = (u32x4*)(L.table + (int64_t)(ok0 ? s0 : 0) * L.row_bytes);
-        u32x4* d1 = (u32x4*)(L.table + (int64_t)(ok1 ? s1 : 0) * L.row_bytes);
-        for (int cidx = lane; cidx < chunks; cidx += 64) {
-            const u32x4 v0 = a0[cidx];
-            const u32x4 v1 = a1[cidx];
-            if (ok0) d0[cidx] = v0;
-            if (ok1) d1[cidx] = v1;
-        }
-    }
-}
-
 struct UpdWs {
     size_t hdr, flag, blk, pos, slot, total;
 };
@@ -620,14 +589,11 @@ fg_status_t prepare_update_layer(fg_cache_t* cache, const char* who, int32_t lay
 
 // The five launches for the layers described in B (descriptors complete, first-workgroup tables not yet).
 fg_status_t launch_update(UpdBatch& B, hipStream_t st) {
-    int64_t max_copy = 0;
     B.sel_first[0] = B.scan_first[0] = 0;
     for (int i = 0; i < B.n_layers; ++i) {  // at least one workgroup per layer: it resets the statistics and writes the header
         const int64_t n = B.l[i].n > 0 ? B.l[i].n : 1;
         B.sel_first[i + 1] = B.sel_first[i] + (int)fg_ceil_div(n, SEL_CHUNK);
         B.scan_first[i + 1] = B.scan_first[i] + (int)fg_ceil_div(n, FG_SCAN_BLOCK);
-        const int64_t cap = B.l[i].n < B.l[i].c.capacity ? B.l[i].n : B.l[i].c.capacity;
-        if (cap > max_copy) max_copy = cap;
     }
     const unsigned n_sel = (unsigned)B.sel_first[B.n_layers], n_scan = (unsigned)B.scan_first[B.n_layers];
     hipLaunchKernelGGL(update_digit0_kernel, dim3(n_sel), dim3(SEL_THREADS), 0, st, B);
@@ -638,12 +604,15 @@ fg_status_t launch_update(UpdBatch& B, hipStream_t st) {
     FG_LAUNCH_CHECK("classify_update_kernel");
     hipLaunchKernelGGL(assign_slots_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
     FG_LAUNCH_CHECK("assign_slots_kernel");
-    if (max_copy > 0) {
-        int64_t gx = fg_ceil_div(max_copy, 2 * (COPY_THREADS / 64));
-        if (gx > 2048) gx = 2048;
-        hipLaunchKernelGGL(copy_admitted_rows_kernel, dim3((unsigned)gx, (unsigned)B.n_layers), dim3(COPY_THREADS), 0, st, B);
-        FG_LAUNCH_CHECK("copy_admitted_rows_kernel");
+    fg_row_copy_batch copies;  // table[aslot[k], :] = h[apos[k], :] for the admitted rows of every layer
+    copies.n = B.n_layers;
+    for (int i = 0; i < B.n_layers; ++i) {
+        const UpdLayer& u = B.l[i];
+        const int64_t cap = u.n < u.c.capacity ? u.n : u.c.capacity;
+        copies.c[i] = fg_row_copy{u.h, u.n, u.h_stride, u.apos, u.aslot, &u.hdr->n_admit, cap, u.table, u.c.capacity, u.row_bytes, u.row_bytes};
     }
+    fg_status_t rc = fg_launch_row_copies(copies, st);
+    if (rc != FG_OK) return rc;
     return FG_OK;
 }
 
@@ -701,4 +670,29 @@ extern "C" fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, floa
         l->head_cur ^= 1;
     }
     return FG_OK;
+}
+
+extern "C" fg_status_t fg_cache_fetch_all(const fg_cache_t* cache, int32_t n_layers, const fg_fetch_layer_t* layers,
+                                          void* stream) {
+    if (n_layers < 0 || n_layers > FG_MAX_COPIES)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fetch_all: n_layers = %d outside 0..%d", n_layers, FG_MAX_COPIES);
+    if (n_layers > 0 && !layers) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fetch_all: layers is NULL");
+    fg_row_copy_batch copies;
+    copies.n = n_layers;
+    for (int i = 0; i < n_layers; ++i) {
+        const fg_fetch_layer_t& a = layers[i];
+        const fg_layer* l;
+        fg_status_t rc = layer_of(cache, a.layer, "fg_cache_fetch_all", &l);
+        if (rc != FG_OK) return rc;
+        if (a.max_hits < 0 || a.h_rows < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fetch_all: negative size for layer %d", a.layer);
+        if (a.max_hits > 0 && (!a.hit_slot_dev || !a.hit_pos_dev || !a.h_dev))
+            FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fetch_all: NULL pointer for layer %d", a.layer);
+        const int64_t row_bytes = (int64_t)l->dim * fg_dtype_size(cache->dtype);
+        if (a.h_stride < row_bytes) FG_FAIL(FG_ERR_SHAPE, "fg_cache_fetch_all: h_stride = %lld smaller than a cache row of %lld bytes", (long long)a.h_stride, (long long)row_bytes);
+        if (((uintptr_t)a.h_dev | (uintptr_t)a.h_stride) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fetch_all: h_dev and h_stride must be 16-byte aligned");
+        copies.c[i] = fg_row_copy{(const char*)l->table, l->capacity, row_bytes, a.hit_slot_dev, a.hit_pos_dev, a.n_hit_dev, a.max_hits,
+                                  (char*)a.h_dev, a.h_rows, a.h_stride, row_bytes};
+    }
+    fg_clear_error();
+    return fg_launch_row_copies(copies, (hipStream_t)stream);
 }

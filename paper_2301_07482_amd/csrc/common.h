@@ -72,6 +72,25 @@ fg_status_t fg_launch_gather(const void* table, int64_t table_rows, int64_t src_
                              const int32_t* src_index, const int32_t* dst_pos, const int64_t* count_dev,
                              int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride, int on_host,
                              hipStream_t stream);
+// Several independent row copies in one launch: dst[dst_idx[k], :] = src[src_idx[k], :] for k < *count (rows a
+// multiple of 16 bytes, 16-byte aligned). Used where a pass copies rows for every cached layer at once.
+constexpr int FG_MAX_COPIES = 8;
+struct fg_row_copy {
+    const char* src;
+    int64_t src_rows, src_stride;
+    const int32_t* src_idx;
+    const int32_t* dst_idx;
+    const int64_t* count;  // device
+    int64_t max_count;
+    char* dst;
+    int64_t dst_rows, dst_stride;
+    int64_t row_bytes;
+};
+struct fg_row_copy_batch {
+    int32_t n;
+    fg_row_copy c[FG_MAX_COPIES];
+};
+fg_status_t fg_launch_row_copies(const fg_row_copy_batch& batch, hipStream_t stream);
 // fill n bytes with a value (a kernel, so that callers may capture it into a graph)
 fg_status_t fg_launch_fill_u8(uint8_t* p, int64_t n, uint8_t value, hipStream_t stream);
 fg_status_t fg_launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t stream);

@@ -46,7 +46,7 @@ class HotPath:
     """Work buffers, cache and weights of one model; `run(batch, it)` executes one iteration."""
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
-                 weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fused_input=False,
+                 weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
                  one_launch_top_down=True, log_ring=256):
         self.device = device
         self.L = L = len(fanouts)
@@ -94,6 +94,7 @@ class HotPath:
         self.ws_td = torch.zeros(self.ws_td_bytes + 256, dtype=torch.uint8, device=dev)
         # all caches are updated by one call after the last layer (the last loop of Algorithm 1)
         self.update_all = update_all
+        self.fetch_all = fetch_all   # the cached rows of all layers are fetched by one call right after the top-down pass
         self.ws_upd_bytes = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L))
         self.ws_upd = torch.zeros(self.ws_upd_bytes + 256, dtype=torch.uint8, device=dev)
         self.W = {}
@@ -161,6 +162,13 @@ class HotPath:
                                   a["row_start_dev"], a["row_end_dev"], a["col_dev"], a["nnz"], a["n_src"], a["live_src_dev"],
                                   a["hit_dev"], a["hit_pos_dev"], a["hit_slot_dev"], a["normal_pos_dev"], a["normal_ids_dev"],
                                   a["counts_dev"], self.ws, self.ws_bytes, st)
+        cached_layers = list(range(1, L)) if (self.use_cache and self.cache is not None) else []
+        if self.fetch_all and cached_layers:
+            tick("cache_fetch_all")
+            specs = [dict(layer=l, hit_slot_dev=self.hit_slot[l], hit_pos_dev=self.hit_pos[l], n_hit_dev=self._cnt(l, 1),
+                          max_hits=bt.n[l], h_dev=self.H[l], h_rows=bt.n[l], h_stride=self.dims[l] * esz[self.h_code[l]])
+                     for l in cached_layers]
+            B.fg_cache_fetch_all(self.cache, B.fetch_layers(specs), st)
         # ---- loader: raw features of the surviving input nodes (fused: done by fg_gather_aggregate below, which also
         #      copies the layer-1 nodes' own rows into H[0])
         d0b = self.dims[0] * esz[self.feat_code]
@@ -173,7 +181,7 @@ class HotPath:
             in_code, out_code = self.h_code[l - 1], self.h_code[l]
             in_b = self.dims[l - 1] * esz[in_code]
             out_b = self.dims[l] * esz[out_code]
-            if self.use_cache and self.cache is not None and 1 <= l <= L - 1:
+            if l in cached_layers and not self.fetch_all:
                 tick(f"cache_fetch[{l}]")
                 B.fg_gather(B.fg_cache_table(self.cache, l), self.capacity[l - 1], out_b, out_b, self.hit_slot[l],
                             self.hit_pos[l], self._cnt(l, 1), bt.n[l], self.H[l], bt.n[l], out_b, B.FG_TABLE_HBM_REUSED, st)

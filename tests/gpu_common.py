@@ -17,7 +17,7 @@ def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None
                  w.t_stale if t_stale is None else t_stale, w.p_grad if p_grad is None else p_grad, feat_table,
                  w.feat_dtype, w.compute_dtype, weights, features_on_host=(w.feat_location == "host"),
                  use_cache=use_cache, fused_input=fused_input, one_launch_top_down=one_launch_top_down, update_all=update_all,
-                 log_ring=log_ring)
+                 fetch_all=update_all, log_ring=log_ring)
     return hp, weights, feat_table
 
 
