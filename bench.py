@@ -57,6 +57,8 @@ def main():
     ap.add_argument("--sample-workers", type=int, default=8)
     ap.add_argument("--t-stale", type=int, default=None, help="override the workload's staleness bound (not the headline configuration)")
     ap.add_argument("--p-grad", type=float, default=None, help="override the workload's admission fraction (not the headline configuration)")
+    ap.add_argument("--tune", action="append", default=[], metavar="KEY=VALUE",
+                    help="fg_set_tuning(KEY, VALUE) before the run (launch-shape experiments; results do not depend on it)")
     ap.add_argument("--per-layer-update", action="store_true",
                     help="one fg_cache_update per layer instead of one fg_cache_update_all")
     ap.add_argument("--bracket-every", type=int, default=5,
@@ -94,6 +96,11 @@ def main():
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + 32)
     if args.per_layer_update:
         hp.update_all = False
+    if args.tune:
+        from paper_2301_07482_amd import binding as B
+        for kv in args.tune:
+            key, value = kv.split("=")
+            B.fg_set_tuning(key, int(value))
     batches = [DeviceBatch(mb, gn) for mb, gn in sampled]
     torch.cuda.synchronize()
     t_setup = time.time() - t0

@@ -244,6 +244,14 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void classify_update_kernel(UpdBatch
     const UpdLayer& L = B.l[layer_of_block(B.scan_first, B.n_layers, blockIdx.x, local)];
     const CacheRW& c = L.c;
     const int t = threadIdx.x;
+    // this thread's element first: the loads are in flight while the selection below runs
+    const int j = local * FG_SCAN_BLOCK + t;
+    const bool in = j < L.n;
+    const int jc = in ? j : 0;
+    const uint8_t live_j = (in && L.n > 0) ? (L.live ? L.live[jc] : (uint8_t)1) : (uint8_t)0;
+    const uint32_t key_j = (in && L.n > 0) ? order_key(L.gnorm[jc]) : 0u;
+    const uint8_t hit_j = (in && L.n > 0) ? L.hit[jc] : (uint8_t)0;
+    const int32_t v = (in && L.n > 0) ? L.ids[jc] : -1;
     // the rest of the selection, the same in every workgroup of the layer
     uint32_t d0, tau_key = 0;
     long long m;
@@ -272,12 +280,10 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void classify_update_kernel(UpdBatch
         L.hdr->tau_key = tau_key;
         L.hdr->m_live = m;
     }
-    const int j = local * FG_SCAN_BLOCK + t;
     bool admit = false, evict = false;
-    if (j < L.n && (L.live ? L.live[j] != 0 : true)) {
-        const bool low = mode == 2 || (mode == 1 && order_key(L.gnorm[j]) < tau_key);
-        const bool is_hit = L.hit[j] != 0;
-        const int32_t v = L.ids[j];
+    if (live_j != 0) {
+        const bool low = mode == 2 || (mode == 1 && key_j < tau_key);
+        const bool is_hit = hit_j != 0;
         const bool v_ok = v >= 0 && v < c.num_nodes;
         if (is_hit && !low && v_ok) {
             c.map[v] = -1;
@@ -304,18 +310,20 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(UpdBatch B)
     const int n_local = B.scan_first[layer + 1] - B.scan_first[layer];
     if (local == 0)  // every workgroup of the layer has used the selection scratch in the previous launch
         for (int i = threadIdx.x; i < (int)(sizeof(SelState) / 4); i += FG_SCAN_BLOCK) ((unsigned int*)L.sel)[i] = 0;
+    // this thread's element and the ring header first: in flight while the preceding workgroups' counts are added up
+    const int j = local * FG_SCAN_BLOCK + threadIdx.x;
+    const bool admit = j < L.n && L.flag[j] != 0;
+    const int32_t v_j = j < L.n ? L.ids[j] : -1;
+    const int64_t head = *c.head;
     long long before = 0;
     for (int b = threadIdx.x; b < local; b += FG_SCAN_BLOCK) before += L.blk[b];
     before = fg_block_sum(before, red);
-    const int j = local * FG_SCAN_BLOCK + threadIdx.x;
-    const bool admit = j < L.n && L.flag[j] != 0;
     int total;
     const long long rank = before + fg_block_rank(admit, total, sc);
     bool overwrote = false;
     if (admit && rank < c.capacity) {
-        const int64_t head = *c.head;
         const int32_t s = (int32_t)((head + rank) % c.capacity);
-        const int32_t v = L.ids[j];
+        const int32_t v = v_j;
         const int32_t old = c.slot_node[s];
         if (old >= 0 && old < c.num_nodes && c.map[old] == s) {
             const int64_t age = c.iter + 1 - (int64_t)c.slot_stamp[s];
@@ -334,7 +342,7 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(UpdBatch B)
             const long long all = before + total;
             const long long in = all < c.capacity ? all : c.capacity;
             L.hdr->n_admit = in;
-            *c.head_next = (*c.head + in) % c.capacity;
+            *c.head_next = (head + in) % c.capacity;
             if (L.stats) {
                 L.stats[0] = in;
                 L.stats[3] = all - in;

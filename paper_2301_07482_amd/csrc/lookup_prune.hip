@@ -42,14 +42,22 @@ __device__ __forceinline__ void classify_mark_chunk(
     int32_t* __restrict__ slot_ws, int32_t* __restrict__ blk_counts, int chunk, bool have_candidates = false) {
     const int j = chunk * FG_SCAN_BLOCK + threadIdx.x;
     const bool in = j < n;
-    const bool is_live = in && (live ? live[j] != 0 : true);
+    // everything this position may need is requested at once (one memory round trip instead of a chain of four)
+    const uint8_t live_j = in ? (live ? live[j] : (uint8_t)1) : (uint8_t)0;
+    int32_t s0 = 0, e0 = 0, slot_j = -1, id_j = -1;
+    if (in && row_start) {
+        s0 = row_start[j];
+        e0 = row_end[j];
+    }
+    if (in && has_cache) {
+        if (have_candidates) slot_j = slot_ws[j];  // the node's usable slot or -1, looked up for every position beforehand
+        else id_j = ids[j];
+    }
+    const bool is_live = live_j != 0;
     bool hit = false;
     int32_t slot = -1;
-    if (have_candidates) {  // slot_ws[j] already holds the node's usable slot or -1, looked up for every position
-        if (is_live && has_cache) slot = slot_ws[j];
-        hit = slot >= 0;
-    } else if (is_live && has_cache) {
-        slot = cache_lookup(cv, ids[j]);
+    if (is_live && has_cache) {
+        slot = have_candidates ? slot_j : cache_lookup(cv, id_j);
         hit = slot >= 0;
     }
     const bool normal = is_live && !hit;
@@ -58,16 +66,20 @@ __device__ __forceinline__ void classify_mark_chunk(
         slot_ws[j] = slot;
         if (hit_out) hit_out[j] = hit ? 1 : 0;
         if (row_start) {
-            const int32_t s0 = row_start[j];
             if (!normal) {
                 row_end[j] = s0;
             } else {
-                const int32_t e0 = row_end[j];
                 if (live_src && j < n_src) live_src[j] = 1;
                 if (live_src && s0 >= 0 && s0 <= e0 && (int64_t)e0 <= nnz) {
-                    for (int32_t e = s0; e < e0; ++e) {
-                        const int32_t c = col[e];
-                        if (c >= 0 && c < n_src) live_src[c] = 1;  // many writers, one value
+                    // neighbour positions eight at a time: the loads go out together (a slot past the end re-reads
+                    // the last one), then the marks (many writers, one value)
+                    for (int32_t e = s0; e < e0; e += 8) {
+                        int32_t c[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) c[u] = col[e + u < e0 ? e + u : e0 - 1];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u)
+                            if (e + u < e0 && c[u] >= 0 && c[u] < n_src) live_src[c[u]] = 1;
                     }
                 }
             }
@@ -96,6 +108,11 @@ __device__ __forceinline__ void compact_lists_chunk(
     const int32_t* __restrict__ blk_counts, int32_t* __restrict__ hit_pos, int32_t* __restrict__ hit_slot,
     int32_t* __restrict__ normal_pos, int32_t* __restrict__ normal_ids, int64_t* __restrict__ counts_out, int chunk,
     int n_chunks, long long* red, int* sc) {
+    // this position's class, slot and id are requested before the counts of the preceding workgroups are added up
+    const int j = chunk * FG_SCAN_BLOCK + threadIdx.x;
+    const uint8_t c = j < n ? cls_ws[j] : CLS_DEAD;
+    const int32_t slot_j = j < n ? slot_ws[j] : -1;
+    const int32_t id_j = (j < n && normal_ids) ? ids[j] : -1;
     long long p_live = 0, p_hit = 0, p_norm = 0;
     for (int b = threadIdx.x; b < chunk; b += FG_SCAN_BLOCK) {
         p_live += blk_counts[3 * b + 0];
@@ -106,18 +123,16 @@ __device__ __forceinline__ void compact_lists_chunk(
     p_hit = fg_block_sum(p_hit, red);
     p_norm = fg_block_sum(p_norm, red);
 
-    const int j = chunk * FG_SCAN_BLOCK + threadIdx.x;
-    const uint8_t c = j < n ? cls_ws[j] : CLS_DEAD;
     int t_hit, t_norm;
     const int r_hit = fg_block_rank(c == CLS_HIT, t_hit, sc);
     const int r_norm = fg_block_rank(c == CLS_NORMAL, t_norm, sc);
     if (c == CLS_HIT && hit_pos) {
         hit_pos[p_hit + r_hit] = j;
-        hit_slot[p_hit + r_hit] = slot_ws[j];
+        hit_slot[p_hit + r_hit] = slot_j;
     }
     if (c == CLS_NORMAL) {
         normal_pos[p_norm + r_norm] = j;
-        if (normal_ids) normal_ids[p_norm + r_norm] = ids[j];
+        if (normal_ids) normal_ids[p_norm + r_norm] = id_j;
     }
     if (chunk == n_chunks - 1 && threadIdx.x == 0) {
         counts_out[0] = p_live + t_hit + t_norm;

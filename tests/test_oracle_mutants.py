@@ -1,0 +1,96 @@
+"""Do the pins of the oracle bite? Each case plants one plausible mistake in the oracle (a dropped term, a wrong
+sign or bound, swapped operands), on the CPU, and requires that at least one pin of test_oracle_pins.py then fails.
+The mistakes are made by editing the source text of one oracle function and re-executing it in the oracle module."""
+import inspect
+import textwrap
+
+import pytest
+
+from oracle import freshgnn_oracle as O
+from tests import test_oracle_pins as P
+
+PINS = [
+    (P.test_full_neighbourhood_equals_dense_recursion, [(1, 0), (2, 1), (3, 2)]),
+    (P.test_intermediate_layers_equal_dense_recursion, [()]),
+    (P.test_mean_closed_forms, [()]),
+    (P.test_linear_panels_and_activation, [()]),
+    (P.test_bf16_rounding_points, [()]),
+    (P.test_prune_matches_depth_first_needed_set, [(s,) for s in range(4)]),
+    (P.test_exact_history_invariant, [()]),
+    (P.test_degenerate_settings_reduce_to_neighbour_sampling, [(0.0, 5), (0.7, 0)]),
+    (P.test_admit_everything_keeps_everything_computed, [()]),
+    (P.test_threshold_is_rank_statistic_and_order_free, [()]),
+    (P.test_trace_gradient_and_staleness, [()]),
+    (P.test_trace_ring, [()]),
+    (P.test_staleness_boundary, [()]),
+    (P.test_cache_matches_dictionary_model, [(5, 2, 0.5), (16, 4, 0.9), (3, 1, 1.0), (40, 50, 0.3)]),
+]
+
+# (owner, function, text in its source, replacement)
+MUTANTS = [
+    ("aggregate sums instead of averaging", None, "aggregate", "/ float(len(nb))", "/ 1.0"),
+    ("aggregate divides by degree + 1", None, "aggregate", "/ float(len(nb))", "/ float(len(nb) + 1)"),
+    ("aggregate reads rows instead of neighbours", None, "aggregate", "h[nb]", "h[[r] * len(nb)]"),
+    ("linear swaps the self and neighbour panels", None, "linear", "@ W[:d_in] + np.asarray(agg, dtype=np.float64) @ W[d_in:]",
+     "@ W[d_in:] + np.asarray(agg, dtype=np.float64) @ W[:d_in]"),
+    ("linear drops the bias", None, "linear", "+ np.asarray(b, dtype=np.float64))", "+ 0.0 * np.asarray(b, dtype=np.float64))"),
+    ("linear applies ReLU after the last layer too", None, "linear", "if relu else z", "if True else z"),
+    ("linear never applies ReLU", None, "linear", "if relu else z", "if False else z"),
+    ("an entry is usable in the iteration that admitted it", "HistoricalCache", "slot_of", "age < 1", "age < 0"),
+    ("staleness bound one too short", "HistoricalCache", "slot_of", "age > self.t_stale", "age >= self.t_stale"),
+    ("staleness bound one too long", "HistoricalCache", "slot_of", "age > self.t_stale", "age > self.t_stale + 1"),
+    ("recycled slots still hit for their old owner", "HistoricalCache", "slot_of", "int(self.slot_node[s]) != int(v)", "False"),
+    ("threshold rank one too low", None, "admission_threshold", "[k]), k", "[k - 1]), k"),
+    ("threshold count rounds up", None, "admission_threshold", "np.floor(", "np.ceil("),
+    ("ties at the threshold are admitted", None, "cache_update", "not hit[j] and g[j] < tau", "not hit[j] and g[j] <= tau"),
+    ("hits with large norms are kept", None, "cache_update", "cache.map[ids[j]] = -1", "pass"),
+    ("hits at the threshold are kept", None, "cache_update", "hit[j] and not (g[j] < tau)", "hit[j] and not (g[j] <= tau)"),
+    ("population of the percentile is the computed nodes only", None, "cache_update", "admission_threshold(g[live], p_grad)",
+     "admission_threshold(g[live & ~hit], p_grad)"),
+    ("admitted rows are stamped with the next iteration", None, "cache_update", "cache.slot_stamp[s] = i", "cache.slot_stamp[s] = i + 1"),
+    ("the ring header does not advance", None, "cache_update", "cache.head = (head + admitted) % cache.capacity if cache.capacity else 0",
+     "cache.head = head"),
+    ("the ring does not wrap", None, "cache_update", "s = (head + admitted) % cache.capacity", "s = min(head + admitted, cache.capacity - 1)"),
+    ("admission beyond the capacity overwrites this update's own slots", None, "cache_update", "if admitted >= cache.capacity:", "if False:"),
+    ("the wrong row is stored", None, "cache_update", "cache.table[s] = h[j]", "cache.table[s] = h[admitted]"),
+    ("a normal row does not keep its own position live", None, "lookup_prune", "live_src[j] = True", "pass"),
+    ("pruned nodes are looked up", None, "lookup_prune", "if not live[j]:\n            continue", "if False:\n            continue"),
+    ("rows that are not normal keep their neighbours", None, "lookup_prune", "end[j] = start[j]", "pass"),
+    ("neighbours of hit rows stay live", None, "lookup_prune", "if normal[j]:", "if live[j]:"),
+    ("hits are listed as normal too", None, "lookup_prune", "        else:\n            normal_pos.append(j)", "        normal_pos.append(j)"),
+]
+
+
+def _plant(owner, name, old, new):
+    target = getattr(O, owner) if owner else O
+    original = getattr(target, name)
+    src = textwrap.dedent(inspect.getsource(original))
+    assert src.count(old) == 1, f"the text to change occurs {src.count(old)} times in {name}"
+    scope = {}
+    exec(compile(src.replace(old, new), f"<mutant of {name}>", "exec"), O.__dict__, scope)
+    setattr(target, name, scope[name])
+    return target, name, original
+
+
+def _first_failing_pin():
+    for fn, cases in PINS:
+        for args in cases:
+            try:
+                fn(*args)
+            except Exception as e:  # an assertion of the pin, or the mistake making the oracle itself stumble
+                return f"{fn.__name__}{args}: {type(e).__name__}"
+    return None
+
+
+def test_pins_pass_on_the_unmodified_oracle():
+    assert _first_failing_pin() is None
+
+
+@pytest.mark.parametrize("what,owner,name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_a_planted_mistake_fails_a_pin(what, owner, name, old, new):
+    target, attr, original = _plant(owner, name, old, new)
+    try:
+        caught = _first_failing_pin()
+    finally:
+        setattr(target, attr, original)
+    assert caught is not None, f"no pin notices that {what}"
