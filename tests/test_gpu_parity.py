@@ -350,6 +350,73 @@ def test_iteration_counter_must_not_go_backwards(env):
         B.fg_cache_destroy(cache)
 
 
+def test_update_all_and_fetch_all_with_unequal_and_empty_layers(env):
+    """fg_cache_update_all / fg_cache_fetch_all over three layers of very different sizes, one of them empty in some
+    iterations, against the oracle's per-layer updates: cache state, statistics and fetched rows."""
+    torch, B = env
+    from paper_2301_07482_amd.pipeline import _tensor_from_ptr
+    r = np.random.default_rng(77)
+    N, dims, caps, t_stale, p = 30000, [8, 16, 4], [300, 5000, 64], 3, 0.6
+    oc = [O.HistoricalCache(N, caps[k], dims[k], t_stale) for k in range(3)]
+    cache = B.fg_cache_create(N, caps, dims, B.FG_F32, t_stale, None)
+    try:
+        for i in range(12):
+            ns = [int(r.integers(0, 400)) if i % 3 else 0, int(r.integers(3000, 9000)), int(r.integers(1, 90))]
+            ids = [r.permutation(N)[:n].astype(np.int32) for n in ns]
+            live = [r.random(n) < 0.85 for n in ns]
+            gn = [np.round(np.exp(r.standard_normal(n)), 2).astype(np.float32) for n in ns]
+            rows = [r.standard_normal((n, dims[k])).astype(np.float32) for k, n in enumerate(ns)]
+            look = [O.lookup_prune(oc[k], i, ids[k], live[k], None, None, None, 0) for k in range(3)]
+            # device lookups (per layer), then one fetch call and one update call for all three layers
+            t_ids = [dev(torch, a) for a in ids]
+            t_live = [dev(torch, a.astype(np.uint8)) for a in live]
+            t_hit = [torch.zeros(max(n, 1), dtype=torch.uint8, device="cuda") for n in ns]
+            t_pos = [torch.zeros(max(n, 1), dtype=torch.int32, device="cuda") for n in ns]
+            t_slot = [torch.zeros(max(n, 1), dtype=torch.int32, device="cuda") for n in ns]
+            t_norm = [torch.zeros(max(n, 1), dtype=torch.int32, device="cuda") for n in ns]
+            t_cnt = torch.zeros((3, 3), dtype=torch.int64, device="cuda")
+            for k in range(3):
+                wsb = B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, ns[k])
+                ws = torch.zeros(max(wsb, 16), dtype=torch.uint8, device="cuda")
+                B.fg_lookup_prune(cache, k + 1, i, t_ids[k], ns[k], t_live[k], None, None, None, 0, 0, None, t_hit[k], t_pos[k],
+                                  t_slot[k], t_norm[k], None, t_cnt[k], ws, wsb, None)
+            t_H = [torch.full((max(n, 1), dims[k]), -5.0, device="cuda") for k, n in enumerate(ns)]
+            B.fg_cache_fetch_all(cache, B.fetch_layers([dict(layer=k + 1, hit_slot_dev=t_slot[k], hit_pos_dev=t_pos[k],
+                                                             n_hit_dev=t_cnt[k].data_ptr() + 8, max_hits=ns[k], h_dev=t_H[k],
+                                                             h_rows=ns[k], h_stride=dims[k] * 4) for k in range(3)]), None)
+            for k in range(3):
+                got = t_H[k].cpu().numpy()[:ns[k]]
+                assert np.array_equal(t_hit[k].cpu().numpy()[:ns[k]].astype(bool), look[k]["hit"])
+                want = np.full((ns[k], dims[k]), -5.0, np.float32)
+                if len(look[k]["hit_pos"]):
+                    want[look[k]["hit_pos"]] = oc[k].table[look[k]["hit_slot"]]
+                assert np.array_equal(got, want), f"fetched rows of layer {k + 1} at iteration {i}"
+            t_rows = [dev(torch, a) if a.size else torch.zeros((1, dims[k]), device="cuda") for k, a in enumerate(rows)]
+            t_gn = [dev(torch, a) if a.size else torch.zeros(1, device="cuda") for a in gn]
+            t_stats = torch.zeros((3, 4), dtype=torch.int64, device="cuda")
+            wsb = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n) for n in ns)
+            ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+            B.fg_cache_update_all(cache, i, p, B.update_layers([dict(layer=k + 1, n=ns[k], ids_dev=t_ids[k], live_dev=t_live[k],
+                                                                     hit_dev=t_hit[k], gnorm_dev=t_gn[k], h_dev=t_rows[k],
+                                                                     h_stride=dims[k] * 4, stats_dev=t_stats[k].data_ptr())
+                                                                for k in range(3)]), ws, wsb, None)
+            stats = t_stats.cpu().numpy().tolist()
+            for k in range(3):
+                st = O.cache_update(oc[k], i, ids[k], live[k], look[k]["hit"], gn[k], p, rows[k])
+                assert stats[k] == [st["admitted"], st["evicted_by_gradient"], st["overwritten"], st["dropped_overflow"]], \
+                    f"stats of layer {k + 1} at iteration {i}"
+                exp = _export(torch, B, cache, caps[k], i + 1, layer=k + 1)
+                valid = oc[k].valid_entries(i + 1)
+                assert exp["head"] == oc[k].head
+                assert dict(zip(exp["nodes"].tolist(), zip(exp["slots"].tolist(), exp["stamps"].tolist()))) == valid
+                tab = _tensor_from_ptr(B.fg_cache_table(cache, k + 1), (caps[k], dims[k]), torch.float32, caps[k] * dims[k] * 4,
+                                       "cuda").cpu().numpy()
+                for v, (s, _) in valid.items():
+                    assert np.array_equal(tab[s], oc[k].table[s])
+    finally:
+        B.fg_cache_destroy(cache)
+
+
 # ------------------------------------------------------------------------------------------------ whole iterations
 
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
