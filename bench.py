@@ -245,6 +245,35 @@ def main():
     hits = {l: float(np.mean([c[l][1] for c in counts_all])) for l in range(1, L)}
     n0_all = float(np.mean([batches[it].n[0] for it in steps_it]))
 
+    # Everything but the dense updates (lookup, prune, compaction, fetch, loader, aggregation, update) as one
+    # bandwidth figure: algorithmic bytes of those steps over the time of their calls in the breakdown pass.
+    stats = [stats_log[it % hp.ring] for it in roof_it]
+    e_comp = 4 if w.compute_dtype == "f32" else 2
+    def layer_bytes(it, c, st):
+        total = 0.0
+        for l in range(1, L + 1):
+            n_l, n_hit, n_norm = batches[it].n[l], float(c[l][1]), float(c[l][2])
+            edges_l = float((batches[it].end[l] - batches[it].start[l]).sum().item())      # left under normal rows
+            total += n_l * (4 + 1 + 4 + 8) + edges_l * (4 + 1) + 4 * (2 * n_hit + n_norm)     # lookup, prune, lists
+            if l >= 2 or args.no_fuse:
+                d_prev = hp.dims[l - 1] * (esz[w.feat_dtype] if l == 1 else e_comp)
+                total += edges_l * (4 + d_prev) + n_norm * hp.dims[l - 1] * e_comp           # aggregation
+            if l < L:
+                row = hp.dims[l] * e_comp
+                total += n_hit * (8 + 2 * row)                                                # cache fetch
+                total += 2 * n_l * 6 + float(st[l][0]) * (2 * row + 12) + float(st[l][1]) * 4  # update
+        return total
+    path_bytes = gather_bytes + float(np.mean([layer_bytes(it, c, st) for it, c, st in zip(roof_it, counts, stats)]))
+    path_ms = sum(v for k, v in call_avg_ms.items() if not k.startswith("linear"))
+    hbm_path = dict(bytes_per_step=path_bytes, ms_per_step=path_ms, achieved=path_bytes / (path_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=path_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                    note="all calls except fg_linear; times from the breakdown pass (every call bracketed)")
+    # table rows the loader would read with the caches empty: every edge of block 1 plus every layer-1 node's own row
+    if args.no_fuse:
+        rows_no_cache = n0_all
+    else:
+        rows_no_cache = float(np.mean([batches[it].nnz[1] + batches[it].n[1] for it in steps_it]))
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         cpu_baseline = time_oracle(w, sampled, weights)
@@ -265,7 +294,9 @@ def main():
         "cpu_baseline": cpu_baseline,
         "per_call_ms": {k: round(v, 5) for k, v in sorted(call_avg_ms.items())},
         "dominant_call": dom,
-        "per_step": {"table_rows_read": n_input, "input_rows_sampled": n0_all,
+        "hbm_path": hbm_path,
+        "per_step": {"table_rows_read": n_input, "table_rows_without_cache": rows_no_cache,
+                     "io_saving": 1.0 - n_input / rows_no_cache if rows_no_cache else 0.0, "input_rows_sampled": n0_all,
                      "hits": hits, "gather_bytes": gather_bytes, "linear_flops": lin_flops},
         "host": {"sampling_s": t_sample, "setup_s": t_setup},
     }
