@@ -478,14 +478,30 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
         int32_t rr[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) rr[i] = __shfl(r, 8 * (i >> 2) + 4 * half + (i & 3), 64);
+        // A block whose 32 rows are all in range and whose columns all exist (every block but the ragged last ones)
+        // is stored without a condition per element: 32 branches would put every store in a basic block of its own.
+        const bool whole = __all(r >= 0) && n0 + BNW <= d_out;
+        if (whole) {
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-            const int c = n0 + nb * 32 + l32;
+            for (int nb = 0; nb < NB; ++nb) {
+                char* out_col = h_out + (int64_t)(n0 + nb * 32 + l32) * 4;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                float v = (float)(sum[nb][i] + bv[nb]);
-                if (relu) v = v > 0.f ? v : 0.f;
-                if (rr[i] >= 0 && c < d_out) *(float*)(h_out + (int64_t)rr[i] * out_stride + (int64_t)c * 4) = v;
+                for (int i = 0; i < 16; ++i) {
+                    float v = (float)(sum[nb][i] + bv[nb]);
+                    if (relu) v = v > 0.f ? v : 0.f;
+                    *(float*)(out_col + (int64_t)rr[i] * out_stride) = v;
+                }
+            }
+        } else {
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const int c = n0 + nb * 32 + l32;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float v = (float)(sum[nb][i] + bv[nb]);
+                    if (relu) v = v > 0.f ? v : 0.f;
+                    if (rr[i] >= 0 && c < d_out) *(float*)(h_out + (int64_t)rr[i] * out_stride + (int64_t)c * 4) = v;
+                }
             }
         }
         r = r_next;
