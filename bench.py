@@ -230,12 +230,21 @@ def main():
     # three bf16 pieces per operand (6 partial products on v_mfma_f32_32x32x16_bf16), so the matrix cores execute 6x
     # the algorithmic flops at the bf16 rate: that figure is given as well.
     lin_tf = lin_flops[1] / (lin1_ms * 1e-3) / 1e12
-    linear_roof = dict(bound="mfma", kernel="linear_f32x3_panel_kernel<2> (fg_linear, layer 1: fp32 products from 3-way bf16 "
-                                            "splits on the bf16 matrix cores)",
-                       achieved=lin_tf, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_tf / FP32_MFMA_PEAK_TFLOPS,
-                       traffic=None, flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms,
-                       executed=dict(tflops=6 * lin_tf, peak=BF16_MFMA_PEAK_TFLOPS, frac=6 * lin_tf / BF16_MFMA_PEAK_TFLOPS,
-                                     note="bf16 MFMA flops issued (6 partial products per fp32 product)"))
+    if w.compute_dtype == "bf16":
+        linear_roof = dict(bound="mfma", kernel="linear_bf16_kernel (fg_linear, layer 1, bf16 MFMA, fp32 accumulation)",
+                           achieved=lin_tf, peak=BF16_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_tf / BF16_MFMA_PEAK_TFLOPS,
+                           traffic=None, flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms)
+    elif hp.dims[0] % 32 == 0:
+        linear_roof = dict(bound="mfma", kernel="linear_f32x3_panel_kernel<2> (fg_linear, layer 1: fp32 products from 3-way bf16 "
+                                                "splits on the bf16 matrix cores)",
+                           achieved=lin_tf, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_tf / FP32_MFMA_PEAK_TFLOPS,
+                           traffic=None, flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms,
+                           executed=dict(tflops=6 * lin_tf, peak=BF16_MFMA_PEAK_TFLOPS, frac=6 * lin_tf / BF16_MFMA_PEAK_TFLOPS,
+                                         note="bf16 MFMA flops issued (6 partial products per fp32 product)"))
+    else:  # input width not a multiple of 32: the LDS-tiled fp32-MFMA kernel
+        linear_roof = dict(bound="mfma", kernel="linear_f32_kernel (fg_linear, layer 1, fp32 MFMA)",
+                           achieved=lin_tf, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_tf / FP32_MFMA_PEAK_TFLOPS,
+                           traffic=None, flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms)
     if w.name == "large_hbm" and not (args.no_cache or args.no_fuse):   # the configuration the counter runs were made on
         loader_roof["traffic"] = profiled_traffic("aggregate_mean_kernel<0, 0, true>")
         linear_roof["traffic"] = profiled_traffic("linear_f32x3_panel_kernel<2>")
