@@ -240,7 +240,12 @@ fg_status_t fg_gather_aggregate(const int32_t* row_start_dev, const int32_t* row
  *   h_out[r, :] = act( h_src[r, :] . W[0:d_in, :] + agg[k, :] . W[d_in:2*d_in, :] + bias ),  r = rows[k]
  *   act = ReLU if relu != 0, identity otherwise.
  *   h_src (in_dtype; F16 rows are converted to BF16 when w_dtype is BF16), agg (F32 when w_dtype is F32, BF16 when BF16)
- *   W [2*d_in x d_out] row-major, w_dtype F32 (fp32 MFMA, fp32 accumulate) or BF16 (bf16 MFMA, fp32 accumulate)
+ *   W [2*d_in x d_out] row-major, w_dtype F32 or BF16 (bf16 MFMA, fp32 accumulate).
+ *   F32: every product of two fp32 values is formed exactly enough for the 1e-5 bar of the path: either by the fp32
+ *   matrix instructions, or (the default where the shape allows) from an exact three-way bf16 split of both factors,
+ *   six partial products on the bf16 matrix instructions (the dropped ones are below 2^-26 of the product); sums are
+ *   carried in fp32 over 32 k values and in fp64 across them. Inputs are expected finite and below 2^127 in
+ *   magnitude (the split of a larger value overflows to infinity).
  *   bias float[d_out] (device); h_out rows of out_dtype (F32 or BF16) written at position rows[k]
  *   d_in must be a multiple of 4 (8 for 16-bit inputs), d_out a multiple of 4.
  */
