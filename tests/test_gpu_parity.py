@@ -577,23 +577,43 @@ def test_iterations_medium(env):
 
 
 def test_iterations_large_hbm_full_size(env):
-    """The benchmarked workload at its full size (111 M nodes, 57 GB table in HBM, 2 x 11.1 M cache slots), more
-    iterations than the staleness bound so that entries age out; index work compared in full every iteration,
-    gathered rows on a sample, numerics every 8th iteration."""
+    """The benchmarked workload at its full size (111 M nodes, 57 GB table in HBM, 2 x 11.1 M cache slots) in the launch
+    configuration bench.py times (fused loader, whole-pass top-down, fetch and update calls), more iterations than the
+    staleness bound so that entries age out; index work compared in full every iteration, the layer-1 nodes' own
+    feature rows on a sample, numerics every 8th iteration."""
     torch, B = env
     w = wl.WORKLOADS["large_hbm"]
-    hits, worst = run_workload_parity(torch, w, 24, check_numeric_every=8, sample_rows=20000)
+    hits, worst = run_workload_parity(torch, w, 24, check_numeric_every=8, sample_rows=20000, fused=True)
     print(f"large_hbm: {hits} hits, worst rel err {worst:.3e}")
     assert hits > 1000
 
 
+def test_iterations_large_hbm_full_size_separate_calls(env):
+    """The same workload through the per-layer calls (fg_lookup_prune incl. layer 0, fg_gather of every surviving input
+    row, fg_aggregate for layer 1, fg_gather of cached rows, fg_cache_update per layer)."""
+    torch, B = env
+    w = wl.WORKLOADS["large_hbm"]
+    hits, worst = run_workload_parity(torch, w, 8, check_numeric_every=4, sample_rows=20000, one_launch_top_down=False)
+    print(f"large_hbm, separate calls: {hits} hits, worst rel err {worst:.3e}")
+    assert hits > 0
+
+
 def test_iterations_large_host_resident(env):
-    """Same graph with the feature table in pinned host memory, gathered zero-copy over the host link."""
+    """Same graph with the feature table in pinned host memory, read zero-copy over the host link by the fused loader
+    (the configuration bench.py --workload large_host times)."""
     torch, B = env
     w = wl.WORKLOADS["large_host"]
-    hits, worst = run_workload_parity(torch, w, 6, check_numeric_every=5, sample_rows=20000)
+    hits, worst = run_workload_parity(torch, w, 6, check_numeric_every=5, sample_rows=20000, fused=True)
     print(f"large_host: {hits} hits, worst rel err {worst:.3e}")
     assert hits > 0
+
+
+def test_iterations_large_host_resident_separate_gather(env):
+    """The host-resident table through fg_gather (every surviving input row copied to HBM first)."""
+    torch, B = env
+    w = wl.WORKLOADS["large_host"]
+    hits, worst = run_workload_parity(torch, w, 3, check_numeric_every=2, sample_rows=20000)
+    print(f"large_host, separate gather: {hits} hits, worst rel err {worst:.3e}")
 
 
 # ------------------------------------------------------------------------------------------------ bf16 path
@@ -645,5 +665,12 @@ def test_iterations_very_large_bf16(env):
     are those of the workload."""
     torch, B = env
     w = wl.WORKLOADS["very_large"].scaled(8)
-    hits, worst = run_workload_parity(torch, w, 8, check_numeric_every=3, sample_rows=20000)
-    print(f"{w.name}: {hits} hits, worst rel err {worst:.3e}")
+    feat = None
+    for fused in (True, False):   # the fused loader (what bench.py times) and the separate gather, on one table
+        g = wl.make_graph(w)
+        if feat is None:
+            from fg_inputs import device as fdev
+            feat = fdev.feature_table(w.seed, w.num_nodes, w.feat_dim, w.feat_dtype, w.feat_location)
+        hits, worst = run_workload_parity(torch, w, 8 if fused else 3, check_numeric_every=3, sample_rows=20000, feat_table=feat,
+                                          fused=fused)
+        print(f"{w.name} (fused loader: {fused}): {hits} hits, worst rel err {worst:.3e}")
