@@ -34,6 +34,10 @@ class ExplicitGraph:
         v = np.asarray(v, dtype=np.int64)
         return self.indptr[v + 1] - self.indptr[v]
 
+    def access_estimate(self):
+        """How often each node is named as an in-neighbour: what a uniform neighbour sampler visits in proportion to."""
+        return np.bincount(self.indices, minlength=self.num_nodes).astype(np.float64)
+
     def neighbour(self, v, slot):
         v = np.asarray(v, dtype=np.int64)
         if self.indices.shape[0] == 0:
@@ -78,6 +82,14 @@ class ChungLuGraph:
     def expected_degree(self, v):
         r = self.id_to_rank(v).astype(np.float64)
         return self.c * (r + 0.5 + self.r0) ** (-self.alpha)
+
+    def access_estimate(self, v):
+        """Proportional to the probability that a neighbour slot names v (every slot is a draw proportional to w)."""
+        return self.expected_degree(v)
+
+    def hottest(self, count):
+        """The `count` nodes with the largest access estimate, largest first: w falls strictly with the rank."""
+        return self.rank_to_id(np.arange(min(int(count), self.num_nodes), dtype=np.int64)).astype(np.int32)
 
     def degree(self, v):
         v = np.asarray(v, dtype=np.int64)

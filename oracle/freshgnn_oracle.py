@@ -13,6 +13,8 @@ once to the storage type:
   bottom-up  (Alg. 1, the cache fetch line and the f_W line; Eq. 1): `gather`,
              `aggregate`, `linear`
   update     (Alg. 1, Update line; Sections 4.1.1, 4.1.2, 4.2): `cache_update`
+  feature side of the bidirectional cache (Section 4.2): `BidirectionalCache`, `hot_order`;
+             `iteration(..., feature_side=...)` loads raw features through it
 
 Where the paper leaves something open (the Update procedure has no printed body;
 mini-batch layout; percentile ties; slot capacity) the reading taken is stated in
@@ -22,7 +24,8 @@ Pins (tests marked "not gpu"): dense whole-graph recursion of Eq. 1 on small
 graphs with full neighbourhoods; closed forms of the mean; identity-panel
 weights; a depth-first "needed set" for the pruning; a dictionary model of the
 cache; hand-worked admit/evict/staleness/ring traces; the degenerate settings of
-Section 4.1.3. The I/O-saving percentages the paper reports depend on its
+Section 4.1.3; for the shared buffer a byte-by-byte model of what has been overwritten,
+a hand-worked displacement trace, and the bit-identity of every loaded feature row. The I/O-saving percentages the paper reports depend on its
 datasets and real gradients: parity unpinned for those, they are not reproduced.
 """
 import numpy as np
@@ -56,6 +59,22 @@ def storage_numpy_dtype(dtype):
     return {"f32": np.float32, "f16": np.float16, "bf16": np.float32}[dtype]
 
 
+def element_bytes(dtype):
+    return {"f32": 4, "f16": 2, "bf16": 2}[dtype]
+
+
+def row_image(values, dtype):
+    """The bytes a row of storage type `dtype` occupies in memory (little endian); bf16 = upper half of the fp32 word."""
+    if dtype == "f32":
+        return np.ascontiguousarray(values, dtype=np.float32).view(np.uint8)
+    if dtype == "f16":
+        return np.ascontiguousarray(values, dtype=np.float16).view(np.uint8)
+    if dtype == "bf16":
+        bits = np.ascontiguousarray(values, dtype=np.float32).view(np.uint32) >> np.uint32(16)
+        return bits.astype(np.uint16).view(np.uint8)
+    raise ValueError(dtype)
+
+
 # --------------------------------------------------------------------------- the cache C^(l)
 
 class HistoricalCache:
@@ -74,7 +93,10 @@ class HistoricalCache:
     is exact.
     """
 
-    def __init__(self, num_nodes, capacity, dim, t_stale, dtype="f32"):
+    def __init__(self, num_nodes, capacity, dim, t_stale, dtype="f32", storage=None):
+        """`storage`: optional uint8 array of capacity * dim * element_bytes bytes in which every admitted row is
+        also laid down byte for byte (slot s at s * row bytes): the ring's share of a buffer it has in common
+        with raw features (`BidirectionalCache`)."""
         self.num_nodes = int(num_nodes)
         self.capacity = int(capacity)
         self.dim = int(dim)
@@ -85,6 +107,17 @@ class HistoricalCache:
         self.slot_stamp = np.zeros(self.capacity, dtype=np.int32)
         self.table = np.zeros((self.capacity, self.dim), dtype=storage_numpy_dtype(dtype))
         self.head = 0
+        self.used = 0            # slots written at least once: 0 .. used-1 (the ring fills upwards until it first wraps)
+        self.storage = storage
+        self.row_bytes = self.dim * element_bytes(dtype)
+        if storage is not None:
+            assert storage.dtype == np.uint8 and storage.shape == (self.capacity * self.row_bytes,)
+
+    def store(self, s, row):
+        """Write an embedding into slot s (the table and, if the ring lives in a shared buffer, its bytes there)."""
+        self.table[s] = row
+        if self.storage is not None:
+            self.storage[s * self.row_bytes:(s + 1) * self.row_bytes] = row_image(self.table[s], self.dtype)
 
     def slot_of(self, v, i):
         """Slot holding a usable embedding of node v at iteration i, or -1 (the set C^(l) is {v: slot_of >= 0})."""
@@ -106,6 +139,107 @@ class HistoricalCache:
             if v >= 0 and self.slot_of(v, i) == s:
                 out[v] = (s, int(self.slot_stamp[s]))
         return out
+
+
+# --------------------------------------------------------------------------- feature side (Section 4.2)
+
+RING_ALIGN = 256   # a ring's first byte in the shared buffer is rounded up to this
+
+
+def hot_order(score, count):
+    """The `count` nodes with the largest estimated saved memory access, largest first (ties: smaller id first).
+
+    The paper orders the raw features it caches by that estimate without defining it; `score[v]` is whatever
+    estimate the caller has (the tests and workloads use how often v is named as a neighbour).
+    """
+    score = np.asarray(score, dtype=np.float64)
+    order = sorted(range(len(score)), key=lambda v: (-score[v], v))
+    return np.asarray(order[:int(count)], dtype=np.int32)
+
+
+class BidirectionalCache:
+    """The device buffer that raw features and historical embeddings share (Section 4.2, "bidirectional cache").
+
+    One buffer of `buffer_bytes` bytes.
+      * Embedding side, from the left end: the ring of cached layer 1, then layer 2, ...; a ring starts at the
+        next multiple of RING_ALIGN and slot s of ring l occupies the bytes [base_l + s*row_l, base_l + (s+1)*row_l).
+        The rings are `HistoricalCache` objects that lay their admitted rows down in this buffer.
+      * Feature side, from the right end: before training the raw feature rows of the hot nodes are written, the
+        one of rank r (0 = largest estimated saved access) at [B - (r+1)*w, B - r*w), w = bytes of a feature row.
+        The more valuable a row, the farther it is from the embeddings.
+      * Junction: the two sides may overlap. A feature row is lost the moment an embedding is written over any of
+        its bytes, and not earlier. A ring hands out slots 0, 1, 2, ... until it first wraps, so the bytes ring l
+        has written are exactly [base_l, base_l + used_l*row_l).
+    Reading taken where the paper is silent: one ring per cached layer with the preset capacity (the rings do not
+    grow past it), laid out in layer order; a feature row straddling the end of a ring's written part counts as lost.
+    """
+
+    def __init__(self, num_nodes, capacities, dims, t_stale, dtype, buffer_bytes):
+        self.num_nodes = int(num_nodes)
+        self.buffer_bytes = int(buffer_bytes)
+        self.buf = np.zeros(self.buffer_bytes, dtype=np.uint8)
+        self.rings = {}
+        self.ring_base = {}
+        at = 0
+        for k, (cap, dim) in enumerate(zip(capacities, dims)):
+            l = k + 1
+            at = -(-at // RING_ALIGN) * RING_ALIGN
+            size = int(cap) * int(dim) * element_bytes(dtype)
+            assert at + size <= self.buffer_bytes, "the rings do not fit into the buffer"
+            self.ring_base[l] = at
+            self.rings[l] = HistoricalCache(num_nodes, cap, dim, t_stale, dtype, storage=self.buf[at:at + size])
+            at += size
+        self.rank_of = np.full(self.num_nodes, -1, dtype=np.int32)   # node -> rank of its row on the feature side
+        self.n_feat = 0
+        self.feat_row_bytes = 0
+        self.feat_dtype = None
+
+    def fill_features(self, hot_ids, feature_rows, feat_dtype):
+        """Populate the buffer with the rows of `hot_ids` (hottest first, distinct) before any embedding is admitted."""
+        assert all(r.used == 0 for r in self.rings.values()), "features are placed before training starts"
+        hot_ids = np.asarray(hot_ids, dtype=np.int64)
+        assert len(np.unique(hot_ids)) == len(hot_ids)
+        rows = np.asarray(feature_rows(hot_ids))
+        w = rows.shape[1] * element_bytes(feat_dtype) if len(hot_ids) else 0
+        assert len(hot_ids) * w <= self.buffer_bytes, "more rows than the buffer holds"
+        self.rank_of[:] = -1
+        self.n_feat, self.feat_row_bytes, self.feat_dtype = len(hot_ids), w, feat_dtype
+        B = self.buffer_bytes
+        for r, v in enumerate(hot_ids):
+            self.buf[B - (r + 1) * w:B - r * w] = row_image(rows[r], feat_dtype)
+            self.rank_of[v] = r
+
+    def feature_rank(self, v):
+        """Rank of node v's row if it is on the feature side and no embedding has been written over it, else -1."""
+        r = int(self.rank_of[v])
+        if r < 0:
+            return -1
+        lo = self.buffer_bytes - (r + 1) * self.feat_row_bytes
+        hi = lo + self.feat_row_bytes
+        for l, ring in self.rings.items():
+            w_lo = self.ring_base[l]
+            w_hi = w_lo + ring.used * ring.row_bytes
+            if ring.used > 0 and lo < w_hi and hi > w_lo:   # overlap with a non-empty written range
+                return -1
+        return r
+
+    def load(self, ids, feature_rows):
+        """Load_feature through the feature side: rows of `ids`, those still cached taken from the buffer, the rest
+        from the table. Returns (rows, from_buffer flags); the rows are bit copies either way."""
+        ids = np.asarray(ids, dtype=np.int64)
+        ranks = np.asarray([self.feature_rank(v) for v in ids], dtype=np.int64)
+        miss = ranks < 0
+        if miss.all():
+            return np.asarray(feature_rows(ids)), ~miss
+        B, w = self.buffer_bytes, self.feat_row_bytes
+        np_dt = storage_numpy_dtype(self.feat_dtype)
+        out = np.zeros((len(ids), w // element_bytes(self.feat_dtype)), dtype=np_dt)
+        if miss.any():
+            out[miss] = feature_rows(ids[miss])
+        for k in np.nonzero(~miss)[0]:
+            r = ranks[k]
+            out[k] = self.buf[B - (r + 1) * w:B - r * w].view(np_dt)
+        return out, ~miss
 
 
 # --------------------------------------------------------------------------- top-down pass
@@ -257,10 +391,11 @@ def cache_update(cache, i, ids, live, hit, gnorm, p_grad, h):
                 overwritten += 1
             cache.slot_node[s] = ids[j]
             cache.slot_stamp[s] = i
-            cache.table[s] = h[j]
+            cache.store(s, h[j])
             cache.map[ids[j]] = s
             admitted += 1
     cache.head = (head + admitted) % cache.capacity if cache.capacity else 0
+    cache.used = cache.capacity if head + admitted >= cache.capacity else max(cache.used, head + admitted)
     return dict(admitted=admitted, evicted_by_gradient=evicted, overwritten=overwritten, dropped_overflow=dropped, tau=tau)
 
 
@@ -282,13 +417,14 @@ def check_minibatch(mb):
 
 
 def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_dtype="f32", compute_dtype="f32",
-              update=True):
+              update=True, feature_side=None):
     """One pass of Algorithm 1 without loss/backward (gradient norms are given).
 
     mb        sampled mini-batch (its `end` arrays are modified: pruning)
     caches    {l: HistoricalCache} for l = 1..L-1 (missing or None: that layer is never looked up)
     feature_rows(ids) -> raw feature rows; weights[l] = (W_l, b_l); gnorms[l] = norms by position
     dims      [d_0..d_L]
+    feature_side   optional BidirectionalCache whose rings are `caches`: raw features are loaded through it
     Types: H(0) in feat_dtype; H(l), AGG(l) for l >= 1 in compute_dtype except H(L) which is fp32.
     In the bf16 setting the own rows and the mean are rounded to bf16 before the product and W is bf16.
     Returns a record of every intermediate the GPU path exposes.
@@ -309,7 +445,12 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
     AGG = [None] * (L + 1)
     H[0] = np.zeros((len(mb.ids[0]), dims[0]), dtype=storage_numpy_dtype(feat_dtype))
     input_pos = look[0]["normal_pos"]
-    gather(feature_rows, mb.ids[0][input_pos], H[0], input_pos)
+    from_buffer = np.zeros(len(input_pos), dtype=bool)
+    if feature_side is None:
+        gather(feature_rows, mb.ids[0][input_pos], H[0], input_pos)
+    elif len(input_pos):
+        rows, from_buffer = feature_side.load(mb.ids[0][input_pos], feature_rows)
+        H[0][input_pos] = rows
     for l in range(1, L + 1):
         out_dtype = "f32" if l == L else compute_dtype
         H[l] = np.zeros((len(mb.ids[l]), dims[l]), dtype=storage_numpy_dtype(out_dtype))
@@ -332,5 +473,5 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
         for l in range(1, L):
             if caches.get(l) is not None:
                 stats[l] = cache_update(caches[l], i, mb.ids[l], live[l], look[l]["hit"], gnorms[l], p_grad, H[l])
-    rec.update(live=live, look=look, H=H, AGG=AGG, stats=stats)
+    rec.update(live=live, look=look, H=H, AGG=AGG, stats=stats, feature_from_buffer=from_buffer)
     return rec

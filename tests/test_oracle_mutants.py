@@ -7,6 +7,7 @@ import textwrap
 import pytest
 
 from oracle import freshgnn_oracle as O
+from tests import test_oracle_feature_side as F
 from tests import test_oracle_pins as P
 
 PINS = [
@@ -24,6 +25,14 @@ PINS = [
     (P.test_trace_ring, [()]),
     (P.test_staleness_boundary, [()]),
     (P.test_cache_matches_dictionary_model, [(5, 2, 0.5), (16, 4, 0.9), (3, 1, 1.0), (40, 50, 0.3)]),
+    (F.test_trace_junction, [()]),
+    (F.test_validity_equals_untouched_bytes_and_rows_stay_bit_identical,
+     [(0, "f32", "f32", 4096, [5, 3], [12, 20], 8, 128), (1, "f32", "f32", 8192, [7, 4], [36, 8], 12, 170),
+      (2, "bf16", "f16", 4096, [9, 6], [24, 40], 24, 85), (4, "f32", "f32", 2048, [3, 2, 2], [8, 8, 8], 8, 10)]),
+    (F.test_ring_rows_are_laid_down_in_the_shared_buffer, [()]),
+    (F.test_one_ring_keeps_a_prefix_of_the_hot_list, [()]),
+    (F.test_hot_order_properties, [()]),
+    (F.test_feature_side_changes_where_rows_come_from_and_nothing_else, [()]),
 ]
 
 # (owner, function, text in its source, replacement)
@@ -52,12 +61,40 @@ MUTANTS = [
      "cache.head = head"),
     ("the ring does not wrap", None, "cache_update", "s = (head + admitted) % cache.capacity", "s = min(head + admitted, cache.capacity - 1)"),
     ("admission beyond the capacity overwrites this update's own slots", None, "cache_update", "if admitted >= cache.capacity:", "if False:"),
-    ("the wrong row is stored", None, "cache_update", "cache.table[s] = h[j]", "cache.table[s] = h[admitted]"),
+    ("the wrong row is stored", None, "cache_update", "cache.store(s, h[j])", "cache.store(s, h[admitted])"),
     ("a normal row does not keep its own position live", None, "lookup_prune", "live_src[j] = True", "pass"),
     ("pruned nodes are looked up", None, "lookup_prune", "if not live[j]:\n            continue", "if False:\n            continue"),
     ("rows that are not normal keep their neighbours", None, "lookup_prune", "end[j] = start[j]", "pass"),
     ("neighbours of hit rows stay live", None, "lookup_prune", "if normal[j]:", "if live[j]:"),
     ("hits are listed as normal too", None, "lookup_prune", "        else:\n            normal_pos.append(j)", "        normal_pos.append(j)"),
+    ("a feature row cut by the end of the written part still counts as intact", "BidirectionalCache", "feature_rank",
+     "lo < w_hi and hi > w_lo", "hi <= w_hi and hi > w_lo"),
+    ("a feature row touching the written part from the right counts as lost", "BidirectionalCache", "feature_rank",
+     "lo < w_hi and hi > w_lo", "lo <= w_hi and hi > w_lo"),
+    ("an empty ring displaces the feature row lying across its first byte", "BidirectionalCache", "feature_rank",
+     "ring.used > 0 and lo", "lo"),
+    ("only the first ring displaces features", "BidirectionalCache", "feature_rank",
+     "for l, ring in self.rings.items():", "for l, ring in list(self.rings.items())[:1]:"),
+    ("the written part is measured in feature rows", "BidirectionalCache", "feature_rank",
+     "w_lo + ring.used * ring.row_bytes", "w_lo + ring.used * self.feat_row_bytes"),
+    ("the hottest row is placed next to the embeddings", "BidirectionalCache", "fill_features",
+     "self.rank_of[v] = r", "self.rank_of[v] = len(hot_ids) - 1 - r"),
+    ("feature rows are placed from the left end", "BidirectionalCache", "fill_features",
+     "self.buf[B - (r + 1) * w:B - r * w] = row_image(rows[r], feat_dtype)", "self.buf[r * w:(r + 1) * w] = row_image(rows[r], feat_dtype)"),
+    ("the second ring starts right after the first without alignment", "BidirectionalCache", "__init__",
+     "at = -(-at // RING_ALIGN) * RING_ALIGN", "at = at"),
+    ("the written part of a ring shrinks back when the header wraps", None, "cache_update",
+     "cache.used = cache.capacity if head + admitted >= cache.capacity else max(cache.used, head + admitted)",
+     "cache.used = (head + admitted) % cache.capacity"),
+    ("the written part stops growing one slot early", None, "cache_update",
+     "max(cache.used, head + admitted)", "max(cache.used, head + admitted - 1)"),
+    ("rings do not write their rows into the shared buffer", "HistoricalCache", "store",
+     "if self.storage is not None:", "if False:"),
+    ("bf16 rows are laid down as their low halves", None, "row_image", ">> np.uint32(16)", "& np.uint32(0xFFFF)"),
+    ("the hot list is in ascending order of the estimate", None, "hot_order", "(-score[v], v)", "(score[v], v)"),
+    ("ties in the hot list go to the larger id", None, "hot_order", "(-score[v], v)", "(-score[v], -v)"),
+    ("cached feature rows are read at the neighbouring rank", "BidirectionalCache", "load",
+     "out[k] = self.buf[B - (r + 1) * w:B - r * w].view(np_dt)", "out[k] = self.buf[B - (r + 2) * w:B - (r + 1) * w].view(np_dt) if r + 2 <= self.n_feat else 0"),
 ]
 
 
