@@ -8,6 +8,8 @@
  *   bottom-up  for l = 1..L:    fg_gather (cached rows of V_cache; or fg_cache_fetch_all once for all layers),
  *                               fg_aggregate, fg_linear
  *   update     fg_cache_update  for l = 1..L-1   (or fg_cache_update_all once)
+ * With raw features sharing the cache's buffer (fg_cache_create_bidirectional, fg_cache_fill_features) the loader is
+ * fg_gather_features / fg_gather_aggregate_features.
  *
  * Conventions
  *   - Every pointer named *_dev or documented "device" is device memory owned by the caller
@@ -71,14 +73,54 @@ int32_t fg_version(void);
  * n_layers: number of cached layers; layer indices 1..n_layers are valid in the calls below
  * (for an L-layer model pass L-1). capacity[k], dim[k]: slots and row width of layer k+1 (host arrays).
  * The library allocates (hipMalloc) and owns all cache memory:
- *   num_nodes*4 + capacity*(dim*sizeof(dtype) + 8) bytes per layer.
+ *   num_nodes*4 + capacity*(dim*sizeof(dtype) + 8) bytes per layer; the slot tables of all layers lie in one buffer.
  * The initialisation is queued on `stream`. *out is NULL on error.
  */
 fg_status_t fg_cache_create(fg_cache_t** out, int64_t num_nodes, int32_t n_layers, const int64_t* capacity,
                             const int32_t* dim, fg_dtype_t dtype, int32_t t_stale, void* stream);
+
+/*
+ * The bidirectional cache of Section 4.2: the same historical embedding cache, created inside a buffer of
+ * `buffer_bytes` bytes (a multiple of 256, at least the rings' size) that raw features share.
+ *   Embedding side: the slot table ("ring") of layer 1 starts at byte 0, every further layer's at the next
+ *   multiple of 256 after the previous ring; slot s of a ring occupies [base + s*row, base + (s+1)*row).
+ *   Feature side: fg_cache_fill_features places raw feature rows from the right end of the buffer.
+ *   Junction: the two sides may overlap. A feature row is lost as soon as an embedding has been written over any
+ *   of its bytes and not earlier; a ring writes its slots in increasing order until it first wraps, so what ring l
+ *   has written is [base_l, base_l + used_l*row_l), used_l = number of distinct slots written since create/clear.
+ * At most 8 cached layers. fg_cache_create is this call with a buffer that just holds the rings.
+ */
+fg_status_t fg_cache_create_bidirectional(fg_cache_t** out, int64_t num_nodes, int32_t n_layers, const int64_t* capacity,
+                                          const int32_t* dim, fg_dtype_t dtype, int32_t t_stale, int64_t buffer_bytes,
+                                          void* stream);
+/*
+ * Populates the feature side before training (Section 4.2): the raw feature row of hot_ids_dev[r] (device int32,
+ * distinct node ids in decreasing order of estimated saved memory access; r = 0 is the most valuable) is copied from
+ * `table` (device, or host memory mapped into the device address space; row v at table + v*src_stride) to the bytes
+ * [buffer_bytes - (r+1)*row_bytes, buffer_bytes - r*row_bytes) of the buffer, so the least valuable rows are the
+ * first an advancing ring overwrites. An id outside [0, min(num_nodes, table_rows)) leaves its rank unused.
+ * Only valid while the embedding side is empty (after create or fg_cache_clear; FG_ERR_STATE otherwise);
+ * n_hot*row_bytes must fit into the buffer; row_bytes a multiple of 16, table and src_stride 16-byte aligned.
+ * The first call allocates a node -> rank array of num_nodes*4 bytes. fg_cache_clear drops the feature side.
+ */
+fg_status_t fg_cache_fill_features(fg_cache_t* cache, const int32_t* hot_ids_dev, int64_t n_hot, const void* table,
+                                   int64_t table_rows, int64_t src_stride, int64_t row_bytes, void* stream);
+/*
+ * For k < *count_dev (NULL = max_count): rank_out_dev[k] = rank of node ids_dev[k]'s row on the feature side if it
+ * was placed and is still intact, else -1 (also for an id outside [0, num_nodes)). *n_found_dev (int64 device, may
+ * be NULL) = how many are >= 0. rank_out_dev may be NULL. For tests and monitoring; the loaders below look up inline.
+ */
+fg_status_t fg_feature_lookup(const fg_cache_t* cache, const int32_t* ids_dev, const int64_t* count_dev, int64_t max_count,
+                              int32_t* rank_out_dev, int64_t* n_found_dev, void* stream);
+/* The shared buffer (device pointer; *buffer_bytes_out = its size, may be NULL), rows placed on the feature side,
+ * and the byte offset of a layer's ring in the buffer (-1 on error). For tests and monitoring. */
+const void* fg_cache_buffer(const fg_cache_t* cache, int64_t* buffer_bytes_out);
+int64_t fg_cache_feature_rows(const fg_cache_t* cache);
+int64_t fg_cache_ring_offset(const fg_cache_t* cache, int32_t layer);
+
 /* Frees everything the cache owns. Synchronises the device first. NULL is accepted. */
 fg_status_t fg_cache_destroy(fg_cache_t* cache);
-/* Empties all layers (as after create), queued on `stream`. */
+/* Empties all layers (as after create) and drops the feature side, queued on `stream`. */
 fg_status_t fg_cache_clear(fg_cache_t* cache, void* stream);
 /* Device pointer to the slot table of `layer` ([capacity x dim], row stride dim*sizeof(dtype)); NULL on error. */
 const void* fg_cache_table(const fg_cache_t* cache, int32_t layer);
@@ -199,6 +241,18 @@ fg_status_t fg_gather(const void* table, int64_t table_rows, int64_t src_stride,
                       void* stream);
 
 /*
+ * Load_feature through the feature side of the bidirectional cache (Section 4.2): fg_gather with node ids as
+ * src_index, where the row of a node that fg_feature_lookup would find is read from the shared buffer in HBM
+ * instead of from `table`. The result is the same bit copy as fg_gather's; only where the bytes come from differs.
+ * table_rows <= the cache's num_nodes; row_bytes must equal the placed rows' size; everything 16-byte aligned.
+ * Without a populated feature side this is fg_gather.
+ */
+fg_status_t fg_gather_features(const fg_cache_t* cache, const void* table, int64_t table_rows, int64_t src_stride,
+                               int64_t row_bytes, const int32_t* ids_dev, const int32_t* dst_pos_dev, const int64_t* count_dev,
+                               int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride, int32_t table_kind,
+                               void* stream);
+
+/*
  * Mean aggregation over sampled neighbours (AGG of Eq. 1 with the mean aggregator), for the rows listed:
  *   agg[k, :] = (1/deg) * sum_{e in [row_start[r], row_end[r])} h_src[col[e], :],  r = rows[k], k < *n_rows_dev;
  *   a row without neighbours gives zeros.
@@ -234,6 +288,14 @@ fg_status_t fg_gather_aggregate(const int32_t* row_start_dev, const int32_t* row
                                 int64_t table_rows, int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg,
                                 int64_t agg_stride, fg_dtype_t out_dtype, void* h_self_out, int64_t h_self_stride,
                                 int32_t n_self_rows, void* stream);
+
+/* fg_gather_aggregate reading through the feature side like fg_gather_features (same arguments and result). */
+fg_status_t fg_gather_aggregate_features(const fg_cache_t* cache, const int32_t* row_start_dev, const int32_t* row_end_dev,
+                                         const int32_t* col_dev, int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev,
+                                         const int64_t* n_rows_dev, int64_t max_rows, const int32_t* src_ids_dev, int32_t n_src,
+                                         const void* table, int64_t table_rows, int64_t src_stride, int32_t dim,
+                                         fg_dtype_t in_dtype, void* agg, int64_t agg_stride, fg_dtype_t out_dtype,
+                                         void* h_self_out, int64_t h_self_stride, int32_t n_self_rows, void* stream);
 
 /*
  * Dense update of a GraphSAGE-mean layer (phi of Eq. 1; the f_W line of Algorithm 1), for the rows listed:

@@ -27,6 +27,15 @@ SIGNATURES = {
     "fg_last_error": (C.c_char_p, []),
     "fg_version": (_i32, []),
     "fg_cache_create": (_i32, [C.POINTER(_p), _i64, _i32, C.POINTER(_i64), C.POINTER(_i32), _i32, _i32, _p]),
+    "fg_cache_create_bidirectional": (_i32, [C.POINTER(_p), _i64, _i32, C.POINTER(_i64), C.POINTER(_i32), _i32, _i32, _i64, _p]),
+    "fg_cache_fill_features": (_i32, [_p, _p, _i64, _p, _i64, _i64, _i64, _p]),
+    "fg_feature_lookup": (_i32, [_p, _p, _p, _i64, _p, _p, _p]),
+    "fg_cache_buffer": (_p, [_p, C.POINTER(_i64)]),
+    "fg_cache_feature_rows": (_i64, [_p]),
+    "fg_cache_ring_offset": (_i64, [_p, _i32]),
+    "fg_gather_features": (_i32, [_p, _p, _i64, _i64, _i64, _p, _p, _p, _i64, _p, _i64, _i64, _i32, _p]),
+    "fg_gather_aggregate_features": (_i32, [_p, _p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _p, _i64, _i64, _i32, _i32, _p,
+                                            _i64, _i32, _p, _i64, _i32, _p]),
     "fg_cache_destroy": (_i32, [_p]),
     "fg_cache_clear": (_i32, [_p, _p]),
     "fg_cache_table": (_p, [_p, _i32]),
@@ -121,6 +130,37 @@ def fg_cache_create(num_nodes, capacity, dim, dtype, t_stale, stream=None):
     return handle
 
 
+def fg_cache_create_bidirectional(num_nodes, capacity, dim, dtype, t_stale, buffer_bytes, stream=None):
+    n = len(capacity)
+    handle = _p()
+    cap = (_i64 * max(n, 1))(*capacity)
+    dm = (_i32 * max(n, 1))(*dim)
+    _check(_lib.fg_cache_create_bidirectional(C.byref(handle), num_nodes, n, cap, dm, dtype, t_stale, buffer_bytes, stream))
+    return handle
+
+
+def fg_cache_fill_features(cache, hot_ids, n_hot, table, table_rows, src_stride, row_bytes, stream=None):
+    _check(_lib.fg_cache_fill_features(cache, ptr(hot_ids), n_hot, ptr(table), table_rows, src_stride, row_bytes, stream))
+
+
+def fg_feature_lookup(cache, ids, count, max_count, rank_out, n_found, stream=None):
+    _check(_lib.fg_feature_lookup(cache, ptr(ids), ptr(count), max_count, ptr(rank_out), ptr(n_found), stream))
+
+
+def fg_cache_buffer(cache):
+    """(device address, bytes) of the buffer embeddings and raw features share."""
+    n = _i64(0)
+    return _lib.fg_cache_buffer(cache, C.byref(n)), n.value
+
+
+def fg_cache_feature_rows(cache):
+    return _lib.fg_cache_feature_rows(cache)
+
+
+def fg_cache_ring_offset(cache, layer):
+    return _lib.fg_cache_ring_offset(cache, layer)
+
+
 def fg_cache_destroy(cache):
     _check(_lib.fg_cache_destroy(cache))
 
@@ -173,6 +213,12 @@ def fg_gather(table, table_rows, src_stride, row_bytes, src_index, dst_pos, coun
                           ptr(dst), dst_rows, dst_stride, table_kind, stream))
 
 
+def fg_gather_features(cache, table, table_rows, src_stride, row_bytes, ids, dst_pos, count, max_count, dst, dst_rows, dst_stride,
+                       table_kind=0, stream=None):
+    _check(_lib.fg_gather_features(cache, ptr(table), table_rows, src_stride, row_bytes, ptr(ids), ptr(dst_pos), ptr(count),
+                                   max_count, ptr(dst), dst_rows, dst_stride, table_kind, stream))
+
+
 def fg_aggregate(row_start, row_end, col, nnz, n_block_rows, rows, n_rows, max_rows, h_src, n_src, src_stride, dim, in_dtype,
                  agg, agg_stride, out_dtype, stream=None):
     _check(_lib.fg_aggregate(ptr(row_start), ptr(row_end), ptr(col), nnz, n_block_rows, ptr(rows), ptr(n_rows), max_rows,
@@ -185,6 +231,15 @@ def fg_gather_aggregate(row_start, row_end, col, nnz, n_block_rows, rows, n_rows
     _check(_lib.fg_gather_aggregate(ptr(row_start), ptr(row_end), ptr(col), nnz, n_block_rows, ptr(rows), ptr(n_rows), max_rows,
                                     ptr(src_ids), n_src, ptr(table), table_rows, src_stride, dim, in_dtype, ptr(agg),
                                     agg_stride, out_dtype, ptr(h_self_out), h_self_stride, n_self_rows, stream))
+
+
+def fg_gather_aggregate_features(cache, row_start, row_end, col, nnz, n_block_rows, rows, n_rows, max_rows, src_ids, n_src, table,
+                                 table_rows, src_stride, dim, in_dtype, agg, agg_stride, out_dtype, h_self_out=None,
+                                 h_self_stride=0, n_self_rows=0, stream=None):
+    _check(_lib.fg_gather_aggregate_features(cache, ptr(row_start), ptr(row_end), ptr(col), nnz, n_block_rows, ptr(rows),
+                                             ptr(n_rows), max_rows, ptr(src_ids), n_src, ptr(table), table_rows, src_stride, dim,
+                                             in_dtype, ptr(agg), agg_stride, out_dtype, ptr(h_self_out), h_self_stride,
+                                             n_self_rows, stream))
 
 
 def fg_linear(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows, n_rows, max_rows, d_in, d_out, W, w_dtype, bias, relu,

@@ -111,13 +111,15 @@ __device__ __forceinline__ u32x4 load_piece(const char* p) {
 // pieces = 16-byte pieces per row (may exceed `lanes`, then a lane loops).
 // INDIRECT: h_src is a table indexed by node id and src_ids[] maps a neighbour position to its id (the fused
 // loader + first-layer aggregation); table rows are then read with streaming loads, once each.
-template <int IN, int OUT, bool INDIRECT>
+// FEAT (with INDIRECT): a node whose raw features are still on the feature side of the shared buffer (Section 4.2)
+// is read from there. The staged entry of such a neighbour is -2 - rank instead of the node id.
+template <int IN, int OUT, bool INDIRECT, bool FEAT>
 __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
     const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ col,
     int64_t nnz, int n_block_rows, const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev,
     int64_t max_rows, const char* __restrict__ h_src, int64_t n_src, int64_t src_stride, int pieces, char* __restrict__ agg,
     int64_t agg_stride, int lanes_log2, const int32_t* __restrict__ src_ids, int n_ids, char* __restrict__ self_out,
-    int64_t self_stride, int n_self) {
+    int64_t self_stride, int n_self, fg_feat_side F) {
     constexpr int PER = Elem<IN>::PER16;
     constexpr int OUT_BYTES = (OUT == FG_F32 ? 4 : 2) * PER;
     extern __shared__ int32_t nb_lds[];  // [groups_per_block][AGG_MAX_STAGE]
@@ -141,7 +143,13 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
         const char* self_row = nullptr;
         if (INDIRECT && self_out && r >= 0 && r < n_ids && r < n_self) {
             const int32_t v = src_ids[r];
-            if (v >= 0 && v < n_src) self_row = h_src + (int64_t)v * src_stride;
+            if (v >= 0 && v < n_src) {
+                self_row = h_src + (int64_t)v * src_stride;
+                if constexpr (FEAT) {
+                    const int32_t fr = fg_feature_rank(F, v);
+                    if (fr >= 0) self_row = F.end - (int64_t)(fr + 1) * F.row_bytes;
+                }
+            }
         }
         for (int p0 = 0; p0 < pieces; p0 += lanes) {
             const int piece = p0 + lane;
@@ -158,6 +166,12 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
                 for (int t = lane; t < cnt; t += lanes) {
                     int32_t c = col[s0 + base + t];
                     if (INDIRECT) c = (c >= 0 && c < n_ids) ? src_ids[c] : -1;
+                    if constexpr (FEAT) {
+                        if (c >= 0 && c < n_src) {
+                            const int32_t fr = fg_feature_rank(F, c);
+                            if (fr >= 0) c = -2 - fr;
+                        }
+                    }
                     my_nb[t] = c;
                 }
                 // lanes of a group sit in one wavefront when lanes <= 64, so LDS writes above are visible
@@ -169,6 +183,28 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
                 // end of the row (or an out-of-range index) re-reads the batch's first row, which is in cache by
                 // then, and is dropped when the values are added up. Nothing touches a loaded value before the
                 // whole batch has been issued.
+                if constexpr (FEAT) {
+                    // the same batching with a row address per neighbour: the table, or the feature side for an entry <= -2
+                    auto row_of = [&](int32_t c) -> const char* {
+                        if (c <= -2) return F.end - (int64_t)(-1 - c) * F.row_bytes;  // rank -2-c starts at end - (rank+1)*row
+                        return (c >= 0 && c < n_src) ? h_src + (int64_t)c * src_stride : nullptr;
+                    };
+                    for (int t = 0; t < cnt; t += AGG_UNROLL) {
+                        u32x4 raw[AGG_UNROLL];
+                        bool ok[AGG_UNROLL];
+                        const char* first = row_of(my_nb[t]);
+                        const char* safe = first ? first : h_src;
+#pragma unroll
+                        for (int u = 0; u < AGG_UNROLL; ++u) {
+                            const char* p = (t + u < cnt) ? row_of(my_nb[t + u]) : nullptr;
+                            ok[u] = p != nullptr;
+                            raw[u] = load_piece<INDIRECT>((ok[u] ? p : safe) + (int64_t)(active ? piece : 0) * 16);
+                        }
+#pragma unroll
+                        for (int u = 0; u < AGG_UNROLL; ++u)
+                            if (ok[u]) Elem<IN>::unpack(raw[u], acc);
+                    }
+                } else
                 for (int t = 0; t < cnt; t += AGG_UNROLL) {
                     u32x4 raw[AGG_UNROLL];
                     bool ok[AGG_UNROLL];
@@ -200,7 +236,7 @@ static fg_status_t aggregate_common(const char* who, const int32_t* row_start_de
                                     const int64_t* n_rows_dev, int64_t max_rows, const void* h_src, int64_t n_src,
                                     int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
                                     fg_dtype_t out_dtype, const int32_t* src_ids, int32_t n_ids, void* self_out,
-                                    int64_t self_stride, int32_t n_self, void* stream) {
+                                    int64_t self_stride, int32_t n_self, void* stream, const fg_feat_side* feat = nullptr) {
     if (max_rows < 0 || n_block_rows < 0 || n_src < 0 || dim <= 0 || nnz < 0 || n_ids < 0)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (max_rows %lld, n_block_rows %d, n_src %lld, dim %d, nnz %lld)", who,
                 (long long)max_rows, n_block_rows, (long long)n_src, dim, (long long)nnz);
@@ -227,11 +263,27 @@ static fg_status_t aggregate_common(const char* who, const int32_t* row_start_de
     if (blocks > cap) blocks = cap;
     const size_t lds = (size_t)gpb * AGG_MAX_STAGE * sizeof(int32_t);
     hipStream_t st = (hipStream_t)stream;
-#define FG_AGG_LAUNCH(IN, OUT, IND)                                                                                    \
-    hipLaunchKernelGGL((aggregate_mean_kernel<IN, OUT, IND>), dim3((unsigned)blocks), dim3(AGG_THREADS), lds, st,       \
+    const bool with_feat = feat && feat->rank && src_ids;
+    if (with_feat && feat->row_bytes != (int64_t)dim * isz)
+        FG_FAIL(FG_ERR_SHAPE, "%s: rows of %lld bytes differ from the %lld-byte rows on the feature side", who, (long long)dim * isz,
+                (long long)feat->row_bytes);
+    const fg_feat_side F = with_feat ? *feat : fg_feat_side{};
+#define FG_AGG_LAUNCH_F(IN, OUT, IND, FT)                                                                              \
+    hipLaunchKernelGGL((aggregate_mean_kernel<IN, OUT, IND, FT>), dim3((unsigned)blocks), dim3(AGG_THREADS), lds, st,   \
                        row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,          \
-                       (const char*)h_src, n_src, src_stride, pieces, (char*)agg, agg_stride, lg, src_ids, n_ids,          \
-                       (char*)self_out, self_stride, n_self)
+                       (const char*)h_src, n_src, src_stride, pieces, (char*)agg, agg_stride, lg, src_ids, n_ids,       \
+                       (char*)self_out, self_stride, n_self, F)
+#define FG_AGG_LAUNCH(IN, OUT, IND)                       \
+    do {                                                  \
+        if constexpr (IND) {                              \
+            if (with_feat)                                \
+                FG_AGG_LAUNCH_F(IN, OUT, true, true);     \
+            else                                          \
+                FG_AGG_LAUNCH_F(IN, OUT, true, false);    \
+        } else {                                          \
+            FG_AGG_LAUNCH_F(IN, OUT, false, false);       \
+        }                                                 \
+    } while (0)
 #define FG_AGG_OUT(IN, IND)                            \
     do {                                               \
         if (out_dtype == FG_F32)                       \
@@ -257,6 +309,7 @@ static fg_status_t aggregate_common(const char* who, const int32_t* row_start_de
 #undef FG_AGG_IN
 #undef FG_AGG_OUT
 #undef FG_AGG_LAUNCH
+#undef FG_AGG_LAUNCH_F
     FG_LAUNCH_CHECK("aggregate_mean_kernel");
     return FG_OK;
 }
@@ -271,6 +324,25 @@ extern "C" fg_status_t fg_aggregate(const int32_t* row_start_dev, const int32_t*
                             0, stream);
 }
 
+static fg_status_t gather_aggregate_checked(const char* who, const fg_feat_side* feat, const int32_t* row_start_dev,
+                                            const int32_t* row_end_dev, const int32_t* col_dev, int64_t nnz,
+                                            int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                            int64_t max_rows, const int32_t* src_ids_dev, int32_t n_src, const void* table,
+                                            int64_t table_rows, int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg,
+                                            int64_t agg_stride, fg_dtype_t out_dtype, void* h_self_out, int64_t h_self_stride,
+                                            int32_t n_self_rows, void* stream) {
+    if (max_rows > 0 && !src_ids_dev) FG_FAIL(FG_ERR_INVALID_ARG, "%s: src_ids_dev is NULL", who);
+    if (h_self_out) {
+        if (n_self_rows < 0 || h_self_stride < (int64_t)dim * fg_dtype_size(in_dtype))
+            FG_FAIL(FG_ERR_SHAPE, "%s: h_self_out needs n_self_rows >= 0 and a stride of at least one row", who);
+        if (((uintptr_t)h_self_out | (uintptr_t)h_self_stride) & 15)
+            FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_self_out and its stride must be 16-byte aligned", who);
+    }
+    return aggregate_common(who, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows, table,
+                            table_rows, src_stride, dim, in_dtype, agg, agg_stride, out_dtype, src_ids_dev, n_src, h_self_out,
+                            h_self_stride, n_self_rows, stream, feat);
+}
+
 extern "C" fg_status_t fg_gather_aggregate(const int32_t* row_start_dev, const int32_t* row_end_dev,
                                            const int32_t* col_dev, int64_t nnz, int32_t n_block_rows,
                                            const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
@@ -278,14 +350,25 @@ extern "C" fg_status_t fg_gather_aggregate(const int32_t* row_start_dev, const i
                                            int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg,
                                            int64_t agg_stride, fg_dtype_t out_dtype, void* h_self_out,
                                            int64_t h_self_stride, int32_t n_self_rows, void* stream) {
-    if (max_rows > 0 && !src_ids_dev) FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather_aggregate: src_ids_dev is NULL");
-    if (h_self_out) {
-        if (n_self_rows < 0 || h_self_stride < (int64_t)dim * fg_dtype_size(in_dtype))
-            FG_FAIL(FG_ERR_SHAPE, "fg_gather_aggregate: h_self_out needs n_self_rows >= 0 and a stride of at least one row");
-        if (((uintptr_t)h_self_out | (uintptr_t)h_self_stride) & 15)
-            FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather_aggregate: h_self_out and its stride must be 16-byte aligned");
-    }
-    return aggregate_common("fg_gather_aggregate", row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev,
-                            n_rows_dev, max_rows, table, table_rows, src_stride, dim, in_dtype, agg, agg_stride, out_dtype,
-                            src_ids_dev, n_src, h_self_out, h_self_stride, n_self_rows, stream);
+    return gather_aggregate_checked("fg_gather_aggregate", nullptr, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows,
+                                    rows_dev, n_rows_dev, max_rows, src_ids_dev, n_src, table, table_rows, src_stride, dim,
+                                    in_dtype, agg, agg_stride, out_dtype, h_self_out, h_self_stride, n_self_rows, stream);
+}
+
+extern "C" fg_status_t fg_gather_aggregate_features(const fg_cache_t* cache, const int32_t* row_start_dev,
+                                                    const int32_t* row_end_dev, const int32_t* col_dev, int64_t nnz,
+                                                    int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                                    int64_t max_rows, const int32_t* src_ids_dev, int32_t n_src,
+                                                    const void* table, int64_t table_rows, int64_t src_stride, int32_t dim,
+                                                    fg_dtype_t in_dtype, void* agg, int64_t agg_stride, fg_dtype_t out_dtype,
+                                                    void* h_self_out, int64_t h_self_stride, int32_t n_self_rows,
+                                                    void* stream) {
+    if (!cache) FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather_aggregate_features: cache is NULL");
+    if (table_rows > cache->num_nodes)
+        FG_FAIL(FG_ERR_SHAPE, "fg_gather_aggregate_features: the table has %lld rows but the cache was created for %lld nodes",
+                (long long)table_rows, (long long)cache->num_nodes);
+    const fg_feat_side F = fg_feature_side(cache);
+    return gather_aggregate_checked("fg_gather_aggregate_features", &F, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows,
+                                    rows_dev, n_rows_dev, max_rows, src_ids_dev, n_src, table, table_rows, src_stride, dim,
+                                    in_dtype, agg, agg_stride, out_dtype, h_self_out, h_self_stride, n_self_rows, stream);
 }

@@ -2,7 +2,9 @@
 // admission and check-out by gradient norm, Section 4.1.1; staleness bound, Section 4.1.2).
 //
 // State per cached layer, all in HBM: map[num_nodes] (slot of a node or -1), table[capacity x dim],
-// slot_node[capacity], slot_stamp[capacity], head, and 16 KB of selection scratch. A node v is usable at
+// slot_node[capacity], slot_stamp[capacity], head, and 16 KB of selection scratch. The tables of all layers
+// lie in one buffer, from its left end in layer order; raw features can be placed from its right end (the
+// bidirectional cache of Section 4.2, see the feature side at the end of this file). A node v is usable at
 // iteration i iff
 //   s = map[v] >= 0, slot_node[s] == v and 1 <= i - slot_stamp[s] <= t_stale.
 // The back-pointer test makes every location single-writer during an update: admitting into a slot never
@@ -59,6 +61,7 @@ struct CacheRW {
     int32_t* slot_stamp;
     const int64_t* head;  // current ring header
     int64_t* head_next;   // where an update leaves the advanced header (the two swap roles after every update)
+    int64_t* used;        // slots written at least once (what the ring has overwritten of the shared buffer)
     int64_t capacity;
     int64_t num_nodes;
     int64_t iter;
@@ -343,6 +346,11 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(UpdBatch B)
             const long long in = all < c.capacity ? all : c.capacity;
             L.hdr->n_admit = in;
             *c.head_next = (head + in) % c.capacity;
+            const int64_t reach = head + in;  // the ring fills slots upwards until it first wraps
+            if (reach >= c.capacity)
+                *c.used = c.capacity;
+            else if (reach > *c.used)
+                *c.used = reach;
             if (L.stats) {
                 L.stats[0] = in;
                 L.stats[3] = all - in;
@@ -427,12 +435,13 @@ void free_layers(fg_cache_t* c) {
             if (l.map) (void)hipFree(l.map);
             if (l.slot_node) (void)hipFree(l.slot_node);
             if (l.slot_stamp) (void)hipFree(l.slot_stamp);
-            if (l.table) (void)hipFree(l.table);
             if (l.head) (void)hipFree(l.head);
             if (l.sel) (void)hipFree(l.sel);
         }
         delete[] c->layers;
     }
+    if (c->buffer) (void)hipFree(c->buffer);
+    if (c->feat_rank) (void)hipFree(c->feat_rank);
     delete c;
 }
 
@@ -452,54 +461,93 @@ extern "C" fg_status_t fg_cache_clear(fg_cache_t* cache, void* stream) {
         if ((rc = fg_launch_fill_i32(l.map, cache->num_nodes, -1, st)) != FG_OK) return rc;
         if ((rc = fg_launch_fill_i32(l.slot_node, l.capacity, -1, st)) != FG_OK) return rc;
         if ((rc = fg_launch_fill_i32(l.slot_stamp, l.capacity, 0, st)) != FG_OK) return rc;
-        if ((rc = fg_launch_fill_i32((int32_t*)l.head, 4, 0, st)) != FG_OK) return rc;
+        if ((rc = fg_launch_fill_i32((int32_t*)l.head, 8, 0, st)) != FG_OK) return rc;
         if ((rc = fg_launch_fill_i32((int32_t*)l.sel, sizeof(SelState) / 4, 0, st)) != FG_OK) return rc;
         l.head_cur = 0;
         l.last_iter = INT64_MIN;
     }
+    // an emptied ring has "written" nothing, so rows placed earlier would count as intact although embeddings
+    // may have been written over them: the feature side is dropped with the embeddings
+    if (cache->feat_rank && cache->n_feat > 0) {
+        fg_status_t rc = fg_launch_fill_i32(cache->feat_rank, cache->num_nodes, -1, st);
+        if (rc != FG_OK) return rc;
+    }
+    cache->n_feat = 0;
+    cache->feat_row_bytes = 0;
     fg_clear_error();
     return FG_OK;
 }
 
+static fg_status_t create_cache(const char* who, fg_cache_t** out, int64_t num_nodes, int32_t n_layers, const int64_t* capacity,
+                                const int32_t* dim, fg_dtype_t dtype, int32_t t_stale, int64_t buffer_bytes, void* stream);
+
 extern "C" fg_status_t fg_cache_create(fg_cache_t** out, int64_t num_nodes, int32_t n_layers, const int64_t* capacity,
                                        const int32_t* dim, fg_dtype_t dtype, int32_t t_stale, void* stream) {
-    if (!out) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create: out is NULL");
+    return create_cache("fg_cache_create", out, num_nodes, n_layers, capacity, dim, dtype, t_stale, 0, stream);
+}
+
+extern "C" fg_status_t fg_cache_create_bidirectional(fg_cache_t** out, int64_t num_nodes, int32_t n_layers,
+                                                     const int64_t* capacity, const int32_t* dim, fg_dtype_t dtype,
+                                                     int32_t t_stale, int64_t buffer_bytes, void* stream) {
+    if (out) *out = nullptr;
+    if (buffer_bytes <= 0 || buffer_bytes % FG_RING_ALIGN)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create_bidirectional: buffer_bytes = %lld must be a positive multiple of %lld",
+                (long long)buffer_bytes, (long long)FG_RING_ALIGN);
+    if (n_layers > FG_MAX_RINGS)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create_bidirectional: at most %d cached layers share a buffer with features", FG_MAX_RINGS);
+    return create_cache("fg_cache_create_bidirectional", out, num_nodes, n_layers, capacity, dim, dtype, t_stale, buffer_bytes, stream);
+}
+
+// buffer_bytes = 0: a buffer that just holds the rings
+static fg_status_t create_cache(const char* who, fg_cache_t** out, int64_t num_nodes, int32_t n_layers, const int64_t* capacity,
+                                const int32_t* dim, fg_dtype_t dtype, int32_t t_stale, int64_t buffer_bytes, void* stream) {
+    if (!out) FG_FAIL(FG_ERR_INVALID_ARG, "%s: out is NULL", who);
     *out = nullptr;
     if (num_nodes <= 0 || num_nodes > INT32_MAX)
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create: num_nodes = %lld must be in 1..2^31-1", (long long)num_nodes);
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: num_nodes = %lld must be in 1..2^31-1", who, (long long)num_nodes);
     if (n_layers < 0 || (n_layers > 0 && (!capacity || !dim)))
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create: n_layers = %d needs capacity and dim arrays", n_layers);
-    if (t_stale < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create: t_stale = %d is negative", t_stale);
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: n_layers = %d needs capacity and dim arrays", who, n_layers);
+    if (t_stale < 0) FG_FAIL(FG_ERR_INVALID_ARG, "%s: t_stale = %d is negative", who, t_stale);
     const int esz = fg_dtype_size(dtype);
-    if (!esz) FG_FAIL(FG_ERR_DTYPE, "fg_cache_create: unknown element type %d", (int)dtype);
+    if (!esz) FG_FAIL(FG_ERR_DTYPE, "%s: unknown element type %d", who, (int)dtype);
+    int64_t rings_end = 0;  // rings from the left end of the buffer, in layer order, each start aligned
     for (int i = 0; i < n_layers; ++i) {
         if (capacity[i] <= 0 || capacity[i] > INT32_MAX)
-            FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_create: capacity[%d] = %lld must be in 1..2^31-1", i, (long long)capacity[i]);
+            FG_FAIL(FG_ERR_INVALID_ARG, "%s: capacity[%d] = %lld must be in 1..2^31-1", who, i, (long long)capacity[i]);
         if (dim[i] <= 0 || ((int64_t)dim[i] * esz) % 16)
-            FG_FAIL(FG_ERR_SHAPE, "fg_cache_create: dim[%d] = %d must give rows that are a multiple of 16 bytes", i, dim[i]);
+            FG_FAIL(FG_ERR_SHAPE, "%s: dim[%d] = %d must give rows that are a multiple of 16 bytes", who, i, dim[i]);
+        rings_end = (int64_t)fg_align_up((size_t)rings_end, FG_RING_ALIGN) + capacity[i] * dim[i] * esz;
     }
+    if (buffer_bytes == 0) buffer_bytes = (int64_t)fg_align_up((size_t)rings_end, FG_RING_ALIGN);
+    if (buffer_bytes < rings_end)
+        FG_FAIL(FG_ERR_SHAPE, "%s: buffer_bytes = %lld cannot hold the rings (%lld bytes)", who, (long long)buffer_bytes, (long long)rings_end);
     fg_cache_t* c = new fg_cache_t();
     c->num_nodes = num_nodes;
     c->n_layers = n_layers;
     c->dtype = dtype;
     c->t_stale = t_stale;
     c->layers = n_layers ? new fg_layer[n_layers]() : nullptr;
-    for (int i = 0; i < n_layers; ++i) {
+    c->buffer_bytes = buffer_bytes;
+    hipError_t e = buffer_bytes > 0 ? hipMalloc((void**)&c->buffer, (size_t)buffer_bytes) : hipSuccess;
+    int64_t at = 0;
+    for (int i = 0; i < n_layers && e == hipSuccess; ++i) {
         fg_layer& l = c->layers[i];
         l.capacity = capacity[i];
         l.dim = dim[i];
-        hipError_t e = hipMalloc((void**)&l.map, (size_t)num_nodes * 4);
+        at = (int64_t)fg_align_up((size_t)at, FG_RING_ALIGN);
+        l.base = at;
+        l.table = c->buffer + at;
+        at += l.capacity * l.dim * esz;
+        e = hipMalloc((void**)&l.map, (size_t)num_nodes * 4);
         if (e == hipSuccess) e = hipMalloc((void**)&l.slot_node, (size_t)l.capacity * 4);
         if (e == hipSuccess) e = hipMalloc((void**)&l.slot_stamp, (size_t)l.capacity * 4);
-        if (e == hipSuccess) e = hipMalloc(&l.table, (size_t)l.capacity * l.dim * esz);
-        if (e == hipSuccess) e = hipMalloc((void**)&l.head, 16);
+        if (e == hipSuccess) e = hipMalloc((void**)&l.head, 32);
         if (e == hipSuccess) e = hipMalloc(&l.sel, sizeof(SelState));
-        if (e != hipSuccess) {
-            free_layers(c);
-            (void)hipGetLastError();
-            FG_FAIL(e == hipErrorOutOfMemory ? FG_ERR_OOM : FG_ERR_HIP, "fg_cache_create: allocation for layer %d failed: %s",
-                    i + 1, hipGetErrorString(e));
-        }
+    }
+    if (e != hipSuccess) {
+        free_layers(c);
+        (void)hipGetLastError();
+        FG_FAIL(e == hipErrorOutOfMemory ? FG_ERR_OOM : FG_ERR_HIP, "%s: device allocation failed: %s", who, hipGetErrorString(e));
     }
     fg_status_t rc = fg_cache_clear(c, stream);
     if (rc != FG_OK) {
@@ -540,7 +588,7 @@ extern "C" fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, i
     const size_t need = fg_ws_export_bytes(l->capacity);
     if (!ws_dev || ws_bytes < need) FG_FAIL(FG_ERR_SHAPE, "fg_cache_export: workspace of %zu bytes given, %zu needed", ws_bytes, need);
     fg_clear_error();
-    CacheRW c{l->map, l->slot_node, l->slot_stamp, l->head + l->head_cur, nullptr, l->capacity, cache->num_nodes, iter, cache->t_stale};
+    CacheRW c{l->map, l->slot_node, l->slot_stamp, l->head + l->head_cur, nullptr, l->head + 2, l->capacity, cache->num_nodes, iter, cache->t_stale};
     uint8_t* flag = (uint8_t*)ws_dev;
     int32_t* blk = (int32_t*)((char*)ws_dev + fg_align_up((size_t)l->capacity, 256));
     const int nb = (int)fg_ceil_div(l->capacity, FG_SCAN_BLOCK);
@@ -574,7 +622,7 @@ fg_status_t prepare_update_layer(fg_cache_t* cache, const char* who, int32_t lay
     if (iter < 0 || iter > INT32_MAX - 1) FG_FAIL(FG_ERR_INVALID_ARG, "%s: iteration %lld out of range", who, (long long)iter);
     const UpdWs w = upd_layout(n);
     UpdLayer& u = *out;
-    u.c = CacheRW{l->map, l->slot_node, l->slot_stamp, l->head + l->head_cur, l->head + (l->head_cur ^ 1), l->capacity, cache->num_nodes, iter, cache->t_stale};
+    u.c = CacheRW{l->map, l->slot_node, l->slot_stamp, l->head + l->head_cur, l->head + (l->head_cur ^ 1), l->head + 2, l->capacity, cache->num_nodes, iter, cache->t_stale};
     u.ids = ids_dev;
     u.live = live_dev;
     u.hit = hit_dev;
@@ -703,4 +751,157 @@ extern "C" fg_status_t fg_cache_fetch_all(const fg_cache_t* cache, int32_t n_lay
     }
     fg_clear_error();
     return fg_launch_row_copies(copies, (hipStream_t)stream);
+}
+
+// ---- feature side of the shared buffer (Section 4.2) ---------------------------------------------------------
+//
+// Before training the raw feature rows of a caller-ordered hot list are copied to the right end of the buffer,
+// the hottest farthest from the rings. Nothing ever moves or invalidates them explicitly: a row counts as lost
+// once a ring has written over any of its bytes, which a reader decides from the rings' `used` counters
+// (fg_feature_rank). The loader variants consult the node -> rank array first and read a surviving row from HBM
+// instead of the feature table.
+
+fg_feat_side fg_feature_side(const fg_cache_t* cache) {
+    fg_feat_side F = {};
+    if (!cache || cache->n_feat <= 0 || !cache->feat_rank) return F;
+    F.rank = cache->feat_rank;
+    F.end = cache->buffer + cache->buffer_bytes;
+    F.row_bytes = cache->feat_row_bytes;
+    F.n_rows = cache->n_feat;
+    F.buffer_bytes = cache->buffer_bytes;
+    F.n_rings = cache->n_layers;
+    for (int i = 0; i < cache->n_layers && i < FG_MAX_RINGS; ++i) {
+        const fg_layer& l = cache->layers[i];
+        F.ring_lo[i] = l.base;
+        F.ring_row[i] = (int64_t)l.dim * fg_dtype_size(cache->dtype);
+        F.ring_used[i] = l.head + 2;
+    }
+    return F;
+}
+
+namespace {
+
+constexpr int FEAT_THREADS = 256;
+
+// One wavefront per rank: rank[hot[r]] = r and the node's table row goes to end - (r+1)*row_bytes.
+__global__ __launch_bounds__(FEAT_THREADS) void place_features_kernel(const int32_t* __restrict__ hot, int64_t n_hot,
+                                                                      const char* __restrict__ table, int64_t table_rows,
+                                                                      int64_t src_stride, int64_t row_bytes,
+                                                                      int32_t* __restrict__ rank, int64_t num_nodes,
+                                                                      char* __restrict__ end) {
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const int lane = threadIdx.x & 63;
+    const int chunks = (int)(row_bytes >> 4);
+    const int64_t n_waves = ((int64_t)gridDim.x * FEAT_THREADS) >> 6;
+    for (int64_t r = ((int64_t)blockIdx.x * FEAT_THREADS + threadIdx.x) >> 6; r < n_hot; r += n_waves) {
+        const int32_t v = hot[r];
+        if (v < 0 || v >= num_nodes || v >= table_rows) continue;  // the rank stays unused
+        if (lane == 0) rank[v] = (int32_t)r;
+        const u32x4* src = (const u32x4*)(table + (int64_t)v * src_stride);
+        u32x4* dst = (u32x4*)(end - (r + 1) * row_bytes);
+        for (int c = lane; c < chunks; c += 64) dst[c] = __builtin_nontemporal_load(src + c);
+    }
+}
+
+__global__ __launch_bounds__(FEAT_THREADS) void feature_lookup_kernel(fg_feat_side F, int64_t num_nodes,
+                                                                      const int32_t* __restrict__ ids,
+                                                                      const int64_t* __restrict__ count_dev, int64_t max_count,
+                                                                      int32_t* __restrict__ rank_out,
+                                                                      unsigned long long* __restrict__ n_found) {
+    int64_t count = count_dev ? *count_dev : max_count;
+    if (count > max_count) count = max_count;
+    int found = 0;
+    for (int64_t k = (int64_t)blockIdx.x * FEAT_THREADS + threadIdx.x; k < count; k += (int64_t)gridDim.x * FEAT_THREADS) {
+        const int32_t v = ids[k];
+        const int32_t r = (F.rank && v >= 0 && v < num_nodes) ? fg_feature_rank(F, v) : -1;
+        if (rank_out) rank_out[k] = r;
+        found += r >= 0;
+    }
+    if (n_found) {
+        __shared__ int red[FEAT_THREADS / 64];
+        int w = found;
+        for (int off = 32; off > 0; off >>= 1) w += __shfl_down(w, off, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = w;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            int s = 0;
+            for (int i = 0; i < FEAT_THREADS / 64; ++i) s += red[i];
+            if (s) atomicAdd(n_found, (unsigned long long)s);
+        }
+    }
+}
+
+}  // namespace
+
+extern "C" fg_status_t fg_cache_fill_features(fg_cache_t* cache, const int32_t* hot_ids_dev, int64_t n_hot, const void* table,
+                                              int64_t table_rows, int64_t src_stride, int64_t row_bytes, void* stream) {
+    if (!cache) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fill_features: cache is NULL");
+    if (n_hot < 0 || table_rows < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fill_features: negative size");
+    if (n_hot > INT32_MAX) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fill_features: n_hot = %lld exceeds 2^31-1", (long long)n_hot);
+    if (n_hot > 0 && (!hot_ids_dev || !table)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fill_features: hot_ids_dev and table are required");
+    if (row_bytes <= 0 || row_bytes % 16) FG_FAIL(FG_ERR_SHAPE, "fg_cache_fill_features: row_bytes = %lld must be a positive multiple of 16", (long long)row_bytes);
+    if (src_stride < row_bytes) FG_FAIL(FG_ERR_SHAPE, "fg_cache_fill_features: src_stride = %lld smaller than a row of %lld bytes", (long long)src_stride, (long long)row_bytes);
+    if (((uintptr_t)table | (uintptr_t)src_stride) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fill_features: table and src_stride must be 16-byte aligned");
+    if (cache->n_layers > FG_MAX_RINGS) FG_FAIL(FG_ERR_SHAPE, "fg_cache_fill_features: at most %d cached layers share a buffer with features", FG_MAX_RINGS);
+    if (cache->buffer_bytes % 16) FG_FAIL(FG_ERR_STATE, "fg_cache_fill_features: the buffer size is not a multiple of 16");
+    if (n_hot > cache->buffer_bytes / row_bytes)
+        FG_FAIL(FG_ERR_SHAPE, "fg_cache_fill_features: %lld rows of %lld bytes do not fit into the buffer of %lld bytes", (long long)n_hot,
+                (long long)row_bytes, (long long)cache->buffer_bytes);
+    for (int i = 0; i < cache->n_layers; ++i)
+        if (cache->layers[i].last_iter != INT64_MIN)
+            FG_FAIL(FG_ERR_STATE, "fg_cache_fill_features: layer %d has been updated; features are placed into an empty cache (after create or clear)", i + 1);
+    hipStream_t st = (hipStream_t)stream;
+    if (!cache->feat_rank) {
+        hipError_t e = hipMalloc((void**)&cache->feat_rank, (size_t)cache->num_nodes * 4);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            cache->feat_rank = nullptr;
+            FG_FAIL(e == hipErrorOutOfMemory ? FG_ERR_OOM : FG_ERR_HIP, "fg_cache_fill_features: allocating the rank array failed: %s", hipGetErrorString(e));
+        }
+    }
+    fg_clear_error();
+    fg_status_t rc = fg_launch_fill_i32(cache->feat_rank, cache->num_nodes, -1, st);
+    if (rc != FG_OK) return rc;
+    cache->n_feat = n_hot;
+    cache->feat_row_bytes = n_hot > 0 ? row_bytes : 0;
+    if (n_hot == 0) return FG_OK;
+    int64_t blocks = fg_ceil_div(n_hot, FEAT_THREADS / 64);
+    if (blocks > 256 * 8) blocks = 256 * 8;
+    hipLaunchKernelGGL(place_features_kernel, dim3((unsigned)blocks), dim3(FEAT_THREADS), 0, st, hot_ids_dev, n_hot, (const char*)table,
+                       table_rows, src_stride, row_bytes, cache->feat_rank, cache->num_nodes, cache->buffer + cache->buffer_bytes);
+    FG_LAUNCH_CHECK("place_features_kernel");
+    return FG_OK;
+}
+
+extern "C" fg_status_t fg_feature_lookup(const fg_cache_t* cache, const int32_t* ids_dev, const int64_t* count_dev, int64_t max_count,
+                                         int32_t* rank_out_dev, int64_t* n_found_dev, void* stream) {
+    if (!cache) FG_FAIL(FG_ERR_INVALID_ARG, "fg_feature_lookup: cache is NULL");
+    if (max_count < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_feature_lookup: max_count = %lld is negative", (long long)max_count);
+    if (max_count > 0 && !ids_dev) FG_FAIL(FG_ERR_INVALID_ARG, "fg_feature_lookup: ids_dev is NULL");
+    fg_clear_error();
+    hipStream_t st = (hipStream_t)stream;
+    if (n_found_dev) {
+        fg_status_t rc = fg_launch_fill_i32((int32_t*)n_found_dev, 2, 0, st);
+        if (rc != FG_OK) return rc;
+    }
+    if (max_count == 0) return FG_OK;
+    int64_t blocks = fg_ceil_div(max_count, FEAT_THREADS);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(feature_lookup_kernel, dim3((unsigned)blocks), dim3(FEAT_THREADS), 0, st, fg_feature_side(cache), cache->num_nodes,
+                       ids_dev, count_dev, max_count, rank_out_dev, (unsigned long long*)n_found_dev);
+    FG_LAUNCH_CHECK("feature_lookup_kernel");
+    return FG_OK;
+}
+
+extern "C" const void* fg_cache_buffer(const fg_cache_t* cache, int64_t* buffer_bytes_out) {
+    if (buffer_bytes_out) *buffer_bytes_out = cache ? cache->buffer_bytes : 0;
+    return cache ? cache->buffer : nullptr;
+}
+
+extern "C" int64_t fg_cache_feature_rows(const fg_cache_t* cache) { return cache ? cache->n_feat : 0; }
+
+extern "C" int64_t fg_cache_ring_offset(const fg_cache_t* cache, int32_t layer) {
+    const fg_layer* l;
+    if (layer_of(cache, layer, "fg_cache_ring_offset", &l) != FG_OK) return -1;
+    return l->base;
 }

@@ -11,8 +11,10 @@ struct fg_layer {
     int32_t* map = nullptr;         // [num_nodes] slot of each node or -1
     int32_t* slot_node = nullptr;   // [capacity] owner of each slot or -1
     int32_t* slot_stamp = nullptr;  // [capacity] iteration whose update filled the slot
-    void* table = nullptr;          // [capacity x dim]
-    int64_t* head = nullptr;        // device int64[2]: ring header, double-buffered (head_cur indexes the current one)
+    void* table = nullptr;          // [capacity x dim], inside the cache's shared buffer at byte offset `base`
+    int64_t base = 0;
+    int64_t* head = nullptr;        // device int64[4]: ring header, double-buffered (head_cur indexes the current one);
+                                    // [2] = slots written at least once (0 .. used-1: the ring fills upwards until it wraps)
     int head_cur = 0;
     void* sel = nullptr;            // selection scratch of the update (two histograms and a count), all-zero between updates
     int64_t last_iter = INT64_MIN;  // host: iteration of the last update
@@ -24,7 +26,46 @@ struct fg_cache {
     fg_dtype_t dtype = FG_F32;
     int32_t t_stale = 0;
     fg_layer* layers = nullptr;  // host array [n_layers], layer l at index l-1
+    // the buffer embeddings and raw features share (Section 4.2): rings from the left end in layer order,
+    // feature rows from the right end, rank r at [buffer_bytes - (r+1)*feat_row_bytes, buffer_bytes - r*feat_row_bytes)
+    char* buffer = nullptr;
+    int64_t buffer_bytes = 0;
+    int32_t* feat_rank = nullptr;  // [num_nodes] rank of a node's row on the feature side or -1; allocated by the first fill
+    int64_t n_feat = 0;            // feature rows placed (0: no feature side)
+    int64_t feat_row_bytes = 0;
 };
+
+constexpr int FG_MAX_RINGS = 8;       // cached layers a feature side can share its buffer with
+constexpr int64_t FG_RING_ALIGN = 256;  // a ring's first byte in the shared buffer is a multiple of this
+
+// What a kernel needs to find a node's raw feature row on the feature side of the shared buffer.
+struct fg_feat_side {
+    const int32_t* rank;  // nullptr: nothing placed
+    const char* end;      // one past the buffer: the row of rank r starts at end - (r+1)*row_bytes
+    int64_t row_bytes, n_rows, buffer_bytes;
+    int32_t n_rings;
+    int64_t ring_lo[FG_MAX_RINGS];           // first byte of each ring
+    int64_t ring_row[FG_MAX_RINGS];          // bytes per slot
+    const int64_t* ring_used[FG_MAX_RINGS];  // device: slots written so far
+};
+fg_feat_side fg_feature_side(const fg_cache_t* cache);
+
+// Rank of node v's row (0 <= v < num_nodes) if it was placed and no embedding has been written over any of its
+// bytes, else -1. A ring has written exactly the bytes of its slots 0 .. used-1.
+__device__ __forceinline__ int32_t fg_feature_rank(const fg_feat_side& F, int32_t v) {
+    int32_t r = F.rank[v];
+    if (r < 0 || r >= F.n_rows) return -1;
+    const int64_t lo = F.buffer_bytes - (int64_t)(r + 1) * F.row_bytes, hi = lo + F.row_bytes;
+#pragma unroll
+    for (int i = 0; i < FG_MAX_RINGS; ++i) {
+        if (i < F.n_rings) {
+            const int64_t used = *F.ring_used[i];
+            const int64_t w_lo = F.ring_lo[i], w_hi = w_lo + used * F.ring_row[i];
+            if (used > 0 && lo < w_hi && hi > w_lo) r = -1;
+        }
+    }
+    return r;
+}
 
 void fg_set_error(const char* fmt, ...);
 void fg_clear_error();
@@ -67,11 +108,12 @@ enum fg_tune_id {
 };
 int64_t fg_tuning(fg_tune_id id);
 
-// internal row copy used by fg_gather and by the cache update
+// internal row copy used by fg_gather and by the cache update; feat (may be NULL, else 16-byte rows) makes
+// src_index node ids whose rows are taken from the feature side where they are still there
 fg_status_t fg_launch_gather(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
                              const int32_t* src_index, const int32_t* dst_pos, const int64_t* count_dev,
                              int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride, int on_host,
-                             hipStream_t stream);
+                             hipStream_t stream, const fg_feat_side* feat = nullptr);
 // Several independent row copies in one launch: dst[dst_idx[k], :] = src[src_idx[k], :] for k < *count (rows a
 // multiple of 16 bytes, 16-byte aligned). Used where a pass copies rows for every cached layer at once.
 constexpr int FG_MAX_COPIES = 8;

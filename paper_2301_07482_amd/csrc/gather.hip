@@ -19,14 +19,16 @@ __device__ __forceinline__ V load_row_piece(const V* p) {
         return *p;
 }
 
-template <typename V, int UNROLL, bool NT>
+// FEAT: src_index holds node ids, and a node whose row is still on the feature side of the shared buffer (Section 4.2)
+// is read from there instead of from the table.
+template <typename V, int UNROLL, bool NT, bool FEAT>
 __global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict__ table, int64_t table_rows,
                                                           int64_t src_stride, int chunks,
                                                           const int32_t* __restrict__ src_index,
                                                           const int32_t* __restrict__ dst_pos,
                                                           const int64_t* __restrict__ count_dev, int64_t max_count,
                                                           char* __restrict__ dst, int64_t dst_rows, int64_t dst_stride,
-                                                          int lanes_log2) {
+                                                          int lanes_log2, fg_feat_side F) {
     int64_t count = count_dev ? *count_dev : max_count;
     if (count > max_count) count = max_count;
     const int lanes = 1 << lanes_log2;
@@ -47,6 +49,10 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict
                 const int64_t d = dst_pos ? (int64_t)dst_pos[k] : k;
                 if (s >= 0 && s < table_rows && d >= 0 && d < dst_rows) {
                     src[u] = (const V*)(table + s * src_stride);
+                    if constexpr (FEAT) {
+                        const int32_t r = fg_feature_rank(F, (int32_t)s);
+                        if (r >= 0) src[u] = (const V*)(F.end - (int64_t)(r + 1) * F.row_bytes);
+                    }
                     out[u] = (V*)(dst + d * dst_stride);
                 }
             }
@@ -113,10 +119,10 @@ __global__ void fill_kernel(T* p, int64_t n, T value) {
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
-template <typename V, int UNROLL, bool NT>
+template <typename V, int UNROLL, bool NT, bool FEAT>
 void launch_gather_u(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
                      const int32_t* src_index, const int32_t* dst_pos, const int64_t* count_dev, int64_t max_count,
-                     void* dst, int64_t dst_rows, int64_t dst_stride, int on_host, hipStream_t st) {
+                     void* dst, int64_t dst_rows, int64_t dst_stride, int on_host, hipStream_t st, const fg_feat_side& F) {
     const int chunks = (int)(row_bytes / (int64_t)sizeof(V));
     int lg = 0;
     while ((1 << lg) < chunks && lg < 6) ++lg;
@@ -127,22 +133,23 @@ void launch_gather_u(const void* table, int64_t table_rows, int64_t src_stride, 
     const int64_t cap = 256 * fg_tuning(on_host == 1 ? FG_TUNE_GATHER_HOST_WG_PER_CU : FG_TUNE_GATHER_WG_PER_CU);
     if (blocks > cap) blocks = cap;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL((gather_rows_kernel<V, UNROLL, NT>), dim3((unsigned)blocks), dim3(256), 0, st, (const char*)table,
+    hipLaunchKernelGGL((gather_rows_kernel<V, UNROLL, NT, FEAT>), dim3((unsigned)blocks), dim3(256), 0, st, (const char*)table,
                        table_rows, src_stride, chunks, src_index, dst_pos, count_dev, max_count, (char*)dst, dst_rows,
-                       dst_stride, lg);
+                       dst_stride, lg, F);
 }
 
-template <typename V>
+template <typename V, bool FEAT = false>
 void launch_gather_t(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
                      const int32_t* src_index, const int32_t* dst_pos, const int64_t* count_dev, int64_t max_count,
-                     void* dst, int64_t dst_rows, int64_t dst_stride, int on_host, hipStream_t st) {
+                     void* dst, int64_t dst_rows, int64_t dst_stride, int on_host, hipStream_t st,
+                     const fg_feat_side& F = fg_feat_side{}) {
     const int unroll = (int)fg_tuning(FG_TUNE_GATHER_UNROLL);
     // rows of a big table are read once (streaming loads); rows that were just written or will be read again
     // (cached embeddings, layer outputs) go through the caches normally
     const bool nt = on_host != 2 && fg_tuning(FG_TUNE_GATHER_NONTEMPORAL) != 0;
 #define FG_G(U, N)                                                                                                      \
-    launch_gather_u<V, U, N>(table, table_rows, src_stride, row_bytes, src_index, dst_pos, count_dev, max_count, dst, \
-                             dst_rows, dst_stride, on_host, st)
+    launch_gather_u<V, U, N, FEAT>(table, table_rows, src_stride, row_bytes, src_index, dst_pos, count_dev, max_count, \
+                                   dst, dst_rows, dst_stride, on_host, st, F)
     if (unroll <= 1) { if (nt) FG_G(1, true); else FG_G(1, false); }
     else if (unroll == 2) { if (nt) FG_G(2, true); else FG_G(2, false); }
     else if (unroll <= 4) { if (nt) FG_G(4, true); else FG_G(4, false); }
@@ -190,10 +197,14 @@ fg_status_t fg_launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t
 fg_status_t fg_launch_gather(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
                              const int32_t* src_index, const int32_t* dst_pos, const int64_t* count_dev,
                              int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride, int on_host,
-                             hipStream_t st) {
+                             hipStream_t st, const fg_feat_side* feat) {
     if (max_count == 0 || row_bytes == 0) return FG_OK;
     const uintptr_t bits = (uintptr_t)table | (uintptr_t)dst | (uintptr_t)src_stride | (uintptr_t)dst_stride | (uintptr_t)row_bytes;
-    if ((bits & 15) == 0)
+    if (feat && feat->rank) {
+        if (bits & 15) FG_FAIL(FG_ERR_INVALID_ARG, "gather through the feature side needs 16-byte aligned rows");
+        launch_gather_t<u32x4, true>(table, table_rows, src_stride, row_bytes, src_index, dst_pos, count_dev, max_count, dst,
+                                     dst_rows, dst_stride, on_host, st, *feat);
+    } else if ((bits & 15) == 0)
         launch_gather_t<u32x4>(table, table_rows, src_stride, row_bytes, src_index, dst_pos, count_dev, max_count, dst,
                                dst_rows, dst_stride, on_host, st);
     else if ((bits & 7) == 0)
@@ -209,27 +220,54 @@ fg_status_t fg_launch_gather(const void* table, int64_t table_rows, int64_t src_
     return FG_OK;
 }
 
-extern "C" fg_status_t fg_gather(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
-                                 const int32_t* src_index_dev, const int32_t* dst_pos_dev, const int64_t* count_dev,
-                                 int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride,
-                                 int32_t table_kind, void* stream) {
+static fg_status_t gather_checked(const char* who, const fg_feat_side* feat, const void* table, int64_t table_rows,
+                                  int64_t src_stride, int64_t row_bytes, const int32_t* src_index_dev,
+                                  const int32_t* dst_pos_dev, const int64_t* count_dev, int64_t max_count, void* dst,
+                                  int64_t dst_rows, int64_t dst_stride, int32_t table_kind, void* stream) {
     if (max_count < 0 || table_rows < 0 || dst_rows < 0 || row_bytes < 0)
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather: negative size (max_count %lld, table_rows %lld, dst_rows %lld, row_bytes %lld)",
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: negative size (max_count %lld, table_rows %lld, dst_rows %lld, row_bytes %lld)", who,
                 (long long)max_count, (long long)table_rows, (long long)dst_rows, (long long)row_bytes);
     if (max_count > 0 && row_bytes > 0 && (!table || !dst || !src_index_dev))
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather: table, dst and src_index_dev are required");
-    if (row_bytes & 1) FG_FAIL(FG_ERR_SHAPE, "fg_gather: row_bytes = %lld is odd", (long long)row_bytes);
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: table, dst and src_index_dev are required", who);
+    if (row_bytes & 1) FG_FAIL(FG_ERR_SHAPE, "%s: row_bytes = %lld is odd", who, (long long)row_bytes);
     if (src_stride < row_bytes || dst_stride < row_bytes)
-        FG_FAIL(FG_ERR_SHAPE, "fg_gather: a row stride (%lld, %lld) is smaller than row_bytes = %lld", (long long)src_stride,
+        FG_FAIL(FG_ERR_SHAPE, "%s: a row stride (%lld, %lld) is smaller than row_bytes = %lld", who, (long long)src_stride,
                 (long long)dst_stride, (long long)row_bytes);
     const uintptr_t bits = (uintptr_t)table | (uintptr_t)dst | (uintptr_t)src_stride | (uintptr_t)dst_stride;
     int64_t need = 16;
     while (need > 2 && (row_bytes % need) != 0) need >>= 1;
     if (bits & (uintptr_t)(need - 1))
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather: pointers and strides must be %lld-byte aligned for rows of %lld bytes",
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: pointers and strides must be %lld-byte aligned for rows of %lld bytes", who,
                 (long long)need, (long long)row_bytes);
-    if (table_kind < 0 || table_kind > 2) FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather: table_kind = %d is not FG_TABLE_*", table_kind);
+    if (table_kind < 0 || table_kind > 2) FG_FAIL(FG_ERR_INVALID_ARG, "%s: table_kind = %d is not FG_TABLE_*", who, table_kind);
+    if (feat && feat->rank && max_count > 0 && row_bytes > 0) {
+        if (row_bytes != feat->row_bytes)
+            FG_FAIL(FG_ERR_SHAPE, "%s: row_bytes = %lld differs from the %lld-byte rows on the feature side", who, (long long)row_bytes,
+                    (long long)feat->row_bytes);
+        if (row_bytes % 16 || (bits & 15)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: rows, pointers and strides must be 16-byte aligned", who);
+    }
     fg_clear_error();
     return fg_launch_gather(table, table_rows, src_stride, row_bytes, src_index_dev, dst_pos_dev, count_dev, max_count,
-                            dst, dst_rows, dst_stride, table_kind, (hipStream_t)stream);
+                            dst, dst_rows, dst_stride, table_kind, (hipStream_t)stream, feat);
+}
+
+extern "C" fg_status_t fg_gather(const void* table, int64_t table_rows, int64_t src_stride, int64_t row_bytes,
+                                 const int32_t* src_index_dev, const int32_t* dst_pos_dev, const int64_t* count_dev,
+                                 int64_t max_count, void* dst, int64_t dst_rows, int64_t dst_stride,
+                                 int32_t table_kind, void* stream) {
+    return gather_checked("fg_gather", nullptr, table, table_rows, src_stride, row_bytes, src_index_dev, dst_pos_dev, count_dev,
+                          max_count, dst, dst_rows, dst_stride, table_kind, stream);
+}
+
+extern "C" fg_status_t fg_gather_features(const fg_cache_t* cache, const void* table, int64_t table_rows, int64_t src_stride,
+                                          int64_t row_bytes, const int32_t* ids_dev, const int32_t* dst_pos_dev,
+                                          const int64_t* count_dev, int64_t max_count, void* dst, int64_t dst_rows,
+                                          int64_t dst_stride, int32_t table_kind, void* stream) {
+    if (!cache) FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather_features: cache is NULL");
+    if (table_rows > cache->num_nodes)
+        FG_FAIL(FG_ERR_SHAPE, "fg_gather_features: the table has %lld rows but the cache was created for %lld nodes", (long long)table_rows,
+                (long long)cache->num_nodes);
+    const fg_feat_side F = fg_feature_side(cache);
+    return gather_checked("fg_gather_features", &F, table, table_rows, src_stride, row_bytes, ids_dev, dst_pos_dev, count_dev,
+                          max_count, dst, dst_rows, dst_stride, table_kind, stream);
 }

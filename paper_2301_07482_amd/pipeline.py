@@ -47,7 +47,7 @@ class HotPath:
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
-                 one_launch_top_down=True, log_ring=256):
+                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -105,11 +105,23 @@ class HotPath:
             self.W[l] = torch.from_numpy(np.ascontiguousarray(W)).to(dev).to(wt).contiguous()
             self.bias[l] = torch.from_numpy(np.ascontiguousarray(b)).to(dev)
         self.cache = None
+        self.feature_side = False
         if L > 1:
             caps = [capacity] * (L - 1) if np.isscalar(capacity) else list(capacity)
             self.capacity = caps
-            self.cache = B.fg_cache_create(num_nodes, caps, [dims[l] for l in range(1, L)], self.comp_code, t_stale,
-                                           self._stream())
+            cdims = [dims[l] for l in range(1, L)]
+            if buffer_bytes is None:
+                self.cache = B.fg_cache_create(num_nodes, caps, cdims, self.comp_code, t_stale, self._stream())
+            else:
+                self.cache = B.fg_cache_create_bidirectional(num_nodes, caps, cdims, self.comp_code, t_stale, buffer_bytes,
+                                                             self._stream())
+            # hot_ids (hottest first): their raw features are placed on the feature side of the cache's buffer and the
+            # loader reads them from there while no embedding has been written over them
+            if hot_ids is not None and len(hot_ids):
+                self.hot_ids = torch.from_numpy(np.ascontiguousarray(hot_ids, dtype=np.int32)).to(dev)
+                d0b = dims[0] * B.DTYPE_SIZE[self.feat_code]
+                B.fg_cache_fill_features(self.cache, self.hot_ids, len(hot_ids), self.feat, num_nodes, d0b, d0b, self._stream())
+                self.feature_side = True
 
     def _stream(self):
         return torch.cuda.current_stream().cuda_stream
@@ -174,8 +186,12 @@ class HotPath:
         d0b = self.dims[0] * esz[self.feat_code]
         if not fused:
             tick("gather_features")
-            B.fg_gather(self.feat, self.num_nodes, d0b, d0b, self.input_ids, self.normal_pos[0], self._cnt(0, 2), bt.n[0],
-                        self.H[0], bt.n[0], d0b, self.on_host, st)
+            if self.feature_side:
+                B.fg_gather_features(self.cache, self.feat, self.num_nodes, d0b, d0b, self.input_ids, self.normal_pos[0],
+                                     self._cnt(0, 2), bt.n[0], self.H[0], bt.n[0], d0b, self.on_host, st)
+            else:
+                B.fg_gather(self.feat, self.num_nodes, d0b, d0b, self.input_ids, self.normal_pos[0], self._cnt(0, 2), bt.n[0],
+                            self.H[0], bt.n[0], d0b, self.on_host, st)
         # ---- bottom-up: cached rows, mean aggregation, dense update
         for l in range(1, L + 1):
             in_code, out_code = self.h_code[l - 1], self.h_code[l]
@@ -188,9 +204,13 @@ class HotPath:
             agg_b = self.dims[l - 1] * esz[self.agg_code]
             if fused and l == 1:
                 tick("gather_aggregate[1]")
-                B.fg_gather_aggregate(bt.start[1], bt.end[1], bt.col[1], bt.nnz[1], bt.n[1], self.normal_pos[1],
-                                      self._cnt(1, 2), bt.n[1], bt.ids[0], bt.n[0], self.feat, self.num_nodes, d0b,
-                                      self.dims[0], in_code, self.AGG, agg_b, self.agg_code, self.H[0], d0b, bt.n[0], st)
+                args = (bt.start[1], bt.end[1], bt.col[1], bt.nnz[1], bt.n[1], self.normal_pos[1], self._cnt(1, 2), bt.n[1],
+                        bt.ids[0], bt.n[0], self.feat, self.num_nodes, d0b, self.dims[0], in_code, self.AGG, agg_b,
+                        self.agg_code, self.H[0], d0b, bt.n[0], st)
+                if self.feature_side:
+                    B.fg_gather_aggregate_features(self.cache, *args)
+                else:
+                    B.fg_gather_aggregate(*args)
             else:
                 tick(f"aggregate[{l}]")
                 B.fg_aggregate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),
@@ -234,6 +254,14 @@ class HotPath:
         if not self.fused_input:
             out["input_ids"] = self.input_ids[:int(counts[0, 2])].cpu().numpy()
         return out
+
+    def feature_ranks(self, ids_dev, n):
+        """Rank on the feature side of each of the first n node ids (device int32), -1 where the row is not (or no longer) there."""
+        out = torch.full((max(n, 1),), -7, dtype=torch.int32, device=self.device)
+        found = torch.zeros(1, dtype=torch.int64, device=self.device)
+        B.fg_feature_lookup(self.cache, ids_dev, None, n, out, found, self._stream())
+        torch.cuda.synchronize()
+        return out[:n].cpu().numpy(), int(found.item())
 
     def export_cache(self, layer, it):
         cap = self.capacity[layer - 1]

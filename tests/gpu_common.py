@@ -5,7 +5,8 @@ from fg_inputs import features, workload as wl
 from oracle import freshgnn_oracle as O
 
 
-def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None, p_grad=None, fused_input=False, one_launch_top_down=True, update_all=True, log_ring=256):
+def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None, p_grad=None, fused_input=False, one_launch_top_down=True, update_all=True, log_ring=256,
+                 hot_ids=None, buffer_bytes=None):
     """HotPath for workload `w` with its feature table resident where the workload says."""
     from fg_inputs import device as fdev
     from paper_2301_07482_amd.pipeline import HotPath
@@ -17,7 +18,7 @@ def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None
                  w.t_stale if t_stale is None else t_stale, w.p_grad if p_grad is None else p_grad, feat_table,
                  w.feat_dtype, w.compute_dtype, weights, features_on_host=(w.feat_location == "host"),
                  use_cache=use_cache, fused_input=fused_input, one_launch_top_down=one_launch_top_down, update_all=update_all,
-                 fetch_all=update_all, log_ring=log_ring)
+                 fetch_all=update_all, log_ring=log_ring, hot_ids=hot_ids, buffer_bytes=buffer_bytes)
     return hp, weights, feat_table
 
 
@@ -26,6 +27,15 @@ def make_oracle_caches(w, capacity=None, t_stale=None):
     return {l: O.HistoricalCache(w.num_nodes, w.cache_capacity if capacity is None else capacity, dims[l],
                                  w.t_stale if t_stale is None else t_stale, w.compute_dtype)
             for l in range(1, w.num_layers)}
+
+
+def make_oracle_bidirectional(w, buffer_bytes, capacity=None, t_stale=None):
+    """The oracle's shared buffer for workload `w`; its rings take the place of `make_oracle_caches`."""
+    dims = wl.layer_dims(w)
+    L = w.num_layers
+    cap = w.cache_capacity if capacity is None else capacity
+    return O.BidirectionalCache(w.num_nodes, [cap] * (L - 1), [dims[l] for l in range(1, L)],
+                                w.t_stale if t_stale is None else t_stale, w.compute_dtype, buffer_bytes)
 
 
 def feature_accessor(w):

@@ -75,6 +75,16 @@ def test_argument_validation_needs_no_gpu(B):
     assert code(B.fg_cache_create, 100, [4], [3], B.FG_F32, 3) == B.FG_ERR_SHAPE
     assert code(B.fg_cache_create, 100, [4], [4], 5, 3) == B.FG_ERR_DTYPE
     assert code(B.fg_cache_create, 100, [4], [4], B.FG_F32, -1) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_cache_create_bidirectional, 100, [4], [4], B.FG_F32, 3, 0) == B.FG_ERR_INVALID_ARG        # no buffer
+    assert code(B.fg_cache_create_bidirectional, 100, [4], [4], B.FG_F32, 3, 1000) == B.FG_ERR_INVALID_ARG     # not a multiple of 256
+    assert code(B.fg_cache_create_bidirectional, 100, [100], [64], B.FG_F32, 3, 1024) == B.FG_ERR_SHAPE        # rings do not fit
+    assert code(B.fg_cache_create_bidirectional, 100, [4] * 9, [4] * 9, B.FG_F32, 3, 1 << 20) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_cache_fill_features, None, 4096, 4, 4096, 10, 64, 64) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_feature_lookup, None, 4096, None, 4, 4096, None) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_gather_features, None, 4096, 10, 16, 16, 4096, None, None, 4, 4096, 4, 16) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_gather_aggregate_features, None, 4096, 4096, 4096, 5, 5, None, None, 5, 4096, 9, 4096, 9, 512, 128, B.FG_F32,
+                4096, 512, B.FG_F32) == B.FG_ERR_INVALID_ARG
+    assert B.fg_cache_feature_rows(None) == 0 and B.fg_cache_buffer(None) == (None, 0) and B.fg_cache_ring_offset(None, 1) == -1
     assert code(B.fg_set_tuning, "gather_unroll", -3) == B.FG_ERR_INVALID_ARG
     assert B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, 1000) >= 1000 * 5
     assert B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, 1000) >= 1000 * 9

@@ -420,15 +420,43 @@ def test_update_all_and_fetch_all_with_unequal_and_empty_layers(env):
 # ------------------------------------------------------------------------------------------------ whole iterations
 
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
-                        sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True):
-    """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence."""
+                        sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None):
+    """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
+
+    feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
+    graph's n_hot hottest nodes (Section 4.2). poison: once the rows are placed, the table rows of those nodes are
+    negated on both sides, so a row read from the wrong place shows.
+    """
     g = wl.make_graph(w)
+    frows = G.feature_accessor(w)
+    fs = feature_side
+    hot = g.hottest(fs["n_hot"]) if fs else None
     hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity,
                                              fused_input=fused, one_launch_top_down=one_launch_top_down,
-                                             update_all=one_launch_top_down)
-    caches = G.make_oracle_caches(w, capacity=capacity, t_stale=t_stale)
+                                             update_all=one_launch_top_down, hot_ids=hot,
+                                             buffer_bytes=fs["buffer_bytes"] if fs else None)
+    from paper_2301_07482_amd import binding as FGB
+    bc = None
+    if fs:
+        bc = G.make_oracle_bidirectional(w, fs["buffer_bytes"], capacity=capacity, t_stale=t_stale)
+        bc.fill_features(hot, frows, w.feat_dtype)
+        caches = bc.rings
+        assert hp.feature_side and FGB.fg_cache_feature_rows(hp.cache) == len(hot)
+        assert [FGB.fg_cache_ring_offset(hp.cache, l) for l in bc.rings] == [bc.ring_base[l] for l in bc.rings]
+        if fs.get("poison"):
+            torch.cuda.synchronize()
+            feat_table[torch.as_tensor(hot.astype(np.int64), device=feat_table.device)] *= -1
+            clean, hot_set = frows, set(hot.tolist())
+
+            def frows(ids):
+                rows = clean(ids)
+                flip = np.asarray([int(v) in hot_set for v in np.asarray(ids).tolist()], dtype=bool)
+                rows[flip] = -rows[flip]
+                return rows
+    else:
+        caches = G.make_oracle_caches(w, capacity=capacity, t_stale=t_stale)
     from paper_2301_07482_amd.pipeline import DeviceBatch
-    frows = G.feature_accessor(w)
+    served = 0
     dims = wl.layer_dims(w)
     L = w.num_layers
     p = w.p_grad if p_grad is None else p_grad
@@ -439,7 +467,17 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
             mb = wl.minibatch(w, g, it)
             gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
             bt = DeviceBatch(mb, gn)                       # uploaded before the oracle prunes its copy of the blocks
-            rec = O.iteration(mb, it, caches, frows, weights, gn, p, dims, w.feat_dtype, w.compute_dtype)
+            if bc is not None:
+                # what the loader is about to find on the feature side, for every node of the input layer (or a sample)
+                n0 = len(mb.ids[0])
+                pick = np.arange(n0) if sample_rows is None or n0 <= sample_rows else np.sort(
+                    np.random.default_rng(1000 + it).choice(n0, sample_rows, replace=False))
+                ranks, found = hp.feature_ranks(bt.ids[0], n0)
+                assert np.array_equal(ranks[pick], np.asarray([bc.feature_rank(int(v)) for v in mb.ids[0][pick]], dtype=np.int32)), \
+                    f"feature-side ranks, iteration {it}"
+                assert found == int((ranks >= 0).sum())
+            rec = O.iteration(mb, it, caches, frows, weights, gn, p, dims, w.feat_dtype, w.compute_dtype, feature_side=bc)
+            served += int(rec["feature_from_buffer"].sum())
             # device cache rows at the slots about to be hit, read before this iteration's update recycles slots
             pre_rows = {l: hp.cache_rows(l, rec["look"][l]["hit_slot"]) for l in range(1, L) if len(rec["look"][l]["hit_pos"])}
             hp.run(bt, it)
@@ -514,9 +552,27 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
             filled = np.flatnonzero(oc.slot_node >= 0)
             n_valid = sum(1 for s in filled if oc.slot_of(int(oc.slot_node[s]), iterations) == s)
             assert n_valid == len(exp["nodes"])
+        if bc is not None:
+            # every feature row still intact on the oracle's side holds the same bytes in the device's buffer
+            addr, nbytes = FGB.fg_cache_buffer(hp.cache)
+            assert nbytes == bc.buffer_bytes
+            wb = bc.feat_row_bytes
+            intact = np.asarray([r for r, v in enumerate(hot) if bc.feature_rank(int(v)) == r], dtype=np.int64)
+            if sample_rows is not None and len(intact) > sample_rows:
+                intact = np.sort(np.random.default_rng(5).choice(intact, sample_rows, replace=False))
+            from paper_2301_07482_amd.pipeline import _tensor_from_ptr
+            lo = nbytes - len(hot) * wb
+            region = _tensor_from_ptr(addr + lo, (len(hot), wb), torch.uint8, len(hot) * wb, "cuda")
+            got = region[torch.as_tensor(len(hot) - 1 - intact, device="cuda")].cpu().numpy()
+            want = np.stack([bc.buf[nbytes - (r + 1) * wb: nbytes - r * wb] for r in intact]) if len(intact) else got
+            assert np.array_equal(got, want), "feature rows in the shared buffer"
+            lost = len(hot) - sum(1 for r, v in enumerate(hot) if bc.feature_rank(int(v)) == r) if sample_rows is None else -1
+            print(f"{w.name}: feature side served {served} input rows, {lost} of {len(hot)} rows displaced")
     finally:
         hp.close()
     print(f"{w.name}: worst rel err same-inputs {worst:.3e}, end-to-end {worst_e2e:.3e}")
+    if fs:
+        return total_hits, worst, served
     return total_hits, worst
 
 
@@ -551,6 +607,78 @@ def test_iterations_tiny_small_ring(env):
     w = wl.WORKLOADS["tiny"]
     hits, _ = run_workload_parity(torch, w, 10, capacity=97, p_grad=0.9)
     assert hits > 0
+
+
+def rings_end(w, capacity=None):
+    """Bytes the rings of workload `w` take at the left end of a shared buffer."""
+    dims, es = wl.layer_dims(w), 4 if w.compute_dtype == "f32" else 2
+    at = 0
+    for l in range(1, w.num_layers):
+        at = -(-at // 256) * 256 + (w.cache_capacity if capacity is None else capacity) * dims[l] * es
+    return at
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_iterations_tiny_feature_side_displaced_by_the_ring(env, fused):
+    """Bidirectional cache (Section 4.2): the buffer starts full of raw features (every byte of it, the ring's included)
+    and the ring eats into them as it fills. The table rows of the cached nodes are negated after the fill, so every
+    row the loader takes from the wrong place fails the bit comparison of H[0] or the numerics."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    cap = 1500                                        # rows of 256 bytes on both sides: the ring overlays ranks 524 .. 2023
+    buffer_bytes = cap * 256 + 524 * 256 + 256
+    n_hot = buffer_bytes // 256
+    hits, worst, served = run_workload_parity(torch, w, 14, capacity=cap, p_grad=0.3, fused=fused,
+                                              feature_side=dict(n_hot=n_hot, buffer_bytes=buffer_bytes, poison=True))
+    assert hits > 0 and served > 500
+
+
+def test_iterations_three_layers_feature_side_two_rings_unaligned_rows(env):
+    """Two rings of 1 KB rows against feature rows of 400 bytes (the medium workload's widths on a small graph): feature
+    rows straddle slot ends and the start of the second ring."""
+    torch, B = env
+    import dataclasses
+    w = dataclasses.replace(wl.WORKLOADS["medium"], name="medium/small", num_nodes=60_000, num_edges=1_500_000, batch=64,
+                            cache_capacity=700, t_stale=4)
+    end = rings_end(w)
+    buffer_bytes = -(-(end + 300 * 400) // 256) * 256
+    n_hot = buffer_bytes // 400
+    for fused in (False, True):
+        hits, worst, served = run_workload_parity(torch, w, 9, p_grad=0.8, fused=fused,
+                                                  feature_side=dict(n_hot=n_hot, buffer_bytes=buffer_bytes, poison=True))
+        assert hits > 0 and served > 0
+
+
+def test_feature_side_state_rules(env):
+    """Features go into an empty cache only; a clear drops them; the row width must match."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    hot = wl.make_graph(w).hottest(64)
+    hp, _, feat = G.make_hotpath(w, hot_ids=hot, buffer_bytes=rings_end(w) + 64 * 256)
+    try:
+        ids = dev(torch, hot[:10].astype(np.int32))
+        assert hp.feature_ranks(ids, 10)[0].tolist() == list(range(10))
+        out = torch.zeros((10, 32), dtype=torch.float32, device="cuda")
+        with pytest.raises(B.FgError) as e:           # half-width rows
+            B.fg_gather_features(hp.cache, feat, w.num_nodes, 256, 128, ids, None, None, 10, out, 10, 128)
+        assert e.value.code == B.FG_ERR_SHAPE
+        from paper_2301_07482_amd.pipeline import DeviceBatch
+        mb = wl.minibatch(w, wl.make_graph(w), 0)
+        hp.run(DeviceBatch(mb, {1: wl.grad_norms(w, 0, 1, mb.ids[1])}), 0)
+        with pytest.raises(B.FgError) as e:           # the embedding side is no longer empty
+            B.fg_cache_fill_features(hp.cache, ids, 10, feat, w.num_nodes, 256, 256)
+        assert e.value.code == B.FG_ERR_STATE
+        B.fg_cache_clear(hp.cache)
+        assert B.fg_cache_feature_rows(hp.cache) == 0
+        assert hp.feature_ranks(ids, 10)[0].tolist() == [-1] * 10
+        B.fg_cache_fill_features(hp.cache, ids, 10, feat, w.num_nodes, 256, 256)
+        assert hp.feature_ranks(ids, 10)[0].tolist() == list(range(10))
+        bad = dev(torch, np.asarray([5, -1, w.num_nodes, 7], dtype=np.int32))     # ids out of range leave their rank unused
+        B.fg_cache_fill_features(hp.cache, bad, 4, feat, w.num_nodes, 256, 256)
+        probe = dev(torch, np.asarray([5, 7, -1, w.num_nodes, 6], dtype=np.int32))
+        assert hp.feature_ranks(probe, 5)[0].tolist() == [0, 3, -1, -1, -1]
+    finally:
+        hp.close()
 
 
 def test_iterations_tiny_fused_input(env):
@@ -606,6 +734,20 @@ def test_iterations_large_host_resident(env):
     hits, worst = run_workload_parity(torch, w, 6, check_numeric_every=5, sample_rows=20000, fused=True)
     print(f"large_host: {hits} hits, worst rel err {worst:.3e}")
     assert hits > 0
+
+
+def test_iterations_large_host_resident_feature_side(env):
+    """The host-resident workload with the raw features of the 300,000 hottest nodes on the feature side of the caches'
+    buffer (the configuration bench.py --workload large_host --feature-rows times, with fewer rows so that the CPU side
+    stays within minutes): ranks and gathered rows compared on samples, index work in full."""
+    torch, B = env
+    w = wl.WORKLOADS["large_host"]
+    n_hot = 300_000
+    buffer_bytes = -(-(rings_end(w) + n_hot * 512) // 256) * 256
+    hits, worst, served = run_workload_parity(torch, w, 4, check_numeric_every=3, sample_rows=20000, fused=True,
+                                              feature_side=dict(n_hot=n_hot, buffer_bytes=buffer_bytes))
+    print(f"large_host with feature side: {hits} hits, {served} input rows from the buffer, worst rel err {worst:.3e}")
+    assert served > 10000
 
 
 def test_iterations_large_host_resident_separate_gather(env):
