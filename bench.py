@@ -63,6 +63,9 @@ def main():
                     help="one fg_cache_update per layer instead of one fg_cache_update_all")
     ap.add_argument("--bracket-every", type=int, default=5,
                     help="time the two longest calls with HIP events on every k-th step of the timed region")
+    ap.add_argument("--feature-rows", type=int, default=0,
+                    help="bidirectional cache: place the raw features of this many hottest nodes on the feature side of the "
+                         "caches' buffer (beyond the rings, so none is displaced) and load through it")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy before the warm-up, as the known-size "
                          "reference for scaling hardware traffic counters")
@@ -82,8 +85,9 @@ def main():
                                 p_grad=w.p_grad if args.p_grad is None else args.p_grad)
         wl.WORKLOADS[w.name] = w
     total = args.warmup + args.steps
+    extra = min(args.steps, 20)        # further mini-batches for the per-call breakdown pass after the timed region
     t0 = time.time()
-    sampled = sample_batches(w.name, total, args.sample_workers)
+    sampled = sample_batches(w.name, total + extra, args.sample_workers)
     t_sample = time.time() - t0
 
     import numpy as np
@@ -93,7 +97,13 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     t0 = time.time()
-    hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + 32)
+    hot = buffer_bytes = None
+    if args.feature_rows > 0:
+        hot = wl.make_graph(w).hottest(args.feature_rows)
+        row = w.feat_dim * (4 if w.feat_dtype == "f32" else 2)
+        buffer_bytes = -(-(G.rings_bytes(w) + len(hot) * row) // 256) * 256
+    hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + extra + 32,
+                                       hot_ids=hot, buffer_bytes=buffer_bytes)
     if args.per_layer_update:
         hp.update_all = False
     if args.tune:
@@ -101,7 +111,7 @@ def main():
         for kv in args.tune:
             key, value = kv.split("=")
             B.fg_set_tuning(key, int(value))
-    batches = [DeviceBatch(mb, gn) for mb, gn in sampled]
+    batches = [DeviceBatch(mb, gn) for mb, gn in sampled[:total]]
     torch.cuda.synchronize()
     t_setup = time.time() - t0
     L = hp.L
@@ -163,15 +173,19 @@ def main():
 
     timed_ms = spans(ev)
 
-    # breakdown pass (not part of `value`): the same steps replayed on fresh copies of the blocks with events around
-    # every call. The cache has moved on, so hit counts differ slightly from the timed steps; it is a profile, not a result.
+    # breakdown pass (not part of `value`): the iterations that follow the timed ones, on their own mini-batches, with
+    # events around every call. It is a profile, not a result.
     ev2 = []
-    extra = min(args.steps, 20)
-    replay = [DeviceBatch(*sampled[args.warmup + k]) for k in range(extra)]
+    replay_from_buffer = []
+    replay = [DeviceBatch(*sampled[total + k]) for k in range(extra)]
     for k in range(extra):
         step_events = {}
         hp.run(replay[k], args.warmup + args.steps + k, timer=timer_for(step_events))
         ev2.append(step_events)
+        if hp.feature_side and args.no_fuse:   # the input list of this step, before the next one overwrites it
+            ranks = torch.as_tensor(hp.feature_ranks(replay[k].ids[0], replay[k].n[0])[0], device="cuda")
+            pos = hp.normal_pos[0][:int(hp.counts[0][2].item())].long()
+            replay_from_buffer.append(float((ranks[pos] >= 0).sum().item()))
     torch.cuda.synchronize()
     call_avg_ms = spans(ev2)
 
@@ -201,7 +215,25 @@ def main():
                                       for e, c in zip(edges, counts)]))
         n_input = float(np.mean(edges)) + float(np.mean([c[1][2] for c in counts]))   # table rows read (edges + own rows)
         dom_kernel = "aggregate_mean_kernel<.., true> (fg_gather_aggregate: loader fused with the layer-1 mean)"
-    # edges under normal rows of block 1 (host copy of the block and the device-side normal list are both known)
+    # rows the loader found on the feature side instead of reading them from the table (the placed rows lie beyond the
+    # rings, so which nodes are there does not change during the run)
+    from_buffer = 0.0
+    if hp.feature_side:
+        per_step = []
+        for it in roof_it:
+            bt = batches[it]
+            ranks = torch.as_tensor(hp.feature_ranks(bt.ids[0], bt.n[0])[0], device="cuda")
+            if args.no_fuse:       # counted on the steps of the breakdown pass
+                per_step = replay_from_buffer
+                break
+            else:
+                deg = (bt.end[1] - bt.start[1]).long()
+                first = torch.repeat_interleave(bt.start[1].long(), deg)
+                offs = torch.arange(int(deg.sum().item()), device="cuda") - torch.repeat_interleave(torch.cumsum(deg, 0) - deg, deg)
+                src = bt.col[1].long()[first + offs]
+                own = torch.nonzero(deg > 0).flatten()   # a lower bound of the normal rows (those left with neighbours)
+                per_step.append(float((ranks[src] >= 0).sum().item() + (ranks[own] >= 0).sum().item()))
+        from_buffer = float(np.mean(per_step))
     agg_bytes = {}
     lin_flops = {}
     lin_bytes = {}
@@ -215,7 +247,7 @@ def main():
     gather_ms = timed_ms[LOADER]
     if w.feat_location == "host":
         # host-resident table: the loader is bound by the host link, priced on the table bytes that cross it
-        link_bytes = n_input * feat_row
+        link_bytes = (n_input - from_buffer) * feat_row
         loader_roof = dict(bound="host_link", kernel=dom_kernel, achieved=link_bytes / (gather_ms * 1e-3) / 1e9,
                            peak=PCIE5_X16_GBS, unit="GB/s", frac=link_bytes / (gather_ms * 1e-3) / 1e9 / PCIE5_X16_GBS,
                            traffic=None, bytes_per_launch=link_bytes, ms_per_launch=gather_ms)
@@ -297,15 +329,18 @@ def main():
                    "feat_dtype": w.feat_dtype, "features": w.feat_location, "layers": L, "hidden": w.hidden,
                    "fanouts": list(w.fanouts), "batch": w.batch, "cache_slots_per_layer": w.cache_capacity,
                    "t_stale": w.t_stale, "p_grad": w.p_grad, "cache": not args.no_cache,
-                   "fused_loader": not args.no_fuse, "seed": w.seed},
+                   "fused_loader": not args.no_fuse, "feature_rows": int(args.feature_rows), "seed": w.seed},
         "roofline": roofline,
         "roofline_2": roofline_2,
         "cpu_baseline": cpu_baseline,
         "per_call_ms": {k: round(v, 5) for k, v in sorted(call_avg_ms.items())},
         "dominant_call": dom,
         "hbm_path": hbm_path,
-        "per_step": {"table_rows_read": n_input, "table_rows_without_cache": rows_no_cache,
-                     "io_saving": 1.0 - n_input / rows_no_cache if rows_no_cache else 0.0, "input_rows_sampled": n0_all,
+        "per_step": {"table_rows_read": n_input - from_buffer, "rows_from_feature_side": from_buffer,
+                     "table_rows_without_cache": rows_no_cache,
+                     "io_saving": 1.0 - (n_input - from_buffer) / rows_no_cache if rows_no_cache else 0.0,
+                     "io_saving_embeddings_only": 1.0 - n_input / rows_no_cache if rows_no_cache else 0.0,
+                     "input_rows_sampled": n0_all,
                      "hits": hits, "gather_bytes": gather_bytes, "linear_flops": lin_flops},
         "host": {"sampling_s": t_sample, "setup_s": t_setup},
     }

@@ -29,6 +29,15 @@ def make_oracle_caches(w, capacity=None, t_stale=None):
             for l in range(1, w.num_layers)}
 
 
+def rings_bytes(w, capacity=None):
+    """Bytes the rings of workload `w` take at the left end of a shared buffer (each ring starts at a multiple of 256)."""
+    dims, es = wl.layer_dims(w), 4 if w.compute_dtype == "f32" else 2
+    at = 0
+    for l in range(1, w.num_layers):
+        at = -(-at // 256) * 256 + (w.cache_capacity if capacity is None else capacity) * dims[l] * es
+    return at
+
+
 def make_oracle_bidirectional(w, buffer_bytes, capacity=None, t_stale=None):
     """The oracle's shared buffer for workload `w`; its rings take the place of `make_oracle_caches`."""
     dims = wl.layer_dims(w)

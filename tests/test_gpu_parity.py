@@ -609,13 +609,7 @@ def test_iterations_tiny_small_ring(env):
     assert hits > 0
 
 
-def rings_end(w, capacity=None):
-    """Bytes the rings of workload `w` take at the left end of a shared buffer."""
-    dims, es = wl.layer_dims(w), 4 if w.compute_dtype == "f32" else 2
-    at = 0
-    for l in range(1, w.num_layers):
-        at = -(-at // 256) * 256 + (w.cache_capacity if capacity is None else capacity) * dims[l] * es
-    return at
+rings_end = G.rings_bytes
 
 
 @pytest.mark.parametrize("fused", [False, True])
