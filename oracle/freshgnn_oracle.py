@@ -15,6 +15,9 @@ once to the storage type:
   update     (Alg. 1, Update line; Sections 4.1.1, 4.1.2, 4.2): `cache_update`
   feature side of the bidirectional cache (Section 4.2): `BidirectionalCache`, `hot_order`;
              `iteration(..., feature_side=...)` loads raw features through it
+  backward   (Alg. 1, the loss and loss.backward() lines; Section 4.1.1: the embedding gradients whose norms
+             drive admission and check-out): `softmax_xent_grad`, `layer_backward`, `row_norms`, `backward`;
+             `iteration(..., labels=...)` takes the gradient norms from it instead of from the caller
 
 Where the paper leaves something open (the Update procedure has no printed body;
 mini-batch layout; percentile ties; slot capacity) the reading taken is stated in
@@ -25,7 +28,8 @@ graphs with full neighbourhoods; closed forms of the mean; identity-panel
 weights; a depth-first "needed set" for the pruning; a dictionary model of the
 cache; hand-worked admit/evict/staleness/ring traces; the degenerate settings of
 Section 4.1.3; for the shared buffer a byte-by-byte model of what has been overwritten,
-a hand-worked displacement trace, and the bit-identity of every loaded feature row. The I/O-saving percentages the paper reports depend on its
+a hand-worked displacement trace, and the bit-identity of every loaded feature row; for the backward
+pass central finite differences of the loss through the forward functions of this file. The I/O-saving percentages the paper reports depend on its
 datasets and real gradients: parity unpinned for those, they are not reproduced.
 """
 import numpy as np
@@ -335,6 +339,88 @@ def linear(h_self, agg, W, b, relu):
     return np.maximum(z, 0.0) if relu else z
 
 
+# --------------------------------------------------------------------------- loss and backward pass
+
+def softmax_xent(h, labels):
+    """Mean softmax cross-entropy of the seed outputs (the loss line of Alg. 1; the paper does not fix the loss,
+    node classification is its task): L = -(1/n) sum_i log softmax(h_i)[label_i], in float64."""
+    h = np.asarray(h, dtype=np.float64)
+    z = h - h.max(axis=1, keepdims=True)
+    logp = z - np.log(np.exp(z).sum(axis=1, keepdims=True))
+    return float(-logp[np.arange(len(h)), np.asarray(labels)].mean()) if len(h) else 0.0
+
+
+def softmax_xent_grad(h, labels):
+    """dL/dh for `softmax_xent`: (softmax(h_i) - onehot(label_i)) / n, float64 [n, d]."""
+    h = np.asarray(h, dtype=np.float64)
+    if len(h) == 0:
+        return np.zeros_like(h)
+    z = h - h.max(axis=1, keepdims=True)
+    p = np.exp(z)
+    p /= p.sum(axis=1, keepdims=True)
+    p[np.arange(len(h)), np.asarray(labels)] -= 1.0
+    return p / len(h)
+
+
+def row_norms(x):
+    """L2 norm of every row (the "magnitude of embedding gradients" of Section 4.1.1), float64."""
+    x = np.asarray(x, dtype=np.float64)
+    return np.sqrt((x * x).sum(axis=1))
+
+
+def layer_backward(start, end, col, rows, dh, h_out, h_self, agg, W, n_src, relu):
+    """Backward of one GraphSAGE-mean layer (Eq. 1 with the readings of `aggregate` and `linear`) for the rows in
+    `rows` (V_normal of the layer; fetched and pruned rows were not computed, so nothing flows below them).
+
+    dh      dL/dH(l) by position [n_l, d_out]      h_out  H(l) by position (ReLU passes gradient where it is > 0)
+    h_self  H(l-1)[rows], agg = the means that entered the layer, both [len(rows), d_in]
+    Returns dL/dH(l-1) by position [n_src, d_in], dL/dW [2*d_in, d_out], dL/db [d_out], all float64:
+      dz = dh[rows] * (h_out[rows] > 0)  (no mask after the last layer)
+      dW = [h_self ‖ agg]^T dz,  db = sum of dz,  [d_self ‖ d_agg] = dz W^T
+      dH(l-1)[r] += d_self  for r in rows;  dH(l-1)[c] += d_agg / deg(r)  for every sampled neighbour c of r
+    """
+    W = np.asarray(W, dtype=np.float64)
+    d_in = W.shape[0] // 2
+    dz = np.asarray(dh, dtype=np.float64)[rows]
+    if relu:
+        dz = dz * (np.asarray(h_out)[rows] > 0)
+    x = np.concatenate([np.asarray(h_self, dtype=np.float64), np.asarray(agg, dtype=np.float64)], axis=1)
+    dW = x.T @ dz
+    db = dz.sum(axis=0)
+    dx = dz @ W.T
+    dsrc = np.zeros((n_src, d_in), dtype=np.float64)
+    for k, r in enumerate(rows):
+        dsrc[r] += dx[k, :d_in]
+        nb = col[start[r]:end[r]]
+        if len(nb):
+            np.add.at(dsrc, nb, dx[k, d_in:] / float(len(nb)))
+    return dsrc, dW, db
+
+
+def backward(mb, rec, weights, labels, compute_dtype="f32"):
+    """loss.backward() of Alg. 1 over the pruned mini-batch of one `iteration` record.
+
+    Gradients flow from the seeds down through the rows that were computed (V_normal); a fetched embedding
+    receives its gradient (that is the "zero-cost" signal of Section 4.1.1) and passes nothing below.
+    Returns dH[l] (float64 by position, l = 1..L), gnorm[l] = row norms rounded to float32 (l = 1..L-1),
+    dW[l], db[l]. The gradient with respect to raw features is not formed.
+    """
+    L = mb.num_layers
+    H, AGG, look = rec["H"], rec["AGG"], rec["look"]
+    dH = {L: softmax_xent_grad(H[L], labels)}
+    dW, db = {}, {}
+    for l in range(L, 0, -1):
+        rows = look[l]["normal_pos"]
+        h_prev = np.asarray(H[l - 1])
+        h_self = round_bf16(h_prev[rows].astype(np.float64)) if compute_dtype == "bf16" else h_prev[rows]
+        dsrc, dW[l], db[l] = layer_backward(mb.start[l], mb.end[l], mb.col[l], rows, dH[l], H[l], h_self, AGG[l], weights[l][0],
+                                            len(mb.ids[l - 1]), relu=(l < L))
+        if l >= 2:
+            dH[l - 1] = dsrc
+    gnorm = {l: row_norms(dH[l]).astype(np.float32) for l in range(1, L)}
+    return dict(dH=dH, gnorm=gnorm, dW=dW, db=db)
+
+
 # --------------------------------------------------------------------------- Update(C, V_normal, V, h, i, t_stale, p_grad)
 
 def admission_threshold(g_live, p_grad):
@@ -417,7 +503,7 @@ def check_minibatch(mb):
 
 
 def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_dtype="f32", compute_dtype="f32",
-              update=True, feature_side=None):
+              update=True, feature_side=None, labels=None):
     """One pass of Algorithm 1 without loss/backward (gradient norms are given).
 
     mb        sampled mini-batch (its `end` arrays are modified: pruning)
@@ -425,6 +511,8 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
     feature_rows(ids) -> raw feature rows; weights[l] = (W_l, b_l); gnorms[l] = norms by position
     dims      [d_0..d_L]
     feature_side   optional BidirectionalCache whose rings are `caches`: raw features are loaded through it
+    labels    optional class of every seed: the gradient norms then come from `backward` (softmax cross-entropy on
+              H(L)) and `gnorms` is ignored
     Types: H(0) in feat_dtype; H(l), AGG(l) for l >= 1 in compute_dtype except H(L) which is fp32.
     In the bf16 setting the own rows and the mean are rounded to bf16 before the product and W is bf16.
     Returns a record of every intermediate the GPU path exposes.
@@ -469,6 +557,10 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
         z = linear(h_self, AGG[l], W, b, relu=(l < L))
         H[l][rows] = round_to(z, out_dtype)
     stats = {}
+    rec.update(live=live, look=look, H=H, AGG=AGG)
+    if labels is not None:
+        rec["backward"] = backward(mb, rec, weights, labels, compute_dtype)
+        gnorms = rec["backward"]["gnorm"]
     if update:
         for l in range(1, L):
             if caches.get(l) is not None:

@@ -7,6 +7,7 @@ import textwrap
 import pytest
 
 from oracle import freshgnn_oracle as O
+from tests import test_oracle_backward as BW
 from tests import test_oracle_feature_side as F
 from tests import test_oracle_pins as P
 
@@ -33,6 +34,11 @@ PINS = [
     (F.test_one_ring_keeps_a_prefix_of_the_hot_list, [()]),
     (F.test_hot_order_properties, [()]),
     (F.test_feature_side_changes_where_rows_come_from_and_nothing_else, [()]),
+    (BW.test_loss_gradient_against_finite_differences_and_row_sums, [()]),
+    (BW.test_row_norms, [()]),
+    (BW.test_embedding_gradients_against_finite_differences, [(2, 0), (3, 1), (3, 2)]),
+    (BW.test_weight_gradients_against_finite_differences, [()]),
+    (BW.test_gradient_norms_from_the_backward_pass_drive_the_update, [()]),
 ]
 
 # (owner, function, text in its source, replacement)
@@ -93,6 +99,27 @@ MUTANTS = [
     ("bf16 rows are laid down as their low halves", None, "row_image", ">> np.uint32(16)", "& np.uint32(0xFFFF)"),
     ("the hot list is in ascending order of the estimate", None, "hot_order", "(-score[v], v)", "(score[v], v)"),
     ("ties in the hot list go to the larger id", None, "hot_order", "(-score[v], v)", "(-score[v], -v)"),
+    ("the loss gradient is not averaged over the batch", None, "softmax_xent_grad", "return p / len(h)", "return p"),
+    ("the loss gradient forgets the label term", None, "softmax_xent_grad", "p[np.arange(len(h)), np.asarray(labels)] -= 1.0", "pass"),
+    ("row norms are sums of squares", None, "row_norms", "np.sqrt((x * x).sum(axis=1))", "(x * x).sum(axis=1)"),
+    ("row norms are 1-norms", None, "row_norms", "np.sqrt((x * x).sum(axis=1))", "np.abs(x).sum(axis=1)"),
+    ("the backward pass ignores the ReLU", None, "layer_backward", "if relu:", "if False:"),
+    ("the ReLU mask lets zeros through", None, "layer_backward", "np.asarray(h_out)[rows] > 0)", "np.asarray(h_out)[rows] >= 0)"),
+    ("the backward pass masks the last layer too", None, "backward", "relu=(l < L))", "relu=True)"),
+    ("self and neighbour halves of the input gradient are swapped", None, "layer_backward",
+     "dsrc[r] += dx[k, :d_in]", "dsrc[r] += dx[k, d_in:]"),
+    ("the neighbours' share is not divided by the degree", None, "layer_backward", "dx[k, d_in:] / float(len(nb))", "dx[k, d_in:]"),
+    ("the neighbours' share is divided by degree + 1", None, "layer_backward", "/ float(len(nb)))", "/ float(len(nb) + 1))"),
+    ("a row's own previous embedding receives no gradient", None, "layer_backward", "dsrc[r] += dx[k, :d_in]", "pass"),
+    ("a neighbour sampled by several rows keeps only the last contribution", None, "layer_backward",
+     "np.add.at(dsrc, nb, dx[k, d_in:] / float(len(nb)))", "dsrc[nb] = dx[k, d_in:] / float(len(nb))"),
+    ("the weight gradient swaps its panels", None, "layer_backward",
+     "np.concatenate([np.asarray(h_self, dtype=np.float64), np.asarray(agg, dtype=np.float64)], axis=1)",
+     "np.concatenate([np.asarray(agg, dtype=np.float64), np.asarray(h_self, dtype=np.float64)], axis=1)"),
+    ("the bias gradient is a mean", None, "layer_backward", "db = dz.sum(axis=0)", "db = dz.mean(axis=0)"),
+    ("the input gradient uses the untransposed weights of the self panel twice", None, "layer_backward", "dx = dz @ W.T",
+     "dx = dz @ np.concatenate([W[:d_in], W[:d_in]]).T"),
+    ("gradient norms are taken one layer off", None, "backward", "gnorm = {l: row_norms(dH[l])", "gnorm = {l: row_norms(dH[l + 1])"),
     ("cached feature rows are read at the neighbouring rank", "BidirectionalCache", "load",
      "out[k] = self.buf[B - (r + 1) * w:B - r * w].view(np_dt)", "out[k] = self.buf[B - (r + 2) * w:B - (r + 1) * w].view(np_dt) if r + 2 <= self.n_feat else 0"),
 ]
