@@ -86,3 +86,19 @@ def sample_minibatch(graph, seeds, fanouts, key):
     ids = [x.astype(np.int32) for x in ids]
     return MiniBatch(L, ids, start, end, col)
 
+
+
+def transpose_block(start, end, col, n_src):
+    """The transpose of one sampled block: for every source position j the rows that sampled it, as
+    (t_start[j], t_end[j]) into t_row, rows in ascending order. Built from the block as sampled (before any pruning)."""
+    start = np.asarray(start, dtype=np.int64)
+    end = np.asarray(end, dtype=np.int64)
+    deg = end - start
+    rows = np.repeat(np.arange(len(start), dtype=np.int64), deg)
+    within = np.arange(len(rows), dtype=np.int64) - np.repeat(np.cumsum(deg) - deg, deg)
+    src = np.asarray(col, dtype=np.int64)[np.repeat(start, deg) + within] if len(rows) else np.zeros(0, dtype=np.int64)
+    order = np.argsort(src, kind="stable")
+    counts = np.bincount(src, minlength=n_src)
+    t_end = np.cumsum(counts)
+    t_start = t_end - counts
+    return t_start.astype(np.int32), t_end.astype(np.int32), rows[order].astype(np.int32)

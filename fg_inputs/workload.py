@@ -102,6 +102,12 @@ def grad_norms(w: Workload, it: int, layer: int, node_ids):
     return np.exp(rng.normal(key, np.asarray(node_ids, dtype=np.int64))).astype(np.float32)
 
 
+def node_labels(w: Workload, node_ids):
+    """Synthetic class of a node, a fixed function of its id, in [0, d_L) (the last layer's width stands for the classes)."""
+    key = rng.make_key(w.seed, 0x1ABE1)
+    return (rng.u64(key, np.asarray(node_ids, dtype=np.int64)) % np.uint64(layer_dims(w)[-1])).astype(np.int32)
+
+
 def _round_bf16(x32):
     """Round fp32 values to the nearest bf16 (ties to even), returned as fp32."""
     b = np.asarray(x32, dtype=np.float32).view(np.uint32)

@@ -380,6 +380,45 @@ typedef struct fg_fetch_layer {
 } fg_fetch_layer_t;
 fg_status_t fg_cache_fetch_all(const fg_cache_t* cache, int32_t n_layers, const fg_fetch_layer_t* layers, void* stream);
 
+/*
+ * ---- Backward pass as far as the embedding gradients (Algorithm 1: loss, loss.backward(); Section 4.1.1) ----
+ * The norms of dL/dh^(l) are the gradient criterion of the cache: fg_row_norms of what fg_layer_backward produces
+ * is the gnorm_dev of fg_cache_update. fp32 throughout; sums in fp64.
+ *
+ * fg_softmax_xent_grad: dh[i, c] = (softmax(h[i, :])[c] - [c == labels[i]]) / n, the gradient of the mean softmax
+ * cross-entropy over the n seed rows (the paper trains node classifiers and does not fix the loss further).
+ * A label outside [0, d) leaves out the subtraction for that row.
+ */
+fg_status_t fg_softmax_xent_grad(const float* h_dev, int64_t h_stride, const int32_t* labels_dev, int32_t n, int32_t d,
+                                 float* dh_dev, int64_t dh_stride, void* stream);
+/* norms_dev[i] = sqrt(sum_c x[i, c]^2) for i < n (the magnitude of an embedding's gradient, Section 4.1.1). */
+fg_status_t fg_row_norms(const float* x_dev, int64_t x_stride, int32_t n, int32_t d, float* norms_dev, void* stream);
+/*
+ * Gradient with respect to the inputs of one GraphSAGE-mean layer (the transpose of fg_aggregate + fg_linear):
+ *   dz[k, :] = dh[r, :] * (h[r, :] > 0), r = rows[k]   (h = the layer's output; NULL = no activation, the last layer)
+ *   [d_self ‖ d_agg][k, :] = dz[k, :] . W^T            (W as given to fg_linear: [2*d_in x d_out])
+ *   dh_src[j, :] = [j = rows[k] for some k] d_self[k, :] + sum over the rows r = rows[k] that sampled j of d_agg[k, :] / deg(r)
+ * for every position j < n_src of the layer below (zeros where nothing arrives). Rows that were fetched from the
+ * cache or pruned are not in `rows` and pass nothing down.
+ *   dh_dev, dh_stride, h_dev, h_stride   dL/dH(l) and H(l) by position, n rows of d_out floats
+ *   rows_dev, n_rows_dev, max_rows       V_normal of the layer as produced by the top-down pass (max_rows <= n)
+ *   live_dev, hit_dev [n]                the layer's flags (NULL = all live / no hits): position j is in `rows` iff live and not hit
+ *   row_start_dev, row_end_dev [n]       block l after pruning: deg(r) = row_end[r] - row_start[r]; rows not in `rows` must have deg 0
+ *   t_start_dev, t_end_dev [n_src], t_row_dev [nnz]   the transpose of the sampled block: the rows that sampled position j are
+ *                                        t_row[t_start[j] .. t_end[j]) (of the block before pruning; pruned rows are skipped by deg 0)
+ *   W, d_in, d_out                       the layer's weights; d_in a multiple of 4, d_out of 8
+ *   dh_src_dev, dh_src_stride            out: dL/dH(l-1) by position [n_src x d_in], 16-byte aligned
+ *   ws_dev, ws_bytes                     device workspace >= fg_layer_backward_workspace_bytes(n, max_rows, d_in, d_out), 16-byte aligned
+ * No atomics: every output row has one writer, so results do not depend on scheduling.
+ */
+size_t fg_layer_backward_workspace_bytes(int32_t n, int64_t max_rows, int32_t d_in, int32_t d_out);
+fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride, const float* h_dev, int64_t h_stride, int32_t n,
+                              const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows, const uint8_t* live_dev,
+                              const uint8_t* hit_dev, const int32_t* row_start_dev, const int32_t* row_end_dev,
+                              const int32_t* t_start_dev, const int32_t* t_end_dev, const int32_t* t_row_dev, int64_t nnz,
+                              int32_t n_src, int32_t d_in, int32_t d_out, const float* W, float* dh_src_dev,
+                              int64_t dh_src_stride, void* ws_dev, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -50,6 +50,11 @@ SIGNATURES = {
                                    _p, _i64, _i32, _p]),
     "fg_linear": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _p, _i64, _i32, _i32, _p, _i32, _p, _i32, _p, _i32, _i64, _i32, _p]),
     "fg_cache_update": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _f, _p, _i64, _p, _p, _sz, _p]),
+    "fg_softmax_xent_grad": (_i32, [_p, _i64, _p, _i32, _i32, _p, _i64, _p]),
+    "fg_row_norms": (_i32, [_p, _i64, _i32, _i32, _p, _p]),
+    "fg_layer_backward_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32]),
+    "fg_layer_backward": (_i32, [_p, _i64, _p, _i64, _i32, _p, _p, _i64, _p, _p, _p, _p, _p, _p, _p, _i64, _i32, _i32, _i32, _p, _p,
+                                 _i64, _p, _sz, _p]),
 }
 
 
@@ -251,6 +256,25 @@ def fg_linear(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows, n_rows,
 def fg_cache_update(cache, layer, it, ids, n, live, hit, gnorm, p_grad, h, h_stride, stats, ws, ws_bytes, stream=None):
     _check(_lib.fg_cache_update(cache, layer, it, ptr(ids), n, ptr(live), ptr(hit), ptr(gnorm), p_grad, ptr(h), h_stride,
                                 ptr(stats), ptr(ws), ws_bytes, stream))
+
+
+def fg_softmax_xent_grad(h, h_stride, labels, n, d, dh, dh_stride, stream=None):
+    _check(_lib.fg_softmax_xent_grad(ptr(h), h_stride, ptr(labels), n, d, ptr(dh), dh_stride, stream))
+
+
+def fg_row_norms(x, x_stride, n, d, norms, stream=None):
+    _check(_lib.fg_row_norms(ptr(x), x_stride, n, d, ptr(norms), stream))
+
+
+def fg_layer_backward_workspace_bytes(n, max_rows, d_in, d_out):
+    return _lib.fg_layer_backward_workspace_bytes(n, max_rows, d_in, d_out)
+
+
+def fg_layer_backward(dh, dh_stride, h, h_stride, n, rows, n_rows, max_rows, live, hit, row_start, row_end, t_start, t_end, t_row,
+                      nnz, n_src, d_in, d_out, W, dh_src, dh_src_stride, ws, ws_bytes, stream=None):
+    _check(_lib.fg_layer_backward(ptr(dh), dh_stride, ptr(h), h_stride, n, ptr(rows), ptr(n_rows), max_rows, ptr(live), ptr(hit),
+                                  ptr(row_start), ptr(row_end), ptr(t_start), ptr(t_end), ptr(t_row), nnz, n_src, d_in, d_out,
+                                  ptr(W), ptr(dh_src), dh_src_stride, ptr(ws), ws_bytes, stream))
 
 
 def _struct_array(struct, specs):

@@ -1,0 +1,285 @@
+// Backward pass of the GraphSAGE-mean layers as far as the embedding gradients (Algorithm 1: loss, loss.backward();
+// Section 4.1.1: the norms of dL/dh are what admission to and check-out from the historical cache are decided on).
+//
+//   fg_softmax_xent_grad   dL/dH(L) of the mean softmax cross-entropy over the seeds
+//   fg_layer_backward      dL/dH(l-1) from dL/dH(l) for one layer: ReLU mask, [d_self ‖ d_agg] = dz . W^T on the
+//                          matrix cores (the forward GEMM path with transposed weights), then the transposed mean
+//                          aggregation as a gather over the block's transpose (no atomics: every output row has one
+//                          writer and the sums are carried in fp64, so the result does not depend on scheduling)
+//   fg_row_norms           L2 norm per row
+//
+// Only rows that were computed (V_normal) pass gradient down; a fetched row receives its gradient and stops there.
+// All of it is small next to the forward pass: the layer below the lowest cached one needs no input gradient.
+#include "common.h"
+
+namespace {
+
+constexpr int BW_THREADS = 256;
+
+__device__ __forceinline__ double wave_sum(double v) {
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+__device__ __forceinline__ double wave_max(double v) {
+    for (int off = 32; off > 0; off >>= 1) {
+        const double o = __shfl_xor(v, off, 64);
+        v = o > v ? o : v;
+    }
+    return v;
+}
+
+// one wavefront per row: p = softmax(h[i, :]) in fp64, dh[i, c] = (p[c] - [c == label]) / n
+__global__ __launch_bounds__(BW_THREADS) void softmax_xent_grad_kernel(const char* __restrict__ h, int64_t h_stride,
+                                                                       const int32_t* __restrict__ labels, int n, int d,
+                                                                       char* __restrict__ dh, int64_t dh_stride) {
+    const int lane = threadIdx.x & 63;
+    const int64_t n_waves = ((int64_t)gridDim.x * BW_THREADS) >> 6;
+    for (int64_t i = ((int64_t)blockIdx.x * BW_THREADS + threadIdx.x) >> 6; i < n; i += n_waves) {
+        const float* row = (const float*)(h + i * h_stride);
+        double m = -1.0e300;
+        for (int c = lane; c < d; c += 64) {
+            const double v = (double)row[c];
+            m = v > m ? v : m;
+        }
+        m = wave_max(m);
+        double s = 0.0;
+        for (int c = lane; c < d; c += 64) s += exp((double)row[c] - m);
+        s = wave_sum(s);
+        const int32_t y = labels[i];
+        float* out = (float*)(dh + i * dh_stride);
+        for (int c = lane; c < d; c += 64) {
+            const double p = exp((double)row[c] - m) / s;
+            out[c] = (float)((p - (c == y ? 1.0 : 0.0)) / (double)n);
+        }
+    }
+}
+
+// one wavefront per row: sqrt of the fp64 sum of squares
+__global__ __launch_bounds__(BW_THREADS) void row_norms_kernel(const char* __restrict__ x, int64_t stride, int n, int d,
+                                                               float* __restrict__ norms) {
+    const int lane = threadIdx.x & 63;
+    const int64_t n_waves = ((int64_t)gridDim.x * BW_THREADS) >> 6;
+    for (int64_t i = ((int64_t)blockIdx.x * BW_THREADS + threadIdx.x) >> 6; i < n; i += n_waves) {
+        const float* row = (const float*)(x + i * stride);
+        double s = 0.0;
+        for (int c = lane; c < d; c += 64) {
+            const double v = (double)row[c];
+            s += v * v;
+        }
+        s = wave_sum(s);
+        if (lane == 0) norms[i] = (float)sqrt(s);
+    }
+}
+
+// dz = dh[r, :] * (h[r, :] > 0) for r = rows[k]. The GEMM that follows takes its first K/2 input columns from a
+// matrix indexed by position and the other K/2 from one indexed by list order, so dz is written in that form:
+// columns [0, half) to dz_pos[r, :], columns [half, d) to dz_cmp[k, :].
+__global__ __launch_bounds__(BW_THREADS) void relu_backward_kernel(const char* __restrict__ dh, int64_t dh_stride,
+                                                                   const char* __restrict__ h, int64_t h_stride, int n,
+                                                                   const int32_t* __restrict__ rows,
+                                                                   const int64_t* __restrict__ n_rows_dev, int64_t max_rows,
+                                                                   int d, float* __restrict__ dz_pos, float* __restrict__ dz_cmp) {
+    int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
+    if (n_rows > max_rows) n_rows = max_rows;
+    const int half = d >> 1;
+    const int lane = threadIdx.x & 63;
+    const int64_t n_waves = ((int64_t)gridDim.x * BW_THREADS) >> 6;
+    for (int64_t k = ((int64_t)blockIdx.x * BW_THREADS + threadIdx.x) >> 6; k < n_rows; k += n_waves) {
+        const int32_t r = rows ? rows[k] : (int32_t)k;
+        if (r < 0 || r >= n) continue;
+        const float* g = (const float*)(dh + (int64_t)r * dh_stride);
+        const float* a = h ? (const float*)(h + (int64_t)r * h_stride) : nullptr;
+        for (int c = lane; c < d; c += 64) {
+            float v = g[c];
+            if (a && !(a[c] > 0.f)) v = 0.f;
+            if (c < half)
+                dz_pos[(int64_t)r * half + c] = v;
+            else
+                dz_cmp[k * half + (c - half)] = v;
+        }
+    }
+}
+
+// wt[c, a] = w[a, c]; w is [rows x cols]
+__global__ __launch_bounds__(BW_THREADS) void transpose_kernel(const float* __restrict__ w, int rows, int cols,
+                                                               float* __restrict__ wt) {
+    __shared__ float tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    const int c0 = blockIdx.x * 32, a0 = blockIdx.y * 32;
+    for (int i = ty; i < 32; i += 8)
+        if (a0 + i < rows && c0 + tx < cols) tile[i][tx] = w[(int64_t)(a0 + i) * cols + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < cols && a0 + tx < rows) wt[(int64_t)(c0 + i) * rows + a0 + tx] = tile[tx][i];
+}
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// Transposed mean aggregation. A group of 2^g lanes owns source position j and 16 bytes of the row per lane:
+//   out[j, :] = [j is a computed row] dx[j, 0:d_in]  +  sum over t in [t_start[j], t_end[j]) with r = t_row[t] computed:
+//               dx[r, d_in:2*d_in] / deg(r),   deg(r) = row_end[r] - row_start[r] of the pruned block
+// A row that was not computed has an empty range in the pruned block (deg = 0) and is skipped by that test; such rows of
+// dx were never written. Every position j < n_src is written (zeros where nothing arrives).
+__global__ __launch_bounds__(BW_THREADS) void aggregate_backward_kernel(
+    const char* __restrict__ dx, int n, int d_in, const uint8_t* __restrict__ live, const uint8_t* __restrict__ hit,
+    const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ t_start,
+    const int32_t* __restrict__ t_end, const int32_t* __restrict__ t_row, int64_t nnz, int n_src, char* __restrict__ out,
+    int64_t out_stride, int lanes_log2) {
+    const int lanes = 1 << lanes_log2;
+    const int lane = threadIdx.x & (lanes - 1);
+    const int gpb = BW_THREADS >> lanes_log2;
+    const int pieces = d_in >> 2;
+    const int64_t dx_stride = (int64_t)2 * d_in * 4;
+    for (int64_t j = (int64_t)blockIdx.x * gpb + (threadIdx.x >> lanes_log2); j < n_src; j += (int64_t)gridDim.x * gpb) {
+        int32_t s0 = t_start[j], e0 = t_end[j];
+        if (s0 < 0 || e0 < s0 || (int64_t)e0 > nnz) s0 = e0 = 0;
+        const bool own = j < n && (live ? live[j] != 0 : true) && (hit ? hit[j] == 0 : true);
+        for (int piece = lane; piece < pieces; piece += lanes) {
+            double acc[4] = {0.0, 0.0, 0.0, 0.0};
+            if (own) {
+                const f32x4 v = *(const f32x4*)(dx + j * dx_stride + (int64_t)piece * 16);
+                acc[0] = v.x; acc[1] = v.y; acc[2] = v.z; acc[3] = v.w;
+            }
+            for (int t = s0; t < e0; t += 4) {
+                f32x4 v[4];
+                double w[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    w[u] = 0.0;
+                    v[u] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if (t + u < e0) {
+                        const int32_t r = t_row[t + u];
+                        if (r >= 0 && r < n) {
+                            const int32_t deg = row_end[r] - row_start[r];
+                            if (deg > 0) {
+                                w[u] = 1.0 / (double)deg;
+                                v[u] = *(const f32x4*)(dx + (int64_t)r * dx_stride + (int64_t)(d_in + 4 * piece) * 4);
+                            }
+                        }
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    acc[0] += (double)v[u].x * w[u];
+                    acc[1] += (double)v[u].y * w[u];
+                    acc[2] += (double)v[u].z * w[u];
+                    acc[3] += (double)v[u].w * w[u];
+                }
+            }
+            const f32x4 o = {(float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]};
+            *(f32x4*)(out + j * out_stride + (int64_t)piece * 16) = o;
+        }
+    }
+}
+
+struct BwWs {
+    size_t dz_pos, dz_cmp, wt, dx, total;
+};
+BwWs bw_layout(int64_t n, int64_t max_rows, int64_t d_in, int64_t d_out) {
+    BwWs w;
+    const size_t half = (size_t)(d_out / 2) * 4;
+    w.dz_pos = 0;
+    w.dz_cmp = fg_align_up((size_t)(n > 0 ? n : 1) * half, 256);
+    w.wt = w.dz_cmp + fg_align_up((size_t)(max_rows > 0 ? max_rows : 1) * half, 256);
+    w.dx = w.wt + fg_align_up((size_t)2 * d_in * d_out * 4, 256);
+    w.total = w.dx + fg_align_up((size_t)(n > 0 ? n : 1) * 2 * d_in * 4, 256);
+    return w;
+}
+
+}  // namespace
+
+extern "C" fg_status_t fg_softmax_xent_grad(const float* h_dev, int64_t h_stride, const int32_t* labels_dev, int32_t n, int32_t d,
+                                            float* dh_dev, int64_t dh_stride, void* stream) {
+    if (n < 0 || d <= 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_softmax_xent_grad: bad size (n %d, d %d)", n, d);
+    if (n > 0 && (!h_dev || !labels_dev || !dh_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_softmax_xent_grad: NULL pointer");
+    if (h_stride < (int64_t)d * 4 || dh_stride < (int64_t)d * 4) FG_FAIL(FG_ERR_SHAPE, "fg_softmax_xent_grad: a row stride is smaller than a row");
+    if (((uintptr_t)h_dev | (uintptr_t)dh_dev | (uintptr_t)h_stride | (uintptr_t)dh_stride) & 3)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_softmax_xent_grad: pointers and strides must be 4-byte aligned");
+    fg_clear_error();
+    if (n == 0) return FG_OK;
+    int64_t blocks = fg_ceil_div(n, BW_THREADS / 64);
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(softmax_xent_grad_kernel, dim3((unsigned)blocks), dim3(BW_THREADS), 0, (hipStream_t)stream, (const char*)h_dev,
+                       h_stride, labels_dev, n, d, (char*)dh_dev, dh_stride);
+    FG_LAUNCH_CHECK("softmax_xent_grad_kernel");
+    return FG_OK;
+}
+
+extern "C" fg_status_t fg_row_norms(const float* x_dev, int64_t x_stride, int32_t n, int32_t d, float* norms_dev, void* stream) {
+    if (n < 0 || d <= 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_row_norms: bad size (n %d, d %d)", n, d);
+    if (n > 0 && (!x_dev || !norms_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_row_norms: NULL pointer");
+    if (x_stride < (int64_t)d * 4) FG_FAIL(FG_ERR_SHAPE, "fg_row_norms: the row stride is smaller than a row");
+    if (((uintptr_t)x_dev | (uintptr_t)x_stride | (uintptr_t)norms_dev) & 3) FG_FAIL(FG_ERR_INVALID_ARG, "fg_row_norms: pointers and stride must be 4-byte aligned");
+    fg_clear_error();
+    if (n == 0) return FG_OK;
+    int64_t blocks = fg_ceil_div(n, BW_THREADS / 64);
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(row_norms_kernel, dim3((unsigned)blocks), dim3(BW_THREADS), 0, (hipStream_t)stream, (const char*)x_dev, x_stride, n,
+                       d, norms_dev);
+    FG_LAUNCH_CHECK("row_norms_kernel");
+    return FG_OK;
+}
+
+extern "C" size_t fg_layer_backward_workspace_bytes(int32_t n, int64_t max_rows, int32_t d_in, int32_t d_out) {
+    if (n < 0 || max_rows < 0 || d_in <= 0 || d_out <= 0) return 0;
+    return bw_layout(n, max_rows, d_in, d_out).total;
+}
+
+extern "C" fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride, const float* h_dev, int64_t h_stride, int32_t n,
+                                         const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                                         const uint8_t* live_dev, const uint8_t* hit_dev, const int32_t* row_start_dev,
+                                         const int32_t* row_end_dev, const int32_t* t_start_dev, const int32_t* t_end_dev,
+                                         const int32_t* t_row_dev, int64_t nnz, int32_t n_src, int32_t d_in, int32_t d_out,
+                                         const float* W, float* dh_src_dev, int64_t dh_src_stride, void* ws_dev, size_t ws_bytes,
+                                         void* stream) {
+    const char* who = "fg_layer_backward";
+    if (n < 0 || max_rows < 0 || n_src < 0 || nnz < 0 || d_in <= 0 || d_out <= 0)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (n %d, max_rows %lld, n_src %d, nnz %lld, d_in %d, d_out %d)", who, n, (long long)max_rows,
+                n_src, (long long)nnz, d_in, d_out);
+    if (n_src < n) FG_FAIL(FG_ERR_SHAPE, "%s: the layer below (%d positions) must contain this layer's %d", who, n_src, n);
+    if (max_rows > n) FG_FAIL(FG_ERR_SHAPE, "%s: max_rows = %lld exceeds the layer's %d positions", who, (long long)max_rows, n);
+    if (d_in % 4 || d_out % 8) FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d must be a multiple of 4 and d_out = %d of 8", who, d_in, d_out);
+    if (n_src > 0 && (!dh_src_dev || !t_start_dev || !t_end_dev || (nnz > 0 && !t_row_dev))) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
+    if (n > 0 && (!dh_dev || !row_start_dev || !row_end_dev || !W)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
+    if (dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * 4) || dh_src_stride < (int64_t)d_in * 4)
+        FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
+    if (((uintptr_t)dh_dev | (uintptr_t)h_dev | (uintptr_t)dh_stride | (uintptr_t)h_stride | (uintptr_t)W) & 3)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: dh, h, W and their strides must be 4-byte aligned", who);
+    if (((uintptr_t)dh_src_dev | (uintptr_t)dh_src_stride | (uintptr_t)ws_dev) & 15)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: dh_src_dev, its stride and the workspace must be 16-byte aligned", who);
+    const BwWs L = bw_layout(n, max_rows, d_in, d_out);
+    if (!ws_dev || ws_bytes < L.total) FG_FAIL(FG_ERR_SHAPE, "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes, L.total);
+    fg_clear_error();
+    hipStream_t st = (hipStream_t)stream;
+    char* ws = (char*)ws_dev;
+    float* dz_pos = (float*)(ws + L.dz_pos);
+    float* dz_cmp = (float*)(ws + L.dz_cmp);
+    float* wt = (float*)(ws + L.wt);
+    float* dx = (float*)(ws + L.dx);
+    const int half = d_out / 2;
+    if (n > 0 && max_rows > 0) {
+        int64_t blocks = fg_ceil_div(max_rows, BW_THREADS / 64);
+        if (blocks > 4096) blocks = 4096;
+        hipLaunchKernelGGL(relu_backward_kernel, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dh_dev, dh_stride,
+                           (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_out, dz_pos, dz_cmp);
+        FG_LAUNCH_CHECK("relu_backward_kernel");
+        hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)fg_ceil_div(d_out, 32), (unsigned)fg_ceil_div(2 * d_in, 32)), dim3(BW_THREADS), 0,
+                           st, W, 2 * d_in, d_out, wt);
+        FG_LAUNCH_CHECK("transpose_kernel");
+        // dx[r, :] = [dz_pos[r, :] ‖ dz_cmp[k, :]] . W^T for r = rows[k]: the forward GEMM with K = d_out, N = 2 * d_in
+        fg_status_t rc = fg_linear(dz_pos, n, (int64_t)half * 4, FG_F32, dz_cmp, (int64_t)half * 4, rows_dev, n_rows_dev, max_rows, half,
+                                   2 * d_in, wt, FG_F32, nullptr, 0, dx, n, (int64_t)2 * d_in * 4, FG_F32, stream);
+        if (rc != FG_OK) return rc;
+    }
+    if (n_src == 0) return FG_OK;
+    const int pieces = d_in / 4;
+    int lg = 0;
+    while ((1 << lg) < pieces && lg < 6) ++lg;
+    const int gpb = BW_THREADS >> lg;
+    int64_t blocks = fg_ceil_div(n_src, gpb);
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(aggregate_backward_kernel, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dx, n, d_in, live_dev,
+                       hit_dev, row_start_dev, row_end_dev, t_start_dev, t_end_dev, t_row_dev, nnz, n_src, (char*)dh_src_dev, dh_src_stride, lg);
+    FG_LAUNCH_CHECK("aggregate_backward_kernel");
+    return FG_OK;
+}

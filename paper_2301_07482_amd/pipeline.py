@@ -28,7 +28,9 @@ def layer_bounds(batch, fanouts, num_nodes):
 class DeviceBatch:
     """A sampled mini-batch resident in device memory (ids, two-row-array blocks, gradient norms)."""
 
-    def __init__(self, mb, gnorms, device="cuda"):
+    def __init__(self, mb, gnorms, device="cuda", labels=None):
+        """gnorms: {layer: norms by position} given from outside, or None when `labels` (the seeds' classes) are given and
+        the norms come from the backward pass; the blocks' transposes are then uploaded too."""
         L = mb.num_layers
         self.num_layers = L
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
@@ -40,6 +42,15 @@ class DeviceBatch:
                              for l in range(1, L + 1)]
         self.nnz = [0] + [len(mb.col[l]) for l in range(1, L + 1)]
         self.gnorm = {l: up(np.asarray(g, dtype=np.float32)) for l, g in (gnorms or {}).items()}
+        self.labels = None
+        if labels is not None:
+            from fg_inputs.sampler import transpose_block
+            self.labels = up(np.asarray(labels, dtype=np.int32))
+            self.t_start, self.t_end, self.t_row = [None] * (L + 1), [None] * (L + 1), [None] * (L + 1)
+            for l in range(2, L + 1):       # the input layer needs no gradient
+                ts, te, tr = transpose_block(mb.start[l], mb.end[l], mb.col[l], len(mb.ids[l - 1]))
+                self.t_start[l], self.t_end[l] = up(ts), up(te)
+                self.t_row[l] = up(tr) if len(tr) else torch.zeros(1, dtype=torch.int32, device=device)
 
 
 class HotPath:
@@ -47,7 +58,7 @@ class HotPath:
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
-                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None):
+                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -104,6 +115,15 @@ class HotPath:
             W, b = weights[l]
             self.W[l] = torch.from_numpy(np.ascontiguousarray(W)).to(dev).to(wt).contiguous()
             self.bias[l] = torch.from_numpy(np.ascontiguousarray(b)).to(dev)
+        # backward: the gradient norms of the update come from the backward pass (softmax cross-entropy on H[L] against
+        # the batch's labels) instead of from the batch; fp32 models only
+        self.backward = backward
+        if backward:
+            assert self.comp_code == B.FG_F32, "the backward pass is fp32"
+            self.dH = [None] + [torch.zeros((n[l], dims[l]), dtype=torch.float32, device=dev) for l in range(1, L + 1)]
+            self.gnorm = [None] + [torch.zeros(max(n[l], 1), dtype=torch.float32, device=dev) for l in range(1, L)]
+            self.ws_bw_bytes = max([B.fg_layer_backward_workspace_bytes(n[l], n[l], dims[l - 1], dims[l]) for l in range(2, L + 1)] or [0])
+            self.ws_bw = torch.zeros(self.ws_bw_bytes + 256, dtype=torch.uint8, device=dev)
         self.cache = None
         self.feature_side = False
         if L > 1:
@@ -220,18 +240,33 @@ class HotPath:
             B.fg_linear(self.H[l - 1], bt.n[l - 1], in_b, in_code, self.AGG, agg_b, self.normal_pos[l], self._cnt(l, 2),
                         bt.n[l], self.dims[l - 1], self.dims[l], self.W[l], self.comp_code, self.bias[l],
                         1 if l < L else 0, self.H[l], bt.n[l], out_b, out_code, st)
+        # ---- loss and backward pass down to layer 1: the gradient norms the update admits and checks out by
+        gnorm = bt.gnorm
+        if self.backward:
+            tick("loss_grad")
+            B.fg_softmax_xent_grad(self.H[L], self.dims[L] * 4, bt.labels, bt.n[L], self.dims[L], self.dH[L], self.dims[L] * 4, st)
+            for l in range(L, 1, -1):
+                tick(f"layer_backward[{l}]")
+                B.fg_layer_backward(self.dH[l], self.dims[l] * 4, self.H[l] if l < L else None, self.dims[l] * 4, bt.n[l],
+                                    self.normal_pos[l], self._cnt(l, 2), bt.n[l], self.live[l] if l < L else None, self.hit[l],
+                                    bt.start[l], bt.end[l], bt.t_start[l], bt.t_end[l], bt.t_row[l], bt.nnz[l], bt.n[l - 1],
+                                    self.dims[l - 1], self.dims[l], self.W[l], self.dH[l - 1], self.dims[l - 1] * 4,
+                                    self.ws_bw, self.ws_bw_bytes, st)
+                tick(f"row_norms[{l - 1}]")
+                B.fg_row_norms(self.dH[l - 1], self.dims[l - 1] * 4, bt.n[l - 1], self.dims[l - 1], self.gnorm[l - 1], st)
+            gnorm = self.gnorm
         # ---- update of the caches
         if do_update and self.update_all:
             tick("cache_update_all")
             specs = [dict(layer=l, n=bt.n[l], ids_dev=bt.ids[l], live_dev=self.live[l], hit_dev=self.hit[l],
-                          gnorm_dev=bt.gnorm[l], h_dev=self.H[l], h_stride=self.dims[l] * esz[self.h_code[l]],
+                          gnorm_dev=gnorm[l], h_dev=self.H[l], h_stride=self.dims[l] * esz[self.h_code[l]],
                           stats_dev=self.stats.data_ptr() + l * 32) for l in range(1, L)]
             B.fg_cache_update_all(self.cache, it, self.p_grad, B.update_layers(specs), self.ws_upd, self.ws_upd_bytes, st)
         elif do_update:
             for l in range(1, L):
                 out_b = self.dims[l] * esz[self.h_code[l]]
                 tick(f"cache_update[{l}]")
-                B.fg_cache_update(self.cache, l, it, bt.ids[l], bt.n[l], self.live[l], self.hit[l], bt.gnorm[l],
+                B.fg_cache_update(self.cache, l, it, bt.ids[l], bt.n[l], self.live[l], self.hit[l], gnorm[l],
                                   self.p_grad, self.H[l], out_b, self.stats.data_ptr() + l * 32, self.ws, self.ws_bytes, st)
         tick(None)
 

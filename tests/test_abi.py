@@ -85,6 +85,21 @@ def test_argument_validation_needs_no_gpu(B):
     assert code(B.fg_gather_aggregate_features, None, 4096, 4096, 4096, 5, 5, None, None, 5, 4096, 9, 4096, 9, 512, 128, B.FG_F32,
                 4096, 512, B.FG_F32) == B.FG_ERR_INVALID_ARG
     assert B.fg_cache_feature_rows(None) == 0 and B.fg_cache_buffer(None) == (None, 0) and B.fg_cache_ring_offset(None, 1) == -1
+    assert code(B.fg_softmax_xent_grad, None, 64, 4096, 4, 16, 4096, 64) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_softmax_xent_grad, 4096, 32, 4096, 4, 16, 4096, 64) == B.FG_ERR_SHAPE                     # stride < row
+    assert code(B.fg_row_norms, 4096, 64, 4, 0, 4096) == B.FG_ERR_INVALID_ARG
+    bw = lambda **k: B.fg_layer_backward(**{**dict(dh=4096, dh_stride=1024, h=4096, h_stride=1024, n=10, rows=4096, n_rows=None,
+                                                   max_rows=10, live=None, hit=None, row_start=4096, row_end=4096, t_start=4096,
+                                                   t_end=4096, t_row=4096, nnz=50, n_src=30, d_in=128, d_out=256, W=4096,
+                                                   dh_src=4096, dh_src_stride=512, ws=4096, ws_bytes=1 << 30), **k})
+    assert code(bw, n_src=5) == B.FG_ERR_SHAPE              # the layer below is smaller
+    assert code(bw, max_rows=11) == B.FG_ERR_SHAPE
+    assert code(bw, d_out=252) == B.FG_ERR_SHAPE
+    assert code(bw, ws_bytes=100) == B.FG_ERR_SHAPE
+    assert code(bw, dh_src=None) == B.FG_ERR_INVALID_ARG
+    assert code(bw, dh_src_stride=500) == B.FG_ERR_SHAPE
+    assert B.fg_layer_backward_workspace_bytes(10, 10, 128, 256) >= 10 * (256 * 4 + 2 * 128 * 4) + 2 * 128 * 256 * 4
+    assert B.fg_layer_backward_workspace_bytes(-1, 10, 128, 256) == 0
     assert code(B.fg_set_tuning, "gather_unroll", -3) == B.FG_ERR_INVALID_ARG
     assert B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, 1000) >= 1000 * 5
     assert B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, 1000) >= 1000 * 9

@@ -417,15 +417,104 @@ def test_update_all_and_fetch_all_with_unequal_and_empty_layers(env):
         B.fg_cache_destroy(cache)
 
 
+# ------------------------------------------------------------------------------------------------ backward pass
+
+@pytest.mark.parametrize("n,d", [(1024, 256), (37, 64), (5, 47), (1, 8)])
+def test_loss_gradient_and_row_norms_match_oracle(env, n, d):
+    torch, B = env
+    r = np.random.default_rng(n + d)
+    h = (r.standard_normal((n, d)) * 4).astype(np.float32)
+    y = r.integers(0, d, size=n).astype(np.int32)
+    th, ty = dev(torch, h), dev(torch, y)
+    out = torch.zeros((n, d + 4), dtype=torch.float32, device="cuda")        # strided output
+    B.fg_softmax_xent_grad(th, d * 4, ty, n, d, out, (d + 4) * 4)
+    got = out[:, :d].cpu().numpy()
+    assert T.rel_err_rows(got, O.softmax_xent_grad(h, y)) <= REL_TOL_F32
+    assert not out[:, d:].any().item()
+    norms = torch.zeros(n, dtype=torch.float32, device="cuda")
+    B.fg_row_norms(out, (d + 4) * 4, n, d, norms)
+    np.testing.assert_allclose(norms.cpu().numpy(), O.row_norms(got).astype(np.float32), rtol=5e-7)
+
+
+@pytest.mark.parametrize("d_in,d_out,n,n_src,max_deg,relu,seed", [(128, 256, 900, 4000, 9, True, 0), (256, 256, 1500, 1500, 6, True, 1),
+                                                                 (64, 64, 300, 700, 5, False, 2), (24, 72, 130, 400, 4, True, 3),
+                                                                 (8, 8, 3, 3, 2, True, 4), (256, 256, 1, 40, 30, False, 5)])
+def test_layer_backward_matches_oracle(env, d_in, d_out, n, n_src, max_deg, relu, seed):
+    """A random block, a random subset of computed rows (the others pruned: end = start), random upstream gradient."""
+    torch, B = env
+    from fg_inputs.sampler import transpose_block
+    r = np.random.default_rng(seed)
+    deg = r.integers(0, max_deg + 1, size=n)
+    start = np.concatenate([[0], np.cumsum(deg)[:-1]]).astype(np.int32)
+    end = (start + deg).astype(np.int32)
+    col = np.concatenate([r.choice(n_src, size=k, replace=False) for k in deg] + [np.zeros(0, np.int64)]).astype(np.int32)
+    ts, te, tr = transpose_block(start, end, col, n_src)
+    live = r.random(n) < 0.9
+    hit = live & (r.random(n) < 0.3)
+    normal = live & ~hit
+    rows = np.flatnonzero(normal).astype(np.int32)
+    end_pruned = np.where(normal, end, start).astype(np.int32)
+    dh = r.standard_normal((n, d_out)).astype(np.float32)
+    h = np.maximum(r.standard_normal((n, d_out)), 0).astype(np.float32)
+    W = (r.standard_normal((2 * d_in, d_out)) / np.sqrt(2 * d_in)).astype(np.float32)
+    dummy = np.zeros((len(rows), d_in))
+    want, _, _ = O.layer_backward(start, end_pruned, col, rows, dh, h, dummy, dummy, W, n_src, relu=relu)
+    t = lambda a: dev(torch, a) if len(a) else torch.zeros(1, dtype=torch.from_numpy(np.zeros(1, a.dtype)).dtype, device="cuda")
+    cnt = dev(torch, np.asarray([len(rows)], dtype=np.int64))
+    out = torch.full((n_src, d_in), 7.0, dtype=torch.float32, device="cuda")
+    wsb = B.fg_layer_backward_workspace_bytes(n, n, d_in, d_out)
+    ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+    rows_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
+    rows_dev[:len(rows)] = dev(torch, rows) if len(rows) else rows_dev[:0]
+    B.fg_layer_backward(dev(torch, dh), d_out * 4, dev(torch, h) if relu else None, d_out * 4, n, rows_dev, cnt, n,
+                        dev(torch, live.astype(np.uint8)), dev(torch, hit.astype(np.uint8)), dev(torch, start), dev(torch, end_pruned),
+                        dev(torch, ts), dev(torch, te), t(tr), len(tr), n_src, d_in, d_out, dev(torch, W), out, d_in * 4, ws, wsb)
+    got = out.cpu().numpy()
+    e = T.rel_err_rows(got, want)
+    assert e <= REL_TOL_F32, f"rel err {e:.3e}"
+    assert (np.abs(want).sum(axis=1) == 0).sum() == (np.abs(got).sum(axis=1) == 0).sum()
+
+
+def test_iterations_tiny_with_backward_pass(env):
+    """Whole iterations whose gradient norms come from the backward pass (loss, layer backward, row norms)."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    hits, worst = run_workload_parity(torch, w, 12, backward=True)
+    assert hits > 50
+    hits, worst = run_workload_parity(torch, w, 6, backward=True, fused=True)
+    assert hits > 0
+
+
+def test_iterations_three_layers_with_backward_pass(env):
+    torch, B = env
+    import dataclasses
+    w = dataclasses.replace(wl.WORKLOADS["large_hbm"], name="large_hbm/small", num_nodes=200_000, num_edges=4_000_000, batch=128,
+                            train_nodes=20_000, cache_capacity=20_000, t_stale=6)
+    hits, worst = run_workload_parity(torch, w, 10, p_grad=0.7, backward=True, fused=True)
+    assert hits > 0
+
+
+def test_iterations_large_hbm_full_size_with_backward_pass(env):
+    """The benchmarked workload at full size with real gradient norms (the configuration bench.py --backward times)."""
+    torch, B = env
+    w = wl.WORKLOADS["large_hbm"]
+    hits, worst = run_workload_parity(torch, w, 4, check_numeric_every=3, sample_rows=20000, fused=True, backward=True)
+    assert hits > 0
+
+
 # ------------------------------------------------------------------------------------------------ whole iterations
 
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
-                        sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None):
+                        sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
+                        backward=False):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
     graph's n_hot hottest nodes (Section 4.2). poison: once the rows are placed, the table rows of those nodes are
     negated on both sides, so a row read from the wrong place shows.
+    backward: the gradient norms come from the backward pass of a softmax cross-entropy loss on the seeds' synthetic
+    labels. The embedding gradients and their norms are compared within tolerance; the admission decisions are then taken
+    on both sides from the device's norms (the same fp32 values), so that cache state stays comparable bit for bit.
     """
     g = wl.make_graph(w)
     frows = G.feature_accessor(w)
@@ -434,7 +523,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
     hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity,
                                              fused_input=fused, one_launch_top_down=one_launch_top_down,
                                              update_all=one_launch_top_down, hot_ids=hot,
-                                             buffer_bytes=fs["buffer_bytes"] if fs else None)
+                                             buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward)
     from paper_2301_07482_amd import binding as FGB
     bc = None
     if fs:
@@ -461,12 +550,13 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
     L = w.num_layers
     p = w.p_grad if p_grad is None else p_grad
     total_hits = 0
-    worst = worst_e2e = 0.0
+    worst = worst_e2e = worst_bw = 0.0
     try:
         for it in range(iterations):
             mb = wl.minibatch(w, g, it)
             gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
-            bt = DeviceBatch(mb, gn)                       # uploaded before the oracle prunes its copy of the blocks
+            labels = wl.node_labels(w, mb.ids[L]) if backward else None
+            bt = DeviceBatch(mb, None if backward else gn, labels=labels)   # uploaded before the oracle prunes its copy of the blocks
             if bc is not None:
                 # what the loader is about to find on the feature side, for every node of the input layer (or a sample)
                 n0 = len(mb.ids[0])
@@ -476,12 +566,41 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                 assert np.array_equal(ranks[pick], np.asarray([bc.feature_rank(int(v)) for v in mb.ids[0][pick]], dtype=np.int32)), \
                     f"feature-side ranks, iteration {it}"
                 assert found == int((ranks >= 0).sum())
-            rec = O.iteration(mb, it, caches, frows, weights, gn, p, dims, w.feat_dtype, w.compute_dtype, feature_side=bc)
+            rec = O.iteration(mb, it, caches, frows, weights, gn, p, dims, w.feat_dtype, w.compute_dtype, feature_side=bc,
+                              labels=labels, update=not backward)
             served += int(rec["feature_from_buffer"].sum())
             # device cache rows at the slots about to be hit, read before this iteration's update recycles slots
             pre_rows = {l: hp.cache_rows(l, rec["look"][l]["hit_slot"]) for l in range(1, L) if len(rec["look"][l]["hit_pos"])}
             hp.run(bt, it)
             snap = hp.snapshot(bt)
+            if backward:
+                # (a) every call against the oracle on the SAME inputs (the device's own H and dH of the layer above), so
+                #     that a ReLU output that is +0 on one side and a rounding error above it on the other cannot matter
+                bw = rec["backward"]
+                nl = [len(x) for x in mb.ids]
+                dHd = {l: hp.dH[l][:nl[l]].cpu().numpy() for l in range(1, L + 1)}
+                Hd = {l: G.to_f32(hp.H[l][:nl[l]]) for l in range(1, L + 1)}
+                e = T.rel_err_rows(dHd[L], O.softmax_xent_grad(Hd[L], labels))
+                assert e <= REL_TOL_F32, f"loss gradient, iteration {it}: rel err {e:.3e}"
+                for l in range(L, 1, -1):
+                    rows = rec["look"][l]["normal_pos"]
+                    dummy = np.zeros((len(rows), dims[l - 1]))
+                    want, _, _ = O.layer_backward(mb.start[l], mb.end[l], mb.col[l], rows, dHd[l], Hd[l], dummy, dummy, weights[l][0],
+                                                  nl[l - 1], relu=(l < L))
+                    e = T.rel_err_rows(dHd[l - 1], want)
+                    worst_bw = max(worst_bw, e)
+                    assert e <= REL_TOL_F32, f"dH[{l - 1}] iteration {it} (same inputs): rel err {e:.3e}"
+                dev_norms = {l: hp.gnorm[l][:nl[l]].cpu().numpy() for l in range(1, L)}
+                for l in range(1, L):
+                    np.testing.assert_allclose(dev_norms[l], O.row_norms(dHd[l]).astype(np.float32), rtol=5e-7, atol=1e-37)
+                    # (b) end to end against the pure-oracle backward pass: all but a few rows within the depth-scaled bound
+                    ref = bw["dH"][l]
+                    den = np.maximum(np.abs(ref), np.abs(ref).max(axis=1, keepdims=True) / 16.0) + 1e-300
+                    bad = (np.abs(dHd[l] - ref) / den).max(axis=1) > REL_TOL_F32 * 2 * (L - l + 1)
+                    assert bad.mean() <= 0.01, f"dH[{l}] iteration {it} (end to end): {int(bad.sum())} of {len(bad)} rows off"
+                    # the update itself, from the device's norms on both sides
+                    rec["stats"][l] = O.cache_update(caches[l], it, mb.ids[l], rec["live"][l], rec["look"][l]["hit"], dev_norms[l], p,
+                                                     rec["H"][l])
             for l in range(L, 0 if fused else -1, -1):
                 s, lk = snap["layers"][l], rec["look"][l]
                 assert tuple(snap["counts"][l]) == lk["counts"], f"counts, iteration {it} layer {l}"
@@ -570,7 +689,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
             print(f"{w.name}: feature side served {served} input rows, {lost} of {len(hot)} rows displaced")
     finally:
         hp.close()
-    print(f"{w.name}: worst rel err same-inputs {worst:.3e}, end-to-end {worst_e2e:.3e}")
+    print(f"{w.name}: worst rel err same-inputs {worst:.3e}, end-to-end {worst_e2e:.3e}" + (f", embedding gradients {worst_bw:.3e}" if backward else ""))
     if fs:
         return total_hits, worst, served
     return total_hits, worst

@@ -62,3 +62,16 @@ def test_grad_norms_and_weights():
     assert np.array_equal(gn[:5], wl.grad_norms(w, 2, 1, np.arange(5)))
     W, b = wl.layer_weights(w, 1)
     assert W.shape == (128, 64) and b.shape == (64,) and abs(W.std() - 1 / np.sqrt(128)) < 0.01
+
+
+def test_transposed_block_lists_the_rows_that_sampled_each_position():
+    from fg_inputs.sampler import transpose_block
+    from tests import helpers as T
+    g = T.random_explicit_graph(50, 5, 0)
+    mb = T.sample(g, np.arange(8), [3, 3], 0)
+    for l in (1, 2):
+        ts, te, tr = transpose_block(mb.start[l], mb.end[l], mb.col[l], len(mb.ids[l - 1]))
+        for j in range(len(mb.ids[l - 1])):
+            want = [r for r in range(len(mb.ids[l])) if j in mb.col[l][mb.start[l][r]:mb.end[l][r]]]
+            assert tr[ts[j]:te[j]].tolist() == want
+        assert te[-1] == len(tr) == int((mb.end[l] - mb.start[l]).sum())
