@@ -29,7 +29,7 @@ def _sample_one(args):
     g = wl.make_graph(w)
     mb = wl.minibatch(w, g, it)
     gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, w.num_layers)}
-    return mb, gn
+    return mb, gn, wl.node_labels(w, mb.ids[w.num_layers])
 
 
 def sample_batches(name, count, workers):
@@ -66,6 +66,9 @@ def main():
     ap.add_argument("--feature-rows", type=int, default=0,
                     help="bidirectional cache: place the raw features of this many hottest nodes on the feature side of the "
                          "caches' buffer (beyond the rings, so none is displaced) and load through it")
+    ap.add_argument("--backward", action="store_true",
+                    help="take the gradient norms of the cache update from the backward pass (softmax cross-entropy on the seeds' "
+                         "synthetic labels, layer backward down to layer 1, row norms) instead of the synthetic norms")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy before the warm-up, as the known-size "
                          "reference for scaling hardware traffic counters")
@@ -103,7 +106,9 @@ def main():
         row = w.feat_dim * (4 if w.feat_dtype == "f32" else 2)
         buffer_bytes = -(-(G.rings_bytes(w) + len(hot) * row) // 256) * 256
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + extra + 32,
-                                       hot_ids=hot, buffer_bytes=buffer_bytes)
+                                       hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward)
+    make_batch = (lambda mb, gn, labels: DeviceBatch(mb, None, labels=labels)) if args.backward else \
+        (lambda mb, gn, labels: DeviceBatch(mb, gn))
     if args.per_layer_update:
         hp.update_all = False
     if args.tune:
@@ -111,7 +116,7 @@ def main():
         for kv in args.tune:
             key, value = kv.split("=")
             B.fg_set_tuning(key, int(value))
-    batches = [DeviceBatch(mb, gn) for mb, gn in sampled[:total]]
+    batches = [make_batch(*s) for s in sampled[:total]]
     torch.cuda.synchronize()
     t_setup = time.time() - t0
     L = hp.L
@@ -177,7 +182,7 @@ def main():
     # events around every call. It is a profile, not a result.
     ev2 = []
     replay_from_buffer = []
-    replay = [DeviceBatch(*sampled[total + k]) for k in range(extra)]
+    replay = [make_batch(*sampled[total + k]) for k in range(extra)]
     for k in range(extra):
         step_events = {}
         hp.run(replay[k], args.warmup + args.steps + k, timer=timer_for(step_events))
@@ -305,7 +310,7 @@ def main():
                 total += 2 * n_l * 6 + float(st[l][0]) * (2 * row + 12) + float(st[l][1]) * 4  # update
         return total
     path_bytes = gather_bytes + float(np.mean([layer_bytes(it, c, st) for it, c, st in zip(roof_it, counts, stats)]))
-    path_ms = sum(v for k, v in call_avg_ms.items() if not k.startswith("linear"))
+    path_ms = sum(v for k, v in call_avg_ms.items() if not k.startswith(("linear", "loss_grad", "layer_backward", "row_norms")))
     hbm_path = dict(bytes_per_step=path_bytes, ms_per_step=path_ms, achieved=path_bytes / (path_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=path_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     note="all calls except fg_linear; times from the breakdown pass (every call bracketed)")
@@ -329,7 +334,8 @@ def main():
                    "feat_dtype": w.feat_dtype, "features": w.feat_location, "layers": L, "hidden": w.hidden,
                    "fanouts": list(w.fanouts), "batch": w.batch, "cache_slots_per_layer": w.cache_capacity,
                    "t_stale": w.t_stale, "p_grad": w.p_grad, "cache": not args.no_cache,
-                   "fused_loader": not args.no_fuse, "feature_rows": int(args.feature_rows), "seed": w.seed},
+                   "fused_loader": not args.no_fuse, "feature_rows": int(args.feature_rows),
+                   "gradient_norms": "backward pass" if args.backward else "synthetic input", "seed": w.seed},
         "roofline": roofline,
         "roofline_2": roofline_2,
         "cpu_baseline": cpu_baseline,
@@ -379,7 +385,7 @@ def time_oracle(w, sampled, weights, iterations=10):
     secs = 0.0
     done = 0
     for it in range(min(iterations, len(sampled))):
-        mb, gn = sampled[it]
+        mb, gn = sampled[it][:2]
         mb = mb.copy()
         rows = features.feature_rows(w.seed, mb.ids[0], w.feat_dim, dt)      # not timed: input generation
         order = np.argsort(mb.ids[0], kind="stable")

@@ -408,6 +408,7 @@ fg_status_t fg_row_norms(const float* x_dev, int64_t x_stride, int32_t n, int32_
  *                                        t_row[t_start[j] .. t_end[j]) (of the block before pruning; pruned rows are skipped by deg 0)
  *   W, d_in, d_out                       the layer's weights; d_in a multiple of 4, d_out of 8
  *   dh_src_dev, dh_src_stride            out: dL/dH(l-1) by position [n_src x d_in], 16-byte aligned
+ *   norms_src_dev                        out, float[n_src] or NULL: the L2 norm of every row of dh_src (what fg_row_norms would give)
  *   ws_dev, ws_bytes                     device workspace >= fg_layer_backward_workspace_bytes(n, max_rows, d_in, d_out), 16-byte aligned
  * No atomics: every output row has one writer, so results do not depend on scheduling.
  */
@@ -417,7 +418,7 @@ fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride, const floa
                               const uint8_t* hit_dev, const int32_t* row_start_dev, const int32_t* row_end_dev,
                               const int32_t* t_start_dev, const int32_t* t_end_dev, const int32_t* t_row_dev, int64_t nnz,
                               int32_t n_src, int32_t d_in, int32_t d_out, const float* W, float* dh_src_dev,
-                              int64_t dh_src_stride, void* ws_dev, size_t ws_bytes, void* stream);
+                              int64_t dh_src_stride, float* norms_src_dev, void* ws_dev, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -54,7 +54,7 @@ SIGNATURES = {
     "fg_row_norms": (_i32, [_p, _i64, _i32, _i32, _p, _p]),
     "fg_layer_backward_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32]),
     "fg_layer_backward": (_i32, [_p, _i64, _p, _i64, _i32, _p, _p, _i64, _p, _p, _p, _p, _p, _p, _p, _i64, _i32, _i32, _i32, _p, _p,
-                                 _i64, _p, _sz, _p]),
+                                 _i64, _p, _p, _sz, _p]),
 }
 
 
@@ -271,10 +271,10 @@ def fg_layer_backward_workspace_bytes(n, max_rows, d_in, d_out):
 
 
 def fg_layer_backward(dh, dh_stride, h, h_stride, n, rows, n_rows, max_rows, live, hit, row_start, row_end, t_start, t_end, t_row,
-                      nnz, n_src, d_in, d_out, W, dh_src, dh_src_stride, ws, ws_bytes, stream=None):
+                      nnz, n_src, d_in, d_out, W, dh_src, dh_src_stride, norms_src, ws, ws_bytes, stream=None):
     _check(_lib.fg_layer_backward(ptr(dh), dh_stride, ptr(h), h_stride, n, ptr(rows), ptr(n_rows), max_rows, ptr(live), ptr(hit),
                                   ptr(row_start), ptr(row_end), ptr(t_start), ptr(t_end), ptr(t_row), nnz, n_src, d_in, d_out,
-                                  ptr(W), ptr(dh_src), dh_src_stride, ptr(ws), ws_bytes, stream))
+                                  ptr(W), ptr(dh_src), dh_src_stride, ptr(norms_src), ptr(ws), ws_bytes, stream))
 
 
 def _struct_array(struct, specs):

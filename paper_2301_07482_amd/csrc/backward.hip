@@ -124,7 +124,7 @@ __global__ __launch_bounds__(BW_THREADS) void aggregate_backward_kernel(
     const char* __restrict__ dx, int n, int d_in, const uint8_t* __restrict__ live, const uint8_t* __restrict__ hit,
     const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ t_start,
     const int32_t* __restrict__ t_end, const int32_t* __restrict__ t_row, int64_t nnz, int n_src, char* __restrict__ out,
-    int64_t out_stride, int lanes_log2) {
+    int64_t out_stride, int lanes_log2, float* __restrict__ norms) {
     const int lanes = 1 << lanes_log2;
     const int lane = threadIdx.x & (lanes - 1);
     const int gpb = BW_THREADS >> lanes_log2;
@@ -134,6 +134,7 @@ __global__ __launch_bounds__(BW_THREADS) void aggregate_backward_kernel(
         int32_t s0 = t_start[j], e0 = t_end[j];
         if (s0 < 0 || e0 < s0 || (int64_t)e0 > nnz) s0 = e0 = 0;
         const bool own = j < n && (live ? live[j] != 0 : true) && (hit ? hit[j] == 0 : true);
+        double ss = 0.0;  // this lane's share of the row's sum of squares (of the fp32 values written)
         for (int piece = lane; piece < pieces; piece += lanes) {
             double acc[4] = {0.0, 0.0, 0.0, 0.0};
             if (own) {
@@ -168,6 +169,11 @@ __global__ __launch_bounds__(BW_THREADS) void aggregate_backward_kernel(
             }
             const f32x4 o = {(float)acc[0], (float)acc[1], (float)acc[2], (float)acc[3]};
             *(f32x4*)(out + j * out_stride + (int64_t)piece * 16) = o;
+            ss += (double)o.x * o.x + (double)o.y * o.y + (double)o.z * o.z + (double)o.w * o.w;
+        }
+        if (norms) {  // the lanes of a group are neighbours in one wavefront and leave the loop together
+            for (int off = lanes >> 1; off > 0; off >>= 1) ss += __shfl_xor(ss, off, 64);
+            if (lane == 0) norms[j] = (float)sqrt(ss);
         }
     }
 }
@@ -230,8 +236,8 @@ extern "C" fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride,
                                          const uint8_t* live_dev, const uint8_t* hit_dev, const int32_t* row_start_dev,
                                          const int32_t* row_end_dev, const int32_t* t_start_dev, const int32_t* t_end_dev,
                                          const int32_t* t_row_dev, int64_t nnz, int32_t n_src, int32_t d_in, int32_t d_out,
-                                         const float* W, float* dh_src_dev, int64_t dh_src_stride, void* ws_dev, size_t ws_bytes,
-                                         void* stream) {
+                                         const float* W, float* dh_src_dev, int64_t dh_src_stride, float* norms_src_dev,
+                                         void* ws_dev, size_t ws_bytes, void* stream) {
     const char* who = "fg_layer_backward";
     if (n < 0 || max_rows < 0 || n_src < 0 || nnz < 0 || d_in <= 0 || d_out <= 0)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (n %d, max_rows %lld, n_src %d, nnz %lld, d_in %d, d_out %d)", who, n, (long long)max_rows,
@@ -245,6 +251,7 @@ extern "C" fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride,
         FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
     if (((uintptr_t)dh_dev | (uintptr_t)h_dev | (uintptr_t)dh_stride | (uintptr_t)h_stride | (uintptr_t)W) & 3)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: dh, h, W and their strides must be 4-byte aligned", who);
+    if ((uintptr_t)norms_src_dev & 3) FG_FAIL(FG_ERR_INVALID_ARG, "%s: norms_src_dev must be 4-byte aligned", who);
     if (((uintptr_t)dh_src_dev | (uintptr_t)dh_src_stride | (uintptr_t)ws_dev) & 15)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: dh_src_dev, its stride and the workspace must be 16-byte aligned", who);
     const BwWs L = bw_layout(n, max_rows, d_in, d_out);
@@ -279,7 +286,8 @@ extern "C" fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride,
     int64_t blocks = fg_ceil_div(n_src, gpb);
     if (blocks > 256 * 16) blocks = 256 * 16;
     hipLaunchKernelGGL(aggregate_backward_kernel, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dx, n, d_in, live_dev,
-                       hit_dev, row_start_dev, row_end_dev, t_start_dev, t_end_dev, t_row_dev, nnz, n_src, (char*)dh_src_dev, dh_src_stride, lg);
+                       hit_dev, row_start_dev, row_end_dev, t_start_dev, t_end_dev, t_row_dev, nnz, n_src, (char*)dh_src_dev, dh_src_stride, lg,
+                       norms_src_dev);
     FG_LAUNCH_CHECK("aggregate_backward_kernel");
     return FG_OK;
 }

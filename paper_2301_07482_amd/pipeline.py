@@ -251,9 +251,7 @@ class HotPath:
                                     self.normal_pos[l], self._cnt(l, 2), bt.n[l], self.live[l] if l < L else None, self.hit[l],
                                     bt.start[l], bt.end[l], bt.t_start[l], bt.t_end[l], bt.t_row[l], bt.nnz[l], bt.n[l - 1],
                                     self.dims[l - 1], self.dims[l], self.W[l], self.dH[l - 1], self.dims[l - 1] * 4,
-                                    self.ws_bw, self.ws_bw_bytes, st)
-                tick(f"row_norms[{l - 1}]")
-                B.fg_row_norms(self.dH[l - 1], self.dims[l - 1] * 4, bt.n[l - 1], self.dims[l - 1], self.gnorm[l - 1], st)
+                                    self.gnorm[l - 1], self.ws_bw, self.ws_bw_bytes, st)   # with the row norms of dH[l-1]
             gnorm = self.gnorm
         # ---- update of the caches
         if do_update and self.update_all:

@@ -91,7 +91,7 @@ def test_argument_validation_needs_no_gpu(B):
     bw = lambda **k: B.fg_layer_backward(**{**dict(dh=4096, dh_stride=1024, h=4096, h_stride=1024, n=10, rows=4096, n_rows=None,
                                                    max_rows=10, live=None, hit=None, row_start=4096, row_end=4096, t_start=4096,
                                                    t_end=4096, t_row=4096, nnz=50, n_src=30, d_in=128, d_out=256, W=4096,
-                                                   dh_src=4096, dh_src_stride=512, ws=4096, ws_bytes=1 << 30), **k})
+                                                   dh_src=4096, dh_src_stride=512, norms_src=None, ws=4096, ws_bytes=1 << 30), **k})
     assert code(bw, n_src=5) == B.FG_ERR_SHAPE              # the layer below is smaller
     assert code(bw, max_rows=11) == B.FG_ERR_SHAPE
     assert code(bw, d_out=252) == B.FG_ERR_SHAPE

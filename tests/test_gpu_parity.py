@@ -464,12 +464,14 @@ def test_layer_backward_matches_oracle(env, d_in, d_out, n, n_src, max_deg, relu
     out = torch.full((n_src, d_in), 7.0, dtype=torch.float32, device="cuda")
     wsb = B.fg_layer_backward_workspace_bytes(n, n, d_in, d_out)
     ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+    norms = torch.full((n_src,), -1.0, dtype=torch.float32, device="cuda")
     rows_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
     rows_dev[:len(rows)] = dev(torch, rows) if len(rows) else rows_dev[:0]
     B.fg_layer_backward(dev(torch, dh), d_out * 4, dev(torch, h) if relu else None, d_out * 4, n, rows_dev, cnt, n,
                         dev(torch, live.astype(np.uint8)), dev(torch, hit.astype(np.uint8)), dev(torch, start), dev(torch, end_pruned),
-                        dev(torch, ts), dev(torch, te), t(tr), len(tr), n_src, d_in, d_out, dev(torch, W), out, d_in * 4, ws, wsb)
+                        dev(torch, ts), dev(torch, te), t(tr), len(tr), n_src, d_in, d_out, dev(torch, W), out, d_in * 4, norms, ws, wsb)
     got = out.cpu().numpy()
+    np.testing.assert_allclose(norms.cpu().numpy(), O.row_norms(got).astype(np.float32), rtol=5e-7, atol=1e-37)
     e = T.rel_err_rows(got, want)
     assert e <= REL_TOL_F32, f"rel err {e:.3e}"
     assert (np.abs(want).sum(axis=1) == 0).sum() == (np.abs(got).sum(axis=1) == 0).sum()
