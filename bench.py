@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="take the gradient norms of the cache update from the backward pass (softmax cross-entropy on the seeds' "
                          "synthetic labels, layer backward down to layer 1, row norms) instead of the synthetic norms")
+    ap.add_argument("--weight-grads", action="store_true",
+                    help="with --backward: also form dL/dW and dL/db of every layer (fg_layer_backward_weights)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy before the warm-up, as the known-size "
                          "reference for scaling hardware traffic counters")
@@ -106,7 +108,7 @@ def main():
         row = w.feat_dim * (4 if w.feat_dtype == "f32" else 2)
         buffer_bytes = -(-(G.rings_bytes(w) + len(hot) * row) // 256) * 256
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + extra + 32,
-                                       hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward)
+                                       hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads)
     make_batch = (lambda mb, gn, labels: DeviceBatch(mb, None, labels=labels)) if args.backward else \
         (lambda mb, gn, labels: DeviceBatch(mb, gn))
     if args.per_layer_update:
@@ -310,7 +312,7 @@ def main():
                 total += 2 * n_l * 6 + float(st[l][0]) * (2 * row + 12) + float(st[l][1]) * 4  # update
         return total
     path_bytes = gather_bytes + float(np.mean([layer_bytes(it, c, st) for it, c, st in zip(roof_it, counts, stats)]))
-    path_ms = sum(v for k, v in call_avg_ms.items() if not k.startswith(("linear", "loss_grad", "layer_backward", "row_norms")))
+    path_ms = sum(v for k, v in call_avg_ms.items() if not k.startswith(("linear", "loss_grad", "layer_backward", "row_norms", "weight_grads")))
     hbm_path = dict(bytes_per_step=path_bytes, ms_per_step=path_ms, achieved=path_bytes / (path_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=path_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     note="all calls except fg_linear; times from the breakdown pass (every call bracketed)")
@@ -335,7 +337,8 @@ def main():
                    "fanouts": list(w.fanouts), "batch": w.batch, "cache_slots_per_layer": w.cache_capacity,
                    "t_stale": w.t_stale, "p_grad": w.p_grad, "cache": not args.no_cache,
                    "fused_loader": not args.no_fuse, "feature_rows": int(args.feature_rows),
-                   "gradient_norms": "backward pass" if args.backward else "synthetic input", "seed": w.seed},
+                   "gradient_norms": "backward pass" if args.backward else "synthetic input",
+                   "weight_gradients": bool(args.weight_grads and args.backward), "seed": w.seed},
         "roofline": roofline,
         "roofline_2": roofline_2,
         "cpu_baseline": cpu_baseline,

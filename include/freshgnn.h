@@ -420,6 +420,22 @@ fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride, const floa
                               int32_t n_src, int32_t d_in, int32_t d_out, const float* W, float* dh_src_dev,
                               int64_t dh_src_stride, float* norms_src_dev, void* ws_dev, size_t ws_bytes, void* stream);
 
+/*
+ * Gradient with respect to the weights of one GraphSAGE-mean layer, over the computed rows (dz as in fg_layer_backward):
+ *   dw[a, c] = sum_k x[k, a] * dz[k, c],  x[k, :] = [h_src[rows[k], :] ‖ agg[k, :]]   ([2*d_in x d_out], the layout of W)
+ *   db[c]    = sum_k dz[k, c]                                                          (db_dev may be NULL)
+ * h_src, agg, rows as given to fg_linear for this layer in the forward pass; dh, h (NULL = no activation) by position,
+ * n rows. Products on the fp32 matrix cores, fp32 sums within a slice of the rows, fp64 across slices; the slicing
+ * depends only on max_rows, so results do not depend on scheduling.
+ *   ws_dev, ws_bytes    device workspace >= fg_layer_backward_weights_workspace_bytes(max_rows, d_in, d_out), 16-byte aligned
+ */
+size_t fg_layer_backward_weights_workspace_bytes(int64_t max_rows, int32_t d_in, int32_t d_out);
+fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t n_src, int64_t src_stride, const float* agg_dev,
+                                      int64_t agg_stride, const float* dh_dev, int64_t dh_stride, const float* h_dev,
+                                      int64_t h_stride, int32_t n, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                      int64_t max_rows, int32_t d_in, int32_t d_out, float* dw_dev, float* db_dev,
+                                      void* ws_dev, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -53,6 +53,8 @@ SIGNATURES = {
     "fg_softmax_xent_grad": (_i32, [_p, _i64, _p, _i32, _i32, _p, _i64, _p]),
     "fg_row_norms": (_i32, [_p, _i64, _i32, _i32, _p, _p]),
     "fg_layer_backward_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32]),
+    "fg_layer_backward_weights_workspace_bytes": (_sz, [_i64, _i32, _i32]),
+    "fg_layer_backward_weights": (_i32, [_p, _i32, _i64, _p, _i64, _p, _i64, _p, _i64, _i32, _p, _p, _i64, _i32, _i32, _p, _p, _p, _sz, _p]),
     "fg_layer_backward": (_i32, [_p, _i64, _p, _i64, _i32, _p, _p, _i64, _p, _p, _p, _p, _p, _p, _p, _i64, _i32, _i32, _i32, _p, _p,
                                  _i64, _p, _p, _sz, _p]),
 }
@@ -275,6 +277,16 @@ def fg_layer_backward(dh, dh_stride, h, h_stride, n, rows, n_rows, max_rows, liv
     _check(_lib.fg_layer_backward(ptr(dh), dh_stride, ptr(h), h_stride, n, ptr(rows), ptr(n_rows), max_rows, ptr(live), ptr(hit),
                                   ptr(row_start), ptr(row_end), ptr(t_start), ptr(t_end), ptr(t_row), nnz, n_src, d_in, d_out,
                                   ptr(W), ptr(dh_src), dh_src_stride, ptr(norms_src), ptr(ws), ws_bytes, stream))
+
+
+def fg_layer_backward_weights_workspace_bytes(max_rows, d_in, d_out):
+    return _lib.fg_layer_backward_weights_workspace_bytes(max_rows, d_in, d_out)
+
+
+def fg_layer_backward_weights(h_src, n_src, src_stride, agg, agg_stride, dh, dh_stride, h, h_stride, n, rows, n_rows, max_rows, d_in,
+                              d_out, dw, db, ws, ws_bytes, stream=None):
+    _check(_lib.fg_layer_backward_weights(ptr(h_src), n_src, src_stride, ptr(agg), agg_stride, ptr(dh), dh_stride, ptr(h), h_stride, n,
+                                          ptr(rows), ptr(n_rows), max_rows, d_in, d_out, ptr(dw), ptr(db), ptr(ws), ws_bytes, stream))
 
 
 def _struct_array(struct, specs):

@@ -291,3 +291,211 @@ extern "C" fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride,
     FG_LAUNCH_CHECK("aggregate_backward_kernel");
     return FG_OK;
 }
+
+// ---- weight gradients --------------------------------------------------------------------------------------
+//
+// dW = X^T . dz and db = column sums of dz over the computed rows, X[k, :] = [h_src[rows[k], :] ‖ agg[k, :]],
+// dz[k, :] = dh[rows[k], :] * (h[rows[k], :] > 0). A contraction over the rows (K = tens of thousands) with a small
+// result (2*d_in x d_out), so K is split over the workgroups: workgroup `chunk` multiplies its rows on the fp32
+// matrix cores and leaves a partial result, a second launch adds the partials up in fp64.
+// Both operands are read straight from global memory in the layout v_mfma_f32_32x32x2_f32 wants: for the two rows
+// k, k+1 a lane holds X[k + lane/32][m0 + lane%32] and dz[k + lane/32][n0 + lane%32], 128 contiguous bytes per row.
+// A workgroup of 8 wavefronts (4 along M x 2 along N) owns a 256 x 256 tile of the result, a wavefront 64 x 128 of it
+// (2 x 4 blocks of 32 x 32: 6 operand loads for 8 matrix instructions per pair of rows).
+namespace {
+
+constexpr int WG_THREADS = 512;
+constexpr int WG_TILE = 256;
+constexpr int WG_PAIRS = 4;  // pairs of rows whose loads are issued together
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+__global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
+    const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
+    const char* __restrict__ dh, int64_t dh_stride, const char* __restrict__ h, int64_t h_stride, int n,
+    const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
+    int rows_per_chunk, float* __restrict__ part_w, float* __restrict__ part_b) {
+    int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
+    if (n_rows > max_rows) n_rows = max_rows;
+    const int M = 2 * d_in, N = d_out;
+    const int chunk = blockIdx.x;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l32 = lane & 31, kh = lane >> 5;
+    const int wm = wave & 3, wn = wave >> 2;
+    const int m_base = blockIdx.y * WG_TILE + wm * 64;
+    const int n_base = blockIdx.z * WG_TILE + wn * 128;
+    const int64_t k_begin = (int64_t)chunk * rows_per_chunk;
+    int64_t k_end = k_begin + rows_per_chunk;
+    if (k_end > n_rows) k_end = n_rows;
+
+    // this lane's columns: where they are read from and whether they exist
+    int a_col[2];
+    bool a_self[2], a_ok[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int m = m_base + 32 * i + l32;
+        a_ok[i] = m < M;
+        a_self[i] = m < d_in;
+        a_col[i] = a_ok[i] ? (a_self[i] ? m : m - d_in) : 0;
+    }
+    int b_col[4];
+    bool b_ok[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int c = n_base + 32 * j + l32;
+        b_ok[j] = c < N;
+        b_col[j] = b_ok[j] ? c : 0;
+    }
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+    float colsum[4] = {0.f, 0.f, 0.f, 0.f};
+
+    for (int64_t k0 = k_begin; k0 < k_end; k0 += 2 * WG_PAIRS) {
+        float a[WG_PAIRS][2], g[WG_PAIRS][4], o[WG_PAIRS][4];
+        bool ok[WG_PAIRS];
+        // all loads of the batch first (from a safe row where this lane has none), masks afterwards
+#pragma unroll
+        for (int p = 0; p < WG_PAIRS; ++p) {
+            const int64_t kk = k0 + 2 * p + kh;
+            const bool in = kk < k_end;
+            const int64_t ks = in ? kk : k_begin;  // k_begin < k_end here, so row k_begin exists
+            const int32_t r = rows ? rows[ks] : (int32_t)ks;
+            ok[p] = in && r >= 0 && r < n && r < n_src;
+            const int64_t rs = ok[p] ? r : 0;
+            const float* xs = (const float*)(h_src + rs * src_stride);
+            const float* xa = (const float*)(agg + ks * agg_stride);
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[p][i] = a_self[i] ? xs[a_col[i]] : xa[a_col[i]];
+            const float* gr = (const float*)(dh + rs * dh_stride);
+            const float* hr = h ? (const float*)(h + rs * h_stride) : gr;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                g[p][j] = gr[b_col[j]];
+                o[p][j] = hr[b_col[j]];
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < WG_PAIRS; ++p) {
+#pragma unroll
+            for (int i = 0; i < 2; ++i) a[p][i] = (ok[p] && a_ok[i]) ? a[p][i] : 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const bool pass = ok[p] && b_ok[j] && (h ? o[p][j] > 0.f : true);
+                g[p][j] = pass ? g[p][j] : 0.f;
+                colsum[j] += g[p][j];
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < WG_PAIRS; ++p)
+#pragma unroll
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[p][i], g[p][j], acc[i][j], 0, 0, 0);
+    }
+    // partial result of this chunk (zeros if the chunk lies beyond the rows there are)
+    float* pw = part_w + (int64_t)chunk * M * N;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int c = n_base + 32 * j + l32;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int m = m_base + 32 * i + 8 * (e >> 2) + 4 * kh + (e & 3);  // accumulator element e of this lane
+                if (m < M && c < N) pw[(int64_t)m * N + c] = acc[i][j][e];
+            }
+        }
+    if (blockIdx.y == 0 && wm == 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float s = colsum[j] + __shfl_xor(colsum[j], 32, 64);
+            const int c = n_base + 32 * j + l32;
+            if (kh == 0 && c < N) part_b[(int64_t)chunk * N + c] = s;
+        }
+    }
+}
+
+__global__ __launch_bounds__(BW_THREADS) void weight_grad_reduce_kernel(const float* __restrict__ part_w,
+                                                                        const float* __restrict__ part_b, int n_chunks,
+                                                                        int64_t mn, int n_cols, float* __restrict__ dw,
+                                                                        float* __restrict__ db) {
+    const int64_t i = (int64_t)blockIdx.x * BW_THREADS + threadIdx.x;
+    if (i < mn) {
+        double s = 0.0;
+        for (int c = 0; c < n_chunks; ++c) s += (double)part_w[(int64_t)c * mn + i];
+        dw[i] = (float)s;
+    } else if (db && i - mn < n_cols) {
+        const int64_t j = i - mn;
+        double s = 0.0;
+        for (int c = 0; c < n_chunks; ++c) s += (double)part_b[(int64_t)c * n_cols + j];
+        db[j] = (float)s;
+    }
+}
+
+struct WgPlan {
+    int n_chunks, rows_per_chunk, tiles_m, tiles_n;
+    size_t part_b, total;
+};
+WgPlan wg_plan(int64_t max_rows, int64_t d_in, int64_t d_out) {
+    WgPlan p;
+    p.tiles_m = (int)fg_ceil_div(2 * d_in, WG_TILE);
+    p.tiles_n = (int)fg_ceil_div(d_out, WG_TILE);
+    int64_t chunks = 256 / (p.tiles_m * p.tiles_n);  // one workgroup per compute unit
+    if (chunks < 1) chunks = 1;
+    const int64_t by_rows = fg_ceil_div(max_rows > 0 ? max_rows : 1, 64);
+    if (chunks > by_rows) chunks = by_rows;
+    int64_t per = fg_ceil_div(max_rows > 0 ? max_rows : 1, chunks);
+    per = fg_ceil_div(per, 2 * WG_PAIRS) * 2 * WG_PAIRS;
+    p.rows_per_chunk = (int)per;
+    p.n_chunks = (int)fg_ceil_div(max_rows > 0 ? max_rows : 1, per);
+    p.part_b = fg_align_up((size_t)p.n_chunks * 2 * d_in * d_out * 4, 256);
+    p.total = p.part_b + fg_align_up((size_t)p.n_chunks * d_out * 4, 256);
+    return p;
+}
+
+}  // namespace
+
+extern "C" size_t fg_layer_backward_weights_workspace_bytes(int64_t max_rows, int32_t d_in, int32_t d_out) {
+    if (max_rows < 0 || d_in <= 0 || d_out <= 0) return 0;
+    return wg_plan(max_rows, d_in, d_out).total;
+}
+
+extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t n_src, int64_t src_stride, const float* agg_dev,
+                                                 int64_t agg_stride, const float* dh_dev, int64_t dh_stride, const float* h_dev,
+                                                 int64_t h_stride, int32_t n, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                                 int64_t max_rows, int32_t d_in, int32_t d_out, float* dw_dev, float* db_dev,
+                                                 void* ws_dev, size_t ws_bytes, void* stream) {
+    const char* who = "fg_layer_backward_weights";
+    if (n < 0 || n_src < 0 || max_rows < 0 || d_in <= 0 || d_out <= 0)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (n %d, n_src %d, max_rows %lld, d_in %d, d_out %d)", who, n, n_src, (long long)max_rows, d_in, d_out);
+    if (!dw_dev) FG_FAIL(FG_ERR_INVALID_ARG, "%s: dw_dev is NULL", who);
+    if (max_rows > 0 && n > 0 && n_src > 0 && (!h_src_dev || !agg_dev || !dh_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
+    if (src_stride < (int64_t)d_in * 4 || agg_stride < (int64_t)d_in * 4 || dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * 4))
+        FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
+    if (((uintptr_t)h_src_dev | (uintptr_t)agg_dev | (uintptr_t)dh_dev | (uintptr_t)h_dev | (uintptr_t)dw_dev | (uintptr_t)db_dev |
+         (uintptr_t)src_stride | (uintptr_t)agg_stride | (uintptr_t)dh_stride | (uintptr_t)h_stride) & 3)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: pointers and strides must be 4-byte aligned", who);
+    const WgPlan P = wg_plan(max_rows, d_in, d_out);
+    if (!ws_dev || ws_bytes < P.total) FG_FAIL(FG_ERR_SHAPE, "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes, P.total);
+    if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: the workspace must be 16-byte aligned", who);
+    fg_clear_error();
+    hipStream_t st = (hipStream_t)stream;
+    float* part_w = (float*)ws_dev;
+    float* part_b = (float*)((char*)ws_dev + P.part_b);
+    // without rows (or without anything they could index) every chunk is empty and the partials are zeros
+    const int64_t rows_bound = (n > 0 && n_src > 0) ? max_rows : 0;
+    hipLaunchKernelGGL(weight_grad_partial_kernel, dim3((unsigned)P.n_chunks, (unsigned)P.tiles_m, (unsigned)P.tiles_n), dim3(WG_THREADS), 0, st,
+                       (const char*)h_src_dev, n_src, src_stride, (const char*)agg_dev, agg_stride, (const char*)dh_dev, dh_stride,
+                       (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, rows_bound, d_in, d_out, P.rows_per_chunk, part_w, part_b);
+    FG_LAUNCH_CHECK("weight_grad_partial_kernel");
+    const int64_t mn = (int64_t)2 * d_in * d_out;
+    hipLaunchKernelGGL(weight_grad_reduce_kernel, dim3((unsigned)fg_ceil_div(mn + d_out, BW_THREADS)), dim3(BW_THREADS), 0, st, part_w, part_b,
+                       P.n_chunks, mn, d_out, dw_dev, db_dev);
+    FG_LAUNCH_CHECK("weight_grad_reduce_kernel");
+    return FG_OK;
+}

@@ -58,7 +58,7 @@ class HotPath:
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
-                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False):
+                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -83,7 +83,14 @@ class HotPath:
         self.H = [torch.zeros((n[l], dims[l]), dtype=TORCH_DTYPE[self.h_code[l]], device=dev) for l in range(L + 1)]
         self.agg_code = B.FG_F32 if self.comp_code == B.FG_F32 else B.FG_BF16
         agg_elems = max(n[l] * dims[l - 1] for l in range(1, L + 1))
-        self.AGG = torch.zeros(agg_elems, dtype=TORCH_DTYPE[self.agg_code], device=dev)
+        # the neighbour means of a layer, in list order; with weight gradients every layer keeps its own until the backward pass
+        self.weight_grads = bool(weight_grads and backward)
+        if self.weight_grads:
+            self.AGG_l = [None] + [torch.zeros(n[l] * dims[l - 1], dtype=TORCH_DTYPE[self.agg_code], device=dev) for l in range(1, L + 1)]
+        else:
+            shared = torch.zeros(agg_elems, dtype=TORCH_DTYPE[self.agg_code], device=dev)
+            self.AGG_l = [None] + [shared] * L
+        self.AGG = self.AGG_l[L]
         self.live = [torch.zeros(n[l], dtype=torch.uint8, device=dev) for l in range(L + 1)]
         self.hit = [torch.zeros(n[l], dtype=torch.uint8, device=dev) for l in range(L + 1)]
         self.hit_pos = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
@@ -124,6 +131,12 @@ class HotPath:
             self.gnorm = [None] + [torch.zeros(max(n[l], 1), dtype=torch.float32, device=dev) for l in range(1, L)]
             self.ws_bw_bytes = max([B.fg_layer_backward_workspace_bytes(n[l], n[l], dims[l - 1], dims[l]) for l in range(2, L + 1)] or [0])
             self.ws_bw = torch.zeros(self.ws_bw_bytes + 256, dtype=torch.uint8, device=dev)
+            if self.weight_grads:
+                assert self.feat_code == B.FG_F32, "weight gradients need fp32 features"
+                self.dW = [None] + [torch.zeros((2 * dims[l - 1], dims[l]), dtype=torch.float32, device=dev) for l in range(1, L + 1)]
+                self.db = [None] + [torch.zeros(dims[l], dtype=torch.float32, device=dev) for l in range(1, L + 1)]
+                self.ws_wg_bytes = max(B.fg_layer_backward_weights_workspace_bytes(n[l], dims[l - 1], dims[l]) for l in range(1, L + 1))
+                self.ws_wg = torch.zeros(self.ws_wg_bytes + 256, dtype=torch.uint8, device=dev)
         self.cache = None
         self.feature_side = False
         if L > 1:
@@ -225,7 +238,7 @@ class HotPath:
             if fused and l == 1:
                 tick("gather_aggregate[1]")
                 args = (bt.start[1], bt.end[1], bt.col[1], bt.nnz[1], bt.n[1], self.normal_pos[1], self._cnt(1, 2), bt.n[1],
-                        bt.ids[0], bt.n[0], self.feat, self.num_nodes, d0b, self.dims[0], in_code, self.AGG, agg_b,
+                        bt.ids[0], bt.n[0], self.feat, self.num_nodes, d0b, self.dims[0], in_code, self.AGG_l[1], agg_b,
                         self.agg_code, self.H[0], d0b, bt.n[0], st)
                 if self.feature_side:
                     B.fg_gather_aggregate_features(self.cache, *args)
@@ -234,10 +247,10 @@ class HotPath:
             else:
                 tick(f"aggregate[{l}]")
                 B.fg_aggregate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),
-                               bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], in_code, self.AGG, agg_b,
+                               bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], in_code, self.AGG_l[l], agg_b,
                                self.agg_code, st)
             tick(f"linear[{l}]")
-            B.fg_linear(self.H[l - 1], bt.n[l - 1], in_b, in_code, self.AGG, agg_b, self.normal_pos[l], self._cnt(l, 2),
+            B.fg_linear(self.H[l - 1], bt.n[l - 1], in_b, in_code, self.AGG_l[l], agg_b, self.normal_pos[l], self._cnt(l, 2),
                         bt.n[l], self.dims[l - 1], self.dims[l], self.W[l], self.comp_code, self.bias[l],
                         1 if l < L else 0, self.H[l], bt.n[l], out_b, out_code, st)
         # ---- loss and backward pass down to layer 1: the gradient norms the update admits and checks out by
@@ -253,6 +266,13 @@ class HotPath:
                                     self.dims[l - 1], self.dims[l], self.W[l], self.dH[l - 1], self.dims[l - 1] * 4,
                                     self.gnorm[l - 1], self.ws_bw, self.ws_bw_bytes, st)   # with the row norms of dH[l-1]
             gnorm = self.gnorm
+            if self.weight_grads:
+                for l in range(L, 0, -1):
+                    tick(f"weight_grads[{l}]")
+                    B.fg_layer_backward_weights(self.H[l - 1], bt.n[l - 1], self.dims[l - 1] * 4, self.AGG_l[l], self.dims[l - 1] * 4,
+                                                self.dH[l], self.dims[l] * 4, self.H[l] if l < L else None, self.dims[l] * 4, bt.n[l],
+                                                self.normal_pos[l], self._cnt(l, 2), bt.n[l], self.dims[l - 1], self.dims[l],
+                                                self.dW[l], self.db[l], self.ws_wg, self.ws_wg_bytes, st)
         # ---- update of the caches
         if do_update and self.update_all:
             tick("cache_update_all")

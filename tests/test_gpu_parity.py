@@ -477,6 +477,35 @@ def test_layer_backward_matches_oracle(env, d_in, d_out, n, n_src, max_deg, relu
     assert (np.abs(want).sum(axis=1) == 0).sum() == (np.abs(got).sum(axis=1) == 0).sum()
 
 
+@pytest.mark.parametrize("d_in,d_out,n,n_rows,relu,seed", [(128, 256, 5000, 4100, True, 0), (256, 256, 700, 700, True, 1),
+                                                         (64, 64, 300, 250, False, 2), (24, 72, 130, 77, True, 3),
+                                                         (8, 8, 9, 1, True, 4), (128, 256, 40, 0, True, 5)])
+def test_layer_backward_weights_match_oracle(env, d_in, d_out, n, n_rows, relu, seed):
+    torch, B = env
+    r = np.random.default_rng(seed)
+    n_src = n + 50
+    rows = np.sort(r.permutation(n)[:n_rows]).astype(np.int32)
+    h_src = r.standard_normal((n_src, d_in)).astype(np.float32)
+    agg = r.standard_normal((n, d_in)).astype(np.float32)        # list order; rows beyond n_rows are never read
+    dh = r.standard_normal((n, d_out)).astype(np.float32)
+    h = np.maximum(r.standard_normal((n, d_out)), 0).astype(np.float32)
+    W = np.zeros((2 * d_in, d_out), dtype=np.float32)
+    _, dW, db = O.layer_backward(np.zeros(n, np.int32), np.zeros(n, np.int32), np.zeros(0, np.int32), rows, dh, h, h_src[rows],
+                                 agg[:n_rows], W, n_src, relu=relu)
+    rows_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
+    if n_rows:
+        rows_dev[:n_rows] = dev(torch, rows)
+    cnt = dev(torch, np.asarray([n_rows], dtype=np.int64))
+    wsb = B.fg_layer_backward_weights_workspace_bytes(n, d_in, d_out)
+    ws = torch.full((wsb,), 255, dtype=torch.uint8, device="cuda")           # NaN patterns: every partial must be written
+    t_dw = torch.full((2 * d_in, d_out), 3.0, dtype=torch.float32, device="cuda")
+    t_db = torch.full((d_out,), 3.0, dtype=torch.float32, device="cuda")
+    B.fg_layer_backward_weights(dev(torch, h_src), n_src, d_in * 4, dev(torch, agg), d_in * 4, dev(torch, dh), d_out * 4,
+                                dev(torch, h) if relu else None, d_out * 4, n, rows_dev, cnt, n, d_in, d_out, t_dw, t_db, ws, wsb)
+    e, e_b = T.rel_err_rows(t_dw.cpu().numpy(), dW), T.rel_err_rows(t_db.cpu().numpy()[None, :], db[None, :])
+    assert e <= REL_TOL_F32 and e_b <= REL_TOL_F32, f"rel err dW {e:.3e}, db {e_b:.3e}"
+
+
 def test_iterations_tiny_with_backward_pass(env):
     """Whole iterations whose gradient norms come from the backward pass (loss, layer backward, row norms)."""
     torch, B = env
@@ -525,7 +554,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
     hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity,
                                              fused_input=fused, one_launch_top_down=one_launch_top_down,
                                              update_all=one_launch_top_down, hot_ids=hot,
-                                             buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward)
+                                             buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward)
     from paper_2301_07482_amd import binding as FGB
     bc = None
     if fs:
@@ -552,7 +581,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
     L = w.num_layers
     p = w.p_grad if p_grad is None else p_grad
     total_hits = 0
-    worst = worst_e2e = worst_bw = 0.0
+    worst = worst_e2e = worst_bw = worst_w = 0.0
     try:
         for it in range(iterations):
             mb = wl.minibatch(w, g, it)
@@ -592,6 +621,18 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                     e = T.rel_err_rows(dHd[l - 1], want)
                     worst_bw = max(worst_bw, e)
                     assert e <= REL_TOL_F32, f"dH[{l - 1}] iteration {it} (same inputs): rel err {e:.3e}"
+                # weight gradients, on the device's own inputs of each layer (fused loader: the neighbours' rows of the input
+                # layer were never materialised, the oracle's bit-identical feature rows take their place)
+                for l in range(L, 0, -1):
+                    rows = rec["look"][l]["normal_pos"]
+                    h_prev = rec["H"][0].astype(np.float32) if (fused and l == 1) else G.to_f32(hp.H[l - 1][:nl[l - 1]])
+                    agg_dev = G.to_f32(hp.AGG_l[l][: len(rows) * dims[l - 1]].view(len(rows), dims[l - 1]))
+                    _, dW, db = O.layer_backward(mb.start[l], mb.end[l], mb.col[l], rows, dHd[l], Hd[l], h_prev[rows], agg_dev,
+                                                 weights[l][0], nl[l - 1], relu=(l < L))
+                    e = T.rel_err_rows(hp.dW[l].cpu().numpy(), dW)
+                    e_b = T.rel_err_rows(hp.db[l].cpu().numpy()[None, :], db[None, :])
+                    worst_w = max(worst_w, e, e_b)
+                    assert e <= REL_TOL_F32 and e_b <= REL_TOL_F32, f"dW[{l}] / db[{l}] iteration {it}: rel err {e:.3e} / {e_b:.3e}"
                 dev_norms = {l: hp.gnorm[l][:nl[l]].cpu().numpy() for l in range(1, L)}
                 for l in range(1, L):
                     np.testing.assert_allclose(dev_norms[l], O.row_norms(dHd[l]).astype(np.float32), rtol=5e-7, atol=1e-37)
@@ -691,7 +732,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
             print(f"{w.name}: feature side served {served} input rows, {lost} of {len(hot)} rows displaced")
     finally:
         hp.close()
-    print(f"{w.name}: worst rel err same-inputs {worst:.3e}, end-to-end {worst_e2e:.3e}" + (f", embedding gradients {worst_bw:.3e}" if backward else ""))
+    print(f"{w.name}: worst rel err same-inputs {worst:.3e}, end-to-end {worst_e2e:.3e}" + (f", embedding gradients {worst_bw:.3e}, weight gradients {worst_w:.3e}" if backward else ""))
     if fs:
         return total_hits, worst, served
     return total_hits, worst
