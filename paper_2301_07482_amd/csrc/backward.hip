@@ -355,16 +355,26 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
     float colsum[4] = {0.f, 0.f, 0.f, 0.f};
 
+    // the position of list entry k, or of entry k_begin where k is past the chunk (that entry exists whenever this is called)
+    auto row_of = [&](int64_t kk) -> int32_t {
+        const int64_t ks = kk < k_end ? kk : k_begin;
+        return rows ? rows[ks] : (int32_t)ks;
+    };
+    int32_t r_next[WG_PAIRS];
+#pragma unroll
+    for (int p = 0; p < WG_PAIRS; ++p) r_next[p] = k_begin < k_end ? row_of(k_begin + 2 * p + kh) : 0;
     for (int64_t k0 = k_begin; k0 < k_end; k0 += 2 * WG_PAIRS) {
         float a[WG_PAIRS][2], g[WG_PAIRS][4], o[WG_PAIRS][4];
         bool ok[WG_PAIRS];
-        // all loads of the batch first (from a safe row where this lane has none), masks afterwards
+        // all loads of the batch first (from a safe row where this lane has none), masks afterwards; the positions were
+        // fetched a batch ahead so that the row loads do not wait for them
 #pragma unroll
         for (int p = 0; p < WG_PAIRS; ++p) {
             const int64_t kk = k0 + 2 * p + kh;
             const bool in = kk < k_end;
-            const int64_t ks = in ? kk : k_begin;  // k_begin < k_end here, so row k_begin exists
-            const int32_t r = rows ? rows[ks] : (int32_t)ks;
+            const int64_t ks = in ? kk : k_begin;
+            const int32_t r = r_next[p];
+            r_next[p] = row_of(kk + 2 * WG_PAIRS);
             ok[p] = in && r >= 0 && r < n && r < n_src;
             const int64_t rs = ok[p] ? r : 0;
             const float* xs = (const float*)(h_src + rs * src_stride);
@@ -420,20 +430,48 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
     }
 }
 
+// dw[i] = sum over the chunks of part_w[chunk][i] in fp64. A workgroup owns 128 consecutive elements (32 lanes x 4) and
+// splits the chunks over its 8 wavefront halves; db (the last workgroups) likewise.
+constexpr int RED_GROUPS = BW_THREADS / 32;
 __global__ __launch_bounds__(BW_THREADS) void weight_grad_reduce_kernel(const float* __restrict__ part_w,
                                                                         const float* __restrict__ part_b, int n_chunks,
-                                                                        int64_t mn, int n_cols, float* __restrict__ dw,
-                                                                        float* __restrict__ db) {
-    const int64_t i = (int64_t)blockIdx.x * BW_THREADS + threadIdx.x;
-    if (i < mn) {
-        double s = 0.0;
-        for (int c = 0; c < n_chunks; ++c) s += (double)part_w[(int64_t)c * mn + i];
-        dw[i] = (float)s;
-    } else if (db && i - mn < n_cols) {
-        const int64_t j = i - mn;
-        double s = 0.0;
-        for (int c = 0; c < n_chunks; ++c) s += (double)part_b[(int64_t)c * n_cols + j];
-        db[j] = (float)s;
+                                                                        int64_t mn, int n_cols, int w_blocks,
+                                                                        float* __restrict__ dw, float* __restrict__ db) {
+    __shared__ double red[RED_GROUPS][32][4];
+    const int tx = threadIdx.x & 31, g = threadIdx.x >> 5;
+    const bool is_w = (int)blockIdx.x < w_blocks;
+    const float* part = is_w ? part_w : part_b;
+    const int64_t len = is_w ? mn : n_cols;  // both multiples of 4
+    float* out = is_w ? dw : db;
+    const int64_t i = ((int64_t)(is_w ? blockIdx.x : blockIdx.x - w_blocks) * 32 + tx) * 4;
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+    if (i < len) {
+        for (int c = g; c < n_chunks; c += 4 * RED_GROUPS) {
+            f32x4 v[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int cc = c + u * RED_GROUPS;
+                v[u] = cc < n_chunks ? *(const f32x4*)(part + (int64_t)cc * len + i) : f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                s[0] += (double)v[u].x;
+                s[1] += (double)v[u].y;
+                s[2] += (double)v[u].z;
+                s[3] += (double)v[u].w;
+            }
+        }
+    }
+#pragma unroll
+    for (int q = 0; q < 4; ++q) red[g][tx][q] = s[q];
+    __syncthreads();
+    if (g == 0 && i < len && out) {
+        double t[4] = {0.0, 0.0, 0.0, 0.0};
+        for (int gg = 0; gg < RED_GROUPS; ++gg)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) t[q] += red[gg][tx][q];
+        const f32x4 o = {(float)t[0], (float)t[1], (float)t[2], (float)t[3]};
+        *(f32x4*)(out + i) = o;
     }
 }
 
@@ -474,6 +512,8 @@ extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t
     if (n < 0 || n_src < 0 || max_rows < 0 || d_in <= 0 || d_out <= 0)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (n %d, n_src %d, max_rows %lld, d_in %d, d_out %d)", who, n, n_src, (long long)max_rows, d_in, d_out);
     if (!dw_dev) FG_FAIL(FG_ERR_INVALID_ARG, "%s: dw_dev is NULL", who);
+    if (d_out % 4) FG_FAIL(FG_ERR_SHAPE, "%s: d_out = %d must be a multiple of 4", who, d_out);
+    if (((uintptr_t)dw_dev | (uintptr_t)db_dev) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: dw_dev and db_dev must be 16-byte aligned", who);
     if (max_rows > 0 && n > 0 && n_src > 0 && (!h_src_dev || !agg_dev || !dh_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
     if (src_stride < (int64_t)d_in * 4 || agg_stride < (int64_t)d_in * 4 || dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * 4))
         FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
@@ -494,8 +534,9 @@ extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t
                        (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, rows_bound, d_in, d_out, P.rows_per_chunk, part_w, part_b);
     FG_LAUNCH_CHECK("weight_grad_partial_kernel");
     const int64_t mn = (int64_t)2 * d_in * d_out;
-    hipLaunchKernelGGL(weight_grad_reduce_kernel, dim3((unsigned)fg_ceil_div(mn + d_out, BW_THREADS)), dim3(BW_THREADS), 0, st, part_w, part_b,
-                       P.n_chunks, mn, d_out, dw_dev, db_dev);
+    const int w_blocks = (int)fg_ceil_div(mn, 128), b_blocks = (int)fg_ceil_div(d_out, 128);
+    hipLaunchKernelGGL(weight_grad_reduce_kernel, dim3((unsigned)(w_blocks + b_blocks)), dim3(BW_THREADS), 0, st, part_w, part_b, P.n_chunks,
+                       mn, d_out, w_blocks, dw_dev, db_dev);
     FG_LAUNCH_CHECK("weight_grad_reduce_kernel");
     return FG_OK;
 }
