@@ -128,6 +128,12 @@ const void* fg_cache_table(const fg_cache_t* cache, int32_t layer);
 fg_status_t fg_cache_set_t_stale(fg_cache_t* cache, int32_t t_stale);
 
 /*
+ * Stabilization period (Section 4.1.4): lookups of iterations < n_iterations find nothing and updates of those
+ * iterations admit nothing (regular mini-batch training); from iteration n_iterations on the cache is active. 0 = none.
+ */
+fg_status_t fg_cache_set_stabilization(fg_cache_t* cache, int64_t n_iterations);
+
+/*
  * Snapshot for tests and monitoring: every entry a lookup at iteration `iter` would hit, in slot
  * order: nodes_dev[k], slots_dev[k], stamps_dev[k] (each int32[capacity] device, may be NULL),
  * *count_dev (int64 device) = number of entries, *head_dev (int64 device, may be NULL) = ring header.

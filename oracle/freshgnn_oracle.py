@@ -339,6 +339,28 @@ def linear(h_self, agg, W, b, relu):
     return np.maximum(z, 0.0) if relu else z
 
 
+def aggregate_gcn(start, end, col, rows, h_src):
+    """Propagation of a GCN layer in its row-normalised form, per row in `rows`: the mean over the row's own previous
+    embedding and those of its sampled neighbours, (h_v + sum_u h_u) / (deg + 1): float64 [len(rows), d].
+
+    The paper names GCN among its models without writing the layer down. The graph convolution adds a self loop and
+    normalises by degree; on a sampled block only the row's own sampled degree is known, so the normalisation is by
+    row (the mean aggregator with the node itself included), followed by one weight matrix (`linear_gcn`).
+    """
+    h = np.asarray(h_src)
+    out = np.zeros((len(rows), h.shape[1]), dtype=np.float64)
+    for k, r in enumerate(rows):
+        nb = col[start[r]:end[r]]
+        out[k] = (h[r].astype(np.float64) + h[nb].astype(np.float64).sum(axis=0)) / float(len(nb) + 1)
+    return out
+
+
+def linear_gcn(agg, W, b, relu):
+    """act(agg · W + b) with W [d_in, d_out]: the dense part of a GCN layer, float64."""
+    z = np.asarray(agg, dtype=np.float64) @ np.asarray(W, dtype=np.float64) + np.asarray(b, dtype=np.float64)
+    return np.maximum(z, 0.0) if relu else z
+
+
 # --------------------------------------------------------------------------- loss and backward pass
 
 def softmax_xent(h, labels):
@@ -503,7 +525,7 @@ def check_minibatch(mb):
 
 
 def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_dtype="f32", compute_dtype="f32",
-              update=True, feature_side=None, labels=None):
+              update=True, feature_side=None, labels=None, stabilization=0, model="sage"):
     """One pass of Algorithm 1 without loss/backward (gradient norms are given).
 
     mb        sampled mini-batch (its `end` arrays are modified: pruning)
@@ -511,6 +533,10 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
     feature_rows(ids) -> raw feature rows; weights[l] = (W_l, b_l); gnorms[l] = norms by position
     dims      [d_0..d_L]
     feature_side   optional BidirectionalCache whose rings are `caches`: raw features are loaded through it
+    model     "sage": GraphSAGE-mean layers (`aggregate`, `linear`, W_l [2*d, d']); "gcn": GCN layers (`aggregate_gcn`,
+              `linear_gcn`, W_l [d, d']), fp32 only, no backward pass
+    stabilization   length of the stabilization period (Section 4.1.4): in iterations i < stabilization the historical
+              cache is disabled (no lookup, no admission: regular mini-batch training), afterwards it is active
     labels    optional class of every seed: the gradient norms then come from `backward` (softmax cross-entropy on
               H(L)) and `gnorms` is ignored
     Types: H(0) in feat_dtype; H(l), AGG(l) for l >= 1 in compute_dtype except H(L) which is fp32.
@@ -519,6 +545,9 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
     """
     L = mb.num_layers
     rec = dict(layers={})
+    cache_active = i >= stabilization
+    if not cache_active:
+        caches = {}
     live = [None] * (L + 1)
     look = [None] * (L + 1)
     live[L] = np.ones(len(mb.ids[L]), dtype=bool)
@@ -546,8 +575,13 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
             c = caches[l]
             gather(lambda s: c.table[s], look[l]["hit_slot"], H[l], look[l]["hit_pos"])
         rows = look[l]["normal_pos"]
-        agg64 = aggregate(mb.start[l], mb.end[l], mb.col[l], rows, H[l - 1])
         W, b = weights[l]
+        if model == "gcn":
+            assert compute_dtype == "f32" and labels is None
+            AGG[l] = round_to(aggregate_gcn(mb.start[l], mb.end[l], mb.col[l], rows, H[l - 1]), "f32")
+            H[l][rows] = round_to(linear_gcn(AGG[l], W, b, relu=(l < L)), out_dtype)
+            continue
+        agg64 = aggregate(mb.start[l], mb.end[l], mb.col[l], rows, H[l - 1])
         if compute_dtype == "bf16":
             AGG[l] = round_bf16(agg64)
             h_self = round_bf16(H[l - 1][rows].astype(np.float64))
@@ -561,6 +595,8 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
     if labels is not None:
         rec["backward"] = backward(mb, rec, weights, labels, compute_dtype)
         gnorms = rec["backward"]["gnorm"]
+    if not cache_active:
+        stats = {l: dict(admitted=0, evicted_by_gradient=0, overwritten=0, dropped_overflow=0, tau=None) for l in range(1, L)}
     if update:
         for l in range(1, L):
             if caches.get(l) is not None:

@@ -40,6 +40,7 @@ SIGNATURES = {
     "fg_cache_clear": (_i32, [_p, _p]),
     "fg_cache_table": (_p, [_p, _i32]),
     "fg_cache_set_t_stale": (_i32, [_p, _i32]),
+    "fg_cache_set_stabilization": (_i32, [_p, _i64]),
     "fg_cache_export": (_i32, [_p, _i32, _i64, _p, _p, _p, _p, _p, _p, _sz, _p]),
     "fg_workspace_bytes": (_sz, [_i32, _i64, _i64]),
     "fg_set_tuning": (_i32, [C.c_char_p, _i64]),
@@ -182,6 +183,10 @@ def fg_cache_table(cache, layer):
 
 def fg_cache_set_t_stale(cache, t_stale):
     _check(_lib.fg_cache_set_t_stale(cache, t_stale))
+
+
+def fg_cache_set_stabilization(cache, n_iterations):
+    _check(_lib.fg_cache_set_stabilization(cache, n_iterations))
 
 
 def fg_cache_export(cache, layer, it, nodes, slots, stamps, count, head, ws, ws_bytes, stream=None):

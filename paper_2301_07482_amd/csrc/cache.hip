@@ -578,6 +578,13 @@ extern "C" fg_status_t fg_cache_set_t_stale(fg_cache_t* cache, int32_t t_stale) 
     return FG_OK;
 }
 
+extern "C" fg_status_t fg_cache_set_stabilization(fg_cache_t* cache, int64_t n_iterations) {
+    if (!cache) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_set_stabilization: cache is NULL");
+    if (n_iterations < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_set_stabilization: n_iterations = %lld is negative", (long long)n_iterations);
+    cache->stabilization = n_iterations;
+    return FG_OK;
+}
+
 extern "C" fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, int64_t iter, int32_t* nodes_dev,
                                        int32_t* slots_dev, int32_t* stamps_dev, int64_t* count_dev, int64_t* head_dev,
                                        void* ws_dev, size_t ws_bytes, void* stream) {
@@ -639,7 +646,7 @@ fg_status_t prepare_update_layer(fg_cache_t* cache, const char* who, int32_t lay
     u.table = (char*)l->table;
     u.row_bytes = row_bytes;
     u.n = n;
-    u.p_grad = p_grad;
+    u.p_grad = iter < cache->stabilization ? 0.0f : p_grad;  // stabilization period: nothing is admitted (k = 0)
     return FG_OK;
 }
 

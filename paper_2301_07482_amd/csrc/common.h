@@ -25,6 +25,7 @@ struct fg_cache {
     int32_t n_layers = 0;
     fg_dtype_t dtype = FG_F32;
     int32_t t_stale = 0;
+    int64_t stabilization = 0;   // iterations before this one neither look the cache up nor admit into it (Section 4.1.4)
     fg_layer* layers = nullptr;  // host array [n_layers], layer l at index l-1
     // the buffer embeddings and raw features share (Section 4.2): rings from the left end in layer order,
     // feature rows from the right end, rank r at [buffer_bytes - (r+1)*feat_row_bytes, buffer_bytes - r*feat_row_bytes)
@@ -66,6 +67,9 @@ __device__ __forceinline__ int32_t fg_feature_rank(const fg_feat_side& F, int32_
     }
     return r;
 }
+
+// staleness bound in force for a lookup at iteration `iter`: none is usable during the stabilization period
+static inline int32_t fg_t_stale_at(const fg_cache_t* c, int64_t iter) { return iter < c->stabilization ? 0 : c->t_stale; }
 
 void fg_set_error(const char* fmt, ...);
 void fg_clear_error();

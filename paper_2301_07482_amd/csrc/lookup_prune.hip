@@ -271,7 +271,7 @@ extern "C" fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, i
         if (n > 0 && (!hit_dev || !hit_pos_dev || !hit_slot_dev))
             FG_FAIL(FG_ERR_INVALID_ARG, "fg_lookup_prune: hit_dev, hit_pos_dev and hit_slot_dev are required with a cache");
         const fg_layer& ly = cache->layers[layer - 1];
-        cv = CacheView{ly.map, ly.slot_node, ly.slot_stamp, ly.capacity, cache->num_nodes, iter, cache->t_stale};
+        cv = CacheView{ly.map, ly.slot_node, ly.slot_stamp, ly.capacity, cache->num_nodes, iter, fg_t_stale_at(cache, iter)};
     }
     const WsLayout w = ws_layout(n);
     if (n > 0 && (!ws_dev || ws_bytes < w.total))
@@ -344,7 +344,7 @@ extern "C" fg_status_t fg_top_down(const fg_cache_t* cache, int64_t iter, int32_
             if (in.n > 0 && (!in.hit_dev || !in.hit_pos_dev || !in.hit_slot_dev))
                 FG_FAIL(FG_ERR_INVALID_ARG, "fg_top_down: layers[%d]: hit_dev, hit_pos_dev and hit_slot_dev are required with a cache", i);
             const fg_layer& ly = cache->layers[in.cache_layer - 1];
-            L.cv = CacheView{ly.map, ly.slot_node, ly.slot_stamp, ly.capacity, cache->num_nodes, iter, cache->t_stale};
+            L.cv = CacheView{ly.map, ly.slot_node, ly.slot_stamp, ly.capacity, cache->num_nodes, iter, fg_t_stale_at(cache, iter)};
             L.has_cache = 1;
         }
         const WsLayout w = ws_layout(in.n);

@@ -58,7 +58,7 @@ class HotPath:
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
-                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False):
+                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -148,6 +148,8 @@ class HotPath:
             else:
                 self.cache = B.fg_cache_create_bidirectional(num_nodes, caps, cdims, self.comp_code, t_stale, buffer_bytes,
                                                              self._stream())
+            if stabilization:
+                B.fg_cache_set_stabilization(self.cache, int(stabilization))
             # hot_ids (hottest first): their raw features are placed on the feature side of the cache's buffer and the
             # loader reads them from there while no embedding has been written over them
             if hot_ids is not None and len(hot_ids):

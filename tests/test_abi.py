@@ -105,6 +105,7 @@ def test_argument_validation_needs_no_gpu(B):
     assert code(B.fg_layer_backward_weights, 4096, 10, 512, 4096, 512, 4096, 1024, None, 0, 10, 4096, None, 10, 128, 256, 4096, None,
                 4096, 64) == B.FG_ERR_SHAPE                                                                 # workspace
     assert B.fg_layer_backward_weights_workspace_bytes(67584, 128, 256) >= 256 * 256 * 4
+    assert code(B.fg_cache_set_stabilization, None, 3) == B.FG_ERR_INVALID_ARG
     assert code(B.fg_set_tuning, "gather_unroll", -3) == B.FG_ERR_INVALID_ARG
     assert B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, 1000) >= 1000 * 5
     assert B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, 1000) >= 1000 * 9

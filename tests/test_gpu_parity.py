@@ -537,7 +537,7 @@ def test_iterations_large_hbm_full_size_with_backward_pass(env):
 
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
-                        backward=False):
+                        backward=False, stabilization=0):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
@@ -554,7 +554,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
     hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity,
                                              fused_input=fused, one_launch_top_down=one_launch_top_down,
                                              update_all=one_launch_top_down, hot_ids=hot,
-                                             buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward)
+                                             buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward, stabilization=stabilization)
     from paper_2301_07482_amd import binding as FGB
     bc = None
     if fs:
@@ -598,7 +598,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                     f"feature-side ranks, iteration {it}"
                 assert found == int((ranks >= 0).sum())
             rec = O.iteration(mb, it, caches, frows, weights, gn, p, dims, w.feat_dtype, w.compute_dtype, feature_side=bc,
-                              labels=labels, update=not backward)
+                              labels=labels, update=not backward, stabilization=stabilization)
             served += int(rec["feature_from_buffer"].sum())
             # device cache rows at the slots about to be hit, read before this iteration's update recycles slots
             pre_rows = {l: hp.cache_rows(l, rec["look"][l]["hit_slot"]) for l in range(1, L) if len(rec["look"][l]["hit_pos"])}
@@ -642,8 +642,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                     bad = (np.abs(dHd[l] - ref) / den).max(axis=1) > REL_TOL_F32 * 2 * (L - l + 1)
                     assert bad.mean() <= 0.01, f"dH[{l}] iteration {it} (end to end): {int(bad.sum())} of {len(bad)} rows off"
                     # the update itself, from the device's norms on both sides
-                    rec["stats"][l] = O.cache_update(caches[l], it, mb.ids[l], rec["live"][l], rec["look"][l]["hit"], dev_norms[l], p,
-                                                     rec["H"][l])
+                    rec["stats"][l] = O.cache_update(caches[l], it, mb.ids[l], rec["live"][l], rec["look"][l]["hit"], dev_norms[l],
+                                                     p if it >= stabilization else 0.0, rec["H"][l])
             for l in range(L, 0 if fused else -1, -1):
                 s, lk = snap["layers"][l], rec["look"][l]
                 assert tuple(snap["counts"][l]) == lk["counts"], f"counts, iteration {it} layer {l}"
@@ -761,6 +761,15 @@ def test_iterations_tiny_degenerate_settings(env):
     w = wl.WORKLOADS["tiny"]
     assert run_workload_parity(torch, w, 6, t_stale=0)[0] == 0
     assert run_workload_parity(torch, w, 6, p_grad=0.0)[0] == 0
+
+
+def test_iterations_tiny_stabilization_period(env):
+    """Section 4.1.4: the first iterations run without the cache (no hit, nothing admitted), then it starts empty."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    assert run_workload_parity(torch, w, 5, stabilization=5)[0] == 0
+    assert run_workload_parity(torch, w, 14, stabilization=5)[0] > 0
+    assert run_workload_parity(torch, w, 12, stabilization=4, one_launch_top_down=False, fused=True)[0] > 0
 
 
 def test_iterations_tiny_small_ring(env):

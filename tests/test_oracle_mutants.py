@@ -26,6 +26,8 @@ PINS = [
     (P.test_trace_ring, [()]),
     (P.test_staleness_boundary, [()]),
     (P.test_cache_matches_dictionary_model, [(5, 2, 0.5), (16, 4, 0.9), (3, 1, 1.0), (40, 50, 0.3)]),
+    (P.test_stabilization_period_is_plain_sampling_then_a_cache_that_starts_empty, [()]),
+    (P.test_gcn_full_neighbourhood_equals_dense_recursion_and_closed_forms, [()]),
     (F.test_trace_junction, [()]),
     (F.test_validity_equals_untouched_bytes_and_rows_stay_bit_identical,
      [(0, "f32", "f32", 4096, [5, 3], [12, 20], 8, 128), (1, "f32", "f32", 8192, [7, 4], [36, 8], 12, 170),
@@ -120,6 +122,12 @@ MUTANTS = [
     ("the input gradient uses the untransposed weights of the self panel twice", None, "layer_backward", "dx = dz @ W.T",
      "dx = dz @ np.concatenate([W[:d_in], W[:d_in]]).T"),
     ("gradient norms are taken one layer off", None, "backward", "gnorm = {l: row_norms(dH[l])", "gnorm = {l: row_norms(dH[l + 1])"),
+    ("the GCN propagation leaves the node itself out", None, "aggregate_gcn", "(h[r].astype(np.float64) + h[nb]", "(0 * h[r].astype(np.float64) + h[nb]"),
+    ("the GCN propagation divides by the neighbour count only", None, "aggregate_gcn", "/ float(len(nb) + 1)", "/ float(max(len(nb), 1))"),
+    ("the GCN layer drops its bias", None, "linear_gcn", "+ np.asarray(b, dtype=np.float64)", "+ 0 * np.asarray(b, dtype=np.float64)"),
+    ("the GCN layer never applies ReLU", None, "linear_gcn", "if relu else z", "if False else z"),
+    ("the stabilization period ends one iteration early", None, "iteration", "cache_active = i >= stabilization", "cache_active = i >= stabilization - 1"),
+    ("the cache is looked up during the stabilization period", None, "iteration", "    if not cache_active:\n        caches = {}\n", ""),
     ("cached feature rows are read at the neighbouring rank", "BidirectionalCache", "load",
      "out[k] = self.buf[B - (r + 1) * w:B - r * w].view(np_dt)", "out[k] = self.buf[B - (r + 2) * w:B - (r + 1) * w].view(np_dt) if r + 2 <= self.n_feat else 0"),
 ]

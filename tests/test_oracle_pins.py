@@ -357,3 +357,72 @@ def test_cache_matches_dictionary_model(cap, t_stale, p):
             assert c.map[v] == s and c.slot_node[s] == v and 1 <= i + 1 - stamp <= t_stale
             assert np.array_equal(c.table[s], m.ring[m.where[v]][2])
         assert c.head == m.head
+
+
+# ---------------------------------------------------------------- stabilization period (Section 4.1.4)
+
+def test_stabilization_period_is_plain_sampling_then_a_cache_that_starts_empty():
+    g = T.random_explicit_graph(150, 5, 8)
+    dims = [6, 7, 7, 4]
+    X = np.random.default_rng(1).standard_normal((150, 6)).astype(np.float32)
+    weights = T.random_weights(dims, 2)
+    period = 4
+
+    def run(stabilization, p_grad_of):
+        caches = {l: O.HistoricalCache(150, 80, dims[l], 3) for l in (1, 2)}
+        out = []
+        for it in range(10):
+            seeds = np.random.default_rng(100 + it).permutation(150)[:10]
+            mb = T.sample(g, seeds, [3, 3, 3], it)
+            r = np.random.default_rng(500 + it)
+            gn = {l: np.exp(r.standard_normal(len(mb.ids[l]))).astype(np.float32) for l in (1, 2)}
+            rec = O.iteration(mb, it, caches, lambda ids: X[ids], weights, gn, p_grad_of(it), dims, stabilization=stabilization)
+            out.append((rec, mb))
+        return out, caches
+
+    with_period, ca = run(period, lambda it: 0.6)
+    plain, _ = run(0, lambda it: 0.0)                       # p_grad = 0: neighbour sampling without a cache (Section 4.1.3)
+    gated, cb = run(0, lambda it: 0.0 if it < period else 0.6)   # the same policy said differently: nothing admitted before `period`
+    for it in range(10):
+        a, b, c = with_period[it][0], plain[it][0], gated[it][0]
+        if it < period:                                     # regular mini-batch training
+            for l in range(4):
+                assert np.array_equal(a["H"][l], b["H"][l])
+            assert all(len(a["look"][l]["hit_pos"]) == 0 for l in (1, 2))
+            assert all(a["stats"][l]["admitted"] == 0 for l in (1, 2))
+        for l in range(1, 4):                               # afterwards: a cache that started empty at `period`
+            assert np.array_equal(a["look"][l]["hit_pos"], c["look"][l]["hit_pos"])
+            assert np.array_equal(a["H"][l], c["H"][l])
+    assert sum(len(with_period[it][0]["look"][1]["hit_pos"]) for it in range(period + 1, 10)) > 0
+    assert all(np.array_equal(ca[l].map, cb[l].map) and ca[l].head == cb[l].head for l in (1, 2))
+    assert min(int(s) for l in (1, 2) for s in ca[l].slot_stamp[ca[l].slot_node >= 0]) >= period
+
+
+# ---------------------------------------------------------------- GCN layers
+
+def test_gcn_full_neighbourhood_equals_dense_recursion_and_closed_forms():
+    """H = act(D~^-1 (A + I) H W + b): row-normalised graph convolution with self loops, over the whole graph."""
+    g = T.random_explicit_graph(50, 5, 6)
+    dims = [6, 5, 7, 4]
+    L = 3
+    X = np.random.default_rng(0).standard_normal((50, 6)).astype(np.float32)
+    r = np.random.default_rng(1)
+    weights = {l: ((r.standard_normal((dims[l - 1], dims[l])) / np.sqrt(dims[l - 1])).astype(np.float32),
+                   (0.1 * r.standard_normal(dims[l])).astype(np.float32)) for l in range(1, L + 1)}
+    seeds = np.random.default_rng(2).permutation(50)[:9]
+    mb = T.sample(g, seeds, [5] * L, 0)
+    rec = O.iteration(mb, 0, {}, lambda ids: X[ids], weights, {}, 0.5, dims, model="gcn")
+    A = T.dense_adjacency(g) + np.eye(50)
+    P = A / A.sum(axis=1, keepdims=True)
+    H = X.astype(np.float64)
+    for l in range(1, L + 1):
+        Z = P @ H @ weights[l][0].astype(np.float64) + weights[l][1].astype(np.float64)
+        H = np.maximum(Z, 0) if l < L else Z
+    np.testing.assert_allclose(rec["H"][L], H[seeds], rtol=0, atol=2e-6 * np.abs(H).max())
+    # closed forms of the propagation: an isolated row keeps its own embedding; constant features stay constant
+    start, end, col = np.array([0, 0, 2]), np.array([0, 2, 3]), np.array([0, 2, 1])
+    h = np.array([[1.0, 2.0], [3.0, 5.0], [7.0, 11.0]])
+    got = O.aggregate_gcn(start, end, col, [0, 1, 2], h)
+    assert np.allclose(got, [[1, 2], [(3 + 1 + 7) / 3, (5 + 2 + 11) / 3], [(7 + 3) / 2, (11 + 5) / 2]])
+    assert np.allclose(O.aggregate_gcn(start, end, col, [2, 0], np.full((3, 4), 2.5)), 2.5)
+    assert np.allclose(O.linear_gcn(np.eye(3), np.arange(6.0).reshape(3, 2), [1.0, -10.0], relu=True), [[1, 0], [3, 0], [5, 0]])
