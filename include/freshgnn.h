@@ -304,6 +304,27 @@ fg_status_t fg_gather_aggregate_features(const fg_cache_t* cache, const int32_t*
                                          void* h_self_out, int64_t h_self_stride, int32_t n_self_rows, void* stream);
 
 /*
+ * Propagation of a GCN layer in row-normalised form (the paper lists GCN among its models without writing the layer
+ * down; on a sampled block only the row's own sampled degree is known, so the graph convolution's self loop and degree
+ * normalisation become the mean over the node itself and its sampled neighbours), fp32, for the rows listed:
+ *   m[k, :] = (h_src[r, :] + sum_{e in [row_start[r], row_end[r])} h_src[col[e], :]) / (deg + 1),  r = rows[k]
+ * The dense part of the layer, act(m . W + b) with W [dim x d_out], is fg_linear with d_in = dim/2, and the mean is
+ * written in the form that call reads:
+ *   mean_pos_dev[r, 0:dim/2] = m[k, 0:dim/2]     (by position, n_block_rows rows)  -> fg_linear's h_src
+ *   mean_cmp_dev[k, 0:dim/2] = m[k, dim/2:dim]   (list order, max_rows rows)       -> fg_linear's agg
+ * dim a multiple of 8; other arguments as for fg_aggregate / fg_gather_aggregate.
+ */
+fg_status_t fg_aggregate_gcn(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev, int64_t nnz,
+                             int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                             const float* h_src, int32_t n_src, int64_t src_stride, int32_t dim, float* mean_pos_dev,
+                             float* mean_cmp_dev, void* stream);
+fg_status_t fg_gather_aggregate_gcn(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
+                                    int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                    int64_t max_rows, const int32_t* src_ids_dev, int32_t n_src, const float* table,
+                                    int64_t table_rows, int64_t src_stride, int32_t dim, float* mean_pos_dev,
+                                    float* mean_cmp_dev, void* stream);
+
+/*
  * Dense update of a GraphSAGE-mean layer (phi of Eq. 1; the f_W line of Algorithm 1), for the rows listed:
  *   h_out[r, :] = act( h_src[r, :] . W[0:d_in, :] + agg[k, :] . W[d_in:2*d_in, :] + bias ),  r = rows[k]
  *   act = ReLU if relu != 0, identity otherwise.

@@ -113,13 +113,16 @@ __device__ __forceinline__ u32x4 load_piece(const char* p) {
 // loader + first-layer aggregation); table rows are then read with streaming loads, once each.
 // FEAT (with INDIRECT): a node whose raw features are still on the feature side of the shared buffer (Section 4.2)
 // is read from there. The staged entry of such a neighbour is -2 - rank instead of the node id.
-template <int IN, int OUT, bool INDIRECT, bool FEAT>
+// GCN: the propagation of a GCN layer in row-normalised form: the row's own previous embedding is part of the mean,
+// (h_r + sum of the neighbours) / (deg + 1). The result is written as the two halves the dense update reads: columns
+// [0, dim/2) to gcn_pos[r, :] (by position), columns [dim/2, dim) to agg[k, :] (list order).
+template <int IN, int OUT, bool INDIRECT, bool FEAT, bool GCN = false>
 __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
     const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ col,
     int64_t nnz, int n_block_rows, const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev,
     int64_t max_rows, const char* __restrict__ h_src, int64_t n_src, int64_t src_stride, int pieces, char* __restrict__ agg,
     int64_t agg_stride, int lanes_log2, const int32_t* __restrict__ src_ids, int n_ids, char* __restrict__ self_out,
-    int64_t self_stride, int n_self, fg_feat_side F) {
+    int64_t self_stride, int n_self, fg_feat_side F, char* __restrict__ gcn_pos = nullptr, int64_t gcn_pos_stride = 0) {
     constexpr int PER = Elem<IN>::PER16;
     constexpr int OUT_BYTES = (OUT == FG_F32 ? 4 : 2) * PER;
     extern __shared__ int32_t nb_lds[];  // [groups_per_block][AGG_MAX_STAGE]
@@ -141,7 +144,8 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
         const int deg = e0 - s0;
         // fused loader: the row's own features (position r of the input layer is the same node) go to self_out[r]
         const char* self_row = nullptr;
-        if (INDIRECT && self_out && r >= 0 && r < n_ids && r < n_self) {
+        if (GCN && !INDIRECT && r >= 0 && r < n_src && r < n_block_rows) self_row = h_src + (int64_t)r * src_stride;
+        if (INDIRECT && (self_out || GCN) && r >= 0 && r < n_ids && (GCN ? r < n_block_rows : r < n_self)) {
             const int32_t v = src_ids[r];
             if (v >= 0 && v < n_src) {
                 self_row = h_src + (int64_t)v * src_stride;
@@ -155,10 +159,11 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
             const int piece = p0 + lane;
             const bool active = piece < pieces;
             u32x4 self_piece;
-            if (INDIRECT && self_row && active) self_piece = load_piece<true>(self_row + (int64_t)piece * 16);
+            if ((INDIRECT || GCN) && self_row && active) self_piece = load_piece<INDIRECT>(self_row + (int64_t)piece * 16);
             double acc[PER];
 #pragma unroll
             for (int i = 0; i < PER; ++i) acc[i] = 0.0;
+            if (GCN && self_row && active) Elem<IN>::unpack(self_piece, acc);
             const int deg_ld = n_src > 0 ? deg : 0;  // an empty source has no row to read (the means are then zero)
             for (int base = 0; base < deg_ld; base += AGG_MAX_STAGE) {
                 const int cnt = min(deg_ld - base, AGG_MAX_STAGE);
@@ -223,8 +228,22 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
                 }
                 __builtin_amdgcn_wave_barrier();  // the stage is rewritten by the next pass
             }
-            if (active) store_row_piece<OUT, PER>(agg + k * agg_stride + (int64_t)piece * OUT_BYTES, acc, (double)deg);
-            if (INDIRECT && self_row && active) *(u32x4*)(self_out + (int64_t)r * self_stride + (int64_t)piece * 16) = self_piece;
+            if constexpr (GCN) {
+                const int half = pieces >> 1;
+                if (active && self_row) {
+                    char* dst = piece < half ? gcn_pos + (int64_t)r * gcn_pos_stride + (int64_t)piece * OUT_BYTES
+                                             : agg + k * agg_stride + (int64_t)(piece - half) * OUT_BYTES;
+                    store_row_piece<OUT, PER>(dst, acc, (double)(deg + 1));
+                }
+            } else {
+                if (active) store_row_piece<OUT, PER>(agg + k * agg_stride + (int64_t)piece * OUT_BYTES, acc, (double)deg);
+            }
+            if constexpr (GCN) {
+                if (INDIRECT && self_out && self_row && r < n_self && active)
+                    *(u32x4*)(self_out + (int64_t)r * self_stride + (int64_t)piece * 16) = self_piece;
+            } else {
+                if (INDIRECT && self_row && active) *(u32x4*)(self_out + (int64_t)r * self_stride + (int64_t)piece * 16) = self_piece;
+            }
         }
     }
 }
@@ -236,7 +255,8 @@ static fg_status_t aggregate_common(const char* who, const int32_t* row_start_de
                                     const int64_t* n_rows_dev, int64_t max_rows, const void* h_src, int64_t n_src,
                                     int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
                                     fg_dtype_t out_dtype, const int32_t* src_ids, int32_t n_ids, void* self_out,
-                                    int64_t self_stride, int32_t n_self, void* stream, const fg_feat_side* feat = nullptr) {
+                                    int64_t self_stride, int32_t n_self, void* stream, const fg_feat_side* feat = nullptr,
+                                    void* gcn_pos = nullptr, int64_t gcn_pos_stride = 0) {
     if (max_rows < 0 || n_block_rows < 0 || n_src < 0 || dim <= 0 || nnz < 0 || n_ids < 0)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (max_rows %lld, n_block_rows %d, n_src %lld, dim %d, nnz %lld)", who,
                 (long long)max_rows, n_block_rows, (long long)n_src, dim, (long long)nnz);
@@ -246,7 +266,7 @@ static fg_status_t aggregate_common(const char* who, const int32_t* row_start_de
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
     const int per16 = 16 / isz;
     if (dim % per16) FG_FAIL(FG_ERR_SHAPE, "%s: dim = %d must be a multiple of %d for this type", who, dim, per16);
-    if (src_stride < (int64_t)dim * isz || agg_stride < (int64_t)dim * osz)
+    if (src_stride < (int64_t)dim * isz || agg_stride < (int64_t)dim * osz / (gcn_pos ? 2 : 1))
         FG_FAIL(FG_ERR_SHAPE, "%s: row stride smaller than a row", who);
     if (((uintptr_t)h_src | (uintptr_t)src_stride) & 15)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: the source rows and their stride must be 16-byte aligned", who);
@@ -268,6 +288,20 @@ static fg_status_t aggregate_common(const char* who, const int32_t* row_start_de
         FG_FAIL(FG_ERR_SHAPE, "%s: rows of %lld bytes differ from the %lld-byte rows on the feature side", who, (long long)dim * isz,
                 (long long)feat->row_bytes);
     const fg_feat_side F = with_feat ? *feat : fg_feat_side{};
+    if (gcn_pos) {  // GCN propagation: fp32, halves of the mean to gcn_pos (by position) and agg (list order)
+        if (src_ids)
+            hipLaunchKernelGGL((aggregate_mean_kernel<FG_F32, FG_F32, true, false, true>), dim3((unsigned)blocks), dim3(AGG_THREADS), lds,
+                               st, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,
+                               (const char*)h_src, n_src, src_stride, pieces, (char*)agg, agg_stride, lg, src_ids, n_ids,
+                               (char*)self_out, self_stride, n_self, F, (char*)gcn_pos, gcn_pos_stride);
+        else
+            hipLaunchKernelGGL((aggregate_mean_kernel<FG_F32, FG_F32, false, false, true>), dim3((unsigned)blocks), dim3(AGG_THREADS), lds,
+                               st, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,
+                               (const char*)h_src, n_src, src_stride, pieces, (char*)agg, agg_stride, lg, src_ids, n_ids,
+                               (char*)self_out, self_stride, n_self, F, (char*)gcn_pos, gcn_pos_stride);
+        FG_LAUNCH_CHECK("aggregate_mean_kernel (GCN)");
+        return FG_OK;
+    }
 #define FG_AGG_LAUNCH_F(IN, OUT, IND, FT)                                                                              \
     hipLaunchKernelGGL((aggregate_mean_kernel<IN, OUT, IND, FT>), dim3((unsigned)blocks), dim3(AGG_THREADS), lds, st,   \
                        row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,          \
@@ -371,4 +405,41 @@ extern "C" fg_status_t fg_gather_aggregate_features(const fg_cache_t* cache, con
     return gather_aggregate_checked("fg_gather_aggregate_features", &F, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows,
                                     rows_dev, n_rows_dev, max_rows, src_ids_dev, n_src, table, table_rows, src_stride, dim,
                                     in_dtype, agg, agg_stride, out_dtype, h_self_out, h_self_stride, n_self_rows, stream);
+}
+
+
+// GCN propagation (row-normalised graph convolution with the node itself included), fp32:
+//   m[k, :] = (h_src[r, :] + sum_{e in [row_start[r], row_end[r])} h_src[col[e], :]) / (deg + 1),  r = rows[k]
+// written as the two K-halves fg_linear reads: m[k, 0:dim/2] -> mean_pos[r, :], m[k, dim/2:dim] -> mean_cmp[k, :].
+static fg_status_t aggregate_gcn_checked(const char* who, const int32_t* row_start_dev, const int32_t* row_end_dev,
+                                         const int32_t* col_dev, int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev,
+                                         const int64_t* n_rows_dev, int64_t max_rows, const int32_t* src_ids_dev, int32_t n_ids,
+                                         const void* h_src, int64_t n_src, int64_t src_stride, int32_t dim, void* mean_pos,
+                                         void* mean_cmp, void* h_self_out, int64_t h_self_stride, int32_t n_self_rows, void* stream) {
+    if (dim <= 0 || dim % 8) FG_FAIL(FG_ERR_SHAPE, "%s: dim = %d must be a positive multiple of 8", who, dim);
+    if (max_rows > 0 && (!mean_pos || !mean_cmp)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: mean_pos_dev and mean_cmp_dev are required", who);
+    if (((uintptr_t)mean_pos | (uintptr_t)mean_cmp) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: the outputs must be 16-byte aligned", who);
+    const int64_t half_bytes = (int64_t)dim / 2 * 4;
+    return aggregate_common(who, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows, h_src, n_src,
+                            src_stride, dim, FG_F32, mean_cmp, half_bytes, FG_F32, src_ids_dev, n_ids, h_self_out, h_self_stride,
+                            n_self_rows, stream, nullptr, mean_pos, half_bytes);
+}
+
+extern "C" fg_status_t fg_aggregate_gcn(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev, int64_t nnz,
+                                        int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                                        const float* h_src, int32_t n_src, int64_t src_stride, int32_t dim, float* mean_pos_dev,
+                                        float* mean_cmp_dev, void* stream) {
+    return aggregate_gcn_checked("fg_aggregate_gcn", row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,
+                                 nullptr, 0, h_src, n_src, src_stride, dim, mean_pos_dev, mean_cmp_dev, nullptr, 0, 0, stream);
+}
+
+extern "C" fg_status_t fg_gather_aggregate_gcn(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
+                                               int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                               int64_t max_rows, const int32_t* src_ids_dev, int32_t n_src, const float* table,
+                                               int64_t table_rows, int64_t src_stride, int32_t dim, float* mean_pos_dev,
+                                               float* mean_cmp_dev, void* stream) {
+    if (max_rows > 0 && !src_ids_dev) FG_FAIL(FG_ERR_INVALID_ARG, "fg_gather_aggregate_gcn: src_ids_dev is NULL");
+    return aggregate_gcn_checked("fg_gather_aggregate_gcn", row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev,
+                                 max_rows, src_ids_dev, n_src, table, table_rows, src_stride, dim, mean_pos_dev, mean_cmp_dev, nullptr, 0,
+                                 0, stream);
 }

@@ -58,7 +58,7 @@ class HotPath:
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
-                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0):
+                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage"):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -91,6 +91,12 @@ class HotPath:
             shared = torch.zeros(agg_elems, dtype=TORCH_DTYPE[self.agg_code], device=dev)
             self.AGG_l = [None] + [shared] * L
         self.AGG = self.AGG_l[L]
+        # model "gcn": GCN layers (propagation incl. the node itself, one weight matrix [d_in x d_out]); fp32, forward only.
+        # The mean's first half goes to a by-position buffer, its second half to AGG in list order (what fg_linear reads).
+        self.model = model
+        if model == "gcn":
+            assert self.comp_code == B.FG_F32 and self.feat_code == B.FG_F32 and not backward, "GCN layers: fp32, forward only"
+            self.MEANPOS = torch.zeros(max(n[l] * (dims[l - 1] // 2) for l in range(1, L + 1)), dtype=torch.float32, device=dev)
         self.live = [torch.zeros(n[l], dtype=torch.uint8, device=dev) for l in range(L + 1)]
         self.hit = [torch.zeros(n[l], dtype=torch.uint8, device=dev) for l in range(L + 1)]
         self.hit_pos = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
@@ -237,6 +243,22 @@ class HotPath:
                 B.fg_gather(B.fg_cache_table(self.cache, l), self.capacity[l - 1], out_b, out_b, self.hit_slot[l],
                             self.hit_pos[l], self._cnt(l, 1), bt.n[l], self.H[l], bt.n[l], out_b, B.FG_TABLE_HBM_REUSED, st)
             agg_b = self.dims[l - 1] * esz[self.agg_code]
+            if self.model == "gcn":
+                half = self.dims[l - 1] // 2
+                if fused and l == 1:
+                    tick("gather_aggregate[1]")
+                    B.fg_gather_aggregate_gcn(bt.start[1], bt.end[1], bt.col[1], bt.nnz[1], bt.n[1], self.normal_pos[1],
+                                              self._cnt(1, 2), bt.n[1], bt.ids[0], bt.n[0], self.feat, self.num_nodes, d0b,
+                                              self.dims[0], self.MEANPOS, self.AGG_l[1], st)
+                else:
+                    tick(f"aggregate[{l}]")
+                    B.fg_aggregate_gcn(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),
+                                       bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], self.MEANPOS, self.AGG_l[l], st)
+                tick(f"linear[{l}]")
+                B.fg_linear(self.MEANPOS, bt.n[l], half * 4, B.FG_F32, self.AGG_l[l], half * 4, self.normal_pos[l], self._cnt(l, 2),
+                            bt.n[l], half, self.dims[l], self.W[l], B.FG_F32, self.bias[l], 1 if l < L else 0, self.H[l], bt.n[l],
+                            out_b, out_code, st)
+                continue
             if fused and l == 1:
                 tick("gather_aggregate[1]")
                 args = (bt.start[1], bt.end[1], bt.col[1], bt.nnz[1], bt.n[1], self.normal_pos[1], self._cnt(1, 2), bt.n[1],

@@ -537,7 +537,7 @@ def test_iterations_large_hbm_full_size_with_backward_pass(env):
 
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
-                        backward=False, stabilization=0):
+                        backward=False, stabilization=0, model="sage"):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
@@ -554,7 +554,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
     hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity,
                                              fused_input=fused, one_launch_top_down=one_launch_top_down,
                                              update_all=one_launch_top_down, hot_ids=hot,
-                                             buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward, stabilization=stabilization)
+                                             buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward, stabilization=stabilization, model=model)
     from paper_2301_07482_amd import binding as FGB
     bc = None
     if fs:
@@ -598,7 +598,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                     f"feature-side ranks, iteration {it}"
                 assert found == int((ranks >= 0).sum())
             rec = O.iteration(mb, it, caches, frows, weights, gn, p, dims, w.feat_dtype, w.compute_dtype, feature_side=bc,
-                              labels=labels, update=not backward, stabilization=stabilization)
+                              labels=labels, update=not backward, stabilization=stabilization, model=model)
             served += int(rec["feature_from_buffer"].sum())
             # device cache rows at the slots about to be hit, read before this iteration's update recycles slots
             pre_rows = {l: hp.cache_rows(l, rec["look"][l]["hit_slot"]) for l in range(1, L) if len(rec["look"][l]["hit_pos"])}
@@ -661,9 +661,10 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
             # gathered raw features: bit-exact
             rows_chk = ipos if sample_rows is None or len(ipos) <= sample_rows else np.sort(
                 np.random.default_rng(it).choice(ipos, sample_rows, replace=False))
-            got0 = hp.H[0][torch.as_tensor(rows_chk.astype(np.int64), device="cuda")].cpu().numpy()
-            want0 = rec["H"][0][rows_chk]
-            assert np.array_equal(got0.view(np.uint8), want0.view(np.uint8)), f"gathered features, iteration {it}"
+            if not (fused and model == "gcn"):      # there the own rows enter the mean directly and are never stored
+                got0 = hp.H[0][torch.as_tensor(rows_chk.astype(np.int64), device="cuda")].cpu().numpy()
+                want0 = rec["H"][0][rows_chk]
+                assert np.array_equal(got0.view(np.uint8), want0.view(np.uint8)), f"gathered features, iteration {it}"
             if it % check_numeric_every == 0 or it == iterations - 1:
                 tol = REL_TOL_F32 if w.compute_dtype == "f32" else 2e-2
                 for l in range(1, L + 1):
@@ -677,15 +678,22 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                         # (fused input: the neighbours' rows were never materialised on the device; the oracle's
                         #  bit-identical feature rows take their place)
                         h_prev = rec["H"][0].astype(np.float32) if (fused and l == 1) else G.to_f32(hp.H[l - 1][:len(mb.ids[l - 1])])
-                        agg64 = O.aggregate(mb.start[l], mb.end[l], mb.col[l], npos, h_prev)
+                        agg64 = (O.aggregate_gcn if model == "gcn" else O.aggregate)(mb.start[l], mb.end[l], mb.col[l], npos, h_prev)
                         agg_dtype = "f32" if w.compute_dtype == "f32" else "bf16"
                         agg_want = O.round_to(agg64, agg_dtype).astype(np.float32)
                         agg_got = G.to_f32(hp.AGG[: len(npos) * dims[l - 1]].view(len(npos), dims[l - 1])) if l == L else None
+                        if model == "gcn" and l == L:   # the mean's halves: by position and in list order
+                            hw = dims[l - 1] // 2
+                            agg_got = np.concatenate([G.to_f32(hp.MEANPOS[: bt.n[l] * hw].view(bt.n[l], hw)[idx]),
+                                                      G.to_f32(hp.AGG[: len(npos) * hw].view(len(npos), hw))], axis=1)
                         if agg_got is not None:        # the AGG buffer still holds the last layer's means
                             e_agg = T.rel_err_rows(agg_got, agg_want)
                             assert e_agg <= tol, f"AGG[{l}] iteration {it}: rel err {e_agg:.3e}"
                         h_self = h_prev[npos] if w.compute_dtype == "f32" else O.round_bf16(h_prev[npos])
-                        want_same = O.round_to(O.linear(h_self, agg_want, weights[l][0], weights[l][1], relu=(l < L)), out_dtype)
+                        if model == "gcn":
+                            want_same = O.round_to(O.linear_gcn(agg_want, weights[l][0], weights[l][1], relu=(l < L)), out_dtype)
+                        else:
+                            want_same = O.round_to(O.linear(h_self, agg_want, weights[l][0], weights[l][1], relu=(l < L)), out_dtype)
                         e_same = T.rel_err_rows(got, want_same.astype(np.float32))
                         worst = max(worst, e_same)
                         assert e_same <= tol, f"H[{l}] iteration {it} (same inputs): rel err {e_same:.3e}"
@@ -770,6 +778,53 @@ def test_iterations_tiny_stabilization_period(env):
     assert run_workload_parity(torch, w, 5, stabilization=5)[0] == 0
     assert run_workload_parity(torch, w, 14, stabilization=5)[0] > 0
     assert run_workload_parity(torch, w, 12, stabilization=4, one_launch_top_down=False, fused=True)[0] > 0
+
+
+def test_iterations_gcn_layers(env):
+    """GCN layers (propagation including the node itself, one weight matrix) through the same cached pipeline."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    assert run_workload_parity(torch, w, 12, model="gcn")[0] > 50
+    assert run_workload_parity(torch, w, 8, model="gcn", fused=True)[0] > 0
+    import dataclasses
+    w3 = dataclasses.replace(wl.WORKLOADS["large_hbm"], name="large_hbm/small", num_nodes=200_000, num_edges=4_000_000, batch=128,
+                             train_nodes=20_000, cache_capacity=20_000, t_stale=6)
+    assert run_workload_parity(torch, w3, 8, p_grad=0.7, model="gcn", fused=True)[0] > 0
+
+
+@pytest.mark.parametrize("dim,n,n_src,max_deg,seed", [(128, 700, 3000, 9, 0), (64, 50, 50, 4, 1), (8, 5, 9, 0, 2), (256, 300, 900, 40, 3)])
+def test_aggregate_gcn_matches_oracle(env, dim, n, n_src, max_deg, seed):
+    torch, B = env
+    r = np.random.default_rng(seed)
+    deg = r.integers(0, max_deg + 1, size=n)
+    start = np.concatenate([[0], np.cumsum(deg)[:-1]]).astype(np.int32)
+    end = (start + deg).astype(np.int32)
+    col = np.concatenate([r.choice(n_src, size=k, replace=False) for k in deg] + [np.zeros(0, np.int64)]).astype(np.int32)
+    rows = np.sort(r.permutation(n)[: max(1, n * 3 // 4)]).astype(np.int32)
+    h = r.standard_normal((n_src, dim)).astype(np.float32)
+    want = O.round_to(O.aggregate_gcn(start, end, col, rows, h), "f32")
+    half = dim // 2
+    pos = torch.full((n, half), 9.0, dtype=torch.float32, device="cuda")
+    cmp_ = torch.full((n, half), 9.0, dtype=torch.float32, device="cuda")
+    rows_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
+    rows_dev[:len(rows)] = dev(torch, rows)
+    cnt = dev(torch, np.asarray([len(rows)], dtype=np.int64))
+    tcol = dev(torch, col) if len(col) else torch.zeros(1, dtype=torch.int32, device="cuda")
+    B.fg_aggregate_gcn(dev(torch, start), dev(torch, end), tcol, len(col), n, rows_dev, cnt, n, dev(torch, h), n_src, dim * 4, dim, pos, cmp_)
+    got = np.concatenate([pos.cpu().numpy()[rows], cmp_.cpu().numpy()[:len(rows)]], axis=1)
+    assert T.rel_err_rows(got, want) <= REL_TOL_F32
+    untouched = np.setdiff1d(np.arange(n), rows)
+    assert np.all(pos.cpu().numpy()[untouched] == 9.0) and np.all(cmp_.cpu().numpy()[len(rows):] == 9.0)
+    # the same through the table-indexed variant: ids = a permutation of the table's rows
+    perm = r.permutation(n_src).astype(np.int32)
+    table = np.empty_like(h)
+    table[perm] = h                                  # table[ids[j]] = h[j]
+    pos.fill_(9.0)
+    cmp_.fill_(9.0)
+    B.fg_gather_aggregate_gcn(dev(torch, start), dev(torch, end), tcol, len(col), n, rows_dev, cnt, n, dev(torch, perm), n_src,
+                              dev(torch, table), n_src, dim * 4, dim, pos, cmp_)
+    got = np.concatenate([pos.cpu().numpy()[rows], cmp_.cpu().numpy()[:len(rows)]], axis=1)
+    assert T.rel_err_rows(got, want) <= REL_TOL_F32
 
 
 def test_iterations_tiny_small_ring(env):
