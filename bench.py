@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="take the gradient norms of the cache update from the backward pass (softmax cross-entropy on the seeds' "
                          "synthetic labels, layer backward down to layer 1, row norms) instead of the synthetic norms")
+    ap.add_argument("--model", default="sage", choices=["sage", "gcn"],
+                    help="layer type: GraphSAGE-mean (the headline) or GCN (propagation incl. the node itself, one weight matrix)")
     ap.add_argument("--weight-grads", action="store_true",
                     help="with --backward: also form dL/dW and dL/db of every layer (fg_layer_backward_weights)")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -108,7 +110,7 @@ def main():
         row = w.feat_dim * (4 if w.feat_dtype == "f32" else 2)
         buffer_bytes = -(-(G.rings_bytes(w) + len(hot) * row) // 256) * 256
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + extra + 32,
-                                       hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads)
+                                       hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads, model=args.model)
     make_batch = (lambda mb, gn, labels: DeviceBatch(mb, None, labels=labels)) if args.backward else \
         (lambda mb, gn, labels: DeviceBatch(mb, gn))
     if args.per_layer_update:
@@ -218,7 +220,8 @@ def main():
         # written. The edges under normal rows are what is left in the pruned blocks (rows that are not normal have
         # end = start).
         edges = [float((batches[it].end[1] - batches[it].start[1]).sum().item()) for it in roof_it]
-        gather_bytes = float(np.mean([e * (8 + feat_row) + c[1][2] * (12 + agg_row + 4 + 2 * feat_row)
+        own_row = (4 + feat_row) if args.model == "gcn" else (4 + 2 * feat_row)   # GCN: the own row enters the mean, no copy
+        gather_bytes = float(np.mean([e * (8 + feat_row) + c[1][2] * (12 + agg_row + own_row)
                                       for e, c in zip(edges, counts)]))
         n_input = float(np.mean(edges)) + float(np.mean([c[1][2] for c in counts]))   # table rows read (edges + own rows)
         dom_kernel = "aggregate_mean_kernel<.., true> (fg_gather_aggregate: loader fused with the layer-1 mean)"
@@ -248,8 +251,9 @@ def main():
         d_in, d_out = hp.dims[l - 1], hp.dims[l]
         e_in = 4 if (l == 1 and w.feat_dtype == "f32") or w.compute_dtype == "f32" else 2
         nn = float(np.mean([c[l][2] for c in counts]))
-        lin_flops[l] = 2.0 * nn * 2 * d_in * d_out
-        lin_bytes[l] = nn * (2 * d_in * e_in + d_out * 4) + 2 * d_in * d_out * 4
+        k_l = d_in if args.model == "gcn" else 2 * d_in       # contraction length of the dense update
+        lin_flops[l] = 2.0 * nn * k_l * d_out
+        lin_bytes[l] = nn * (k_l * e_in + d_out * 4) + k_l * d_out * 4
     dom = max(call_avg_ms, key=call_avg_ms.get)
     gather_ms = timed_ms[LOADER]
     if w.feat_location == "host":
@@ -273,7 +277,7 @@ def main():
         linear_roof = dict(bound="mfma", kernel="linear_bf16_kernel (fg_linear, layer 1, bf16 MFMA, fp32 accumulation)",
                            achieved=lin_tf, peak=BF16_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_tf / BF16_MFMA_PEAK_TFLOPS,
                            traffic=None, flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms)
-    elif hp.dims[0] % 32 == 0:
+    elif (hp.dims[0] // 2 if args.model == "gcn" else hp.dims[0]) % 32 == 0:
         linear_roof = dict(bound="mfma", kernel="linear_f32x3_panel_kernel<2> (fg_linear, layer 1: fp32 products from 3-way bf16 "
                                                 "splits on the bf16 matrix cores)",
                            achieved=lin_tf, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_tf / FP32_MFMA_PEAK_TFLOPS,
@@ -284,7 +288,7 @@ def main():
         linear_roof = dict(bound="mfma", kernel="linear_f32_kernel (fg_linear, layer 1, fp32 MFMA)",
                            achieved=lin_tf, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_tf / FP32_MFMA_PEAK_TFLOPS,
                            traffic=None, flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms)
-    if w.name == "large_hbm" and not (args.no_cache or args.no_fuse):   # the configuration the counter runs were made on
+    if w.name == "large_hbm" and not (args.no_cache or args.no_fuse or args.model != "sage" or args.feature_rows):   # the configuration the counter runs were made on
         loader_roof["traffic"] = profiled_traffic("aggregate_mean_kernel<0, 0, true>")
         linear_roof["traffic"] = profiled_traffic("linear_f32x3_panel_kernel<2>")
     # `roofline` is the kernel with the longest launches in the timed region; the other one follows as `roofline_2`
@@ -338,7 +342,7 @@ def main():
                    "t_stale": w.t_stale, "p_grad": w.p_grad, "cache": not args.no_cache,
                    "fused_loader": not args.no_fuse, "feature_rows": int(args.feature_rows),
                    "gradient_norms": "backward pass" if args.backward else "synthetic input",
-                   "weight_gradients": bool(args.weight_grads and args.backward), "seed": w.seed},
+                   "weight_gradients": bool(args.weight_grads and args.backward), "model": args.model, "seed": w.seed},
         "roofline": roofline,
         "roofline_2": roofline_2,
         "cpu_baseline": cpu_baseline,
