@@ -289,7 +289,7 @@ def main():
                            achieved=lin_tf, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_tf / FP32_MFMA_PEAK_TFLOPS,
                            traffic=None, flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms)
     if w.name == "large_hbm" and not (args.no_cache or args.no_fuse or args.model != "sage" or args.feature_rows):   # the configuration the counter runs were made on
-        loader_roof["traffic"] = profiled_traffic("aggregate_mean_kernel<0, 0, true>")
+        loader_roof["traffic"] = profiled_traffic("aggregate_mean_kernel<0, 0, true, false")
         linear_roof["traffic"] = profiled_traffic("linear_f32x3_panel_kernel<2>")
     # `roofline` is the kernel with the longest launches in the timed region; the other one follows as `roofline_2`
     roofline, roofline_2 = (loader_roof, linear_roof) if gather_ms >= lin1_ms else (linear_roof, loader_roof)
