@@ -100,7 +100,7 @@ def main():
     import numpy as np
     import torch
     from paper_2301_07482_amd.pipeline import DeviceBatch
-    from tests import gpu_common as G
+    from paper_2301_07482_amd import pipeline as G
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     t0 = time.time()
@@ -380,7 +380,7 @@ def time_oracle(w, sampled, weights, iterations=10):
     import numpy as np
     from fg_inputs import features, workload as wl
     from oracle import freshgnn_oracle as O
-    from tests import gpu_common as G
+    from tests import gpu_common as G      # builds the oracle's caches: used by this leg only
     try:
         from threadpoolctl import threadpool_limits
         limiter = threadpool_limits(limits=1)
