@@ -298,23 +298,26 @@ extern "C" fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride,
 // dz[k, :] = dh[rows[k], :] * (h[rows[k], :] > 0). A contraction over the rows (K = tens of thousands) with a small
 // result (2*d_in x d_out), so K is split over the workgroups: workgroup `chunk` multiplies its rows on the fp32
 // matrix cores and leaves a partial result, a second launch adds the partials up in fp64.
-// Both operands are read straight from global memory in the layout v_mfma_f32_32x32x2_f32 wants: for the two rows
-// k, k+1 a lane holds X[k + lane/32][m0 + lane%32] and dz[k + lane/32][n0 + lane%32], 128 contiguous bytes per row.
-// A workgroup of 8 wavefronts (4 along M x 2 along N) owns a 256 x 256 tile of the result, a wavefront 64 x 128 of it
-// (2 x 4 blocks of 32 x 32: 6 operand loads for 8 matrix instructions per pair of rows).
+// Both operands are read straight from global memory in the layout v_mfma_f32_32x32x2_f32 wants (for the two rows k, k+1 a
+// lane supplies one element of row k + lane/32 per block), with no transposition and no LDS.
+// A workgroup of 8 wavefronts (4 along M x 2 along N) owns a 256 x 256 tile of the result, a wavefront 64 x 128 of it as
+// 2 x 4 blocks of 32 x 32. The blocks interleave: a lane's elements for the two row blocks are adjacent columns of X and
+// those for the four column blocks adjacent columns of dz, so a pair of rows costs a lane one 8-byte and two 16-byte loads
+// (dh and h) for 8 matrix instructions.
 namespace {
 
 constexpr int WG_THREADS = 512;
 constexpr int WG_TILE = 256;
-constexpr int WG_PAIRS = 4;  // pairs of rows whose loads are issued together
+constexpr int WG_PAIRS = 3;  // pairs of rows whose loads are issued together
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 
 __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const char* __restrict__ dh, int64_t dh_stride, const char* __restrict__ h, int64_t h_stride, int n,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
-    int rows_per_chunk, float* __restrict__ part_w, float* __restrict__ part_b) {
+    float* __restrict__ part_w, float* __restrict__ part_b) {
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
     if (n_rows > max_rows) n_rows = max_rows;
     const int M = 2 * d_in, N = d_out;
@@ -324,28 +327,24 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
     const int wm = wave & 3, wn = wave >> 2;
     const int m_base = blockIdx.y * WG_TILE + wm * 64;
     const int n_base = blockIdx.z * WG_TILE + wn * 128;
-    const int64_t k_begin = (int64_t)chunk * rows_per_chunk;
-    int64_t k_end = k_begin + rows_per_chunk;
+    // the rows there are, split evenly over the chunks of the launch (whole batches per chunk)
+    const int64_t per = (n_rows + gridDim.x - 1) / gridDim.x;
+    const int64_t per_b = (per + 2 * WG_PAIRS - 1) / (2 * WG_PAIRS) * (2 * WG_PAIRS);
+    const int64_t k_begin = (int64_t)chunk * per_b < n_rows ? (int64_t)chunk * per_b : n_rows;
+    int64_t k_end = k_begin + per_b;
     if (k_end > n_rows) k_end = n_rows;
 
-    // this lane's columns: where they are read from and whether they exist
-    int a_col[2];
-    bool a_self[2], a_ok[2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-        const int m = m_base + 32 * i + l32;
-        a_ok[i] = m < M;
-        a_self[i] = m < d_in;
-        a_col[i] = a_ok[i] ? (a_self[i] ? m : m - d_in) : 0;
-    }
-    int b_col[4];
-    bool b_ok[4];
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int c = n_base + 32 * j + l32;
-        b_ok[j] = c < N;
-        b_col[j] = b_ok[j] ? c : 0;
-    }
+    // This lane's columns. A wavefront's 64 rows of the result are split over its two row blocks by parity and its 128
+    // columns over its four column blocks modulo 4, so that a lane's operands for all blocks are adjacent in memory:
+    // X[k][m_pair], X[k][m_pair + 1] (one 8-byte load) and dz[k][n_quad .. n_quad + 3] (16-byte loads).
+    // Row l of result block i is then row m_base + 2*l + i, column l of result block j is column n_base + 4*l + j.
+    const int m_pair = m_base + 2 * l32;
+    const bool a_ok = m_pair < M;              // M is even: both columns exist or neither
+    const bool a_self = m_pair < d_in;         // d_in is even: a pair never straddles the two panels
+    const int a_col = a_ok ? (a_self ? m_pair : m_pair - d_in) : 0;
+    const int n_quad = n_base + 4 * l32;
+    const bool b_ok = n_quad < N;              // N is a multiple of 4
+    const int b_col = b_ok ? n_quad : 0;
     f32x16 acc[2][4];
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -360,14 +359,18 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
         const int64_t ks = kk < k_end ? kk : k_begin;
         return rows ? rows[ks] : (int32_t)ks;
     };
+    // One batch = WG_PAIRS pairs of rows: 11 loads per pair and lane, then 8 matrix instructions per pair. Two batches are
+    // kept in registers: while one is multiplied the loads of the next are in flight. The row positions are fetched one
+    // batch further ahead so that the row loads do not wait for them.
+    struct Batch {
+        f32x2 a[WG_PAIRS];
+        f32x4 g[WG_PAIRS], o[WG_PAIRS];
+        bool ok[WG_PAIRS];
+    };
     int32_t r_next[WG_PAIRS];
 #pragma unroll
     for (int p = 0; p < WG_PAIRS; ++p) r_next[p] = k_begin < k_end ? row_of(k_begin + 2 * p + kh) : 0;
-    for (int64_t k0 = k_begin; k0 < k_end; k0 += 2 * WG_PAIRS) {
-        float a[WG_PAIRS][2], g[WG_PAIRS][4], o[WG_PAIRS][4];
-        bool ok[WG_PAIRS];
-        // all loads of the batch first (from a safe row where this lane has none), masks afterwards; the positions were
-        // fetched a batch ahead so that the row loads do not wait for them
+    auto load_batch = [&](int64_t k0, Batch& B) {  // all loads from a safe row where this lane has none; masks come later
 #pragma unroll
         for (int p = 0; p < WG_PAIRS; ++p) {
             const int64_t kk = k0 + 2 * p + kh;
@@ -375,29 +378,27 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
             const int64_t ks = in ? kk : k_begin;
             const int32_t r = r_next[p];
             r_next[p] = row_of(kk + 2 * WG_PAIRS);
-            ok[p] = in && r >= 0 && r < n && r < n_src;
-            const int64_t rs = ok[p] ? r : 0;
+            B.ok[p] = in && r >= 0 && r < n && r < n_src;
+            const int64_t rs = B.ok[p] ? r : 0;
             const float* xs = (const float*)(h_src + rs * src_stride);
             const float* xa = (const float*)(agg + ks * agg_stride);
-#pragma unroll
-            for (int i = 0; i < 2; ++i) a[p][i] = a_self[i] ? xs[a_col[i]] : xa[a_col[i]];
+            B.a[p] = *(const f32x2*)((a_self ? xs : xa) + a_col);
             const float* gr = (const float*)(dh + rs * dh_stride);
             const float* hr = h ? (const float*)(h + rs * h_stride) : gr;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                g[p][j] = gr[b_col[j]];
-                o[p][j] = hr[b_col[j]];
-            }
+            B.g[p] = *(const f32x4*)(gr + b_col);
+            B.o[p] = *(const f32x4*)(hr + b_col);
         }
+    };
+    auto multiply_batch = [&](Batch& B) {
 #pragma unroll
         for (int p = 0; p < WG_PAIRS; ++p) {
 #pragma unroll
-            for (int i = 0; i < 2; ++i) a[p][i] = (ok[p] && a_ok[i]) ? a[p][i] : 0.f;
+            for (int i = 0; i < 2; ++i) B.a[p][i] = (B.ok[p] && a_ok) ? B.a[p][i] : 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const bool pass = ok[p] && b_ok[j] && (h ? o[p][j] > 0.f : true);
-                g[p][j] = pass ? g[p][j] : 0.f;
-                colsum[j] += g[p][j];
+                const bool pass = B.ok[p] && b_ok && (h ? B.o[p][j] > 0.f : true);
+                B.g[p][j] = pass ? B.g[p][j] : 0.f;
+                colsum[j] += B.g[p][j];
             }
         }
 #pragma unroll
@@ -405,26 +406,36 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[p][i], g[p][j], acc[i][j], 0, 0, 0);
+                for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(B.a[p][i], B.g[p][j], acc[i][j], 0, 0, 0);
+    };
+    constexpr int64_t STEP = 2 * WG_PAIRS;
+    Batch X, Y;
+    if (k_begin < k_end) load_batch(k_begin, X);
+    for (int64_t k0 = k_begin; k0 < k_end; k0 += 2 * STEP) {
+        const bool second = k0 + STEP < k_end;            // uniform over the workgroup
+        if (second) load_batch(k0 + STEP, Y);
+        __builtin_amdgcn_sched_barrier(0);                // the next batch's loads are issued before this batch's arithmetic
+        multiply_batch(X);
+        if (k0 + 2 * STEP < k_end) load_batch(k0 + 2 * STEP, X);
+        __builtin_amdgcn_sched_barrier(0);
+        if (second) multiply_batch(Y);
     }
     // partial result of this chunk (zeros if the chunk lies beyond the rows there are)
     float* pw = part_w + (int64_t)chunk * M * N;
+    // a lane's elements of the four column blocks are four adjacent columns of one row: one 16-byte store
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int c = n_base + 32 * j + l32;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int m = m_base + 32 * i + 8 * (e >> 2) + 4 * kh + (e & 3);  // accumulator element e of this lane
-                if (m < M && c < N) pw[(int64_t)m * N + c] = acc[i][j][e];
-            }
+        for (int e = 0; e < 16; ++e) {
+            const int m = m_base + 2 * (8 * (e >> 2) + 4 * kh + (e & 3)) + i;  // accumulator element e is block row 8*(e/4) + 4*kh + e%4
+            const f32x4 v = {acc[i][0][e], acc[i][1][e], acc[i][2][e], acc[i][3][e]};
+            if (m < M && b_ok) *(f32x4*)(pw + (int64_t)m * N + n_quad) = v;
         }
     if (blockIdx.y == 0 && wm == 0) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const float s = colsum[j] + __shfl_xor(colsum[j], 32, 64);
-            const int c = n_base + 32 * j + l32;
+            const int c = n_quad + j;
             if (kh == 0 && c < N) part_b[(int64_t)chunk * N + c] = s;
         }
     }
@@ -517,9 +528,10 @@ extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t
     if (max_rows > 0 && n > 0 && n_src > 0 && (!h_src_dev || !agg_dev || !dh_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
     if (src_stride < (int64_t)d_in * 4 || agg_stride < (int64_t)d_in * 4 || dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * 4))
         FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
-    if (((uintptr_t)h_src_dev | (uintptr_t)agg_dev | (uintptr_t)dh_dev | (uintptr_t)h_dev | (uintptr_t)dw_dev | (uintptr_t)db_dev |
-         (uintptr_t)src_stride | (uintptr_t)agg_stride | (uintptr_t)dh_stride | (uintptr_t)h_stride) & 3)
-        FG_FAIL(FG_ERR_INVALID_ARG, "%s: pointers and strides must be 4-byte aligned", who);
+    if (d_in % 4) FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d must be a multiple of 4", who, d_in);
+    if (((uintptr_t)h_src_dev | (uintptr_t)agg_dev | (uintptr_t)dh_dev | (uintptr_t)h_dev | (uintptr_t)src_stride | (uintptr_t)agg_stride |
+         (uintptr_t)dh_stride | (uintptr_t)h_stride) & 15)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_src, agg, dh, h and their strides must be 16-byte aligned", who);
     const WgPlan P = wg_plan(max_rows, d_in, d_out);
     if (!ws_dev || ws_bytes < P.total) FG_FAIL(FG_ERR_SHAPE, "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes, P.total);
     if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: the workspace must be 16-byte aligned", who);
@@ -531,7 +543,7 @@ extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t
     const int64_t rows_bound = (n > 0 && n_src > 0) ? max_rows : 0;
     hipLaunchKernelGGL(weight_grad_partial_kernel, dim3((unsigned)P.n_chunks, (unsigned)P.tiles_m, (unsigned)P.tiles_n), dim3(WG_THREADS), 0, st,
                        (const char*)h_src_dev, n_src, src_stride, (const char*)agg_dev, agg_stride, (const char*)dh_dev, dh_stride,
-                       (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, rows_bound, d_in, d_out, P.rows_per_chunk, part_w, part_b);
+                       (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, rows_bound, d_in, d_out, part_w, part_b);
     FG_LAUNCH_CHECK("weight_grad_partial_kernel");
     const int64_t mn = (int64_t)2 * d_in * d_out;
     const int w_blocks = (int)fg_ceil_div(mn, 128), b_blocks = (int)fg_ceil_div(d_out, 128);
