@@ -983,7 +983,9 @@ def test_iterations_large_host_resident_separate_gather(env):
 @pytest.mark.parametrize("src,d_in,d_out,n_rows,max_rows,relu,out", [("f16", 768, 1024, 700, 900, True, "bf16"),
                                                                      ("bf16", 1024, 1024, 300, 300, False, "f32"),
                                                                      ("bf16", 64, 72, 129, 200, True, "bf16"),
-                                                                     ("f16", 8, 8, 5, 130, False, "f32")])
+                                                                     ("f16", 8, 8, 5, 130, False, "f32"),
+                                                                     ("bf16", 64, 1024, 3900, 4096, True, "bf16"),     # 64 x 128 tiles
+                                                                     ("f16", 128, 512, 17000, 17000, False, "f32")])   # 128 x 128 tiles
 def test_linear_bf16_matches_oracle(env, src, d_in, d_out, n_rows, max_rows, relu, out):
     torch, B = env
     r = np.random.default_rng(d_in + d_out)
