@@ -301,21 +301,36 @@ def main():
     # bandwidth figure: algorithmic bytes of those steps over the time of their calls in the breakdown pass.
     stats = [stats_log[it % hp.ring] for it in roof_it]
     e_comp = 4 if w.compute_dtype == "f32" else 2
-    def layer_bytes(it, c, st):
-        total = 0.0
+    def call_bytes(it, c, st):
+        """Algorithmic bytes of every call of one step except the loader and the dense updates, keyed like per_call_ms."""
+        out = {}
+        add = lambda k, v: out.__setitem__(k, out.get(k, 0.0) + v)
         for l in range(1, L + 1):
             n_l, n_hit, n_norm = batches[it].n[l], float(c[l][1]), float(c[l][2])
             edges_l = float((batches[it].end[l] - batches[it].start[l]).sum().item())      # left under normal rows
-            total += n_l * (4 + 1 + 4 + 8) + edges_l * (4 + 1) + 4 * (2 * n_hit + n_norm)     # lookup, prune, lists
+            add("top_down", n_l * (4 + 1 + 4 + 8) + edges_l * (4 + 1) + 4 * (2 * n_hit + n_norm))   # lookup, prune, lists
             if l >= 2 or args.no_fuse:
                 d_prev = hp.dims[l - 1] * (esz[w.feat_dtype] if l == 1 else e_comp)
-                total += edges_l * (4 + d_prev) + n_norm * hp.dims[l - 1] * e_comp           # aggregation
+                add(f"aggregate[{l}]", edges_l * (4 + d_prev) + n_norm * hp.dims[l - 1] * e_comp)
             if l < L:
                 row = hp.dims[l] * e_comp
-                total += n_hit * (8 + 2 * row)                                                # cache fetch
-                total += 2 * n_l * 6 + float(st[l][0]) * (2 * row + 12) + float(st[l][1]) * 4  # update
-        return total
-    path_bytes = gather_bytes + float(np.mean([layer_bytes(it, c, st) for it, c, st in zip(roof_it, counts, stats)]))
+                add("cache_fetch_all", n_hit * (8 + 2 * row))
+                add("cache_update_all", 2 * n_l * 6 + float(st[l][0]) * (2 * row + 12) + float(st[l][1]) * 4)
+        return out
+    per_step_bytes = [call_bytes(it, c, st) for it, c, st in zip(roof_it, counts, stats)]
+    call_avg_bytes = {k: float(np.mean([d.get(k, 0.0) for d in per_step_bytes])) for k in per_step_bytes[0]} if per_step_bytes else {}
+    path_bytes = gather_bytes + sum(call_avg_bytes.values())
+    call_avg_bytes[LOADER] = gather_bytes
+    # every call: time in the breakdown pass, algorithmic bytes (or flops) and the rate they give
+    per_call = {}
+    for k, ms in sorted(call_avg_ms.items()):
+        e = {"ms": round(ms, 5)}
+        if k in call_avg_bytes and ms > 0:
+            e.update(bytes=call_avg_bytes[k], GBps=round(call_avg_bytes[k] / (ms * 1e-3) / 1e9, 1))
+        elif k.startswith("linear[") and ms > 0:
+            f = lin_flops[int(k[7:-1])]
+            e.update(flops=f, TFLOPs=round(f / (ms * 1e-3) / 1e12, 1))
+        per_call[k] = e
     path_ms = sum(v for k, v in call_avg_ms.items() if not k.startswith(("linear", "loss_grad", "layer_backward", "row_norms", "weight_grads")))
     hbm_path = dict(bytes_per_step=path_bytes, ms_per_step=path_ms, achieved=path_bytes / (path_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=path_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
@@ -347,6 +362,7 @@ def main():
         "roofline_2": roofline_2,
         "cpu_baseline": cpu_baseline,
         "per_call_ms": {k: round(v, 5) for k, v in sorted(call_avg_ms.items())},
+        "per_call": per_call,
         "dominant_call": dom,
         "hbm_path": hbm_path,
         "per_step": {"table_rows_read": n_input - from_buffer, "rows_from_feature_side": from_buffer,
