@@ -69,6 +69,8 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="take the gradient norms of the cache update from the backward pass (softmax cross-entropy on the seeds' "
                          "synthetic labels, layer backward down to layer 1, row norms) instead of the synthetic norms")
+    ap.add_argument("--one-launch-seed-layer", action="store_true",
+                    help="run the seed layer through fg_aggregate_linear (one launch) instead of fg_aggregate + fg_linear")
     ap.add_argument("--model", default="sage", choices=["sage", "gcn"],
                     help="layer type: GraphSAGE-mean (the headline) or GCN (propagation incl. the node itself, one weight matrix)")
     ap.add_argument("--weight-grads", action="store_true",
@@ -111,6 +113,8 @@ def main():
         buffer_bytes = -(-(G.rings_bytes(w) + len(hot) * row) // 256) * 256
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + extra + 32,
                                        hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads, model=args.model)
+    if args.one_launch_seed_layer:
+        hp.fuse_small_layers = hp.model == "sage" and not hp.weight_grads
     make_batch = (lambda mb, gn, labels: DeviceBatch(mb, None, labels=labels)) if args.backward else \
         (lambda mb, gn, labels: DeviceBatch(mb, gn))
     if args.per_layer_update:
@@ -319,6 +323,10 @@ def main():
         return out
     per_step_bytes = [call_bytes(it, c, st) for it, c, st in zip(roof_it, counts, stats)]
     call_avg_bytes = {k: float(np.mean([d.get(k, 0.0) for d in per_step_bytes])) for k in per_step_bytes[0]} if per_step_bytes else {}
+    # a small layer that runs aggregation and dense update as one launch counts as a dense call (its means never reach memory)
+    one_launch = [int(k[len("aggregate_linear["):-1]) for k in call_avg_ms if k.startswith("aggregate_linear[")]
+    for l in one_launch:
+        call_avg_bytes.pop(f"aggregate[{l}]", None)
     path_bytes = gather_bytes + sum(call_avg_bytes.values())
     call_avg_bytes[LOADER] = gather_bytes
     # every call: time in the breakdown pass, algorithmic bytes (or flops) and the rate they give
@@ -327,14 +335,14 @@ def main():
         e = {"ms": round(ms, 5)}
         if k in call_avg_bytes and ms > 0:
             e.update(bytes=call_avg_bytes[k], GBps=round(call_avg_bytes[k] / (ms * 1e-3) / 1e9, 1))
-        elif k.startswith("linear[") and ms > 0:
-            f = lin_flops[int(k[7:-1])]
+        elif k.startswith(("linear[", "aggregate_linear[")) and ms > 0:
+            f = lin_flops[int(k[k.index("[") + 1:-1])]
             e.update(flops=f, TFLOPs=round(f / (ms * 1e-3) / 1e12, 1))
         per_call[k] = e
-    path_ms = sum(v for k, v in call_avg_ms.items() if not k.startswith(("linear", "loss_grad", "layer_backward", "row_norms", "weight_grads")))
+    path_ms = sum(v for k, v in call_avg_ms.items() if not k.startswith(("linear", "aggregate_linear", "loss_grad", "layer_backward", "row_norms", "weight_grads")))
     hbm_path = dict(bytes_per_step=path_bytes, ms_per_step=path_ms, achieved=path_bytes / (path_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=path_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                    note="all calls except fg_linear; times from the breakdown pass (every call bracketed)")
+                    note="all calls except the dense updates (fg_linear, fg_aggregate_linear); times from the breakdown pass (every call bracketed)")
     # table rows the loader would read with the caches empty: every edge of block 1 plus every layer-1 node's own row
     if args.no_fuse:
         rows_no_cache = n0_all

@@ -344,6 +344,20 @@ fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_stride, fg_d
                       void* h_out, int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, void* stream);
 
 /*
+ * fg_aggregate followed by fg_linear for one fp32 GraphSAGE-mean layer (Eq. 1 in one call; same results as the two
+ * calls). A layer with few rows, ceil(max_rows/32) * ceil(d_out/32) <= 768 with d_in a multiple of 32 and at most 256
+ * (in practice the seed layer), runs as ONE launch that forms the neighbour means while it loads its operands and never
+ * writes them; any other shape runs the two calls with the means in agg_ws_dev ([max_rows x d_in] floats, agg_stride
+ * bytes between rows, 16-byte aligned; may be NULL when the one-launch form applies).
+ * Arguments as for fg_aggregate (block, rows, h_src = H(l-1) by position) and fg_linear (W, bias, relu, h_out).
+ */
+fg_status_t fg_aggregate_linear(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev, int64_t nnz,
+                                int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                                const float* h_src, int32_t n_src, int64_t src_stride, int32_t d_in, int32_t d_out,
+                                const float* W, const float* bias, int32_t relu, float* agg_ws_dev, int64_t agg_stride,
+                                float* h_out, int32_t n_out, int64_t out_stride, void* stream);
+
+/*
  * Update(C^(l), V_normal^(l), V^(l), h^(l), i, t_stale, p_grad) of Algorithm 1 (Sections 4.1.1, 4.1.2, 4.2).
  * Over the live nodes of the layer (m of them): k = floor(p_grad * m), tau = the gradient norm of rank k
  * (ascending, 0-based; every norm is below tau if k >= m, none if k == 0). Live hits whose norm is not below

@@ -52,6 +52,8 @@ SIGNATURES = {
     "fg_aggregate_gcn": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _p, _p, _p]),
     "fg_gather_aggregate_gcn": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _p, _i64, _i64, _i32, _p, _p, _p]),
     "fg_linear": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _p, _i64, _i32, _i32, _p, _i32, _p, _i32, _p, _i32, _i64, _i32, _p]),
+    "fg_aggregate_linear": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _i32, _p, _p, _i32, _p, _i64, _p, _i32,
+                                   _i64, _p]),
     "fg_cache_update": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _f, _p, _i64, _p, _p, _sz, _p]),
     "fg_softmax_xent_grad": (_i32, [_p, _i64, _p, _i32, _i32, _p, _i64, _p]),
     "fg_row_norms": (_i32, [_p, _i64, _i32, _i32, _p, _p]),
@@ -273,6 +275,18 @@ def fg_linear(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows, n_rows,
               h_out, n_out, out_stride, out_dtype, stream=None):
     _check(_lib.fg_linear(ptr(h_src), n_src, src_stride, in_dtype, ptr(agg), agg_stride, ptr(rows), ptr(n_rows), max_rows,
                           d_in, d_out, ptr(W), w_dtype, ptr(bias), relu, ptr(h_out), n_out, out_stride, out_dtype, stream))
+
+
+def fg_aggregate_linear(row_start, row_end, col, nnz, n_block_rows, rows, n_rows, max_rows, h_src, n_src, src_stride, d_in, d_out, W,
+                        bias, relu, agg_ws, agg_stride, h_out, n_out, out_stride, stream=None):
+    _check(_lib.fg_aggregate_linear(ptr(row_start), ptr(row_end), ptr(col), nnz, n_block_rows, ptr(rows), ptr(n_rows), max_rows,
+                                    ptr(h_src), n_src, src_stride, d_in, d_out, ptr(W), ptr(bias), relu, ptr(agg_ws), agg_stride,
+                                    ptr(h_out), n_out, out_stride, stream))
+
+
+def one_launch_layer(max_rows, d_in, d_out):
+    """Whether fg_aggregate_linear runs a layer of this shape as one launch (the rule stated in freshgnn.h)."""
+    return d_in % 32 == 0 and d_in <= 256 and -(-max_rows // 32) * -(-d_out // 32) <= 768
 
 
 def fg_cache_update(cache, layer, it, ids, n, live, hit, gnorm, p_grad, h, h_stride, stats, ws, ws_bytes, stream=None):

@@ -520,11 +520,15 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
 // copy of a whole panel for a single task.
 constexpr int SK_PART_BYTES = PL_WAVES * 16 * 64 * 8;  // partial sums: [wavefront][accumulator element][lane] doubles
 
+// FUSE: the neighbour means are not read from `agg` but formed here from the block (fg_aggregate's arithmetic: fp64 sum
+// in neighbour order, one division, one rounding to fp32), so a layer with few rows needs one launch instead of two.
+template <bool FUSE>
 __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32_splitk_kernel(
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
-    int64_t out_stride, int n_panels) {
+    int64_t out_stride, int n_panels, const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end,
+    const int32_t* __restrict__ col, int64_t nnz, int n_block_rows) {
     extern __shared__ __attribute__((aligned(16))) float panel[];  // [K][32], later the partial sums
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
     if (n_rows > max_rows) n_rows = max_rows;
@@ -538,9 +542,13 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32_splitk_kernel(
     const int t = threadIdx.x;
     const int lane = t & 63, wave = t >> 6;
     const int l32 = lane & 31, half = lane >> 5;
+    // The K chunks of this wavefront: chunk_of(0 .. cnt-1). Contiguous ranges, or with FUSE every eighth chunk, so that
+    // each wavefront gets chunks of the self half and of the mean half (the means cost several loads per value).
     const int per = (nk + PL_WAVES - 1) / PL_WAVES;
     const int c0 = wave * per < nk ? wave * per : nk;
     const int c1 = c0 + per < nk ? c0 + per : nk;
+    const int cnt = FUSE ? (nk > wave ? (nk - wave + PL_WAVES - 1) / PL_WAVES : 0) : c1 - c0;
+    auto chunk_of = [&](int i) { return FUSE ? wave + i * PL_WAVES : c0 + i; };
 
     // destination / source row of this lane (-1: past the end or out of range; such a lane reads row 0)
     const int64_t g = rb * 32 + l32;
@@ -552,20 +560,59 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32_splitk_kernel(
     const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
     const float* a_agg = (const float*)(agg + (r >= 0 ? g * agg_stride : 0)) + 16 * half;
     auto a_ptr = [&](int s) { return s < nk_self ? a_self + s * KC : a_agg + (s - nk_self) * KC; };
+    // this lane's row of the block (FUSE): its sampled neighbours are col[e0 .. e1)
+    int32_t e0 = 0, e1 = 0;
+    if (FUSE && r >= 0 && r < n_block_rows) {
+        e0 = row_start[r];
+        e1 = row_end[r];
+        if (e0 < 0 || e1 < e0 || (int64_t)e1 > nnz) e0 = e1 = 0;
+    }
+    // the 16 values of chunk s this lane feeds to the matrix instructions
+    constexpr int NBF = 5;  // neighbours whose pieces are in flight together (the seed layer's fan-out)
+    auto load_chunk = [&](int s, f32x4* a) {
+        if (!FUSE || s < nk_self) {
+            const float* p = a_ptr(s);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) a[q] = *(const f32x4*)(p + 4 * q);
+            return;
+        }
+        double acc[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = 0.0;
+        const int64_t off = ((int64_t)(s - nk_self) * KC + 16 * half) * 4;
+        for (int e = e0; e < e1; e += NBF) {
+            f32x4 v[NBF][4];
+            bool ok[NBF];
+            int32_t cc[NBF];
+#pragma unroll
+            for (int u = 0; u < NBF; ++u) cc[u] = col[e + u < e1 ? e + u : e0];  // all positions first, then all rows
+#pragma unroll
+            for (int u = 0; u < NBF; ++u) {
+                const int32_t c = e + u < e1 ? cc[u] : -1;
+                ok[u] = c >= 0 && c < n_src;
+                const float* p = (const float*)(h_src + (ok[u] ? (int64_t)c * src_stride : 0) + off);
+#pragma unroll
+                for (int q = 0; q < 4; ++q) v[u][q] = *(const f32x4*)(p + 4 * q);
+            }
+#pragma unroll
+            for (int u = 0; u < NBF; ++u)
+                if (ok[u])
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[i] += (double)v[u][i >> 2][i & 3];
+        }
+        const double deg = (double)(e1 - e0);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a[i >> 2][i & 3] = deg > 0.0 ? (float)(acc[i] / deg) : 0.f;
+    };
 
     // the first round of A loads goes out before anything else waits on memory
     f32x4 a0[4], a1[4];
-    {
-        const float* p0 = a_ptr(c0 < nk ? c0 : 0);
-        const float* p1 = a_ptr(c0 + 1 < c1 ? c0 + 1 : (c0 < nk ? c0 : 0));
-#pragma unroll
-        for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(p0 + 4 * q);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) a1[q] = *(const f32x4*)(p1 + 4 * q);
-    }
+    load_chunk(cnt > 0 ? chunk_of(0) : 0, a0);
+    load_chunk(cnt > 1 ? chunk_of(1) : (cnt > 0 ? chunk_of(0) : 0), a1);
     // this wavefront's rows of the panel
-    for (int q = lane; q < (c1 - c0) * KC * 8; q += 64) {
-        const int k = c0 * KC + (q >> 3), c4 = (q & 7) * 4;
+    for (int q = lane; q < cnt * KC * 8; q += 64) {
+        const int idx = q >> 3, c4 = (q & 7) * 4;
+        const int k = chunk_of(idx / KC) * KC + idx % KC;
         const f32x4 v = *(const f32x4*)(W + (int64_t)k * d_out + (n0 + c4 < d_out ? n0 + c4 : 0));
         const f32x4 z = {0.f, 0.f, 0.f, 0.f};
         *(f32x4*)(panel + k * PL_BN + c4) = n0 + c4 < d_out ? v : z;
@@ -586,18 +633,14 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32_splitk_kernel(
 #pragma unroll
         for (int i = 0; i < 16; ++i) sum[i] += (double)acc[i];
     };
-    for (int s = c0; s < c1; s += 2) {  // two chunks per round of loads (a chunk past the end re-reads chunk s)
-        const bool two = s + 1 < c1;
-        if (s > c0) {
-            const float* p0 = a_ptr(s);
-            const float* p1 = a_ptr(two ? s + 1 : s);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(p0 + 4 * q);
-#pragma unroll
-            for (int q = 0; q < 4; ++q) a1[q] = *(const f32x4*)(p1 + 4 * q);
+    for (int i = 0; i < cnt; i += 2) {  // two chunks per round of loads (a chunk past the end re-reads chunk i)
+        const bool two = i + 1 < cnt;
+        if (i > 0) {
+            load_chunk(chunk_of(i), a0);
+            load_chunk(chunk_of(two ? i + 1 : i), a1);
         }
-        compute(s, a0);
-        if (two) compute(s + 1, a1);
+        compute(chunk_of(i), a0);
+        if (two) compute(chunk_of(i + 1), a1);
     }
     __syncthreads();  // every wavefront is done with the panel: its space now takes the partial sums
     double* part = (double*)panel;
@@ -662,9 +705,10 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
             const int n_panels = (int)fg_ceil_div(d_out, PL_BN);
             const size_t lds = panel_bytes > (size_t)SK_PART_BYTES ? panel_bytes : (size_t)SK_PART_BYTES;
             const unsigned grid = (unsigned)(fg_ceil_div(fg_ceil_div(max_rows, 32), 8) * 8 * n_panels);
-            hipLaunchKernelGGL(linear_f32_splitk_kernel, dim3(grid), dim3(PL_THREADS), lds, st, (const char*)h_src, n_src,
+            hipLaunchKernelGGL(linear_f32_splitk_kernel<false>, dim3(grid), dim3(PL_THREADS), lds, st, (const char*)h_src, n_src,
                                src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out,
-                               (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels);
+                               (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels, nullptr, nullptr, nullptr,
+                               (int64_t)0, 0);
             FG_LAUNCH_CHECK("linear_f32_splitk_kernel");
             return FG_OK;
         }
@@ -727,4 +771,44 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
         return fg_launch_linear_bf16(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows_dev, n_rows_dev, max_rows,
                                      d_in, d_out, W, bias, relu, h_out, n_out, out_stride, out_dtype, st);
     FG_FAIL(FG_ERR_DTYPE, "fg_linear: weights must be F32 or BF16");
+}
+
+
+// fg_aggregate followed by fg_linear for one fp32 layer. A layer with few rows (the seed layer) runs as one launch that
+// forms the neighbour means while it loads its operands; any other shape runs the two calls, with agg_ws_dev between them.
+extern "C" fg_status_t fg_aggregate_linear(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
+                                           int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                           int64_t max_rows, const float* h_src, int32_t n_src, int64_t src_stride, int32_t d_in,
+                                           int32_t d_out, const float* W, const float* bias, int32_t relu, float* agg_ws_dev,
+                                           int64_t agg_stride, float* h_out, int32_t n_out, int64_t out_stride, void* stream) {
+    const char* who = "fg_aggregate_linear";
+    if (max_rows < 0 || n_block_rows < 0 || n_src < 0 || n_out < 0 || nnz < 0 || d_in <= 0 || d_out <= 0)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size", who);
+    if (max_rows > 0 && (!row_start_dev || !row_end_dev || !h_src || !W || !h_out || (nnz > 0 && !col_dev)))
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
+    if (d_in % 4 || d_out % 4) FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d and d_out = %d must be multiples of 4", who, d_in, d_out);
+    if (src_stride < (int64_t)d_in * 4 || out_stride < (int64_t)d_out * 4) FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
+    if (((uintptr_t)h_src | (uintptr_t)W | (uintptr_t)src_stride) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_src, W and src_stride must be 16-byte aligned", who);
+    if (((uintptr_t)h_out | (uintptr_t)out_stride | (uintptr_t)bias) & 3) FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_out, its stride and bias must be 4-byte aligned", who);
+    const size_t panel_bytes = (size_t)2 * d_in * PL_BN * sizeof(float);
+    const int64_t n_tasks = fg_ceil_div(max_rows, 32) * fg_ceil_div(d_out, PL_BN);
+    const int64_t forced = fg_tuning(FG_TUNE_LINEAR_TILE);
+    if (d_in % KC == 0 && panel_bytes <= 64 * 1024 && n_tasks <= 768 && (forced == 0 || forced == 8)) {
+        fg_clear_error();
+        if (max_rows == 0 || n_src == 0 || n_out == 0) return FG_OK;
+        const int n_panels = (int)fg_ceil_div(d_out, PL_BN);
+        const size_t lds = panel_bytes > (size_t)SK_PART_BYTES ? panel_bytes : (size_t)SK_PART_BYTES;
+        const unsigned grid = (unsigned)(fg_ceil_div(fg_ceil_div(max_rows, 32), 8) * 8 * n_panels);
+        hipLaunchKernelGGL(linear_f32_splitk_kernel<true>, dim3(grid), dim3(PL_THREADS), lds, (hipStream_t)stream, (const char*)h_src,
+                           n_src, src_stride, (const char*)h_src, src_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, W, bias, relu,
+                           (char*)h_out, n_out, out_stride, n_panels, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows);
+        FG_LAUNCH_CHECK("linear_f32_splitk_kernel (fused aggregation)");
+        return FG_OK;
+    }
+    if (max_rows > 0 && !agg_ws_dev) FG_FAIL(FG_ERR_INVALID_ARG, "%s: this shape runs as two launches and needs agg_ws_dev", who);
+    fg_status_t rc = fg_aggregate(row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows, h_src, n_src,
+                                  src_stride, d_in, FG_F32, agg_ws_dev, agg_stride, FG_F32, stream);
+    if (rc != FG_OK) return rc;
+    return fg_linear(h_src, n_src, src_stride, FG_F32, agg_ws_dev, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, W, FG_F32,
+                     bias, relu, h_out, n_out, out_stride, FG_F32, stream);
 }

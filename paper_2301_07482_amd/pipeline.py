@@ -58,7 +58,7 @@ class HotPath:
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
-                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage"):
+                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage", fuse_small_layers=False):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -94,6 +94,9 @@ class HotPath:
         # model "gcn": GCN layers (propagation incl. the node itself, one weight matrix [d_in x d_out]); fp32, forward only.
         # The mean's first half goes to a by-position buffer, its second half to AGG in list order (what fg_linear reads).
         self.model = model
+        # optional: layers with few rows (the seed layer) run aggregation and dense update as one launch (measured no faster
+        # than the two launches, so off by default); not when the weight gradients need the means afterwards
+        self.fuse_small_layers = bool(fuse_small_layers) and model == "sage" and self.comp_code == B.FG_F32 and not self.weight_grads
         if model == "gcn":
             assert self.comp_code == B.FG_F32 and self.feat_code == B.FG_F32 and not backward, "GCN layers: fp32, forward only"
             self.MEANPOS = torch.zeros(max(n[l] * (dims[l - 1] // 2) for l in range(1, L + 1)), dtype=torch.float32, device=dev)
@@ -163,6 +166,10 @@ class HotPath:
                 d0b = dims[0] * B.DTYPE_SIZE[self.feat_code]
                 B.fg_cache_fill_features(self.cache, self.hot_ids, len(hot_ids), self.feat, num_nodes, d0b, d0b, self._stream())
                 self.feature_side = True
+
+    def one_launch(self, l, n_rows):
+        """Whether layer l with n_rows positions runs aggregation and dense update as one launch (its means are then never stored)."""
+        return self.fuse_small_layers and l >= 2 and B.one_launch_layer(n_rows, self.dims[l - 1], self.dims[l])
 
     def _stream(self):
         return torch.cuda.current_stream().cuda_stream
@@ -258,6 +265,12 @@ class HotPath:
                 B.fg_linear(self.MEANPOS, bt.n[l], half * 4, B.FG_F32, self.AGG_l[l], half * 4, self.normal_pos[l], self._cnt(l, 2),
                             bt.n[l], half, self.dims[l], self.W[l], B.FG_F32, self.bias[l], 1 if l < L else 0, self.H[l], bt.n[l],
                             out_b, out_code, st)
+                continue
+            if self.one_launch(l, bt.n[l]):
+                tick(f"aggregate_linear[{l}]")
+                B.fg_aggregate_linear(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),
+                                      bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], self.dims[l], self.W[l],
+                                      self.bias[l], 1 if l < L else 0, None, agg_b, self.H[l], bt.n[l], out_b, st)
                 continue
             if fused and l == 1:
                 tick("gather_aggregate[1]")

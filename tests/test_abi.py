@@ -106,6 +106,11 @@ def test_argument_validation_needs_no_gpu(B):
                 4096, 64) == B.FG_ERR_SHAPE                                                                 # workspace
     assert B.fg_layer_backward_weights_workspace_bytes(67584, 128, 256) >= 256 * 256 * 4
     assert code(B.fg_cache_set_stabilization, None, 3) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_aggregate_linear, 4096, 4096, 4096, 5, 5, None, None, 5, None, 9, 512, 128, 64, 4096, None, 0, None, 512, 4096, 5,
+                256) == B.FG_ERR_INVALID_ARG                                                                # no h_src
+    assert code(B.fg_aggregate_linear, 4096, 4096, 4096, 5, 50000, None, None, 50000, 4096, 50000, 512, 128, 64, 4096, None, 0, None,
+                512, 4096, 50000, 256) == B.FG_ERR_INVALID_ARG                                              # two launches need agg_ws
+    assert B.one_launch_layer(1024, 256, 256) and not B.one_launch_layer(6144, 256, 256) and not B.one_launch_layer(100, 100, 64)
     assert code(B.fg_set_tuning, "gather_unroll", -3) == B.FG_ERR_INVALID_ARG
     assert B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, 1000) >= 1000 * 5
     assert B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, 1000) >= 1000 * 9

@@ -417,6 +417,39 @@ def test_update_all_and_fetch_all_with_unequal_and_empty_layers(env):
         B.fg_cache_destroy(cache)
 
 
+@pytest.mark.parametrize("d_in,d_out,n,n_src,max_deg,relu,seed", [(256, 256, 1024, 6000, 5, False, 0), (64, 64, 256, 1500, 10, True, 1),
+                                                                 (128, 96, 700, 700, 3, True, 2), (256, 256, 4000, 9000, 10, True, 3),
+                                                                 (24, 40, 50, 90, 4, False, 4), (32, 32, 1, 5, 0, True, 5)])
+def test_aggregate_linear_matches_oracle(env, d_in, d_out, n, n_src, max_deg, relu, seed):
+    """One call for aggregation + dense update: the one-launch form for small layers, the two-launch form otherwise."""
+    torch, B = env
+    r = np.random.default_rng(seed)
+    deg = r.integers(0, max_deg + 1, size=n)
+    start = np.concatenate([[0], np.cumsum(deg)[:-1]]).astype(np.int32)
+    end = (start + deg).astype(np.int32)
+    col = np.concatenate([r.choice(n_src, size=k, replace=False) for k in deg] + [np.zeros(0, np.int64)]).astype(np.int32)
+    rows = np.sort(r.permutation(n)[: max(1, n * 4 // 5)]).astype(np.int32)
+    h = r.standard_normal((n_src, d_in)).astype(np.float32)
+    W = (r.standard_normal((2 * d_in, d_out)) / np.sqrt(2 * d_in)).astype(np.float32)
+    b = (0.1 * r.standard_normal(d_out)).astype(np.float32)
+    agg = O.round_to(O.aggregate(start, end, col, rows, h), "f32")
+    want = O.round_to(O.linear(h[rows], agg, W, b, relu), "f32")
+    rows_dev = torch.zeros(n, dtype=torch.int32, device="cuda")
+    rows_dev[:len(rows)] = dev(torch, rows)
+    cnt = dev(torch, np.asarray([len(rows)], dtype=np.int64))
+    tcol = dev(torch, col) if len(col) else torch.zeros(1, dtype=torch.int32, device="cuda")
+    out = torch.full((n, d_out), 5.0, dtype=torch.float32, device="cuda")
+    ws = torch.zeros((n, d_in), dtype=torch.float32, device="cuda")
+    B.fg_aggregate_linear(dev(torch, start), dev(torch, end), tcol, len(col), n, rows_dev, cnt, n, dev(torch, h), n_src, d_in * 4, d_in,
+                          d_out, dev(torch, W), dev(torch, b), 1 if relu else 0, ws, d_in * 4, out, n, d_out * 4)
+    got = out.cpu().numpy()
+    assert T.rel_err_rows(got[rows], want) <= REL_TOL_F32
+    assert np.all(got[np.setdiff1d(np.arange(n), rows)] == 5.0)
+    one = B.one_launch_layer(n, d_in, d_out)
+    assert one == (seed in (0, 1, 2, 5))
+    assert bool(ws.any().item()) == (not one)            # the means are stored only by the two-launch form
+
+
 # ------------------------------------------------------------------------------------------------ backward pass
 
 @pytest.mark.parametrize("n,d", [(1024, 256), (37, 64), (5, 47), (1, 8)])
@@ -681,7 +714,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                         agg64 = (O.aggregate_gcn if model == "gcn" else O.aggregate)(mb.start[l], mb.end[l], mb.col[l], npos, h_prev)
                         agg_dtype = "f32" if w.compute_dtype == "f32" else "bf16"
                         agg_want = O.round_to(agg64, agg_dtype).astype(np.float32)
-                        agg_got = G.to_f32(hp.AGG[: len(npos) * dims[l - 1]].view(len(npos), dims[l - 1])) if l == L else None
+                        agg_got = G.to_f32(hp.AGG[: len(npos) * dims[l - 1]].view(len(npos), dims[l - 1])) \
+                            if (l == L and not hp.one_launch(l, bt.n[l])) else None
                         if model == "gcn" and l == L:   # the mean's halves: by position and in list order
                             hw = dims[l - 1] // 2
                             agg_got = np.concatenate([G.to_f32(hp.MEANPOS[: bt.n[l] * hw].view(bt.n[l], hw)[idx]),
@@ -825,6 +859,26 @@ def test_aggregate_gcn_matches_oracle(env, dim, n, n_src, max_deg, seed):
                               dev(torch, table), n_src, dim * 4, dim, pos, cmp_)
     got = np.concatenate([pos.cpu().numpy()[rows], cmp_.cpu().numpy()[:len(rows)]], axis=1)
     assert T.rel_err_rows(got, want) <= REL_TOL_F32
+
+
+def test_iterations_one_launch_seed_layer(env):
+    """The seed layer through fg_aggregate_linear (aggregation and dense update in one launch)."""
+    torch, B = env
+    import dataclasses
+    from paper_2301_07482_amd import pipeline as P
+    real = P.HotPath.__init__
+
+    def patched(self, *a, **k):
+        k["fuse_small_layers"] = True
+        real(self, *a, **k)
+    P.HotPath.__init__ = patched
+    try:
+        assert run_workload_parity(torch, wl.WORKLOADS["tiny"], 8)[0] > 0
+        w3 = dataclasses.replace(wl.WORKLOADS["large_hbm"], name="large_hbm/small", num_nodes=200_000, num_edges=4_000_000, batch=128,
+                                 train_nodes=20_000, cache_capacity=20_000, t_stale=6)
+        assert run_workload_parity(torch, w3, 6, p_grad=0.7, fused=True)[0] > 0
+    finally:
+        P.HotPath.__init__ = real
 
 
 def test_iterations_tiny_small_ring(env):
