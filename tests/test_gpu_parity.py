@@ -917,6 +917,32 @@ def test_iterations_random_configurations(env, seed):
     run_workload_parity(torch, w, 9, fused=fused, one_launch_top_down=one_launch, conditioned=True)
 
 
+@pytest.mark.parametrize("seed", range(6))
+def test_iterations_random_feature_side(env, seed):
+    """Random depths, row widths, ring sizes, buffer sizes and hot-list lengths for the bidirectional cache, with the
+    table rows of the cached nodes negated after the fill: ranks, gathered rows and buffer contents are compared bit for bit."""
+    torch, B = env
+    import dataclasses
+    r = np.random.default_rng(2000 + seed)
+    L = int(r.integers(2, 5))
+    feat_dim = int(r.choice([8, 24, 64, 100, 128]))
+    hidden = int(r.choice([32, 64, 96]))
+    cap = int(r.choice([40, 300, 2000]))
+    w = dataclasses.replace(wl.WORKLOADS["tiny"], name=f"random-fs/{seed}", num_nodes=int(r.integers(3_000, 30_000)),
+                            num_edges=int(r.integers(20_000, 300_000)), feat_dim=feat_dim, hidden=hidden,
+                            fanouts=tuple(int(x) for x in r.integers(1, 6, size=L)), batch=int(r.integers(8, 150)),
+                            cache_capacity=cap, t_stale=int(r.integers(1, 6)), p_grad=float(r.choice([0.3, 0.7, 1.0])),
+                            seed=int(r.integers(1, 1 << 30)))
+    rings = G.rings_bytes(w)
+    buffer_bytes = -(-int(rings * r.uniform(1.0, 1.6)) // 256) * 256 + 256 * int(r.integers(0, 8))
+    n_hot = int(min(w.num_nodes, (buffer_bytes // (feat_dim * 4)) * r.uniform(0.3, 1.0)))
+    fused = bool(r.integers(0, 2))
+    print(f"L={L} dims {feat_dim}->{hidden} cap={cap} rings={rings} buffer={buffer_bytes} n_hot={n_hot} fused={fused}", flush=True)
+    hits, worst, served = run_workload_parity(torch, w, 8, fused=fused, conditioned=True,
+                                              feature_side=dict(n_hot=n_hot, buffer_bytes=buffer_bytes, poison=True))
+    assert served > 0
+
+
 def test_iterations_tiny_small_ring(env):
     """A cache much smaller than a layer: wrap-around and overflow every iteration."""
     torch, B = env
