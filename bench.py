@@ -71,6 +71,9 @@ def main():
                          "synthetic labels, layer backward down to layer 1, row norms) instead of the synthetic norms")
     ap.add_argument("--one-launch-seed-layer", action="store_true",
                     help="run the seed layer through fg_aggregate_linear (one launch) instead of fg_aggregate + fg_linear")
+    ap.add_argument("--block-positions", action="store_true",
+                    help="give the fused loader block 1 with positions as columns (fg_gather_aggregate) instead of node ids "
+                         "(fg_gather_aggregate_ids)")
     ap.add_argument("--model", default="sage", choices=["sage", "gcn"],
                     help="layer type: GraphSAGE-mean (the headline) or GCN (propagation incl. the node itself, one weight matrix)")
     ap.add_argument("--weight-grads", action="store_true",
@@ -115,8 +118,9 @@ def main():
                                        hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads, model=args.model)
     if args.one_launch_seed_layer:
         hp.fuse_small_layers = hp.model == "sage" and not hp.weight_grads
-    make_batch = (lambda mb, gn, labels: DeviceBatch(mb, None, labels=labels)) if args.backward else \
-        (lambda mb, gn, labels: DeviceBatch(mb, gn))
+    ids_cols = not args.block_positions and not args.no_fuse
+    make_batch = (lambda mb, gn, labels: DeviceBatch(mb, None, labels=labels, col_ids=ids_cols)) if args.backward else \
+        (lambda mb, gn, labels: DeviceBatch(mb, gn, col_ids=ids_cols))
     if args.per_layer_update:
         hp.update_all = False
     if args.tune:
@@ -219,13 +223,15 @@ def main():
         n_input = float(np.mean([c[0][2] for c in counts]))
         dom_kernel = "gather_rows_kernel<.., true> (fg_gather of the raw features)"
     else:
-        # fused loader + layer-1 mean: per edge of a normal row 4 (col) + 4 (id) + one table row read; per normal row
+        # fused loader + layer-1 mean: per edge of a normal row 4 (col) [+ 4 (id) when the block's columns are positions] + one
+        # table row read; per normal row
         # 4 (position) + 8 (start, end) + one mean row written + its own row: 4 (id) + one table row read + one row
         # written. The edges under normal rows are what is left in the pruned blocks (rows that are not normal have
         # end = start).
         edges = [float((batches[it].end[1] - batches[it].start[1]).sum().item()) for it in roof_it]
         own_row = (4 + feat_row) if args.model == "gcn" else (4 + 2 * feat_row)   # GCN: the own row enters the mean, no copy
-        gather_bytes = float(np.mean([e * (8 + feat_row) + c[1][2] * (12 + agg_row + own_row)
+        per_edge = (4 if ids_cols and not hp.feature_side and args.model == "sage" else 8) + feat_row   # column (+ position -> id) + row
+        gather_bytes = float(np.mean([e * per_edge + c[1][2] * (12 + agg_row + own_row)
                                       for e, c in zip(edges, counts)]))
         n_input = float(np.mean(edges)) + float(np.mean([c[1][2] for c in counts]))   # table rows read (edges + own rows)
         dom_kernel = "aggregate_mean_kernel<.., true> (fg_gather_aggregate: loader fused with the layer-1 mean)"
@@ -365,7 +371,8 @@ def main():
                    "t_stale": w.t_stale, "p_grad": w.p_grad, "cache": not args.no_cache,
                    "fused_loader": not args.no_fuse, "feature_rows": int(args.feature_rows),
                    "gradient_norms": "backward pass" if args.backward else "synthetic input",
-                   "weight_gradients": bool(args.weight_grads and args.backward), "model": args.model, "seed": w.seed},
+                   "weight_gradients": bool(args.weight_grads and args.backward), "model": args.model,
+                   "block1_columns": "node ids" if ids_cols else "positions", "seed": w.seed},
         "roofline": roofline,
         "roofline_2": roofline_2,
         "cpu_baseline": cpu_baseline,

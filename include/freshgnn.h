@@ -247,6 +247,19 @@ fg_status_t fg_gather(const void* table, int64_t table_rows, int64_t src_stride,
                       void* stream);
 
 /*
+ * fg_gather_aggregate for a block whose columns are given as node ids: col_ids_dev[e] is the table row of the e-th sampled
+ * neighbour itself (what src_ids_dev[col_dev[e]] is in fg_gather_aggregate), so the loader does not look positions up.
+ * row_ids_dev[n_block_rows] = node id of every row of the block (for the copy of the rows' own features). A sampler that
+ * feeds only this loader need not number the input layer at all. Same results as fg_gather_aggregate.
+ */
+fg_status_t fg_gather_aggregate_ids(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_ids_dev,
+                                    int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                    int64_t max_rows, const int32_t* row_ids_dev, const void* table, int64_t table_rows,
+                                    int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
+                                    fg_dtype_t out_dtype, void* h_self_out, int64_t h_self_stride, int32_t n_self_rows,
+                                    void* stream);
+
+/*
  * Load_feature through the feature side of the bidirectional cache (Section 4.2): fg_gather with node ids as
  * src_index, where the row of a node that fg_feature_lookup would find is read from the shared buffer in HBM
  * instead of from `table`. The result is the same bit copy as fg_gather's; only where the bytes come from differs.

@@ -116,7 +116,9 @@ __device__ __forceinline__ u32x4 load_piece(const char* p) {
 // GCN: the propagation of a GCN layer in row-normalised form: the row's own previous embedding is part of the mean,
 // (h_r + sum of the neighbours) / (deg + 1). The result is written as the two halves the dense update reads: columns
 // [0, dim/2) to gcn_pos[r, :] (by position), columns [dim/2, dim) to agg[k, :] (list order).
-template <int IN, int OUT, bool INDIRECT, bool FEAT, bool GCN = false>
+// COLIDS (with INDIRECT): col[] already holds table rows (node ids), so the position -> id step is skipped for the
+// neighbours; src_ids is then only used for the rows' own ids.
+template <int IN, int OUT, bool INDIRECT, bool FEAT, bool GCN = false, bool COLIDS = false>
 __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
     const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ col,
     int64_t nnz, int n_block_rows, const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev,
@@ -170,7 +172,7 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
                 // stage this row's neighbour positions: coalesced read, broadcast reads afterwards
                 for (int t = lane; t < cnt; t += lanes) {
                     int32_t c = col[s0 + base + t];
-                    if (INDIRECT) c = (c >= 0 && c < n_ids) ? src_ids[c] : -1;
+                    if (INDIRECT && !COLIDS) c = (c >= 0 && c < n_ids) ? src_ids[c] : -1;
                     if constexpr (FEAT) {
                         if (c >= 0 && c < n_src) {
                             const int32_t fr = fg_feature_rank(F, c);
@@ -256,7 +258,7 @@ static fg_status_t aggregate_common(const char* who, const int32_t* row_start_de
                                     int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
                                     fg_dtype_t out_dtype, const int32_t* src_ids, int32_t n_ids, void* self_out,
                                     int64_t self_stride, int32_t n_self, void* stream, const fg_feat_side* feat = nullptr,
-                                    void* gcn_pos = nullptr, int64_t gcn_pos_stride = 0) {
+                                    void* gcn_pos = nullptr, int64_t gcn_pos_stride = 0, bool col_is_ids = false) {
     if (max_rows < 0 || n_block_rows < 0 || n_src < 0 || dim <= 0 || nnz < 0 || n_ids < 0)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (max_rows %lld, n_block_rows %d, n_src %lld, dim %d, nnz %lld)", who,
                 (long long)max_rows, n_block_rows, (long long)n_src, dim, (long long)nnz);
@@ -312,6 +314,11 @@ static fg_status_t aggregate_common(const char* who, const int32_t* row_start_de
         if constexpr (IND) {                              \
             if (with_feat)                                \
                 FG_AGG_LAUNCH_F(IN, OUT, true, true);     \
+            else if (col_is_ids)                          \
+                hipLaunchKernelGGL((aggregate_mean_kernel<IN, OUT, true, false, false, true>), dim3((unsigned)blocks),       \
+                                   dim3(AGG_THREADS), lds, st, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, rows_dev, \
+                                   n_rows_dev, max_rows, (const char*)h_src, n_src, src_stride, pieces, (char*)agg, agg_stride,  \
+                                   lg, src_ids, n_ids, (char*)self_out, self_stride, n_self, F);                                 \
             else                                          \
                 FG_AGG_LAUNCH_F(IN, OUT, true, false);    \
         } else {                                          \
@@ -387,6 +394,25 @@ extern "C" fg_status_t fg_gather_aggregate(const int32_t* row_start_dev, const i
     return gather_aggregate_checked("fg_gather_aggregate", nullptr, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows,
                                     rows_dev, n_rows_dev, max_rows, src_ids_dev, n_src, table, table_rows, src_stride, dim,
                                     in_dtype, agg, agg_stride, out_dtype, h_self_out, h_self_stride, n_self_rows, stream);
+}
+
+extern "C" fg_status_t fg_gather_aggregate_ids(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_ids_dev,
+                                               int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                               int64_t max_rows, const int32_t* row_ids_dev, const void* table, int64_t table_rows,
+                                               int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
+                                               fg_dtype_t out_dtype, void* h_self_out, int64_t h_self_stride, int32_t n_self_rows,
+                                               void* stream) {
+    const char* who = "fg_gather_aggregate_ids";
+    if (max_rows > 0 && !row_ids_dev) FG_FAIL(FG_ERR_INVALID_ARG, "%s: row_ids_dev is NULL", who);
+    if (h_self_out) {
+        if (n_self_rows < 0 || h_self_stride < (int64_t)dim * fg_dtype_size(in_dtype))
+            FG_FAIL(FG_ERR_SHAPE, "%s: h_self_out needs n_self_rows >= 0 and a stride of at least one row", who);
+        if (((uintptr_t)h_self_out | (uintptr_t)h_self_stride) & 15)
+            FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_self_out and its stride must be 16-byte aligned", who);
+    }
+    return aggregate_common(who, row_start_dev, row_end_dev, col_ids_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows, table,
+                            table_rows, src_stride, dim, in_dtype, agg, agg_stride, out_dtype, row_ids_dev, n_block_rows, h_self_out,
+                            h_self_stride, n_self_rows, stream, nullptr, nullptr, 0, true);
 }
 
 extern "C" fg_status_t fg_gather_aggregate_features(const fg_cache_t* cache, const int32_t* row_start_dev,

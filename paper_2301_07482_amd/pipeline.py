@@ -28,7 +28,7 @@ def layer_bounds(batch, fanouts, num_nodes):
 class DeviceBatch:
     """A sampled mini-batch resident in device memory (ids, two-row-array blocks, gradient norms)."""
 
-    def __init__(self, mb, gnorms, device="cuda", labels=None):
+    def __init__(self, mb, gnorms, device="cuda", labels=None, col_ids=False):
         """gnorms: {layer: norms by position} given from outside, or None when `labels` (the seeds' classes) are given and
         the norms come from the backward pass; the blocks' transposes are then uploaded too."""
         L = mb.num_layers
@@ -42,6 +42,10 @@ class DeviceBatch:
                              for l in range(1, L + 1)]
         self.nnz = [0] + [len(mb.col[l]) for l in range(1, L + 1)]
         self.gnorm = {l: up(np.asarray(g, dtype=np.float32)) for l, g in (gnorms or {}).items()}
+        # block 1's columns as node ids (for the loader that takes them directly): the same block, renumbered
+        self.col_ids1 = None
+        if col_ids and L >= 1:
+            self.col_ids1 = up(mb.ids[0][mb.col[1]].astype(np.int32)) if len(mb.col[1]) else torch.zeros(1, dtype=torch.int32, device=device)
         self.labels = None
         if labels is not None:
             from fg_inputs.sampler import transpose_block
@@ -279,6 +283,10 @@ class HotPath:
                         self.agg_code, self.H[0], d0b, bt.n[0], st)
                 if self.feature_side:
                     B.fg_gather_aggregate_features(self.cache, *args)
+                elif getattr(bt, "col_ids1", None) is not None:
+                    B.fg_gather_aggregate_ids(bt.start[1], bt.end[1], bt.col_ids1, bt.nnz[1], bt.n[1], self.normal_pos[1],
+                                              self._cnt(1, 2), bt.n[1], bt.ids[1], self.feat, self.num_nodes, d0b, self.dims[0],
+                                              in_code, self.AGG_l[1], agg_b, self.agg_code, self.H[0], d0b, bt.n[0], st)
                 else:
                     B.fg_gather_aggregate(*args)
             else:

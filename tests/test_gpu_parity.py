@@ -570,7 +570,7 @@ def test_iterations_large_hbm_full_size_with_backward_pass(env):
 
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
-                        backward=False, stabilization=0, model="sage", conditioned=False):
+                        backward=False, stabilization=0, model="sage", conditioned=False, col_ids=False):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
@@ -623,7 +623,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
             mb = wl.minibatch(w, g, it)
             gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
             labels = wl.node_labels(w, mb.ids[L]) if backward else None
-            bt = DeviceBatch(mb, None if backward else gn, labels=labels)   # uploaded before the oracle prunes its copy of the blocks
+            bt = DeviceBatch(mb, None if backward else gn, labels=labels, col_ids=col_ids)   # uploaded before the oracle prunes its copy
             if bc is not None:
                 # what the loader is about to find on the feature side, for every node of the input layer (or a sample)
                 n0 = len(mb.ids[0])
@@ -1025,6 +1025,13 @@ def test_iterations_tiny_fused_input(env):
     assert hits > 100
 
 
+def test_iterations_fused_input_with_node_ids_as_block_columns(env):
+    """The fused loader given block 1 with node ids as columns (fg_gather_aggregate_ids)."""
+    torch, B = env
+    assert run_workload_parity(torch, wl.WORKLOADS["tiny"], 10, fused=True, col_ids=True)[0] > 0
+    assert run_workload_parity(torch, wl.WORKLOADS["medium"], 4, check_numeric_every=2, sample_rows=20000, fused=True, col_ids=True)[0] > 0
+
+
 def test_iterations_medium_fused_input(env):
     torch, B = env
     w = wl.WORKLOADS["medium"]
@@ -1047,7 +1054,7 @@ def test_iterations_large_hbm_full_size(env):
     feature rows on a sample, numerics every 8th iteration."""
     torch, B = env
     w = wl.WORKLOADS["large_hbm"]
-    hits, worst = run_workload_parity(torch, w, 24, check_numeric_every=8, sample_rows=20000, fused=True)
+    hits, worst = run_workload_parity(torch, w, 24, check_numeric_every=8, sample_rows=20000, fused=True, col_ids=True)
     print(f"large_hbm: {hits} hits, worst rel err {worst:.3e}")
     assert hits > 1000
 
