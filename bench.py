@@ -74,6 +74,9 @@ def main():
     ap.add_argument("--block-positions", action="store_true",
                     help="give the fused loader block 1 with positions as columns (fg_gather_aggregate) instead of node ids "
                          "(fg_gather_aggregate_ids)")
+    ap.add_argument("--separate-fetch", action="store_true",
+                    help="fetch the cached embeddings with a launch of their own (fg_cache_fetch_all) instead of inside the "
+                         "id-column loader's launch")
     ap.add_argument("--model", default="sage", choices=["sage", "gcn"],
                     help="layer type: GraphSAGE-mean (the headline) or GCN (propagation incl. the node itself, one weight matrix)")
     ap.add_argument("--weight-grads", action="store_true",
@@ -115,7 +118,8 @@ def main():
         row = w.feat_dim * (4 if w.feat_dtype == "f32" else 2)
         buffer_bytes = -(-(G.rings_bytes(w) + len(hot) * row) // 256) * 256
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + extra + 32,
-                                       hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads, model=args.model)
+                                       hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads, model=args.model,
+                                       fetch_with_loader=not args.separate_fetch)
     if args.one_launch_seed_layer:
         hp.fuse_small_layers = hp.model == "sage" and not hp.weight_grads
     ids_cols = not args.block_positions and not args.no_fuse
@@ -235,6 +239,12 @@ def main():
                                       for e, c in zip(edges, counts)]))
         n_input = float(np.mean(edges)) + float(np.mean([c[1][2] for c in counts]))   # table rows read (edges + own rows)
         dom_kernel = "aggregate_mean_kernel<.., true> (fg_gather_aggregate: loader fused with the layer-1 mean)"
+        fetch_rides = (ids_cols and hp.fetch_with_loader and hp.fetch_all and hp.cache is not None and hp.use_cache
+                       and args.model == "sage" and not hp.feature_side and not hp.one_launch(1, batches[roof_it[0]].n[1]))
+        if fetch_rides:   # the launch also fetches the cached embeddings: per hit 8 (slot, position) + a row read + a row written
+            e_c = 4 if w.compute_dtype == "f32" else 2
+            gather_bytes += float(np.mean([sum(c[l][1] * (8 + 2 * hp.dims[l] * e_c) for l in range(1, L)) for c in counts]))
+            dom_kernel = "loader_fetch_kernel (fg_gather_aggregate_ids: loader fused with the layer-1 mean, cache fetch in the same launch)"
     # rows the loader found on the feature side instead of reading them from the table (the placed rows lie beyond the
     # rings, so which nodes are there does not change during the run)
     from_buffer = 0.0
@@ -299,7 +309,7 @@ def main():
                            achieved=lin_tf, peak=FP32_MFMA_PEAK_TFLOPS, unit="TFLOP/s", frac=lin_tf / FP32_MFMA_PEAK_TFLOPS,
                            traffic=None, flops_per_launch=lin_flops[1], ms_per_launch=lin1_ms)
     if w.name == "large_hbm" and not (args.no_cache or args.no_fuse or args.model != "sage" or args.feature_rows):   # the configuration the counter runs were made on
-        loader_roof["traffic"] = profiled_traffic("aggregate_mean_kernel<0, 0, true, false")
+        loader_roof["traffic"] = profiled_traffic("loader_fetch_kernel<0, 0>" if dom_kernel.startswith("loader_fetch") else "aggregate_mean_kernel<0, 0, true, false")
         linear_roof["traffic"] = profiled_traffic("linear_f32x3_panel_kernel<2>")
     # `roofline` is the kernel with the longest launches in the timed region; the other one follows as `roofline_2`
     roofline, roofline_2 = (loader_roof, linear_roof) if gather_ms >= lin1_ms else (linear_roof, loader_roof)
@@ -324,7 +334,8 @@ def main():
                 add(f"aggregate[{l}]", edges_l * (4 + d_prev) + n_norm * hp.dims[l - 1] * e_comp)
             if l < L:
                 row = hp.dims[l] * e_comp
-                add("cache_fetch_all", n_hit * (8 + 2 * row))
+                if "cache_fetch_all" in call_avg_ms:      # otherwise counted with the loader, whose launch does it
+                    add("cache_fetch_all", n_hit * (8 + 2 * row))
                 add("cache_update_all", 2 * n_l * 6 + float(st[l][0]) * (2 * row + 12) + float(st[l][1]) * 4)
         return out
     per_step_bytes = [call_bytes(it, c, st) for it, c, st in zip(roof_it, counts, stats)]

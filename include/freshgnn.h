@@ -251,12 +251,17 @@ fg_status_t fg_gather(const void* table, int64_t table_rows, int64_t src_stride,
  * neighbour itself (what src_ids_dev[col_dev[e]] is in fg_gather_aggregate), so the loader does not look positions up.
  * row_ids_dev[n_block_rows] = node id of every row of the block (for the copy of the rows' own features). A sampler that
  * feeds only this loader need not number the input layer at all. Same results as fg_gather_aggregate.
+ * cache, n_fetch_layers, fetch_layers: optional (NULL, 0, NULL): the fetch of cached embeddings fg_cache_fetch_all would do
+ * for these layers rides along in the same launch (the two jobs are independent; fp32 -> fp32 and fp16 -> bf16 loaders;
+ * other type pairs run it as a launch of its own first). fg_fetch_layer_t is declared with fg_cache_fetch_all below.
  */
+struct fg_fetch_layer;
 fg_status_t fg_gather_aggregate_ids(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_ids_dev,
                                     int64_t nnz, int32_t n_block_rows, const int32_t* rows_dev, const int64_t* n_rows_dev,
                                     int64_t max_rows, const int32_t* row_ids_dev, const void* table, int64_t table_rows,
                                     int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
                                     fg_dtype_t out_dtype, void* h_self_out, int64_t h_self_stride, int32_t n_self_rows,
+                                    const fg_cache_t* cache, int32_t n_fetch_layers, const struct fg_fetch_layer* fetch_layers,
                                     void* stream);
 
 /*

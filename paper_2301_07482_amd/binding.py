@@ -52,7 +52,7 @@ SIGNATURES = {
     "fg_aggregate_gcn": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _p, _p, _p]),
     "fg_gather_aggregate_gcn": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _p, _i64, _i64, _i32, _p, _p, _p]),
     "fg_gather_aggregate_ids": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _p, _i64, _i64, _i32, _i32, _p, _i64, _i32, _p, _i64,
-                                       _i32, _p]),
+                                       _i32, _p, _i32, _p, _p]),
     "fg_linear": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _p, _i64, _i32, _i32, _p, _i32, _p, _i32, _p, _i32, _i64, _i32, _p]),
     "fg_aggregate_linear": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _i32, _p, _p, _i32, _p, _i64, _p, _i32,
                                    _i64, _p]),
@@ -275,10 +275,13 @@ def fg_gather_aggregate_gcn(row_start, row_end, col, nnz, n_block_rows, rows, n_
 
 def fg_gather_aggregate_ids(row_start, row_end, col_ids, nnz, n_block_rows, rows, n_rows, max_rows, row_ids, table, table_rows,
                             src_stride, dim, in_dtype, agg, agg_stride, out_dtype, h_self_out=None, h_self_stride=0, n_self_rows=0,
-                            stream=None):
+                            cache=None, fetch_layers=None, stream=None):
+    """fetch_layers: a `fetch_layers(...)` array (with `cache`) whose copies share the loader's launch, or None."""
+    n_fetch = len(fetch_layers) if fetch_layers is not None else 0
     _check(_lib.fg_gather_aggregate_ids(ptr(row_start), ptr(row_end), ptr(col_ids), nnz, n_block_rows, ptr(rows), ptr(n_rows),
                                         max_rows, ptr(row_ids), ptr(table), table_rows, src_stride, dim, in_dtype, ptr(agg),
-                                        agg_stride, out_dtype, ptr(h_self_out), h_self_stride, n_self_rows, stream))
+                                        agg_stride, out_dtype, ptr(h_self_out), h_self_stride, n_self_rows, cache, n_fetch,
+                                        C.cast(fetch_layers, _p) if n_fetch else None, stream))
 
 
 def fg_linear(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows, n_rows, max_rows, d_in, d_out, W, w_dtype, bias, relu,

@@ -119,12 +119,13 @@ __device__ __forceinline__ u32x4 load_piece(const char* p) {
 // COLIDS (with INDIRECT): col[] already holds table rows (node ids), so the position -> id step is skipped for the
 // neighbours; src_ids is then only used for the rows' own ids.
 template <int IN, int OUT, bool INDIRECT, bool FEAT, bool GCN = false, bool COLIDS = false>
-__global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
+__device__ __forceinline__ void aggregate_mean_body(
+    const int n_blocks, const int block,  // workgroups doing this work and this workgroup's number among them
     const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ col,
     int64_t nnz, int n_block_rows, const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev,
     int64_t max_rows, const char* __restrict__ h_src, int64_t n_src, int64_t src_stride, int pieces, char* __restrict__ agg,
     int64_t agg_stride, int lanes_log2, const int32_t* __restrict__ src_ids, int n_ids, char* __restrict__ self_out,
-    int64_t self_stride, int n_self, fg_feat_side F, char* __restrict__ gcn_pos = nullptr, int64_t gcn_pos_stride = 0) {
+    int64_t self_stride, int n_self, fg_feat_side F, char* __restrict__ gcn_pos, int64_t gcn_pos_stride) {
     constexpr int PER = Elem<IN>::PER16;
     constexpr int OUT_BYTES = (OUT == FG_F32 ? 4 : 2) * PER;
     extern __shared__ int32_t nb_lds[];  // [groups_per_block][AGG_MAX_STAGE]
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
     const int g_in_block = threadIdx.x >> lanes_log2;
     const int lane = threadIdx.x & (lanes - 1);
     int32_t* my_nb = nb_lds + g_in_block * AGG_MAX_STAGE;
-    for (int64_t k = (int64_t)blockIdx.x * gpb + g_in_block; k < n_rows; k += (int64_t)gridDim.x * gpb) {
+    for (int64_t k = (int64_t)block * gpb + g_in_block; k < n_rows; k += (int64_t)n_blocks * gpb) {
         const int32_t r = rows ? rows[k] : (int32_t)k;
         int32_t s0 = 0, e0 = 0;
         if (r >= 0 && r < n_block_rows) {
@@ -248,6 +249,43 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
             }
         }
     }
+}
+
+
+template <int IN, int OUT, bool INDIRECT, bool FEAT, bool GCN = false, bool COLIDS = false>
+__global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
+    const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ col,
+    int64_t nnz, int n_block_rows, const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev,
+    int64_t max_rows, const char* __restrict__ h_src, int64_t n_src, int64_t src_stride, int pieces, char* __restrict__ agg,
+    int64_t agg_stride, int lanes_log2, const int32_t* __restrict__ src_ids, int n_ids, char* __restrict__ self_out,
+    int64_t self_stride, int n_self, fg_feat_side F, char* __restrict__ gcn_pos = nullptr, int64_t gcn_pos_stride = 0) {
+    aggregate_mean_body<IN, OUT, INDIRECT, FEAT, GCN, COLIDS>(gridDim.x, blockIdx.x, row_start, row_end, col, nnz, n_block_rows, rows,
+                                                              n_rows_dev, max_rows, h_src, n_src, src_stride, pieces, agg, agg_stride,
+                                                              lanes_log2, src_ids, n_ids, self_out, self_stride, n_self, F, gcn_pos,
+                                                              gcn_pos_stride);
+}
+
+// The fused loader with the fetch of cached embeddings riding along: workgroups [0, agg_blocks) are the loader, the
+// remaining ones copy the cached rows of the hits of every cached layer (h_v = C^(l)[v] of Algorithm 1). The two jobs do
+// not depend on each other; sharing a launch saves one of the path's small launches. (Copies first in the grid instead of
+// last measured the same.)
+template <int IN, int OUT>
+__global__ __launch_bounds__(AGG_THREADS) void loader_fetch_kernel(
+    int agg_blocks, fg_row_copy_batch copies, const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end,
+    const int32_t* __restrict__ col, int64_t nnz, int n_block_rows, const int32_t* __restrict__ rows,
+    const int64_t* __restrict__ n_rows_dev, int64_t max_rows, const char* __restrict__ h_src, int64_t n_src, int64_t src_stride,
+    int pieces, char* __restrict__ agg, int64_t agg_stride, int lanes_log2, const int32_t* __restrict__ src_ids, int n_ids,
+    char* __restrict__ self_out, int64_t self_stride, int n_self) {
+    if ((int)blockIdx.x >= agg_blocks) {
+        const int64_t wave = ((int64_t)(blockIdx.x - agg_blocks) * AGG_THREADS + threadIdx.x) >> 6;
+        const int64_t n_waves = ((int64_t)(gridDim.x - agg_blocks) * AGG_THREADS) >> 6;
+        for (int c = 0; c < copies.n; ++c) fg_copy_rows_part(copies.c[c], wave, n_waves, threadIdx.x & 63);
+        return;
+    }
+    aggregate_mean_body<IN, OUT, true, false, false, true>(agg_blocks, blockIdx.x, row_start, row_end, col, nnz, n_block_rows, rows,
+                                                          n_rows_dev, max_rows, h_src, n_src, src_stride, pieces, agg, agg_stride,
+                                                          lanes_log2, src_ids, n_ids, self_out, self_stride, n_self, fg_feat_side{},
+                                                          nullptr, 0);
 }
 
 }  // namespace
@@ -401,6 +439,7 @@ extern "C" fg_status_t fg_gather_aggregate_ids(const int32_t* row_start_dev, con
                                                int64_t max_rows, const int32_t* row_ids_dev, const void* table, int64_t table_rows,
                                                int64_t src_stride, int32_t dim, fg_dtype_t in_dtype, void* agg, int64_t agg_stride,
                                                fg_dtype_t out_dtype, void* h_self_out, int64_t h_self_stride, int32_t n_self_rows,
+                                               const fg_cache_t* cache, int32_t n_fetch_layers, const fg_fetch_layer_t* fetch_layers,
                                                void* stream) {
     const char* who = "fg_gather_aggregate_ids";
     if (max_rows > 0 && !row_ids_dev) FG_FAIL(FG_ERR_INVALID_ARG, "%s: row_ids_dev is NULL", who);
@@ -410,9 +449,54 @@ extern "C" fg_status_t fg_gather_aggregate_ids(const int32_t* row_start_dev, con
         if (((uintptr_t)h_self_out | (uintptr_t)h_self_stride) & 15)
             FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_self_out and its stride must be 16-byte aligned", who);
     }
-    return aggregate_common(who, row_start_dev, row_end_dev, col_ids_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows, table,
-                            table_rows, src_stride, dim, in_dtype, agg, agg_stride, out_dtype, row_ids_dev, n_block_rows, h_self_out,
-                            h_self_stride, n_self_rows, stream, nullptr, nullptr, 0, true);
+    fg_row_copy_batch copies;
+    copies.n = 0;
+    if (n_fetch_layers != 0) {
+        fg_status_t rc = fg_build_fetch_batch(who, cache, n_fetch_layers, fetch_layers, &copies);
+        if (rc != FG_OK) return rc;
+    }
+    int64_t most = 0;
+    for (int i = 0; i < copies.n; ++i) most = copies.c[i].max_count > most ? copies.c[i].max_count : most;
+    const bool f32 = in_dtype == FG_F32 && out_dtype == FG_F32, h16 = in_dtype == FG_F16 && out_dtype == FG_BF16;
+    if (most == 0 || max_rows <= 0 || !(f32 || h16)) {  // nothing to fetch, or a type pair without the shared launch: two launches
+        if (most > 0) {
+            fg_status_t rc = fg_launch_row_copies(copies, (hipStream_t)stream);
+            if (rc != FG_OK) return rc;
+        }
+        return aggregate_common(who, row_start_dev, row_end_dev, col_ids_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows, table,
+                                table_rows, src_stride, dim, in_dtype, agg, agg_stride, out_dtype, row_ids_dev, n_block_rows,
+                                h_self_out, h_self_stride, n_self_rows, stream, nullptr, nullptr, 0, true);
+    }
+    // the loader's own checks, without launching it
+    fg_status_t rc = aggregate_common(who, row_start_dev, row_end_dev, col_ids_dev, nnz, n_block_rows, rows_dev, n_rows_dev, 0, table,
+                                      table_rows, src_stride, dim, in_dtype, agg, agg_stride, out_dtype, row_ids_dev, n_block_rows,
+                                      h_self_out, h_self_stride, n_self_rows, stream, nullptr, nullptr, 0, true);
+    if (rc != FG_OK) return rc;
+    if (!row_start_dev || !row_end_dev || !table || !agg || (nnz > 0 && !col_ids_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
+    const int per16 = 16 / fg_dtype_size(in_dtype);
+    const int pieces = dim / per16;
+    int lg = 0;
+    while ((1 << lg) < pieces && lg < 6) ++lg;
+    const int gpb = AGG_THREADS >> lg;
+    int64_t blocks = fg_ceil_div(max_rows, gpb);
+    const int64_t cap = 256 * fg_tuning(FG_TUNE_AGG_WG_PER_CU);
+    if (blocks > cap) blocks = cap;
+    int64_t copy_blocks = fg_ceil_div(most, 2 * (AGG_THREADS / 64));
+    if (copy_blocks > 64) copy_blocks = 64;
+    const size_t lds = (size_t)gpb * AGG_MAX_STAGE * sizeof(int32_t);
+    hipStream_t st = (hipStream_t)stream;
+    if (f32)
+        hipLaunchKernelGGL((loader_fetch_kernel<FG_F32, FG_F32>), dim3((unsigned)(blocks + copy_blocks)), dim3(AGG_THREADS), lds, st,
+                           (int)blocks, copies, row_start_dev, row_end_dev, col_ids_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,
+                           (const char*)table, table_rows, src_stride, pieces, (char*)agg, agg_stride, lg, row_ids_dev, n_block_rows,
+                           (char*)h_self_out, h_self_stride, n_self_rows);
+    else
+        hipLaunchKernelGGL((loader_fetch_kernel<FG_F16, FG_BF16>), dim3((unsigned)(blocks + copy_blocks)), dim3(AGG_THREADS), lds, st,
+                           (int)blocks, copies, row_start_dev, row_end_dev, col_ids_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,
+                           (const char*)table, table_rows, src_stride, pieces, (char*)agg, agg_stride, lg, row_ids_dev, n_block_rows,
+                           (char*)h_self_out, h_self_stride, n_self_rows);
+    FG_LAUNCH_CHECK("loader_fetch_kernel");
+    return FG_OK;
 }
 
 extern "C" fg_status_t fg_gather_aggregate_features(const fg_cache_t* cache, const int32_t* row_start_dev,

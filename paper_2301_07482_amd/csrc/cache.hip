@@ -735,27 +735,33 @@ extern "C" fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, floa
     return FG_OK;
 }
 
-extern "C" fg_status_t fg_cache_fetch_all(const fg_cache_t* cache, int32_t n_layers, const fg_fetch_layer_t* layers,
-                                          void* stream) {
-    if (n_layers < 0 || n_layers > FG_MAX_COPIES)
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fetch_all: n_layers = %d outside 0..%d", n_layers, FG_MAX_COPIES);
-    if (n_layers > 0 && !layers) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fetch_all: layers is NULL");
-    fg_row_copy_batch copies;
-    copies.n = n_layers;
+fg_status_t fg_build_fetch_batch(const char* who, const fg_cache_t* cache, int32_t n_layers, const fg_fetch_layer_t* layers,
+                                 fg_row_copy_batch* out) {
+    if (n_layers < 0 || n_layers > FG_MAX_COPIES) FG_FAIL(FG_ERR_INVALID_ARG, "%s: n_layers = %d outside 0..%d", who, n_layers, FG_MAX_COPIES);
+    if (n_layers > 0 && !layers) FG_FAIL(FG_ERR_INVALID_ARG, "%s: layers is NULL", who);
+    out->n = n_layers;
     for (int i = 0; i < n_layers; ++i) {
         const fg_fetch_layer_t& a = layers[i];
         const fg_layer* l;
-        fg_status_t rc = layer_of(cache, a.layer, "fg_cache_fetch_all", &l);
+        fg_status_t rc = layer_of(cache, a.layer, who, &l);
         if (rc != FG_OK) return rc;
-        if (a.max_hits < 0 || a.h_rows < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fetch_all: negative size for layer %d", a.layer);
-        if (a.max_hits > 0 && (!a.hit_slot_dev || !a.hit_pos_dev || !a.h_dev))
-            FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fetch_all: NULL pointer for layer %d", a.layer);
+        if (a.max_hits < 0 || a.h_rows < 0) FG_FAIL(FG_ERR_INVALID_ARG, "%s: negative size for layer %d", who, a.layer);
+        if (a.max_hits > 0 && (!a.hit_slot_dev || !a.hit_pos_dev || !a.h_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer for layer %d", who, a.layer);
         const int64_t row_bytes = (int64_t)l->dim * fg_dtype_size(cache->dtype);
-        if (a.h_stride < row_bytes) FG_FAIL(FG_ERR_SHAPE, "fg_cache_fetch_all: h_stride = %lld smaller than a cache row of %lld bytes", (long long)a.h_stride, (long long)row_bytes);
-        if (((uintptr_t)a.h_dev | (uintptr_t)a.h_stride) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_fetch_all: h_dev and h_stride must be 16-byte aligned");
-        copies.c[i] = fg_row_copy{(const char*)l->table, l->capacity, row_bytes, a.hit_slot_dev, a.hit_pos_dev, a.n_hit_dev, a.max_hits,
-                                  (char*)a.h_dev, a.h_rows, a.h_stride, row_bytes};
+        if (a.h_stride < row_bytes)
+            FG_FAIL(FG_ERR_SHAPE, "%s: h_stride = %lld smaller than a cache row of %lld bytes", who, (long long)a.h_stride, (long long)row_bytes);
+        if (((uintptr_t)a.h_dev | (uintptr_t)a.h_stride) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_dev and h_stride must be 16-byte aligned", who);
+        out->c[i] = fg_row_copy{(const char*)l->table, l->capacity, row_bytes, a.hit_slot_dev, a.hit_pos_dev, a.n_hit_dev, a.max_hits,
+                                (char*)a.h_dev, a.h_rows, a.h_stride, row_bytes};
     }
+    return FG_OK;
+}
+
+extern "C" fg_status_t fg_cache_fetch_all(const fg_cache_t* cache, int32_t n_layers, const fg_fetch_layer_t* layers,
+                                          void* stream) {
+    fg_row_copy_batch copies;
+    fg_status_t rc = fg_build_fetch_batch("fg_cache_fetch_all", cache, n_layers, layers, &copies);
+    if (rc != FG_OK) return rc;
     fg_clear_error();
     return fg_launch_row_copies(copies, (hipStream_t)stream);
 }

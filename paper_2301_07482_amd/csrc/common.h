@@ -137,6 +137,34 @@ struct fg_row_copy_batch {
     fg_row_copy c[FG_MAX_COPIES];
 };
 fg_status_t fg_launch_row_copies(const fg_row_copy_batch& batch, hipStream_t stream);
+// the copy work of wavefront `wave` of `n_waves`: a wavefront moves a row in 16-byte pieces, two rows in flight
+__device__ __forceinline__ void fg_copy_rows_part(const fg_row_copy& C, int64_t wave, int64_t n_waves, int lane) {
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    int64_t count = C.count ? *C.count : C.max_count;
+    if (count > C.max_count) count = C.max_count;
+    const int chunks = (int)(C.row_bytes >> 4);
+    for (int64_t k0 = wave; k0 < count; k0 += 2 * n_waves) {
+        const int64_t k1 = k0 + n_waves;
+        const bool has1 = k1 < count;
+        const int32_t s0 = C.src_idx[k0], d0 = C.dst_idx ? C.dst_idx[k0] : (int32_t)k0;
+        const int32_t s1 = has1 ? C.src_idx[k1] : s0, d1 = has1 ? (C.dst_idx ? C.dst_idx[k1] : (int32_t)k1) : d0;
+        const bool ok0 = s0 >= 0 && s0 < C.src_rows && d0 >= 0 && d0 < C.dst_rows;
+        const bool ok1 = has1 && s1 >= 0 && s1 < C.src_rows && d1 >= 0 && d1 < C.dst_rows;
+        const u32x4* a0 = (const u32x4*)(C.src + (int64_t)(ok0 ? s0 : 0) * C.src_stride);
+        const u32x4* a1 = (const u32x4*)(C.src + (int64_t)(ok1 ? s1 : 0) * C.src_stride);
+        u32x4* o0 = (u32x4*)(C.dst + (int64_t)(ok0 ? d0 : 0) * C.dst_stride);
+        u32x4* o1 = (u32x4*)(C.dst + (int64_t)(ok1 ? d1 : 0) * C.dst_stride);
+        for (int c = lane; c < chunks; c += 64) {
+            const u32x4 v0 = a0[c];
+            const u32x4 v1 = a1[c];
+            if (ok0) o0[c] = v0;
+            if (ok1) o1[c] = v1;
+        }
+    }
+}
+// checks the layers of a cache fetch (as fg_cache_fetch_all does) and describes them as row copies
+fg_status_t fg_build_fetch_batch(const char* who, const fg_cache_t* cache, int32_t n_layers, const fg_fetch_layer_t* layers,
+                                 fg_row_copy_batch* out);
 // fill n bytes with a value (a kernel, so that callers may capture it into a graph)
 fg_status_t fg_launch_fill_u8(uint8_t* p, int64_t n, uint8_t value, hipStream_t stream);
 fg_status_t fg_launch_fill_i32(int32_t* p, int64_t n, int32_t value, hipStream_t stream);

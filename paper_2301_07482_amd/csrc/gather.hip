@@ -82,32 +82,8 @@ __global__ __launch_bounds__(256) void gather_rows_kernel(const char* __restrict
 // blockIdx.y selects the copy; a wavefront moves a row in 16-byte pieces, two rows in flight.
 constexpr int COPY_THREADS = 256;
 __global__ __launch_bounds__(COPY_THREADS) void copy_rows_batch_kernel(fg_row_copy_batch B) {
-    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-    const fg_row_copy& C = B.c[blockIdx.y];
-    int64_t count = C.count ? *C.count : C.max_count;
-    if (count > C.max_count) count = C.max_count;
-    const int chunks = (int)(C.row_bytes >> 4);
-    const int lane = threadIdx.x & 63;
-    const int64_t wave = ((int64_t)blockIdx.x * COPY_THREADS + threadIdx.x) >> 6;
-    const int64_t n_waves = ((int64_t)gridDim.x * COPY_THREADS) >> 6;
-    for (int64_t k0 = wave; k0 < count; k0 += 2 * n_waves) {
-        const int64_t k1 = k0 + n_waves;
-        const bool has1 = k1 < count;
-        const int32_t s0 = C.src_idx[k0], d0 = C.dst_idx ? C.dst_idx[k0] : (int32_t)k0;
-        const int32_t s1 = has1 ? C.src_idx[k1] : s0, d1 = has1 ? (C.dst_idx ? C.dst_idx[k1] : (int32_t)k1) : d0;
-        const bool ok0 = s0 >= 0 && s0 < C.src_rows && d0 >= 0 && d0 < C.dst_rows;
-        const bool ok1 = has1 && s1 >= 0 && s1 < C.src_rows && d1 >= 0 && d1 < C.dst_rows;
-        const u32x4* a0 = (const u32x4*)(C.src + (int64_t)(ok0 ? s0 : 0) * C.src_stride);
-        const u32x4* a1 = (const u32x4*)(C.src + (int64_t)(ok1 ? s1 : 0) * C.src_stride);
-        u32x4* o0 = (u32x4*)(C.dst + (int64_t)(ok0 ? d0 : 0) * C.dst_stride);
-        u32x4* o1 = (u32x4*)(C.dst + (int64_t)(ok1 ? d1 : 0) * C.dst_stride);
-        for (int c = lane; c < chunks; c += 64) {
-            const u32x4 v0 = a0[c];
-            const u32x4 v1 = a1[c];
-            if (ok0) o0[c] = v0;
-            if (ok1) o1[c] = v1;
-        }
-    }
+    fg_copy_rows_part(B.c[blockIdx.y], ((int64_t)blockIdx.x * COPY_THREADS + threadIdx.x) >> 6, ((int64_t)gridDim.x * COPY_THREADS) >> 6,
+                      threadIdx.x & 63);
 }
 
 template <typename T>

@@ -62,7 +62,8 @@ class HotPath:
 
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
-                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage", fuse_small_layers=False):
+                 one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage", fuse_small_layers=False,
+                 fetch_with_loader=True):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -126,6 +127,7 @@ class HotPath:
         # all caches are updated by one call after the last layer (the last loop of Algorithm 1)
         self.update_all = update_all
         self.fetch_all = fetch_all   # the cached rows of all layers are fetched by one call right after the top-down pass
+        self.fetch_with_loader = fetch_with_loader  # ... or inside the id-column loader's launch, where that loader runs
         self.ws_upd_bytes = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L))
         self.ws_upd = torch.zeros(self.ws_upd_bytes + 256, dtype=torch.uint8, device=dev)
         self.W = {}
@@ -227,12 +229,18 @@ class HotPath:
                                   a["hit_dev"], a["hit_pos_dev"], a["hit_slot_dev"], a["normal_pos_dev"], a["normal_ids_dev"],
                                   a["counts_dev"], self.ws, self.ws_bytes, st)
         cached_layers = list(range(1, L)) if (self.use_cache and self.cache is not None) else []
+        fetch_specs = None
         if self.fetch_all and cached_layers:
-            tick("cache_fetch_all")
-            specs = [dict(layer=l, hit_slot_dev=self.hit_slot[l], hit_pos_dev=self.hit_pos[l], n_hit_dev=self._cnt(l, 1),
-                          max_hits=bt.n[l], h_dev=self.H[l], h_rows=bt.n[l], h_stride=self.dims[l] * esz[self.h_code[l]])
-                     for l in cached_layers]
-            B.fg_cache_fetch_all(self.cache, B.fetch_layers(specs), st)
+            fetch_specs = B.fetch_layers([dict(layer=l, hit_slot_dev=self.hit_slot[l], hit_pos_dev=self.hit_pos[l],
+                                               n_hit_dev=self._cnt(l, 1), max_hits=bt.n[l], h_dev=self.H[l], h_rows=bt.n[l],
+                                               h_stride=self.dims[l] * esz[self.h_code[l]]) for l in cached_layers])
+            # the id-column loader takes the fetch along in its own launch
+            rides = (self.fetch_with_loader and fused and self.model == "sage" and not self.feature_side
+                     and getattr(bt, "col_ids1", None) is not None and not self.one_launch(1, bt.n[1]))
+            if not rides:
+                tick("cache_fetch_all")
+                B.fg_cache_fetch_all(self.cache, fetch_specs, st)
+                fetch_specs = None
         # ---- loader: raw features of the surviving input nodes (fused: done by fg_gather_aggregate below, which also
         #      copies the layer-1 nodes' own rows into H[0])
         d0b = self.dims[0] * esz[self.feat_code]
@@ -286,7 +294,8 @@ class HotPath:
                 elif getattr(bt, "col_ids1", None) is not None:
                     B.fg_gather_aggregate_ids(bt.start[1], bt.end[1], bt.col_ids1, bt.nnz[1], bt.n[1], self.normal_pos[1],
                                               self._cnt(1, 2), bt.n[1], bt.ids[1], self.feat, self.num_nodes, d0b, self.dims[0],
-                                              in_code, self.AGG_l[1], agg_b, self.agg_code, self.H[0], d0b, bt.n[0], st)
+                                              in_code, self.AGG_l[1], agg_b, self.agg_code, self.H[0], d0b, bt.n[0],
+                                              self.cache if fetch_specs is not None else None, fetch_specs, st)
                 else:
                     B.fg_gather_aggregate(*args)
             else:
@@ -389,7 +398,8 @@ class HotPath:
 # ---- set-up shared by the tests and bench.py (workload -> HotPath); no arithmetic of the method
 
 def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None, p_grad=None, fused_input=False, one_launch_top_down=True, update_all=True, log_ring=256,
-                 hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage"):
+                 hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage",
+                 fetch_with_loader=True):
     """HotPath for workload `w` with its feature table resident where the workload says."""
     from fg_inputs import device as fdev, workload as wl
     dims = wl.layer_dims(w)
@@ -402,7 +412,8 @@ def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None
                  w.t_stale if t_stale is None else t_stale, w.p_grad if p_grad is None else p_grad, feat_table,
                  w.feat_dtype, w.compute_dtype, weights, features_on_host=(w.feat_location == "host"),
                  use_cache=use_cache, fused_input=fused_input, one_launch_top_down=one_launch_top_down, update_all=update_all,
-                 fetch_all=update_all, log_ring=log_ring, hot_ids=hot_ids, buffer_bytes=buffer_bytes, backward=backward, weight_grads=weight_grads, stabilization=stabilization, model=model)
+                 fetch_all=update_all, log_ring=log_ring, hot_ids=hot_ids, buffer_bytes=buffer_bytes, backward=backward, weight_grads=weight_grads, stabilization=stabilization, model=model,
+                 fetch_with_loader=fetch_with_loader)
     return hp, weights, feat_table
 
 

@@ -570,7 +570,8 @@ def test_iterations_large_hbm_full_size_with_backward_pass(env):
 
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
-                        backward=False, stabilization=0, model="sage", conditioned=False, col_ids=False):
+                        backward=False, stabilization=0, model="sage", conditioned=False, col_ids=False,
+                        fetch_with_loader=True):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
@@ -590,7 +591,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
     hp, weights, feat_table = G.make_hotpath(w, feat_table=feat_table, t_stale=t_stale, p_grad=p_grad, capacity=capacity,
                                              fused_input=fused, one_launch_top_down=one_launch_top_down,
                                              update_all=one_launch_top_down, hot_ids=hot,
-                                             buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward, stabilization=stabilization, model=model)
+                                             buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward, stabilization=stabilization, model=model,
+                                             fetch_with_loader=fetch_with_loader)
     from paper_2301_07482_amd import binding as FGB
     bc = None
     if fs:
@@ -1026,10 +1028,13 @@ def test_iterations_tiny_fused_input(env):
 
 
 def test_iterations_fused_input_with_node_ids_as_block_columns(env):
-    """The fused loader given block 1 with node ids as columns (fg_gather_aggregate_ids)."""
+    """The fused loader given block 1 with node ids as columns (fg_gather_aggregate_ids), with the fetch of the cached
+    embeddings inside its launch (one and two cached layers) and as a launch of its own."""
     torch, B = env
-    assert run_workload_parity(torch, wl.WORKLOADS["tiny"], 10, fused=True, col_ids=True)[0] > 0
-    assert run_workload_parity(torch, wl.WORKLOADS["medium"], 4, check_numeric_every=2, sample_rows=20000, fused=True, col_ids=True)[0] > 0
+    for ride in (True, False):
+        assert run_workload_parity(torch, wl.WORKLOADS["tiny"], 10, fused=True, col_ids=True, fetch_with_loader=ride)[0] > 0
+        assert run_workload_parity(torch, wl.WORKLOADS["medium"], 4, check_numeric_every=2, sample_rows=20000, fused=True, col_ids=True,
+                                   fetch_with_loader=ride)[0] > 0
 
 
 def test_iterations_medium_fused_input(env):
@@ -1159,5 +1164,5 @@ def test_iterations_very_large_bf16(env):
             from fg_inputs import device as fdev
             feat = fdev.feature_table(w.seed, w.num_nodes, w.feat_dim, w.feat_dtype, w.feat_location)
         hits, worst = run_workload_parity(torch, w, 8 if fused else 3, check_numeric_every=3, sample_rows=20000, feat_table=feat,
-                                          fused=fused)
+                                          fused=fused, col_ids=fused)
         print(f"{w.name} (fused loader: {fused}): {hits} hits, worst rel err {worst:.3e}")
