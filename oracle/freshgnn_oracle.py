@@ -461,7 +461,34 @@ def admission_threshold(g_live, p_grad):
     return float(np.sort(np.asarray(g_live, dtype=np.float32))[k]), k
 
 
-def cache_update(cache, i, ids, live, hit, gnorm, p_grad, h):
+SAVING_MAX = 2047   # the estimate of saved accesses saturates here
+
+
+def access_estimate(start, end, col, hit, below=None):
+    """Estimated memory accesses a cached embedding of each node of one layer would save (the quantity the policy "for
+    accuracy and performance" of Section 7.4 prioritises by; the text does not define it, this is the reading taken).
+
+    It is the number of rows read to produce the node's embedding in this mini-batch, counted along the pruned blocks
+    like a tree: a raw feature row is one read (`below` None: the layer below is the input layer), a node served from
+    the cache is one read, a computed node reads what its own row of the layer below and each of its remaining
+    neighbours read. Saturates at SAVING_MAX at every layer.
+    start, end, col: the layer's block after pruning; hit: per position; below: the estimates of the layer below by
+    position. Returns one integer per position of the layer.
+    """
+    n = len(start)
+    out = np.zeros(n, dtype=np.int64)
+    for j in range(n):
+        if hit[j]:
+            out[j] = 1
+            continue
+        total = 1 if below is None else int(below[j])
+        for c in range(int(start[j]), int(end[j])):
+            total += 1 if below is None else int(below[col[c]])
+        out[j] = min(total, SAVING_MAX)
+    return out
+
+
+def cache_update(cache, i, ids, live, hit, gnorm, p_grad, h, saving=None, budget=None):
     """Update of one layer's cache after iteration i (Sections 4.1.1, 4.1.2, ring of 4.2).
 
     Population: all live nodes of the layer, computed or fetched (the paper's example compares the
@@ -472,7 +499,9 @@ def cache_update(cache, i, ids, live, hit, gnorm, p_grad, h):
       * normal nodes with norm below tau are admitted in ascending position order into the slots
         head, head+1, ... (mod capacity): row copied from h, slot owner and stamp = i written, mapping
         entry set. A recycled slot's previous owner stops hitting because the slot no longer names it.
-        If more are admissible than there are slots, the first `capacity` in position order get in.
+        At most min(budget, capacity) get in (budget None: capacity). If more are admissible, those with the largest
+        `saving` (estimated saved accesses by position, see `access_estimate`; None: all equal) are taken, among equal
+        ones the lower positions first; without estimates that is the first `capacity` in position order.
       * the header advances by the number admitted.
     Staleness needs no pass of its own: `HistoricalCache.slot_of` enforces the bound.
     Returns counts (admitted, evicted_by_gradient, overwritten_valid, dropped_overflow) and tau.
@@ -488,20 +517,26 @@ def cache_update(cache, i, ids, live, hit, gnorm, p_grad, h):
             cache.map[ids[j]] = -1
             evicted += 1
     head = cache.head
-    for j in range(n):
-        if live[j] and not hit[j] and g[j] < tau:
-            if admitted >= cache.capacity:
-                dropped += 1
-                continue
-            s = (head + admitted) % cache.capacity
-            old = int(cache.slot_node[s])
-            if old >= 0 and cache.slot_of(old, i + 1) == s:
-                overwritten += 1
-            cache.slot_node[s] = ids[j]
-            cache.slot_stamp[s] = i
-            cache.store(s, h[j])
-            cache.map[ids[j]] = s
-            admitted += 1
+    room = cache.capacity if budget is None else min(int(budget), cache.capacity)
+    candidates = [j for j in range(n) if live[j] and not hit[j] and g[j] < tau]
+    if len(candidates) > room:
+        worth = (lambda j: 0) if saving is None else (lambda j: min(int(saving[j]), SAVING_MAX))
+        chosen = set(sorted(candidates, key=lambda j: (-worth(j), j))[:room])
+    else:
+        chosen = set(candidates)
+    for j in candidates:
+        if j not in chosen:
+            dropped += 1
+            continue
+        s = (head + admitted) % cache.capacity
+        old = int(cache.slot_node[s])
+        if old >= 0 and cache.slot_of(old, i + 1) == s:
+            overwritten += 1
+        cache.slot_node[s] = ids[j]
+        cache.slot_stamp[s] = i
+        cache.store(s, h[j])
+        cache.map[ids[j]] = s
+        admitted += 1
     cache.head = (head + admitted) % cache.capacity if cache.capacity else 0
     cache.used = cache.capacity if head + admitted >= cache.capacity else max(cache.used, head + admitted)
     return dict(admitted=admitted, evicted_by_gradient=evicted, overwritten=overwritten, dropped_overflow=dropped, tau=tau)
@@ -525,7 +560,7 @@ def check_minibatch(mb):
 
 
 def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_dtype="f32", compute_dtype="f32",
-              update=True, feature_side=None, labels=None, stabilization=0, model="sage"):
+              update=True, feature_side=None, labels=None, stabilization=0, model="sage", admit_budget=None):
     """One pass of Algorithm 1 without loss/backward (gradient norms are given).
 
     mb        sampled mini-batch (its `end` arrays are modified: pruning)
@@ -537,6 +572,8 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
               `linear_gcn`, W_l [d, d']), fp32 only, no backward pass
     stabilization   length of the stabilization period (Section 4.1.4): in iterations i < stabilization the historical
               cache is disabled (no lookup, no admission: regular mini-batch training), afterwards it is active
+    admit_budget   optional {l: rows}: the access-aware admission policy. A layer's update admits at most that many rows
+              and, when more are admissible, prefers those with the largest `access_estimate`
     labels    optional class of every seed: the gradient norms then come from `backward` (softmax cross-entropy on
               H(L)) and `gnorms` is ignored
     Types: H(0) in feat_dtype; H(l), AGG(l) for l >= 1 in compute_dtype except H(L) which is fp32.
@@ -597,9 +634,16 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
         gnorms = rec["backward"]["gnorm"]
     if not cache_active:
         stats = {l: dict(admitted=0, evicted_by_gradient=0, overwritten=0, dropped_overflow=0, tau=None) for l in range(1, L)}
+    saving = {}
+    if admit_budget is not None:
+        below = None
+        for l in range(1, L):
+            saving[l] = below = access_estimate(mb.start[l], mb.end[l], mb.col[l], look[l]["hit"], below)
+        rec["saving"] = saving
     if update:
         for l in range(1, L):
             if caches.get(l) is not None:
-                stats[l] = cache_update(caches[l], i, mb.ids[l], live[l], look[l]["hit"], gnorms[l], p_grad, H[l])
+                stats[l] = cache_update(caches[l], i, mb.ids[l], live[l], look[l]["hit"], gnorms[l], p_grad, H[l],
+                                        saving=saving.get(l), budget=None if admit_budget is None else admit_budget.get(l))
     rec.update(live=live, look=look, H=H, AGG=AGG, stats=stats, feature_from_buffer=from_buffer)
     return rec

@@ -7,6 +7,7 @@ import textwrap
 import pytest
 
 from oracle import freshgnn_oracle as O
+from tests import test_oracle_access_policy as AP
 from tests import test_oracle_backward as BW
 from tests import test_oracle_feature_side as F
 from tests import test_oracle_pins as P
@@ -41,6 +42,13 @@ PINS = [
     (BW.test_embedding_gradients_against_finite_differences, [(2, 0), (3, 1), (3, 2)]),
     (BW.test_weight_gradients_against_finite_differences, [()]),
     (BW.test_gradient_norms_from_the_backward_pass_drive_the_update, [()]),
+    (AP.test_estimate_counts_the_rows_an_unshared_evaluation_reads, [(0,), (1,), (2,)]),
+    (AP.test_estimate_on_full_trees_is_a_product_and_saturates, [()]),
+    (AP.test_estimate_hand_example, [()]),
+    (AP.test_admission_hand_example, [()]),
+    (AP.test_admission_is_the_rank_definition, [(0,), (1,), (2,)]),
+    (AP.test_without_estimates_and_budget_nothing_changes, [(5, 2, 0.5), (16, 4, 0.9)]),
+    (AP.test_iteration_with_budget_admits_the_costliest_rows, [()]),
 ]
 
 # (owner, function, text in its source, replacement)
@@ -68,7 +76,24 @@ MUTANTS = [
     ("the ring header does not advance", None, "cache_update", "cache.head = (head + admitted) % cache.capacity if cache.capacity else 0",
      "cache.head = head"),
     ("the ring does not wrap", None, "cache_update", "s = (head + admitted) % cache.capacity", "s = min(head + admitted, cache.capacity - 1)"),
-    ("admission beyond the capacity overwrites this update's own slots", None, "cache_update", "if admitted >= cache.capacity:", "if False:"),
+    ("admission beyond the capacity overwrites this update's own slots", None, "cache_update", "if len(candidates) > room:", "if False:"),
+    ("the rows that save least are preferred", None, "cache_update", "(-worth(j), j)", "(worth(j), j)"),
+    ("equal estimates go to the higher positions", None, "cache_update", "(-worth(j), j)", "(-worth(j), -j)"),
+    ("the admission budget is ignored", None, "cache_update", "min(int(budget), cache.capacity)", "cache.capacity"),
+    ("the admission budget may exceed the ring", None, "cache_update", "min(int(budget), cache.capacity)", "int(budget)"),
+    ("estimates are compared beyond their saturation point", None, "cache_update", "min(int(saving[j]), SAVING_MAX)", "int(saving[j])"),
+    ("the chosen rows are written in order of their estimate", None, "cache_update",
+     "    for j in candidates:\n        if j not in chosen:\n            dropped += 1\n            continue\n",
+     "    dropped += len(candidates) - len(chosen)\n    for j in sorted(chosen, key=lambda j: (-worth(j), j)) if len(candidates) > room else candidates:\n"),
+    ("a cached node counts its whole subtree", None, "access_estimate", "if hit[j]:", "if False:"),
+    ("a cached node counts nothing", None, "access_estimate", "out[j] = 1\n", "out[j] = 0\n"),
+    ("a node's own row of the layer below is not counted", None, "access_estimate", "total = 1 if below is None else int(below[j])", "total = 0"),
+    ("a node's own row counts one read at every layer", None, "access_estimate", "total = 1 if below is None else int(below[j])", "total = 1"),
+    ("neighbours count one read each at every layer", None, "access_estimate", "total += 1 if below is None else int(below[col[c]])", "total += 1"),
+    ("neighbours are looked up by edge number", None, "access_estimate", "int(below[col[c]])", "int(below[c % len(below)])"),
+    ("the estimate does not saturate", None, "access_estimate", "min(total, SAVING_MAX)", "total"),
+    ("the estimates of a layer feed its own update one layer off", None, "iteration", "saving=saving.get(l),", "saving=saving.get(l - 1) if l > 1 else saving.get(l),"),
+    ("the iteration ignores the budget", None, "iteration", "budget=None if admit_budget is None else admit_budget.get(l))", "budget=None)"),
     ("the wrong row is stored", None, "cache_update", "cache.store(s, h[j])", "cache.store(s, h[admitted])"),
     ("a normal row does not keep its own position live", None, "lookup_prune", "live_src[j] = True", "pass"),
     ("pruned nodes are looked up", None, "lookup_prune", "if not live[j]:\n            continue", "if False:\n            continue"),
