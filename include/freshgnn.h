@@ -402,6 +402,12 @@ fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t iter, cons
  *   ws_dev, ws_bytes    device workspace, >= the sum over the listed layers of
  *                       fg_workspace_bytes(FG_WS_CACHE_UPDATE, layers[i].n, 0); 16-byte aligned
  * Nothing is launched if any layer's arguments are rejected.
+ * Access-aware admission (the cache policy "for accuracy and performance" of Section 7.4, which prefers embeddings that
+ * save more memory access; the text defines neither the estimate nor the rule, so both are this library's reading): a
+ * layer admits at most min(max_admit, capacity) rows per update. If more pass the gradient rule, those with the largest
+ * saving_dev[position] (values above 2047 count as 2047) get in, among equal ones the lower positions; the admitted rows
+ * are still written in position order from the ring header, and stats_dev[3] counts the rows turned away. saving_dev
+ * NULL: all equal, i.e. the first max_admit in position order. One more launch when a layer uses it.
  */
 typedef struct fg_update_layer {
     int32_t layer;
@@ -413,9 +419,27 @@ typedef struct fg_update_layer {
     const void* h_dev;
     int64_t h_stride;
     int64_t* stats_dev;
+    const int32_t* saving_dev; /* access-aware admission: estimates by position (fg_access_estimate), or NULL */
+    int64_t max_admit;         /* rows this update may admit; 0 = the ring's capacity */
 } fg_update_layer_t;
 fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, float p_grad, int32_t n_layers,
                                 const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * The estimate the access-aware admission ranks by: the rows read to produce each node's embedding in this mini-batch,
+ * counted along the pruned block like a tree (no credit for neighbours shared with other rows). out[j] = 1 for a node
+ * served from the cache (hit_dev[j] != 0); otherwise below[j] + the sum of below[col[c]] over the neighbours left in row
+ * j, with below == NULL meaning the input layer (every row one read). Saturates at 2047. Call it bottom-up, layer 1
+ * first, after the top-down pass has pruned the blocks.
+ *   row_start_dev, row_end_dev [n], col_dev [nnz]   the layer's block after pruning (columns: positions in the layer below)
+ *   hit_dev [n]                                      the layer's hit flags, or NULL (no cache at this layer)
+ *   below_dev [n_src]                                estimates of the layer below by position, or NULL; n_src >= n
+ *   out_dev [n]                                      int32 estimates by position
+ * All pointers device memory; one launch, no host synchronisation.
+ */
+fg_status_t fg_access_estimate(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev, int64_t nnz,
+                               int32_t n, const uint8_t* hit_dev, const int32_t* below_dev, int32_t n_src, int32_t* out_dev,
+                               void* stream);
 
 /*
  * The fetch of cached embeddings (h_v = C^(l)[v], Algorithm 1) for every hit of every listed layer in one launch:

@@ -51,6 +51,7 @@ SIGNATURES = {
                                    _p, _i64, _i32, _p]),
     "fg_aggregate_gcn": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _p, _p, _p]),
     "fg_gather_aggregate_gcn": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _p, _i64, _i64, _i32, _p, _p, _p]),
+    "fg_access_estimate": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i32, _p, _p]),
     "fg_gather_aggregate_ids": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _p, _i64, _i64, _i32, _i32, _p, _i64, _i32, _p, _i64,
                                        _i32, _p, _i32, _p, _p]),
     "fg_linear": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _p, _i64, _i32, _i32, _p, _i32, _p, _i32, _p, _i32, _i64, _i32, _p]),
@@ -82,7 +83,7 @@ SIGNATURES["fg_top_down"] = (_i32, [_p, _i64, _i32, C.POINTER(TopDownLayer), _p,
 class UpdateLayer(C.Structure):
     """fg_update_layer_t"""
     _fields_ = [("layer", _i32), ("n", _i32), ("ids_dev", _p), ("live_dev", _p), ("hit_dev", _p), ("gnorm_dev", _p),
-                ("h_dev", _p), ("h_stride", _i64), ("stats_dev", _p)]
+                ("h_dev", _p), ("h_stride", _i64), ("stats_dev", _p), ("saving_dev", _p), ("max_admit", _i64)]
 
 
 class FetchLayer(C.Structure):
@@ -353,6 +354,10 @@ def update_layers(specs):
 def fetch_layers(specs):
     """ctypes array of fg_fetch_layer_t from dicts keyed by the field names."""
     return _struct_array(FetchLayer, specs)
+
+
+def fg_access_estimate(row_start, row_end, col, nnz, n, hit, below, n_src, out, stream=None):
+    _check(_lib.fg_access_estimate(ptr(row_start), ptr(row_end), ptr(col), nnz, n, ptr(hit), ptr(below), n_src, ptr(out), stream))
 
 
 def fg_cache_fetch_all(cache, layers, stream=None):

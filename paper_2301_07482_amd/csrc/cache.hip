@@ -24,6 +24,11 @@
 //                    hand out ring slots head + rank, write slot_node / slot_stamp / map, list (position, slot);
 //                    the last workgroup leaves the advanced header in the spare header cell
 //   5. row copy      table[slot] = h[position]
+// With the access-aware policy (a layer given estimates of saved accesses and a budget smaller than what is admissible;
+// Section 7.4 names the policy, the rule is this build's reading) launch 3 also histograms the estimates of the
+// admissible nodes and one more launch between 3 and 4 (rank_saving) finds the estimate of rank `room` from the top,
+// re-flags every admissible node as in / tie / out and counts per workgroup; launch 4 then lets the first ties in
+// position order fill what the larger estimates leave of the room.
 #include "common.h"
 #include "scan.h"
 
@@ -34,7 +39,11 @@ struct UpdHeader {        // lives at the start of a layer's update workspace
     int32_t mode;         // 0: nothing is below tau, 1: compare with tau_key, 2: everything is below tau
     int64_t n_admit;      // rows to copy (<= capacity)
     int64_t m_live;
+    int64_t n_cand;       // access-aware policy: admissible nodes, and how many of those whose estimate equals the
+    int64_t tie_room;     //   threshold estimate still fit (-1: every admissible node fits)
 };
+
+__device__ __forceinline__ int clamp_saving(int32_t a) { return a < 0 ? 0 : (a > 2047 ? 2047 : a); }
 
 __device__ __forceinline__ uint32_t order_key(float f) {
     const uint32_t b = __float_as_uint(f);
@@ -53,7 +62,10 @@ struct SelState {
     unsigned int hist1[SEL_BINS];
     unsigned int n_surv;
     unsigned int pad[3];
+    unsigned int hist2[SEL_BINS];  // estimates of saved accesses of the admissible nodes (access-aware policy)
 };
+
+static_assert(SEL_BINS == 2048, "clamp_saving saturates the estimates at the last bin");
 
 struct CacheRW {
     int32_t* map;
@@ -77,8 +89,11 @@ struct UpdLayer {
     int64_t* stats;
     SelState* sel;
     UpdHeader* hdr;
-    uint8_t* flag;       // admissible or not, per position
-    int32_t* blk;        // admissible per workgroup of launch 3
+    uint8_t* flag;       // per position: 0 not admitted, 1 admissible (in position order while there is room), 2 in for sure
+    int32_t* blk;        // flag-1 nodes per workgroup of launch 3
+    int32_t* blk_sure;   // flag-2 nodes per workgroup (access-aware policy)
+    const int32_t* saving;  // estimates of saved accesses by position, or NULL
+    int64_t room;        // rows this update may admit (<= capacity)
     int32_t* apos;       // admitted positions; before launch 4 the same memory holds the survivor keys
     int32_t* aslot;      // their slots
     const char* h;
@@ -301,6 +316,63 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void classify_update_kernel(UpdBatch
         L.blk[local] = n_admit;
         if (L.stats && n_evict) atomicAdd((unsigned long long*)&L.stats[1], (unsigned long long)n_evict);
     }
+    if (L.saving) {  // uniform over the layer
+        for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
+        __syncthreads();
+        if (admit) atomicAdd(&hist[clamp_saving(L.saving[j])], 1u);
+        __syncthreads();
+        for (int b = t; b < SEL_BINS; b += SEL_THREADS)
+            if (hist[b]) atomicAdd(&L.sel->hist2[b], hist[b]);
+    }
+}
+
+// Access-aware policy, between classify and assign_slots: with T admissible nodes and room for R < T of them, the R
+// largest estimates get in, equal estimates in position order. Every workgroup finds the threshold estimate a* (rank
+// T - R in ascending order) and how many nodes at a* still fit, then re-flags its nodes: above a* -> 2, at a* -> 1,
+// below -> 0. With T <= R the flags stay as they are.
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void rank_saving_kernel(UpdBatch B) {
+    __shared__ unsigned int hist[SEL_BINS];
+    __shared__ long long red[16];
+    __shared__ uint32_t s_bin;
+    __shared__ long long s_rank;
+    int local;
+    const UpdLayer& L = B.l[layer_of_block(B.scan_first, B.n_layers, blockIdx.x, local)];
+    if (!L.saving) return;
+    const int t = threadIdx.x;
+    const int j = local * FG_SCAN_BLOCK + t;
+    const bool cand = j < L.n && L.flag[j] != 0;
+    const int a_j = cand ? clamp_saving(L.saving[j]) : 0;
+    for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = L.sel->hist2[b];
+    __syncthreads();
+    long long c = 0;
+#pragma unroll
+    for (int q = 0; q < SEL_BPT; ++q) c += hist[SEL_BPT * t + q];
+    const long long T = fg_block_sum(c, red);
+    if (T <= L.room) {
+        if (local == 0 && t == 0) {
+            L.hdr->n_cand = T;
+            L.hdr->tie_room = -1;
+        }
+        if (t == 0) L.blk_sure[local] = 0;
+        return;
+    }
+    if (t == 0) s_rank = T - L.room;
+    __syncthreads();
+    select_bin(hist, red, &s_bin, &s_rank);
+    const int a_star = (int)s_bin;
+    const long long tie_room = (long long)hist[a_star] - s_rank;  // nodes at a* that get in
+    const bool sure = cand && a_j > a_star, tie = cand && a_j == a_star;
+    if (cand) L.flag[j] = sure ? 2 : (tie ? 1 : 0);
+    const int n_sure = __syncthreads_count(sure);
+    const int n_tie = __syncthreads_count(tie);
+    if (t == 0) {
+        L.blk_sure[local] = n_sure;
+        L.blk[local] = n_tie;
+        if (local == 0) {
+            L.hdr->n_cand = T;
+            L.hdr->tie_room = tie_room;
+        }
+    }
 }
 
 __global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(UpdBatch B) {
@@ -315,16 +387,34 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(UpdBatch B)
         for (int i = threadIdx.x; i < (int)(sizeof(SelState) / 4); i += FG_SCAN_BLOCK) ((unsigned int*)L.sel)[i] = 0;
     // this thread's element and the ring header first: in flight while the preceding workgroups' counts are added up
     const int j = local * FG_SCAN_BLOCK + threadIdx.x;
-    const bool admit = j < L.n && L.flag[j] != 0;
+    const uint8_t flag_j = j < L.n ? L.flag[j] : (uint8_t)0;
     const int32_t v_j = j < L.n ? L.ids[j] : -1;
     const int64_t head = *c.head;
     long long before = 0;
     for (int b = threadIdx.x; b < local; b += FG_SCAN_BLOCK) before += L.blk[b];
     before = fg_block_sum(before, red);
     int total;
-    const long long rank = before + fg_block_rank(admit, total, sc);
+    long long rank = before + fg_block_rank(flag_j == 1, total, sc);  // among the flag-1 nodes, in position order
+    long long room = L.room, n_cand = -1, sure_all = 0;
+    bool admit = flag_j == 1 && rank < room;
+    if (L.saving) {  // uniform over the layer: flag-2 nodes are in, flag-1 nodes share what is left of the room
+        const long long tie_room = L.hdr->tie_room;
+        n_cand = L.hdr->n_cand;
+        if (tie_room >= 0) {
+            long long sure_before = 0;
+            for (int b = threadIdx.x; b < local; b += FG_SCAN_BLOCK) sure_before += L.blk_sure[b];
+            sure_before = fg_block_sum(sure_before, red);
+            int sure_total;
+            const long long sure_rank = sure_before + fg_block_rank(flag_j == 2, sure_total, sc);
+            const long long ties_in = rank < tie_room ? rank : tie_room;  // ties admitted before this position
+            admit = flag_j == 2 || (flag_j == 1 && rank < tie_room);
+            rank = sure_rank + ties_in;
+            room = tie_room;
+            sure_all = sure_before + sure_total;
+        }
+    }
     bool overwrote = false;
-    if (admit && rank < c.capacity) {
+    if (admit) {
         const int32_t s = (int32_t)((head + rank) % c.capacity);
         const int32_t v = v_j;
         const int32_t old = c.slot_node[s];
@@ -342,8 +432,9 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(UpdBatch B)
     if (threadIdx.x == 0) {
         if (L.stats && n_over) atomicAdd((unsigned long long*)&L.stats[2], (unsigned long long)n_over);
         if (local == n_local - 1) {
-            const long long all = before + total;
-            const long long in = all < c.capacity ? all : c.capacity;
+            const long long ties = before + total;
+            const long long in = sure_all + (ties < room ? ties : room);
+            const long long all = n_cand >= 0 ? n_cand : ties;
             L.hdr->n_admit = in;
             *c.head_next = (head + in) % c.capacity;
             const int64_t reach = head + in;  // the ring fills slots upwards until it first wraps
@@ -360,7 +451,7 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void assign_slots_kernel(UpdBatch B)
 }
 
 struct UpdWs {
-    size_t hdr, flag, blk, pos, slot, total;
+    size_t hdr, flag, blk, blk_sure, pos, slot, total;
 };
 UpdWs upd_layout(int64_t n) {
     UpdWs w;
@@ -368,7 +459,8 @@ UpdWs upd_layout(int64_t n) {
     w.hdr = 0;
     w.flag = 256;
     w.blk = w.flag + fg_align_up((size_t)n, 256);
-    w.pos = w.blk + fg_align_up((size_t)nb * 4, 256);
+    w.blk_sure = w.blk + fg_align_up((size_t)nb * 4, 256);
+    w.pos = w.blk_sure + fg_align_up((size_t)nb * 4, 256);
     w.slot = w.pos + fg_align_up((size_t)n * 4, 256);
     w.total = w.slot + fg_align_up((size_t)n * 4, 256);
     return w;
@@ -614,7 +706,7 @@ namespace {
 fg_status_t prepare_update_layer(fg_cache_t* cache, const char* who, int32_t layer, int64_t iter, const int32_t* ids_dev,
                                  int32_t n, const uint8_t* live_dev, const uint8_t* hit_dev, const float* gnorm_dev,
                                  float p_grad, const void* h_dev, int64_t h_stride, int64_t* stats_dev, char* ws,
-                                 UpdLayer* out) {
+                                 UpdLayer* out, const int32_t* saving_dev = nullptr, int64_t max_admit = 0) {
     const fg_layer* lc;
     fg_status_t rc = layer_of(cache, layer, who, &lc);
     if (rc != FG_OK) return rc;
@@ -627,6 +719,7 @@ fg_status_t prepare_update_layer(fg_cache_t* cache, const char* who, int32_t lay
     if (((uintptr_t)h_dev | (uintptr_t)h_stride) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_dev and h_stride must be 16-byte aligned", who);
     if (iter < l->last_iter) FG_FAIL(FG_ERR_STATE, "%s: iteration %lld after %lld: the counter must not go backwards", who, (long long)iter, (long long)l->last_iter);
     if (iter < 0 || iter > INT32_MAX - 1) FG_FAIL(FG_ERR_INVALID_ARG, "%s: iteration %lld out of range", who, (long long)iter);
+    if (max_admit < 0) FG_FAIL(FG_ERR_INVALID_ARG, "%s: max_admit = %lld is negative", who, (long long)max_admit);
     const UpdWs w = upd_layout(n);
     UpdLayer& u = *out;
     u.c = CacheRW{l->map, l->slot_node, l->slot_stamp, l->head + l->head_cur, l->head + (l->head_cur ^ 1), l->head + 2, l->capacity, cache->num_nodes, iter, cache->t_stale};
@@ -639,6 +732,9 @@ fg_status_t prepare_update_layer(fg_cache_t* cache, const char* who, int32_t lay
     u.hdr = (UpdHeader*)(ws + w.hdr);
     u.flag = (uint8_t*)(ws + w.flag);
     u.blk = (int32_t*)(ws + w.blk);
+    u.blk_sure = (int32_t*)(ws + w.blk_sure);
+    u.room = (max_admit > 0 && max_admit < l->capacity) ? max_admit : l->capacity;
+    u.saving = (n > 0 && u.room < n) ? saving_dev : nullptr;  // with room for every node of the layer the estimates decide nothing
     u.apos = (int32_t*)(ws + w.pos);
     u.aslot = (int32_t*)(ws + w.slot);
     u.h = (const char*)h_dev;
@@ -665,6 +761,12 @@ fg_status_t launch_update(UpdBatch& B, hipStream_t st) {
     FG_LAUNCH_CHECK("update_digit1_kernel");
     hipLaunchKernelGGL(classify_update_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
     FG_LAUNCH_CHECK("classify_update_kernel");
+    bool ranked = false;
+    for (int i = 0; i < B.n_layers; ++i) ranked |= B.l[i].saving != nullptr;
+    if (ranked) {
+        hipLaunchKernelGGL(rank_saving_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
+        FG_LAUNCH_CHECK("rank_saving_kernel");
+    }
     hipLaunchKernelGGL(assign_slots_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
     FG_LAUNCH_CHECK("assign_slots_kernel");
     fg_row_copy_batch copies;  // table[aslot[k], :] = h[apos[k], :] for the admitted rows of every layer
@@ -717,7 +819,8 @@ extern "C" fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, floa
                 FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update_all: layer %d is listed twice", layers[i].layer);
         const fg_update_layer_t& a = layers[i];
         fg_status_t rc = prepare_update_layer(cache, "fg_cache_update_all", a.layer, iter, a.ids_dev, a.n, a.live_dev, a.hit_dev,
-                                              a.gnorm_dev, p_grad, a.h_dev, a.h_stride, a.stats_dev, (char*)ws_dev + off, &B.l[i]);
+                                              a.gnorm_dev, p_grad, a.h_dev, a.h_stride, a.stats_dev, (char*)ws_dev + off, &B.l[i],
+                                              a.saving_dev, a.max_admit);
         if (rc != FG_OK) return rc;
         off += upd_layout(a.n).total;
     }
@@ -732,6 +835,58 @@ extern "C" fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, floa
         l->last_iter = iter;
         l->head_cur ^= 1;
     }
+    return FG_OK;
+}
+
+// ---- estimate of saved accesses (input of the access-aware admission) -------------------------------------------
+
+namespace {
+
+constexpr int EST_THREADS = 256;
+
+// One thread per row of a pruned block: 1 for a node served from the cache; otherwise what its own row of the layer
+// below and each remaining neighbour read (1 each when the layer below is the input layer). Saturates at 2047.
+__global__ __launch_bounds__(EST_THREADS) void access_estimate_kernel(const int32_t* __restrict__ row_start,
+                                                                      const int32_t* __restrict__ row_end,
+                                                                      const int32_t* __restrict__ col, int64_t nnz, int n,
+                                                                      const uint8_t* __restrict__ hit,
+                                                                      const int32_t* __restrict__ below, int n_src,
+                                                                      int32_t* __restrict__ out) {
+    const int j = blockIdx.x * EST_THREADS + threadIdx.x;
+    if (j >= n) return;
+    if (hit && hit[j]) {
+        out[j] = 1;
+        return;
+    }
+    int64_t b = row_start[j], e = row_end[j];
+    if (b < 0) b = 0;
+    if (e > nnz) e = nnz;
+    int64_t total = below ? (j < n_src ? clamp_saving(below[j]) : 0) : 1;
+    for (int64_t c = b; c < e; ++c) {
+        if (below) {
+            const int32_t u = col[c];
+            if (u >= 0 && u < n_src) total += clamp_saving(below[u]);
+        } else {
+            total += 1;
+        }
+    }
+    out[j] = total > 2047 ? 2047 : (int32_t)total;
+}
+
+}  // namespace
+
+extern "C" fg_status_t fg_access_estimate(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
+                                          int64_t nnz, int32_t n, const uint8_t* hit_dev, const int32_t* below_dev,
+                                          int32_t n_src, int32_t* out_dev, void* stream) {
+    if (n < 0 || nnz < 0 || n_src < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_access_estimate: negative size");
+    if (n > 0 && (!row_start_dev || !row_end_dev || !out_dev || (nnz > 0 && !col_dev)))
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_access_estimate: NULL pointer");
+    if (below_dev && n_src < n) FG_FAIL(FG_ERR_SHAPE, "fg_access_estimate: the layer below has %d nodes, fewer than this layer's %d", n_src, n);
+    fg_clear_error();
+    if (n == 0) return FG_OK;
+    hipLaunchKernelGGL(access_estimate_kernel, dim3((unsigned)fg_ceil_div(n, EST_THREADS)), dim3(EST_THREADS), 0, (hipStream_t)stream,
+                       row_start_dev, row_end_dev, col_dev, nnz, n, hit_dev, below_dev, n_src, out_dev);
+    FG_LAUNCH_CHECK("access_estimate_kernel");
     return FG_OK;
 }
 

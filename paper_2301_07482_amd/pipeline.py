@@ -63,7 +63,7 @@ class HotPath:
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
                  one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage", fuse_small_layers=False,
-                 fetch_with_loader=True):
+                 fetch_with_loader=True, admit_budget=None):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -107,6 +107,7 @@ class HotPath:
             self.MEANPOS = torch.zeros(max(n[l] * (dims[l - 1] // 2) for l in range(1, L + 1)), dtype=torch.float32, device=dev)
         self.live = [torch.zeros(n[l], dtype=torch.uint8, device=dev) for l in range(L + 1)]
         self.hit = [torch.zeros(n[l], dtype=torch.uint8, device=dev) for l in range(L + 1)]
+        self.saving = [torch.zeros(n[l] if admit_budget else 0, dtype=torch.int32, device=dev) for l in range(L + 1)]
         self.hit_pos = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
         self.hit_slot = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
         self.normal_pos = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
@@ -128,6 +129,8 @@ class HotPath:
         self.update_all = update_all
         self.fetch_all = fetch_all   # the cached rows of all layers are fetched by one call right after the top-down pass
         self.fetch_with_loader = fetch_with_loader  # ... or inside the id-column loader's launch, where that loader runs
+        self.admit_budget = dict(admit_budget) if admit_budget else None   # {layer: rows per update}: access-aware admission
+        assert not (self.admit_budget and not update_all), "the access-aware admission needs fg_cache_update_all"
         self.ws_upd_bytes = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L))
         self.ws_upd = torch.zeros(self.ws_upd_bytes + 256, dtype=torch.uint8, device=dev)
         self.W = {}
@@ -329,10 +332,17 @@ class HotPath:
                                                 self.dW[l], self.db[l], self.ws_wg, self.ws_wg_bytes, st)
         # ---- update of the caches
         if do_update and self.update_all:
+            if self.admit_budget:   # access-aware admission: the estimates, bottom-up over the pruned blocks
+                tick("access_estimate")
+                for l in range(1, L):
+                    B.fg_access_estimate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.hit[l],
+                                         self.saving[l - 1] if l > 1 else None, bt.n[l - 1], self.saving[l], st)
             tick("cache_update_all")
             specs = [dict(layer=l, n=bt.n[l], ids_dev=bt.ids[l], live_dev=self.live[l], hit_dev=self.hit[l],
                           gnorm_dev=gnorm[l], h_dev=self.H[l], h_stride=self.dims[l] * esz[self.h_code[l]],
-                          stats_dev=self.stats.data_ptr() + l * 32) for l in range(1, L)]
+                          stats_dev=self.stats.data_ptr() + l * 32,
+                          saving_dev=self.saving[l] if self.admit_budget else None,
+                          max_admit=int(self.admit_budget.get(l, 0)) if self.admit_budget else 0) for l in range(1, L)]
             B.fg_cache_update_all(self.cache, it, self.p_grad, B.update_layers(specs), self.ws_upd, self.ws_upd_bytes, st)
         elif do_update:
             for l in range(1, L):
@@ -399,7 +409,7 @@ class HotPath:
 
 def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None, p_grad=None, fused_input=False, one_launch_top_down=True, update_all=True, log_ring=256,
                  hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage",
-                 fetch_with_loader=True):
+                 fetch_with_loader=True, admit_budget=None):
     """HotPath for workload `w` with its feature table resident where the workload says."""
     from fg_inputs import device as fdev, workload as wl
     dims = wl.layer_dims(w)
@@ -413,7 +423,7 @@ def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None
                  w.feat_dtype, w.compute_dtype, weights, features_on_host=(w.feat_location == "host"),
                  use_cache=use_cache, fused_input=fused_input, one_launch_top_down=one_launch_top_down, update_all=update_all,
                  fetch_all=update_all, log_ring=log_ring, hot_ids=hot_ids, buffer_bytes=buffer_bytes, backward=backward, weight_grads=weight_grads, stabilization=stabilization, model=model,
-                 fetch_with_loader=fetch_with_loader)
+                 fetch_with_loader=fetch_with_loader, admit_budget=admit_budget)
     return hp, weights, feat_table
 
 

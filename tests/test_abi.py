@@ -88,6 +88,9 @@ def test_argument_validation_needs_no_gpu(B):
                 B.FG_F32) == B.FG_ERR_INVALID_ARG                                                           # no row ids
     assert code(B.fg_gather_aggregate_ids, 4096, 4096, 4096, 5, 5, None, None, 5, 4096, 4096, 9, 512, 128, B.FG_F32, 4096, 512,
                 B.FG_F32, cache=None, fetch_layers=B.fetch_layers([dict(layer=1)])) == B.FG_ERR_INVALID_ARG # a fetch needs a cache
+    assert code(B.fg_access_estimate, None, 4096, 4096, 5, 5, None, None, 9, 4096) == B.FG_ERR_INVALID_ARG         # no row starts
+    assert code(B.fg_access_estimate, 4096, 4096, 4096, 5, 5, None, 4096, 3, 4096) == B.FG_ERR_SHAPE             # layer below smaller
+    assert code(B.fg_access_estimate, 4096, 4096, 4096, 5, -1, None, None, 9, 4096) == B.FG_ERR_INVALID_ARG
     assert B.fg_cache_feature_rows(None) == 0 and B.fg_cache_buffer(None) == (None, 0) and B.fg_cache_ring_offset(None, 1) == -1
     assert code(B.fg_softmax_xent_grad, None, 64, 4096, 4, 16, 4096, 64) == B.FG_ERR_INVALID_ARG
     assert code(B.fg_softmax_xent_grad, 4096, 32, 4096, 4, 16, 4096, 64) == B.FG_ERR_SHAPE                     # stride < row

@@ -417,6 +417,91 @@ def test_update_all_and_fetch_all_with_unequal_and_empty_layers(env):
         B.fg_cache_destroy(cache)
 
 
+# ------------------------------------------------------------------------------------------------ access-aware admission
+
+@pytest.mark.parametrize("n,n_src,max_deg,seed", [(0, 5, 3, 0), (1, 1, 0, 1), (700, 3000, 12, 2), (5000, 40000, 30, 3), (300, 300, 2500, 4)])
+def test_access_estimate_matches_oracle(env, n, n_src, max_deg, seed):
+    """fg_access_estimate against the oracle, bit for bit: the input layer below (NULL) and estimates below, hits,
+    pruned rows, saturation (rows of up to 2500 neighbours and estimates beyond 2047 below)."""
+    torch, B = env
+    r = np.random.default_rng(seed)
+    deg = r.integers(0, max_deg + 1, size=n)
+    gap = r.integers(0, 3, size=n)                                   # unused columns between rows, as pruning leaves them
+    start = (np.cumsum(deg + gap) - deg - gap).astype(np.int32)
+    end = (start + deg).astype(np.int32)
+    pruned = r.random(n) < 0.2
+    end[pruned] = start[pruned]
+    nnz = int((deg + gap).sum())
+    col = r.integers(0, max(n_src, 1), size=nnz).astype(np.int32)
+    hit = r.random(n) < 0.25
+    for below in (None, r.integers(1, 40, size=n_src).astype(np.int32), r.integers(1, 5000, size=n_src).astype(np.int32)):
+        want = O.access_estimate(start, end, col, hit, below)
+        out = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
+        B.fg_access_estimate(dev(torch, start) if n else None, dev(torch, end) if n else None, dev(torch, col) if nnz else None, nnz, n,
+                             dev(torch, hit.astype(np.uint8)) if n else None, None if below is None else dev(torch, below), n_src, out)
+        assert np.array_equal(out.cpu().numpy()[:n], want)
+        if n:      # no hit flags: every row is computed
+            want = O.access_estimate(start, end, col, np.zeros(n, dtype=bool), below)
+            B.fg_access_estimate(dev(torch, start), dev(torch, end), dev(torch, col) if nnz else None, nnz, n, None,
+                                 None if below is None else dev(torch, below), n_src, out)
+            assert np.array_equal(out.cpu().numpy()[:n], want)
+
+
+def test_access_aware_admission_matches_oracle(env):
+    """fg_cache_update_all with estimates and budgets against the oracle's rule, three layers in one call: a budget that
+    changes every update with few distinct estimates (many ties at the threshold), estimates beyond the saturation point
+    with only the ring's capacity as the limit, and a budget without estimates (position order). Cache state, statistics
+    and stored rows, bit for bit."""
+    torch, B = env
+    from paper_2301_07482_amd.pipeline import _tensor_from_ptr
+    r = np.random.default_rng(91)
+    N, dims, caps, t_stale, p = 30000, [8, 16, 4], [4000, 900, 300], 3, 0.8
+    oc = [O.HistoricalCache(N, caps[k], dims[k], t_stale) for k in range(3)]
+    cache = B.fg_cache_create(N, caps, dims, B.FG_F32, t_stale, None)
+    turned_away = [0, 0, 0]
+    try:
+        for i in range(14):
+            ns = [int(r.integers(2000, 9000)), int(r.integers(1500, 3000)), int(r.integers(0, 700)) if i % 4 else 0]
+            ids = [r.permutation(N)[:n].astype(np.int32) for n in ns]
+            live = [r.random(n) < 0.85 for n in ns]
+            gn = [np.round(np.exp(r.standard_normal(n)), 2).astype(np.float32) for n in ns]
+            rows = [r.standard_normal((n, dims[k])).astype(np.float32) for k, n in enumerate(ns)]
+            saving = [r.integers(1, 9, size=ns[0]).astype(np.int32), r.integers(0, 6000, size=ns[1]).astype(np.int32), None]
+            budget = [int(r.integers(1, 3000)) if i % 5 else 10 ** 6, None, int(r.integers(1, 200))]
+            look = [O.lookup_prune(oc[k], i, ids[k], live[k], None, None, None, 0) for k in range(3)]
+            t_ids = [dev(torch, a) if a.size else torch.zeros(1, dtype=torch.int32, device="cuda") for a in ids]
+            t_live = [dev(torch, a.astype(np.uint8)) if a.size else torch.zeros(1, dtype=torch.uint8, device="cuda") for a in live]
+            t_hit = [dev(torch, look[k]["hit"].astype(np.uint8)) if ns[k] else torch.zeros(1, dtype=torch.uint8, device="cuda") for k in range(3)]
+            t_rows = [dev(torch, a) if a.size else torch.zeros((1, dims[k]), device="cuda") for k, a in enumerate(rows)]
+            t_gn = [dev(torch, a) if a.size else torch.zeros(1, device="cuda") for a in gn]
+            t_sav = [None if a is None else dev(torch, a) for a in saving]
+            t_stats = torch.zeros((3, 4), dtype=torch.int64, device="cuda")
+            wsb = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n) for n in ns)
+            ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
+            B.fg_cache_update_all(cache, i, p, B.update_layers([dict(layer=k + 1, n=ns[k], ids_dev=t_ids[k], live_dev=t_live[k],
+                                                                     hit_dev=t_hit[k], gnorm_dev=t_gn[k], h_dev=t_rows[k],
+                                                                     h_stride=dims[k] * 4, stats_dev=t_stats[k].data_ptr(),
+                                                                     saving_dev=t_sav[k], max_admit=budget[k] or 0)
+                                                                for k in range(3)]), ws, wsb, None)
+            stats = t_stats.cpu().numpy().tolist()
+            for k in range(3):
+                st = O.cache_update(oc[k], i, ids[k], live[k], look[k]["hit"], gn[k], p, rows[k], saving=saving[k], budget=budget[k])
+                assert stats[k] == [st["admitted"], st["evicted_by_gradient"], st["overwritten"], st["dropped_overflow"]], \
+                    f"stats of layer {k + 1} at iteration {i}: {stats[k]} {st}"
+                turned_away[k] += st["dropped_overflow"]
+                exp = _export(torch, B, cache, caps[k], i + 1, layer=k + 1)
+                valid = oc[k].valid_entries(i + 1)
+                assert exp["head"] == oc[k].head
+                assert dict(zip(exp["nodes"].tolist(), zip(exp["slots"].tolist(), exp["stamps"].tolist()))) == valid
+                tab = _tensor_from_ptr(B.fg_cache_table(cache, k + 1), (caps[k], dims[k]), torch.float32, caps[k] * dims[k] * 4,
+                                       "cuda").cpu().numpy()
+                for v, (s, _) in valid.items():
+                    assert np.array_equal(tab[s], oc[k].table[s])
+        assert all(t > 0 for t in turned_away), turned_away
+    finally:
+        B.fg_cache_destroy(cache)
+
+
 @pytest.mark.parametrize("d_in,d_out,n,n_src,max_deg,relu,seed", [(256, 256, 1024, 6000, 5, False, 0), (64, 64, 256, 1500, 10, True, 1),
                                                                  (128, 96, 700, 700, 3, True, 2), (256, 256, 4000, 9000, 10, True, 3),
                                                                  (24, 40, 50, 90, 4, False, 4), (32, 32, 1, 5, 0, True, 5)])
@@ -571,7 +656,7 @@ def test_iterations_large_hbm_full_size_with_backward_pass(env):
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
                         backward=False, stabilization=0, model="sage", conditioned=False, col_ids=False,
-                        fetch_with_loader=True):
+                        fetch_with_loader=True, admit_budget=None):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
@@ -592,7 +677,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                                              fused_input=fused, one_launch_top_down=one_launch_top_down,
                                              update_all=one_launch_top_down, hot_ids=hot,
                                              buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward, stabilization=stabilization, model=model,
-                                             fetch_with_loader=fetch_with_loader)
+                                             fetch_with_loader=fetch_with_loader, admit_budget=admit_budget)
     from paper_2301_07482_amd import binding as FGB
     bc = None
     if fs:
@@ -636,7 +721,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                     f"feature-side ranks, iteration {it}"
                 assert found == int((ranks >= 0).sum())
             rec = O.iteration(mb, it, caches, frows, weights, gn, p, dims, w.feat_dtype, w.compute_dtype, feature_side=bc,
-                              labels=labels, update=not backward, stabilization=stabilization, model=model)
+                              labels=labels, update=not backward, stabilization=stabilization, model=model,
+                              admit_budget=admit_budget)
             served += int(rec["feature_from_buffer"].sum())
             # device cache rows at the slots about to be hit, read before this iteration's update recycles slots
             pre_rows = {l: hp.cache_rows(l, rec["look"][l]["hit_slot"]) for l in range(1, L) if len(rec["look"][l]["hit_pos"])}
@@ -757,6 +843,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                         assert np.array_equal(got, pre_rows[l])
                         assert conditioned or T.rel_err_rows(got, rec["H"][l][hpos].astype(np.float32)) <= tol * l
             for l in range(1, L):
+                if admit_budget and it >= stabilization:      # the estimates the update ranked by
+                    assert np.array_equal(hp.saving[l][:len(mb.ids[l])].cpu().numpy(), rec["saving"][l]), f"estimates, iteration {it} layer {l}"
                 st = rec["stats"][l]
                 assert snap["stats"][l].tolist() == [st["admitted"], st["evicted_by_gradient"], st["overwritten"],
                                                      st["dropped_overflow"]], f"update stats, iteration {it} layer {l}"
@@ -1035,6 +1123,18 @@ def test_iterations_fused_input_with_node_ids_as_block_columns(env):
         assert run_workload_parity(torch, wl.WORKLOADS["tiny"], 10, fused=True, col_ids=True, fetch_with_loader=ride)[0] > 0
         assert run_workload_parity(torch, wl.WORKLOADS["medium"], 4, check_numeric_every=2, sample_rows=20000, fused=True, col_ids=True,
                                    fetch_with_loader=ride)[0] > 0
+
+
+def test_iterations_access_aware_admission(env):
+    """Whole iterations with the access-aware admission on both sides: estimates, admitted sets, cache state and outputs.
+    Budgets small enough that rows are turned away in every update; two and three layers; with the fused loader."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    assert run_workload_parity(torch, w, w.iterations, admit_budget={1: 40})[0] > 0
+    assert run_workload_parity(torch, w, 12, fused=True, col_ids=True, admit_budget={1: 150}, t_stale=6, p_grad=0.9)[0] > 0
+    w = wl.WORKLOADS["medium"]
+    assert run_workload_parity(torch, w, 5, check_numeric_every=2, sample_rows=20000, fused=True, col_ids=True,
+                               admit_budget={1: 3000, 2: 400}, p_grad=0.9)[0] > 0
 
 
 def test_iterations_medium_fused_input(env):
