@@ -74,6 +74,12 @@ def main():
     ap.add_argument("--block-positions", action="store_true",
                     help="give the fused loader block 1 with positions as columns (fg_gather_aggregate) instead of node ids "
                          "(fg_gather_aggregate_ids)")
+    ap.add_argument("--cache-slots", type=int, default=None, help="override the workload's slots per cached layer (not the headline configuration)")
+    ap.add_argument("--access-aware", action="store_true",
+                    help="access-aware admission: every update admits at most capacity / t_stale rows per layer, those with "
+                         "the largest estimate of saved row reads first (fg_access_estimate, fg_cache_update_all)")
+    ap.add_argument("--admit-budget", default=None, metavar="ROWS[,ROWS...]",
+                    help="access-aware admission with these budgets for layers 1, 2, ... instead of capacity / t_stale")
     ap.add_argument("--separate-fetch", action="store_true",
                     help="fetch the cached embeddings with a launch of their own (fg_cache_fetch_all) instead of inside the "
                          "id-column loader's launch")
@@ -94,11 +100,17 @@ def main():
     if args.scale > 1:
         w = w.scaled(args.scale)
         wl.WORKLOADS[w.name] = w
-    if args.t_stale is not None or args.p_grad is not None:
+    if args.t_stale is not None or args.p_grad is not None or args.cache_slots is not None:
         import dataclasses
         w = dataclasses.replace(w, name=w.name + "/policy", t_stale=w.t_stale if args.t_stale is None else args.t_stale,
-                                p_grad=w.p_grad if args.p_grad is None else args.p_grad)
+                                p_grad=w.p_grad if args.p_grad is None else args.p_grad,
+                                cache_capacity=w.cache_capacity if args.cache_slots is None else args.cache_slots)
         wl.WORKLOADS[w.name] = w
+    admit_budget = None
+    if args.admit_budget:
+        admit_budget = {l + 1: int(v) for l, v in enumerate(args.admit_budget.split(","))}
+    elif args.access_aware:      # what a ring of this size can hold for a whole staleness window
+        admit_budget = {l: max(1, -(-w.cache_capacity // max(w.t_stale, 1))) for l in range(1, w.num_layers)}
     total = args.warmup + args.steps
     extra = min(args.steps, 20)        # further mini-batches for the per-call breakdown pass after the timed region
     t0 = time.time()
@@ -119,7 +131,7 @@ def main():
         buffer_bytes = -(-(G.rings_bytes(w) + len(hot) * row) // 256) * 256
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + extra + 32,
                                        hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads, model=args.model,
-                                       fetch_with_loader=not args.separate_fetch)
+                                       fetch_with_loader=not args.separate_fetch, admit_budget=admit_budget)
     if args.one_launch_seed_layer:
         hp.fuse_small_layers = hp.model == "sage" and not hp.weight_grads
     ids_cols = not args.block_positions and not args.no_fuse
@@ -397,6 +409,7 @@ def main():
                      "io_saving_embeddings_only": 1.0 - n_input / rows_no_cache if rows_no_cache else 0.0,
                      "input_rows_sampled": n0_all,
                      "hits": hits, "gather_bytes": gather_bytes, "linear_flops": lin_flops},
+        "admit_budget": admit_budget,
         "host": {"sampling_s": t_sample, "setup_s": t_setup},
     }
     print(json.dumps(out))

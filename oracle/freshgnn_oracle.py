@@ -18,6 +18,8 @@ once to the storage type:
   backward   (Alg. 1, the loss and loss.backward() lines; Section 4.1.1: the embedding gradients whose norms
              drive admission and check-out): `softmax_xent_grad`, `layer_backward`, `row_norms`, `backward`;
              `iteration(..., labels=...)` takes the gradient norms from it instead of from the caller
+  access-aware admission (Section 7.4 names a policy that prefers embeddings saving more memory access, without
+             a rule): `access_estimate`, `cache_update(..., saving=, budget=)`, `iteration(..., admit_budget=...)`
 
 Where the paper leaves something open (the Update procedure has no printed body;
 mini-batch layout; percentile ties; slot capacity) the reading taken is stated in
@@ -31,6 +33,9 @@ Section 4.1.3; for the shared buffer a byte-by-byte model of what has been overw
 a hand-worked displacement trace, and the bit-identity of every loaded feature row; for the backward
 pass central finite differences of the loss through the forward functions of this file. The I/O-saving percentages the paper reports depend on its
 datasets and real gradients: parity unpinned for those, they are not reproduced.
+The access-aware admission is pinned to the reading stated in `access_estimate` and `cache_update` (an
+instrumented recursive evaluation that counts the rows it reads, closed forms on full trees, the rank definition
+of "the B largest", the dictionary model); against the paper it is parity unpinned: the paper gives no rule.
 """
 import numpy as np
 
