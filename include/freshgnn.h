@@ -426,6 +426,37 @@ fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, float p_grad, i
                                 const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream);
 
 /*
+ * Neighbour sampling of one block on the device (uniform sampling with a fan-out per layer, Section 7.1; the paper samples
+ * on CPU threads, Section 5, so the scheme below is this library's): from the nodes of layer `layer` to block `layer`
+ * and the node list of the layer below, over an in-neighbour CSR in device-visible memory.
+ * For node v with degree d: slots 0..d-1 if d <= fanout, otherwise slot j = floor((j + u_j) * (d / fanout)) in double
+ * precision, clipped to d-1, for j = 0..fanout-1 (one slot from each of `fanout` equal strata), with u_j the top 53 bits of
+ * w(w(w(mix(key), layer), v), j), w(k, c) = mix(k + (c + 1) * 0x9E3779B97F4A7C15) and mix the SplitMix64 output function.
+ * The row keeps the neighbours at those slots in slot order, without v itself and without repeats. The layer below is this
+ * layer's nodes followed by the neighbours not among them, each once, in order of first occurrence (rows in order, slots
+ * in order). The result is a pure function of the arguments.
+ *   indptr_dev [num_nodes + 1] int64, indices_dev [num_edges] int32   in-neighbours of v: indices[indptr[v] .. indptr[v+1])
+ *   ids_dev [max_rows], n_dev, max_rows   distinct node ids of the layer; device-side count (NULL = max_rows) and its
+ *                                         host-side bound; fanout in 1..32
+ *   row_start_dev, row_end_dev [max_rows] out: rows back to back, rows at and beyond the count are empty
+ *   col_dev [max_rows * fanout]           out: positions in the layer below
+ *   col_ids_dev [max_rows * fanout]       out, optional (NULL): the same columns as node ids
+ *   ids_below_dev [max_below]             out: node ids of the layer below; max_below >= max_rows, and at least
+ *                                         max_rows * (1 + fanout) to be safe for every input: if counts_dev[0] comes out
+ *                                         larger than max_below the list was cut and the block must be discarded
+ *   counts_dev [2] int64                  out: nodes of the layer below, edges of the block
+ *   ws_dev, ws_bytes                      device workspace, >= fg_sample_block_workspace_bytes(max_rows, fanout) (0 for
+ *                                         sizes the call rejects); 16-byte aligned
+ * Six launches on `stream`, no host synchronisation. Node ids outside [0, num_nodes) get empty rows.
+ */
+size_t fg_sample_block_workspace_bytes(int64_t max_rows, int32_t fanout);
+fg_status_t fg_sample_block(const int64_t* indptr_dev, const int32_t* indices_dev, int64_t num_nodes, int64_t num_edges,
+                            const int32_t* ids_dev, const int64_t* n_dev, int64_t max_rows, int32_t fanout, uint64_t key,
+                            int32_t layer, int32_t* row_start_dev, int32_t* row_end_dev, int32_t* col_dev, int32_t* col_ids_dev,
+                            int32_t* ids_below_dev, int64_t max_below, int64_t* counts_dev, void* ws_dev, size_t ws_bytes,
+                            void* stream);
+
+/*
  * The estimate the access-aware admission ranks by: the rows read to produce each node's embedding in this mini-batch,
  * counted along the pruned block like a tree (no credit for neighbours shared with other rows). out[j] = 1 for a node
  * served from the cache (hit_dev[j] != 0); otherwise below[j] + the sum of below[col[c]] over the neighbours left in row

@@ -51,6 +51,8 @@ SIGNATURES = {
                                    _p, _i64, _i32, _p]),
     "fg_aggregate_gcn": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _p, _p, _p]),
     "fg_gather_aggregate_gcn": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _p, _i64, _i64, _i32, _p, _p, _p]),
+    "fg_sample_block_workspace_bytes": (_sz, [_i64, _i32]),
+    "fg_sample_block": (_i32, [_p, _p, _i64, _i64, _p, _p, _i64, _i32, C.c_uint64, _i32, _p, _p, _p, _p, _p, _i64, _p, _p, _sz, _p]),
     "fg_access_estimate": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i32, _p, _p]),
     "fg_gather_aggregate_ids": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _p, _i64, _i64, _i32, _i32, _p, _i64, _i32, _p, _i64,
                                        _i32, _p, _i32, _p, _p]),
@@ -354,6 +356,17 @@ def update_layers(specs):
 def fetch_layers(specs):
     """ctypes array of fg_fetch_layer_t from dicts keyed by the field names."""
     return _struct_array(FetchLayer, specs)
+
+
+def fg_sample_block_workspace_bytes(max_rows, fanout):
+    return int(_lib.fg_sample_block_workspace_bytes(max_rows, fanout))
+
+
+def fg_sample_block(indptr, indices, num_nodes, num_edges, ids, n_dev, max_rows, fanout, key, layer, row_start, row_end, col, col_ids,
+                    ids_below, max_below, counts, ws, ws_bytes, stream=None):
+    _check(_lib.fg_sample_block(ptr(indptr), ptr(indices), num_nodes, num_edges, ptr(ids), ptr(n_dev), max_rows, fanout, key, layer,
+                                ptr(row_start), ptr(row_end), ptr(col), ptr(col_ids), ptr(ids_below), max_below, ptr(counts),
+                                ptr(ws), ws_bytes, stream))
 
 
 def fg_access_estimate(row_start, row_end, col, nnz, n, hit, below, n_src, out, stream=None):

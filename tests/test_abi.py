@@ -91,6 +91,14 @@ def test_argument_validation_needs_no_gpu(B):
     assert code(B.fg_access_estimate, None, 4096, 4096, 5, 5, None, None, 9, 4096) == B.FG_ERR_INVALID_ARG         # no row starts
     assert code(B.fg_access_estimate, 4096, 4096, 4096, 5, 5, None, 4096, 3, 4096) == B.FG_ERR_SHAPE             # layer below smaller
     assert code(B.fg_access_estimate, 4096, 4096, 4096, 5, -1, None, None, 9, 4096) == B.FG_ERR_INVALID_ARG
+    smp = lambda **k: B.fg_sample_block(**{**dict(indptr=4096, indices=4096, num_nodes=100, num_edges=500, ids=4096, n_dev=None, max_rows=10,
+                                                  fanout=5, key=7, layer=1, row_start=4096, row_end=4096, col=4096, col_ids=None,
+                                                  ids_below=4096, max_below=60, counts=4096, ws=4096, ws_bytes=1 << 30), **k})
+    assert code(smp, fanout=33) == B.FG_ERR_INVALID_ARG and code(smp, fanout=0) == B.FG_ERR_INVALID_ARG
+    assert code(smp, layer=0) == B.FG_ERR_INVALID_ARG and code(smp, counts=None) == B.FG_ERR_INVALID_ARG
+    assert code(smp, max_below=9) == B.FG_ERR_SHAPE and code(smp, ws_bytes=64) == B.FG_ERR_SHAPE
+    assert code(smp, ids=None) == B.FG_ERR_INVALID_ARG and code(smp, num_nodes=1 << 31) == B.FG_ERR_INVALID_ARG
+    assert B.fg_sample_block_workspace_bytes(1000, 15) >= 1000 * 15 * 16 and B.fg_sample_block_workspace_bytes(10, 40) == 0
     assert B.fg_cache_feature_rows(None) == 0 and B.fg_cache_buffer(None) == (None, 0) and B.fg_cache_ring_offset(None, 1) == -1
     assert code(B.fg_softmax_xent_grad, None, 64, 4096, 4, 16, 4096, 64) == B.FG_ERR_INVALID_ARG
     assert code(B.fg_softmax_xent_grad, 4096, 32, 4096, 4, 16, 4096, 64) == B.FG_ERR_SHAPE                     # stride < row

@@ -417,6 +417,80 @@ def test_update_all_and_fetch_all_with_unequal_and_empty_layers(env):
         B.fg_cache_destroy(cache)
 
 
+# ------------------------------------------------------------------------------------------------ device-side sampler
+
+def _random_multigraph(num_nodes, max_deg, seed, hubs=0):
+    """In-neighbour CSR with self loops, repeated neighbours, isolated nodes and a few very wide rows."""
+    r = np.random.default_rng(seed)
+    deg = r.integers(0, max_deg + 1, size=num_nodes)
+    deg[r.integers(0, num_nodes, size=hubs)] = r.integers(500, 3000, size=hubs)
+    indptr = np.zeros(num_nodes + 1, dtype=np.int64)
+    indptr[1:] = np.cumsum(deg)
+    near = (np.repeat(np.arange(num_nodes), deg) + r.integers(-4, 5, size=int(indptr[-1]))) % num_nodes
+    far = r.integers(0, num_nodes, size=int(indptr[-1]))
+    indices = np.where(r.random(int(indptr[-1])) < 0.5, near, far).astype(np.int32)
+    return indptr, indices
+
+
+def _device_sample(torch, B, indptr_t, indices_t, N, seeds, fanouts, key, slack=0):
+    """All blocks of a mini-batch through fg_sample_block, each layer's device-side count feeding the next call."""
+    L = len(fanouts)
+    out = dict(ids=[None] * (L + 1), start=[None] * (L + 1), end=[None] * (L + 1), col=[None] * (L + 1), col_ids=[None] * (L + 1))
+    bound = len(seeds) + slack
+    cur = torch.zeros(max(bound, 1), dtype=torch.int32, device="cuda")
+    cur[:len(seeds)] = dev(torch, np.asarray(seeds, dtype=np.int32))
+    n_dev = torch.tensor([len(seeds)], dtype=torch.int64, device="cuda")
+    out["ids"][L] = [int(v) for v in seeds]
+    for l in range(L, 0, -1):
+        f = int(fanouts[l - 1])
+        below_bound = bound * (1 + f)
+        start = torch.full((max(bound, 1),), -3, dtype=torch.int32, device="cuda")
+        end = torch.full((max(bound, 1),), -3, dtype=torch.int32, device="cuda")
+        col = torch.full((max(bound * f, 1),), -3, dtype=torch.int32, device="cuda")
+        col_ids = torch.full((max(bound * f, 1),), -3, dtype=torch.int32, device="cuda") if l % 2 else None
+        below = torch.full((max(below_bound, 1),), -3, dtype=torch.int32, device="cuda")
+        counts = torch.full((2,), -3, dtype=torch.int64, device="cuda")
+        wsb = B.fg_sample_block_workspace_bytes(bound, f)
+        ws = torch.zeros(max(wsb, 16), dtype=torch.uint8, device="cuda")
+        B.fg_sample_block(indptr_t, indices_t, N, int(indices_t.numel()), cur, n_dev, bound, f, key, l, start, end, col, col_ids,
+                          below, below_bound, counts, ws, wsb)
+        n = int(n_dev.item())
+        nb, nnz = (int(x) for x in counts.cpu().tolist())
+        out["start"][l], out["end"][l] = start.cpu().numpy()[:n].tolist(), end.cpu().numpy()[:n].tolist()
+        assert start.cpu().numpy()[n:bound].tolist() == [nnz] * (bound - n) == end.cpu().numpy()[n:bound].tolist()
+        out["col"][l] = col.cpu().numpy()[:nnz].tolist()
+        out["col_ids"][l] = col_ids.cpu().numpy()[:nnz].tolist() if col_ids is not None else None
+        out["ids"][l - 1] = below.cpu().numpy()[:nb].tolist()
+        cur, n_dev, bound = below, counts[:1].clone(), below_bound
+    return out
+
+
+@pytest.mark.parametrize("N,max_deg,hubs,n_seeds,fanouts,slack,seed", [
+    (50, 6, 0, 9, (3, 2), 0, 0), (400, 40, 5, 40, (10, 5), 3, 1), (30000, 60, 40, 700, (15, 10, 5), 100, 2),
+    (2000, 100, 10, 300, (32, 1), 0, 3), (500, 3, 0, 0, (4, 4), 5, 4), (5000, 45, 20, 1100, (25, 15), 0, 5)])
+def test_sample_block_matches_oracle(env, N, max_deg, hubs, n_seeds, fanouts, slack, seed):
+    """fg_sample_block, layer after layer on device-side counts, against the oracle's sampler: node lists, row bounds,
+    columns as positions and as ids, counts; bit for bit. Graphs with self loops, repeated neighbours, isolated nodes and
+    rows far wider than the fan-out; fan-outs 1 and 32; no seeds; bounds larger than the counts."""
+    torch, B = env
+    from oracle import sampler_oracle as S
+    indptr, indices = _random_multigraph(N, max_deg, seed, hubs)
+    indptr_t, indices_t = dev(torch, indptr), dev(torch, indices) if len(indices) else torch.zeros(1, dtype=torch.int32, device="cuda")
+    r = np.random.default_rng(seed)
+    for rep in range(3):
+        seeds = r.permutation(N)[:n_seeds]
+        key = int(r.integers(0, 2 ** 62))
+        want = S.sample_minibatch(indptr, indices, seeds, fanouts, key)
+        got = _device_sample(torch, B, indptr_t, indices_t, N, seeds, fanouts, key, slack)
+        L = len(fanouts)
+        for l in range(L, 0, -1):
+            assert got["ids"][l - 1] == want["ids"][l - 1], f"nodes of layer {l - 1}"
+            assert got["start"][l] == want["start"][l] and got["end"][l] == want["end"][l], f"rows of block {l}"
+            assert got["col"][l] == want["col"][l], f"columns of block {l}"
+            if got["col_ids"][l] is not None:
+                assert got["col_ids"][l] == want["col_ids"][l]
+
+
 # ------------------------------------------------------------------------------------------------ access-aware admission
 
 @pytest.mark.parametrize("n,n_src,max_deg,seed", [(0, 5, 3, 0), (1, 1, 0, 1), (700, 3000, 12, 2), (5000, 40000, 30, 3), (300, 300, 2500, 4)])
