@@ -36,7 +36,37 @@ def _load():
         _lib = C.CDLL(LIB_PATH)
         _lib.fgin_fill_features.restype = C.c_int
         _lib.fgin_fill_features.argtypes = [C.c_void_p, C.c_uint64, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_void_p]
+        _g = [C.c_int64, C.c_uint64, C.c_uint64, C.c_uint64] + [C.c_double] * 6 + [C.c_uint64, C.c_uint64]
+        _lib.fgin_chunglu_degrees.restype = C.c_int
+        _lib.fgin_chunglu_degrees.argtypes = _g + [C.c_void_p, C.c_void_p]
+        _lib.fgin_chunglu_indices.restype = C.c_int
+        _lib.fgin_chunglu_indices.argtypes = _g + [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
     return _lib
+
+
+def chunglu_csr(graph):
+    """The Chung-Lu graph `graph` written out as an in-neighbour CSR in HBM: (indptr int64 [N + 1], indices int32 [E]).
+    Evaluated on the device, so single entries can differ from `graph.neighbour` on the host (another pow); the CSR
+    returned is the graph for whoever samples from it."""
+    import torch
+    g = graph
+    args = [g.num_nodes, g._a, g._ainv, g._b, float(g.c), float(g.r0), float(g.alpha), float(g._lo), float(g._span),
+            1.0 / float(g._e), int(g._key_deg), int(g._key_nbr)]
+    st = torch.cuda.current_stream().cuda_stream
+    deg = torch.empty(g.num_nodes, dtype=torch.int64, device="cuda")
+    rc = _load().fgin_chunglu_degrees(*args, deg.data_ptr(), st)
+    if rc != 0:
+        raise RuntimeError(f"fgin_chunglu_degrees failed with {rc}")
+    indptr = torch.zeros(g.num_nodes + 1, dtype=torch.int64, device="cuda")
+    torch.cumsum(deg, 0, out=indptr[1:])
+    del deg
+    edges = int(indptr[-1].item())
+    indices = torch.empty(max(edges, 1), dtype=torch.int32, device="cuda")
+    rc = _lib.fgin_chunglu_indices(*args, indptr.data_ptr(), edges, indices.data_ptr(), st)
+    if rc != 0:
+        raise RuntimeError(f"fgin_chunglu_indices failed with {rc}")
+    torch.cuda.synchronize()
+    return indptr, indices[:edges]
 
 
 def feature_table(seed, num_nodes, dim, dtype="f32", location="hbm"):

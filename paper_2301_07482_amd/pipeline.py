@@ -57,6 +57,68 @@ class DeviceBatch:
                 self.t_row[l] = up(tr) if len(tr) else torch.zeros(1, dtype=torch.int32, device=device)
 
 
+class SampledBatch:
+    """A mini-batch sampled on the device (`DeviceSampler.sample`): the same fields as `DeviceBatch`, without labels and
+    transposed blocks (forward path and cache update)."""
+
+    def __init__(self, L):
+        self.num_layers = L
+        self.n, self.nnz = [0] * (L + 1), [0] * (L + 1)
+        self.ids = [None] * (L + 1)
+        self.start, self.end, self.col = [None] * (L + 1), [None] * (L + 1), [None] * (L + 1)
+        self.col_ids1 = None
+        self.gnorm = {}
+        self.labels = None
+
+
+class DeviceSampler:
+    """Samples whole mini-batches with fg_sample_block over an in-neighbour CSR in HBM: one call per block, each layer's
+    device-side count feeding the next call, one read-back of the counts at the end (the rest of the path takes the
+    layer sizes as host integers)."""
+
+    def __init__(self, indptr, indices, num_nodes, fanouts, batch, device="cuda"):
+        self.indptr, self.indices = indptr, indices
+        self.num_nodes, self.num_edges = int(num_nodes), int(indices.numel())
+        self.fanouts = [int(f) for f in fanouts]
+        self.L = L = len(self.fanouts)
+        self.device = device
+        self.bound = [0] * (L + 1)
+        self.bound[L] = int(batch)
+        for l in range(L, 0, -1):
+            self.bound[l - 1] = self.bound[l] * (1 + self.fanouts[l - 1])
+        self.ws_bytes = max(B.fg_sample_block_workspace_bytes(self.bound[l], self.fanouts[l - 1]) for l in range(1, L + 1))
+        self.ws = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)
+
+    def sample(self, seeds, key, timer=None):
+        """seeds: int32 device tensor of distinct node ids (at most `batch`); key: the mini-batch's 64-bit key."""
+        L, dev = self.L, self.device
+        st = torch.cuda.current_stream().cuda_stream
+        bt = SampledBatch(L)
+        counts = torch.zeros((L + 1, 2), dtype=torch.int64, device=dev)
+        counts[L, 0] = int(seeds.numel())
+        bt.ids[L] = seeds
+        i32 = lambda n: torch.empty(max(int(n), 1), dtype=torch.int32, device=dev)
+        for l in range(L, 0, -1):
+            f, rows = self.fanouts[l - 1], self.bound[l] if l < L else int(seeds.numel())
+            bt.start[l], bt.end[l], bt.col[l], bt.ids[l - 1] = i32(rows), i32(rows), i32(rows * f), i32(self.bound[l - 1])
+            col_ids = i32(rows * f) if l == 1 else None
+            B.fg_sample_block(self.indptr, self.indices, self.num_nodes, self.num_edges, bt.ids[l], counts[l].data_ptr(), rows, f,
+                              int(key), l, bt.start[l], bt.end[l], bt.col[l], col_ids, bt.ids[l - 1], self.bound[l - 1],
+                              counts[l - 1].data_ptr(), self.ws, self.ws_bytes, st)
+            if l == 1:
+                bt.col_ids1 = col_ids
+        # counts[l - 1] = (nodes of layer l - 1, edges of block l)
+        host = counts.cpu().tolist()
+        for l in range(L + 1):
+            bt.n[l] = int(host[l][0])
+            assert bt.n[l] <= self.bound[l], "a layer outgrew its bound"
+            bt.ids[l] = bt.ids[l][:max(bt.n[l], 1)] if l < L else bt.ids[l]
+        for l in range(1, L + 1):
+            bt.nnz[l] = int(host[l - 1][1])
+            bt.start[l], bt.end[l] = bt.start[l][:max(bt.n[l], 1)], bt.end[l][:max(bt.n[l], 1)]
+        return bt
+
+
 class HotPath:
     """Work buffers, cache and weights of one model; `run(batch, it)` executes one iteration."""
 

@@ -730,7 +730,7 @@ def test_iterations_large_hbm_full_size_with_backward_pass(env):
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
                         backward=False, stabilization=0, model="sage", conditioned=False, col_ids=False,
-                        fetch_with_loader=True, admit_budget=None):
+                        fetch_with_loader=True, admit_budget=None, device_sampler=False):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
@@ -779,12 +779,41 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
     p = w.p_grad if p_grad is None else p_grad
     total_hits = 0
     worst = worst_e2e = worst_bw = worst_w = 0.0
+    sampler = None
+    if device_sampler:      # the graph written out as a CSR on the device; the oracle samples from a copy of the same CSR
+        from fg_inputs import device as fdev, rng
+        from fg_inputs.sampler import MiniBatch
+        from oracle import sampler_oracle as S
+        from paper_2301_07482_amd.pipeline import DeviceSampler
+        indptr_t, indices_t = fdev.chunglu_csr(g)
+        csr = (indptr_t.cpu().numpy(), indices_t.cpu().numpy())
+        sampler = DeviceSampler(indptr_t, indices_t, w.num_nodes, w.fanouts, w.batch)
     try:
         for it in range(iterations):
-            mb = wl.minibatch(w, g, it)
-            gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
-            labels = wl.node_labels(w, mb.ids[L]) if backward else None
-            bt = DeviceBatch(mb, None if backward else gn, labels=labels, col_ids=col_ids)   # uploaded before the oracle prunes its copy
+            if sampler is not None:
+                seeds = wl.seed_nodes(w, it)
+                key = int(rng.make_key(w.seed, 0x5A3, it))
+                o = S.sample_minibatch(csr[0], csr[1], seeds, w.fanouts, key)
+                a32 = lambda x: np.asarray(x, dtype=np.int32)
+                mb = MiniBatch(L, [a32(x) for x in o["ids"]], [None] + [a32(x) for x in o["start"][1:]],
+                               [None] + [a32(x) for x in o["end"][1:]], [None] + [a32(x) for x in o["col"][1:]])
+                bt = sampler.sample(dev(torch, seeds.astype(np.int32)), key)
+                assert bt.n == [len(x) for x in mb.ids] and bt.nnz[1:] == [len(mb.col[l]) for l in range(1, L + 1)]
+                for l in range(L + 1):
+                    assert np.array_equal(bt.ids[l].cpu().numpy()[:bt.n[l]], mb.ids[l]), f"sampled nodes, iteration {it} layer {l}"
+                for l in range(1, L + 1):
+                    assert np.array_equal(bt.start[l].cpu().numpy()[:bt.n[l]], mb.start[l])
+                    assert np.array_equal(bt.end[l].cpu().numpy()[:bt.n[l]], mb.end[l])
+                    assert np.array_equal(bt.col[l].cpu().numpy()[:bt.nnz[l]], mb.col[l]), f"sampled block, iteration {it} layer {l}"
+                assert np.array_equal(bt.col_ids1.cpu().numpy()[:bt.nnz[1]], a32(o["col_ids"][1]))
+                gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
+                bt.gnorm = {l: dev(torch, x) for l, x in gn.items()}
+                labels = None
+            else:
+                mb = wl.minibatch(w, g, it)
+                gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
+                labels = wl.node_labels(w, mb.ids[L]) if backward else None
+                bt = DeviceBatch(mb, None if backward else gn, labels=labels, col_ids=col_ids)   # uploaded before the oracle prunes its copy
             if bc is not None:
                 # what the loader is about to find on the feature side, for every node of the input layer (or a sample)
                 n0 = len(mb.ids[0])
@@ -1209,6 +1238,35 @@ def test_iterations_access_aware_admission(env):
     w = wl.WORKLOADS["medium"]
     assert run_workload_parity(torch, w, 5, check_numeric_every=2, sample_rows=20000, fused=True, col_ids=True,
                                admit_budget={1: 3000, 2: 400}, p_grad=0.9)[0] > 0
+
+
+def test_device_csr_is_the_host_graph_up_to_pow_rounding(env):
+    """The CSR the device writes for a synthetic graph is the host's graph: same degrees and the same neighbour at every
+    slot, except where the device's pow and numpy's differ in the last place right at a rounding boundary."""
+    torch, B = env
+    from fg_inputs import device as fdev
+    w = wl.WORKLOADS["tiny"]
+    g = wl.make_graph(w)
+    indptr_t, indices_t = fdev.chunglu_csr(g)
+    indptr, indices = indptr_t.cpu().numpy(), indices_t.cpu().numpy()
+    nodes = np.arange(w.num_nodes)
+    deg = g.degree(nodes)
+    assert (np.diff(indptr) != deg).mean() < 1e-3 and abs(int(indptr[-1]) - w.num_edges) < 0.05 * w.num_edges
+    same = np.flatnonzero(np.diff(indptr) == deg)
+    v = np.repeat(same, deg[same])
+    slot = np.arange(len(v)) - np.repeat(np.cumsum(deg[same]) - deg[same], deg[same])
+    at = indptr[v] + slot
+    assert (indices[at] != g.neighbour(v, slot)).mean() < 1e-3
+    assert indices.min() >= 0 and indices.max() < w.num_nodes
+
+
+def test_iterations_on_device_sampled_minibatches(env):
+    """The mini-batches come from fg_sample_block (the graph written out as a CSR in HBM, the oracle sampling from a copy
+    of it): sampled nodes and blocks bit for bit, then the whole iteration on them as in the other tests."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    assert run_workload_parity(torch, w, w.iterations, fused=True, col_ids=True, device_sampler=True)[0] > 0
+    assert run_workload_parity(torch, w, 6, device_sampler=True)[0] > 0
 
 
 def test_iterations_medium_fused_input(env):
