@@ -80,6 +80,10 @@ def main():
                          "the largest estimate of saved row reads first (fg_access_estimate, fg_cache_update_all)")
     ap.add_argument("--admit-budget", default=None, metavar="ROWS[,ROWS...]",
                     help="access-aware admission with these budgets for layers 1, 2, ... instead of capacity / t_stale")
+    ap.add_argument("--device-sampler", action="store_true",
+                    help="sample the mini-batches on the device (fg_sample_block over the graph written out as a CSR in HBM) "
+                         "instead of on host cores; the sampling rate is reported under `sampler`, `value` stays the path's rate "
+                         "on resident mini-batches")
     ap.add_argument("--separate-fetch", action="store_true",
                     help="fetch the cached embeddings with a launch of their own (fg_cache_fetch_all) instead of inside the "
                          "id-column loader's launch")
@@ -114,7 +118,11 @@ def main():
     total = args.warmup + args.steps
     extra = min(args.steps, 20)        # further mini-batches for the per-call breakdown pass after the timed region
     t0 = time.time()
-    sampled = sample_batches(w.name, total + extra, args.sample_workers)
+    if args.device_sampler:      # the mini-batches are sampled on the device below; the host samples only what the CPU oracle is timed on
+        assert not args.backward, "--device-sampler: the transposed blocks of the backward pass are built on the host"
+        sampled = [] if args.no_cpu_baseline else sample_batches(w.name, 10, args.sample_workers)
+    else:
+        sampled = sample_batches(w.name, total + extra, args.sample_workers)
     t_sample = time.time() - t0
 
     import numpy as np
@@ -144,7 +152,47 @@ def main():
         for kv in args.tune:
             key, value = kv.split("=")
             B.fg_set_tuning(key, int(value))
-    batches = [make_batch(*s) for s in sampled[:total]]
+    sampler_report = {"where": "host", "workers": args.sample_workers, "seconds": t_sample, "minibatches": total + extra,
+                      "minibatches_per_s": (total + extra) / t_sample if t_sample > 0 else None}
+    if args.device_sampler:
+        from fg_inputs import device as fdev, rng
+        graph = wl.make_graph(w)
+        t1 = time.time()
+        indptr_t, indices_t = fdev.chunglu_csr(graph)
+        t_csr = time.time() - t1
+        ds = G.DeviceSampler(indptr_t, indices_t, w.num_nodes, w.fanouts, w.batch)
+        seeds = [torch.from_numpy(wl.seed_nodes(w, it).astype(np.int32)).cuda() for it in range(total + extra)]
+        keys = [int(rng.make_key(w.seed, 0x5A3, it)) for it in range(total + extra)]
+        ds.sample(seeds[0], keys[0])                      # first call: code objects, allocator
+        outs = [ds.buffers() for _ in range(total + extra)]   # a consumer would recycle a few of these; here every mini-batch is kept
+        torch.cuda.synchronize()
+        for it in range(total + extra):                   # untimed pass: first use of the output memory
+            ds.sample(seeds[it], keys[it], finish=False, out=outs[it])
+        torch.cuda.synchronize()
+        import gc
+        gc.collect()
+        gc.disable()      # keeping 100 mini-batch objects alive otherwise triggers a full collection inside the timed loop (30 ms)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t1 = time.time()
+        e0.record()
+        batches = [ds.sample(seeds[it], keys[it], finish=False, out=outs[it]) for it in range(total + extra)]   # no synchronisation per mini-batch
+        e1.record()
+        torch.cuda.synchronize()
+        t_dev = time.time() - t1
+        gc.enable()
+        for b in batches:
+            b.finish()
+        sampler_report = {"where": "device", "minibatches": total + extra, "seconds": t_dev,
+                          "ms_per_minibatch": 1e3 * t_dev / (total + extra), "minibatches_per_s": (total + extra) / t_dev,
+                          "gpu_ms_per_minibatch": e0.elapsed_time(e1) / (total + extra), "csr_seconds": t_csr,
+                          "csr_bytes": int(indptr_t.numel() * 8 + indices_t.numel() * 4),
+                          "edges_per_minibatch": float(np.mean([sum(b.nnz) for b in batches]))}
+        for it, b in enumerate(batches):                  # synthetic gradient norms by node id, as for host-sampled batches
+            b.gnorm = {l: torch.from_numpy(wl.grad_norms(w, it, l, b.ids[l][:b.n[l]].cpu().numpy())).cuda() for l in range(1, w.num_layers)}
+        replay_batches = batches[total:]
+        batches = batches[:total]
+    else:
+        batches = [make_batch(*s) for s in sampled[:total]]
     torch.cuda.synchronize()
     t_setup = time.time() - t0
     L = hp.L
@@ -210,7 +258,7 @@ def main():
     # events around every call. It is a profile, not a result.
     ev2 = []
     replay_from_buffer = []
-    replay = [make_batch(*sampled[total + k]) for k in range(extra)]
+    replay = replay_batches if args.device_sampler else [make_batch(*sampled[total + k]) for k in range(extra)]
     for k in range(extra):
         step_events = {}
         hp.run(replay[k], args.warmup + args.steps + k, timer=timer_for(step_events))
@@ -410,6 +458,7 @@ def main():
                      "input_rows_sampled": n0_all,
                      "hits": hits, "gather_bytes": gather_bytes, "linear_flops": lin_flops},
         "admit_budget": admit_budget,
+        "sampler": sampler_report,
         "host": {"sampling_s": t_sample, "setup_s": t_setup},
     }
     print(json.dumps(out))

@@ -69,6 +69,22 @@ class SampledBatch:
         self.col_ids1 = None
         self.gnorm = {}
         self.labels = None
+        self._counts = self._bound = self._n_seeds = None
+
+    def finish(self):
+        """Read the layer sizes back (synchronises with the sampling launches) and cut the arrays to them."""
+        L = self.num_layers
+        host = self._counts.cpu().tolist()      # row l: (nodes of layer l, edges of block l + 1); row L is not written
+        host[L][0] = self._n_seeds
+        for l in range(L + 1):
+            self.n[l] = int(host[l][0])
+            assert self.n[l] <= self._bound[l], "a layer outgrew its bound"
+            if l < L:
+                self.ids[l] = self.ids[l][:max(self.n[l], 1)]
+        for l in range(1, L + 1):
+            self.nnz[l] = int(host[l - 1][1])
+            self.start[l], self.end[l] = self.start[l][:max(self.n[l], 1)], self.end[l][:max(self.n[l], 1)]
+        return self
 
 
 class DeviceSampler:
@@ -86,37 +102,49 @@ class DeviceSampler:
         self.bound[L] = int(batch)
         for l in range(L, 0, -1):
             self.bound[l - 1] = self.bound[l] * (1 + self.fanouts[l - 1])
+        self.out_at, at = {}, 0
+        for l in range(L, 0, -1):      # where each output array of a mini-batch starts in its one allocation (256-byte aligned)
+            rows, f = self.bound[l], self.fanouts[l - 1]
+            offs = []
+            for size in (rows, rows, rows * f, self.bound[l - 1], rows * f if l == 1 else 0):
+                offs.append(at)
+                at += -(-max(size, 1) // 64) * 64
+            self.out_at[l] = offs
+        self.out_elems = at
         self.ws_bytes = max(B.fg_sample_block_workspace_bytes(self.bound[l], self.fanouts[l - 1]) for l in range(1, L + 1))
         self.ws = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)
 
-    def sample(self, seeds, key, timer=None):
-        """seeds: int32 device tensor of distinct node ids (at most `batch`); key: the mini-batch's 64-bit key."""
+    def buffers(self):
+        """The output memory of one mini-batch (`sample(..., out=...)`): allocate it ahead of time, or reuse a consumed one."""
+        return (torch.empty(self.out_elems, dtype=torch.int32, device=self.device),
+                torch.empty((self.L + 1, 2), dtype=torch.int64, device=self.device))
+
+    def sample(self, seeds, key, finish=True, out=None):
+        """seeds: int32 device tensor of distinct node ids (at most `batch`); key: the mini-batch's 64-bit key.
+        finish=False: only the launches; `SampledBatch.finish()` later reads the counts back (sampling ahead of the
+        consumer needs no synchronisation per mini-batch that way)."""
         L, dev = self.L, self.device
         st = torch.cuda.current_stream().cuda_stream
         bt = SampledBatch(L)
-        counts = torch.zeros((L + 1, 2), dtype=torch.int64, device=dev)
-        counts[L, 0] = int(seeds.numel())
+        n_seeds = int(seeds.numel())
+        assert n_seeds <= self.bound[L]
+        buf, counts = out if out is not None else self.buffers()   # every output array; counts row l: nodes of layer l, edges of block l + 1
         bt.ids[L] = seeds
-        i32 = lambda n: torch.empty(max(int(n), 1), dtype=torch.int32, device=dev)
+        cp = counts.data_ptr()
         for l in range(L, 0, -1):
-            f, rows = self.fanouts[l - 1], self.bound[l] if l < L else int(seeds.numel())
-            bt.start[l], bt.end[l], bt.col[l], bt.ids[l - 1] = i32(rows), i32(rows), i32(rows * f), i32(self.bound[l - 1])
-            col_ids = i32(rows * f) if l == 1 else None
-            B.fg_sample_block(self.indptr, self.indices, self.num_nodes, self.num_edges, bt.ids[l], counts[l].data_ptr(), rows, f,
-                              int(key), l, bt.start[l], bt.end[l], bt.col[l], col_ids, bt.ids[l - 1], self.bound[l - 1],
-                              counts[l - 1].data_ptr(), self.ws, self.ws_bytes, st)
+            f = self.fanouts[l - 1]
+            rows = self.bound[l] if l < L else n_seeds
+            o = self.out_at[l]
+            bt.start[l], bt.end[l] = buf[o[0]:o[0] + max(rows, 1)], buf[o[1]:o[1] + max(rows, 1)]
+            bt.col[l], bt.ids[l - 1] = buf[o[2]:o[2] + max(rows * f, 1)], buf[o[3]:o[3] + self.bound[l - 1]]
+            col_ids = buf[o[4]:o[4] + max(rows * f, 1)] if l == 1 else None
+            B.fg_sample_block(self.indptr, self.indices, self.num_nodes, self.num_edges, bt.ids[l], None if l == L else cp + 16 * l,
+                              rows, f, int(key), l, bt.start[l], bt.end[l], bt.col[l], col_ids, bt.ids[l - 1], self.bound[l - 1],
+                              cp + 16 * (l - 1), self.ws, self.ws_bytes, st)
             if l == 1:
                 bt.col_ids1 = col_ids
-        # counts[l - 1] = (nodes of layer l - 1, edges of block l)
-        host = counts.cpu().tolist()
-        for l in range(L + 1):
-            bt.n[l] = int(host[l][0])
-            assert bt.n[l] <= self.bound[l], "a layer outgrew its bound"
-            bt.ids[l] = bt.ids[l][:max(bt.n[l], 1)] if l < L else bt.ids[l]
-        for l in range(1, L + 1):
-            bt.nnz[l] = int(host[l - 1][1])
-            bt.start[l], bt.end[l] = bt.start[l][:max(bt.n[l], 1)], bt.end[l][:max(bt.n[l], 1)]
-        return bt
+        bt._counts, bt._bound, bt._n_seeds = counts, self.bound, n_seeds
+        return bt.finish() if finish else bt
 
 
 class HotPath:

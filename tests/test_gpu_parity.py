@@ -1260,6 +1260,57 @@ def test_device_csr_is_the_host_graph_up_to_pow_rounding(env):
     assert indices.min() >= 0 and indices.max() < w.num_nodes
 
 
+def _local_csr(torch, indptr_t, indices_t, nodes):
+    """The rows of `nodes` out of a CSR in device memory, as something the oracle's sampler can index: a dictionary
+    v -> first entry, v + 1 -> one past the last, into a short array holding just those rows (in node order)."""
+    order = np.unique(np.asarray(nodes, dtype=np.int64))
+    t = torch.from_numpy(order).cuda()
+    lo, hi = indptr_t[t], indptr_t[t + 1]
+    length = hi - lo
+    total = int(length.sum().item())
+    first = torch.cumsum(length, 0) - length
+    at = torch.repeat_interleave(lo, length) + (torch.arange(total, device="cuda") - torch.repeat_interleave(first, length))
+    rows = indices_t[at].cpu().numpy() if total else np.zeros(0, dtype=np.int32)
+    first, length = first.cpu().numpy(), length.cpu().numpy()
+    indptr = {}
+    for v, a, d in zip(order.tolist(), first.tolist(), length.tolist()):
+        indptr[v] = a
+        indptr[v + 1] = a + d
+    return indptr, rows
+
+
+def test_sampler_at_full_size(env):
+    """fg_sample_block on the large workload's graph (111 M nodes, 1.6 G edges as a CSR in HBM), in the configuration
+    bench.py --device-sampler runs: batch 1024, fan-outs 15/10/5. Every block of two mini-batches against the oracle's
+    sampler, which is handed the rows of the layer's nodes copied out of the same CSR; bit for bit."""
+    torch, B = env
+    from fg_inputs import device as fdev, rng
+    from oracle import sampler_oracle as S
+    from paper_2301_07482_amd.pipeline import DeviceSampler
+    w = wl.WORKLOADS["large_hbm"]
+    indptr_t, indices_t = fdev.chunglu_csr(wl.make_graph(w))
+    assert abs(int(indices_t.numel()) - w.num_edges) < 0.01 * w.num_edges
+    sampler = DeviceSampler(indptr_t, indices_t, w.num_nodes, w.fanouts, w.batch)
+    L = w.num_layers
+    for it in (0, 7):
+        seeds = wl.seed_nodes(w, it)
+        key = int(rng.make_key(w.seed, 0x5A3, it))
+        bt = sampler.sample(dev(torch, seeds.astype(np.int32)), key)
+        cur = [int(v) for v in seeds]
+        for l in range(L, 0, -1):
+            indptr, rows = _local_csr(torch, indptr_t, indices_t, cur)
+            start, end, col, col_ids, below = S.sample_block(indptr, rows, cur, int(w.fanouts[l - 1]), S.layer_key(key, l))
+            assert bt.n[l - 1] == len(below) and bt.nnz[l] == len(col)
+            assert bt.ids[l - 1].cpu().numpy()[:len(below)].tolist() == below, f"nodes of layer {l - 1}, mini-batch {it}"
+            assert bt.start[l].cpu().numpy()[:len(cur)].tolist() == start and bt.end[l].cpu().numpy()[:len(cur)].tolist() == end
+            assert bt.col[l].cpu().numpy()[:len(col)].tolist() == col, f"columns of block {l}, mini-batch {it}"
+            if l == 1:
+                assert bt.col_ids1.cpu().numpy()[:len(col)].tolist() == col_ids
+            cur = below
+        print(f"mini-batch {it}: layers {bt.n}, edges {bt.nnz[1:]}")
+        assert bt.n[0] > 300_000 and bt.nnz[1] > 400_000
+
+
 def test_iterations_on_device_sampled_minibatches(env):
     """The mini-batches come from fg_sample_block (the graph written out as a CSR in HBM, the oracle sampling from a copy
     of it): sampled nodes and blocks bit for bit, then the whole iteration on them as in the other tests."""
