@@ -426,6 +426,9 @@ def main():
     else:
         rows_no_cache = float(np.mean([batches[it].nnz[1] + batches[it].n[1] for it in steps_it]))
 
+    if args.device_sampler:      # the loop with nothing resident beforehand but the graph, the table and the seeds
+        sampler_report["in_loop"] = sampled_loop(w, hp, ds, first_it=total + extra, steps=args.steps, warmup=10)
+
     cpu_baseline = None
     if not args.no_cpu_baseline:
         cpu_baseline = time_oracle(w, sampled, weights)
@@ -462,6 +465,59 @@ def main():
         "host": {"sampling_s": t_sample, "setup_s": t_setup},
     }
     print(json.dumps(out))
+
+
+def sampled_loop(w, hp, ds, first_it, steps, warmup):
+    """Iterations whose mini-batches are sampled on the device while the loop runs: the sampler works one mini-batch ahead on
+    a second stream (its three layer sizes reach the host through a pinned copy on that stream), gradient norms are made on
+    the device from the sampled node ids, and the path waits for the sampler's event. Four sets of buffers rotate."""
+    import torch
+    from fg_inputs import device as fdev, rng, workload as wl
+    L, K = w.num_layers, 4
+    side = torch.cuda.Stream()
+    main = torch.cuda.current_stream()
+    outs = [ds.buffers() for _ in range(K)]
+    gn = [{l: torch.empty(ds.bound[l], dtype=torch.float32, device="cuda") for l in range(1, L)} for _ in range(K)]
+    host_counts = [torch.zeros((L + 1, 2), dtype=torch.int64, pin_memory=True) for _ in range(K)]
+    sampled_ev = [torch.cuda.Event() for _ in range(K)]
+    consumed_ev = [torch.cuda.Event() for _ in range(K)]
+    n_it = warmup + steps
+    seeds = [torch.from_numpy(wl.seed_nodes(w, first_it + t).astype("int32")).cuda() for t in range(n_it)]
+    keys = [int(rng.make_key(w.seed, 0x5A3, first_it + t)) for t in range(n_it)]
+    gkeys = [{l: int(rng.make_key(w.seed, 0x6AD, first_it + t, l)) for l in range(1, L)} for t in range(n_it)]
+    torch.cuda.synchronize()
+
+    def launch(t):
+        k = t % K
+        with torch.cuda.stream(side):
+            if t >= K:
+                side.wait_event(consumed_ev[k])        # the path is done with this set of buffers
+            bt = ds.sample(seeds[t], keys[t], finish=False, out=outs[k])
+            for l in range(1, L):
+                fdev.grad_norms(bt.ids[l], bt._counts.data_ptr() + 16 * l, ds.bound[l], gkeys[t][l], gn[k][l], side.cuda_stream)
+            bt.gnorm = gn[k]
+            host_counts[k].copy_(bt._counts, non_blocking=True)
+            sampled_ev[k].record(side)
+        return bt
+
+    pending = launch(0)
+    t_start = None
+    for t in range(n_it):
+        if t == warmup:
+            torch.cuda.synchronize()
+            t_start = time.time()
+        nxt = launch(t + 1) if t + 1 < n_it else None
+        k = t % K
+        sampled_ev[k].synchronize()                    # the host needs the layer sizes
+        pending.finish(host_counts[k])
+        main.wait_event(sampled_ev[k])
+        hp.run(pending, first_it + t)
+        consumed_ev[k].record(main)
+        pending = nxt
+    torch.cuda.synchronize()
+    dt = time.time() - t_start
+    return {"steps": steps, "warmup": warmup, "ms_per_step": 1e3 * dt / steps, "minibatches_per_s": steps / dt,
+            "note": "sampling (second stream, one mini-batch ahead), gradient norms and the whole path inside the timed loop"}
 
 
 def profiled_traffic(kernel_prefix):

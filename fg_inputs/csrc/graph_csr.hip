@@ -71,3 +71,27 @@ extern "C" int fgin_chunglu_indices(int64_t n, uint64_t a, uint64_t ainv, uint64
     hipLaunchKernelGGL(chunglu_indices_kernel, dim3(256 * 32), dim3(256), 0, (hipStream_t)stream, G, indptr, edges, indices_out);
     return hipGetLastError() == hipSuccess ? 0 : 2;
 }
+
+// Synthetic embedding-gradient norms exp(N(0, 1)) keyed by node id (the recipe of fg_inputs/workload.py, grad_norms),
+// for loops that sample on the device and so have the node ids only there. Evaluated with the device's log, cos and exp:
+// the last bit of a value can differ from the host's evaluation of the same formula.
+namespace {
+__global__ void grad_norms_kernel(const int32_t* __restrict__ ids, const int64_t* __restrict__ n_dev, int64_t max_n, uint64_t key,
+                                  float* __restrict__ out) {
+    int64_t n = n_dev ? *n_dev : max_n;
+    if (n > max_n) n = max_n;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t c = (uint64_t)(int64_t)ids[i];
+    const double u1 = unit(word(key, c * 2ull)), u2 = unit(word(key, c * 2ull + 1ull));
+    out[i] = (float)exp(sqrt(-2.0 * log(1.0 - u1)) * cos(6.283185307179586 * u2));
+}
+}  // namespace
+
+extern "C" int fgin_grad_norms(const int32_t* ids, const int64_t* n_dev, int64_t max_n, uint64_t key, float* out, void* stream) {
+    if (max_n < 0 || (max_n > 0 && (!ids || !out))) return 1;
+    if (max_n == 0) return 0;
+    hipLaunchKernelGGL(grad_norms_kernel, dim3((unsigned)((max_n + 255) / 256)), dim3(256), 0, (hipStream_t)stream, ids, n_dev, max_n,
+                       key, out);
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}

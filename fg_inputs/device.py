@@ -41,7 +41,17 @@ def _load():
         _lib.fgin_chunglu_degrees.argtypes = _g + [C.c_void_p, C.c_void_p]
         _lib.fgin_chunglu_indices.restype = C.c_int
         _lib.fgin_chunglu_indices.argtypes = _g + [C.c_void_p, C.c_int64, C.c_void_p, C.c_void_p]
+        _lib.fgin_grad_norms.restype = C.c_int
+        _lib.fgin_grad_norms.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_uint64, C.c_void_p, C.c_void_p]
     return _lib
+
+
+def grad_norms(ids, n_dev_ptr, max_n, key, out, stream):
+    """out[i] = the synthetic gradient norm of node ids[i] under `key` (see workload.grad_norms) for i below the
+    device-side count at address n_dev_ptr (None: max_n), on `stream` (a raw stream handle)."""
+    rc = _load().fgin_grad_norms(ids.data_ptr(), n_dev_ptr, max_n, int(key), out.data_ptr(), stream)
+    if rc != 0:
+        raise RuntimeError(f"fgin_grad_norms failed with {rc}")
 
 
 def chunglu_csr(graph):

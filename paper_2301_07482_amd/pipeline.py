@@ -71,10 +71,11 @@ class SampledBatch:
         self.labels = None
         self._counts = self._bound = self._n_seeds = None
 
-    def finish(self):
-        """Read the layer sizes back (synchronises with the sampling launches) and cut the arrays to them."""
+    def finish(self, host_counts=None):
+        """Read the layer sizes back (synchronises with the sampling launches) and cut the arrays to them. host_counts: the
+        counts already copied to the host by the caller (a pinned copy made on the sampling stream)."""
         L = self.num_layers
-        host = self._counts.cpu().tolist()      # row l: (nodes of layer l, edges of block l + 1); row L is not written
+        host = (self._counts.cpu() if host_counts is None else host_counts).tolist()   # row l: (nodes of layer l, edges of block l + 1); row L is not written
         host[L][0] = self._n_seeds
         for l in range(L + 1):
             self.n[l] = int(host[l][0])

@@ -1311,6 +1311,22 @@ def test_sampler_at_full_size(env):
         assert bt.n[0] > 300_000 and bt.nnz[1] > 400_000
 
 
+def test_device_gradient_norms_are_the_host_recipe(env):
+    """The synthetic gradient norms made on the device from node ids (for loops that sample there) are those of
+    workload.grad_norms up to the last place of the device's log / cos / exp; a device-side count cuts the list."""
+    torch, B = env
+    from fg_inputs import device as fdev, rng
+    w = wl.WORKLOADS["tiny"]
+    ids = np.random.default_rng(0).permutation(w.num_nodes)[:3000].astype(np.int32)
+    want = wl.grad_norms(w, 5, 1, ids)
+    out = torch.full((3000,), -1.0, device="cuda")
+    cnt = torch.tensor([2500], dtype=torch.int64, device="cuda")
+    fdev.grad_norms(dev(torch, ids), cnt.data_ptr(), 3000, int(rng.make_key(w.seed, 0x6AD, 5, 1)), out, None)
+    got = out.cpu().numpy()
+    np.testing.assert_allclose(got[:2500], want[:2500], rtol=2e-6)
+    assert np.all(got[2500:] == -1.0)
+
+
 def test_iterations_on_device_sampled_minibatches(env):
     """The mini-batches come from fg_sample_block (the graph written out as a CSR in HBM, the oracle sampling from a copy
     of it): sampled nodes and blocks bit for bit, then the whole iteration on them as in the other tests."""
