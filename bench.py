@@ -445,7 +445,7 @@ def main():
                    "t_stale": w.t_stale, "p_grad": w.p_grad, "cache": not args.no_cache,
                    "fused_loader": not args.no_fuse, "feature_rows": int(args.feature_rows),
                    "gradient_norms": "backward pass" if args.backward else "synthetic input",
-                   "weight_gradients": bool(args.weight_grads and args.backward), "model": args.model,
+                   "weight_gradients": bool(args.weight_grads and args.backward), "layer_type": args.model,
                    "block1_columns": "node ids" if ids_cols else "positions", "seed": w.seed},
         "roofline": roofline,
         "roofline_2": roofline_2,

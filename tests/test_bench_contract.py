@@ -1,0 +1,40 @@
+"""The command line contract of bench.py: one JSON line with the agreed fields, and a refusal of more than one GPU."""
+import json
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+BENCH = os.path.join(ROOT, "bench.py")
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    p = subprocess.run([sys.executable, BENCH, "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert p.returncode == 2 and "one GPU" in p.stderr and p.stdout.strip() == ""
+    env = dict(os.environ, WORLD_SIZE="4")
+    p = subprocess.run([sys.executable, BENCH], capture_output=True, text=True, timeout=120, env=env)
+    assert p.returncode == 2 and "one GPU" in p.stderr
+
+
+@pytest.mark.gpu
+def test_one_json_line_with_the_agreed_fields():
+    p = subprocess.run([sys.executable, BENCH, "--workload", "tiny", "--steps", "6", "--warmup", "4", "--sample-workers", "2"],
+                       capture_output=True, text=True, timeout=600)
+    assert p.returncode == 0, p.stderr[-2000:]
+    lines = [ln for ln in p.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1, "bench.py prints exactly one line on stdout"
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling", "vs_baseline",
+                "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 6 and d["warmup"] == 4 and d["higher_is_better"] is True
+    assert d["vs_baseline"] is None and d["data"] == "synthetic" and d["dtype"] == "f32" and d["unit"] == "mini-batches/s"
+    assert d["config"]["workload"] == "tiny" and "model" not in d["config"] and d["config"]["layer_type"] == "sage"
+    assert d["value"] > 0 and abs(d["value"] * d["ms_per_step"] / 1e3 - 1.0) < 1e-6
+    r = d["roofline"]
+    assert set(("bound", "achieved", "peak", "unit", "frac", "traffic")) <= set(r)
+    assert r["bound"] in ("hbm", "mfma", "alu", "host_link") and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
+    c = d["cpu_baseline"]
+    assert c["kind"] == "oracle" and c["value"] > 0 and c["cores"] >= 1 and c["unit"] == d["unit"] and c["sample"]
