@@ -119,7 +119,6 @@ def main():
     extra = min(args.steps, 20)        # further mini-batches for the per-call breakdown pass after the timed region
     t0 = time.time()
     if args.device_sampler:      # the mini-batches are sampled on the device below; the host samples only what the CPU oracle is timed on
-        assert not args.backward, "--device-sampler: the transposed blocks of the backward pass are built on the host"
         sampled = [] if args.no_cpu_baseline else sample_batches(w.name, 10, args.sample_workers)
     else:
         sampled = sample_batches(w.name, total + extra, args.sample_workers)
@@ -160,7 +159,7 @@ def main():
         t1 = time.time()
         indptr_t, indices_t = fdev.chunglu_csr(graph)
         t_csr = time.time() - t1
-        ds = G.DeviceSampler(indptr_t, indices_t, w.num_nodes, w.fanouts, w.batch)
+        ds = G.DeviceSampler(indptr_t, indices_t, w.num_nodes, w.fanouts, w.batch, transposes=args.backward)
         seeds = [torch.from_numpy(wl.seed_nodes(w, it).astype(np.int32)).cuda() for it in range(total + extra)]
         keys = [int(rng.make_key(w.seed, 0x5A3, it)) for it in range(total + extra)]
         ds.sample(seeds[0], keys[0])                      # first call: code objects, allocator
@@ -188,7 +187,10 @@ def main():
                           "csr_bytes": int(indptr_t.numel() * 8 + indices_t.numel() * 4),
                           "edges_per_minibatch": float(np.mean([sum(b.nnz) for b in batches]))}
         for it, b in enumerate(batches):                  # synthetic gradient norms by node id, as for host-sampled batches
-            b.gnorm = {l: torch.from_numpy(wl.grad_norms(w, it, l, b.ids[l][:b.n[l]].cpu().numpy())).cuda() for l in range(1, w.num_layers)}
+            if args.backward:                             # ... or the seeds' classes, when the norms come from the backward pass
+                b.labels = torch.from_numpy(wl.node_labels(w, wl.seed_nodes(w, it)).astype(np.int32)).cuda()
+            else:
+                b.gnorm = {l: torch.from_numpy(wl.grad_norms(w, it, l, b.ids[l][:b.n[l]].cpu().numpy())).cuda() for l in range(1, w.num_layers)}
         replay_batches = batches[total:]
         batches = batches[:total]
     else:
@@ -427,7 +429,7 @@ def main():
         rows_no_cache = float(np.mean([batches[it].nnz[1] + batches[it].n[1] for it in steps_it]))
 
     if args.device_sampler:      # the loop with nothing resident beforehand but the graph, the table and the seeds
-        sampler_report["in_loop"] = sampled_loop(w, hp, ds, first_it=total + extra, steps=args.steps, warmup=10)
+        sampler_report["in_loop"] = sampled_loop(w, hp, ds, first_it=total + extra, steps=args.steps, warmup=10, backward=args.backward)
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -467,7 +469,7 @@ def main():
     print(json.dumps(out))
 
 
-def sampled_loop(w, hp, ds, first_it, steps, warmup):
+def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False):
     """Iterations whose mini-batches are sampled on the device while the loop runs: the sampler works one mini-batch ahead on
     a second stream (its three layer sizes reach the host through a pinned copy on that stream), gradient norms are made on
     the device from the sampled node ids, and the path waits for the sampler's event. Four sets of buffers rotate."""
@@ -485,6 +487,7 @@ def sampled_loop(w, hp, ds, first_it, steps, warmup):
     seeds = [torch.from_numpy(wl.seed_nodes(w, first_it + t).astype("int32")).cuda() for t in range(n_it)]
     keys = [int(rng.make_key(w.seed, 0x5A3, first_it + t)) for t in range(n_it)]
     gkeys = [{l: int(rng.make_key(w.seed, 0x6AD, first_it + t, l)) for l in range(1, L)} for t in range(n_it)]
+    labels = [torch.from_numpy(wl.node_labels(w, wl.seed_nodes(w, first_it + t)).astype("int32")).cuda() for t in range(n_it)] if backward else None
     torch.cuda.synchronize()
 
     def launch(t):
@@ -493,9 +496,12 @@ def sampled_loop(w, hp, ds, first_it, steps, warmup):
             if t >= K:
                 side.wait_event(consumed_ev[k])        # the path is done with this set of buffers
             bt = ds.sample(seeds[t], keys[t], finish=False, out=outs[k])
-            for l in range(1, L):
-                fdev.grad_norms(bt.ids[l], bt._counts.data_ptr() + 16 * l, ds.bound[l], gkeys[t][l], gn[k][l], side.cuda_stream)
-            bt.gnorm = gn[k]
+            if backward:          # the norms come from the backward pass; it needs the seeds' classes
+                bt.labels = labels[t]
+            else:
+                for l in range(1, L):
+                    fdev.grad_norms(bt.ids[l], bt._counts.data_ptr() + 16 * l, ds.bound[l], gkeys[t][l], gn[k][l], side.cuda_stream)
+                bt.gnorm = gn[k]
             host_counts[k].copy_(bt._counts, non_blocking=True)
             sampled_ev[k].record(side)
         return bt

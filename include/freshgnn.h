@@ -457,6 +457,23 @@ fg_status_t fg_sample_block(const int64_t* indptr_dev, const int32_t* indices_de
                             void* stream);
 
 /*
+ * The transpose of a sampled block, which fg_layer_backward walks: for every position j of the layer below, the rows that
+ * sampled it, in ascending order, back to back (t_row[t_start[j] .. t_end[j])). Built from the block as given: call it on
+ * the sampled block, before the top-down pass prunes rows.
+ *   row_start_dev, row_end_dev [max_rows], col_dev [max_nnz]   the block; n_dev: device-side row count (NULL = max_rows)
+ *   n_src_dev, max_src                     device-side node count of the layer below (NULL = max_src) and its bound;
+ *                                          columns outside [0, count) are ignored
+ *   t_start_dev, t_end_dev [max_src], t_row_dev [max_nnz]      out; positions at and beyond the count get empty lists
+ *   ws_dev, ws_bytes                       device workspace, >= fg_transpose_block_workspace_bytes(max_src); 16-byte aligned
+ * Six launches, no host synchronisation; the result does not depend on the order in which threads run.
+ */
+size_t fg_transpose_block_workspace_bytes(int64_t max_src);
+fg_status_t fg_transpose_block(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
+                               const int64_t* n_dev, int64_t max_rows, const int64_t* n_src_dev, int64_t max_src, int64_t max_nnz,
+                               int32_t* t_start_dev, int32_t* t_end_dev, int32_t* t_row_dev, void* ws_dev, size_t ws_bytes,
+                               void* stream);
+
+/*
  * The estimate the access-aware admission ranks by: the rows read to produce each node's embedding in this mini-batch,
  * counted along the pruned block like a tree (no credit for neighbours shared with other rows). out[j] = 1 for a node
  * served from the cache (hit_dev[j] != 0); otherwise below[j] + the sum of below[col[c]] over the neighbours left in row

@@ -98,3 +98,18 @@ def sample_minibatch(indptr, indices, seeds, fanouts, key):
         start[l], end[l], col[l], col_ids[l], ids[l - 1] = sample_block(indptr, indices, ids[l], int(fanouts[l - 1]),
                                                                         layer_key(key, l))
     return dict(ids=ids, start=start, end=end, col=col, col_ids=col_ids)
+
+
+def transpose_block(start, end, col, n_src):
+    """The transpose of a sampled block, which the backward pass walks: for every position j of the layer below the rows
+    that sampled it, in ascending order, stored back to back. Returns (t_start, t_end, t_row) as lists."""
+    rows_of = [[] for _ in range(n_src)]
+    for i in range(len(start)):
+        for e in range(int(start[i]), int(end[i])):
+            rows_of[int(col[e])].append(i)
+    t_start, t_end, t_row = [], [], []
+    for j in range(n_src):
+        t_start.append(len(t_row))
+        t_row.extend(rows_of[j])
+        t_end.append(len(t_row))
+    return t_start, t_end, t_row

@@ -53,6 +53,8 @@ SIGNATURES = {
     "fg_gather_aggregate_gcn": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _p, _i64, _i64, _i32, _p, _p, _p]),
     "fg_sample_block_workspace_bytes": (_sz, [_i64, _i32]),
     "fg_sample_block": (_i32, [_p, _p, _i64, _i64, _p, _p, _i64, _i32, C.c_uint64, _i32, _p, _p, _p, _p, _p, _i64, _p, _p, _sz, _p]),
+    "fg_transpose_block_workspace_bytes": (_sz, [_i64]),
+    "fg_transpose_block": (_i32, [_p, _p, _p, _p, _i64, _p, _i64, _i64, _p, _p, _p, _p, _sz, _p]),
     "fg_access_estimate": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i32, _p, _p]),
     "fg_gather_aggregate_ids": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _p, _i64, _i64, _i32, _i32, _p, _i64, _i32, _p, _i64,
                                        _i32, _p, _i32, _p, _p]),
@@ -367,6 +369,16 @@ def fg_sample_block(indptr, indices, num_nodes, num_edges, ids, n_dev, max_rows,
     _check(_lib.fg_sample_block(ptr(indptr), ptr(indices), num_nodes, num_edges, ptr(ids), ptr(n_dev), max_rows, fanout, key, layer,
                                 ptr(row_start), ptr(row_end), ptr(col), ptr(col_ids), ptr(ids_below), max_below, ptr(counts),
                                 ptr(ws), ws_bytes, stream))
+
+
+def fg_transpose_block_workspace_bytes(max_src):
+    return int(_lib.fg_transpose_block_workspace_bytes(max_src))
+
+
+def fg_transpose_block(row_start, row_end, col, n_dev, max_rows, n_src_dev, max_src, max_nnz, t_start, t_end, t_row, ws, ws_bytes,
+                       stream=None):
+    _check(_lib.fg_transpose_block(ptr(row_start), ptr(row_end), ptr(col), ptr(n_dev), max_rows, ptr(n_src_dev), max_src, max_nnz,
+                                   ptr(t_start), ptr(t_end), ptr(t_row), ptr(ws), ws_bytes, stream))
 
 
 def fg_access_estimate(row_start, row_end, col, nnz, n, hit, below, n_src, out, stream=None):

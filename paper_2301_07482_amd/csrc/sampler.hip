@@ -344,3 +344,166 @@ extern "C" fg_status_t fg_sample_block(const int64_t* indptr_dev, const int32_t*
     FG_LAUNCH_CHECK("sample_columns_kernel");
     return FG_OK;
 }
+
+// ---- transpose of a sampled block (what the backward pass walks) ---------------------------------------------------
+//
+// For every position j of the layer below: the rows that sampled it, ascending, back to back. Launches: clear the
+// counters; count the edges per source; sum the counters per workgroup; exclusive scan (t_start, t_end); every edge
+// takes the next free place of its source's list (the order of arrival is arbitrary); every list is sorted (lists are
+// short: a source is sampled by a handful of rows), which makes the result independent of that order.
+namespace {
+
+constexpr int TR_THREADS = 256;
+
+struct TrArgs {
+    const int32_t* row_start;
+    const int32_t* row_end;
+    const int32_t* col;
+    const int64_t* n_dev;
+    int64_t max_rows;
+    const int64_t* n_src_dev;
+    int64_t max_src;
+    int64_t max_nnz;
+    int32_t* t_start;
+    int32_t* t_end;
+    int32_t* t_row;
+    int32_t* cnt;   // [max_src] edges per source, then the next free place of its list
+    int32_t* blk;   // per workgroup of the scan
+};
+
+__device__ __forceinline__ int64_t tr_count(const int64_t* dev, int64_t bound) {
+    int64_t n = dev ? *dev : bound;
+    if (n < 0) n = 0;
+    return n < bound ? n : bound;
+}
+
+// f(row, source) for every edge of row `i` that names a valid source
+template <typename F>
+__device__ __forceinline__ void tr_row_edges(const TrArgs& A, int64_t i, int64_t n_src, F f) {
+    int64_t b = A.row_start[i], e = A.row_end[i];
+    if (b < 0) b = 0;
+    if (e > A.max_nnz) e = A.max_nnz;
+    for (int64_t k = b; k < e; ++k) {
+        const int32_t c = A.col[k];
+        if (c >= 0 && c < n_src) f((int32_t)i, c);
+    }
+}
+
+__global__ __launch_bounds__(TR_THREADS) void transpose_count_kernel(TrArgs A) {
+    const int64_t n = tr_count(A.n_dev, A.max_rows), n_src = tr_count(A.n_src_dev, A.max_src);
+    const int64_t i = (int64_t)blockIdx.x * TR_THREADS + threadIdx.x;
+    if (i < n) tr_row_edges(A, i, n_src, [&](int32_t, int32_t c) { atomicAdd(&A.cnt[c], 1); });
+}
+
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void transpose_sum_kernel(TrArgs A) {
+    __shared__ long long red[16];
+    const int64_t j = (int64_t)blockIdx.x * FG_SCAN_BLOCK + threadIdx.x;
+    const long long s = fg_block_sum(j < A.max_src ? (long long)A.cnt[j] : 0, red);
+    if (threadIdx.x == 0) A.blk[blockIdx.x] = (int32_t)s;
+}
+
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void transpose_scan_kernel(TrArgs A) {
+    __shared__ long long red[16];
+    __shared__ int wave_sum[FG_SCAN_BLOCK / FG_WAVE];
+    const int64_t j = (int64_t)blockIdx.x * FG_SCAN_BLOCK + threadIdx.x;
+    long long before = 0;
+    for (int b = threadIdx.x; b < (int)blockIdx.x; b += FG_SCAN_BLOCK) before += A.blk[b];
+    before = fg_block_sum(before, red);
+    const int c = j < A.max_src ? A.cnt[j] : 0;
+    int incl = c;  // inclusive scan over the wavefront, then the wavefronts before this one
+    for (int off = 1; off < FG_WAVE; off <<= 1) {
+        const int v = __shfl_up(incl, off, FG_WAVE);
+        if (fg_lane() >= off) incl += v;
+    }
+    if (fg_lane() == FG_WAVE - 1) wave_sum[fg_wave()] = incl;
+    __syncthreads();
+    int earlier = 0;
+    for (int w = 0; w < fg_wave(); ++w) earlier += wave_sum[w];
+    if (j < A.max_src) {
+        const long long first = before + earlier + incl - c;
+        A.t_start[j] = (int32_t)first;
+        A.t_end[j] = (int32_t)(first + c);
+        A.cnt[j] = 0;  // from here on: the next free place of the list
+    }
+}
+
+__global__ __launch_bounds__(TR_THREADS) void transpose_fill_kernel(TrArgs A) {
+    const int64_t n = tr_count(A.n_dev, A.max_rows), n_src = tr_count(A.n_src_dev, A.max_src);
+    const int64_t i = (int64_t)blockIdx.x * TR_THREADS + threadIdx.x;
+    if (i < n)
+        tr_row_edges(A, i, n_src, [&](int32_t row, int32_t c) {
+            const int64_t at = (int64_t)A.t_start[c] + atomicAdd(&A.cnt[c], 1);
+            if (at < A.max_nnz) A.t_row[at] = row;
+        });
+}
+
+__global__ __launch_bounds__(TR_THREADS) void transpose_sort_kernel(TrArgs A) {
+    const int64_t j = (int64_t)blockIdx.x * TR_THREADS + threadIdx.x;
+    if (j >= A.max_src) return;
+    int64_t b = A.t_start[j], e = A.t_end[j];
+    if (e > A.max_nnz) e = A.max_nnz;
+    for (int64_t k = b + 1; k < e; ++k) {  // insertion sort
+        const int32_t v = A.t_row[k];
+        int64_t q = k;
+        while (q > b && A.t_row[q - 1] > v) {
+            A.t_row[q] = A.t_row[q - 1];
+            --q;
+        }
+        A.t_row[q] = v;
+    }
+}
+
+size_t tr_layout(int64_t max_src, size_t* blk_at) {
+    const size_t src = (size_t)(max_src > 0 ? max_src : 1);
+    *blk_at = fg_align_up(src * 4, 256);
+    return *blk_at + fg_align_up((size_t)fg_ceil_div((int64_t)src, FG_SCAN_BLOCK) * 4, 256);
+}
+
+}  // namespace
+
+extern "C" size_t fg_transpose_block_workspace_bytes(int64_t max_src) {
+    if (max_src < 0 || max_src > INT32_MAX) return 0;
+    size_t at;
+    return tr_layout(max_src, &at);
+}
+
+extern "C" fg_status_t fg_transpose_block(const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* col_dev,
+                                          const int64_t* n_dev, int64_t max_rows, const int64_t* n_src_dev, int64_t max_src,
+                                          int64_t max_nnz, int32_t* t_start_dev, int32_t* t_end_dev, int32_t* t_row_dev,
+                                          void* ws_dev, size_t ws_bytes, void* stream) {
+    const char* who = "fg_transpose_block";
+    if (max_rows < 0 || max_src < 0 || max_nnz < 0 || max_rows > INT32_MAX || max_src > INT32_MAX || max_nnz > INT32_MAX)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (max_rows %lld, max_src %lld, max_nnz %lld)", who, (long long)max_rows,
+                (long long)max_src, (long long)max_nnz);
+    if (max_rows > 0 && (!row_start_dev || !row_end_dev || (max_nnz > 0 && !col_dev))) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL block", who);
+    if (max_src > 0 && (!t_start_dev || !t_end_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL output", who);
+    if (max_nnz > 0 && !t_row_dev) FG_FAIL(FG_ERR_INVALID_ARG, "%s: t_row_dev is NULL", who);
+    size_t blk_at;
+    const size_t need = tr_layout(max_src, &blk_at);
+    if (max_src > 0 && (!ws_dev || ws_bytes < need)) FG_FAIL(FG_ERR_SHAPE, "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes, need);
+    if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: workspace must be 16-byte aligned", who);
+    fg_clear_error();
+    if (max_src == 0) return FG_OK;
+    hipStream_t st = (hipStream_t)stream;
+    TrArgs A{row_start_dev, row_end_dev, col_dev, n_dev, max_rows, n_src_dev, max_src, max_nnz, t_start_dev, t_end_dev, t_row_dev,
+             (int32_t*)ws_dev, (int32_t*)((char*)ws_dev + blk_at)};
+    fg_status_t rc = fg_launch_fill_i32(A.cnt, max_src, 0, st);
+    if (rc != FG_OK) return rc;
+    const unsigned row_blocks = (unsigned)fg_ceil_div(max_rows > 0 ? max_rows : 1, TR_THREADS);
+    const unsigned scan_blocks = (unsigned)fg_ceil_div(max_src, FG_SCAN_BLOCK);
+    if (max_rows > 0) {
+        hipLaunchKernelGGL(transpose_count_kernel, dim3(row_blocks), dim3(TR_THREADS), 0, st, A);
+        FG_LAUNCH_CHECK("transpose_count_kernel");
+    }
+    hipLaunchKernelGGL(transpose_sum_kernel, dim3(scan_blocks), dim3(FG_SCAN_BLOCK), 0, st, A);
+    FG_LAUNCH_CHECK("transpose_sum_kernel");
+    hipLaunchKernelGGL(transpose_scan_kernel, dim3(scan_blocks), dim3(FG_SCAN_BLOCK), 0, st, A);
+    FG_LAUNCH_CHECK("transpose_scan_kernel");
+    if (max_rows > 0) {
+        hipLaunchKernelGGL(transpose_fill_kernel, dim3(row_blocks), dim3(TR_THREADS), 0, st, A);
+        FG_LAUNCH_CHECK("transpose_fill_kernel");
+        hipLaunchKernelGGL(transpose_sort_kernel, dim3((unsigned)fg_ceil_div(max_src, TR_THREADS)), dim3(TR_THREADS), 0, st, A);
+        FG_LAUNCH_CHECK("transpose_sort_kernel");
+    }
+    return FG_OK;
+}

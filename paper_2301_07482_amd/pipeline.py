@@ -58,8 +58,8 @@ class DeviceBatch:
 
 
 class SampledBatch:
-    """A mini-batch sampled on the device (`DeviceSampler.sample`): the same fields as `DeviceBatch`, without labels and
-    transposed blocks (forward path and cache update)."""
+    """A mini-batch sampled on the device (`DeviceSampler.sample`): the same fields as `DeviceBatch`; the transposed blocks
+    only if the sampler was asked for them, `labels` (the seeds' classes) for the caller to set."""
 
     def __init__(self, L):
         self.num_layers = L
@@ -69,6 +69,7 @@ class SampledBatch:
         self.col_ids1 = None
         self.gnorm = {}
         self.labels = None
+        self.t_start, self.t_end, self.t_row = [None] * (L + 1), [None] * (L + 1), [None] * (L + 1)
         self._counts = self._bound = self._n_seeds = None
 
     def finish(self, host_counts=None):
@@ -93,7 +94,8 @@ class DeviceSampler:
     device-side count feeding the next call, one read-back of the counts at the end (the rest of the path takes the
     layer sizes as host integers)."""
 
-    def __init__(self, indptr, indices, num_nodes, fanouts, batch, device="cuda"):
+    def __init__(self, indptr, indices, num_nodes, fanouts, batch, device="cuda", transposes=False):
+        """transposes: also build the transposed blocks of layers 2..L (fg_transpose_block), which the backward pass walks."""
         self.indptr, self.indices = indptr, indices
         self.num_nodes, self.num_edges = int(num_nodes), int(indices.numel())
         self.fanouts = [int(f) for f in fanouts]
@@ -107,12 +109,17 @@ class DeviceSampler:
         for l in range(L, 0, -1):      # where each output array of a mini-batch starts in its one allocation (256-byte aligned)
             rows, f = self.bound[l], self.fanouts[l - 1]
             offs = []
-            for size in (rows, rows, rows * f, self.bound[l - 1], rows * f if l == 1 else 0):
+            tr = transposes and l >= 2      # t_start, t_end over the layer below, t_row over the edges
+            for size in (rows, rows, rows * f, self.bound[l - 1], rows * f if l == 1 else 0,
+                         self.bound[l - 1] if tr else 0, self.bound[l - 1] if tr else 0, rows * f if tr else 0):
                 offs.append(at)
                 at += -(-max(size, 1) // 64) * 64
             self.out_at[l] = offs
         self.out_elems = at
         self.ws_bytes = max(B.fg_sample_block_workspace_bytes(self.bound[l], self.fanouts[l - 1]) for l in range(1, L + 1))
+        self.transposes = transposes
+        if transposes:
+            self.ws_bytes = max([self.ws_bytes] + [B.fg_transpose_block_workspace_bytes(self.bound[l - 1]) for l in range(2, L + 1)])
         self.ws = torch.zeros(self.ws_bytes, dtype=torch.uint8, device=device)
 
     def buffers(self):
@@ -144,6 +151,11 @@ class DeviceSampler:
                               cp + 16 * (l - 1), self.ws, self.ws_bytes, st)
             if l == 1:
                 bt.col_ids1 = col_ids
+            if self.transposes and l >= 2:
+                nb = self.bound[l - 1]
+                bt.t_start[l], bt.t_end[l], bt.t_row[l] = buf[o[5]:o[5] + nb], buf[o[6]:o[6] + nb], buf[o[7]:o[7] + max(rows * f, 1)]
+                B.fg_transpose_block(bt.start[l], bt.end[l], bt.col[l], None if l == L else cp + 16 * l, rows, cp + 16 * (l - 1), nb,
+                                     rows * f, bt.t_start[l], bt.t_end[l], bt.t_row[l], self.ws, self.ws_bytes, st)
         bt._counts, bt._bound, bt._n_seeds = counts, self.bound, n_seeds
         return bt.finish() if finish else bt
 

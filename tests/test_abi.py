@@ -99,6 +99,10 @@ def test_argument_validation_needs_no_gpu(B):
     assert code(smp, max_below=9) == B.FG_ERR_SHAPE and code(smp, ws_bytes=64) == B.FG_ERR_SHAPE
     assert code(smp, ids=None) == B.FG_ERR_INVALID_ARG and code(smp, num_nodes=1 << 31) == B.FG_ERR_INVALID_ARG
     assert B.fg_sample_block_workspace_bytes(1000, 15) >= 1000 * 15 * 16 and B.fg_sample_block_workspace_bytes(10, 40) == 0
+    assert code(B.fg_transpose_block, None, 4096, 4096, None, 10, None, 30, 50, 4096, 4096, 4096, 4096, 1 << 20) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_transpose_block, 4096, 4096, 4096, None, 10, None, 30, 50, 4096, 4096, None, 4096, 1 << 20) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_transpose_block, 4096, 4096, 4096, None, 10, None, 30, 50, 4096, 4096, 4096, 4096, 16) == B.FG_ERR_SHAPE
+    assert B.fg_transpose_block_workspace_bytes(5000) >= 5000 * 4 and B.fg_transpose_block_workspace_bytes(-1) == 0
     assert B.fg_cache_feature_rows(None) == 0 and B.fg_cache_buffer(None) == (None, 0) and B.fg_cache_ring_offset(None, 1) == -1
     assert code(B.fg_softmax_xent_grad, None, 64, 4096, 4, 16, 4096, 64) == B.FG_ERR_INVALID_ARG
     assert code(B.fg_softmax_xent_grad, 4096, 32, 4096, 4, 16, 4096, 64) == B.FG_ERR_SHAPE                     # stride < row

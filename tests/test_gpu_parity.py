@@ -491,6 +491,37 @@ def test_sample_block_matches_oracle(env, N, max_deg, hubs, n_seeds, fanouts, sl
                 assert got["col_ids"][l] == want["col_ids"][l]
 
 
+@pytest.mark.parametrize("n,n_src,max_deg,slack,seed", [(0, 4, 3, 2, 0), (1, 1, 0, 0, 1), (700, 3000, 12, 50, 2), (6000, 40000, 15, 0, 3),
+                                                        (3000, 40, 10, 7, 4)])
+def test_transpose_block_matches_oracle(env, n, n_src, max_deg, slack, seed):
+    """fg_transpose_block against the oracle's definition, bit for bit: rows pruned in between, bounds larger than the
+    device-side counts, sources sampled by hundreds of rows (40 sources for 3000 rows), an empty block."""
+    torch, B = env
+    from oracle import sampler_oracle as S
+    r = np.random.default_rng(seed)
+    deg = r.integers(0, max_deg + 1, size=n)
+    gap = r.integers(0, 3, size=n)
+    start = (np.cumsum(deg + gap) - deg - gap).astype(np.int32)
+    end = (start + deg).astype(np.int32)
+    nnz = int((deg + gap).sum())
+    col = r.integers(0, max(n_src, 1), size=nnz).astype(np.int32)
+    want = S.transpose_block(start, end, col, n_src)
+    rows_b, src_b = n + slack, n_src + slack
+    pad = lambda a, m: dev(torch, np.concatenate([a, np.full(m - len(a), 7, dtype=np.int32)])) if m else torch.zeros(1, dtype=torch.int32, device="cuda")
+    t_start = torch.full((max(src_b, 1),), -3, dtype=torch.int32, device="cuda")
+    t_end = torch.full((max(src_b, 1),), -3, dtype=torch.int32, device="cuda")
+    t_row = torch.full((max(nnz, 1),), -3, dtype=torch.int32, device="cuda")
+    cnt = torch.tensor([n, n_src], dtype=torch.int64, device="cuda")
+    wsb = B.fg_transpose_block_workspace_bytes(src_b)
+    ws = torch.zeros(max(wsb, 16), dtype=torch.uint8, device="cuda")
+    B.fg_transpose_block(pad(start, rows_b), pad(end, rows_b), dev(torch, col) if nnz else None, cnt.data_ptr(), rows_b,
+                         cnt.data_ptr() + 8, src_b, nnz, t_start, t_end, t_row, ws, wsb)
+    total = len(want[2])
+    assert t_start.cpu().numpy()[:n_src].tolist() == want[0] and t_end.cpu().numpy()[:n_src].tolist() == want[1]
+    assert t_row.cpu().numpy()[:total].tolist() == want[2]
+    assert t_start.cpu().numpy()[n_src:src_b].tolist() == [total] * slack == t_end.cpu().numpy()[n_src:src_b].tolist()
+
+
 # ------------------------------------------------------------------------------------------------ access-aware admission
 
 @pytest.mark.parametrize("n,n_src,max_deg,seed", [(0, 5, 3, 0), (1, 1, 0, 1), (700, 3000, 12, 2), (5000, 40000, 30, 3), (300, 300, 2500, 4)])
@@ -787,7 +818,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
         from paper_2301_07482_amd.pipeline import DeviceSampler
         indptr_t, indices_t = fdev.chunglu_csr(g)
         csr = (indptr_t.cpu().numpy(), indices_t.cpu().numpy())
-        sampler = DeviceSampler(indptr_t, indices_t, w.num_nodes, w.fanouts, w.batch)
+        sampler = DeviceSampler(indptr_t, indices_t, w.num_nodes, w.fanouts, w.batch, transposes=backward)
     try:
         for it in range(iterations):
             if sampler is not None:
@@ -809,6 +840,14 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                 gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
                 bt.gnorm = {l: dev(torch, x) for l, x in gn.items()}
                 labels = None
+                if backward:
+                    from fg_inputs.sampler import transpose_block
+                    labels = wl.node_labels(w, mb.ids[L])
+                    bt.labels = dev(torch, labels.astype(np.int32))
+                    for l in range(2, L + 1):
+                        ts, te, tr = transpose_block(mb.start[l], mb.end[l], mb.col[l], len(mb.ids[l - 1]))
+                        assert np.array_equal(bt.t_start[l].cpu().numpy()[:bt.n[l - 1]], ts) and np.array_equal(bt.t_end[l].cpu().numpy()[:bt.n[l - 1]], te)
+                        assert np.array_equal(bt.t_row[l].cpu().numpy()[:bt.nnz[l]], tr), f"transposed block, iteration {it} layer {l}"
             else:
                 mb = wl.minibatch(w, g, it)
                 gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
@@ -1334,6 +1373,12 @@ def test_iterations_on_device_sampled_minibatches(env):
     w = wl.WORKLOADS["tiny"]
     assert run_workload_parity(torch, w, w.iterations, fused=True, col_ids=True, device_sampler=True)[0] > 0
     assert run_workload_parity(torch, w, 6, device_sampler=True)[0] > 0
+    # with the backward pass on transposed blocks built on the device; three layers
+    assert run_workload_parity(torch, w, 6, fused=True, device_sampler=True, backward=True)[0] > 0
+    import dataclasses
+    w3 = dataclasses.replace(wl.WORKLOADS["large_hbm"], name="large_hbm/small", num_nodes=200_000, num_edges=4_000_000, batch=128,
+                             train_nodes=20_000, cache_capacity=20_000, t_stale=6)
+    assert run_workload_parity(torch, w3, 8, p_grad=0.7, fused=True, device_sampler=True, backward=True)[0] > 0
 
 
 def test_iterations_medium_fused_input(env):

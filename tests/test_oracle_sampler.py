@@ -100,6 +100,24 @@ def test_minibatch_structure():
     assert S.layer_key(1234, 1) != S.layer_key(1234, 2)
 
 
+def test_transpose_lists_every_edge_once_under_its_source():
+    """Against the harness's sort-based transpose (written separately) and against the definition edge by edge, on blocks
+    with pruned rows in between."""
+    from fg_inputs.sampler import transpose_block
+    g = multigraph(300, 20, 9)
+    out = S.sample_minibatch(g.indptr, g.indices, list(range(0, 120, 3)), (6, 4), 77)
+    for l in (1, 2):
+        start, end, col = np.array(out["start"][l]), np.array(out["end"][l]), np.array(out["col"][l])
+        end = np.where(np.arange(len(end)) % 5 == 2, start, end)                 # some rows pruned
+        n_src = len(out["ids"][l - 1])
+        ts, te, tr = S.transpose_block(start, end, col, n_src)
+        hs, he, hr = transpose_block(start, end, col, n_src)
+        assert ts == hs.tolist() and te == he.tolist() and tr == hr.tolist()
+        edges = sorted((int(col[e]), i) for i in range(len(start)) for e in range(start[i], end[i]))
+        assert [(j, r) for j in range(n_src) for r in tr[ts[j]:te[j]]] == edges
+        assert ts[0] == 0 and ts[1:] == te[:-1] and te[-1] == len(edges)
+
+
 # ---------------------------------------------------------------- do these pins bite?
 
 SAMPLER_MUTANTS = [
@@ -117,6 +135,8 @@ SAMPLER_MUTANTS = [
     ("rows are not stored back to back", "sample_block", "start.append(len(col))", "start.append(len(col) + (1 if col else 0))"),
     ("the generator drops its second round", "mix", "x = ((x ^ (x >> 27)) * 0x94D049BB133111EB) & MASK", "pass"),
     ("the top bits are not the ones used", "unit", "(w >> 11)", "(w & ((1 << 53) - 1))"),
+    ("the transpose files an edge under its row", "transpose_block", "rows_of[int(col[e])].append(i)", "rows_of[i % n_src].append(int(col[e]))"),
+    ("the transpose lists of consecutive sources overlap", "transpose_block", "t_start.append(len(t_row))", "t_start.append(max(len(t_row) - 1, 0))"),
 ]
 
 SAMPLER_PINS = [
@@ -125,6 +145,7 @@ SAMPLER_PINS = [
     (test_every_sampled_neighbour_is_a_neighbour_from_its_own_stratum, [()]),
     (test_inclusion_frequencies_are_uniform, [()]),
     (test_minibatch_structure, [()]),
+    (test_transpose_lists_every_edge_once_under_its_source, [()]),
 ]
 
 
