@@ -140,3 +140,18 @@ def test_zero_sized_calls_are_noops_without_gpu(B):
     B.fg_gather(None, 0, 16, 16, None, None, None, 0, None, 0, 16)
     B.fg_aggregate(None, None, None, 0, 0, None, None, 0, None, 0, 16, 4, B.FG_F32, None, 16, B.FG_F32)
     B.fg_cache_destroy(None)
+
+
+def test_header_is_plain_c(tmp_path):
+    """include/freshgnn.h compiles as C99 and as C++17 on its own (no torch or HIP types in the boundary)."""
+    import shutil
+    import subprocess
+    src = tmp_path / "uses_header.c"
+    src.write_text('#include "freshgnn.h"\nint main(void) { return 0; }\n')
+    inc = os.path.join(ROOT, "include")
+    for cc, std in (("gcc", "-std=c99"), ("g++", "-std=c++17")):
+        if shutil.which(cc) is None:
+            pytest.skip(f"{cc} not found")
+        args = [cc, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-fsyntax-only"] + (["-x", "c++"] if cc == "g++" else []) + [str(src)]
+        p = subprocess.run(args, capture_output=True, text=True)
+        assert p.returncode == 0, p.stderr
