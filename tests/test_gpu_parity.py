@@ -3,6 +3,8 @@
 Bars: bit-exact for flags, index lists, counts, pruned row ends, gathered rows and cache state;
 REL_TOL_F32 for aggregation and linear outputs (relative error as defined in helpers.rel_err_rows).
 """
+import os
+
 import numpy as np
 import pytest
 
@@ -1125,7 +1127,7 @@ def test_iterations_one_launch_seed_layer(env):
         P.HotPath.__init__ = real
 
 
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("FG_RANDOM_SEEDS", "10"))))
 def test_iterations_random_configurations(env, seed):
     """Depths 1 to 4, random widths (multiples of 4, so the tiled and the panel GEMMs both occur), fan-outs, batch sizes,
     cache sizes (down to rings that overflow), admission fractions and staleness bounds, in a random pipeline mode."""
@@ -1149,7 +1151,33 @@ def test_iterations_random_configurations(env, seed):
     run_workload_parity(torch, w, 9, fused=fused, one_launch_top_down=one_launch, conditioned=True)
 
 
-@pytest.mark.parametrize("seed", range(6))
+@pytest.mark.parametrize("seed", range(int(os.environ.get("FG_RANDOM_SEEDS", "10"))))
+def test_iterations_random_configurations_widened(env, seed):
+    """The options added around the core path, drawn at random together: mini-batches sampled on the device, block columns
+    as node ids with the cache fetch inside or outside the loader's launch, access-aware admission with random budgets, a
+    stabilization period; depths 2 to 4, random widths, fan-outs up to 12, rings that overflow."""
+    torch, B = env
+    import dataclasses
+    r = np.random.default_rng(5000 + seed)
+    L = int(r.integers(2, 5))
+    feat_dim = int(r.choice([8, 32, 64, 128]))
+    hidden = int(r.choice([32, 64, 96, 256]))
+    w = dataclasses.replace(wl.WORKLOADS["tiny"], name=f"random-w/{seed}", num_nodes=int(r.integers(3_000, 40_000)),
+                            num_edges=int(r.integers(20_000, 600_000)), feat_dim=feat_dim, hidden=hidden,
+                            fanouts=tuple(int(x) for x in r.integers(1, 13, size=L)), batch=int(r.integers(1, 120)),
+                            cache_capacity=int(r.choice([7, 60, 500, 5000])), t_stale=int(r.integers(1, 6)),
+                            p_grad=float(r.choice([0.2, 0.5, 0.9, 1.0])), seed=int(r.integers(1, 1 << 30)))
+    kw = dict(fused=bool(r.integers(0, 2)), device_sampler=bool(r.integers(0, 2)), fetch_with_loader=bool(r.integers(0, 2)),
+              stabilization=int(r.choice([0, 0, 3])))
+    kw["col_ids"] = kw["fused"] and bool(r.integers(0, 2))
+    if r.integers(0, 2):
+        kw["admit_budget"] = {l: int(r.choice([1, 5, 40, 400])) for l in range(1, L)}
+    print(f"L={L} dims {feat_dim}->{hidden} fanouts {w.fanouts} batch {w.batch} N={w.num_nodes} E={w.num_edges} cap={w.cache_capacity} "
+          f"t_stale={w.t_stale} p_grad={w.p_grad} {kw}", flush=True)
+    run_workload_parity(torch, w, 9, conditioned=True, **kw)
+
+
+@pytest.mark.parametrize("seed", range(int(os.environ.get("FG_RANDOM_SEEDS", "6"))))
 def test_iterations_random_feature_side(env, seed):
     """Random depths, row widths, ring sizes, buffer sizes and hot-list lengths for the bidirectional cache, with the
     table rows of the cached nodes negated after the fill: ranks, gathered rows and buffer contents are compared bit for bit."""
