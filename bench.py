@@ -84,6 +84,9 @@ def main():
                     help="sample the mini-batches on the device (fg_sample_block over the graph written out as a CSR in HBM) "
                          "instead of on host cores; the sampling rate is reported under `sampler`, `value` stays the path's rate "
                          "on resident mini-batches")
+    ap.add_argument("--no-overlap-update", action="store_true",
+                    help="run the whole cache update after the last layer on the one stream, instead of its selection part on a "
+                         "second stream beside the layers (possible because the gradient norms are given from outside)")
     ap.add_argument("--separate-fetch", action="store_true",
                     help="fetch the cached embeddings with a launch of their own (fg_cache_fetch_all) instead of inside the "
                          "id-column loader's launch")
@@ -138,7 +141,8 @@ def main():
         buffer_bytes = -(-(G.rings_bytes(w) + len(hot) * row) // 256) * 256
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + extra + 32,
                                        hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads, model=args.model,
-                                       fetch_with_loader=not args.separate_fetch, admit_budget=admit_budget)
+                                       fetch_with_loader=not args.separate_fetch, admit_budget=admit_budget,
+                                       overlap_update=not args.no_overlap_update)
     if args.one_launch_seed_layer:
         hp.fuse_small_layers = hp.model == "sage" and not hp.weight_grads
     ids_cols = not args.block_positions and not args.no_fuse
@@ -261,6 +265,8 @@ def main():
     ev2 = []
     replay_from_buffer = []
     replay = replay_batches if args.device_sampler else [make_batch(*sampled[total + k]) for k in range(extra)]
+    overlapped = hp.overlap_update
+    hp.overlap_update = False          # every call on the one stream here, so that each has a time of its own
     for k in range(extra):
         step_events = {}
         hp.run(replay[k], args.warmup + args.steps + k, timer=timer_for(step_events))
@@ -270,6 +276,7 @@ def main():
             pos = hp.normal_pos[0][:int(hp.counts[0][2].item())].long()
             replay_from_buffer.append(float((ranks[pos] >= 0).sum().item()))
     torch.cuda.synchronize()
+    hp.overlap_update = overlapped
     call_avg_ms = spans(ev2)
 
     counts_log = hp.counts_log.cpu().numpy()
@@ -448,6 +455,8 @@ def main():
                    "fused_loader": not args.no_fuse, "feature_rows": int(args.feature_rows),
                    "gradient_norms": "backward pass" if args.backward else "synthetic input",
                    "weight_gradients": bool(args.weight_grads and args.backward), "layer_type": args.model,
+                   "update_selection": "second stream, beside the layers" if (hp.overlap_update and not args.backward and not args.no_cache
+                                                                              and not args.per_layer_update and not hp.feature_side) else "after the layers",
                    "block1_columns": "node ids" if ids_cols else "positions", "seed": w.seed},
         "roofline": roofline,
         "roofline_2": roofline_2,

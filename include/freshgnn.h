@@ -426,6 +426,23 @@ fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, float p_grad, i
                                 const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream);
 
 /*
+ * fg_cache_update_all in two parts, for callers whose gradient norms are known before the embeddings are (norms supplied
+ * from outside, as in the benchmark workloads): _select does everything but the row copy (threshold, check-outs,
+ * admissions, slots, the cache's index and ring header: it reads ids, live, hit, gnorm, saving and never h_dev), so it can
+ * run on another stream while the layers are still being computed; _commit copies the admitted rows from h_dev into
+ * their slots. Same descriptors, same iteration and the same workspace (untouched in between) for both calls. Between
+ * the two the cache must not be looked up or updated (FG_ERR_STATE from fg_lookup_prune, fg_top_down and the update
+ * calls); rows already cached may be fetched (fg_cache_fetch_all, fg_gather on fg_cache_table), and _commit must be
+ * ordered after those fetches, because a recycled slot's old row is overwritten by it. With raw features placed in the
+ * cache's buffer (fg_cache_fill_features) _select must also be ordered after the iteration's feature loads: it advances
+ * the rings' written extents, which decide whether a placed feature row is still valid.
+ */
+fg_status_t fg_cache_update_select(fg_cache_t* cache, int64_t iter, float p_grad, int32_t n_layers,
+                                   const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream);
+fg_status_t fg_cache_update_commit(fg_cache_t* cache, int64_t iter, int32_t n_layers, const fg_update_layer_t* layers,
+                                   void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
  * Neighbour sampling of one block on the device (uniform sampling with a fan-out per layer, Section 7.1; the paper samples
  * on CPU threads, Section 5, so the scheme below is this library's): from the nodes of layer `layer` to block `layer`
  * and the node list of the layer below, over an in-neighbour CSR in device-visible memory.

@@ -98,6 +98,8 @@ class FetchLayer(C.Structure):
 
 SIGNATURES["fg_cache_fetch_all"] = (_i32, [_p, _i32, C.POINTER(FetchLayer), _p])
 SIGNATURES["fg_cache_update_all"] = (_i32, [_p, _i64, _f, _i32, C.POINTER(UpdateLayer), _p, _sz, _p])
+SIGNATURES["fg_cache_update_select"] = (_i32, [_p, _i64, _f, _i32, C.POINTER(UpdateLayer), _p, _sz, _p])
+SIGNATURES["fg_cache_update_commit"] = (_i32, [_p, _i64, _i32, C.POINTER(UpdateLayer), _p, _sz, _p])
 
 for _name, (_res, _args) in SIGNATURES.items():
     _fn = getattr(_lib, _name)
@@ -391,3 +393,11 @@ def fg_cache_fetch_all(cache, layers, stream=None):
 
 def fg_cache_update_all(cache, it, p_grad, layers, ws, ws_bytes, stream=None):
     _check(_lib.fg_cache_update_all(cache, it, p_grad, len(layers), layers, ptr(ws), ws_bytes, stream))
+
+
+def fg_cache_update_select(cache, it, p_grad, layers, ws, ws_bytes, stream=None):
+    _check(_lib.fg_cache_update_select(cache, it, p_grad, len(layers), layers, ptr(ws), ws_bytes, stream))
+
+
+def fg_cache_update_commit(cache, it, layers, ws, ws_bytes, stream=None):
+    _check(_lib.fg_cache_update_commit(cache, it, len(layers), layers, ptr(ws), ws_bytes, stream))

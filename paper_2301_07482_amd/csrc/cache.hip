@@ -557,6 +557,7 @@ extern "C" fg_status_t fg_cache_clear(fg_cache_t* cache, void* stream) {
         if ((rc = fg_launch_fill_i32((int32_t*)l.sel, sizeof(SelState) / 4, 0, st)) != FG_OK) return rc;
         l.head_cur = 0;
         l.last_iter = INT64_MIN;
+        l.copy_pending = false;
     }
     // an emptied ring has "written" nothing, so rows placed earlier would count as intact although embeddings
     // may have been written over them: the feature side is dropped with the embeddings
@@ -746,8 +747,9 @@ fg_status_t prepare_update_layer(fg_cache_t* cache, const char* who, int32_t lay
     return FG_OK;
 }
 
-// The five launches for the layers described in B (descriptors complete, first-workgroup tables not yet).
-fg_status_t launch_update(UpdBatch& B, hipStream_t st) {
+// The launches for the layers described in B (descriptors complete, first-workgroup tables not yet): `select` = the
+// four (five with the access-aware ranking) launches that decide and write the cache's index, `commit` = the row copy.
+fg_status_t launch_update(UpdBatch& B, hipStream_t st, bool select = true, bool commit = true) {
     B.sel_first[0] = B.scan_first[0] = 0;
     for (int i = 0; i < B.n_layers; ++i) {  // at least one workgroup per layer: it resets the statistics and writes the header
         const int64_t n = B.l[i].n > 0 ? B.l[i].n : 1;
@@ -755,6 +757,7 @@ fg_status_t launch_update(UpdBatch& B, hipStream_t st) {
         B.scan_first[i + 1] = B.scan_first[i] + (int)fg_ceil_div(n, FG_SCAN_BLOCK);
     }
     const unsigned n_sel = (unsigned)B.sel_first[B.n_layers], n_scan = (unsigned)B.scan_first[B.n_layers];
+    if (select) {
     hipLaunchKernelGGL(update_digit0_kernel, dim3(n_sel), dim3(SEL_THREADS), 0, st, B);
     FG_LAUNCH_CHECK("update_digit0_kernel");
     hipLaunchKernelGGL(update_digit1_kernel, dim3(n_sel), dim3(SEL_THREADS), 0, st, B);
@@ -769,6 +772,8 @@ fg_status_t launch_update(UpdBatch& B, hipStream_t st) {
     }
     hipLaunchKernelGGL(assign_slots_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
     FG_LAUNCH_CHECK("assign_slots_kernel");
+    }
+    if (!commit) return FG_OK;
     fg_row_copy_batch copies;  // table[aslot[k], :] = h[apos[k], :] for the admitted rows of every layer
     copies.n = B.n_layers;
     for (int i = 0; i < B.n_layers; ++i) {
@@ -787,6 +792,8 @@ extern "C" fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t
                                        int32_t n, const uint8_t* live_dev, const uint8_t* hit_dev,
                                        const float* gnorm_dev, float p_grad, const void* h_dev, int64_t h_stride,
                                        int64_t* stats_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (cache && layer >= 1 && layer <= cache->n_layers && cache->layers[layer - 1].copy_pending)
+        FG_FAIL(FG_ERR_STATE, "fg_cache_update: layer %d still waits for fg_cache_update_commit", layer);
     UpdBatch B;
     B.n_layers = 1;
     fg_status_t rc = prepare_update_layer(cache, "fg_cache_update", layer, iter, ids_dev, n, live_dev, hit_dev, gnorm_dev,
@@ -804,38 +811,70 @@ extern "C" fg_status_t fg_cache_update(fg_cache_t* cache, int32_t layer, int64_t
     return FG_OK;
 }
 
-extern "C" fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, float p_grad, int32_t n_layers,
-                                           const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream) {
-    if (n_layers < 0 || n_layers > FG_MAX_UPD_LAYERS)
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update_all: n_layers = %d outside 0..%d", n_layers, FG_MAX_UPD_LAYERS);
-    if (n_layers > 0 && !layers) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update_all: layers is NULL");
-    if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update_all: workspace must be 16-byte aligned");
+namespace {
+
+// phase 0: the whole update; 1: selection and index only; 2: the row copy of a selection made by phase 1 with the same
+// descriptors and workspace (the ring headers have been swapped by then, so the descriptors are rebuilt without them)
+fg_status_t update_all(const char* who, int phase, fg_cache_t* cache, int64_t iter, float p_grad, int32_t n_layers,
+                       const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream) {
+    if (n_layers < 0 || n_layers > FG_MAX_UPD_LAYERS) FG_FAIL(FG_ERR_INVALID_ARG, "%s: n_layers = %d outside 0..%d", who, n_layers, FG_MAX_UPD_LAYERS);
+    if (n_layers > 0 && !layers) FG_FAIL(FG_ERR_INVALID_ARG, "%s: layers is NULL", who);
+    if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: workspace must be 16-byte aligned", who);
+    if (phase == 2 && n_layers > 0) {
+        if (!cache) FG_FAIL(FG_ERR_INVALID_ARG, "%s: cache is NULL", who);
+        for (int i = 0; i < n_layers; ++i) {
+            const int32_t layer = layers[i].layer;
+            if (layer < 1 || layer > cache->n_layers) FG_FAIL(FG_ERR_INVALID_ARG, "%s: layer %d outside 1..%d", who, layer, cache->n_layers);
+            if (cache->layers[layer - 1].last_iter != iter || !cache->layers[layer - 1].copy_pending)
+                FG_FAIL(FG_ERR_STATE, "%s: layer %d has no selection of iteration %lld waiting for its rows", who, layer, (long long)iter);
+        }
+    }
     UpdBatch B;
     B.n_layers = n_layers;
     size_t off = 0;
     for (int i = 0; i < n_layers; ++i) {
         for (int k = 0; k < i; ++k)
-            if (layers[k].layer == layers[i].layer)
-                FG_FAIL(FG_ERR_INVALID_ARG, "fg_cache_update_all: layer %d is listed twice", layers[i].layer);
+            if (layers[k].layer == layers[i].layer) FG_FAIL(FG_ERR_INVALID_ARG, "%s: layer %d is listed twice", who, layers[i].layer);
         const fg_update_layer_t& a = layers[i];
-        fg_status_t rc = prepare_update_layer(cache, "fg_cache_update_all", a.layer, iter, a.ids_dev, a.n, a.live_dev, a.hit_dev,
-                                              a.gnorm_dev, p_grad, a.h_dev, a.h_stride, a.stats_dev, (char*)ws_dev + off, &B.l[i],
-                                              a.saving_dev, a.max_admit);
+        if (phase != 2 && cache && a.layer >= 1 && a.layer <= cache->n_layers && cache->layers[a.layer - 1].copy_pending)
+            FG_FAIL(FG_ERR_STATE, "%s: layer %d still waits for fg_cache_update_commit", who, a.layer);
+        fg_status_t rc = prepare_update_layer(cache, who, a.layer, phase == 2 ? cache->layers[a.layer - 1].last_iter : iter, a.ids_dev, a.n,
+                                              a.live_dev, a.hit_dev, a.gnorm_dev, p_grad, a.h_dev, a.h_stride, a.stats_dev,
+                                              (char*)ws_dev + off, &B.l[i], a.saving_dev, a.max_admit);
         if (rc != FG_OK) return rc;
         off += upd_layout(a.n).total;
     }
-    if (n_layers > 0 && (!ws_dev || ws_bytes < off))
-        FG_FAIL(FG_ERR_SHAPE, "fg_cache_update_all: workspace of %zu bytes given, %zu needed", ws_bytes, off);
+    if (n_layers > 0 && (!ws_dev || ws_bytes < off)) FG_FAIL(FG_ERR_SHAPE, "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes, off);
     fg_clear_error();
     if (n_layers == 0) return FG_OK;
-    fg_status_t rc = launch_update(B, (hipStream_t)stream);
+    fg_status_t rc = launch_update(B, (hipStream_t)stream, phase != 2, phase != 1);
     if (rc != FG_OK) return rc;
     for (int i = 0; i < n_layers; ++i) {
         fg_layer* l = &cache->layers[layers[i].layer - 1];
-        l->last_iter = iter;
-        l->head_cur ^= 1;
+        if (phase != 2) {
+            l->last_iter = iter;
+            l->head_cur ^= 1;
+        }
+        l->copy_pending = phase == 1;
     }
     return FG_OK;
+}
+
+}  // namespace
+
+extern "C" fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, float p_grad, int32_t n_layers,
+                                           const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream) {
+    return update_all("fg_cache_update_all", 0, cache, iter, p_grad, n_layers, layers, ws_dev, ws_bytes, stream);
+}
+
+extern "C" fg_status_t fg_cache_update_select(fg_cache_t* cache, int64_t iter, float p_grad, int32_t n_layers,
+                                              const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream) {
+    return update_all("fg_cache_update_select", 1, cache, iter, p_grad, n_layers, layers, ws_dev, ws_bytes, stream);
+}
+
+extern "C" fg_status_t fg_cache_update_commit(fg_cache_t* cache, int64_t iter, int32_t n_layers, const fg_update_layer_t* layers,
+                                              void* ws_dev, size_t ws_bytes, void* stream) {
+    return update_all("fg_cache_update_commit", 2, cache, iter, 0.0f, n_layers, layers, ws_dev, ws_bytes, stream);
 }
 
 // ---- estimate of saved accesses (input of the access-aware admission) -------------------------------------------

@@ -18,6 +18,7 @@ struct fg_layer {
     int head_cur = 0;
     void* sel = nullptr;            // selection scratch of the update (two histograms and a count), all-zero between updates
     int64_t last_iter = INT64_MIN;  // host: iteration of the last update
+    bool copy_pending = false;      // host: fg_cache_update_select has run for last_iter, fg_cache_update_commit not yet
 };
 
 struct fg_cache {

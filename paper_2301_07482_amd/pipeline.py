@@ -166,7 +166,7 @@ class HotPath:
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
                  one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage", fuse_small_layers=False,
-                 fetch_with_loader=True, admit_budget=None):
+                 fetch_with_loader=True, admit_budget=None, overlap_update=True):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -232,6 +232,9 @@ class HotPath:
         self.update_all = update_all
         self.fetch_all = fetch_all   # the cached rows of all layers are fetched by one call right after the top-down pass
         self.fetch_with_loader = fetch_with_loader  # ... or inside the id-column loader's launch, where that loader runs
+        self.overlap_update = overlap_update  # selection part of the update on a second stream beside the layers (norms given from outside)
+        self.side = torch.cuda.Stream(device=device) if overlap_update else None
+        self.ev_pruned, self.ev_selected = torch.cuda.Event(), torch.cuda.Event()
         self.admit_budget = dict(admit_budget) if admit_budget else None   # {layer: rows per update}: access-aware admission
         assert not (self.admit_budget and not update_all), "the access-aware admission needs fg_cache_update_all"
         self.ws_upd_bytes = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L))
@@ -291,6 +294,20 @@ class HotPath:
             B.fg_cache_destroy(self.cache)
             self.cache = None
 
+    def _estimates(self, bt, st):
+        for l in range(1, self.L):
+            B.fg_access_estimate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.hit[l],
+                                 self.saving[l - 1] if l > 1 else None, bt.n[l - 1], self.saving[l], st)
+
+    def _update_specs(self, bt, gnorm):
+        esz = B.DTYPE_SIZE
+        return B.update_layers([dict(layer=l, n=bt.n[l], ids_dev=bt.ids[l], live_dev=self.live[l], hit_dev=self.hit[l],
+                                     gnorm_dev=gnorm[l], h_dev=self.H[l], h_stride=self.dims[l] * esz[self.h_code[l]],
+                                     stats_dev=self.stats.data_ptr() + l * 32,
+                                     saving_dev=self.saving[l] if self.admit_budget else None,
+                                     max_admit=int(self.admit_budget.get(l, 0)) if self.admit_budget else 0)
+                                for l in range(1, self.L)])
+
     def _cnt(self, l, k):
         return self.counts.data_ptr() + (l * 3 + k) * 8
 
@@ -335,6 +352,21 @@ class HotPath:
                                   a["hit_dev"], a["hit_pos_dev"], a["hit_slot_dev"], a["normal_pos_dev"], a["normal_ids_dev"],
                                   a["counts_dev"], self.ws, self.ws_bytes, st)
         cached_layers = list(range(1, L)) if (self.use_cache and self.cache is not None) else []
+        # With gradient norms given from outside nothing of the update but its row copy depends on the layers computed below:
+        # threshold, check-outs, admissions and slots are decided now, on a second stream, beside the loader and the layers.
+        # (Not with raw features in the cache's buffer: the loader reads the rings' written extents, which the selection
+        # advances. Copying the admitted rows over there too, beside the seed layer, measured slower than on this stream.)
+        early_select = None
+        if do_update and self.update_all and self.overlap_update and not self.backward and cached_layers and not self.feature_side:
+            main = torch.cuda.current_stream()
+            self.ev_pruned.record(main)
+            with torch.cuda.stream(self.side):
+                self.side.wait_event(self.ev_pruned)
+                if self.admit_budget:
+                    self._estimates(bt, self.side.cuda_stream)
+                early_select = self._update_specs(bt, bt.gnorm)
+                B.fg_cache_update_select(self.cache, it, self.p_grad, early_select, self.ws_upd, self.ws_upd_bytes, self.side.cuda_stream)
+                self.ev_selected.record(self.side)
         fetch_specs = None
         if self.fetch_all and cached_layers:
             fetch_specs = B.fetch_layers([dict(layer=l, hit_slot_dev=self.hit_slot[l], hit_pos_dev=self.hit_pos[l],
@@ -434,19 +466,16 @@ class HotPath:
                                                 self.normal_pos[l], self._cnt(l, 2), bt.n[l], self.dims[l - 1], self.dims[l],
                                                 self.dW[l], self.db[l], self.ws_wg, self.ws_wg_bytes, st)
         # ---- update of the caches
-        if do_update and self.update_all:
+        if early_select is not None:      # the selection ran beside the layers: only the admitted rows are left to copy
+            tick("cache_update_commit")
+            torch.cuda.current_stream().wait_event(self.ev_selected)
+            B.fg_cache_update_commit(self.cache, it, early_select, self.ws_upd, self.ws_upd_bytes, st)
+        elif do_update and self.update_all:
             if self.admit_budget:   # access-aware admission: the estimates, bottom-up over the pruned blocks
                 tick("access_estimate")
-                for l in range(1, L):
-                    B.fg_access_estimate(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.hit[l],
-                                         self.saving[l - 1] if l > 1 else None, bt.n[l - 1], self.saving[l], st)
+                self._estimates(bt, st)
             tick("cache_update_all")
-            specs = [dict(layer=l, n=bt.n[l], ids_dev=bt.ids[l], live_dev=self.live[l], hit_dev=self.hit[l],
-                          gnorm_dev=gnorm[l], h_dev=self.H[l], h_stride=self.dims[l] * esz[self.h_code[l]],
-                          stats_dev=self.stats.data_ptr() + l * 32,
-                          saving_dev=self.saving[l] if self.admit_budget else None,
-                          max_admit=int(self.admit_budget.get(l, 0)) if self.admit_budget else 0) for l in range(1, L)]
-            B.fg_cache_update_all(self.cache, it, self.p_grad, B.update_layers(specs), self.ws_upd, self.ws_upd_bytes, st)
+            B.fg_cache_update_all(self.cache, it, self.p_grad, self._update_specs(bt, gnorm), self.ws_upd, self.ws_upd_bytes, st)
         elif do_update:
             for l in range(1, L):
                 out_b = self.dims[l] * esz[self.h_code[l]]
@@ -512,7 +541,7 @@ class HotPath:
 
 def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None, p_grad=None, fused_input=False, one_launch_top_down=True, update_all=True, log_ring=256,
                  hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage",
-                 fetch_with_loader=True, admit_budget=None):
+                 fetch_with_loader=True, admit_budget=None, overlap_update=True):
     """HotPath for workload `w` with its feature table resident where the workload says."""
     from fg_inputs import device as fdev, workload as wl
     dims = wl.layer_dims(w)
@@ -526,7 +555,7 @@ def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None
                  w.feat_dtype, w.compute_dtype, weights, features_on_host=(w.feat_location == "host"),
                  use_cache=use_cache, fused_input=fused_input, one_launch_top_down=one_launch_top_down, update_all=update_all,
                  fetch_all=update_all, log_ring=log_ring, hot_ids=hot_ids, buffer_bytes=buffer_bytes, backward=backward, weight_grads=weight_grads, stabilization=stabilization, model=model,
-                 fetch_with_loader=fetch_with_loader, admit_budget=admit_budget)
+                 fetch_with_loader=fetch_with_loader, admit_budget=admit_budget, overlap_update=overlap_update)
     return hp, weights, feat_table
 
 
