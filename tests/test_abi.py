@@ -68,6 +68,8 @@ def test_argument_validation_needs_no_gpu(B):
     assert code(B.fg_cache_update, None, 1, 0, None, 0, None, None, None, 0.5, None, 0, None, None, 0) == B.FG_ERR_INVALID_ARG
     assert code(B.fg_cache_update_all, None, 0, 0.5, B.update_layers([dict(layer=1, n=0)]), None, 0) == B.FG_ERR_INVALID_ARG
     assert code(B.fg_cache_update_all, None, 0, 0.5, B.update_layers([dict(layer=1, n=0)] * 9), None, 0) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_cache_update_select, None, 0, 0.5, B.update_layers([dict(layer=1, n=0)]), None, 0) == B.FG_ERR_INVALID_ARG
+    assert code(B.fg_cache_update_commit, None, 0, B.update_layers([dict(layer=1, n=0)]), None, 0) == B.FG_ERR_INVALID_ARG
     assert code(B.fg_cache_fetch_all, None, B.fetch_layers([dict(layer=1)])) == B.FG_ERR_INVALID_ARG
     assert code(B.fg_cache_fetch_all, None, B.fetch_layers([dict(layer=1)] * 9)) == B.FG_ERR_INVALID_ARG
     assert code(B.fg_cache_create, 0, [4], [4], B.FG_F32, 3) == B.FG_ERR_INVALID_ARG

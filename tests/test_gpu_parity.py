@@ -398,10 +398,25 @@ def test_update_all_and_fetch_all_with_unequal_and_empty_layers(env):
             t_stats = torch.zeros((3, 4), dtype=torch.int64, device="cuda")
             wsb = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n) for n in ns)
             ws = torch.zeros(wsb, dtype=torch.uint8, device="cuda")
-            B.fg_cache_update_all(cache, i, p, B.update_layers([dict(layer=k + 1, n=ns[k], ids_dev=t_ids[k], live_dev=t_live[k],
-                                                                     hit_dev=t_hit[k], gnorm_dev=t_gn[k], h_dev=t_rows[k],
-                                                                     h_stride=dims[k] * 4, stats_dev=t_stats[k].data_ptr())
-                                                                for k in range(3)]), ws, wsb, None)
+            specs = B.update_layers([dict(layer=k + 1, n=ns[k], ids_dev=t_ids[k], live_dev=t_live[k], hit_dev=t_hit[k],
+                                          gnorm_dev=t_gn[k], h_dev=t_rows[k], h_stride=dims[k] * 4, stats_dev=t_stats[k].data_ptr())
+                                     for k in range(3)])
+            if i % 2:       # the same update in two calls; in between the cache refuses lookups and further updates
+                B.fg_cache_update_select(cache, i, p, specs, ws, wsb, None)
+                for call in (lambda: B.fg_cache_update_all(cache, i, p, specs, ws, wsb, None),
+                             lambda: B.fg_cache_update_select(cache, i, p, specs, ws, wsb, None),
+                             lambda: B.fg_lookup_prune(cache, 2, i + 1, t_ids[1], ns[1], t_live[1], None, None, None, 0, 0, None, t_hit[1],
+                                                       t_pos[1], t_slot[1], t_norm[1], None, t_cnt[1], ws, wsb, None),
+                             lambda: B.fg_cache_update_commit(cache, i + 1, specs, ws, wsb, None)):
+                    with pytest.raises(B.FgError) as e:
+                        call()
+                    assert e.value.code == B.FG_ERR_STATE
+                B.fg_cache_update_commit(cache, i, specs, ws, wsb, None)
+                with pytest.raises(B.FgError) as e:
+                    B.fg_cache_update_commit(cache, i, specs, ws, wsb, None)       # nothing is waiting any more
+                assert e.value.code == B.FG_ERR_STATE
+            else:
+                B.fg_cache_update_all(cache, i, p, specs, ws, wsb, None)
             stats = t_stats.cpu().numpy().tolist()
             for k in range(3):
                 st = O.cache_update(oc[k], i, ids[k], live[k], look[k]["hit"], gn[k], p, rows[k])
@@ -763,7 +778,7 @@ def test_iterations_large_hbm_full_size_with_backward_pass(env):
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
                         backward=False, stabilization=0, model="sage", conditioned=False, col_ids=False,
-                        fetch_with_loader=True, admit_budget=None, device_sampler=False):
+                        fetch_with_loader=True, admit_budget=None, device_sampler=False, overlap_update=True):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
@@ -784,7 +799,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                                              fused_input=fused, one_launch_top_down=one_launch_top_down,
                                              update_all=one_launch_top_down, hot_ids=hot,
                                              buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward, stabilization=stabilization, model=model,
-                                             fetch_with_loader=fetch_with_loader, admit_budget=admit_budget)
+                                             fetch_with_loader=fetch_with_loader, admit_budget=admit_budget,
+                                             overlap_update=overlap_update)
     from paper_2301_07482_amd import binding as FGB
     bc = None
     if fs:
@@ -1032,6 +1048,8 @@ def test_iterations_tiny(env):
     hits, worst = run_workload_parity(torch, w, w.iterations)
     print(f"tiny: {hits} hits over {w.iterations} iterations, worst rel err {worst:.3e}")
     assert hits > 100
+    # the update as one call after the layers instead of its selection on a second stream beside them
+    assert run_workload_parity(torch, w, w.iterations, overlap_update=False)[0] == hits
 
 
 def test_iterations_tiny_layer_by_layer_top_down(env):
@@ -1168,7 +1186,7 @@ def test_iterations_random_configurations_widened(env, seed):
                             cache_capacity=int(r.choice([7, 60, 500, 5000])), t_stale=int(r.integers(1, 6)),
                             p_grad=float(r.choice([0.2, 0.5, 0.9, 1.0])), seed=int(r.integers(1, 1 << 30)))
     kw = dict(fused=bool(r.integers(0, 2)), device_sampler=bool(r.integers(0, 2)), fetch_with_loader=bool(r.integers(0, 2)),
-              stabilization=int(r.choice([0, 0, 3])))
+              stabilization=int(r.choice([0, 0, 3])), overlap_update=bool(seed % 2))
     kw["col_ids"] = kw["fused"] and bool(r.integers(0, 2))
     if r.integers(0, 2):
         kw["admit_budget"] = {l: int(r.choice([1, 5, 40, 400])) for l in range(1, L)}
