@@ -84,6 +84,9 @@ def main():
                     help="sample the mini-batches on the device (fg_sample_block over the graph written out as a CSR in HBM) "
                          "instead of on host cores; the sampling rate is reported under `sampler`, `value` stays the path's rate "
                          "on resident mini-batches")
+    ap.add_argument("--no-lookahead", action="store_true",
+                    help="do not hand the next mini-batch to the step before it (its top-down pass then runs at the start of its own "
+                         "step instead of on the second stream beside the previous step's layers)")
     ap.add_argument("--no-overlap-update", action="store_true",
                     help="run the whole cache update after the last layer on the one stream, instead of its selection part on a "
                          "second stream beside the layers (possible because the gradient norms are given from outside)")
@@ -212,7 +215,7 @@ def main():
         del a, b
 
     for it in range(args.warmup):
-        hp.run(batches[it], it)
+        hp.run(batches[it], it, next_bt=None if args.no_lookahead else batches[it + 1])
     torch.cuda.synchronize()
 
     # timed region: exactly `steps` iterations. HIP events on the launch stream bracket only the two longest calls,
@@ -241,7 +244,8 @@ def main():
     for k in range(args.steps):
         it = args.warmup + k
         step_events = {}
-        hp.run(batches[it], it, timer=timer_for(step_events, only=BRACKETED) if k % args.bracket_every == 0 else None)
+        ahead = batches[it + 1] if (it + 1 < total and not args.no_lookahead) else None      # its top-down pass runs beside this step's layers
+        hp.run(batches[it], it, timer=timer_for(step_events, only=BRACKETED) if k % args.bracket_every == 0 else None, next_bt=ahead)
         ev.append(step_events)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
@@ -455,6 +459,9 @@ def main():
                    "fused_loader": not args.no_fuse, "feature_rows": int(args.feature_rows),
                    "gradient_norms": "backward pass" if args.backward else "synthetic input",
                    "weight_gradients": bool(args.weight_grads and args.backward), "layer_type": args.model,
+                   "top_down": "of the next mini-batch on the second stream, beside this step's layers" if (
+                       not args.no_lookahead and hp.overlap_update and not args.backward and not args.no_cache and not args.per_layer_update
+                       and not hp.feature_side and hp.one_launch_top_down) else "at the start of the step",
                    "update_selection": "second stream, beside the layers" if (hp.overlap_update and not args.backward and not args.no_cache
                                                                               and not args.per_layer_update and not hp.feature_side) else "after the layers",
                    "block1_columns": "node ids" if ids_cols else "positions", "seed": w.seed},

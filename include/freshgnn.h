@@ -431,9 +431,10 @@ fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, float p_grad, i
  * admissions, slots, the cache's index and ring header: it reads ids, live, hit, gnorm, saving and never h_dev), so it can
  * run on another stream while the layers are still being computed; _commit copies the admitted rows from h_dev into
  * their slots. Same descriptors, same iteration and the same workspace (untouched in between) for both calls. Between
- * the two the cache must not be looked up or updated (FG_ERR_STATE from fg_lookup_prune, fg_top_down and the update
- * calls); rows already cached may be fetched (fg_cache_fetch_all, fg_gather on fg_cache_table), and _commit must be
- * ordered after those fetches, because a recycled slot's old row is overwritten by it. With raw features placed in the
+ * the two the cache must not be updated again (FG_ERR_STATE). Lookups ordered after _select see the new index, so the next
+ * mini-batch may be looked up and pruned before _commit; the rows of its hits must be fetched after _commit. Rows cached
+ * before may be fetched in between (fg_cache_fetch_all, fg_gather on fg_cache_table), and _commit must be ordered after
+ * those fetches, because a recycled slot's old row is overwritten by it. With raw features placed in the
  * cache's buffer (fg_cache_fill_features) _select must also be ordered after the iteration's feature loads: it advances
  * the rings' written extents, which decide whether a placed feature row is still valid.
  */

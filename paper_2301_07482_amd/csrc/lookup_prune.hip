@@ -254,8 +254,6 @@ extern "C" fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, i
                                        int32_t* hit_slot_dev, int32_t* normal_pos_dev, int32_t* normal_ids_dev,
                                        int64_t* counts_dev, void* ws_dev, size_t ws_bytes, void* stream) {
     if (n < 0) FG_FAIL(FG_ERR_INVALID_ARG, "fg_lookup_prune: n = %d is negative", n);
-    if (cache && layer >= 1 && layer <= cache->n_layers && cache->layers[layer - 1].copy_pending)
-        FG_FAIL(FG_ERR_STATE, "fg_lookup_prune: layer %d has admitted rows whose copy is still due (fg_cache_update_commit)", layer);
     if (!counts_dev) FG_FAIL(FG_ERR_INVALID_ARG, "fg_lookup_prune: counts_dev is NULL");
     if (n > 0 && (!ids_dev || !normal_pos_dev))
         FG_FAIL(FG_ERR_INVALID_ARG, "fg_lookup_prune: ids_dev and normal_pos_dev are required");
@@ -316,10 +314,6 @@ extern "C" fg_status_t fg_top_down(const fg_cache_t* cache, int64_t iter, int32_
                                    const fg_top_down_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream) {
     if (n_layers <= 0 || n_layers > TD_MAX_LAYERS || !layers)
         FG_FAIL(FG_ERR_INVALID_ARG, "fg_top_down: n_layers = %d must be in 1..%d and layers non-NULL", n_layers, TD_MAX_LAYERS);
-    if (cache)
-        for (int i = 0; i < cache->n_layers; ++i)
-            if (cache->layers[i].copy_pending)
-                FG_FAIL(FG_ERR_STATE, "fg_top_down: layer %d has admitted rows whose copy is still due (fg_cache_update_commit)", i + 1);
     TdArgs a{};
     a.count = n_layers;
     size_t off = 0;

@@ -216,6 +216,14 @@ class HotPath:
         self.normal_pos = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
         self.input_ids = torch.zeros(n[0], dtype=torch.int32, device=dev)
         self.self_ids = torch.zeros(n[1], dtype=torch.int32, device=dev)
+        # what the top-down pass writes exists twice (iterations alternate), so that the pass for the next mini-batch can
+        # run while this one's layers are computed (`run(..., next_bt=...)`)
+        mk = lambda dt: [torch.zeros(n[l], dtype=dt, device=dev) for l in range(L + 1)]
+        self._lists = [dict(live=self.live, hit=self.hit, hit_pos=self.hit_pos, hit_slot=self.hit_slot, normal_pos=self.normal_pos,
+                            input_ids=self.input_ids, self_ids=self.self_ids),
+                       dict(live=mk(torch.uint8), hit=mk(torch.uint8), hit_pos=mk(torch.int32), hit_slot=mk(torch.int32),
+                            normal_pos=mk(torch.int32), input_ids=torch.zeros_like(self.input_ids), self_ids=torch.zeros_like(self.self_ids))]
+        self._td_for = None      # (iteration, id of the mini-batch) whose top-down pass has already been launched on the second stream
         # device-side counts/stats are kept per iteration in a ring, so a timed loop can be read back afterwards
         self.ring = int(log_ring)
         self.counts_log = torch.zeros((self.ring, L + 1, 3), dtype=torch.int64, device=dev)
@@ -234,7 +242,7 @@ class HotPath:
         self.fetch_with_loader = fetch_with_loader  # ... or inside the id-column loader's launch, where that loader runs
         self.overlap_update = overlap_update  # selection part of the update on a second stream beside the layers (norms given from outside)
         self.side = torch.cuda.Stream(device=device) if overlap_update else None
-        self.ev_pruned, self.ev_selected = torch.cuda.Event(), torch.cuda.Event()
+        self.ev_pruned, self.ev_selected, self.ev_next_pruned, self.ev_done = (torch.cuda.Event() for _ in range(4))
         self.admit_budget = dict(admit_budget) if admit_budget else None   # {layer: rows per update}: access-aware admission
         assert not (self.admit_budget and not update_all), "the access-aware admission needs fg_cache_update_all"
         self.ws_upd_bytes = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L))
@@ -311,19 +319,10 @@ class HotPath:
     def _cnt(self, l, k):
         return self.counts.data_ptr() + (l * 3 + k) * 8
 
-    def run(self, bt, it, update=True, timer=None):
-        """One iteration on torch's current stream. `timer(name, stream)` (optional) is called before each C-ABI call
-        and with name None after the last call of a stream (stream None = the current stream)."""
-        L = self.L
-        self.counts = self.counts_log[it % self.ring]
-        self.stats = self.stats_log[it % self.ring]
-        tick = timer if timer is not None else (lambda name, stream=None: None)
-        esz = B.DTYPE_SIZE
-        st = torch.cuda.current_stream().cuda_stream
-        do_update = update and self.use_cache and self.cache is not None
-        assert all(bt.n[l] <= self.n_max[l] for l in range(L + 1)), "mini-batch larger than the static bounds"
-        # ---- top-down: lookup, prune, V_normal (layers L .. 0)
-        fused = self.fused_input
+    def _top_down(self, bt, it, st, tick):
+        """Lookup, prune, V_normal for layers L .. 0 (or 1 with the fused loader) of mini-batch `bt` on stream `st`, into the
+        currently bound lists."""
+        L, fused = self.L, self.fused_input
         lowest = 1 if fused else 0
 
         def layer_args(l):
@@ -351,6 +350,35 @@ class HotPath:
                                   a["row_start_dev"], a["row_end_dev"], a["col_dev"], a["nnz"], a["n_src"], a["live_src_dev"],
                                   a["hit_dev"], a["hit_pos_dev"], a["hit_slot_dev"], a["normal_pos_dev"], a["normal_ids_dev"],
                                   a["counts_dev"], self.ws, self.ws_bytes, st)
+
+    def _bind(self, it):
+        """Point the per-iteration state (lists of the top-down pass, counters, statistics) at iteration `it`'s copies."""
+        for k, v in self._lists[it % 2].items():
+            setattr(self, k, v)
+        self.counts = self.counts_log[it % self.ring]
+        self.stats = self.stats_log[it % self.ring]
+
+    def run(self, bt, it, update=True, timer=None, next_bt=None):
+        """One iteration on torch's current stream. `timer(name, stream)` (optional) is called before each C-ABI call
+        and with name None after the last call of a stream (stream None = the current stream).
+        next_bt: the mini-batch of iteration it + 1, if the caller has it: where the update's selection runs on the second
+        stream (see below), the top-down pass of that mini-batch follows it there, beside this iteration's layers, and
+        the next call (which must be for that mini-batch and iteration) finds it done."""
+        L = self.L
+        self._bind(it)
+        tick = timer if timer is not None else (lambda name, stream=None: None)
+        esz = B.DTYPE_SIZE
+        st = torch.cuda.current_stream().cuda_stream
+        do_update = update and self.use_cache and self.cache is not None
+        assert all(bt.n[l] <= self.n_max[l] for l in range(L + 1)), "mini-batch larger than the static bounds"
+        fused = self.fused_input
+        pruned_ahead = self._td_for == (it, id(bt))
+        self._td_for = None
+        if pruned_ahead:
+            torch.cuda.current_stream().wait_event(self.ev_next_pruned)
+        else:
+            self._top_down(bt, it, st, tick)
+
         cached_layers = list(range(1, L)) if (self.use_cache and self.cache is not None) else []
         # With gradient norms given from outside nothing of the update but its row copy depends on the layers computed below:
         # threshold, check-outs, admissions and slots are decided now, on a second stream, beside the loader and the layers.
@@ -359,14 +387,25 @@ class HotPath:
         early_select = None
         if do_update and self.update_all and self.overlap_update and not self.backward and cached_layers and not self.feature_side:
             main = torch.cuda.current_stream()
-            self.ev_pruned.record(main)
+            if not pruned_ahead:
+                self.ev_pruned.record(main)
             with torch.cuda.stream(self.side):
-                self.side.wait_event(self.ev_pruned)
+                if not pruned_ahead:
+                    self.side.wait_event(self.ev_pruned)
+                self.side.wait_event(self.ev_done)     # the previous iteration's row copy has read the update's workspace
                 if self.admit_budget:
                     self._estimates(bt, self.side.cuda_stream)
                 early_select = self._update_specs(bt, bt.gnorm)
                 B.fg_cache_update_select(self.cache, it, self.p_grad, early_select, self.ws_upd, self.ws_upd_bytes, self.side.cuda_stream)
                 self.ev_selected.record(self.side)
+                if next_bt is not None and self.one_launch_top_down:
+                    # the cache's index is final for this iteration: the next mini-batch can be looked up and pruned now,
+                    # into the other set of lists (free since the previous iteration's row copy: ev_done above)
+                    self._bind(it + 1)
+                    self._top_down(next_bt, it + 1, self.side.cuda_stream, lambda name, stream=None: None)
+                    self.ev_next_pruned.record(self.side)
+                    self._td_for = (it + 1, id(next_bt))
+                    self._bind(it)
         fetch_specs = None
         if self.fetch_all and cached_layers:
             fetch_specs = B.fetch_layers([dict(layer=l, hit_slot_dev=self.hit_slot[l], hit_pos_dev=self.hit_pos[l],
@@ -470,6 +509,7 @@ class HotPath:
             tick("cache_update_commit")
             torch.cuda.current_stream().wait_event(self.ev_selected)
             B.fg_cache_update_commit(self.cache, it, early_select, self.ws_upd, self.ws_upd_bytes, st)
+            self.ev_done.record(torch.cuda.current_stream())
         elif do_update and self.update_all:
             if self.admit_budget:   # access-aware admission: the estimates, bottom-up over the pruned blocks
                 tick("access_estimate")

@@ -401,12 +401,10 @@ def test_update_all_and_fetch_all_with_unequal_and_empty_layers(env):
             specs = B.update_layers([dict(layer=k + 1, n=ns[k], ids_dev=t_ids[k], live_dev=t_live[k], hit_dev=t_hit[k],
                                           gnorm_dev=t_gn[k], h_dev=t_rows[k], h_stride=dims[k] * 4, stats_dev=t_stats[k].data_ptr())
                                      for k in range(3)])
-            if i % 2:       # the same update in two calls; in between the cache refuses lookups and further updates
+            if i % 2:       # the same update in two calls; in between the cache refuses further updates
                 B.fg_cache_update_select(cache, i, p, specs, ws, wsb, None)
                 for call in (lambda: B.fg_cache_update_all(cache, i, p, specs, ws, wsb, None),
                              lambda: B.fg_cache_update_select(cache, i, p, specs, ws, wsb, None),
-                             lambda: B.fg_lookup_prune(cache, 2, i + 1, t_ids[1], ns[1], t_live[1], None, None, None, 0, 0, None, t_hit[1],
-                                                       t_pos[1], t_slot[1], t_norm[1], None, t_cnt[1], ws, wsb, None),
                              lambda: B.fg_cache_update_commit(cache, i + 1, specs, ws, wsb, None)):
                     with pytest.raises(B.FgError) as e:
                         call()
@@ -778,7 +776,8 @@ def test_iterations_large_hbm_full_size_with_backward_pass(env):
 def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=None, p_grad=None, capacity=None,
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
                         backward=False, stabilization=0, model="sage", conditioned=False, col_ids=False,
-                        fetch_with_loader=True, admit_budget=None, device_sampler=False, overlap_update=True):
+                        fetch_with_loader=True, admit_budget=None, device_sampler=False, overlap_update=True,
+                        lookahead=False):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
@@ -838,7 +837,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
         csr = (indptr_t.cpu().numpy(), indices_t.cpu().numpy())
         sampler = DeviceSampler(indptr_t, indices_t, w.num_nodes, w.fanouts, w.batch, transposes=backward)
     try:
-        for it in range(iterations):
+        def prepare(it):
+            """Mini-batch `it` on both sides: sampled (or sampled on the device and compared), uploaded, with its norms."""
             if sampler is not None:
                 seeds = wl.seed_nodes(w, it)
                 key = int(rng.make_key(w.seed, 0x5A3, it))
@@ -871,6 +871,12 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                 gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
                 labels = wl.node_labels(w, mb.ids[L]) if backward else None
                 bt = DeviceBatch(mb, None if backward else gn, labels=labels, col_ids=col_ids)   # uploaded before the oracle prunes its copy
+            return mb, bt, gn, labels
+
+        ahead = prepare(0) if (lookahead and iterations) else None
+        for it in range(iterations):
+            mb, bt, gn, labels = ahead if lookahead else prepare(it)
+            ahead = prepare(it + 1) if (lookahead and it + 1 < iterations) else None     # uploaded before this iteration runs
             if bc is not None:
                 # what the loader is about to find on the feature side, for every node of the input layer (or a sample)
                 n0 = len(mb.ids[0])
@@ -886,7 +892,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
             served += int(rec["feature_from_buffer"].sum())
             # device cache rows at the slots about to be hit, read before this iteration's update recycles slots
             pre_rows = {l: hp.cache_rows(l, rec["look"][l]["hit_slot"]) for l in range(1, L) if len(rec["look"][l]["hit_pos"])}
-            hp.run(bt, it)
+            hp.run(bt, it, next_bt=ahead[1] if ahead is not None else None)
             snap = hp.snapshot(bt)
             if backward:
                 # (a) every call against the oracle on the SAME inputs (the device's own H and dH of the layer above), so
@@ -1050,6 +1056,10 @@ def test_iterations_tiny(env):
     assert hits > 100
     # the update as one call after the layers instead of its selection on a second stream beside them
     assert run_workload_parity(torch, w, w.iterations, overlap_update=False)[0] == hits
+    # every mini-batch handed to the iteration before it: its top-down pass runs on the second stream beside that
+    # iteration's layers, into the other set of lists
+    assert run_workload_parity(torch, w, w.iterations, lookahead=True)[0] == hits
+    assert run_workload_parity(torch, w, w.iterations, lookahead=True, fused=True, col_ids=True, admit_budget={1: 60})[0] > 0
 
 
 def test_iterations_tiny_layer_by_layer_top_down(env):
@@ -1186,7 +1196,7 @@ def test_iterations_random_configurations_widened(env, seed):
                             cache_capacity=int(r.choice([7, 60, 500, 5000])), t_stale=int(r.integers(1, 6)),
                             p_grad=float(r.choice([0.2, 0.5, 0.9, 1.0])), seed=int(r.integers(1, 1 << 30)))
     kw = dict(fused=bool(r.integers(0, 2)), device_sampler=bool(r.integers(0, 2)), fetch_with_loader=bool(r.integers(0, 2)),
-              stabilization=int(r.choice([0, 0, 3])), overlap_update=bool(seed % 2))
+              stabilization=int(r.choice([0, 0, 3])), overlap_update=bool(seed % 2), lookahead=bool((seed // 2) % 2))
     kw["col_ids"] = kw["fused"] and bool(r.integers(0, 2))
     if r.integers(0, 2):
         kw["admit_budget"] = {l: int(r.choice([1, 5, 40, 400])) for l in range(1, L)}
@@ -1449,7 +1459,7 @@ def test_iterations_large_hbm_full_size(env):
     feature rows on a sample, numerics every 8th iteration."""
     torch, B = env
     w = wl.WORKLOADS["large_hbm"]
-    hits, worst = run_workload_parity(torch, w, 24, check_numeric_every=8, sample_rows=20000, fused=True, col_ids=True)
+    hits, worst = run_workload_parity(torch, w, 24, check_numeric_every=8, sample_rows=20000, fused=True, col_ids=True, lookahead=True)
     print(f"large_hbm: {hits} hits, worst rel err {worst:.3e}")
     assert hits > 1000
 
