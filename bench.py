@@ -61,7 +61,7 @@ def main():
                     help="fg_set_tuning(KEY, VALUE) before the run (launch-shape experiments; results do not depend on it)")
     ap.add_argument("--per-layer-update", action="store_true",
                     help="one fg_cache_update per layer instead of one fg_cache_update_all")
-    ap.add_argument("--bracket-every", type=int, default=5,
+    ap.add_argument("--bracket-every", type=int, default=10,
                     help="time the two longest calls with HIP events on every k-th step of the timed region")
     ap.add_argument("--feature-rows", type=int, default=0,
                     help="bidirectional cache: place the raw features of this many hottest nodes on the feature side of the "
@@ -241,14 +241,24 @@ def main():
 
     torch.cuda.synchronize()
     t_start = time.perf_counter()
+    # Two kinds of bracketed steps: every `--bracket-every`-th step runs with every call on the one stream, so that the
+    # bracketed launches have the chip to themselves (the durations `roofline` is priced on, comparable with a kernel
+    # trace); half way between them a step is bracketed as it normally runs, with the bookkeeping launches of the second
+    # stream beside it (`ms_per_launch_overlapped`).
+    ev_ovl = []
+    overlapped = hp.overlap_update
     for k in range(args.steps):
         it = args.warmup + k
         step_events = {}
-        ahead = batches[it + 1] if (it + 1 < total and not args.no_lookahead) else None      # its top-down pass runs beside this step's layers
-        hp.run(batches[it], it, timer=timer_for(step_events, only=BRACKETED) if k % args.bracket_every == 0 else None, next_bt=ahead)
-        ev.append(step_events)
+        alone = k % args.bracket_every == 0
+        beside = overlapped and k % args.bracket_every == args.bracket_every // 2
+        ahead = batches[it + 1] if (it + 1 < total and not args.no_lookahead and not alone) else None   # its top-down pass runs beside this step's layers
+        hp.overlap_update = overlapped and not alone
+        hp.run(batches[it], it, timer=timer_for(step_events, only=BRACKETED) if (alone or beside) else None, next_bt=ahead)
+        (ev if alone else ev_ovl).append(step_events)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
+    hp.overlap_update = overlapped
 
     ms_per_step = 1e3 * elapsed / args.steps
     value = args.steps / elapsed
@@ -263,6 +273,7 @@ def main():
         return {k: float(np.mean(v)) for k, v in out.items()}
 
     timed_ms = spans(ev)
+    timed_ovl_ms = spans(ev_ovl)
 
     # breakdown pass (not part of `value`): the iterations that follow the timed ones, on their own mini-batches, with
     # events around every call. It is a profile, not a result.
@@ -385,6 +396,9 @@ def main():
         loader_roof["traffic"] = profiled_traffic("loader_fetch_kernel<0, 0>" if dom_kernel.startswith("loader_fetch") else "aggregate_mean_kernel<0, 0, true, false")
         linear_roof["traffic"] = profiled_traffic("linear_f32x3_panel_kernel<2>")
     # `roofline` is the kernel with the longest launches in the timed region; the other one follows as `roofline_2`
+    if LOADER in timed_ovl_ms:       # the same launches as they run in most steps, beside the second stream's bookkeeping
+        loader_roof["ms_per_launch_overlapped"] = timed_ovl_ms[LOADER]
+        linear_roof["ms_per_launch_overlapped"] = timed_ovl_ms.get("linear[1]")
     roofline, roofline_2 = (loader_roof, linear_roof) if gather_ms >= lin1_ms else (linear_roof, loader_roof)
 
     hits = {l: float(np.mean([c[l][1] for c in counts_all])) for l in range(1, L)}
