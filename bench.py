@@ -145,7 +145,7 @@ def main():
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + extra + 32,
                                        hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads, model=args.model,
                                        fetch_with_loader=not args.separate_fetch, admit_budget=admit_budget,
-                                       overlap_update=not args.no_overlap_update)
+                                       overlap_update=not args.no_overlap_update, overlap_min_rows=65536)
     if args.one_launch_seed_layer:
         hp.fuse_small_layers = hp.model == "sage" and not hp.weight_grads
     ids_cols = not args.block_positions and not args.no_fuse

@@ -166,7 +166,7 @@ class HotPath:
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
                  one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage", fuse_small_layers=False,
-                 fetch_with_loader=True, admit_budget=None, overlap_update=True):
+                 fetch_with_loader=True, admit_budget=None, overlap_update=True, overlap_min_rows=0):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -240,7 +240,11 @@ class HotPath:
         self.update_all = update_all
         self.fetch_all = fetch_all   # the cached rows of all layers are fetched by one call right after the top-down pass
         self.fetch_with_loader = fetch_with_loader  # ... or inside the id-column loader's launch, where that loader runs
-        self.overlap_update = overlap_update  # selection part of the update on a second stream beside the layers (norms given from outside)
+        # selection part of the update (and the next top-down pass) on a second stream beside the layers (norms given from
+        # outside). Below about 65 k input rows per mini-batch the layers are too short to hide anything and the cross-stream
+        # waits cost more than they save: callers that time small workloads pass overlap_min_rows.
+        overlap_update = overlap_update and self.n_max[0] >= overlap_min_rows
+        self.overlap_update = overlap_update
         self.side = torch.cuda.Stream(device=device) if overlap_update else None
         self.ev_pruned, self.ev_selected, self.ev_next_pruned, self.ev_done = (torch.cuda.Event() for _ in range(4))
         self.admit_budget = dict(admit_budget) if admit_budget else None   # {layer: rows per update}: access-aware admission
@@ -581,7 +585,7 @@ class HotPath:
 
 def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None, p_grad=None, fused_input=False, one_launch_top_down=True, update_all=True, log_ring=256,
                  hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage",
-                 fetch_with_loader=True, admit_budget=None, overlap_update=True):
+                 fetch_with_loader=True, admit_budget=None, overlap_update=True, overlap_min_rows=0):
     """HotPath for workload `w` with its feature table resident where the workload says."""
     from fg_inputs import device as fdev, workload as wl
     dims = wl.layer_dims(w)
@@ -595,7 +599,8 @@ def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None
                  w.feat_dtype, w.compute_dtype, weights, features_on_host=(w.feat_location == "host"),
                  use_cache=use_cache, fused_input=fused_input, one_launch_top_down=one_launch_top_down, update_all=update_all,
                  fetch_all=update_all, log_ring=log_ring, hot_ids=hot_ids, buffer_bytes=buffer_bytes, backward=backward, weight_grads=weight_grads, stabilization=stabilization, model=model,
-                 fetch_with_loader=fetch_with_loader, admit_budget=admit_budget, overlap_update=overlap_update)
+                 fetch_with_loader=fetch_with_loader, admit_budget=admit_budget, overlap_update=overlap_update,
+                 overlap_min_rows=overlap_min_rows)
     return hp, weights, feat_table
 
 
