@@ -224,6 +224,7 @@ class HotPath:
                        dict(live=mk(torch.uint8), hit=mk(torch.uint8), hit_pos=mk(torch.int32), hit_slot=mk(torch.int32),
                             normal_pos=mk(torch.int32), input_ids=torch.zeros_like(self.input_ids), self_ids=torch.zeros_like(self.self_ids))]
         self._td_for = None      # (iteration, id of the mini-batch) whose top-down pass has already been launched on the second stream
+        self._row_copy_due = None  # (iteration, descriptors) of a selection whose rows are not copied yet
         # device-side counts/stats are kept per iteration in a ring, so a timed loop can be read back afterwards
         self.ring = int(log_ring)
         self.counts_log = torch.zeros((self.ring, L + 1, 3), dtype=torch.int64, device=dev)
@@ -303,6 +304,8 @@ class HotPath:
 
     def close(self):
         if self.cache is not None:
+            self.flush()
+            torch.cuda.synchronize()
             B.fg_cache_destroy(self.cache)
             self.cache = None
 
@@ -355,6 +358,19 @@ class HotPath:
                                   a["hit_dev"], a["hit_pos_dev"], a["hit_slot_dev"], a["normal_pos_dev"], a["normal_ids_dev"],
                                   a["counts_dev"], self.ws, self.ws_bytes, st)
 
+    def flush(self, selection_done=False):
+        """Copy the rows admitted by the last iteration into the cache, if that is still due (`run` leaves it to the next
+        call when that call's top-down pass is already on the second stream). Called by everything that reads the cache."""
+        if self._row_copy_due is None:
+            return
+        it, specs = self._row_copy_due
+        self._row_copy_due = None
+        main = torch.cuda.current_stream()
+        if not selection_done:
+            main.wait_event(self.ev_selected)
+        B.fg_cache_update_commit(self.cache, it, specs, self.ws_upd, self.ws_upd_bytes, main.cuda_stream)
+        self.ev_done.record(main)
+
     def _bind(self, it):
         """Point the per-iteration state (lists of the top-down pass, counters, statistics) at iteration `it`'s copies."""
         for k, v in self._lists[it % 2].items():
@@ -379,8 +395,10 @@ class HotPath:
         pruned_ahead = self._td_for == (it, id(bt))
         self._td_for = None
         if pruned_ahead:
-            torch.cuda.current_stream().wait_event(self.ev_next_pruned)
+            torch.cuda.current_stream().wait_event(self.ev_next_pruned)   # behind the previous selection on that stream
+            self.flush(selection_done=True)
         else:
+            self.flush()
             self._top_down(bt, it, st, tick)
 
         cached_layers = list(range(1, L)) if (self.use_cache and self.cache is not None) else []
@@ -510,10 +528,10 @@ class HotPath:
                                                 self.dW[l], self.db[l], self.ws_wg, self.ws_wg_bytes, st)
         # ---- update of the caches
         if early_select is not None:      # the selection ran beside the layers: only the admitted rows are left to copy
-            tick("cache_update_commit")
-            torch.cuda.current_stream().wait_event(self.ev_selected)
-            B.fg_cache_update_commit(self.cache, it, early_select, self.ws_upd, self.ws_upd_bytes, st)
-            self.ev_done.record(torch.cuda.current_stream())
+            self._row_copy_due = (it, early_select)
+            if self._td_for is None:      # otherwise the next call does it, behind the wait it has anyway (one wait less per step)
+                tick("cache_update_commit")
+                self.flush()
         elif do_update and self.update_all:
             if self.admit_budget:   # access-aware admission: the estimates, bottom-up over the pruned blocks
                 tick("access_estimate")
@@ -531,6 +549,7 @@ class HotPath:
     # ---- read-back helpers for tests and reports (synchronising) -------------------------------------------
     def snapshot(self, bt):
         """Host copies of what one `run` produced (lists cut to their device-side counts)."""
+        self.flush()
         L = self.L
         torch.cuda.synchronize()
         counts = self.counts.cpu().numpy()
@@ -557,6 +576,7 @@ class HotPath:
         return out[:n].cpu().numpy(), int(found.item())
 
     def export_cache(self, layer, it):
+        self.flush()
         cap = self.capacity[layer - 1]
         dev = self.device
         nodes = torch.zeros(cap, dtype=torch.int32, device=dev)
@@ -574,6 +594,7 @@ class HotPath:
 
     def cache_rows(self, layer, slots):
         """Rows of the cache table at the given slots, as a host array (bf16 widened to fp32)."""
+        self.flush()
         cap, d = self.capacity[layer - 1], self.dims[layer]
         nbytes = cap * d * B.DTYPE_SIZE[self.comp_code]
         tab = _tensor_from_ptr(B.fg_cache_table(self.cache, layer), (cap, d), TORCH_DTYPE[self.comp_code], nbytes, self.device)
