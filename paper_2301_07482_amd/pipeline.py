@@ -223,7 +223,7 @@ class HotPath:
                             input_ids=self.input_ids, self_ids=self.self_ids),
                        dict(live=mk(torch.uint8), hit=mk(torch.uint8), hit_pos=mk(torch.int32), hit_slot=mk(torch.int32),
                             normal_pos=mk(torch.int32), input_ids=torch.zeros_like(self.input_ids), self_ids=torch.zeros_like(self.self_ids))]
-        self._td_for = None      # (iteration, id of the mini-batch) whose top-down pass has already been launched on the second stream
+        self._td_for = None      # (iteration, mini-batch) whose top-down pass has already been launched on the second stream
         self._row_copy_due = None  # (iteration, descriptors) of a selection whose rows are not copied yet
         # device-side counts/stats are kept per iteration in a ring, so a timed loop can be read back afterwards
         self.ring = int(log_ring)
@@ -392,13 +392,13 @@ class HotPath:
         do_update = update and self.use_cache and self.cache is not None
         assert all(bt.n[l] <= self.n_max[l] for l in range(L + 1)), "mini-batch larger than the static bounds"
         fused = self.fused_input
-        pruned_ahead = self._td_for == (it, id(bt))
+        promised = self._td_for is not None
+        pruned_ahead = promised and self._td_for[0] == it and self._td_for[1] is bt
         self._td_for = None
-        if pruned_ahead:
+        if promised:      # (also when the promise was not kept: that pass writes the lists this call is about to use)
             torch.cuda.current_stream().wait_event(self.ev_next_pruned)   # behind the previous selection on that stream
-            self.flush(selection_done=True)
-        else:
-            self.flush()
+        self.flush(selection_done=promised)
+        if not pruned_ahead:
             self._top_down(bt, it, st, tick)
 
         cached_layers = list(range(1, L)) if (self.use_cache and self.cache is not None) else []
@@ -426,7 +426,7 @@ class HotPath:
                     self._bind(it + 1)
                     self._top_down(next_bt, it + 1, self.side.cuda_stream, lambda name, stream=None: None)
                     self.ev_next_pruned.record(self.side)
-                    self._td_for = (it + 1, id(next_bt))
+                    self._td_for = (it + 1, next_bt)
                     self._bind(it)
         fetch_specs = None
         if self.fetch_all and cached_layers:

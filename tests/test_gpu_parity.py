@@ -1062,6 +1062,35 @@ def test_iterations_tiny(env):
     assert run_workload_parity(torch, w, w.iterations, lookahead=True, fused=True, col_ids=True, admit_budget={1: 60})[0] > 0
 
 
+def test_lookahead_promise_not_kept(env):
+    """A mini-batch announced as the next one (its top-down pass is then already on the second stream) but not run next:
+    the call that follows, for another mini-batch, still gives the sequential results."""
+    torch, B = env
+    from paper_2301_07482_amd.pipeline import DeviceBatch
+    w = wl.WORKLOADS["tiny"]
+    g = wl.make_graph(w)
+    L = w.num_layers
+    hp, weights, _ = G.make_hotpath(w, fused_input=True)
+    ref, _, _ = G.make_hotpath(w, fused_input=True, overlap_update=False)
+    try:
+        def batch(it):
+            mb = wl.minibatch(w, g, it)
+            return DeviceBatch(mb, {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}, col_ids=True)
+        for it in range(8):
+            decoy = batch(100 + it) if it % 2 else None          # announced, never run
+            hp.run(batch(it), it, next_bt=decoy)
+            ref.run(batch(it), it)
+            torch.cuda.synchronize()
+            n = len(wl.minibatch(w, g, it).ids[L])
+            assert torch.equal(hp.H[L][:n], ref.H[L][:n]), f"outputs, iteration {it}"
+            for l in range(1, L):
+                ea, eb = hp.export_cache(l, it + 1), ref.export_cache(l, it + 1)
+                assert ea["head"] == eb["head"] and np.array_equal(ea["nodes"], eb["nodes"]) and np.array_equal(ea["slots"], eb["slots"])
+    finally:
+        hp.close()
+        ref.close()
+
+
 def test_iterations_tiny_layer_by_layer_top_down(env):
     """The same iterations with one fg_lookup_prune and one fg_cache_update call per layer instead of fg_top_down and
     fg_cache_update_all."""
