@@ -758,20 +758,20 @@ fg_status_t launch_update(UpdBatch& B, hipStream_t st, bool select = true, bool 
     }
     const unsigned n_sel = (unsigned)B.sel_first[B.n_layers], n_scan = (unsigned)B.scan_first[B.n_layers];
     if (select) {
-    hipLaunchKernelGGL(update_digit0_kernel, dim3(n_sel), dim3(SEL_THREADS), 0, st, B);
-    FG_LAUNCH_CHECK("update_digit0_kernel");
-    hipLaunchKernelGGL(update_digit1_kernel, dim3(n_sel), dim3(SEL_THREADS), 0, st, B);
-    FG_LAUNCH_CHECK("update_digit1_kernel");
-    hipLaunchKernelGGL(classify_update_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
-    FG_LAUNCH_CHECK("classify_update_kernel");
-    bool ranked = false;
-    for (int i = 0; i < B.n_layers; ++i) ranked |= B.l[i].saving != nullptr;
-    if (ranked) {
-        hipLaunchKernelGGL(rank_saving_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
-        FG_LAUNCH_CHECK("rank_saving_kernel");
-    }
-    hipLaunchKernelGGL(assign_slots_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
-    FG_LAUNCH_CHECK("assign_slots_kernel");
+        hipLaunchKernelGGL(update_digit0_kernel, dim3(n_sel), dim3(SEL_THREADS), 0, st, B);
+        FG_LAUNCH_CHECK("update_digit0_kernel");
+        hipLaunchKernelGGL(update_digit1_kernel, dim3(n_sel), dim3(SEL_THREADS), 0, st, B);
+        FG_LAUNCH_CHECK("update_digit1_kernel");
+        hipLaunchKernelGGL(classify_update_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
+        FG_LAUNCH_CHECK("classify_update_kernel");
+        bool ranked = false;
+        for (int i = 0; i < B.n_layers; ++i) ranked |= B.l[i].saving != nullptr;
+        if (ranked) {
+            hipLaunchKernelGGL(rank_saving_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
+            FG_LAUNCH_CHECK("rank_saving_kernel");
+        }
+        hipLaunchKernelGGL(assign_slots_kernel, dim3(n_scan), dim3(FG_SCAN_BLOCK), 0, st, B);
+        FG_LAUNCH_CHECK("assign_slots_kernel");
     }
     if (!commit) return FG_OK;
     fg_row_copy_batch copies;  // table[aslot[k], :] = h[apos[k], :] for the admitted rows of every layer
@@ -781,9 +781,7 @@ fg_status_t launch_update(UpdBatch& B, hipStream_t st, bool select = true, bool 
         const int64_t cap = u.n < u.c.capacity ? u.n : u.c.capacity;
         copies.c[i] = fg_row_copy{u.h, u.n, u.h_stride, u.apos, u.aslot, &u.hdr->n_admit, cap, u.table, u.c.capacity, u.row_bytes, u.row_bytes};
     }
-    fg_status_t rc = fg_launch_row_copies(copies, st);
-    if (rc != FG_OK) return rc;
-    return FG_OK;
+    return fg_launch_row_copies(copies, st);
 }
 
 }  // namespace
