@@ -38,3 +38,13 @@ def test_one_json_line_with_the_agreed_fields():
     assert r["bound"] in ("hbm", "mfma", "alu", "host_link") and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["value"] > 0 and c["cores"] >= 1 and c["unit"] == d["unit"] and c["sample"]
+
+
+@pytest.mark.gpu
+def test_plain_c_caller():
+    """tests/c/c_abi_example (built by __graft_entry__.build() with gcc): the library called from C without Python or torch."""
+    exe = os.path.join(ROOT, "tests", "c", "c_abi_example")
+    if not os.path.exists(exe):
+        pytest.skip("tests/c/c_abi_example is not built: run __graft_entry__.build()")
+    p = subprocess.run([exe], capture_output=True, text=True, timeout=300)
+    assert p.returncode == 0 and p.stdout.strip() == "ok", (p.returncode, p.stdout, p.stderr)
