@@ -248,6 +248,7 @@ class HotPath:
         self.overlap_update = overlap_update
         self.side = torch.cuda.Stream(device=device) if overlap_update else None
         self.ev_pruned, self.ev_selected, self.ev_next_pruned, self.ev_done = (torch.cuda.Event() for _ in range(4))
+        self.ev_bw = [torch.cuda.Event() for _ in range(L + 1)]
         self.admit_budget = dict(admit_budget) if admit_budget else None   # {layer: rows per update}: access-aware admission
         assert not (self.admit_budget and not update_all), "the access-aware admission needs fg_cache_update_all"
         self.ws_upd_bytes = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L))
@@ -509,8 +510,26 @@ class HotPath:
         # ---- loss and backward pass down to layer 1: the gradient norms the update admits and checks out by
         gnorm = bt.gnorm
         if self.backward:
+            def weight_grads(l, stream):
+                B.fg_layer_backward_weights(self.H[l - 1], bt.n[l - 1], self.dims[l - 1] * 4, self.AGG_l[l], self.dims[l - 1] * 4,
+                                            self.dH[l], self.dims[l] * 4, self.H[l] if l < L else None, self.dims[l] * 4, bt.n[l],
+                                            self.normal_pos[l], self._cnt(l, 2), bt.n[l], self.dims[l - 1], self.dims[l],
+                                            self.dW[l], self.db[l], self.ws_wg, self.ws_wg_bytes, stream)
+
+            # The weight gradients of a layer need that layer's output gradient and nothing later: with a second stream they
+            # run there, each as soon as its dH exists, beside the rest of the backward chain and the cache update.
+            wg_beside = self.weight_grads and self.overlap_update and timer is None
+
+            def weight_grads_beside(l):
+                self.ev_bw[l].record(torch.cuda.current_stream())
+                with torch.cuda.stream(self.side):
+                    self.side.wait_event(self.ev_bw[l])
+                    weight_grads(l, self.side.cuda_stream)
+
             tick("loss_grad")
             B.fg_softmax_xent_grad(self.H[L], self.dims[L] * 4, bt.labels, bt.n[L], self.dims[L], self.dH[L], self.dims[L] * 4, st)
+            if wg_beside:
+                weight_grads_beside(L)
             for l in range(L, 1, -1):
                 tick(f"layer_backward[{l}]")
                 B.fg_layer_backward(self.dH[l], self.dims[l] * 4, self.H[l] if l < L else None, self.dims[l] * 4, bt.n[l],
@@ -518,14 +537,13 @@ class HotPath:
                                     bt.start[l], bt.end[l], bt.t_start[l], bt.t_end[l], bt.t_row[l], bt.nnz[l], bt.n[l - 1],
                                     self.dims[l - 1], self.dims[l], self.W[l], self.dH[l - 1], self.dims[l - 1] * 4,
                                     self.gnorm[l - 1], self.ws_bw, self.ws_bw_bytes, st)   # with the row norms of dH[l-1]
+                if wg_beside:
+                    weight_grads_beside(l - 1)
             gnorm = self.gnorm
-            if self.weight_grads:
+            if self.weight_grads and not wg_beside:
                 for l in range(L, 0, -1):
                     tick(f"weight_grads[{l}]")
-                    B.fg_layer_backward_weights(self.H[l - 1], bt.n[l - 1], self.dims[l - 1] * 4, self.AGG_l[l], self.dims[l - 1] * 4,
-                                                self.dH[l], self.dims[l] * 4, self.H[l] if l < L else None, self.dims[l] * 4, bt.n[l],
-                                                self.normal_pos[l], self._cnt(l, 2), bt.n[l], self.dims[l - 1], self.dims[l],
-                                                self.dW[l], self.db[l], self.ws_wg, self.ws_wg_bytes, st)
+                    weight_grads(l, st)
         # ---- update of the caches
         if early_select is not None:      # the selection ran beside the layers: only the admitted rows are left to copy
             self._row_copy_due = (it, early_select)
@@ -544,6 +562,9 @@ class HotPath:
                 tick(f"cache_update[{l}]")
                 B.fg_cache_update(self.cache, l, it, bt.ids[l], bt.n[l], self.live[l], self.hit[l], gnorm[l],
                                   self.p_grad, self.H[l], out_b, self.stats.data_ptr() + l * 32, self.ws, self.ws_bytes, st)
+        if self.backward and self.weight_grads and self.overlap_update and timer is None:
+            self.ev_bw[0].record(self.side)       # the next iteration overwrites what the weight gradients read
+            torch.cuda.current_stream().wait_event(self.ev_bw[0])
         tick(None)
 
     # ---- read-back helpers for tests and reports (synchronising) -------------------------------------------
