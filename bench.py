@@ -454,7 +454,8 @@ def main():
         rows_no_cache = float(np.mean([batches[it].nnz[1] + batches[it].n[1] for it in steps_it]))
 
     if args.device_sampler:      # the loop with nothing resident beforehand but the graph, the table and the seeds
-        sampler_report["in_loop"] = sampled_loop(w, hp, ds, first_it=total + extra, steps=args.steps, warmup=10, backward=args.backward)
+        sampler_report["in_loop"] = sampled_loop(w, hp, ds, first_it=total + extra, steps=args.steps, warmup=10, backward=args.backward,
+                                                 lookahead=not args.no_lookahead)
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -499,7 +500,7 @@ def main():
     print(json.dumps(out))
 
 
-def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False):
+def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False, lookahead=True):
     """Iterations whose mini-batches are sampled on the device while the loop runs: the sampler works one mini-batch ahead on
     a second stream (its three layer sizes reach the host through a pinned copy on that stream), gradient norms are made on
     the device from the sampled node ids, and the path waits for the sampler's event. Four sets of buffers rotate."""
@@ -536,24 +537,35 @@ def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False):
             sampled_ev[k].record(side)
         return bt
 
-    pending = launch(0)
+    def ready(t, bt):
+        """Mini-batch t with its layer sizes on the host (waits for the sampler's event) and the path's stream behind it."""
+        k = t % K
+        sampled_ev[k].synchronize()
+        bt.finish(host_counts[k])
+        main.wait_event(sampled_ev[k])
+        return bt
+
+    # the sampler works two mini-batches ahead, so that the next one is complete (sizes known) when this one is run and
+    # its top-down pass can go to the second stream beside this one's layers
+    queue = {0: launch(0)}
+    if n_it > 1:
+        queue[1] = launch(1)
+    cur = ready(0, queue.pop(0))
     t_start = None
     for t in range(n_it):
         if t == warmup:
             torch.cuda.synchronize()
             t_start = time.time()
-        nxt = launch(t + 1) if t + 1 < n_it else None
-        k = t % K
-        sampled_ev[k].synchronize()                    # the host needs the layer sizes
-        pending.finish(host_counts[k])
-        main.wait_event(sampled_ev[k])
-        hp.run(pending, first_it + t)
-        consumed_ev[k].record(main)
-        pending = nxt
+        if t + 2 < n_it:
+            queue[t + 2] = launch(t + 2)
+        nxt = ready(t + 1, queue.pop(t + 1)) if t + 1 < n_it else None
+        hp.run(cur, first_it + t, next_bt=nxt if lookahead else None)
+        consumed_ev[t % K].record(main)
+        cur = nxt
     torch.cuda.synchronize()
     dt = time.time() - t_start
     return {"steps": steps, "warmup": warmup, "ms_per_step": 1e3 * dt / steps, "minibatches_per_s": steps / dt,
-            "note": "sampling (second stream, one mini-batch ahead), gradient norms and the whole path inside the timed loop"}
+            "note": "sampling (a stream of its own, two mini-batches ahead), gradient norms and the whole path inside the timed loop"}
 
 
 def profiled_traffic(kernel_prefix):
