@@ -18,6 +18,13 @@ pytestmark = pytest.mark.gpu
 REL_TOL_F32 = 1e-5
 
 
+def random_seeds(default):
+    """Seeds of the random-configuration tests: FG_RANDOM_SEEDS of them (default given per test), starting at
+    FG_RANDOM_SEED_BASE (default 0), so that a longer run can cover seeds that the default run does not."""
+    base = int(os.environ.get("FG_RANDOM_SEED_BASE", "0"))
+    return range(base, base + int(os.environ.get("FG_RANDOM_SEEDS", str(default))))
+
+
 @pytest.fixture(scope="module")
 def env():
     import torch
@@ -1184,7 +1191,7 @@ def test_iterations_one_launch_seed_layer(env):
         P.HotPath.__init__ = real
 
 
-@pytest.mark.parametrize("seed", range(int(os.environ.get("FG_RANDOM_SEEDS", "10"))))
+@pytest.mark.parametrize("seed", random_seeds(10))
 def test_iterations_random_configurations(env, seed):
     """Depths 1 to 4, random widths (multiples of 4, so the tiled and the panel GEMMs both occur), fan-outs, batch sizes,
     cache sizes (down to rings that overflow), admission fractions and staleness bounds, in a random pipeline mode."""
@@ -1208,7 +1215,7 @@ def test_iterations_random_configurations(env, seed):
     run_workload_parity(torch, w, 9, fused=fused, one_launch_top_down=one_launch, conditioned=True)
 
 
-@pytest.mark.parametrize("seed", range(int(os.environ.get("FG_RANDOM_SEEDS", "10"))))
+@pytest.mark.parametrize("seed", random_seeds(10))
 def test_iterations_random_configurations_widened(env, seed):
     """The options added around the core path, drawn at random together: mini-batches sampled on the device, block columns
     as node ids with the cache fetch inside or outside the loader's launch, access-aware admission with random budgets, a
@@ -1234,7 +1241,7 @@ def test_iterations_random_configurations_widened(env, seed):
     run_workload_parity(torch, w, 9, conditioned=True, **kw)
 
 
-@pytest.mark.parametrize("seed", range(int(os.environ.get("FG_RANDOM_SEEDS", "6"))))
+@pytest.mark.parametrize("seed", random_seeds(6))
 def test_iterations_random_feature_side(env, seed):
     """Random depths, row widths, ring sizes, buffer sizes and hot-list lengths for the bidirectional cache, with the
     table rows of the cached nodes negated after the fill: ranks, gathered rows and buffer contents are compared bit for bit."""
