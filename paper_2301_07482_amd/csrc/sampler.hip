@@ -77,11 +77,9 @@ __device__ __forceinline__ void smp_insert(const SmpArgs& A, int32_t node, uint3
     const unsigned long long mine = ((unsigned long long)(uint32_t)node << 32) | order;
     uint32_t h = smp_hash(A, node);
     for (uint32_t probe = 0; probe <= A.mask; ++probe) {
-        unsigned long long cur = __hip_atomic_load(&A.table[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (cur == SMP_EMPTY) {
-            cur = atomicCAS(&A.table[h], SMP_EMPTY, mine);
-            if (cur == SMP_EMPTY) return;
-        }
+        // most nodes occur once, so the slot is usually empty: one operation instead of a load followed by one
+        const unsigned long long cur = atomicCAS(&A.table[h], SMP_EMPTY, mine);
+        if (cur == SMP_EMPTY) return;
         if ((uint32_t)(cur >> 32) == (uint32_t)node) {
             atomicMin(&A.table[h], mine);
             return;
