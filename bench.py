@@ -45,8 +45,8 @@ def sample_batches(name, count, workers):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="large_hbm")
     ap.add_argument("--scale", type=int, default=1, help="divide node/edge/cache counts (debugging on small boxes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -125,7 +125,7 @@ def main():
     extra = min(args.steps, 20)        # further mini-batches for the per-call breakdown pass after the timed region
     t0 = time.time()
     if args.device_sampler:      # the mini-batches are sampled on the device below; the host samples only what the CPU oracle is timed on
-        sampled = [] if args.no_cpu_baseline else sample_batches(w.name, 10, args.sample_workers)
+        sampled = [] if args.no_cpu_baseline else sample_batches(w.name, 20, args.sample_workers)
     else:
         sampled = sample_batches(w.name, total + extra, args.sample_workers)
     t_sample = time.time() - t0
@@ -582,7 +582,7 @@ def profiled_traffic(kernel_prefix):
     return None
 
 
-def time_oracle(w, sampled, weights, iterations=10):
+def time_oracle(w, sampled, weights, iterations=20):
     """The CPU oracle timed on the first `iterations` mini-batches of the same workload (from an empty cache),
     single-threaded; feature rows are regenerated beforehand and not timed."""
     import numpy as np
