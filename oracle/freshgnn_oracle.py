@@ -31,7 +31,10 @@ weights; a depth-first "needed set" for the pruning; a dictionary model of the
 cache; hand-worked admit/evict/staleness/ring traces; the degenerate settings of
 Section 4.1.3; for the shared buffer a byte-by-byte model of what has been overwritten,
 a hand-worked displacement trace, and the bit-identity of every loaded feature row; for the backward
-pass central finite differences of the loss through the forward functions of this file. The I/O-saving percentages the paper reports depend on its
+pass (GraphSAGE and GCN layers) central finite differences of the loss through the forward functions of this file;
+for the mixed-precision setting (fp16 features, bf16 operands of every matrix product, bf16 embeddings, fp32 last
+layer) a hand-worked example, identity-panel weights that expose each rounded operand bit for bit, and exact
+rational arithmetic, with a library bfloat16 conversion as the rounding routine. The I/O-saving percentages the paper reports depend on its
 datasets and real gradients: parity unpinned for those, they are not reproduced.
 The access-aware admission is pinned to the reading stated in `access_estimate` and `cache_update` (an
 instrumented recursive evaluation that counts the rows it reads, closed forms on full trees, the rank definition
@@ -395,7 +398,7 @@ def row_norms(x):
     return np.sqrt((x * x).sum(axis=1))
 
 
-def layer_backward(start, end, col, rows, dh, h_out, h_self, agg, W, n_src, relu):
+def layer_backward(start, end, col, rows, dh, h_out, h_self, agg, W, n_src, relu, compute_dtype="f32"):
     """Backward of one GraphSAGE-mean layer (Eq. 1 with the readings of `aggregate` and `linear`) for the rows in
     `rows` (V_normal of the layer; fetched and pruned rows were not computed, so nothing flows below them).
 
@@ -405,15 +408,21 @@ def layer_backward(start, end, col, rows, dh, h_out, h_self, agg, W, n_src, relu
       dz = dh[rows] * (h_out[rows] > 0)  (no mask after the last layer)
       dW = [h_self ‖ agg]^T dz,  db = sum of dz,  [d_self ‖ d_agg] = dz W^T
       dH(l-1)[r] += d_self  for r in rows;  dH(l-1)[c] += d_agg / deg(r)  for every sampled neighbour c of r
+    In the bf16 setting the operands of both matrix products are bf16, as in the forward product: dz is rounded to
+    bf16 before it enters dz W^T and [h_self ‖ agg]^T dz (h_self and agg arrive rounded, W is rounded here); the bias
+    gradient sums the unrounded dz; products, sums and every result stay in higher precision.
     """
     W = np.asarray(W, dtype=np.float64)
     d_in = W.shape[0] // 2
     dz = np.asarray(dh, dtype=np.float64)[rows]
     if relu:
         dz = dz * (np.asarray(h_out)[rows] > 0)
+    db = dz.sum(axis=0)
+    if compute_dtype == "bf16":
+        dz = round_bf16(dz).astype(np.float64)
+        W = round_bf16(W).astype(np.float64)
     x = np.concatenate([np.asarray(h_self, dtype=np.float64), np.asarray(agg, dtype=np.float64)], axis=1)
     dW = x.T @ dz
-    db = dz.sum(axis=0)
     dx = dz @ W.T
     dsrc = np.zeros((n_src, d_in), dtype=np.float64)
     for k, r in enumerate(rows):
@@ -424,13 +433,41 @@ def layer_backward(start, end, col, rows, dh, h_out, h_self, agg, W, n_src, relu
     return dsrc, dW, db
 
 
-def backward(mb, rec, weights, labels, compute_dtype="f32"):
+def layer_backward_gcn(start, end, col, rows, dh, h_out, agg, W, n_src, relu):
+    """Backward of one GCN layer in the form of `aggregate_gcn` / `linear_gcn`, for the rows in `rows`.
+
+    agg = the propagated rows m_r = (h_r + sum of the sampled neighbours' rows) / (deg(r) + 1) that entered the layer.
+      dz = dh[rows] * (h_out[rows] > 0)  (no mask after the last layer)
+      dW = agg^T dz,  db = sum of dz,  dm = dz W^T
+      dH(l-1)[r] += dm_r / (deg(r) + 1);  dH(l-1)[c] += dm_r / (deg(r) + 1)  for every sampled neighbour c of r
+    Returns dL/dH(l-1) by position [n_src, d_in], dL/dW [d_in, d_out], dL/db [d_out], float64.
+    """
+    W = np.asarray(W, dtype=np.float64)
+    dz = np.asarray(dh, dtype=np.float64)[rows]
+    if relu:
+        dz = dz * (np.asarray(h_out)[rows] > 0)
+    dW = np.asarray(agg, dtype=np.float64).T @ dz
+    db = dz.sum(axis=0)
+    dm = dz @ W.T
+    dsrc = np.zeros((n_src, W.shape[0]), dtype=np.float64)
+    for k, r in enumerate(rows):
+        nb = col[start[r]:end[r]]
+        share = dm[k] / float(len(nb) + 1)
+        dsrc[r] += share
+        if len(nb):
+            np.add.at(dsrc, nb, share)
+    return dsrc, dW, db
+
+
+def backward(mb, rec, weights, labels, compute_dtype="f32", model="sage"):
     """loss.backward() of Alg. 1 over the pruned mini-batch of one `iteration` record.
 
     Gradients flow from the seeds down through the rows that were computed (V_normal); a fetched embedding
     receives its gradient (that is the "zero-cost" signal of Section 4.1.1) and passes nothing below.
     Returns dH[l] (float64 by position, l = 1..L), gnorm[l] = row norms rounded to float32 (l = 1..L-1),
     dW[l], db[l]. The gradient with respect to raw features is not formed.
+    In the bf16 setting dH(l) is carried as float32 between the layers (each layer's result rounded once to float32,
+    as the device stores it) and the matrix products take bf16 operands (`layer_backward`).
     """
     L = mb.num_layers
     H, AGG, look = rec["H"], rec["AGG"], rec["look"]
@@ -439,9 +476,14 @@ def backward(mb, rec, weights, labels, compute_dtype="f32"):
     for l in range(L, 0, -1):
         rows = look[l]["normal_pos"]
         h_prev = np.asarray(H[l - 1])
-        h_self = round_bf16(h_prev[rows].astype(np.float64)) if compute_dtype == "bf16" else h_prev[rows]
-        dsrc, dW[l], db[l] = layer_backward(mb.start[l], mb.end[l], mb.col[l], rows, dH[l], H[l], h_self, AGG[l], weights[l][0],
-                                            len(mb.ids[l - 1]), relu=(l < L))
+        if model == "gcn":
+            dsrc, dW[l], db[l] = layer_backward_gcn(mb.start[l], mb.end[l], mb.col[l], rows, dH[l], H[l], AGG[l], weights[l][0],
+                                                    len(mb.ids[l - 1]), relu=(l < L))
+        else:
+            h_self = round_bf16(h_prev[rows].astype(np.float64)) if compute_dtype == "bf16" else h_prev[rows]
+            dh_l = dH[l].astype(np.float32) if compute_dtype == "bf16" else dH[l]
+            dsrc, dW[l], db[l] = layer_backward(mb.start[l], mb.end[l], mb.col[l], rows, dh_l, H[l], h_self, AGG[l], weights[l][0],
+                                                len(mb.ids[l - 1]), relu=(l < L), compute_dtype=compute_dtype)
         if l >= 2:
             dH[l - 1] = dsrc
     gnorm = {l: row_norms(dH[l]).astype(np.float32) for l in range(1, L)}
@@ -574,7 +616,7 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
     dims      [d_0..d_L]
     feature_side   optional BidirectionalCache whose rings are `caches`: raw features are loaded through it
     model     "sage": GraphSAGE-mean layers (`aggregate`, `linear`, W_l [2*d, d']); "gcn": GCN layers (`aggregate_gcn`,
-              `linear_gcn`, W_l [d, d']), fp32 only, no backward pass
+              `linear_gcn`, W_l [d, d']), fp32 only
     stabilization   length of the stabilization period (Section 4.1.4): in iterations i < stabilization the historical
               cache is disabled (no lookup, no admission: regular mini-batch training), afterwards it is active
     admit_budget   optional {l: rows}: the access-aware admission policy. A layer's update admits at most that many rows
@@ -582,7 +624,9 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
     labels    optional class of every seed: the gradient norms then come from `backward` (softmax cross-entropy on
               H(L)) and `gnorms` is ignored
     Types: H(0) in feat_dtype; H(l), AGG(l) for l >= 1 in compute_dtype except H(L) which is fp32.
-    In the bf16 setting the own rows and the mean are rounded to bf16 before the product and W is bf16.
+    In the bf16 setting the operands of the product are bf16: the own rows, the mean and W are each rounded to bf16
+    before it (a no-op for operands stored as bf16); products, sums, bias and ReLU stay in higher precision, and the
+    result is rounded once to the layer's storage type.
     Returns a record of every intermediate the GPU path exposes.
     """
     L = mb.num_layers
@@ -619,7 +663,7 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
         rows = look[l]["normal_pos"]
         W, b = weights[l]
         if model == "gcn":
-            assert compute_dtype == "f32" and labels is None
+            assert compute_dtype == "f32"
             AGG[l] = round_to(aggregate_gcn(mb.start[l], mb.end[l], mb.col[l], rows, H[l - 1]), "f32")
             H[l][rows] = round_to(linear_gcn(AGG[l], W, b, relu=(l < L)), out_dtype)
             continue
@@ -627,6 +671,7 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
         if compute_dtype == "bf16":
             AGG[l] = round_bf16(agg64)
             h_self = round_bf16(H[l - 1][rows].astype(np.float64))
+            W = round_bf16(W)
         else:
             AGG[l] = round_to(agg64, "f32")
             h_self = H[l - 1][rows]
@@ -635,7 +680,7 @@ def iteration(mb, i, caches, feature_rows, weights, gnorms, p_grad, dims, feat_d
     stats = {}
     rec.update(live=live, look=look, H=H, AGG=AGG)
     if labels is not None:
-        rec["backward"] = backward(mb, rec, weights, labels, compute_dtype)
+        rec["backward"] = backward(mb, rec, weights, labels, compute_dtype, model)
         gnorms = rec["backward"]["gnorm"]
     if not cache_active:
         stats = {l: dict(admitted=0, evicted_by_gradient=0, overwritten=0, dropped_overflow=0, tau=None) for l in range(1, L)}

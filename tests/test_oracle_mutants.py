@@ -10,6 +10,7 @@ from oracle import freshgnn_oracle as O
 from tests import test_oracle_access_policy as AP
 from tests import test_oracle_backward as BW
 from tests import test_oracle_feature_side as F
+from tests import test_oracle_mixed_precision as MP
 from tests import test_oracle_pins as P
 
 PINS = [
@@ -49,6 +50,13 @@ PINS = [
     (AP.test_admission_is_the_rank_definition, [(0,), (1,), (2,)]),
     (AP.test_without_estimates_and_budget_nothing_changes, [(5, 2, 0.5), (16, 4, 0.9)]),
     (AP.test_iteration_with_budget_admits_the_costliest_rows, [()]),
+    (MP.test_worked_example_of_the_rounding_points, [()]),
+    (MP.test_identity_panels_show_each_rounded_operand_bit_for_bit, [(0,), (1,)]),
+    (MP.test_products_take_bf16_operands_and_the_last_layer_keeps_fp32, [()]),
+    (MP.test_cached_rows_are_bf16_and_fetched_bit_for_bit, [()]),
+    (MP.test_backward_rounds_the_output_gradient_before_both_products, [()]),
+    (MP.test_backward_of_a_lower_layer_masks_then_rounds_and_uses_rounded_weights, [()]),
+    (MP.test_gcn_gradients_against_finite_differences, [(0,), (1,)]),
 ]
 
 # (owner, function, text in its source, replacement)
@@ -153,6 +161,42 @@ MUTANTS = [
     ("the GCN layer never applies ReLU", None, "linear_gcn", "if relu else z", "if False else z"),
     ("the stabilization period ends one iteration early", None, "iteration", "cache_active = i >= stabilization", "cache_active = i >= stabilization - 1"),
     ("the cache is looked up during the stabilization period", None, "iteration", "    if not cache_active:\n        caches = {}\n", ""),
+    ("mixed precision: the mean enters the product unrounded", None, "iteration", "AGG[l] = round_bf16(agg64)", 'AGG[l] = round_to(agg64, "f32")'),
+    ("mixed precision: the mean is rounded to fp16 instead of bf16", None, "iteration", "AGG[l] = round_bf16(agg64)",
+     'AGG[l] = round_to(agg64, "f16").astype(np.float32)'),
+    ("mixed precision: the own rows enter the product as fp16", None, "iteration",
+     "h_self = round_bf16(H[l - 1][rows].astype(np.float64))", "h_self = H[l - 1][rows]"),
+    ("mixed precision: the weights enter the product unrounded", None, "iteration", "W = round_bf16(W)", "W = W"),
+    ("mixed precision: hidden embeddings are stored as fp32", None, "iteration",
+     'out_dtype = "f32" if l == L else compute_dtype', 'out_dtype = "f32"'),
+    ("mixed precision: the last layer is rounded to bf16 too", None, "iteration",
+     'out_dtype = "f32" if l == L else compute_dtype', "out_dtype = compute_dtype"),
+    ("mixed precision: hidden embeddings are rounded to fp16", None, "iteration",
+     'out_dtype = "f32" if l == L else compute_dtype', 'out_dtype = "f32" if l == L else "f16"'),
+    ("mixed precision: the output gradient enters the backward products unrounded", None, "layer_backward",
+     "dz = round_bf16(dz).astype(np.float64)", "dz = dz"),
+    ("mixed precision: the backward product uses unrounded weights", None, "layer_backward",
+     "W = round_bf16(W).astype(np.float64)", "W = W"),
+    ("mixed precision: the bias gradient sums the rounded output gradient", None, "layer_backward",
+     "    db = dz.sum(axis=0)\n", '    db = (round_bf16(dz).astype(np.float64) if compute_dtype == "bf16" else dz).sum(axis=0)\n'),
+    ("mixed precision: the weight gradient takes the own rows as fp16", None, "backward",
+     'h_self = round_bf16(h_prev[rows].astype(np.float64)) if compute_dtype == "bf16" else h_prev[rows]', "h_self = h_prev[rows]"),
+    ("mixed precision: embedding gradients are carried in fp64 between the layers", None, "backward",
+     'dh_l = dH[l].astype(np.float32) if compute_dtype == "bf16" else dH[l]', "dh_l = dH[l]"),
+    ("mixed precision: the backward pass ignores the setting", None, "backward", "compute_dtype=compute_dtype)", 'compute_dtype="f32")'),
+    ("GCN backward: shares are divided by the neighbour count only", None, "layer_backward_gcn",
+     "share = dm[k] / float(len(nb) + 1)", "share = dm[k] / float(max(len(nb), 1))"),
+    ("GCN backward: the node itself receives nothing", None, "layer_backward_gcn", "        dsrc[r] += share\n", "        pass\n"),
+    ("GCN backward: the node itself receives the undivided gradient", None, "layer_backward_gcn", "        dsrc[r] += share\n", "        dsrc[r] += dm[k]\n"),
+    ("GCN backward: no ReLU mask", None, "layer_backward_gcn", "if relu:", "if False:"),
+    ("GCN backward: a neighbour sampled by several rows keeps the last share", None, "layer_backward_gcn",
+     "np.add.at(dsrc, nb, share)", "dsrc[nb] = share"),
+    ("GCN backward: the weight gradient is taken from the output", None, "layer_backward_gcn",
+     "dW = np.asarray(agg, dtype=np.float64).T @ dz", "dW = np.asarray(agg, dtype=np.float64).T @ np.asarray(dh, dtype=np.float64)[rows]"),
+    ("GCN backward: the bias gradient is a mean", None, "layer_backward_gcn", "db = dz.sum(axis=0)", "db = dz.mean(axis=0)"),
+    ("GCN backward: the input gradient uses W instead of its transpose", None, "layer_backward_gcn", "dm = dz @ W.T",
+     "dm = dz @ W.T if W.shape[0] != W.shape[1] else dz @ W"),
+    ("GCN backward: the GraphSAGE rule is applied", None, "backward", 'if model == "gcn":', "if False:"),
     ("cached feature rows are read at the neighbouring rank", "BidirectionalCache", "load",
      "out[k] = self.buf[B - (r + 1) * w:B - r * w].view(np_dt)", "out[k] = self.buf[B - (r + 2) * w:B - (r + 1) * w].view(np_dt) if r + 2 <= self.n_feat else 0"),
 ]
