@@ -12,8 +12,10 @@ Layout of a sampled L-layer mini-batch (layer L = seeds, layer 0 = input nodes):
 
 Per row, min(degree, fanout) neighbour slots are chosen (all of them when the
 degree does not exceed the fan-out, otherwise one slot from each of `fanout`
-equal strata of the slot range, which gives every slot the same inclusion
-probability); self loops and repeated neighbours within the row are dropped.
+disjoint strata of the slot range with integer bounds, the whole choice then
+turned round the row by a common random offset, which gives `fanout` distinct
+slots and every slot the same inclusion probability); self loops and repeated
+neighbours within the row are dropped.
 `fanouts` lists the fan-out from the input side to the seed side: block l uses
 `fanouts[l - 1]`.
 
@@ -55,11 +57,18 @@ def sample_minibatch(graph, seeds, fanouts, key):
         n = cur.shape[0]
         deg = graph.degree(cur)
         j = np.arange(f, dtype=np.int64)[None, :]
-        u = rng.uniform(rng.u64_2(rng.make_key(key, l), cur[:, None], j))
-        strat = np.floor((j + u) * (deg[:, None].astype(np.float64) / f)).astype(np.int64)
-        slot = np.where(deg[:, None] <= f, j, strat)
+        key_l = rng.make_key(key, l)
+        u = rng.uniform(rng.u64_2(key_l, cur[:, None], j))
+        dcol = deg[:, None].astype(np.int64)
+        first = (j * dcol) // f
+        width = np.maximum(((j + 1) * dcol) // f - first, 1)
+        inside = np.minimum(np.floor(u * width).astype(np.int64), width - 1)
+        turn = np.floor(rng.uniform(rng.u64_2(key_l, cur, np.int64(f))) * deg).astype(np.int64)
+        turn = np.minimum(turn, np.maximum(deg - 1, 0))[:, None]
+        strat = (first + inside + turn) % np.maximum(dcol, 1)
+        slot = np.where(dcol <= f, j, strat)
         valid = j < np.minimum(deg, f)[:, None]
-        slot = np.where(valid, np.minimum(slot, np.maximum(deg[:, None] - 1, 0)), 0)
+        slot = np.where(valid, np.minimum(slot, np.maximum(dcol - 1, 0)), 0)
         nb = np.where(valid, graph.neighbour(np.broadcast_to(cur[:, None], slot.shape), slot), -1)
         valid &= nb != cur[:, None]
         for a in range(1, f):

@@ -447,10 +447,12 @@ fg_status_t fg_cache_update_commit(fg_cache_t* cache, int64_t iter, int32_t n_la
  * Neighbour sampling of one block on the device (uniform sampling with a fan-out per layer, Section 7.1; the paper samples
  * on CPU threads, Section 5, so the scheme below is this library's): from the nodes of layer `layer` to block `layer`
  * and the node list of the layer below, over an in-neighbour CSR in device-visible memory.
- * For node v with degree d: slots 0..d-1 if d <= fanout, otherwise slot j = floor((j + u_j) * (d / fanout)) in double
- * precision, clipped to d-1, for j = 0..fanout-1 (one slot from each of `fanout` equal strata), with u_j the top 53 bits of
- * w(w(w(mix(key), layer), v), j), w(k, c) = mix(k + (c + 1) * 0x9E3779B97F4A7C15) and mix the SplitMix64 output function.
- * The row keeps the neighbours at those slots in slot order, without v itself and without repeats. The layer below is this
+ * For node v with degree d: slots 0..d-1 if d <= fanout; otherwise f = fanout disjoint strata with integer bounds,
+ * stratum j = [floor(j d / f), floor((j + 1) d / f)), draw j = 0..f-1 takes the slot at offset floor(u_j * width_j) of
+ * stratum j, and all f slots are moved round the row by the common offset floor(u_f * d), modulo d: f distinct slots,
+ * every slot of the row with probability f / d. u_j is the top 53 bits of w(w(w(mix(key), layer), v), j) scaled to [0, 1),
+ * w(k, c) = mix(k + (c + 1) * 0x9E3779B97F4A7C15) and mix the SplitMix64 output function.
+ * The row keeps the neighbours at those slots in the order of j, without v itself and without repeats. The layer below is this
  * layer's nodes followed by the neighbours not among them, each once, in order of first occurrence (rows in order, slots
  * in order). The result is a pure function of the arguments.
  *   indptr_dev [num_nodes + 1] int64, indices_dev [num_edges] int32   in-neighbours of v: indices[indptr[v] .. indptr[v+1])

@@ -16,17 +16,21 @@ mix(key + (c + 1) * GAMMA) mod 2**64; the draw of slot j of node v in the block 
 word(word(word(mix(K), l), v), j), mapped to [0, 1) by its top 53 bits.
 
 One block (layer l, nodes `cur`, fan-out f), for every node v at position i, with d its degree:
-  * d <= f: the candidate slots are 0 .. d-1; otherwise slot j (j = 0 .. f-1) is floor((j + u_j) * (d / f)) in double
-    precision, clipped to d-1: one slot from each of f equal strata, so every slot is equally likely;
-  * the candidates are the neighbours at those slots in slot order, without v itself and without a neighbour that
+  * d <= f: the candidate slots are 0 .. d-1; otherwise the row is cut into f disjoint strata with integer bounds,
+    stratum j = [floor(j d / f), floor((j + 1) d / f)) (each holds at least one slot), draw j (j = 0 .. f-1) picks the
+    slot at offset floor(u_j * width_j) of stratum j, and all f slots are then moved round the row by one common
+    offset floor(u_f * d) modulo d: f distinct slots for every row, and every slot of the row is taken with
+    probability exactly f / d (min(d, f) distinct neighbours when the row has no self loop or repeated neighbour);
+  * the candidates are the neighbours at those slots in the order of j, without v itself and without a neighbour that
     already occurred earlier in the same row;
   * the layer below is `cur` followed by the candidates that are not in `cur`, each once, in the order in which they
     first occur (rows in position order, slots in order); the block's columns are positions in that list.
 Rows are stored back to back: start[i] = end[i-1], start[0] = 0.
 
 Pins (tests marked "not gpu"): the vectorised input generator of the test harness, which was written separately from
-the same statement; membership and stratum of every sampled neighbour; inclusion frequencies against f / d; the
-structural invariants of a mini-batch; published SplitMix64 reference outputs.
+the same statement; membership and stratum of every sampled neighbour; exactly min(d, f) distinct neighbours on
+simple graphs; inclusion frequencies against f / d (d not a multiple of f included); the structural invariants of a
+mini-batch; published SplitMix64 reference outputs.
 """
 
 MASK = (1 << 64) - 1
@@ -58,11 +62,13 @@ def row_candidates(indptr, indices, v, fanout, key_l):
     d = hi - lo
     kv = word(key_l, v)
     out = []
+    turn = min(int(unit(word(kv, fanout)) * d), d - 1) if d > fanout else 0
     for j in range(min(d, fanout)):
         if d <= fanout:
             slot = j
         else:
-            slot = min(int((j + unit(word(kv, j))) * (d / fanout)), d - 1)
+            first, width = (j * d) // fanout, ((j + 1) * d) // fanout - (j * d) // fanout
+            slot = (first + min(int(unit(word(kv, j)) * width), width - 1) + turn) % d
         u = int(indices[lo + slot])
         if u != v and u not in out:
             out.append(u)

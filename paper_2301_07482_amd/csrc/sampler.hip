@@ -2,9 +2,11 @@
 // CPU threads, Section 5): from the nodes of layer l to the block (start, end, columns) and the node list of layer l-1,
 // over an in-neighbour CSR held in device-visible memory.
 //
-// Per node v with degree d and fan-out f: slots 0..d-1 when d <= f, otherwise slot j = floor((j + u_j) * (d / f)) in
-// double precision (one slot from each of f equal strata), u_j from the counter-based SplitMix64 generator keyed by
-// (mini-batch key, layer, v, j); the neighbours at those slots in slot order, without v and without repeats. The layer
+// Per node v with degree d and fan-out f: slots 0..d-1 when d <= f; otherwise the row is cut into f disjoint strata
+// with integer bounds, stratum j = [floor(j d / f), floor((j + 1) d / f)), draw j takes the slot at offset
+// floor(u_j * width_j) of stratum j, and the f slots are moved round the row by a common offset floor(u_f * d) modulo d
+// (f distinct slots, every slot of the row with probability f / d); u_j from the counter-based SplitMix64 generator
+// keyed by (mini-batch key, layer, v, j); the neighbours at those slots in the order of j, without v and without repeats. The layer
 // below is the layer's own nodes followed by the new neighbours in order of first occurrence; columns are positions in
 // that list. Everything is a pure function of the inputs: no atomics decide an order, so the result is the same in
 // every run.
@@ -114,10 +116,16 @@ __global__ __launch_bounds__(SMP_THREADS) void sample_draw_kernel(SmpArgs A) {
             if (j < f && j < d) {
                 int64_t slot = j;
                 if (d > f) {
-                    const uint64_t w = smp_word(smp_word(A.key_l, (uint64_t)v), (uint64_t)j);
-                    const double u = (double)(w >> 11) * (1.0 / 9007199254740992.0);
-                    slot = (int64_t)(((double)j + u) * ((double)d / (double)f));
-                    if (slot > d - 1) slot = d - 1;
+                    const uint64_t kv = smp_word(A.key_l, (uint64_t)v);
+                    const double scale = 1.0 / 9007199254740992.0;
+                    const double u = (double)(smp_word(kv, (uint64_t)j) >> 11) * scale;
+                    const double ut = (double)(smp_word(kv, (uint64_t)f) >> 11) * scale;
+                    const int64_t first = ((int64_t)j * d) / f, width = ((int64_t)(j + 1) * d) / f - first;
+                    int64_t inside = (int64_t)(u * (double)width);
+                    if (inside > width - 1) inside = width - 1;
+                    int64_t turn = (int64_t)(ut * (double)d);
+                    if (turn > d - 1) turn = d - 1;
+                    slot = (first + inside + turn) % d;
                 }
                 const int64_t at = lo + slot;
                 if (at >= 0 && at < A.num_edges) {

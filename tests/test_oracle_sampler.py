@@ -59,27 +59,53 @@ def test_every_sampled_neighbour_is_a_neighbour_from_its_own_stratum():
         if d <= f:
             assert got == list(dict.fromkeys(u for u in nb if u != v))          # all of them, in slot order, once each
         else:
-            # strata: slot j lies in [j d / f, (j + 1) d / f); every candidate must be reachable from a distinct stratum, in order
-            strata = [set(nb[int(np.floor(j * d / f)):min(int(np.ceil((j + 1) * d / f)), d)]) for j in range(f)]
-            j = 0
-            for u in got:
-                while j < f and u not in strata[j]:
+            # stratum j holds the slots [floor(j d / f), floor((j + 1) d / f)), all moved round the row by one offset:
+            # for some offset every candidate must come from a stratum of its own, in the order of j
+            def reachable(turn):
+                strata = [{nb[(s + turn) % d] for s in range(j * d // f, (j + 1) * d // f)} for j in range(f)]
+                j = 0
+                for u in got:
+                    while j < f and u not in strata[j]:
+                        j += 1
+                    if j == f:
+                        return False
                     j += 1
-                assert j < f
-                j += 1
+                return True
+            assert any(reachable(t) for t in range(d))
 
 
-def test_inclusion_frequencies_are_uniform():
-    """A node with 12 distinct neighbours and fan-out 4: over many keys every neighbour is sampled 4/12 of the time."""
-    indptr = np.array([0, 12] + [12] * 12)
-    indices = np.arange(1, 13)
-    count = np.zeros(13)
+@pytest.mark.parametrize("f", [3, 5, 10, 15])
+def test_a_row_without_self_loop_or_repeats_gets_exactly_min_degree_fanout_distinct_neighbours(f):
+    """Section 7.1: a fan-out of f samples f neighbours of a node that has more than f; all of them otherwise."""
+    g = T.random_explicit_graph(150, 40, 11 + f, allow_isolated=True)       # simple graph: no self loops, no parallel edges
+    key_l = S.layer_key(5, 1)
+    deg = np.diff(g.indptr)
+    assert (deg > f).sum() > 20 and ((deg % f != 0) & (deg > f)).sum() > 10
+    for v in range(150):
+        got = S.row_candidates(g.indptr, g.indices, v, f, key_l)
+        assert len(got) == len(set(got)) == min(int(deg[v]), f), (v, int(deg[v]), got)
+    out = S.sample_minibatch(g.indptr, g.indices, list(range(0, 150, 3)), (f, f), 77)
+    for l in (1, 2):
+        want = np.minimum(deg[np.array(out["ids"][l])], f)
+        assert (np.array(out["end"][l]) - np.array(out["start"][l])).tolist() == want.tolist()
+
+
+@pytest.mark.parametrize("d,f", [(12, 4), (13, 4), (7, 5), (50, 15)])
+def test_inclusion_frequencies_are_uniform(d, f):
+    """A node with d distinct neighbours and fan-out f: over many keys every neighbour is sampled f/d of the time,
+    also when f does not divide d."""
+    indptr = np.array([0, d] + [d] * d)
+    indices = np.arange(1, d + 1)
+    count = np.zeros(d + 1)
     trials = 6000
     for k in range(trials):
-        for u in S.row_candidates(indptr, indices, 0, 4, S.layer_key(k, 1)):
+        got = S.row_candidates(indptr, indices, 0, f, S.layer_key(k, 1))
+        assert len(got) == f
+        for u in got:
             count[u] += 1
     freq = count[1:] / trials
-    assert np.all(np.abs(freq - 4 / 12) < 5 * np.sqrt((1 / 3) * (2 / 3) / trials)), freq
+    p = f / d
+    assert np.all(np.abs(freq - p) < 5 * np.sqrt(p * (1 - p) / trials)), freq
 
 
 def test_minibatch_structure():
@@ -118,13 +144,27 @@ def test_transpose_lists_every_edge_once_under_its_source():
         assert ts[0] == 0 and ts[1:] == te[:-1] and te[-1] == len(edges)
 
 
+def test_transpose_hand_example():
+    """Three rows over four sources: row 0 samples positions 1, 0; row 1 nothing; row 2 samples positions 1, 2."""
+    ts, te, tr = S.transpose_block([0, 2, 2], [2, 2, 4], [1, 0, 1, 2], 4)
+    assert (ts, te, tr) == ([0, 1, 3, 4], [1, 3, 4, 4], [0, 0, 2, 2])
+    # a pruned row (end = start) drops out; the column array keeps its entries
+    ts, te, tr = S.transpose_block([0, 2, 2], [0, 2, 4], [1, 0, 1, 2], 4)
+    assert (ts, te, tr) == ([0, 0, 1, 2], [0, 1, 2, 2], [2, 2])
+
+
 # ---------------------------------------------------------------- do these pins bite?
 
 SAMPLER_MUTANTS = [
     ("self loops are kept", "row_candidates", "if u != v and u not in out:", "if u not in out:"),
     ("repeated neighbours are kept", "row_candidates", "if u != v and u not in out:", "if u != v:"),
-    ("every stratum is sampled at its first slot", "row_candidates", "(j + unit(word(kv, j)))", "(j + 0.0)"),
-    ("slots are drawn from the whole row", "row_candidates", "int((j + unit(word(kv, j))) * (d / fanout))", "int(unit(word(kv, j)) * d)"),
+    ("every stratum is sampled at its first slot", "row_candidates", "min(int(unit(word(kv, j)) * width), width - 1)", "0"),
+    ("slots are drawn from the whole row", "row_candidates", "first + min(int(unit(word(kv, j)) * width), width - 1)", "int(unit(word(kv, j)) * d)"),
+    ("strata have real-valued bounds, so neighbouring ones share a slot", "row_candidates",
+     "slot = (first + min(int(unit(word(kv, j)) * width), width - 1) + turn) % d", "slot = (min(int((j + unit(word(kv, j))) * (d / fanout)), d - 1) + turn) % d"),
+    ("the choice is not turned round the row", "row_candidates", "turn = min(int(unit(word(kv, fanout)) * d), d - 1) if d > fanout else 0", "turn = 0"),
+    ("the turn shares its draw with the first stratum", "row_candidates", "unit(word(kv, fanout)) * d", "unit(word(kv, 0)) * d"),
+    ("the last stratum stops one slot early", "row_candidates", "((j + 1) * d) // fanout - (j * d) // fanout", "max(((j + 1) * d) // fanout - (j * d) // fanout - (1 if j == fanout - 1 else 0), 1)"),
     ("the slot's draw ignores the node", "row_candidates", "kv = word(key_l, v)", "kv = key_l"),
     ("all slots of a node share one draw", "row_candidates", "unit(word(kv, j))", "unit(word(kv, 0))"),
     ("small rows lose their last neighbour", "row_candidates", "range(min(d, fanout))", "range(min(d, fanout) - (1 if d <= fanout and d > 1 else 0))"),
@@ -143,9 +183,11 @@ SAMPLER_PINS = [
     (test_generator_reproduces_published_splitmix64_outputs, [()]),
     (test_matches_the_vectorised_harness_sampler, [(0, (3, 2), 6), (1, (4, 3, 2), 9), (3, (10, 5), 40)]),
     (test_every_sampled_neighbour_is_a_neighbour_from_its_own_stratum, [()]),
-    (test_inclusion_frequencies_are_uniform, [()]),
+    (test_a_row_without_self_loop_or_repeats_gets_exactly_min_degree_fanout_distinct_neighbours, [(3,), (10,)]),
+    (test_inclusion_frequencies_are_uniform, [(12, 4), (13, 4)]),
     (test_minibatch_structure, [()]),
     (test_transpose_lists_every_edge_once_under_its_source, [()]),
+    (test_transpose_hand_example, [()]),
 ]
 
 
