@@ -20,6 +20,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 FP32_MFMA_PEAK_TFLOPS = 157.3  # MI355X published dense fp32 matrix rate
 BF16_MFMA_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16 matrix rate
 PCIE5_X16_GBS = 64.0            # PCIe Gen5 x16, one direction (workloads whose feature table stays in host memory)
+PAPER_T_STALE, PAPER_P_GRAD = 200, 0.9   # the paper's default thresholds (Section 7.1)
 
 
 def _sample_one(args):
@@ -97,6 +98,9 @@ def main():
                     help="layer type: GraphSAGE-mean (the headline) or GCN (propagation incl. the node itself, one weight matrix)")
     ap.add_argument("--weight-grads", action="store_true",
                     help="with --backward: also form dL/dW and dL/db of every layer (fg_layer_backward_weights)")
+    ap.add_argument("--no-policy-paper", action="store_true",
+                    help="skip the second measurement with the paper's default thresholds (t_stale 200, p_grad 0.9), reported "
+                         "as `policy_paper`")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device-to-device copy before the warm-up, as the known-size "
                          "reference for scaling hardware traffic counters")
@@ -121,13 +125,27 @@ def main():
         admit_budget = {l + 1: int(v) for l, v in enumerate(args.admit_budget.split(","))}
     elif args.access_aware:      # what a ring of this size can hold for a whole staleness window
         admit_budget = {l: max(1, -(-w.cache_capacity // max(w.t_stale, 1))) for l in range(1, w.num_layers)}
-    total = args.warmup + args.steps
+    # The cache reaches its steady state after t_stale + 1 updates (entries admitted by the first update have then aged
+    # out): whatever --warmup says, that many untimed iterations run before the timed region; those beyond --warmup are
+    # reported as `prefill_steps`.
+    prefill = 0 if args.no_cache else max(0, w.t_stale + 1 - args.warmup)
+    first_timed = prefill + args.warmup
+    total = first_timed + args.steps
     extra = min(args.steps, 20)        # further mini-batches for the per-call breakdown pass after the timed region
+    policy_w = None
+    if not (args.no_policy_paper or args.no_cache or w.num_layers < 2 or args.backward or args.device_sampler or args.feature_rows
+            or args.t_stale is not None or args.p_grad is not None):
+        import dataclasses
+        policy_w = dataclasses.replace(w, name=w.name + "/paper_policy", t_stale=PAPER_T_STALE, p_grad=PAPER_P_GRAD)
+        wl.WORKLOADS[policy_w.name] = policy_w
+    n_sampled = total + extra
+    if policy_w is not None:
+        n_sampled = max(n_sampled, max(policy_w.t_stale + 1, args.warmup) + args.steps)
     t0 = time.time()
     if args.device_sampler:      # the mini-batches are sampled on the device below; the host samples only what the CPU oracle is timed on
         sampled = [] if args.no_cpu_baseline else sample_batches(w.name, 20, args.sample_workers)
     else:
-        sampled = sample_batches(w.name, total + extra, args.sample_workers)
+        sampled = sample_batches(w.name, n_sampled, args.sample_workers)
     t_sample = time.time() - t0
 
     import numpy as np
@@ -158,8 +176,8 @@ def main():
         for kv in args.tune:
             key, value = kv.split("=")
             B.fg_set_tuning(key, int(value))
-    sampler_report = {"where": "host", "workers": args.sample_workers, "seconds": t_sample, "minibatches": total + extra,
-                      "minibatches_per_s": (total + extra) / t_sample if t_sample > 0 else None}
+    sampler_report = {"where": "host", "workers": args.sample_workers, "seconds": t_sample, "minibatches": n_sampled,
+                      "minibatches_per_s": n_sampled / t_sample if t_sample > 0 else None}
     if args.device_sampler:
         from fg_inputs import device as fdev, rng
         graph = wl.make_graph(w)
@@ -214,8 +232,10 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
-    for it in range(args.warmup):
-        hp.run(batches[it], it, next_bt=None if args.no_lookahead else batches[it + 1])
+    # untimed: prefill + warm-up. The last of these steps is given no look-ahead, so that the top-down pass of the first
+    # timed mini-batch runs inside the timed region like that of every other timed step.
+    for it in range(first_timed):
+        hp.run(batches[it], it, next_bt=None if (args.no_lookahead or it + 1 == first_timed) else batches[it + 1])
     torch.cuda.synchronize()
 
     # timed region: exactly `steps` iterations. HIP events on the launch stream bracket only the two longest calls,
@@ -223,57 +243,10 @@ def main():
     # 3 us of stream time); the other calls are timed in a separate pass below.
     LOADER = "gather_features" if args.no_fuse else "gather_aggregate[1]"
     BRACKETED = (LOADER, "linear[1]")   # the two longest calls; whichever is longer is reported as `roofline`
-    ev = []
-
-    def timer_for(step_events, only=None):
-        is_open = {}
-
-        def tick(name, stream=None):
-            key = id(stream) if stream is not None else 0
-            if only is not None:
-                if not (name in only or is_open.get(key, False)):
-                    return
-                is_open[key] = name in only
-            e = torch.cuda.Event(enable_timing=True)
-            e.record(stream) if stream is not None else e.record()
-            step_events.setdefault(key, []).append((name, e))
-        return tick
-
-    torch.cuda.synchronize()
-    t_start = time.perf_counter()
-    # Two kinds of bracketed steps: every `--bracket-every`-th step runs with every call on the one stream, so that the
-    # bracketed launches have the chip to themselves (the durations `roofline` is priced on, comparable with a kernel
-    # trace); half way between them a step is bracketed as it normally runs, with the bookkeeping launches of the second
-    # stream beside it (`ms_per_launch_overlapped`).
-    ev_ovl = []
-    overlapped = hp.overlap_update
-    for k in range(args.steps):
-        it = args.warmup + k
-        step_events = {}
-        alone = k % args.bracket_every == 0
-        beside = overlapped and k % args.bracket_every == args.bracket_every // 2
-        ahead = batches[it + 1] if (it + 1 < total and not args.no_lookahead and not alone) else None   # its top-down pass runs beside this step's layers
-        hp.overlap_update = overlapped and not alone
-        hp.run(batches[it], it, timer=timer_for(step_events, only=BRACKETED) if (alone or beside) else None, next_bt=ahead)
-        (ev if alone else ev_ovl).append(step_events)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    hp.overlap_update = overlapped
-
+    elapsed, timed_ms, timed_ovl_ms = timed_region(hp, batches, first_timed, args.steps, total, args.bracket_every,
+                                                   not args.no_lookahead, BRACKETED)
     ms_per_step = 1e3 * elapsed / args.steps
     value = args.steps / elapsed
-
-    def spans(event_log):
-        out = {}
-        for step_events in event_log:
-            for per_stream in step_events.values():
-                for (name, e0), (_, e1) in zip(per_stream[:-1], per_stream[1:]):
-                    if name is not None:
-                        out.setdefault(name, []).append(e0.elapsed_time(e1))
-        return {k: float(np.mean(v)) for k, v in out.items()}
-
-    timed_ms = spans(ev)
-    timed_ovl_ms = spans(ev_ovl)
 
     # breakdown pass (not part of `value`): the iterations that follow the timed ones, on their own mini-batches, with
     # events around every call. It is a profile, not a result.
@@ -284,7 +257,7 @@ def main():
     hp.overlap_update = False          # every call on the one stream here, so that each has a time of its own
     for k in range(extra):
         step_events = {}
-        hp.run(replay[k], args.warmup + args.steps + k, timer=timer_for(step_events))
+        hp.run(replay[k], first_timed + args.steps + k, timer=timer_for(step_events))
         ev2.append(step_events)
         if hp.feature_side and args.no_fuse:   # the input list of this step, before the next one overwrites it
             ranks = torch.as_tensor(hp.feature_ranks(replay[k].ids[0], replay[k].n[0])[0], device="cuda")
@@ -296,39 +269,16 @@ def main():
 
     counts_log = hp.counts_log.cpu().numpy()
     stats_log = hp.stats_log.cpu().numpy()
-    steps_it = [args.warmup + k for k in range(args.steps)]
+    steps_it = [first_timed + k for k in range(args.steps)]
     # the roofline figures price the launches that were bracketed: the same steps' counts
-    roof_it = [args.warmup + k for k in range(args.steps) if k % args.bracket_every == 0]
+    roof_it = [first_timed + k for k in range(args.steps) if k % args.bracket_every == 0]
     counts = [counts_log[it % hp.ring] for it in roof_it]
     counts_all = [counts_log[it % hp.ring] for it in steps_it]
     esz = {"f32": 4, "f16": 2, "bf16": 2}
     # algorithmic bytes / flops per step, averaged over the timed steps
     feat_row = w.feat_dim * esz[w.feat_dtype]
     agg_row = w.feat_dim * (4 if w.compute_dtype == "f32" else 2)
-    if args.no_fuse:
-        # feature gather: per gathered row 4 (id) + row read + row written
-        gather_bytes = float(np.mean([c[0][2] * (4 + 2 * feat_row) for c in counts]))
-        n_input = float(np.mean([c[0][2] for c in counts]))
-        dom_kernel = "gather_rows_kernel<.., true> (fg_gather of the raw features)"
-    else:
-        # fused loader + layer-1 mean: per edge of a normal row 4 (col) [+ 4 (id) when the block's columns are positions] + one
-        # table row read; per normal row
-        # 4 (position) + 8 (start, end) + one mean row written + its own row: 4 (id) + one table row read + one row
-        # written. The edges under normal rows are what is left in the pruned blocks (rows that are not normal have
-        # end = start).
-        edges = [float((batches[it].end[1] - batches[it].start[1]).sum().item()) for it in roof_it]
-        own_row = (4 + feat_row) if args.model == "gcn" else (4 + 2 * feat_row)   # GCN: the own row enters the mean, no copy
-        per_edge = (4 if ids_cols and not hp.feature_side and args.model == "sage" else 8) + feat_row   # column (+ position -> id) + row
-        gather_bytes = float(np.mean([e * per_edge + c[1][2] * (12 + agg_row + own_row)
-                                      for e, c in zip(edges, counts)]))
-        n_input = float(np.mean(edges)) + float(np.mean([c[1][2] for c in counts]))   # table rows read (edges + own rows)
-        dom_kernel = "aggregate_mean_kernel<.., true> (fg_gather_aggregate: loader fused with the layer-1 mean)"
-        fetch_rides = (ids_cols and hp.fetch_with_loader and hp.fetch_all and hp.cache is not None and hp.use_cache
-                       and args.model == "sage" and not hp.feature_side and not hp.one_launch(1, batches[roof_it[0]].n[1]))
-        if fetch_rides:   # the launch also fetches the cached embeddings: per hit 8 (slot, position) + a row read + a row written
-            e_c = 4 if w.compute_dtype == "f32" else 2
-            gather_bytes += float(np.mean([sum(c[l][1] * (8 + 2 * hp.dims[l] * e_c) for l in range(1, L)) for c in counts]))
-            dom_kernel = "loader_fetch_kernel (fg_gather_aggregate_ids: loader fused with the layer-1 mean, cache fetch in the same launch)"
+    gather_bytes, n_input, dom_kernel = loader_bytes(hp, w, batches, roof_it, counts, not args.no_fuse, ids_cols, args.model)
     # rows the loader found on the feature side instead of reading them from the table (the placed rows lie beyond the
     # rings, so which nodes are there does not change during the run)
     from_buffer = 0.0
@@ -395,6 +345,9 @@ def main():
     if w.name == "large_hbm" and not (args.no_cache or args.no_fuse or args.model != "sage" or args.feature_rows):   # the configuration the counter runs were made on
         loader_roof["traffic"] = profiled_traffic("loader_fetch_kernel<0, 0>" if dom_kernel.startswith("loader_fetch") else "aggregate_mean_kernel<0, 0, true, false")
         linear_roof["traffic"] = profiled_traffic("linear_f32x3_panel_kernel<2>")
+        for r in (loader_roof, linear_roof):      # not measured in this run: counters need the profiler around the process
+            r["traffic_source"] = ("profiles/bench_large_hbm_hbm_traffic.md: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this "
+                                   "command, committed with the code") if r["traffic"] is not None else None
     # `roofline` is the kernel with the longest launches in the timed region; the other one follows as `roofline_2`
     if LOADER in timed_ovl_ms:       # the same launches as they run in most steps, beside the second stream's bookkeeping
         loader_roof["ms_per_launch_overlapped"] = timed_ovl_ms[LOADER]
@@ -447,6 +400,17 @@ def main():
     hbm_path = dict(bytes_per_step=path_bytes, ms_per_step=path_ms, achieved=path_bytes / (path_ms * 1e-3) / 1e9, peak=HBM_PEAK_GBS,
                     unit="GB/s", frac=path_bytes / (path_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
                     note="all calls except the dense updates (fg_linear, fg_aggregate_linear); times from the breakdown pass (every call bracketed)")
+    # The benchmark spec's figure: lookup + prune + compaction + cache fetch + feature gather + aggregation (steps a1-a6 of the
+    # path: everything up to the dense updates, without the cache update), algorithmic bytes over the time of those calls
+    # in the breakdown pass, where every call runs on the one stream and has a time of its own.
+    a1_a6 = [k for k in call_avg_ms if k.startswith(("top_down", "lookup_prune", "gather_features", "gather_aggregate", "cache_fetch", "aggregate["))]
+    a1_a6_bytes = sum(call_avg_bytes.get(k, 0.0) for k in a1_a6)
+    a1_a6_ms = sum(call_avg_ms[k] for k in a1_a6)
+    path_a1_a6 = dict(bound="hbm", bytes=a1_a6_bytes, ms=a1_a6_ms, achieved=a1_a6_bytes / (a1_a6_ms * 1e-3) / 1e9 if a1_a6_ms else None,
+                      peak=HBM_PEAK_GBS, unit="GB/s", frac=a1_a6_bytes / (a1_a6_ms * 1e-3) / 1e9 / HBM_PEAK_GBS if a1_a6_ms else None,
+                      calls=sorted(a1_a6), target_frac=0.60,
+                      note="lookup+gather+aggregate path (top-down pass, loader with the cache fetch, aggregations of the upper "
+                           "layers; aggregations that run inside a dense update's launch are counted with that update), one stream, every call bracketed")
     # table rows the loader would read with the caches empty: every edge of block 1 plus every layer-1 node's own row
     if args.no_fuse:
         rows_no_cache = n0_all
@@ -462,6 +426,11 @@ def main():
         cpu_baseline = time_oracle(w, sampled, weights)
 
     hp.close()
+    policy_paper = None
+    if policy_w is not None:
+        del batches, replay
+        torch.cuda.empty_cache()
+        policy_paper = policy_paper_run(policy_w, feat, sampled, args, ids_cols)
     out = {
         "metric": "sampled mini-batches/sec (lookup+gather+aggregate+update); achieved GB/s vs roofline",
         "value": value, "unit": "mini-batches/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -480,8 +449,11 @@ def main():
                    "update_selection": "second stream, beside the layers" if (hp.overlap_update and not args.backward and not args.no_cache
                                                                               and not args.per_layer_update and not hp.feature_side) else "after the layers",
                    "block1_columns": "node ids" if ids_cols else "positions", "seed": w.seed},
+        "prefill_steps": prefill,
         "roofline": roofline,
         "roofline_2": roofline_2,
+        "path_a1_a6": path_a1_a6,
+        "policy_paper": policy_paper,
         "cpu_baseline": cpu_baseline,
         "per_call_ms": {k: round(v, 5) for k, v in sorted(call_avg_ms.items())},
         "per_call": per_call,
@@ -498,6 +470,148 @@ def main():
         "host": {"sampling_s": t_sample, "setup_s": t_setup},
     }
     print(json.dumps(out))
+
+
+def timer_for(step_events, only=None):
+    """A `timer` for HotPath.run that records a HIP event (on the stream the call is launched on) before each call named
+    in `only` (every call if None) and after it."""
+    import torch
+    is_open = {}
+
+    def tick(name, stream=None):
+        key = id(stream) if stream is not None else 0
+        if only is not None:
+            if not (name in only or is_open.get(key, False)):
+                return
+            is_open[key] = name in only
+        e = torch.cuda.Event(enable_timing=True)
+        e.record(stream) if stream is not None else e.record()
+        step_events.setdefault(key, []).append((name, e))
+    return tick
+
+
+def spans(event_log):
+    """Mean time of every bracketed call over the steps of an event log, ms."""
+    import numpy as np
+    out = {}
+    for step_events in event_log:
+        for per_stream in step_events.values():
+            for (name, e0), (_, e1) in zip(per_stream[:-1], per_stream[1:]):
+                if name is not None:
+                    out.setdefault(name, []).append(e0.elapsed_time(e1))
+    return {k: float(np.mean(v)) for k, v in out.items()}
+
+
+def timed_region(hp, batches, first_timed, steps, total, bracket_every, lookahead, bracketed):
+    """Exactly `steps` iterations (mini-batches first_timed ..) between two device synchronisations. HIP events on the
+    launch stream bracket only the calls named in `bracketed`, and only on every `bracket_every`-th step, so that the
+    region is not perturbed (an event record costs about 3 us of stream time). Two kinds of bracketed steps: every
+    `bracket_every`-th step runs with every call on the one stream, so that the bracketed launches have the chip to
+    themselves (the durations `roofline` is priced on, comparable with a kernel trace); half way between them a step is
+    bracketed as it normally runs, with the bookkeeping launches of the second stream beside it.
+    Returns (seconds, {call: ms} of the one-stream steps, {call: ms} of the overlapped steps)."""
+    import torch
+    ev, ev_ovl = [], []
+    overlapped = hp.overlap_update
+    torch.cuda.synchronize()
+    t_start = time.perf_counter()
+    for k in range(steps):
+        it = first_timed + k
+        step_events = {}
+        alone = k % bracket_every == 0
+        beside = overlapped and k % bracket_every == bracket_every // 2
+        ahead = batches[it + 1] if (it + 1 < total and lookahead and not alone) else None   # its top-down pass runs beside this step's layers
+        hp.overlap_update = overlapped and not alone
+        hp.run(batches[it], it, timer=timer_for(step_events, only=bracketed) if (alone or beside) else None, next_bt=ahead)
+        (ev if alone else ev_ovl).append(step_events)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    hp.overlap_update = overlapped
+    return elapsed, spans(ev), spans(ev_ovl)
+
+
+def loader_bytes(hp, w, batches, its, counts, fused, ids_cols, model):
+    """Algorithmic bytes per launch of the loader, averaged over the iterations `its` (their device-side counts in
+    `counts`), the table rows it reads, and the kernel's name."""
+    import numpy as np
+    esz = {"f32": 4, "f16": 2, "bf16": 2}
+    L = hp.L
+    feat_row = w.feat_dim * esz[w.feat_dtype]
+    agg_row = w.feat_dim * (4 if w.compute_dtype == "f32" else 2)
+    if not fused:
+        # feature gather: per gathered row 4 (id) + row read + row written
+        gather_bytes = float(np.mean([c[0][2] * (4 + 2 * feat_row) for c in counts]))
+        n_input = float(np.mean([c[0][2] for c in counts]))
+        return gather_bytes, n_input, "gather_rows_kernel<.., true> (fg_gather of the raw features)"
+    # fused loader + layer-1 mean: per edge of a normal row 4 (col) [+ 4 (id) when the block's columns are positions] + one
+    # table row read; per normal row 4 (position) + 8 (start, end) + one mean row written + its own row: 4 (id) + one
+    # table row read + one row written. The edges under normal rows are what is left in the pruned blocks (rows that are
+    # not normal have end = start).
+    edges = [float((batches[it].end[1] - batches[it].start[1]).sum().item()) for it in its]
+    own_row = (4 + feat_row) if model == "gcn" else (4 + 2 * feat_row)   # GCN: the own row enters the mean, no copy
+    per_edge = (4 if ids_cols and not hp.feature_side and model == "sage" else 8) + feat_row   # column (+ position -> id) + row
+    gather_bytes = float(np.mean([e * per_edge + c[1][2] * (12 + agg_row + own_row) for e, c in zip(edges, counts)]))
+    n_input = float(np.mean(edges)) + float(np.mean([c[1][2] for c in counts]))   # table rows read (edges + own rows)
+    kernel = "aggregate_mean_kernel<.., true> (fg_gather_aggregate: loader fused with the layer-1 mean)"
+    fetch_rides = (ids_cols and hp.fetch_with_loader and hp.fetch_all and hp.cache is not None and hp.use_cache
+                   and model == "sage" and not hp.feature_side and not hp.one_launch(1, batches[its[0]].n[1]))
+    if fetch_rides:   # the launch also fetches the cached embeddings: per hit 8 (slot, position) + a row read + a row written
+        e_c = 4 if w.compute_dtype == "f32" else 2
+        gather_bytes += float(np.mean([sum(c[l][1] * (8 + 2 * hp.dims[l] * e_c) for l in range(1, L)) for c in counts]))
+        kernel = "loader_fetch_kernel (fg_gather_aggregate_ids: loader fused with the layer-1 mean, cache fetch in the same launch)"
+    return gather_bytes, n_input, kernel
+
+
+def policy_paper_run(w, feat, sampled, args, ids_cols):
+    """The same path with the paper's default thresholds (Section 7.1: t_stale 200, p_grad 0.9) instead of the workload's,
+    on a cache of its own that is first brought to its steady state (t_stale + 1 untimed iterations): throughput, what
+    the pruning saves, and the loader's roofline figures, measured like the headline's."""
+    import numpy as np
+    import torch
+    from paper_2301_07482_amd import pipeline as G
+    from paper_2301_07482_amd.pipeline import DeviceBatch
+    first_timed = max(w.t_stale + 1, args.warmup)
+    total = first_timed + args.steps
+    fused = not args.no_fuse
+    hp, _, _ = G.make_hotpath(w, feat_table=feat, fused_input=fused, log_ring=total + 32, model=args.model,
+                              fetch_with_loader=not args.separate_fetch, overlap_update=not args.no_overlap_update,
+                              overlap_min_rows=65536)
+    try:
+        batches = [DeviceBatch(mb, gn, col_ids=ids_cols) for mb, gn, _ in sampled[:total]]
+        for it in range(first_timed):
+            hp.run(batches[it], it, next_bt=None if (args.no_lookahead or it + 1 == first_timed) else batches[it + 1])
+        loader = "gather_aggregate[1]" if fused else "gather_features"
+        elapsed, timed_ms, _ = timed_region(hp, batches, first_timed, args.steps, total, args.bracket_every, not args.no_lookahead,
+                                            (loader, "linear[1]"))
+        counts_log = hp.counts_log.cpu().numpy()
+        roof_it = [first_timed + k for k in range(args.steps) if k % args.bracket_every == 0]
+        steps_it = [first_timed + k for k in range(args.steps)]
+        counts = [counts_log[it % hp.ring] for it in roof_it]
+        counts_all = [counts_log[it % hp.ring] for it in steps_it]
+        nbytes, _, kernel = loader_bytes(hp, w, batches, roof_it, counts, fused, ids_cols, args.model)
+        _, rows_read, _ = loader_bytes(hp, w, batches, steps_it, counts_all, fused, ids_cols, args.model)
+        if fused:
+            rows_no_cache = float(np.mean([batches[it].nnz[1] + batches[it].n[1] for it in steps_it]))
+        else:
+            rows_no_cache = float(np.mean([batches[it].n[0] for it in steps_it]))
+        ms = timed_ms[loader]
+        on_host = w.feat_location == "host"
+        esz = {"f32": 4, "f16": 2, "bf16": 2}
+        moved = rows_read * w.feat_dim * esz[w.feat_dtype] if on_host else nbytes
+        peak = PCIE5_X16_GBS if on_host else HBM_PEAK_GBS
+        return {"t_stale": w.t_stale, "p_grad": w.p_grad, "prefill_steps": first_timed - args.warmup, "warmup": args.warmup,
+                "steps": args.steps, "value": args.steps / elapsed, "unit": "mini-batches/s", "ms_per_step": 1e3 * elapsed / args.steps,
+                "io_saving": 1.0 - rows_read / rows_no_cache if rows_no_cache else 0.0,
+                "table_rows_read": rows_read, "table_rows_without_cache": rows_no_cache,
+                "hits": {l: float(np.mean([c[l][1] for c in counts_all])) for l in range(1, hp.L)},
+                "roofline": {"bound": "host_link" if on_host else "hbm", "kernel": kernel, "achieved": moved / (ms * 1e-3) / 1e9,
+                             "peak": peak, "unit": "GB/s", "frac": moved / (ms * 1e-3) / 1e9 / peak, "traffic": None,
+                             "bytes_per_launch": moved, "ms_per_launch": ms},
+                "note": "the paper's default thresholds on the same workload, same kernels and launch configuration"}
+    finally:
+        hp.close()
+        del hp
+        torch.cuda.empty_cache()
 
 
 def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False, lookahead=True):
@@ -582,6 +696,17 @@ def profiled_traffic(kernel_prefix):
     return None
 
 
+def cpu_model():
+    """Model name of the host's processor as /proc/cpuinfo gives it."""
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.lower().startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return None
+
+
 def time_oracle(w, sampled, weights, iterations=20):
     """The CPU oracle timed on the first `iterations` mini-batches of the same workload (from an empty cache),
     single-threaded; feature rows are regenerated beforehand and not timed."""
@@ -617,7 +742,8 @@ def time_oracle(w, sampled, weights, iterations=20):
             break
     if limiter is not None:
         limiter.restore_original_limits()
-    return {"value": done / secs, "unit": "mini-batches/s", "cores": 1, "kind": "oracle",
+    return {"value": done / secs, "unit": "mini-batches/s", "cores": 1, "cpu_model": cpu_model(), "host_cores": os.cpu_count(),
+            "kind": "oracle",
             "sample": f"iterations 0..{done - 1} of the same workload from an empty cache, {secs:.1f} s of CPU time, "
                       "feature-row generation excluded"}
 

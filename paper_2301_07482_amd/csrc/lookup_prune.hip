@@ -247,7 +247,7 @@ WsLayout ws_layout(int64_t n) {
 
 size_t fg_ws_lookup_prune_bytes(int64_t n) { return ws_layout(n).total; }
 
-extern "C" fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, int64_t iter, const int32_t* ids_dev,
+static fg_status_t lookup_prune_launch(const fg_cache_t* cache, int32_t layer, int64_t iter, const int32_t* ids_dev,
                                        int32_t n, const uint8_t* live_dev, const int32_t* row_start_dev,
                                        int32_t* row_end_dev, const int32_t* col_dev, int64_t nnz, int32_t n_src,
                                        uint8_t* live_src_dev, uint8_t* hit_dev, int32_t* hit_pos_dev,
@@ -301,6 +301,17 @@ extern "C" fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, i
                        cache ? hit_pos_dev : nullptr, hit_slot_dev, normal_pos_dev, normal_ids_dev, counts_dev);
     FG_LAUNCH_CHECK("compact_lists_kernel");
     return FG_OK;
+}
+
+extern "C" fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, int64_t iter, const int32_t* ids_dev,
+                                       int32_t n, const uint8_t* live_dev, const int32_t* row_start_dev,
+                                       int32_t* row_end_dev, const int32_t* col_dev, int64_t nnz, int32_t n_src,
+                                       uint8_t* live_src_dev, uint8_t* hit_dev, int32_t* hit_pos_dev,
+                                       int32_t* hit_slot_dev, int32_t* normal_pos_dev, int32_t* normal_ids_dev,
+                                       int64_t* counts_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+    return lookup_prune_launch(cache, layer, iter, ids_dev, n, live_dev, row_start_dev, row_end_dev, col_dev, nnz, n_src,
+                               live_src_dev, hit_dev, hit_pos_dev, hit_slot_dev, normal_pos_dev, normal_ids_dev, counts_dev,
+                               ws_dev, ws_bytes, stream);
 }
 
 extern "C" size_t fg_top_down_workspace_bytes(int32_t n_layers, const fg_top_down_layer_t* layers) {
@@ -375,7 +386,8 @@ extern "C" fg_status_t fg_top_down(const fg_cache_t* cache, int64_t iter, int32_
     int64_t prep = 0;
     for (int i = 0; i < n_layers; ++i) {
         if (a.layer[i].has_cache) prep = prep > a.layer[i].n ? prep : a.layer[i].n;
-        if (a.layer[i].live_src) prep = prep > a.layer[i].n_src / 4 ? prep : a.layer[i].n_src / 4;
+        // every liveness array is cleared by this launch, however short it is
+        if (a.layer[i].live_src) prep = prep > fg_ceil_div(a.layer[i].n_src, 4) ? prep : fg_ceil_div(a.layer[i].n_src, 4);
     }
     if (prep > 0) {
         const int64_t blocks = fg_ceil_div(prep, 256) < 2048 ? fg_ceil_div(prep, 256) : 2048;

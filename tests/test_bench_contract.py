@@ -38,6 +38,16 @@ def test_one_json_line_with_the_agreed_fields():
     assert r["bound"] in ("hbm", "mfma", "alu", "host_link") and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
     c = d["cpu_baseline"]
     assert c["kind"] == "oracle" and c["value"] > 0 and c["cores"] >= 1 and c["unit"] == d["unit"] and c["sample"]
+    assert isinstance(c["cpu_model"], str) and c["cpu_model"]
+    # the cache is brought to its steady state whatever --warmup says: t_stale + 1 = 11 untimed iterations, 4 of them warm-up
+    assert d["prefill_steps"] == 7
+    a = d["path_a1_a6"]
+    assert a["bound"] == "hbm" and a["bytes"] > 0 and a["ms"] > 0 and abs(a["frac"] - a["achieved"] / a["peak"]) < 1e-9
+    assert not any(k.startswith(("linear", "cache_update")) for k in a["calls"]) and any(k.startswith("top_down") for k in a["calls"])
+    pp = d["policy_paper"]
+    assert (pp["t_stale"], pp["p_grad"]) == (200, 0.9) and pp["prefill_steps"] + pp["warmup"] == 201 and pp["steps"] == 6
+    assert pp["value"] > 0 and 0.0 <= pp["io_saving"] < 1.0 and pp["roofline"]["frac"] > 0
+    assert pp["table_rows_read"] <= pp["table_rows_without_cache"]
 
 
 @pytest.mark.gpu

@@ -139,6 +139,35 @@ def test_lookup_prune_matches_oracle(env, n, n_src, max_deg, seed):
         B.fg_cache_destroy(cache)
 
 
+def test_top_down_clears_liveness_of_the_smallest_batches(env):
+    """One seed with two neighbours, no cache, then one seed without neighbours into the same buffers: the second pass
+    must not see the first one's liveness marks (a layer below with fewer than four positions is cleared too)."""
+    torch, B = env
+    z = lambda n, dt: torch.zeros(max(n, 1), dtype=dt, device="cuda")
+    live0, hit1, hit0 = torch.full((3,), 5, dtype=torch.uint8, device="cuda"), z(1, torch.uint8), z(3, torch.uint8)
+    lists = {l: [z(n, torch.int32) for _ in range(4)] for l, n in ((1, 1), (0, 3))}
+    counts = torch.zeros((2, 3), dtype=torch.int64, device="cuda")
+    ids1, ids0 = dev(torch, np.array([7], np.int32)), dev(torch, np.array([7, 3, 9], np.int32))
+    start, col = dev(torch, np.array([0], np.int32)), dev(torch, np.array([1, 2], np.int32))
+    for end_host, want_live in (([2], [1, 1, 1]), ([0], [1, 0, 0])):
+        end = dev(torch, np.array(end_host, np.int32))
+        specs = [dict(cache_layer=0, ids_dev=ids1, n=1, live_dev=None, row_start_dev=start, row_end_dev=end, col_dev=col, nnz=2,
+                      n_src=3, live_src_dev=live0, hit_dev=hit1, hit_pos_dev=lists[1][0], hit_slot_dev=lists[1][1],
+                      normal_pos_dev=lists[1][2], normal_ids_dev=None, counts_dev=counts.data_ptr() + 24),
+                 dict(cache_layer=0, ids_dev=ids0, n=3, live_dev=live0, row_start_dev=None, row_end_dev=None, col_dev=None, nnz=0,
+                      n_src=0, live_src_dev=None, hit_dev=hit0, hit_pos_dev=lists[0][0], hit_slot_dev=lists[0][1],
+                      normal_pos_dev=lists[0][2], normal_ids_dev=lists[0][3], counts_dev=counts.data_ptr())]
+        layers = B.top_down_layers(specs)
+        wsb = B.fg_top_down_workspace_bytes(layers)
+        ws = torch.zeros(wsb + 16, dtype=torch.uint8, device="cuda")
+        B.fg_top_down(None, 0, layers, ws, wsb, None)
+        torch.cuda.synchronize()
+        assert live0.cpu().numpy().tolist() == want_live
+        n_in = int(counts[0, 2].item())
+        assert n_in == sum(want_live) and lists[0][2][:n_in].cpu().numpy().tolist() == [j for j in range(3) if want_live[j]]
+        assert lists[0][3][:n_in].cpu().numpy().tolist() == [[7, 3, 9][j] for j in range(3) if want_live[j]]
+
+
 def _device_update(torch, B, cache, i, ids, live, gn, p, rows, misalign=False):
     """Lookup (no block) followed by the update on the device; returns the hit flags. `misalign` puts the norms
     and the liveness flags at addresses that are not multiples of 16 and 4 bytes."""
