@@ -186,6 +186,24 @@ fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, int64_t iter
                             int32_t* normal_ids_dev, int64_t* counts_dev, void* ws_dev, size_t ws_bytes, void* stream);
 
 /*
+ * fg_lookup_prune for callers that cannot allocate device memory or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc. Same arguments without ws_dev / ws_bytes, same
+ * kernels, same results. The scratch memory (a class and a slot per position, three counts per workgroup of 1024
+ * positions: 5 bytes per position) is a device array built into the library, about 10.5 MB, which every GPU the
+ * library runs on holds until the process ends. The call allocates and frees nothing; its first call on a device asks
+ * the runtime for the address of that device's copy of the array (no allocation; make that first call outside a capture).
+ * n > FG_LOOKUP_PRUNE_STATIC_MAX_N is rejected with FG_ERR_SHAPE. All calls on one GPU share that GPU's array: calls
+ * that may overlap on one GPU (different streams, different threads) race; calls on one stream do not. Nothing in the
+ * array needs clearing between calls: every byte a call reads it has written itself.
+ */
+#define FG_LOOKUP_PRUNE_STATIC_MAX_N 2097152
+fg_status_t fg_lookup_prune_static(const fg_cache_t* cache, int32_t layer, int64_t iter, const int32_t* ids_dev, int32_t n,
+                                   const uint8_t* live_dev, const int32_t* row_start_dev, int32_t* row_end_dev,
+                                   const int32_t* col_dev, int64_t nnz, int32_t n_src, uint8_t* live_src_dev,
+                                   uint8_t* hit_dev, int32_t* hit_pos_dev, int32_t* hit_slot_dev, int32_t* normal_pos_dev,
+                                   int32_t* normal_ids_dev, int64_t* counts_dev, void* stream);
+
+/*
  * The whole top-down pass (fg_lookup_prune for every layer from the seeds down) in one call. Layer by layer the
  * pass is a chain of dependent random reads; here the cache lookups of all layers, which do not depend on
  * liveness, are done up front in one launch and the per-layer steps only combine flags and walk the rows.

@@ -45,6 +45,7 @@ SIGNATURES = {
     "fg_workspace_bytes": (_sz, [_i32, _i64, _i64]),
     "fg_set_tuning": (_i32, [C.c_char_p, _i64]),
     "fg_lookup_prune": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _p, _i64, _i32, _p, _p, _p, _p, _p, _p, _p, _p, _sz, _p]),
+    "fg_lookup_prune_static": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _p, _i64, _i32, _p, _p, _p, _p, _p, _p, _p, _p]),
     "fg_gather": (_i32, [_p, _i64, _i64, _i64, _p, _p, _p, _i64, _p, _i64, _i64, _i32, _p]),
     "fg_aggregate": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _i32, _p, _i64, _i32, _p]),
     "fg_gather_aggregate": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _p, _i64, _i64, _i32, _i32, _p, _i64, _i32,
@@ -212,6 +213,16 @@ def fg_lookup_prune(cache, layer, it, ids, n, live, row_start, row_end, col, nnz
     _check(_lib.fg_lookup_prune(cache, layer, it, ptr(ids), n, ptr(live), ptr(row_start), ptr(row_end), ptr(col), nnz, n_src,
                                 ptr(live_src), ptr(hit), ptr(hit_pos), ptr(hit_slot), ptr(normal_pos), ptr(normal_ids),
                                 ptr(counts), ptr(ws), ws_bytes, stream))
+
+
+FG_LOOKUP_PRUNE_STATIC_MAX_N = 2097152
+
+
+def fg_lookup_prune_static(cache, layer, it, ids, n, live, row_start, row_end, col, nnz, n_src, live_src, hit, hit_pos, hit_slot,
+                           normal_pos, normal_ids, counts, stream=None):
+    _check(_lib.fg_lookup_prune_static(cache, layer, it, ptr(ids), n, ptr(live), ptr(row_start), ptr(row_end), ptr(col), nnz,
+                                       n_src, ptr(live_src), ptr(hit), ptr(hit_pos), ptr(hit_slot), ptr(normal_pos),
+                                       ptr(normal_ids), ptr(counts), stream))
 
 
 def top_down_layers(specs):

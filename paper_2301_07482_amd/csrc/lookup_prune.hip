@@ -8,6 +8,8 @@
 //      (live, hit, normal) count per workgroup.
 //   2. compact: ballot/popcount ranks inside each workgroup, offset by the counts of the workgroups before
 //      it, give hit_pos/hit_slot/normal_pos in ascending position order.
+#include <atomic>
+
 #include "common.h"
 #include "scan.h"
 
@@ -312,6 +314,46 @@ extern "C" fg_status_t fg_lookup_prune(const fg_cache_t* cache, int32_t layer, i
     return lookup_prune_launch(cache, layer, iter, ids_dev, n, live_dev, row_start_dev, row_end_dev, col_dev, nnz, n_src,
                                live_src_dev, hit_dev, hit_pos_dev, hit_slot_dev, normal_pos_dev, normal_ids_dev, counts_dev,
                                ws_dev, ws_bytes, stream);
+}
+
+// ---- the same call for callers that cannot allocate: its scratch memory is a device array of the library -------------
+//
+// classify_mark_kernel leaves a class and a slot per position and three counts per workgroup there, compact_lists_kernel
+// reads them back: everything read has been written by the same call, so nothing needs clearing between calls.
+constexpr int64_t LP_STATIC_MAX_N = FG_LOOKUP_PRUNE_STATIC_MAX_N;
+constexpr size_t LP_STATIC_BYTES = ((size_t)LP_STATIC_MAX_N + 255) / 256 * 256                      // class per position
+                                   + ((size_t)LP_STATIC_MAX_N * 4 + 255) / 256 * 256               // slot per position
+                                   + (((size_t)LP_STATIC_MAX_N + FG_SCAN_BLOCK - 1) / FG_SCAN_BLOCK * 12 + 255) / 256 * 256;
+static __device__ __align__(256) unsigned char scratch[LP_STATIC_BYTES];
+
+constexpr int LP_MAX_DEVICES = 64;
+static std::atomic<void*> scratch_of_device[LP_MAX_DEVICES];   // each device holds its own copy of the array
+
+extern "C" fg_status_t fg_lookup_prune_static(const fg_cache_t* cache, int32_t layer, int64_t iter, const int32_t* ids_dev,
+                                              int32_t n, const uint8_t* live_dev, const int32_t* row_start_dev,
+                                              int32_t* row_end_dev, const int32_t* col_dev, int64_t nnz, int32_t n_src,
+                                              uint8_t* live_src_dev, uint8_t* hit_dev, int32_t* hit_pos_dev,
+                                              int32_t* hit_slot_dev, int32_t* normal_pos_dev, int32_t* normal_ids_dev,
+                                              int64_t* counts_dev, void* stream) {
+    if (n > LP_STATIC_MAX_N)
+        FG_FAIL(FG_ERR_SHAPE, "fg_lookup_prune_static: n = %d exceeds the %lld positions its built-in scratch memory holds "
+                "(use fg_lookup_prune with a workspace)", n, (long long)LP_STATIC_MAX_N);
+    if (ws_layout(n > 0 ? n : 0).total > LP_STATIC_BYTES)
+        FG_FAIL(FG_ERR_SHAPE, "fg_lookup_prune_static: n = %d needs more scratch memory than is built in", n);
+    int device = -1;
+    FG_HIP(hipGetDevice(&device));
+    if (device < 0 || device >= LP_MAX_DEVICES)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_lookup_prune_static: device %d outside 0..%d", device, LP_MAX_DEVICES - 1);
+    void* ws = scratch_of_device[device].load(std::memory_order_acquire);
+    if (!ws) {
+        // the array's name is not a device address on the host: ask for the address of this device's copy, once
+        FG_HIP(hipGetSymbolAddress(&ws, HIP_SYMBOL(scratch)));
+        if (!ws) FG_FAIL(FG_ERR_HIP, "fg_lookup_prune_static: the scratch array has no address on device %d", device);
+        scratch_of_device[device].store(ws, std::memory_order_release);
+    }
+    return lookup_prune_launch(cache, layer, iter, ids_dev, n, live_dev, row_start_dev, row_end_dev, col_dev, nnz, n_src,
+                               live_src_dev, hit_dev, hit_pos_dev, hit_slot_dev, normal_pos_dev, normal_ids_dev, counts_dev,
+                               ws, LP_STATIC_BYTES, stream);
 }
 
 extern "C" size_t fg_top_down_workspace_bytes(int32_t n_layers, const fg_top_down_layer_t* layers) {
