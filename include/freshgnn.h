@@ -146,7 +146,7 @@ fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, int64_t iter
 /*
  * Launch-shape overrides for measurements (defaults are tuned for MI355X and need no call). Keys:
  * "gather_wg_per_cu", "gather_host_wg_per_cu", "gather_unroll" (1, 2, 4, 8), "gather_nontemporal" (0/1),
- * "aggregate_wg_per_cu", "linear_tile" (fp32 GEMM variant: 0 = default, 8 = one task per workgroup with K split over its wavefronts, 32 = panel kernel, 64 / 128 = LDS-tiled kernel with that many rows). Process-wide, not thread-safe against concurrent launches. Results never depend on them.
+ * "aggregate_wg_per_cu", "top_down_walk" (fg_top_down: 1 = its first launch walks the first two blocks down from the seeds, 0 = one layer per launch), "linear_tile" (fp32 GEMM variant: 0 = default, 8 = one task per workgroup with K split over its wavefronts, 32 = panel kernel, 64 / 128 = LDS-tiled kernel with that many rows). Process-wide, not thread-safe against concurrent launches. Results never depend on them.
  */
 fg_status_t fg_set_tuning(const char* key, int64_t value);
 
@@ -205,15 +205,22 @@ fg_status_t fg_lookup_prune_static(const fg_cache_t* cache, int32_t layer, int64
 
 /*
  * The whole top-down pass (fg_lookup_prune for every layer from the seeds down) in one call. Layer by layer the
- * pass is a chain of dependent random reads; here the cache lookups of all layers, which do not depend on
- * liveness, are done up front in one launch and the per-layer steps only combine flags and walk the rows.
+ * pass is a chain of dependent random reads, and every launch boundary adds to it; here the cache lookups of all
+ * layers, which do not depend on liveness, are done in the first launch, where one wavefront per seed also walks the
+ * first two blocks down (a seed's neighbours, and their neighbours unless they are cached), so that the liveness of
+ * the two layers below the seeds is settled at once; the layers so settled are classified by one launch, and every
+ * further layer by one launch that also compacts the lists of the layers above it. Three launches for three layers.
  * Same results as calling fg_lookup_prune layer by layer.
  *
  * layers[0] is the seed layer, layers[i+1] the layer below layers[i]; each entry carries the arguments of
  * fg_lookup_prune for its layer (same meaning, same NULL rules). cache_layer = 0: no lookup for this layer;
  * otherwise the layer of `cache` to look up (1..n_layers of the cache). layers[i].live_src_dev, when given,
  * must be layers[i+1].live_dev. At most 8 layers.
- * ws_dev: >= fg_top_down_workspace_bytes(n_layers, layers) bytes, 16-byte aligned.
+ * ws_dev: >= fg_top_down_workspace_bytes(n_layers, layers) bytes, 16-byte aligned. Its second half carries liveness
+ * marks between the launches and must be ALL ZERO when a call starts; every call leaves it all zero. So: zero-fill the
+ * workspace once after allocating it, pass the same ws_dev and ws_bytes on every call that uses it, use it for
+ * nothing else, and do not let two calls that share it overlap. (A workspace sized for the largest mini-batch serves
+ * every smaller one.)
  */
 typedef struct fg_top_down_layer {
     int32_t cache_layer;

@@ -265,24 +265,25 @@ __global__ __launch_bounds__(AGG_THREADS) void aggregate_mean_kernel(
                                                               gcn_pos_stride);
 }
 
-// The fused loader with the fetch of cached embeddings riding along: workgroups [0, agg_blocks) are the loader, the
-// remaining ones copy the cached rows of the hits of every cached layer (h_v = C^(l)[v] of Algorithm 1). The two jobs do
-// not depend on each other; sharing a launch saves one of the path's small launches. (Copies first in the grid instead of
-// last measured the same.)
+// The fused loader with the fetch of cached embeddings riding along: the first copy_blocks workgroups copy the cached rows
+// of the hits of every cached layer (h_v = C^(l)[v] of Algorithm 1), the remaining ones are the loader. The two jobs do
+// not depend on each other; sharing a launch saves one of the path's small launches. The copies come first in the grid:
+// the loader's workgroups stay resident until the end of the launch, so workgroups behind them would only start then
+// (with a few thousand hits per mini-batch that was a tail of tens of microseconds).
 template <int IN, int OUT>
 __global__ __launch_bounds__(AGG_THREADS) void loader_fetch_kernel(
-    int agg_blocks, fg_row_copy_batch copies, const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end,
+    int copy_blocks, fg_row_copy_batch copies, const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end,
     const int32_t* __restrict__ col, int64_t nnz, int n_block_rows, const int32_t* __restrict__ rows,
     const int64_t* __restrict__ n_rows_dev, int64_t max_rows, const char* __restrict__ h_src, int64_t n_src, int64_t src_stride,
     int pieces, char* __restrict__ agg, int64_t agg_stride, int lanes_log2, const int32_t* __restrict__ src_ids, int n_ids,
     char* __restrict__ self_out, int64_t self_stride, int n_self) {
-    if ((int)blockIdx.x >= agg_blocks) {
-        const int64_t wave = ((int64_t)(blockIdx.x - agg_blocks) * AGG_THREADS + threadIdx.x) >> 6;
-        const int64_t n_waves = ((int64_t)(gridDim.x - agg_blocks) * AGG_THREADS) >> 6;
+    if ((int)blockIdx.x < copy_blocks) {
+        const int64_t wave = ((int64_t)blockIdx.x * AGG_THREADS + threadIdx.x) >> 6;
+        const int64_t n_waves = ((int64_t)copy_blocks * AGG_THREADS) >> 6;
         for (int c = 0; c < copies.n; ++c) fg_copy_rows_part(copies.c[c], wave, n_waves, threadIdx.x & 63);
         return;
     }
-    aggregate_mean_body<IN, OUT, true, false, false, true>(agg_blocks, blockIdx.x, row_start, row_end, col, nnz, n_block_rows, rows,
+    aggregate_mean_body<IN, OUT, true, false, false, true>((int)gridDim.x - copy_blocks, (int)blockIdx.x - copy_blocks, row_start, row_end, col, nnz, n_block_rows, rows,
                                                           n_rows_dev, max_rows, h_src, n_src, src_stride, pieces, agg, agg_stride,
                                                           lanes_log2, src_ids, n_ids, self_out, self_stride, n_self, fg_feat_side{},
                                                           nullptr, 0);
@@ -481,18 +482,19 @@ extern "C" fg_status_t fg_gather_aggregate_ids(const int32_t* row_start_dev, con
     int64_t blocks = fg_ceil_div(max_rows, gpb);
     const int64_t cap = 256 * fg_tuning(FG_TUNE_AGG_WG_PER_CU);
     if (blocks > cap) blocks = cap;
-    int64_t copy_blocks = fg_ceil_div(most, 2 * (AGG_THREADS / 64));
-    if (copy_blocks > 64) copy_blocks = 64;
+    // sized by the bound on the hits (their number is known on the device only): a wavefront copies two rows at a time
+    int64_t copy_blocks = fg_ceil_div(most, 8 * (AGG_THREADS / 64));
+    if (copy_blocks > 256) copy_blocks = 256;
     const size_t lds = (size_t)gpb * AGG_MAX_STAGE * sizeof(int32_t);
     hipStream_t st = (hipStream_t)stream;
     if (f32)
         hipLaunchKernelGGL((loader_fetch_kernel<FG_F32, FG_F32>), dim3((unsigned)(blocks + copy_blocks)), dim3(AGG_THREADS), lds, st,
-                           (int)blocks, copies, row_start_dev, row_end_dev, col_ids_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,
+                           (int)copy_blocks, copies, row_start_dev, row_end_dev, col_ids_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,
                            (const char*)table, table_rows, src_stride, pieces, (char*)agg, agg_stride, lg, row_ids_dev, n_block_rows,
                            (char*)h_self_out, h_self_stride, n_self_rows);
     else
         hipLaunchKernelGGL((loader_fetch_kernel<FG_F16, FG_BF16>), dim3((unsigned)(blocks + copy_blocks)), dim3(AGG_THREADS), lds, st,
-                           (int)blocks, copies, row_start_dev, row_end_dev, col_ids_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,
+                           (int)copy_blocks, copies, row_start_dev, row_end_dev, col_ids_dev, nnz, n_block_rows, rows_dev, n_rows_dev, max_rows,
                            (const char*)table, table_rows, src_stride, pieces, (char*)agg, agg_stride, lg, row_ids_dev, n_block_rows,
                            (char*)h_self_out, h_self_stride, n_self_rows);
     FG_LAUNCH_CHECK("loader_fetch_kernel");

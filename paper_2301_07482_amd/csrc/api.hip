@@ -20,9 +20,10 @@ size_t fg_ws_lookup_prune_bytes(int64_t n);
 size_t fg_ws_cache_update_bytes(int64_t n);
 size_t fg_ws_export_bytes(int64_t capacity);
 
-static int64_t g_tune[FG_TUNE_COUNT] = {16, 4, 1, 1, 16, 0};
+static int64_t g_tune[FG_TUNE_COUNT] = {16, 4, 1, 1, 16, 0, 1};
 static const char* const g_tune_names[FG_TUNE_COUNT] = {"gather_wg_per_cu", "gather_host_wg_per_cu", "gather_unroll",
-                                                        "gather_nontemporal", "aggregate_wg_per_cu", "linear_tile"};
+                                                        "gather_nontemporal", "aggregate_wg_per_cu", "linear_tile",
+                                                        "top_down_walk"};
 
 int64_t fg_tuning(fg_tune_id id) { return g_tune[id]; }
 
@@ -31,7 +32,7 @@ extern "C" fg_status_t fg_set_tuning(const char* key, int64_t value) {
     if (value < 0 || value > 4096) FG_FAIL(FG_ERR_INVALID_ARG, "fg_set_tuning: value %lld out of range", (long long)value);
     for (int i = 0; i < FG_TUNE_COUNT; ++i) {
         if (strcmp(key, g_tune_names[i]) == 0) {
-            if (value == 0 && i != FG_TUNE_GATHER_NONTEMPORAL && i != FG_TUNE_LINEAR_TILE) FG_FAIL(FG_ERR_INVALID_ARG, "fg_set_tuning: %s must be positive", key);
+            if (value == 0 && i != FG_TUNE_GATHER_NONTEMPORAL && i != FG_TUNE_LINEAR_TILE && i != FG_TUNE_TOP_DOWN_WALK) FG_FAIL(FG_ERR_INVALID_ARG, "fg_set_tuning: %s must be positive", key);
             g_tune[i] = value;
             return FG_OK;
         }

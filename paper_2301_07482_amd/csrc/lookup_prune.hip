@@ -156,24 +156,43 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void compact_lists_kernel(
 // ---- the whole top-down pass with short dependency chains ---------------------------------------------------
 //
 // Layer by layer, every step is a chain of dependent random reads (liveness -> id -> map -> slot owner and stamp
-// -> row range -> neighbour positions): latency, not bandwidth or launch overhead, sets its time. The cache
-// lookups do not depend on liveness, so one preparation launch does them for every position of every cached
-// layer at once (and clears the liveness arrays); the per-layer phases that follow only combine flags and walk
-// the rows. The compaction of a layer shares a launch with the classification of the layer below.
+// -> row range -> neighbour positions): latency, not bandwidth or launch overhead, sets its time, and every
+// launch boundary adds to it. The pass is therefore cut into as few launches as its data dependences allow:
+//
+//   1. walk + lookups. The cache lookups do not depend on liveness, so every position of every cached layer is
+//      looked up here. Beside them, one wavefront per seed row walks down the first two blocks: a seed that is
+//      computed marks itself and its neighbours in the layer below, and each of those (one per lane) that is not
+//      cached marks itself and its own neighbours in the layer below that. A node reached from several seeds is
+//      walked once per seed; the marks are idempotent, and for sampled mini-batches (few repeats) the extra work
+//      is small. This settles the liveness of the two layers below the seeds in one launch instead of two.
+//   2. classify: every layer whose liveness is known (up to three) at once: liveness, hit or normal, row cut,
+//      per-workgroup counts; the lowest of them marks the layer below it.
+//   3. compact those layers (ballot ranks + the counts of the preceding workgroups), in the same launch as the
+//      classification of the next layer down, and so on until the last layer is compacted.
+//
+// Liveness travels between launches as one byte per position in the workspace ("marks"), which are all zero between
+// calls: whoever reads a mark clears it. The byte arrays the caller gets (live_src) are written in full by the
+// classification of their layer, so nothing has to be cleared ahead of the marking.
 constexpr int TD_MAX_LAYERS = 8;
+constexpr int TD_WALK_THREADS = 256;
 
 struct TdLayer {
     CacheView cv;
     int has_cache;
     const int32_t* ids;
     int n;
-    const uint8_t* live;
+    const uint8_t* live;   // liveness given by the caller (seed layer, or a layer whose upper neighbour marks nothing); may be null = all live
+    uint8_t* mark;         // workspace, one byte per position, zero between calls: set by the layer above (or the walk)
+    uint8_t* live_out;     // non-null: liveness = mark, written here in full (the caller's live_src array of the layer above)
     const int32_t* row_start;
     int32_t* row_end;
     const int32_t* col;
     int64_t nnz;
     int n_src;
-    uint8_t* live_src;
+    uint8_t* mark_below;   // where normal rows mark the layer below: the next layer's `mark`, or the caller's live_src bytes
+                           // (last layer of the list; cleared by the first launch), or null
+    int n_mark;            // positions of the layer below that can be marked
+    uint8_t* clear_below;  // non-null: mark_below is the caller's array and is cleared by the first launch
     uint8_t* hit;
     int32_t* hit_pos;
     int32_t* hit_slot;
@@ -190,14 +209,66 @@ struct TdArgs {
     int count;
 };
 
-__global__ __launch_bounds__(256) void td_prepare_kernel(TdArgs a) {
-    const int64_t gtid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t gsize = (int64_t)gridDim.x * blockDim.x;
+// Marks the neighbours of one row, eight loads in flight (a slot past the end re-reads the last one).
+__device__ __forceinline__ void td_mark_row(const int32_t* __restrict__ col, int32_t s, int32_t e, uint8_t* __restrict__ mark,
+                                            int n_mark) {
+    for (int32_t x = s; x < e; x += 8) {
+        int32_t c[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) c[u] = col[x + u < e ? x + u : e - 1];
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            if (x + u < e && c[u] >= 0 && c[u] < n_mark) mark[c[u]] = 1;
+    }
+}
+
+// One wavefront per seed row; lane k takes the row itself (k = 0) or its k-th neighbour and, with two hops, walks that
+// node's row of the next block.
+__device__ __forceinline__ void td_walk_rows(const TdArgs& a, int hops, int block, int n_blocks) {
+    const TdLayer& A = a.layer[0];
+    const TdLayer& B = a.layer[1];
+    const int lane = threadIdx.x & 63;
+    const int n_waves = n_blocks * (TD_WALK_THREADS / 64);
+    for (int r = (block * TD_WALK_THREADS + (int)threadIdx.x) >> 6; r < A.n; r += n_waves) {
+        const uint8_t live_r = A.live ? A.live[r] : (uint8_t)1;
+        const int32_t s0 = A.row_start[r], e0 = A.row_end[r];
+        const int32_t id_r = A.has_cache ? A.ids[r] : -1;
+        if (!live_r) continue;
+        if (A.has_cache && cache_lookup(A.cv, id_r) >= 0) continue;   // a cached seed needs nothing below it
+        const int deg = (s0 >= 0 && s0 <= e0 && (int64_t)e0 <= A.nnz) ? e0 - s0 : 0;
+        for (int k = lane; k <= deg; k += 64) {
+            const int32_t t = k == 0 ? r : A.col[s0 + k - 1];
+            if (t < 0 || t >= A.n_mark) continue;
+            if (hops < 2) {
+                A.mark_below[t] = 1;
+                continue;
+            }
+            // everything this node may need is requested before anything is stored
+            const int32_t id_t = B.has_cache ? B.ids[t] : -1;
+            const int32_t s1 = B.row_start[t], e1 = B.row_end[t];
+            const bool cached = B.has_cache && cache_lookup(B.cv, id_t) >= 0;
+            A.mark_below[t] = 1;
+            if (cached || !B.mark_below) continue;
+            if (t < B.n_mark) B.mark_below[t] = 1;
+            if (s1 >= 0 && s1 <= e1 && (int64_t)e1 <= B.nnz) td_mark_row(B.col, s1, e1, B.mark_below, B.n_mark);
+        }
+    }
+}
+
+// Launch 1: workgroups [0, walk_blocks) walk down from the seeds; the others look every position of every cached layer up
+// and clear the caller's liveness array below the last layer, if that is wanted.
+__global__ __launch_bounds__(TD_WALK_THREADS) void td_walk_kernel(TdArgs a, int hops, int walk_blocks) {
+    if ((int)blockIdx.x < walk_blocks) {
+        td_walk_rows(a, hops, blockIdx.x, walk_blocks);
+        return;
+    }
+    const int64_t gtid = (int64_t)(blockIdx.x - walk_blocks) * blockDim.x + threadIdx.x;
+    const int64_t gsize = (int64_t)(gridDim.x - walk_blocks) * blockDim.x;
     for (int i = 0; i < a.count; ++i) {
         const TdLayer& L = a.layer[i];
         if (L.has_cache)
             for (int64_t j = gtid; j < L.n; j += gsize) L.slot[j] = cache_lookup(L.cv, L.ids[j]);
-        uint8_t* p = L.live_src;
+        uint8_t* p = L.clear_below;
         if (!p) continue;
         const int64_t n = L.n_src;
         const int64_t head = ((uintptr_t)p & 3) ? 4 - (int64_t)((uintptr_t)p & 3) : 0;  // bytes up to 4-byte alignment
@@ -208,23 +279,91 @@ __global__ __launch_bounds__(256) void td_prepare_kernel(TdArgs a) {
     }
 }
 
-// workgroups [0, nc_cur) classify layer `cur`; workgroups [nc_cur, nc_cur + nc_prev) compact layer `prev`
-__global__ __launch_bounds__(FG_SCAN_BLOCK) void td_phase_kernel(TdArgs a, int cur, int prev, int nc_cur, int nc_prev) {
+// One chunk of FG_SCAN_BLOCK positions of one layer: liveness (from the caller or from the marks, which are cleared),
+// class, row cut, and, if `mark`, the marks of a normal row in the layer below.
+__device__ __forceinline__ void td_classify_chunk(const TdLayer& L, int chunk, bool mark) {
+    const int j = chunk * FG_SCAN_BLOCK + threadIdx.x;
+    const bool in = j < L.n;
+    uint8_t live_j = 0;
+    if (in) live_j = L.live_out ? L.mark[j] : (L.live ? L.live[j] : (uint8_t)1);
+    int32_t s0 = 0, e0 = 0, slot_j = -1;
+    if (in && L.row_start) {
+        s0 = L.row_start[j];
+        e0 = L.row_end[j];
+    }
+    if (in && L.has_cache) slot_j = L.slot[j];   // the node's usable slot or -1, looked up for every position by launch 1
+    const bool is_live = live_j != 0;
+    const bool hit = is_live && L.has_cache && slot_j >= 0;
+    const int32_t slot = hit ? slot_j : -1;
+    const bool normal = is_live && !hit;
+    if (in) {
+        if (L.live_out) {
+            L.live_out[j] = is_live ? 1 : 0;
+            if (is_live) L.mark[j] = 0;
+        }
+        L.cls[j] = is_live ? (hit ? CLS_HIT : CLS_NORMAL) : CLS_DEAD;
+        L.slot[j] = slot;
+        if (L.hit) L.hit[j] = hit ? 1 : 0;
+        if (L.row_start) {
+            if (!normal) {
+                L.row_end[j] = s0;
+            } else if (mark && L.mark_below) {
+                if (j < L.n_mark) L.mark_below[j] = 1;
+                if (s0 >= 0 && s0 <= e0 && (int64_t)e0 <= L.nnz) td_mark_row(L.col, s0, e0, L.mark_below, L.n_mark);
+            }
+        }
+    }
+    const int c_live = __syncthreads_count(is_live);
+    const int c_hit = __syncthreads_count(hit);
+    if (threadIdx.x == 0) {
+        L.blk[3 * chunk + 0] = c_live;
+        L.blk[3 * chunk + 1] = c_hit;
+        L.blk[3 * chunk + 2] = c_live - c_hit;
+    }
+}
+
+struct TdPhase {
+    int cls_first, cls_last;   // layers classified by this launch (cls_first > cls_last: none)
+    int mark_from;             // those at or beyond this index also mark the layer below
+    int cmp_first, cmp_last;   // layers compacted by this launch
+    int cls_blocks;            // workgroups that classify; the rest compact
+};
+
+__device__ __forceinline__ int td_chunks(int n) { return (n + FG_SCAN_BLOCK - 1) / FG_SCAN_BLOCK; }
+
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void td_phase_kernel(TdArgs a, TdPhase p) {
     __shared__ long long red[16];
     __shared__ int sc[17];
-    const int b = blockIdx.x;
-    if (b < nc_cur) {
-        const TdLayer& L = a.layer[cur];
-        classify_mark_chunk(L.cv, L.has_cache, L.ids, L.n, L.live, L.row_start, L.row_end, L.col, L.nnz, L.n_src, L.live_src,
-                            L.hit, L.cls, L.slot, L.blk, b, true);
-    } else if (prev >= 0) {
-        const TdLayer& P = a.layer[prev];
-        if (nc_prev == 0) {
-            if (threadIdx.x < 3) P.counts[threadIdx.x] = 0;
-        } else {
-            compact_lists_chunk(P.ids, P.n, P.cls, P.slot, P.blk, P.has_cache ? P.hit_pos : nullptr, P.hit_slot, P.normal_pos,
-                                P.normal_ids, P.counts, b - nc_cur, nc_prev, red, sc);
+    int b = blockIdx.x;
+    if (b < p.cls_blocks) {
+        for (int i = p.cls_first; i <= p.cls_last; ++i) {
+            const int nc = td_chunks(a.layer[i].n);
+            if (b < nc) {
+                td_classify_chunk(a.layer[i], b, i >= p.mark_from);
+                return;
+            }
+            b -= nc;
         }
+        return;
+    }
+    b -= p.cls_blocks;
+    for (int i = p.cmp_first; i <= p.cmp_last; ++i) {
+        const TdLayer& P = a.layer[i];
+        const int nc = td_chunks(P.n);
+        if (nc == 0) {      // an empty layer has one workgroup, which writes its counts
+            if (b == 0) {
+                if (threadIdx.x < 3) P.counts[threadIdx.x] = 0;
+                return;
+            }
+            b -= 1;
+            continue;
+        }
+        if (b < nc) {
+            compact_lists_chunk(P.ids, P.n, P.cls, P.slot, P.blk, P.has_cache ? P.hit_pos : nullptr, P.hit_slot, P.normal_pos,
+                                P.normal_ids, P.counts, b, nc, red, sc);
+            return;
+        }
+        b -= nc;
     }
 }
 
@@ -356,20 +495,31 @@ extern "C" fg_status_t fg_lookup_prune_static(const fg_cache_t* cache, int32_t l
                                ws, LP_STATIC_BYTES, stream);
 }
 
-extern "C" size_t fg_top_down_workspace_bytes(int32_t n_layers, const fg_top_down_layer_t* layers) {
-    if (n_layers <= 0 || !layers) return 0;
+// Workspace of the whole pass: its first half holds class, slot and counts of every layer (laid out back to back for the
+// sizes of the call), its second half the marks. The halves never overlap for any sizes that fit, so the marks stay
+// all-zero between calls whatever the layer sizes of the calls are.
+static size_t td_other_bytes(int32_t n_layers, const fg_top_down_layer_t* layers) {
     size_t total = 0;
     for (int i = 0; i < n_layers; ++i) total += ws_layout(layers[i].n > 0 ? layers[i].n : 0).total;
     return total;
+}
+
+extern "C" size_t fg_top_down_workspace_bytes(int32_t n_layers, const fg_top_down_layer_t* layers) {
+    if (n_layers <= 0 || !layers) return 0;
+    return 2 * td_other_bytes(n_layers, layers) + 512;
 }
 
 extern "C" fg_status_t fg_top_down(const fg_cache_t* cache, int64_t iter, int32_t n_layers,
                                    const fg_top_down_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream) {
     if (n_layers <= 0 || n_layers > TD_MAX_LAYERS || !layers)
         FG_FAIL(FG_ERR_INVALID_ARG, "fg_top_down: n_layers = %d must be in 1..%d and layers non-NULL", n_layers, TD_MAX_LAYERS);
+    const size_t need = fg_top_down_workspace_bytes(n_layers, layers);
+    if (!ws_dev || ws_bytes < need) FG_FAIL(FG_ERR_SHAPE, "fg_top_down: workspace of %zu bytes given, %zu needed", ws_bytes, need);
+    if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_top_down: workspace must be 16-byte aligned");
+    const size_t marks_at = (ws_bytes / 2 + 255) / 256 * 256;   // depends on the workspace alone, not on the layers of the call
     TdArgs a{};
     a.count = n_layers;
-    size_t off = 0;
+    size_t off = 0, mark_off = marks_at;
     for (int i = 0; i < n_layers; ++i) {
         const fg_top_down_layer_t& in = layers[i];
         TdLayer& L = a.layer[i];
@@ -409,7 +559,6 @@ extern "C" fg_status_t fg_top_down(const fg_cache_t* cache, int64_t iter, int32_
         L.col = in.col_dev;
         L.nnz = in.nnz;
         L.n_src = in.n_src;
-        L.live_src = has_block ? in.live_src_dev : nullptr;
         L.hit = in.hit_dev;
         L.hit_pos = in.hit_pos_dev;
         L.hit_slot = in.hit_slot_dev;
@@ -420,30 +569,73 @@ extern "C" fg_status_t fg_top_down(const fg_cache_t* cache, int64_t iter, int32_
         L.slot = (int32_t*)((char*)ws_dev + off + w.slot);
         L.blk = (int32_t*)((char*)ws_dev + off + w.blk);
         off += w.total;
+        L.mark = (uint8_t*)ws_dev + mark_off;
+        mark_off += fg_align_up((size_t)(in.n > 0 ? in.n : 0), 256);
     }
-    if (!ws_dev || ws_bytes < off) FG_FAIL(FG_ERR_SHAPE, "fg_top_down: workspace of %zu bytes given, %zu needed", ws_bytes, off);
-    if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "fg_top_down: workspace must be 16-byte aligned");
+    if (off > marks_at || mark_off > ws_bytes) FG_FAIL(FG_ERR_SHAPE, "fg_top_down: the workspace is too small for these layers");
+    // how liveness reaches each layer, and where each layer marks
+    for (int i = 0; i < n_layers; ++i) a.layer[i].live_out = nullptr;
+    for (int i = 0; i < n_layers; ++i) {
+        TdLayer& L = a.layer[i];
+        uint8_t* live_src = L.row_start ? layers[i].live_src_dev : nullptr;
+        L.mark_below = L.clear_below = nullptr;
+        L.n_mark = 0;
+        if (!live_src) continue;
+        if (i + 1 < n_layers) {      // the layer below is part of the call: marks in the workspace, bytes written by its classification
+            L.mark_below = a.layer[i + 1].mark;
+            L.n_mark = L.n_src < a.layer[i + 1].n ? L.n_src : a.layer[i + 1].n;
+            a.layer[i + 1].live_out = live_src;
+        } else {                     // the caller's array is marked directly and cleared first
+            L.mark_below = L.clear_below = live_src;
+            L.n_mark = L.n_src;
+        }
+    }
     fg_clear_error();
     hipStream_t st = (hipStream_t)stream;
+    // hops the walk takes from the seeds: a block whose marks go to a layer of this call
+    int hops = 0;
+    if (fg_tuning(FG_TUNE_TOP_DOWN_WALK) != 0 && n_layers >= 2 && a.layer[0].mark_below && a.layer[0].n > 0) {
+        hops = 1;
+        const int64_t second = (int64_t)a.layer[0].n + a.layer[0].nnz;   // rows of the second block the walk visits, at most
+        if (n_layers >= 3 && a.layer[1].row_start && a.layer[1].mark_below && second <= 262144) hops = 2;
+    }
     int64_t prep = 0;
     for (int i = 0; i < n_layers; ++i) {
         if (a.layer[i].has_cache) prep = prep > a.layer[i].n ? prep : a.layer[i].n;
-        // every liveness array is cleared by this launch, however short it is
-        if (a.layer[i].live_src) prep = prep > fg_ceil_div(a.layer[i].n_src, 4) ? prep : fg_ceil_div(a.layer[i].n_src, 4);
+        // the caller's liveness array below the last layer is cleared by this launch, however short it is
+        if (a.layer[i].clear_below) prep = prep > fg_ceil_div(a.layer[i].n_src, 4) ? prep : fg_ceil_div(a.layer[i].n_src, 4);
     }
-    if (prep > 0) {
-        const int64_t blocks = fg_ceil_div(prep, 256) < 2048 ? fg_ceil_div(prep, 256) : 2048;
-        hipLaunchKernelGGL(td_prepare_kernel, dim3((unsigned)blocks), dim3(256), 0, st, a);
-        FG_LAUNCH_CHECK("td_prepare_kernel");
+    const int walk_blocks = hops > 0 ? (int)fg_ceil_div(a.layer[0].n, TD_WALK_THREADS / 64) : 0;
+    int64_t prep_blocks = fg_ceil_div(prep, TD_WALK_THREADS);
+    if (prep_blocks > 2048) prep_blocks = 2048;
+    if (walk_blocks + prep_blocks > 0) {
+        hipLaunchKernelGGL(td_walk_kernel, dim3((unsigned)(walk_blocks + prep_blocks)), dim3(TD_WALK_THREADS), 0, st, a, hops, walk_blocks);
+        FG_LAUNCH_CHECK("td_walk_kernel");
     }
-    for (int i = 0; i <= n_layers; ++i) {
-        const int nc_cur = i < n_layers ? (int)fg_ceil_div(a.layer[i].n, FG_SCAN_BLOCK) : 0;
-        const int nc_prev = i > 0 ? (int)fg_ceil_div(a.layer[i - 1].n, FG_SCAN_BLOCK) : 0;
-        const int grid = nc_cur + (i > 0 ? (nc_prev > 0 ? nc_prev : 1) : 0);
-        if (grid == 0) continue;
-        hipLaunchKernelGGL(td_phase_kernel, dim3(grid), dim3(FG_SCAN_BLOCK), 0, st, a, i < n_layers ? i : -1, i > 0 ? i - 1 : -1,
-                           nc_cur, nc_prev);
-        FG_LAUNCH_CHECK("td_phase_kernel");
+    // classification of the layers [lo, hi], then compaction of those beside the classification of the next layer
+    auto chunks = [&](int i) { return (int)fg_ceil_div(a.layer[i].n, FG_SCAN_BLOCK); };
+    int cmp_first = 0, cmp_last = -1;          // classified, not yet compacted
+    int next = 0;                              // first layer not yet classified
+    while (next < n_layers || cmp_first <= cmp_last) {
+        TdPhase p{};
+        p.cls_first = next;
+        p.cls_last = next - 1;
+        if (next < n_layers) p.cls_last = next == 0 ? hops : next;     // the first classification takes every layer the walk settled
+        p.mark_from = (next == 0) ? hops : next;                         // layers above `hops` were marked from by the walk
+        p.cmp_first = cmp_first;
+        p.cmp_last = cmp_last;
+        p.cls_blocks = 0;
+        for (int i = p.cls_first; i <= p.cls_last; ++i) p.cls_blocks += chunks(i);
+        int cmp_blocks = 0;
+        for (int i = p.cmp_first; i <= p.cmp_last; ++i) cmp_blocks += chunks(i) > 0 ? chunks(i) : 1;
+        if (p.cls_blocks + cmp_blocks > 0) {
+            hipLaunchKernelGGL(td_phase_kernel, dim3((unsigned)(p.cls_blocks + cmp_blocks)), dim3(FG_SCAN_BLOCK), 0, st, a, p);
+            FG_LAUNCH_CHECK("td_phase_kernel");
+        }
+        cmp_first = p.cls_first;
+        cmp_last = p.cls_last;
+        next = p.cls_last + 1 > next ? p.cls_last + 1 : next;
+        if (p.cls_first > p.cls_last) break;   // that launch only compacted: done
     }
     return FG_OK;
 }

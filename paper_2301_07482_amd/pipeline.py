@@ -180,8 +180,7 @@ class HotPath:
         # fused_input: layer 1 aggregates straight from the feature table (fg_gather_aggregate); only the layer-1
         # nodes' own rows are gathered into H[0] and the top-down pass stops at layer 1
         self.fused_input = fused_input
-        # one_launch_top_down: the whole top-down pass as one cooperative launch (fg_top_down) instead of one
-        # fg_lookup_prune call per layer
+        # one_launch_top_down: the whole top-down pass as one call (fg_top_down) instead of one fg_lookup_prune call per layer
         self.one_launch_top_down = one_launch_top_down
         self.n_max, self.nnz_max = layer_bounds(batch, fanouts, num_nodes)
         n = self.n_max
@@ -235,7 +234,8 @@ class HotPath:
                        max([B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L)] or [0]))
         self.ws = torch.zeros(ws_bytes + 256, dtype=torch.uint8, device=dev)
         self.ws_bytes = ws_bytes
-        self.ws_td_bytes = sum(B.fg_workspace_bytes(B.FG_WS_LOOKUP_PRUNE, n[l]) for l in range(L + 1))
+        # workspace of fg_top_down: zero-filled once, then kept all-zero by the calls themselves
+        self.ws_td_bytes = B.fg_top_down_workspace_bytes(B.top_down_layers([dict(n=n[l]) for l in range(L, -1, -1)]))
         self.ws_td = torch.zeros(self.ws_td_bytes + 256, dtype=torch.uint8, device=dev)
         # all caches are updated by one call after the last layer (the last loop of Algorithm 1)
         self.update_all = update_all
