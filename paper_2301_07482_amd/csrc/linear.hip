@@ -321,6 +321,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+constexpr int X3_LIST = 8;                                  // tasks whose rows a wavefront lists ahead in LDS
+constexpr int X3_LIST_BYTES = PL_WAVES * X3_LIST * 32 * 4;  // the lists of a workgroup
 
 // v[0..7] -> three fragments of eight bf16 (element j in half j % 2 of word j / 2)
 __device__ __forceinline__ void split8(const float* v, u32x4& t1, u32x4& t2, u32x4& t3) {
@@ -345,7 +348,7 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
-    int64_t out_stride, int n_panels, int n_groups) {
+    int64_t out_stride, int n_panels, int n_groups, int near_out) {
     constexpr int BNW = PL_BN * NB;
     extern __shared__ __attribute__((aligned(16))) u32x4 bfrag[];  // [3 terms][K / 8 groups of k][BNW columns]
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
@@ -362,22 +365,28 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
     if (group >= n_blocks) return;  // uniform over the workgroup, before the barrier
 
     // group gi = (chunk * 2 + m) * 2 + half holds k = 32 * chunk + 16 * half + 8 * m + (0..7): the eight k values that
-    // half-wavefront `half` feeds to matrix instruction m of the chunk
-    for (int q = t; q < ngr * BNW; q += PL_THREADS) {
-        const int col = q % BNW, gi = q / BNW;
+    // half-wavefront `half` feeds to matrix instruction m of the chunk. A thread takes a block of 8 k x 4 columns of W:
+    // eight 16-byte loads, all issued before the first value is used (one memory round trip per pass, and the layers
+    // of the workloads need a single pass), then the four columns' fragments.
+    for (int q = t; q < ngr * (BNW / 4); q += PL_THREADS) {
+        const int c4 = (q % (BNW / 4)) * 4, gi = q / (BNW / 4);
         const int k0 = 32 * (gi >> 2) + 16 * (gi & 1) + 8 * ((gi >> 1) & 1);
-        const bool in = n0 + col < d_out;
-        const float* wp = W + (int64_t)k0 * d_out + (in ? n0 + col : 0);
-        float v[8];
+        const bool in = n0 + c4 < d_out;      // d_out is a multiple of 4: the four columns exist together
+        const float* wp = W + (int64_t)k0 * d_out + (in ? n0 + c4 : 0);
+        f32x4 w4[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = wp[(int64_t)e * d_out];
+        for (int e = 0; e < 8; ++e) w4[e] = *(const f32x4*)(wp + (int64_t)e * d_out);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) v[e] = in ? v[e] : 0.f;
-        u32x4 t1, t2, t3;
-        split8(v, t1, t2, t3);
-        bfrag[(0 * ngr + gi) * BNW + col] = t1;
-        bfrag[(1 * ngr + gi) * BNW + col] = t2;
-        bfrag[(2 * ngr + gi) * BNW + col] = t3;
+        for (int cc = 0; cc < 4; ++cc) {
+            float v[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) v[e] = in ? w4[e][cc] : 0.f;
+            u32x4 t1, t2, t3;
+            split8(v, t1, t2, t3);
+            bfrag[(0 * ngr + gi) * BNW + c4 + cc] = t1;
+            bfrag[(1 * ngr + gi) * BNW + c4 + cc] = t2;
+            bfrag[(2 * ngr + gi) * BNW + c4 + cc] = t3;
+        }
     }
     __syncthreads();
 
@@ -389,11 +398,12 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
         const int c = n0 + nb * 32 + l32;
         bv[nb] = (bias && c < d_out) ? (double)bias[c] : 0.0;
     }
-    // Destination / source row of this lane in row block rbx (-1: past the end or out of range), in two steps: the
-    // load is issued unconditionally (clamped index; a valid dummy address if there is no row list) and its value is
-    // looked at a whole task later. A branch around the load, or any use of the value next to it, would make the
-    // wavefront wait for everything it has in flight: the prefetched A values and the previous task's stores.
-    auto row_raw = [&](int64_t rbx) -> int32_t {
+    // The destination / source rows of a wavefront's next X3_LIST tasks are kept in LDS (behind the fragments): lane l32's
+    // row of task t at rowlist[t * 32 + l32], -1 for a row past the end or out of range. Reading them costs no wait on
+    // global memory: a global load of a row index in the middle of a task would make the wavefront wait for everything
+    // it has in flight (the A values fetched ahead, the previous task's stores), since those complete in order.
+    int32_t* rowlist = (int32_t*)(bfrag + 3 * ngr * BNW) + wave * (X3_LIST * 32);
+    auto row_raw = [&](int64_t rbx) -> int32_t {      // unconditional load: clamped index, a valid dummy address without a list
         int64_t g = rbx * 32 + l32;
         g = g < n_rows ? g : n_rows - 1;  // n_rows >= 1 here
         const int32_t* src = rows ? rows + g : (const int32_t*)h_src;
@@ -406,108 +416,141 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
         return r;
     };
     const int64_t stride = (int64_t)n_groups * PL_WAVES;
-    int64_t rb = group + (int64_t)n_groups * wave;
-    if (rb >= n_blocks) return;
-    int32_t r = row_decode(row_raw(rb), rb);
-    int32_t r_next = row_decode(row_raw(rb + stride), rb + stride);
-    const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
-    const float* a_agg = (const float*)(agg + (r >= 0 ? (rb * 32 + l32) * agg_stride : 0)) + 16 * half;
-    f32x4 a0[4], a1[4];
+    for (int64_t rb0 = group + (int64_t)n_groups * wave; rb0 < n_blocks; rb0 += X3_LIST * stride) {
+        {
+            int32_t raw[X3_LIST];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(a_self + 4 * q);  // step 0 of the first task
-    for (; rb < n_blocks; rb += stride) {
-        const int32_t raw_after = row_raw(rb + 2 * stride);  // looked at when this task is done
-        double sum[NB][16];
+            for (int q = 0; q < X3_LIST; ++q) raw[q] = row_raw(rb0 + q * stride);
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+            for (int q = 0; q < X3_LIST; ++q) rowlist[q * 32 + l32] = row_decode(raw[q], rb0 + q * stride);   // both halves write the same value
+        }
+        int32_t r = rowlist[l32];
+        const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+        const float* a_agg = (const float*)(agg + (r >= 0 ? (rb0 * 32 + l32) * agg_stride : 0)) + 16 * half;
+        f32x4 a0[4], a1[4];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) sum[nb][i] = 0.0;
-        auto compute = [&](int step, const f32x4* a) {
-            float av[16];
+        for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(a_self + 4 * q);  // step 0 of the first task of the list
+        for (int tk = 0; tk < X3_LIST; ++tk) {
+            const int64_t rb = rb0 + tk * stride;
+            if (rb >= n_blocks) break;
+            // the row of the next task: its first K step is fetched during this task's last one (the last task of a
+            // list fetches row 0 instead, and the next list starts with a fetch of its own)
+            const int32_t r_next = tk + 1 < X3_LIST ? rowlist[(tk + 1) * 32 + l32] : -1;
+            // Two fp32 accumulators per column block, kept across the whole K range: `big` takes the products of the two
+            // leading bf16 terms, `small` the five products that are 2^-8 and 2^-16 of those. What limits an fp32
+            // running sum is the rounding of the sum itself at every accumulation step; with the leading term alone
+            // `big` is rounded once per 16 k values (a sixth of the steps), and the roundings of `small` are 2^-8 of
+            // that. Modelled and measured error: that of folding every 32 k values into fp64 (the output's own
+            // rounding dominates), with none of the fold's vector work and half its registers.
+            f32x16 big[NB], small[NB];
 #pragma unroll
-            for (int q = 0; q < 16; ++q) av[q] = a[q >> 2][q & 3];
-            u32x4 A[3][2];  // [term][m]
-            split8(av, A[0][0], A[1][0], A[2][0]);
-            split8(av + 8, A[0][1], A[1][1], A[2][1]);
-            // (A term, W term) pairs, smallest products first
-            constexpr int TA[6] = {2, 0, 1, 1, 0, 0};
-            constexpr int TW[6] = {0, 2, 1, 0, 1, 0};
+            for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                f32x16 acc;
+                for (int i = 0; i < 16; ++i) big[nb][i] = small[nb][i] = 0.f;
+            auto compute = [&](int step, const f32x4* a) {
+                float av[16];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+                for (int q = 0; q < 16; ++q) av[q] = a[q >> 2][q & 3];
+                u32x4 A[3][2];  // [term][m]
+                split8(av, A[0][0], A[1][0], A[2][0]);
+                split8(av + 8, A[0][1], A[1][1], A[2][1]);
+                // (A term, W term) pairs of the small products, smallest first; the leading pair (0, 0) goes to `big`
+                constexpr int TA[5] = {2, 0, 1, 1, 0};
+                constexpr int TW[5] = {0, 2, 1, 0, 1};
 #pragma unroll
                 for (int m = 0; m < 2; ++m) {
-                    const int base = ((step * 2 + m) * 2 + half) * BNW + nb * 32 + l32;
-                    u32x4 f[3];
+                    u32x4 f[NB][3];
 #pragma unroll
-                    for (int term = 0; term < 3; ++term) f[term] = bfrag[term * ngr * BNW + base];
+                    for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                    for (int e = 0; e < 6; ++e)
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[TA[e]][m]),
-                                                                      __builtin_bit_cast(bf16x8, f[TW[e]]), acc, 0, 0, 0);
+                        for (int term = 0; term < 3; ++term)
+                            f[nb][term] = bfrag[term * ngr * BNW + ((step * 2 + m) * 2 + half) * BNW + nb * 32 + l32];
+                    // the accumulator chains alternate, so that consecutive matrix instructions never depend on each other
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        big[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[0][m]),
+                                                                          __builtin_bit_cast(bf16x8, f[nb][0]), big[nb], 0, 0, 0);
+#pragma unroll
+                    for (int e = 0; e < 5; ++e)
+#pragma unroll
+                        for (int nb = 0; nb < NB; ++nb)
+                            small[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, A[TA[e]][m]),
+                                                                                __builtin_bit_cast(bf16x8, f[nb][TW[e]]), small[nb], 0, 0, 0);
                 }
+            };
+            for (int step = 0; step < nk; step += 2) {
+                {
+                    const int s1 = step + 1;
+                    const float* p = s1 < nk_self ? a_self + s1 * KC : a_agg + (s1 - nk_self) * KC;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sum[nb][i] += (double)acc[i];
+                    for (int q = 0; q < 4; ++q) a1[q] = *(const f32x4*)(p + 4 * q);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                compute(step, a0);
+                {
+                    const int s2 = step + 2;
+                    const float* nxt = (const float*)(h_src + (r_next >= 0 ? (int64_t)r_next * src_stride : 0)) + 16 * half;
+                    const float* cur = s2 < nk_self ? a_self + s2 * KC : a_agg + (s2 < nk ? s2 - nk_self : 0) * KC;
+                    const float* p = s2 < nk ? cur : nxt;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(p + 4 * q);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                compute(step + 1, a1);
             }
-        };
-        for (int step = 0; step < nk; step += 2) {
-            {
-                const int s1 = step + 1;
-                const float* p = s1 < nk_self ? a_self + s1 * KC : a_agg + (s1 - nk_self) * KC;
+            // accumulator element i is row 8*(i/4) + 4*half + i%4 of the block, column l32 of its column block: the
+            // destination rows of elements 4q .. 4q+3 are four consecutive entries of the list
+            int32_t rr[16];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) a1[q] = *(const f32x4*)(p + 4 * q);
+            for (int q = 0; q < 4; ++q) {
+                const i32x4 four = *(const i32x4*)(rowlist + tk * 32 + 8 * q + 4 * half);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) rr[4 * q + u] = four[u];
             }
-            __builtin_amdgcn_sched_barrier(0);
-            compute(step, a0);
-            {
-                const int s2 = step + 2;
-                const float* nxt = (const float*)(h_src + (r_next >= 0 ? (int64_t)r_next * src_stride : 0)) + 16 * half;
-                const float* cur = s2 < nk_self ? a_self + s2 * KC : a_agg + (s2 < nk ? s2 - nk_self : 0) * KC;
-                const float* p = s2 < nk ? cur : nxt;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(p + 4 * q);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            compute(step + 1, a1);
-        }
-        const int32_t r_after = row_decode(raw_after, rb + 2 * stride);  // before the stores below are in flight
-        // accumulator element i is row 8*(i/4) + 4*half + i%4 of the block, column l32 of its column block. Lane m
-        // (< 32) holds the destination row of block row m: all 16 exchanges are issued before the first one is used.
-        int32_t rr[16];
-#pragma unroll
-        for (int i = 0; i < 16; ++i) rr[i] = __shfl(r, 8 * (i >> 2) + 4 * half + (i & 3), 64);
-        // A block whose 32 rows are all in range and whose columns all exist (every block but the ragged last ones)
-        // is stored without a condition per element: 32 branches would put every store in a basic block of its own.
-        const bool whole = __all(r >= 0) && n0 + BNW <= d_out;
-        if (whole) {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                char* out_col = h_out + (int64_t)(n0 + nb * 32 + l32) * 4;
+            // A block whose 32 rows are all in range and whose columns all exist (every block but the ragged last ones)
+            // is stored without a condition per element: 32 branches would put every store in a basic block of its own.
+            const bool whole = __all(r >= 0) && n0 + BNW <= d_out;
+            if (whole && near_out) {
+                // every byte offset into h_out fits 31 bits and rows and stride fit 24: one full-rate multiply per row,
+                // shared by the column blocks, and the stores take the uniform base with a 32-bit offset
+                const uint32_t col_off = (uint32_t)(n0 + l32) * 4u;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    float v = (float)(sum[nb][i] + bv[nb]);
-                    if (relu) v = v > 0.f ? v : 0.f;
-                    *(float*)(out_col + (int64_t)rr[i] * out_stride) = v;
+                    const uint32_t row_off = __umul24((uint32_t)rr[i], (uint32_t)out_stride) + col_off;
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb) {
+                        float v = (float)((double)big[nb][i] + (double)small[nb][i] + bv[nb]);
+                        if (relu) v = fmaxf(v, 0.f);
+                        *(float*)(h_out + (size_t)(row_off + (uint32_t)nb * 128u)) = v;
+                    }
+                }
+            } else if (whole) {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    char* out_col = h_out + (int64_t)(n0 + nb * 32 + l32) * 4;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        float v = (float)((double)big[nb][i] + (double)small[nb][i] + bv[nb]);
+                        if (relu) v = fmaxf(v, 0.f);
+                        *(float*)(out_col + (int64_t)rr[i] * out_stride) = v;
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const int c = n0 + nb * 32 + l32;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        float v = (float)((double)big[nb][i] + (double)small[nb][i] + bv[nb]);
+                        if (relu) v = fmaxf(v, 0.f);
+                        if (rr[i] >= 0 && c < d_out) *(float*)(h_out + (int64_t)rr[i] * out_stride + (int64_t)c * 4) = v;
+                    }
                 }
             }
-        } else {
-#pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const int c = n0 + nb * 32 + l32;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float v = (float)(sum[nb][i] + bv[nb]);
-                    if (relu) v = v > 0.f ? v : 0.f;
-                    if (rr[i] >= 0 && c < d_out) *(float*)(h_out + (int64_t)rr[i] * out_stride + (int64_t)c * 4) = v;
-                }
-            }
+            r = r_next;
+            a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+            a_agg = (const float*)(agg + (r >= 0 ? ((rb + stride) * 32 + l32) * agg_stride : 0)) + 16 * half;
         }
-        r = r_next;
-        r_next = r_after;
-        a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
-        a_agg = (const float*)(agg + (r >= 0 ? ((rb + stride) * 32 + l32) * agg_stride : 0)) + 16 * half;
     }
 }
 
@@ -716,23 +759,25 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
         const size_t x3_bytes = (size_t)2 * d_in * 192;
         if (d_in % KC == 0 && x3_bytes <= 144 * 1024 && (forced == 0 || forced == 301 || forced == 302)) {
             const int nb = (forced != 301 && 2 * x3_bytes <= 144 * 1024) ? 2 : 1;
-            const size_t lds = x3_bytes * nb;
+            const size_t lds = x3_bytes * nb + X3_LIST_BYTES;     // fragments of the panel, then the wavefronts' row lists
             const int n_panels = (int)fg_ceil_div(d_out, PL_BN * nb);
             int q = 256 / (8 * n_panels);  // register use allows one workgroup per compute unit
             if (q < 1) q = 1;
             const int64_t blocks32 = fg_ceil_div(max_rows, 32);
             while (q > 1 && (int64_t)8 * (q - 1) >= blocks32) --q;
             const int n_groups = 8 * q;
+            // output offsets in 32 bits: every byte of h_out below 2^31, rows and stride below 2^24
+            const int near_out = ((int64_t)n_out * out_stride < (1ll << 31) && n_out < (1 << 24) && out_stride < (1 << 24)) ? 1 : 0;
             if (nb == 2)
                 hipLaunchKernelGGL(linear_f32x3_panel_kernel<2>, dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), lds, st,
                                    (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev,
                                    max_rows, d_in, d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels,
-                                   n_groups);
+                                   n_groups, near_out);
             else
                 hipLaunchKernelGGL(linear_f32x3_panel_kernel<1>, dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), lds, st,
                                    (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev,
                                    max_rows, d_in, d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels,
-                                   n_groups);
+                                   n_groups, near_out);
             FG_LAUNCH_CHECK("linear_f32x3_panel_kernel");
             return FG_OK;
         }
