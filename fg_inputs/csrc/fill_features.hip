@@ -26,11 +26,16 @@ __global__ void fill_features_kernel(T* out, uint64_t key, int64_t first_row, in
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const uint64_t base = (uint64_t)first_row * (uint64_t)dim;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-        const float v = feature_value(key, base + (uint64_t)i);
-        if constexpr (sizeof(T) == 4)
+        float v = feature_value(key, base + (uint64_t)i);
+        if constexpr (sizeof(T) == 4) {
             out[i] = v;
-        else
+        } else {
+            // The fp16 value is the fp32 product rounded once more. Left to itself the compiler may merge multiply and
+            // conversion into one mixed-precision instruction that rounds the exact product straight to fp16, which
+            // differs where the fp32 product lands on an fp16 tie; the empty statement keeps the two roundings apart.
+            asm volatile("" : "+v"(v));
             out[i] = __float2half_rn(v);
+        }
     }
 }
 

@@ -157,3 +157,32 @@ def test_header_is_plain_c(tmp_path):
         args = [cc, std, "-Wall", "-Wextra", "-Werror", "-pedantic", "-I", inc, "-fsyntax-only"] + (["-x", "c++"] if cc == "g++" else []) + [str(src)]
         p = subprocess.run(args, capture_output=True, text=True)
         assert p.returncode == 0, p.stderr
+
+
+def test_three_way_bf16_split_is_exact_on_the_documented_input_domain():
+    """fg_linear forms fp32 products from an exact three-way bf16 split of both factors (x = x1 + x2 + x3, each term the
+    bf16 nearest to what is left). A host model of that split, with bf16 subnormals flushed to zero as the matrix
+    instructions may do: it loses nothing for magnitudes in [2^-100, 2^127), which is the domain the header documents,
+    and it does lose bits once the third term falls below the smallest normal bf16 (magnitudes near 2^-112 and below)."""
+    import numpy as np
+
+    def bf16_flush(x):
+        x = x.astype(np.float32)
+        b = x.view(np.uint32).astype(np.uint64)
+        r = ((b + 0x7FFF + ((b >> 16) & 1)) & 0xFFFF0000).astype(np.uint32).view(np.float32)
+        return np.where(np.abs(r) < np.float32(2.0 ** -126), np.float32(0), r)
+
+    def split_error(x):
+        x1 = bf16_flush(x)
+        r1 = (x - x1).astype(np.float32)
+        x2 = bf16_flush(r1)
+        r2 = (r1 - x2).astype(np.float32)
+        x3 = bf16_flush(r2)
+        return np.abs(x.astype(np.float64) - (x1.astype(np.float64) + x2.astype(np.float64) + x3.astype(np.float64))) / np.abs(x)
+
+    r = np.random.default_rng(0)
+    mant = (1.0 + r.random(200000)).astype(np.float32) * np.where(r.random(200000) < 0.5, -1, 1).astype(np.float32)
+    for e in (-100, -60, 0, 60, 126):
+        x = (mant * np.float32(2.0 ** e)).astype(np.float32)
+        assert split_error(x).max() == 0.0, e
+    assert split_error((mant * np.float32(2.0 ** -114)).astype(np.float32)).max() > 2.0 ** -20
