@@ -375,9 +375,12 @@ fg_status_t fg_gather_aggregate_gcn(const int32_t* row_start_dev, const int32_t*
  *   W [2*d_in x d_out] row-major, w_dtype F32 or BF16 (bf16 MFMA, fp32 accumulate).
  *   F32: every product of two fp32 values is formed exactly enough for the 1e-5 bar of the path: either by the fp32
  *   matrix instructions, or (the default where the shape allows) from an exact three-way bf16 split of both factors,
- *   six partial products on the bf16 matrix instructions (the dropped ones are below 2^-26 of the product); sums are
- *   carried in fp32 over 32 k values and in fp64 across them. Inputs are expected finite and below 2^127 in
- *   magnitude (the split of a larger value overflows to infinity).
+ *   six partial products on the bf16 matrix instructions (the dropped ones are below 2^-26 of the product). The
+ *   leading partial product has an fp32 running sum of its own, the five small ones share a second one (the roundings
+ *   of a running sum are what limits it, and the small products' are 2^-8 of the leading one's); the two are added in
+ *   fp64 with the bias and rounded once. Input domain of that kernel: finite values below 2^127 in magnitude (the
+ *   split of a larger value overflows to infinity); a nonzero value below 2^-100 may lose its third bf16 term to
+ *   underflow, i.e. keeps 16 instead of 24 significant bits (harmless next to larger values of the same row).
  *   bias float[d_out] (device); h_out rows of out_dtype (F32 or BF16) written at position rows[k]
  *   d_in must be a multiple of 4 (8 for 16-bit inputs), d_out a multiple of 4.
  */
@@ -559,7 +562,7 @@ fg_status_t fg_cache_fetch_all(const fg_cache_t* cache, int32_t n_layers, const 
 /*
  * ---- Backward pass as far as the embedding gradients (Algorithm 1: loss, loss.backward(); Section 4.1.1) ----
  * The norms of dL/dh^(l) are the gradient criterion of the cache: fg_row_norms of what fg_layer_backward produces
- * is the gnorm_dev of fg_cache_update. fp32 throughout; sums in fp64.
+ * is the gnorm_dev of fg_cache_update. Gradients are fp32 throughout; sums in fp64.
  *
  * fg_softmax_xent_grad: dh[i, c] = (softmax(h[i, :])[c] - [c == labels[i]]) / n, the gradient of the mean softmax
  * cross-entropy over the n seed rows (the paper trains node classifiers and does not fix the loss further).
@@ -597,6 +600,36 @@ fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride, const floa
                               int64_t dh_src_stride, float* norms_src_dev, void* ws_dev, size_t ws_bytes, void* stream);
 
 /*
+ * The same for a GCN layer in the form of fg_aggregate_gcn + fg_linear (Section 7.5: the method carries over to other
+ * layer types; m_r = (h_r + sum of the sampled neighbours' rows) / (deg(r) + 1), one weight matrix W [d_in x d_out]):
+ *   dz as above,  dm[k, :] = dz[k, :] . W^T,
+ *   dh_src[j, :] = [j = rows[k] for some k] dm[k, :] / (deg(j) + 1) + sum over the rows r = rows[k] that sampled j of dm[k, :] / (deg(r) + 1)
+ * Arguments as for fg_layer_backward; d_in a multiple of 4, d_out of 8.
+ */
+size_t fg_layer_backward_gcn_workspace_bytes(int32_t n, int64_t max_rows, int32_t d_in, int32_t d_out);
+fg_status_t fg_layer_backward_gcn(const float* dh_dev, int64_t dh_stride, const float* h_dev, int64_t h_stride, int32_t n,
+                                  const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows, const uint8_t* live_dev,
+                                  const uint8_t* hit_dev, const int32_t* row_start_dev, const int32_t* row_end_dev,
+                                  const int32_t* t_start_dev, const int32_t* t_end_dev, const int32_t* t_row_dev, int64_t nnz,
+                                  int32_t n_src, int32_t d_in, int32_t d_out, const float* W, float* dh_src_dev,
+                                  int64_t dh_src_stride, float* norms_src_dev, void* ws_dev, size_t ws_bytes, void* stream);
+/*
+ * fg_layer_backward for the mixed-precision setting of Section 7.4's largest runs (embeddings and weights in bf16). The
+ * paper does not say where the backward pass rounds; the reading taken mirrors the forward product: both operands of
+ * dz . W^T are bf16 (dz rounded to nearest even after the mask, W as stored), products and sums in fp32, and the gradients
+ * themselves (dh, dh_src, the norms) stay fp32.
+ *   h_dev, h_stride   H(l) by position in bf16 (NULL = no activation);  W  bf16 [2*d_in x d_out], 16-byte aligned
+ *   d_in a multiple of 8, d_out of 16; everything else as for fg_layer_backward.
+ */
+size_t fg_layer_backward_bf16_workspace_bytes(int32_t n, int64_t max_rows, int32_t d_in, int32_t d_out);
+fg_status_t fg_layer_backward_bf16(const float* dh_dev, int64_t dh_stride, const void* h_dev, int64_t h_stride, int32_t n,
+                                   const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows, const uint8_t* live_dev,
+                                   const uint8_t* hit_dev, const int32_t* row_start_dev, const int32_t* row_end_dev,
+                                   const int32_t* t_start_dev, const int32_t* t_end_dev, const int32_t* t_row_dev, int64_t nnz,
+                                   int32_t n_src, int32_t d_in, int32_t d_out, const void* W, float* dh_src_dev,
+                                   int64_t dh_src_stride, float* norms_src_dev, void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
  * Gradient with respect to the weights of one GraphSAGE-mean layer, over the computed rows (dz as in fg_layer_backward):
  *   dw[a, c] = sum_k x[k, a] * dz[k, c],  x[k, :] = [h_src[rows[k], :] ‖ agg[k, :]]   ([2*d_in x d_out], the layout of W)
  *   db[c]    = sum_k dz[k, c]                                                          (db_dev may be NULL)
@@ -611,6 +644,21 @@ fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t n_src, int
                                       int64_t h_stride, int32_t n, const int32_t* rows_dev, const int64_t* n_rows_dev,
                                       int64_t max_rows, int32_t d_in, int32_t d_out, float* dw_dev, float* db_dev,
                                       void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * For a GCN layer the same call serves: its input rows are the propagated rows m_r, which fg_aggregate_gcn leaves as a
+ * by-position first half and a list-order second half; give those as h_src and agg with d_in = half the layer's input
+ * width and dw comes out as [d_in x d_out], the layout of the layer's W.
+ *
+ * fg_layer_backward_weights_bf16: the mixed-precision setting. agg and h are bf16, h_src is fp32, fp16 or bf16 (src_dtype;
+ * rounded to bf16 as the forward product rounds it); dz is rounded to bf16 before it enters x^T dz, the bias gradient
+ * sums the unrounded dz; products, sums and results as above. d_in and d_out multiples of 8. Same workspace size.
+ */
+fg_status_t fg_layer_backward_weights_bf16(const void* h_src_dev, int32_t n_src, int64_t src_stride, fg_dtype_t src_dtype,
+                                           const void* agg_dev, int64_t agg_stride, const float* dh_dev, int64_t dh_stride,
+                                           const void* h_dev, int64_t h_stride, int32_t n, const int32_t* rows_dev,
+                                           const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out,
+                                           float* dw_dev, float* db_dev, void* ws_dev, size_t ws_bytes, void* stream);
 
 #ifdef __cplusplus
 }

@@ -70,6 +70,14 @@ SIGNATURES = {
     "fg_layer_backward_weights": (_i32, [_p, _i32, _i64, _p, _i64, _p, _i64, _p, _i64, _i32, _p, _p, _i64, _i32, _i32, _p, _p, _p, _sz, _p]),
     "fg_layer_backward": (_i32, [_p, _i64, _p, _i64, _i32, _p, _p, _i64, _p, _p, _p, _p, _p, _p, _p, _i64, _i32, _i32, _i32, _p, _p,
                                  _i64, _p, _p, _sz, _p]),
+    "fg_layer_backward_gcn_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32]),
+    "fg_layer_backward_gcn": (_i32, [_p, _i64, _p, _i64, _i32, _p, _p, _i64, _p, _p, _p, _p, _p, _p, _p, _i64, _i32, _i32, _i32, _p, _p,
+                                     _i64, _p, _p, _sz, _p]),
+    "fg_layer_backward_bf16_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32]),
+    "fg_layer_backward_bf16": (_i32, [_p, _i64, _p, _i64, _i32, _p, _p, _i64, _p, _p, _p, _p, _p, _p, _p, _i64, _i32, _i32, _i32, _p, _p,
+                                      _i64, _p, _p, _sz, _p]),
+    "fg_layer_backward_weights_bf16": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _i64, _p, _i64, _i32, _p, _p, _i64, _i32, _i32, _p, _p,
+                                              _p, _sz, _p]),
 }
 
 
@@ -333,15 +341,28 @@ def fg_row_norms(x, x_stride, n, d, norms, stream=None):
     _check(_lib.fg_row_norms(ptr(x), x_stride, n, d, ptr(norms), stream))
 
 
-def fg_layer_backward_workspace_bytes(n, max_rows, d_in, d_out):
-    return _lib.fg_layer_backward_workspace_bytes(n, max_rows, d_in, d_out)
+LAYER_BACKWARD_KINDS = {"sage": "fg_layer_backward", "gcn": "fg_layer_backward_gcn", "bf16": "fg_layer_backward_bf16"}
+
+
+def fg_layer_backward_workspace_bytes(n, max_rows, d_in, d_out, kind="sage"):
+    return getattr(_lib, LAYER_BACKWARD_KINDS[kind] + "_workspace_bytes")(n, max_rows, d_in, d_out)
 
 
 def fg_layer_backward(dh, dh_stride, h, h_stride, n, rows, n_rows, max_rows, live, hit, row_start, row_end, t_start, t_end, t_row,
-                      nnz, n_src, d_in, d_out, W, dh_src, dh_src_stride, norms_src, ws, ws_bytes, stream=None):
-    _check(_lib.fg_layer_backward(ptr(dh), dh_stride, ptr(h), h_stride, n, ptr(rows), ptr(n_rows), max_rows, ptr(live), ptr(hit),
-                                  ptr(row_start), ptr(row_end), ptr(t_start), ptr(t_end), ptr(t_row), nnz, n_src, d_in, d_out,
-                                  ptr(W), ptr(dh_src), dh_src_stride, ptr(norms_src), ptr(ws), ws_bytes, stream))
+                      nnz, n_src, d_in, d_out, W, dh_src, dh_src_stride, norms_src, ws, ws_bytes, stream=None, kind="sage"):
+    """kind: "sage" = fg_layer_backward, "gcn" = fg_layer_backward_gcn, "bf16" = fg_layer_backward_bf16 (same argument lists)."""
+    fn = getattr(_lib, LAYER_BACKWARD_KINDS[kind])
+    _check(fn(ptr(dh), dh_stride, ptr(h), h_stride, n, ptr(rows), ptr(n_rows), max_rows, ptr(live), ptr(hit),
+              ptr(row_start), ptr(row_end), ptr(t_start), ptr(t_end), ptr(t_row), nnz, n_src, d_in, d_out,
+              ptr(W), ptr(dh_src), dh_src_stride, ptr(norms_src), ptr(ws), ws_bytes, stream))
+
+
+def fg_layer_backward_gcn(*args, **kw):
+    fg_layer_backward(*args, kind="gcn", **kw)
+
+
+def fg_layer_backward_bf16(*args, **kw):
+    fg_layer_backward(*args, kind="bf16", **kw)
 
 
 def fg_layer_backward_weights_workspace_bytes(max_rows, d_in, d_out):
@@ -352,6 +373,13 @@ def fg_layer_backward_weights(h_src, n_src, src_stride, agg, agg_stride, dh, dh_
                               d_out, dw, db, ws, ws_bytes, stream=None):
     _check(_lib.fg_layer_backward_weights(ptr(h_src), n_src, src_stride, ptr(agg), agg_stride, ptr(dh), dh_stride, ptr(h), h_stride, n,
                                           ptr(rows), ptr(n_rows), max_rows, d_in, d_out, ptr(dw), ptr(db), ptr(ws), ws_bytes, stream))
+
+
+def fg_layer_backward_weights_bf16(h_src, n_src, src_stride, src_dtype, agg, agg_stride, dh, dh_stride, h, h_stride, n, rows, n_rows,
+                                   max_rows, d_in, d_out, dw, db, ws, ws_bytes, stream=None):
+    _check(_lib.fg_layer_backward_weights_bf16(ptr(h_src), n_src, src_stride, src_dtype, ptr(agg), agg_stride, ptr(dh), dh_stride, ptr(h),
+                                               h_stride, n, ptr(rows), ptr(n_rows), max_rows, d_in, d_out, ptr(dw), ptr(db), ptr(ws),
+                                               ws_bytes, stream))
 
 
 def _struct_array(struct, specs):

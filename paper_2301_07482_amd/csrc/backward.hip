@@ -11,10 +11,12 @@
 // Only rows that were computed (V_normal) pass gradient down; a fetched row receives its gradient and stops there.
 // All of it is small next to the forward pass: the layer below the lowest cached one needs no input gradient.
 #include "common.h"
+#include <hip/hip_fp16.h>
 
 namespace {
 
 constexpr int BW_THREADS = 256;
+typedef float f32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ double wave_sum(double v) {
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
@@ -71,14 +73,23 @@ __global__ __launch_bounds__(BW_THREADS) void row_norms_kernel(const char* __res
     }
 }
 
+// round an fp32 value to bf16 bits, nearest even (finite inputs)
+__device__ __forceinline__ unsigned short bw_bf16_bits(float f) {
+    const unsigned int b = __float_as_uint(f);
+    return (unsigned short)((b + 0x7FFFu + ((b >> 16) & 1u)) >> 16);
+}
+__device__ __forceinline__ float bw_bf16_value(unsigned short b) { return __uint_as_float((unsigned int)b << 16); }
+
 // dz = dh[r, :] * (h[r, :] > 0) for r = rows[k]. The GEMM that follows takes its first K/2 input columns from a
 // matrix indexed by position and the other K/2 from one indexed by list order, so dz is written in that form:
 // columns [0, half) to dz_pos[r, :], columns [half, d) to dz_cmp[k, :].
+// BF16: the layer's output h is bf16 and dz is rounded to bf16 (the operand type of the bf16 matrix product that follows).
+template <bool BF16>
 __global__ __launch_bounds__(BW_THREADS) void relu_backward_kernel(const char* __restrict__ dh, int64_t dh_stride,
                                                                    const char* __restrict__ h, int64_t h_stride, int n,
                                                                    const int32_t* __restrict__ rows,
                                                                    const int64_t* __restrict__ n_rows_dev, int64_t max_rows,
-                                                                   int d, float* __restrict__ dz_pos, float* __restrict__ dz_cmp) {
+                                                                   int d, void* __restrict__ dz_pos_v, void* __restrict__ dz_cmp_v) {
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
     if (n_rows > max_rows) n_rows = max_rows;
     const int half = d >> 1;
@@ -88,22 +99,33 @@ __global__ __launch_bounds__(BW_THREADS) void relu_backward_kernel(const char* _
         const int32_t r = rows ? rows[k] : (int32_t)k;
         if (r < 0 || r >= n) continue;
         const float* g = (const float*)(dh + (int64_t)r * dh_stride);
-        const float* a = h ? (const float*)(h + (int64_t)r * h_stride) : nullptr;
+        const char* a = h ? h + (int64_t)r * h_stride : nullptr;
         for (int c = lane; c < d; c += 64) {
             float v = g[c];
-            if (a && !(a[c] > 0.f)) v = 0.f;
-            if (c < half)
-                dz_pos[(int64_t)r * half + c] = v;
-            else
-                dz_cmp[k * half + (c - half)] = v;
+            if (a) {
+                const float act = BF16 ? bw_bf16_value(((const unsigned short*)a)[c]) : ((const float*)a)[c];
+                if (!(act > 0.f)) v = 0.f;
+            }
+            if constexpr (BF16) {
+                const unsigned short b = bw_bf16_bits(v);
+                if (c < half)
+                    ((unsigned short*)dz_pos_v)[(int64_t)r * half + c] = b;
+                else
+                    ((unsigned short*)dz_cmp_v)[k * half + (c - half)] = b;
+            } else {
+                if (c < half)
+                    ((float*)dz_pos_v)[(int64_t)r * half + c] = v;
+                else
+                    ((float*)dz_cmp_v)[k * half + (c - half)] = v;
+            }
         }
     }
 }
 
 // wt[c, a] = w[a, c]; w is [rows x cols]
-__global__ __launch_bounds__(BW_THREADS) void transpose_kernel(const float* __restrict__ w, int rows, int cols,
-                                                               float* __restrict__ wt) {
-    __shared__ float tile[32][33];
+template <typename T>
+__global__ __launch_bounds__(BW_THREADS) void transpose_kernel(const T* __restrict__ w, int rows, int cols, T* __restrict__ wt) {
+    __shared__ T tile[32][33];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
     const int c0 = blockIdx.x * 32, a0 = blockIdx.y * 32;
     for (int i = ty; i < 32; i += 8)
@@ -113,13 +135,15 @@ __global__ __launch_bounds__(BW_THREADS) void transpose_kernel(const float* __re
         if (c0 + i < cols && a0 + tx < rows) wt[(int64_t)(c0 + i) * rows + a0 + tx] = tile[tx][i];
 }
 
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-
 // Transposed mean aggregation. A group of 2^g lanes owns source position j and 16 bytes of the row per lane:
 //   out[j, :] = [j is a computed row] dx[j, 0:d_in]  +  sum over t in [t_start[j], t_end[j]) with r = t_row[t] computed:
 //               dx[r, d_in:2*d_in] / deg(r),   deg(r) = row_end[r] - row_start[r] of the pruned block
 // A row that was not computed has an empty range in the pruned block (deg = 0) and is skipped by that test; such rows of
 // dx were never written. Every position j < n_src is written (zeros where nothing arrives).
+// GCN: the transpose of the propagation (h_r + sum of the neighbours) / (deg + 1): dx has d_in columns, and
+//   out[j, :] = [j computed] dx[j, :] / (deg(j) + 1)  +  sum over the computed rows r that sampled j of dx[r, :] / (deg(r) + 1)
+// (a row found in a transposed list sampled at least one neighbour, so it is computed exactly when deg(r) > 0).
+template <bool GCN>
 __global__ __launch_bounds__(BW_THREADS) void aggregate_backward_kernel(
     const char* __restrict__ dx, int n, int d_in, const uint8_t* __restrict__ live, const uint8_t* __restrict__ hit,
     const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ t_start,
@@ -129,17 +153,23 @@ __global__ __launch_bounds__(BW_THREADS) void aggregate_backward_kernel(
     const int lane = threadIdx.x & (lanes - 1);
     const int gpb = BW_THREADS >> lanes_log2;
     const int pieces = d_in >> 2;
-    const int64_t dx_stride = (int64_t)2 * d_in * 4;
+    const int64_t dx_stride = (int64_t)(GCN ? 1 : 2) * d_in * 4;
+    const int nb_col = GCN ? 0 : d_in;      // first column of the neighbours' share in a row of dx
     for (int64_t j = (int64_t)blockIdx.x * gpb + (threadIdx.x >> lanes_log2); j < n_src; j += (int64_t)gridDim.x * gpb) {
         int32_t s0 = t_start[j], e0 = t_end[j];
         if (s0 < 0 || e0 < s0 || (int64_t)e0 > nnz) s0 = e0 = 0;
         const bool own = j < n && (live ? live[j] != 0 : true) && (hit ? hit[j] == 0 : true);
+        double own_w = 1.0;
+        if (GCN && own) {
+            const int32_t deg = row_end[j] - row_start[j];
+            own_w = 1.0 / (double)((deg > 0 ? deg : 0) + 1);
+        }
         double ss = 0.0;  // this lane's share of the row's sum of squares (of the fp32 values written)
         for (int piece = lane; piece < pieces; piece += lanes) {
             double acc[4] = {0.0, 0.0, 0.0, 0.0};
             if (own) {
                 const f32x4 v = *(const f32x4*)(dx + j * dx_stride + (int64_t)piece * 16);
-                acc[0] = v.x; acc[1] = v.y; acc[2] = v.z; acc[3] = v.w;
+                acc[0] = (double)v.x * own_w; acc[1] = (double)v.y * own_w; acc[2] = (double)v.z * own_w; acc[3] = (double)v.w * own_w;
             }
             for (int t = s0; t < e0; t += 4) {
                 f32x4 v[4];
@@ -153,8 +183,8 @@ __global__ __launch_bounds__(BW_THREADS) void aggregate_backward_kernel(
                         if (r >= 0 && r < n) {
                             const int32_t deg = row_end[r] - row_start[r];
                             if (deg > 0) {
-                                w[u] = 1.0 / (double)deg;
-                                v[u] = *(const f32x4*)(dx + (int64_t)r * dx_stride + (int64_t)(d_in + 4 * piece) * 4);
+                                w[u] = 1.0 / (double)(GCN ? deg + 1 : deg);
+                                v[u] = *(const f32x4*)(dx + (int64_t)r * dx_stride + (int64_t)(nb_col + 4 * piece) * 4);
                             }
                         }
                     }
@@ -181,18 +211,24 @@ __global__ __launch_bounds__(BW_THREADS) void aggregate_backward_kernel(
 struct BwWs {
     size_t dz_pos, dz_cmp, wt, dx, total;
 };
-BwWs bw_layout(int64_t n, int64_t max_rows, int64_t d_in, int64_t d_out) {
+// esz: bytes per element of dz and of the transposed weights (4, or 2 in the bf16 setting); cols: columns of dx
+BwWs bw_layout(int64_t n, int64_t max_rows, int64_t cols, int64_t d_out, int64_t esz) {
     BwWs w;
-    const size_t half = (size_t)(d_out / 2) * 4;
+    const size_t half = (size_t)(d_out / 2) * esz;
     w.dz_pos = 0;
     w.dz_cmp = fg_align_up((size_t)(n > 0 ? n : 1) * half, 256);
     w.wt = w.dz_cmp + fg_align_up((size_t)(max_rows > 0 ? max_rows : 1) * half, 256);
-    w.dx = w.wt + fg_align_up((size_t)2 * d_in * d_out * 4, 256);
-    w.total = w.dx + fg_align_up((size_t)(n > 0 ? n : 1) * 2 * d_in * 4, 256);
+    w.dx = w.wt + fg_align_up((size_t)cols * d_out * esz, 256);
+    w.total = w.dx + fg_align_up((size_t)(n > 0 ? n : 1) * cols * 4, 256);
     return w;
 }
 
 }  // namespace
+
+fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype, const void* agg,
+                                  int64_t agg_stride, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                                  int32_t d_in, int32_t d_out, const void* W, const float* bias, int32_t relu, void* h_out,
+                                  int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, hipStream_t st);
 
 extern "C" fg_status_t fg_softmax_xent_grad(const float* h_dev, int64_t h_stride, const int32_t* labels_dev, int32_t n, int32_t d,
                                             float* dh_dev, int64_t dh_stride, void* stream) {
@@ -226,57 +262,89 @@ extern "C" fg_status_t fg_row_norms(const float* x_dev, int64_t x_stride, int32_
     return FG_OK;
 }
 
-extern "C" size_t fg_layer_backward_workspace_bytes(int32_t n, int64_t max_rows, int32_t d_in, int32_t d_out) {
+// kind of layer a backward call is for
+enum BwKind { BW_SAGE_F32 = 0, BW_GCN_F32 = 1, BW_SAGE_BF16 = 2 };
+
+static size_t layer_backward_ws(int kind, int32_t n, int64_t max_rows, int32_t d_in, int32_t d_out) {
     if (n < 0 || max_rows < 0 || d_in <= 0 || d_out <= 0) return 0;
-    return bw_layout(n, max_rows, d_in, d_out).total;
+    return bw_layout(n, max_rows, kind == BW_GCN_F32 ? d_in : 2 * (int64_t)d_in, d_out, kind == BW_SAGE_BF16 ? 2 : 4).total;
 }
 
-extern "C" fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride, const float* h_dev, int64_t h_stride, int32_t n,
-                                         const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
-                                         const uint8_t* live_dev, const uint8_t* hit_dev, const int32_t* row_start_dev,
-                                         const int32_t* row_end_dev, const int32_t* t_start_dev, const int32_t* t_end_dev,
-                                         const int32_t* t_row_dev, int64_t nnz, int32_t n_src, int32_t d_in, int32_t d_out,
-                                         const float* W, float* dh_src_dev, int64_t dh_src_stride, float* norms_src_dev,
+extern "C" size_t fg_layer_backward_workspace_bytes(int32_t n, int64_t max_rows, int32_t d_in, int32_t d_out) {
+    return layer_backward_ws(BW_SAGE_F32, n, max_rows, d_in, d_out);
+}
+extern "C" size_t fg_layer_backward_gcn_workspace_bytes(int32_t n, int64_t max_rows, int32_t d_in, int32_t d_out) {
+    return layer_backward_ws(BW_GCN_F32, n, max_rows, d_in, d_out);
+}
+extern "C" size_t fg_layer_backward_bf16_workspace_bytes(int32_t n, int64_t max_rows, int32_t d_in, int32_t d_out) {
+    return layer_backward_ws(BW_SAGE_BF16, n, max_rows, d_in, d_out);
+}
+
+// The three layer kinds share the sequence: mask (+ rounding), transposed weights, dz . W^T on the forward GEMM path, transposed
+// aggregation with the row norms.
+static fg_status_t layer_backward_launch(const char* who, int kind, const float* dh_dev, int64_t dh_stride, const void* h_dev,
+                                         int64_t h_stride, int32_t n, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                         int64_t max_rows, const uint8_t* live_dev, const uint8_t* hit_dev,
+                                         const int32_t* row_start_dev, const int32_t* row_end_dev, const int32_t* t_start_dev,
+                                         const int32_t* t_end_dev, const int32_t* t_row_dev, int64_t nnz, int32_t n_src, int32_t d_in,
+                                         int32_t d_out, const void* W, float* dh_src_dev, int64_t dh_src_stride, float* norms_src_dev,
                                          void* ws_dev, size_t ws_bytes, void* stream) {
-    const char* who = "fg_layer_backward";
+    const bool gcn = kind == BW_GCN_F32, b16 = kind == BW_SAGE_BF16;
+    const int esz = b16 ? 2 : 4;
     if (n < 0 || max_rows < 0 || n_src < 0 || nnz < 0 || d_in <= 0 || d_out <= 0)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (n %d, max_rows %lld, n_src %d, nnz %lld, d_in %d, d_out %d)", who, n, (long long)max_rows,
                 n_src, (long long)nnz, d_in, d_out);
     if (n_src < n) FG_FAIL(FG_ERR_SHAPE, "%s: the layer below (%d positions) must contain this layer's %d", who, n_src, n);
     if (max_rows > n) FG_FAIL(FG_ERR_SHAPE, "%s: max_rows = %lld exceeds the layer's %d positions", who, (long long)max_rows, n);
-    if (d_in % 4 || d_out % 8) FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d must be a multiple of 4 and d_out = %d of 8", who, d_in, d_out);
+    if (d_in % (b16 ? 8 : 4) || d_out % (b16 ? 16 : 8))
+        FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d must be a multiple of %d and d_out = %d of %d", who, d_in, b16 ? 8 : 4, d_out, b16 ? 16 : 8);
     if (n_src > 0 && (!dh_src_dev || !t_start_dev || !t_end_dev || (nnz > 0 && !t_row_dev))) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
     if (n > 0 && (!dh_dev || !row_start_dev || !row_end_dev || !W)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
-    if (dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * 4) || dh_src_stride < (int64_t)d_in * 4)
+    if (dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * esz) || dh_src_stride < (int64_t)d_in * 4)
         FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
-    if (((uintptr_t)dh_dev | (uintptr_t)h_dev | (uintptr_t)dh_stride | (uintptr_t)h_stride | (uintptr_t)W) & 3)
-        FG_FAIL(FG_ERR_INVALID_ARG, "%s: dh, h, W and their strides must be 4-byte aligned", who);
+    if (((uintptr_t)dh_dev | (uintptr_t)dh_stride) & 3 || ((uintptr_t)h_dev | (uintptr_t)h_stride) & (uintptr_t)(esz - 1))
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: dh, h and their strides must be aligned to their element size", who);
+    if ((uintptr_t)W & (b16 ? 15 : 3)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: W must be %d-byte aligned", who, b16 ? 16 : 4);
     if ((uintptr_t)norms_src_dev & 3) FG_FAIL(FG_ERR_INVALID_ARG, "%s: norms_src_dev must be 4-byte aligned", who);
     if (((uintptr_t)dh_src_dev | (uintptr_t)dh_src_stride | (uintptr_t)ws_dev) & 15)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: dh_src_dev, its stride and the workspace must be 16-byte aligned", who);
-    const BwWs L = bw_layout(n, max_rows, d_in, d_out);
+    const int cols = gcn ? d_in : 2 * d_in;       // columns of dz . W^T
+    const BwWs L = bw_layout(n, max_rows, cols, d_out, esz);
     if (!ws_dev || ws_bytes < L.total) FG_FAIL(FG_ERR_SHAPE, "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes, L.total);
     fg_clear_error();
     hipStream_t st = (hipStream_t)stream;
     char* ws = (char*)ws_dev;
-    float* dz_pos = (float*)(ws + L.dz_pos);
-    float* dz_cmp = (float*)(ws + L.dz_cmp);
-    float* wt = (float*)(ws + L.wt);
+    void* dz_pos = ws + L.dz_pos;
+    void* dz_cmp = ws + L.dz_cmp;
+    void* wt = ws + L.wt;
     float* dx = (float*)(ws + L.dx);
     const int half = d_out / 2;
     if (n > 0 && max_rows > 0) {
         int64_t blocks = fg_ceil_div(max_rows, BW_THREADS / 64);
         if (blocks > 4096) blocks = 4096;
-        hipLaunchKernelGGL(relu_backward_kernel, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dh_dev, dh_stride,
-                           (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_out, dz_pos, dz_cmp);
-        FG_LAUNCH_CHECK("relu_backward_kernel");
-        hipLaunchKernelGGL(transpose_kernel, dim3((unsigned)fg_ceil_div(d_out, 32), (unsigned)fg_ceil_div(2 * d_in, 32)), dim3(BW_THREADS), 0,
-                           st, W, 2 * d_in, d_out, wt);
-        FG_LAUNCH_CHECK("transpose_kernel");
-        // dx[r, :] = [dz_pos[r, :] ‖ dz_cmp[k, :]] . W^T for r = rows[k]: the forward GEMM with K = d_out, N = 2 * d_in
-        fg_status_t rc = fg_linear(dz_pos, n, (int64_t)half * 4, FG_F32, dz_cmp, (int64_t)half * 4, rows_dev, n_rows_dev, max_rows, half,
-                                   2 * d_in, wt, FG_F32, nullptr, 0, dx, n, (int64_t)2 * d_in * 4, FG_F32, stream);
-        if (rc != FG_OK) return rc;
+        const dim3 tgrid((unsigned)fg_ceil_div(d_out, 32), (unsigned)fg_ceil_div(cols, 32));
+        if (b16) {
+            hipLaunchKernelGGL(relu_backward_kernel<true>, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dh_dev, dh_stride,
+                               (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_out, dz_pos, dz_cmp);
+            FG_LAUNCH_CHECK("relu_backward_kernel");
+            hipLaunchKernelGGL(transpose_kernel<unsigned short>, tgrid, dim3(BW_THREADS), 0, st, (const unsigned short*)W, cols, d_out,
+                               (unsigned short*)wt);
+            FG_LAUNCH_CHECK("transpose_kernel");
+            // dx[r, :] = [dz_pos[r, :] ‖ dz_cmp[k, :]] . W^T, bf16 operands, fp32 sums and result
+            fg_status_t rc = fg_launch_linear_bf16(dz_pos, n, (int64_t)half * 2, FG_BF16, dz_cmp, (int64_t)half * 2, rows_dev, n_rows_dev,
+                                                   max_rows, half, cols, wt, nullptr, 0, dx, n, (int64_t)cols * 4, FG_F32, st);
+            if (rc != FG_OK) return rc;
+        } else {
+            hipLaunchKernelGGL(relu_backward_kernel<false>, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dh_dev, dh_stride,
+                               (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_out, dz_pos, dz_cmp);
+            FG_LAUNCH_CHECK("relu_backward_kernel");
+            hipLaunchKernelGGL(transpose_kernel<float>, tgrid, dim3(BW_THREADS), 0, st, (const float*)W, cols, d_out, (float*)wt);
+            FG_LAUNCH_CHECK("transpose_kernel");
+            // dx[r, :] = [dz_pos[r, :] ‖ dz_cmp[k, :]] . W^T for r = rows[k]: the forward GEMM with K = d_out, N = cols
+            fg_status_t rc = fg_linear(dz_pos, n, (int64_t)half * 4, FG_F32, dz_cmp, (int64_t)half * 4, rows_dev, n_rows_dev, max_rows, half,
+                                       cols, wt, FG_F32, nullptr, 0, dx, n, (int64_t)cols * 4, FG_F32, stream);
+            if (rc != FG_OK) return rc;
+        }
     }
     if (n_src == 0) return FG_OK;
     const int pieces = d_in / 4;
@@ -285,12 +353,52 @@ extern "C" fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride,
     const int gpb = BW_THREADS >> lg;
     int64_t blocks = fg_ceil_div(n_src, gpb);
     if (blocks > 256 * 16) blocks = 256 * 16;
-    hipLaunchKernelGGL(aggregate_backward_kernel, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dx, n, d_in, live_dev,
-                       hit_dev, row_start_dev, row_end_dev, t_start_dev, t_end_dev, t_row_dev, nnz, n_src, (char*)dh_src_dev, dh_src_stride, lg,
-                       norms_src_dev);
+    if (gcn)
+        hipLaunchKernelGGL(aggregate_backward_kernel<true>, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dx, n, d_in, live_dev,
+                           hit_dev, row_start_dev, row_end_dev, t_start_dev, t_end_dev, t_row_dev, nnz, n_src, (char*)dh_src_dev, dh_src_stride,
+                           lg, norms_src_dev);
+    else
+        hipLaunchKernelGGL(aggregate_backward_kernel<false>, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dx, n, d_in, live_dev,
+                           hit_dev, row_start_dev, row_end_dev, t_start_dev, t_end_dev, t_row_dev, nnz, n_src, (char*)dh_src_dev, dh_src_stride,
+                           lg, norms_src_dev);
     FG_LAUNCH_CHECK("aggregate_backward_kernel");
     return FG_OK;
 }
+
+#define FG_LAYER_BACKWARD_ARGS                                                                                                      \
+    dh_dev, dh_stride, h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, live_dev, hit_dev, row_start_dev, row_end_dev, t_start_dev, \
+        t_end_dev, t_row_dev, nnz, n_src, d_in, d_out, W, dh_src_dev, dh_src_stride, norms_src_dev, ws_dev, ws_bytes, stream
+
+extern "C" fg_status_t fg_layer_backward(const float* dh_dev, int64_t dh_stride, const float* h_dev, int64_t h_stride, int32_t n,
+                                         const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                                         const uint8_t* live_dev, const uint8_t* hit_dev, const int32_t* row_start_dev,
+                                         const int32_t* row_end_dev, const int32_t* t_start_dev, const int32_t* t_end_dev,
+                                         const int32_t* t_row_dev, int64_t nnz, int32_t n_src, int32_t d_in, int32_t d_out,
+                                         const float* W, float* dh_src_dev, int64_t dh_src_stride, float* norms_src_dev,
+                                         void* ws_dev, size_t ws_bytes, void* stream) {
+    return layer_backward_launch("fg_layer_backward", BW_SAGE_F32, FG_LAYER_BACKWARD_ARGS);
+}
+
+extern "C" fg_status_t fg_layer_backward_gcn(const float* dh_dev, int64_t dh_stride, const float* h_dev, int64_t h_stride, int32_t n,
+                                             const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                                             const uint8_t* live_dev, const uint8_t* hit_dev, const int32_t* row_start_dev,
+                                             const int32_t* row_end_dev, const int32_t* t_start_dev, const int32_t* t_end_dev,
+                                             const int32_t* t_row_dev, int64_t nnz, int32_t n_src, int32_t d_in, int32_t d_out,
+                                             const float* W, float* dh_src_dev, int64_t dh_src_stride, float* norms_src_dev,
+                                             void* ws_dev, size_t ws_bytes, void* stream) {
+    return layer_backward_launch("fg_layer_backward_gcn", BW_GCN_F32, FG_LAYER_BACKWARD_ARGS);
+}
+
+extern "C" fg_status_t fg_layer_backward_bf16(const float* dh_dev, int64_t dh_stride, const void* h_dev, int64_t h_stride, int32_t n,
+                                              const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                                              const uint8_t* live_dev, const uint8_t* hit_dev, const int32_t* row_start_dev,
+                                              const int32_t* row_end_dev, const int32_t* t_start_dev, const int32_t* t_end_dev,
+                                              const int32_t* t_row_dev, int64_t nnz, int32_t n_src, int32_t d_in, int32_t d_out,
+                                              const void* W, float* dh_src_dev, int64_t dh_src_stride, float* norms_src_dev,
+                                              void* ws_dev, size_t ws_bytes, void* stream) {
+    return layer_backward_launch("fg_layer_backward_bf16", BW_SAGE_BF16, FG_LAYER_BACKWARD_ARGS);
+}
+#undef FG_LAYER_BACKWARD_ARGS
 
 // ---- weight gradients --------------------------------------------------------------------------------------
 //
@@ -313,8 +421,12 @@ constexpr int WG_PAIRS = 3;  // pairs of rows whose loads are issued together
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
+// B16: the bf16 setting. agg and h are bf16, h_src is of type src_code (fp32 and fp16 values are rounded to bf16, as the
+// forward product rounds them), dz is rounded to bf16 before it enters the product and summed unrounded for the bias
+// gradient. The products of two bf16 values are exact in fp32, so the fp32 matrix instruction serves both settings.
+template <bool B16>
 __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
-    const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
+    const char* __restrict__ h_src, int n_src, int64_t src_stride, int src_code, const char* __restrict__ agg, int64_t agg_stride,
     const char* __restrict__ dh, int64_t dh_stride, const char* __restrict__ h, int64_t h_stride, int n,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     float* __restrict__ part_w, float* __restrict__ part_b) {
@@ -336,12 +448,14 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
 
     // This lane's columns. A wavefront's 64 rows of the result are split over its two row blocks by parity and its 128
     // columns over its four column blocks modulo 4, so that a lane's operands for all blocks are adjacent in memory:
-    // X[k][m_pair], X[k][m_pair + 1] (one 8-byte load) and dz[k][n_quad .. n_quad + 3] (16-byte loads).
+    // X[k][m_pair], X[k][m_pair + 1] (one load) and dz[k][n_quad .. n_quad + 3] (16-byte loads).
     // Row l of result block i is then row m_base + 2*l + i, column l of result block j is column n_base + 4*l + j.
     const int m_pair = m_base + 2 * l32;
     const bool a_ok = m_pair < M;              // M is even: both columns exist or neither
     const bool a_self = m_pair < d_in;         // d_in is even: a pair never straddles the two panels
     const int a_col = a_ok ? (a_self ? m_pair : m_pair - d_in) : 0;
+    const bool a_wide = !B16 || (a_self && src_code == FG_F32);   // this lane's pair of X is two fp32 values
+    const bool a_half = B16 && a_self && src_code == FG_F16;      // ... two fp16 values (otherwise two bf16 values)
     const int n_quad = n_base + 4 * l32;
     const bool b_ok = n_quad < N;              // N is a multiple of 4
     const int b_col = b_ok ? n_quad : 0;
@@ -359,12 +473,12 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
         const int64_t ks = kk < k_end ? kk : k_begin;
         return rows ? rows[ks] : (int32_t)ks;
     };
-    // One batch = WG_PAIRS pairs of rows: 11 loads per pair and lane, then 8 matrix instructions per pair. Two batches are
+    // One batch = WG_PAIRS pairs of rows: the loads of a pair, then 8 matrix instructions per pair. Two batches are
     // kept in registers: while one is multiplied the loads of the next are in flight. The row positions are fetched one
     // batch further ahead so that the row loads do not wait for them.
     struct Batch {
-        f32x2 a[WG_PAIRS];
-        f32x4 g[WG_PAIRS], o[WG_PAIRS];
+        f32x2 a[WG_PAIRS];      // B16: the raw bits of the pair (one word where the pair is two 16-bit values)
+        f32x4 g[WG_PAIRS], o[WG_PAIRS];   // B16: o holds the four bf16 outputs in its first two words
         bool ok[WG_PAIRS];
     };
     int32_t r_next[WG_PAIRS];
@@ -380,25 +494,62 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
             r_next[p] = row_of(kk + 2 * WG_PAIRS);
             B.ok[p] = in && r >= 0 && r < n && r < n_src;
             const int64_t rs = B.ok[p] ? r : 0;
-            const float* xs = (const float*)(h_src + rs * src_stride);
-            const float* xa = (const float*)(agg + ks * agg_stride);
-            B.a[p] = *(const f32x2*)((a_self ? xs : xa) + a_col);
-            const float* gr = (const float*)(dh + rs * dh_stride);
-            const float* hr = h ? (const float*)(h + rs * h_stride) : gr;
-            B.g[p] = *(const f32x4*)(gr + b_col);
-            B.o[p] = *(const f32x4*)(hr + b_col);
+            const char* xs = h_src + rs * src_stride;
+            const char* xa = agg + ks * agg_stride;
+            const char* gr = dh + rs * dh_stride;
+            if constexpr (B16) {
+                if (a_wide) {
+                    B.a[p] = *(const f32x2*)(xs + (int64_t)a_col * 4);
+                } else {
+                    B.a[p][0] = *(const float*)((a_self ? xs : xa) + (int64_t)a_col * 2);
+                    B.a[p][1] = 0.f;
+                }
+                const f32x2 o2 = *(const f32x2*)(h ? h + rs * h_stride + (int64_t)b_col * 2 : gr);
+                B.o[p][0] = o2[0];
+                B.o[p][1] = o2[1];
+            } else {
+                B.a[p] = *(const f32x2*)((a_self ? xs : xa) + (int64_t)a_col * 4);
+                B.o[p] = *(const f32x4*)((h ? h + rs * h_stride : gr) + (int64_t)b_col * 4);
+            }
+            B.g[p] = *(const f32x4*)(gr + (int64_t)b_col * 4);
         }
     };
     auto multiply_batch = [&](Batch& B) {
 #pragma unroll
         for (int p = 0; p < WG_PAIRS; ++p) {
+            if constexpr (B16) {
+                float x0, x1;
+                if (a_wide) {
+                    x0 = bw_bf16_value(bw_bf16_bits(B.a[p][0]));
+                    x1 = bw_bf16_value(bw_bf16_bits(B.a[p][1]));
+                } else {
+                    const unsigned int w = __float_as_uint(B.a[p][0]);
+                    if (a_half) {
+                        x0 = bw_bf16_value(bw_bf16_bits(__half2float(__ushort_as_half((unsigned short)(w & 0xFFFFu)))));
+                        x1 = bw_bf16_value(bw_bf16_bits(__half2float(__ushort_as_half((unsigned short)(w >> 16)))));
+                    } else {
+                        x0 = __uint_as_float(w << 16);
+                        x1 = __uint_as_float(w & 0xFFFF0000u);
+                    }
+                }
+                B.a[p][0] = x0;
+                B.a[p][1] = x1;
+            }
 #pragma unroll
             for (int i = 0; i < 2; ++i) B.a[p][i] = (B.ok[p] && a_ok) ? B.a[p][i] : 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const bool pass = B.ok[p] && b_ok && (h ? B.o[p][j] > 0.f : true);
+                float act;
+                if constexpr (B16) {
+                    const unsigned int w = __float_as_uint(B.o[p][j >> 1]);
+                    act = (j & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
+                } else {
+                    act = B.o[p][j];
+                }
+                const bool pass = B.ok[p] && b_ok && (h ? act > 0.f : true);
                 B.g[p][j] = pass ? B.g[p][j] : 0.f;
                 colsum[j] += B.g[p][j];
+                if constexpr (B16) B.g[p][j] = bw_bf16_value(bw_bf16_bits(B.g[p][j]));
             }
         }
 #pragma unroll
@@ -514,21 +665,24 @@ extern "C" size_t fg_layer_backward_weights_workspace_bytes(int64_t max_rows, in
     return wg_plan(max_rows, d_in, d_out).total;
 }
 
-extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t n_src, int64_t src_stride, const float* agg_dev,
-                                                 int64_t agg_stride, const float* dh_dev, int64_t dh_stride, const float* h_dev,
-                                                 int64_t h_stride, int32_t n, const int32_t* rows_dev, const int64_t* n_rows_dev,
-                                                 int64_t max_rows, int32_t d_in, int32_t d_out, float* dw_dev, float* db_dev,
-                                                 void* ws_dev, size_t ws_bytes, void* stream) {
-    const char* who = "fg_layer_backward_weights";
+static fg_status_t weights_backward_launch(const char* who, bool b16, const void* h_src_dev, int32_t n_src, int64_t src_stride,
+                                           fg_dtype_t src_dtype, const void* agg_dev, int64_t agg_stride, const float* dh_dev,
+                                           int64_t dh_stride, const void* h_dev, int64_t h_stride, int32_t n, const int32_t* rows_dev,
+                                           const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, float* dw_dev,
+                                           float* db_dev, void* ws_dev, size_t ws_bytes, void* stream) {
     if (n < 0 || n_src < 0 || max_rows < 0 || d_in <= 0 || d_out <= 0)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (n %d, n_src %d, max_rows %lld, d_in %d, d_out %d)", who, n, n_src, (long long)max_rows, d_in, d_out);
     if (!dw_dev) FG_FAIL(FG_ERR_INVALID_ARG, "%s: dw_dev is NULL", who);
-    if (d_out % 4) FG_FAIL(FG_ERR_SHAPE, "%s: d_out = %d must be a multiple of 4", who, d_out);
+    if (src_dtype != FG_F32 && src_dtype != FG_F16 && src_dtype != FG_BF16) FG_FAIL(FG_ERR_DTYPE, "%s: h_src must be fp32, fp16 or bf16", who);
+    if (!b16 && src_dtype != FG_F32) FG_FAIL(FG_ERR_DTYPE, "%s: h_src must be fp32", who);
+    const int64_t src_esz = src_dtype == FG_F32 ? 4 : 2, esz = b16 ? 2 : 4;
+    const int mult = b16 ? 8 : 4;     // a lane's loads stay 4-, 8- or 16-byte aligned
+    if (d_out % mult) FG_FAIL(FG_ERR_SHAPE, "%s: d_out = %d must be a multiple of %d", who, d_out, mult);
     if (((uintptr_t)dw_dev | (uintptr_t)db_dev) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: dw_dev and db_dev must be 16-byte aligned", who);
     if (max_rows > 0 && n > 0 && n_src > 0 && (!h_src_dev || !agg_dev || !dh_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
-    if (src_stride < (int64_t)d_in * 4 || agg_stride < (int64_t)d_in * 4 || dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * 4))
+    if (src_stride < (int64_t)d_in * src_esz || agg_stride < (int64_t)d_in * esz || dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * esz))
         FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
-    if (d_in % 4) FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d must be a multiple of 4", who, d_in);
+    if (d_in % mult) FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d must be a multiple of %d", who, d_in, mult);
     if (((uintptr_t)h_src_dev | (uintptr_t)agg_dev | (uintptr_t)dh_dev | (uintptr_t)h_dev | (uintptr_t)src_stride | (uintptr_t)agg_stride |
          (uintptr_t)dh_stride | (uintptr_t)h_stride) & 15)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_src, agg, dh, h and their strides must be 16-byte aligned", who);
@@ -541,9 +695,15 @@ extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t
     float* part_b = (float*)((char*)ws_dev + P.part_b);
     // without rows (or without anything they could index) every chunk is empty and the partials are zeros
     const int64_t rows_bound = (n > 0 && n_src > 0) ? max_rows : 0;
-    hipLaunchKernelGGL(weight_grad_partial_kernel, dim3((unsigned)P.n_chunks, (unsigned)P.tiles_m, (unsigned)P.tiles_n), dim3(WG_THREADS), 0, st,
-                       (const char*)h_src_dev, n_src, src_stride, (const char*)agg_dev, agg_stride, (const char*)dh_dev, dh_stride,
-                       (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, rows_bound, d_in, d_out, part_w, part_b);
+    const dim3 grid((unsigned)P.n_chunks, (unsigned)P.tiles_m, (unsigned)P.tiles_n);
+    if (b16)
+        hipLaunchKernelGGL(weight_grad_partial_kernel<true>, grid, dim3(WG_THREADS), 0, st, (const char*)h_src_dev, n_src, src_stride,
+                           (int)src_dtype, (const char*)agg_dev, agg_stride, (const char*)dh_dev, dh_stride, (const char*)h_dev, h_stride, n,
+                           rows_dev, n_rows_dev, rows_bound, d_in, d_out, part_w, part_b);
+    else
+        hipLaunchKernelGGL(weight_grad_partial_kernel<false>, grid, dim3(WG_THREADS), 0, st, (const char*)h_src_dev, n_src, src_stride,
+                           (int)src_dtype, (const char*)agg_dev, agg_stride, (const char*)dh_dev, dh_stride, (const char*)h_dev, h_stride, n,
+                           rows_dev, n_rows_dev, rows_bound, d_in, d_out, part_w, part_b);
     FG_LAUNCH_CHECK("weight_grad_partial_kernel");
     const int64_t mn = (int64_t)2 * d_in * d_out;
     const int w_blocks = (int)fg_ceil_div(mn, 128), b_blocks = (int)fg_ceil_div(d_out, 128);
@@ -551,4 +711,24 @@ extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t
                        mn, d_out, w_blocks, dw_dev, db_dev);
     FG_LAUNCH_CHECK("weight_grad_reduce_kernel");
     return FG_OK;
+}
+
+extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t n_src, int64_t src_stride, const float* agg_dev,
+                                                 int64_t agg_stride, const float* dh_dev, int64_t dh_stride, const float* h_dev,
+                                                 int64_t h_stride, int32_t n, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                                 int64_t max_rows, int32_t d_in, int32_t d_out, float* dw_dev, float* db_dev,
+                                                 void* ws_dev, size_t ws_bytes, void* stream) {
+    return weights_backward_launch("fg_layer_backward_weights", false, h_src_dev, n_src, src_stride, FG_F32, agg_dev, agg_stride, dh_dev,
+                                   dh_stride, h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_in, d_out, dw_dev, db_dev, ws_dev,
+                                   ws_bytes, stream);
+}
+
+extern "C" fg_status_t fg_layer_backward_weights_bf16(const void* h_src_dev, int32_t n_src, int64_t src_stride, fg_dtype_t src_dtype,
+                                                      const void* agg_dev, int64_t agg_stride, const float* dh_dev, int64_t dh_stride,
+                                                      const void* h_dev, int64_t h_stride, int32_t n, const int32_t* rows_dev,
+                                                      const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out,
+                                                      float* dw_dev, float* db_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+    return weights_backward_launch("fg_layer_backward_weights_bf16", true, h_src_dev, n_src, src_stride, src_dtype, agg_dev, agg_stride,
+                                   dh_dev, dh_stride, h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_in, d_out, dw_dev, db_dev,
+                                   ws_dev, ws_bytes, stream);
 }

@@ -198,15 +198,20 @@ class HotPath:
             shared = torch.zeros(agg_elems, dtype=TORCH_DTYPE[self.agg_code], device=dev)
             self.AGG_l = [None] + [shared] * L
         self.AGG = self.AGG_l[L]
-        # model "gcn": GCN layers (propagation incl. the node itself, one weight matrix [d_in x d_out]); fp32, forward only.
+        # model "gcn": GCN layers (propagation incl. the node itself, one weight matrix [d_in x d_out]); fp32.
         # The mean's first half goes to a by-position buffer, its second half to AGG in list order (what fg_linear reads).
         self.model = model
         # optional: layers with few rows (the seed layer) run aggregation and dense update as one launch (measured no faster
         # than the two launches, so off by default); not when the weight gradients need the means afterwards
         self.fuse_small_layers = bool(fuse_small_layers) and model == "sage" and self.comp_code == B.FG_F32 and not self.weight_grads
         if model == "gcn":
-            assert self.comp_code == B.FG_F32 and self.feat_code == B.FG_F32 and not backward, "GCN layers: fp32, forward only"
-            self.MEANPOS = torch.zeros(max(n[l] * (dims[l - 1] // 2) for l in range(1, L + 1)), dtype=torch.float32, device=dev)
+            assert self.comp_code == B.FG_F32 and self.feat_code == B.FG_F32, "GCN layers: fp32"
+            if self.weight_grads:   # like the means: every layer keeps its own until the backward pass
+                self.MEANPOS_l = [None] + [torch.zeros(n[l] * (dims[l - 1] // 2), dtype=torch.float32, device=dev) for l in range(1, L + 1)]
+            else:
+                shared_pos = torch.zeros(max(n[l] * (dims[l - 1] // 2) for l in range(1, L + 1)), dtype=torch.float32, device=dev)
+                self.MEANPOS_l = [None] + [shared_pos] * L
+            self.MEANPOS = self.MEANPOS_l[L]
         self.live = [torch.zeros(n[l], dtype=torch.uint8, device=dev) for l in range(L + 1)]
         self.hit = [torch.zeros(n[l], dtype=torch.uint8, device=dev) for l in range(L + 1)]
         self.saving = [torch.zeros(n[l] if admit_budget else 0, dtype=torch.int32, device=dev) for l in range(L + 1)]
@@ -261,17 +266,21 @@ class HotPath:
             self.W[l] = torch.from_numpy(np.ascontiguousarray(W)).to(dev).to(wt).contiguous()
             self.bias[l] = torch.from_numpy(np.ascontiguousarray(b)).to(dev)
         # backward: the gradient norms of the update come from the backward pass (softmax cross-entropy on H[L] against
-        # the batch's labels) instead of from the batch; fp32 models only
+        # the batch's labels) instead of from the batch. Gradients are fp32 in every setting; the bf16 model rounds the
+        # operands of the backward matrix products as the forward ones
         self.backward = backward
+        self.bw_kind = "gcn" if model == "gcn" else ("sage" if self.comp_code == B.FG_F32 else "bf16")
         if backward:
-            assert self.comp_code == B.FG_F32, "the backward pass is fp32"
+            assert self.comp_code in (B.FG_F32, B.FG_BF16), "the backward pass is for the fp32 and the bf16 model"
             self.dH = [None] + [torch.zeros((n[l], dims[l]), dtype=torch.float32, device=dev) for l in range(1, L + 1)]
             self.gnorm = [None] + [torch.zeros(max(n[l], 1), dtype=torch.float32, device=dev) for l in range(1, L)]
-            self.ws_bw_bytes = max([B.fg_layer_backward_workspace_bytes(n[l], n[l], dims[l - 1], dims[l]) for l in range(2, L + 1)] or [0])
+            self.ws_bw_bytes = max([B.fg_layer_backward_workspace_bytes(n[l], n[l], dims[l - 1], dims[l], kind=self.bw_kind)
+                                    for l in range(2, L + 1)] or [0])
             self.ws_bw = torch.zeros(self.ws_bw_bytes + 256, dtype=torch.uint8, device=dev)
             if self.weight_grads:
-                assert self.feat_code == B.FG_F32, "weight gradients need fp32 features"
-                self.dW = [None] + [torch.zeros((2 * dims[l - 1], dims[l]), dtype=torch.float32, device=dev) for l in range(1, L + 1)]
+                assert self.feat_code == B.FG_F32 or self.bw_kind == "bf16", "weight gradients of the fp32 models need fp32 features"
+                w_rows = [None] + [(1 if model == "gcn" else 2) * dims[l - 1] for l in range(1, L + 1)]
+                self.dW = [None] + [torch.zeros((w_rows[l], dims[l]), dtype=torch.float32, device=dev) for l in range(1, L + 1)]
                 self.db = [None] + [torch.zeros(dims[l], dtype=torch.float32, device=dev) for l in range(1, L + 1)]
                 self.ws_wg_bytes = max(B.fg_layer_backward_weights_workspace_bytes(n[l], dims[l - 1], dims[l]) for l in range(1, L + 1))
                 self.ws_wg = torch.zeros(self.ws_wg_bytes + 256, dtype=torch.uint8, device=dev)
@@ -468,13 +477,13 @@ class HotPath:
                     tick("gather_aggregate[1]")
                     B.fg_gather_aggregate_gcn(bt.start[1], bt.end[1], bt.col[1], bt.nnz[1], bt.n[1], self.normal_pos[1],
                                               self._cnt(1, 2), bt.n[1], bt.ids[0], bt.n[0], self.feat, self.num_nodes, d0b,
-                                              self.dims[0], self.MEANPOS, self.AGG_l[1], st)
+                                              self.dims[0], self.MEANPOS_l[1], self.AGG_l[1], st)
                 else:
                     tick(f"aggregate[{l}]")
                     B.fg_aggregate_gcn(bt.start[l], bt.end[l], bt.col[l], bt.nnz[l], bt.n[l], self.normal_pos[l], self._cnt(l, 2),
-                                       bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], self.MEANPOS, self.AGG_l[l], st)
+                                       bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], self.MEANPOS_l[l], self.AGG_l[l], st)
                 tick(f"linear[{l}]")
-                B.fg_linear(self.MEANPOS, bt.n[l], half * 4, B.FG_F32, self.AGG_l[l], half * 4, self.normal_pos[l], self._cnt(l, 2),
+                B.fg_linear(self.MEANPOS_l[l], bt.n[l], half * 4, B.FG_F32, self.AGG_l[l], half * 4, self.normal_pos[l], self._cnt(l, 2),
                             bt.n[l], half, self.dims[l], self.W[l], B.FG_F32, self.bias[l], 1 if l < L else 0, self.H[l], bt.n[l],
                             out_b, out_code, st)
                 continue
@@ -511,10 +520,23 @@ class HotPath:
         gnorm = bt.gnorm
         if self.backward:
             def weight_grads(l, stream):
-                B.fg_layer_backward_weights(self.H[l - 1], bt.n[l - 1], self.dims[l - 1] * 4, self.AGG_l[l], self.dims[l - 1] * 4,
-                                            self.dH[l], self.dims[l] * 4, self.H[l] if l < L else None, self.dims[l] * 4, bt.n[l],
-                                            self.normal_pos[l], self._cnt(l, 2), bt.n[l], self.dims[l - 1], self.dims[l],
-                                            self.dW[l], self.db[l], self.ws_wg, self.ws_wg_bytes, stream)
+                act = self.H[l] if l < L else None
+                tail = (bt.n[l], self.normal_pos[l], self._cnt(l, 2), bt.n[l])
+                if self.bw_kind == "gcn":    # the layer's input rows are the propagated rows: by-position half ‖ list-order half
+                    half = self.dims[l - 1] // 2
+                    B.fg_layer_backward_weights(self.MEANPOS_l[l], bt.n[l], half * 4, self.AGG_l[l], half * 4, self.dH[l],
+                                                self.dims[l] * 4, act, self.dims[l] * 4, *tail, half, self.dims[l],
+                                                self.dW[l], self.db[l], self.ws_wg, self.ws_wg_bytes, stream)
+                elif self.bw_kind == "bf16":
+                    B.fg_layer_backward_weights_bf16(self.H[l - 1], bt.n[l - 1], self.dims[l - 1] * esz[self.h_code[l - 1]],
+                                                     self.h_code[l - 1], self.AGG_l[l], self.dims[l - 1] * 2, self.dH[l],
+                                                     self.dims[l] * 4, act, self.dims[l] * 2, *tail, self.dims[l - 1],
+                                                     self.dims[l], self.dW[l], self.db[l], self.ws_wg, self.ws_wg_bytes, stream)
+                else:
+                    B.fg_layer_backward_weights(self.H[l - 1], bt.n[l - 1], self.dims[l - 1] * 4, self.AGG_l[l],
+                                                self.dims[l - 1] * 4, self.dH[l], self.dims[l] * 4, act, self.dims[l] * 4,
+                                                *tail, self.dims[l - 1], self.dims[l], self.dW[l], self.db[l], self.ws_wg,
+                                                self.ws_wg_bytes, stream)
 
             # The weight gradients of a layer need that layer's output gradient and nothing later: with a second stream they
             # run there, each as soon as its dH exists, beside the rest of the backward chain and the cache update.
@@ -532,11 +554,11 @@ class HotPath:
                 weight_grads_beside(L)
             for l in range(L, 1, -1):
                 tick(f"layer_backward[{l}]")
-                B.fg_layer_backward(self.dH[l], self.dims[l] * 4, self.H[l] if l < L else None, self.dims[l] * 4, bt.n[l],
-                                    self.normal_pos[l], self._cnt(l, 2), bt.n[l], self.live[l] if l < L else None, self.hit[l],
-                                    bt.start[l], bt.end[l], bt.t_start[l], bt.t_end[l], bt.t_row[l], bt.nnz[l], bt.n[l - 1],
-                                    self.dims[l - 1], self.dims[l], self.W[l], self.dH[l - 1], self.dims[l - 1] * 4,
-                                    self.gnorm[l - 1], self.ws_bw, self.ws_bw_bytes, st)   # with the row norms of dH[l-1]
+                B.fg_layer_backward(self.dH[l], self.dims[l] * 4, self.H[l] if l < L else None, self.dims[l] * esz[self.h_code[l]],
+                                    bt.n[l], self.normal_pos[l], self._cnt(l, 2), bt.n[l], self.live[l] if l < L else None,
+                                    self.hit[l], bt.start[l], bt.end[l], bt.t_start[l], bt.t_end[l], bt.t_row[l], bt.nnz[l],
+                                    bt.n[l - 1], self.dims[l - 1], self.dims[l], self.W[l], self.dH[l - 1], self.dims[l - 1] * 4,
+                                    self.gnorm[l - 1], self.ws_bw, self.ws_bw_bytes, st, kind=self.bw_kind)   # with the row norms of dH[l-1]
                 if wg_beside:
                     weight_grads_beside(l - 1)
             gnorm = self.gnorm
