@@ -420,6 +420,8 @@ def main():
     if args.device_sampler:      # the loop with nothing resident beforehand but the graph, the table and the seeds
         sampler_report["in_loop"] = sampled_loop(w, hp, ds, first_it=total + extra, steps=args.steps, warmup=10, backward=args.backward,
                                                  lookahead=not args.no_lookahead)
+        sampler_report["in_loop_host_sizes"] = sampled_loop(w, hp, ds, first_it=total + extra + args.steps + 10, steps=args.steps, warmup=10,
+                                                            backward=args.backward, lookahead=not args.no_lookahead, host_sizes=True)
 
     cpu_baseline = None
     if not args.no_cpu_baseline:
@@ -614,10 +616,12 @@ def policy_paper_run(w, feat, sampled, args, ids_cols):
         torch.cuda.empty_cache()
 
 
-def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False, lookahead=True):
-    """Iterations whose mini-batches are sampled on the device while the loop runs: the sampler works one mini-batch ahead on
-    a second stream (its three layer sizes reach the host through a pinned copy on that stream), gradient norms are made on
-    the device from the sampled node ids, and the path waits for the sampler's event. Four sets of buffers rotate."""
+def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False, lookahead=True, host_sizes=False):
+    """Iterations whose mini-batches are sampled on the device while the loop runs: the sampler works two mini-batches ahead
+    on a second stream, gradient norms are made on the device from the sampled node ids, and the path's stream waits for
+    the sampler's event. The layer sizes stay in device memory (the calls get the sampler's bounds and the addresses of the
+    counts), so the host never waits for the device inside the loop; host_sizes=True is the variant in which the sizes
+    reach the host through a pinned copy and the host waits for each mini-batch's event. Four sets of buffers rotate."""
     import torch
     from fg_inputs import device as fdev, rng, workload as wl
     L, K = w.num_layers, 4
@@ -647,15 +651,17 @@ def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False, lookahead=T
                 for l in range(1, L):
                     fdev.grad_norms(bt.ids[l], bt._counts.data_ptr() + 16 * l, ds.bound[l], gkeys[t][l], gn[k][l], side.cuda_stream)
                 bt.gnorm = gn[k]
-            host_counts[k].copy_(bt._counts, non_blocking=True)
+            if host_sizes:
+                host_counts[k].copy_(bt._counts, non_blocking=True)
             sampled_ev[k].record(side)
         return bt
 
     def ready(t, bt):
-        """Mini-batch t with its layer sizes on the host (waits for the sampler's event) and the path's stream behind it."""
+        """Mini-batch t with the path's stream behind its sampling (host_sizes: and its layer sizes on the host)."""
         k = t % K
-        sampled_ev[k].synchronize()
-        bt.finish(host_counts[k])
+        if host_sizes:
+            sampled_ev[k].synchronize()
+            bt.finish(host_counts[k])
         main.wait_event(sampled_ev[k])
         return bt
 
@@ -679,7 +685,9 @@ def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False, lookahead=T
     torch.cuda.synchronize()
     dt = time.time() - t_start
     return {"steps": steps, "warmup": warmup, "ms_per_step": 1e3 * dt / steps, "minibatches_per_s": steps / dt,
-            "note": "sampling (a stream of its own, two mini-batches ahead), gradient norms and the whole path inside the timed loop"}
+            "host_synchronisations_per_minibatch": 1 if host_sizes else 0,
+            "note": "sampling (a stream of its own, two mini-batches ahead), gradient norms and the whole path inside the timed loop; "
+                    + ("layer sizes read back through a pinned copy" if host_sizes else "layer sizes never leave the device")}
 
 
 def profiled_traffic(kernel_prefix):

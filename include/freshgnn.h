@@ -239,6 +239,10 @@ typedef struct fg_top_down_layer {
     int32_t* normal_pos_dev;
     int32_t* normal_ids_dev;
     int64_t* counts_dev;
+    const int64_t* n_dev; /* NULL, or the layer's size as a count in device memory (a mini-batch sampled on the device, Section 5:
+                             sampling runs ahead of training and nothing waits for its sizes): n, nnz and n_src are then
+                             host-side bounds, every array holds that many entries, positions at or beyond
+                             min(*n_dev, n) are dead, and the flags of the positions up to n are still written */
 } fg_top_down_layer_t;
 size_t fg_top_down_workspace_bytes(int32_t n_layers, const fg_top_down_layer_t* layers);
 fg_status_t fg_top_down(const fg_cache_t* cache, int64_t iter, int32_t n_layers, const fg_top_down_layer_t* layers,
@@ -449,6 +453,9 @@ typedef struct fg_update_layer {
     int64_t* stats_dev;
     const int32_t* saving_dev; /* access-aware admission: estimates by position (fg_access_estimate), or NULL */
     int64_t max_admit;         /* rows this update may admit; 0 = the ring's capacity */
+    const int64_t* n_dev;      /* NULL, or the layer's size as a count in device memory (a mini-batch sampled on the device):
+                                  n is then its host-side bound, the arrays hold n entries and positions at or beyond
+                                  min(*n_dev, n) are ignored; the workspace is sized by n */
 } fg_update_layer_t;
 fg_status_t fg_cache_update_all(fg_cache_t* cache, int64_t iter, float p_grad, int32_t n_layers,
                                 const fg_update_layer_t* layers, void* ws_dev, size_t ws_bytes, void* stream);

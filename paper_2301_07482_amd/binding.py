@@ -85,7 +85,7 @@ class TopDownLayer(C.Structure):
     """fg_top_down_layer_t"""
     _fields_ = [("cache_layer", _i32), ("n", _i32), ("ids_dev", _p), ("live_dev", _p), ("row_start_dev", _p),
                 ("row_end_dev", _p), ("col_dev", _p), ("nnz", _i64), ("n_src", _i32), ("live_src_dev", _p), ("hit_dev", _p),
-                ("hit_pos_dev", _p), ("hit_slot_dev", _p), ("normal_pos_dev", _p), ("normal_ids_dev", _p), ("counts_dev", _p)]
+                ("hit_pos_dev", _p), ("hit_slot_dev", _p), ("normal_pos_dev", _p), ("normal_ids_dev", _p), ("counts_dev", _p), ("n_dev", _p)]
 
 
 SIGNATURES["fg_top_down_workspace_bytes"] = (_sz, [_i32, C.POINTER(TopDownLayer)])
@@ -96,7 +96,7 @@ SIGNATURES["fg_top_down"] = (_i32, [_p, _i64, _i32, C.POINTER(TopDownLayer), _p,
 class UpdateLayer(C.Structure):
     """fg_update_layer_t"""
     _fields_ = [("layer", _i32), ("n", _i32), ("ids_dev", _p), ("live_dev", _p), ("hit_dev", _p), ("gnorm_dev", _p),
-                ("h_dev", _p), ("h_stride", _i64), ("stats_dev", _p), ("saving_dev", _p), ("max_admit", _i64)]
+                ("h_dev", _p), ("h_stride", _i64), ("stats_dev", _p), ("saving_dev", _p), ("max_admit", _i64), ("n_dev", _p)]
 
 
 class FetchLayer(C.Structure):

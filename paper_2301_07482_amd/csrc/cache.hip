@@ -100,9 +100,17 @@ struct UpdLayer {
     int64_t h_stride;
     char* table;
     int64_t row_bytes;
-    int32_t n;
+    int32_t n;           // positions of the layer: the caller's bound ...
+    const int64_t* n_dev;  // ... and, if non-null, the count in device memory (positions at or beyond it are not live)
     float p_grad;
 };
+
+// positions of the layer that exist: the device-side count where the caller gave one, never above the bound
+__device__ __forceinline__ int upd_count(const UpdLayer& L) {
+    if (!L.n_dev) return L.n;
+    const int64_t c = *L.n_dev;
+    return c < 0 ? 0 : (c < (int64_t)L.n ? (int)c : L.n);
+}
 
 struct UpdBatch {
     int32_t n_layers;
@@ -215,7 +223,7 @@ __global__ __launch_bounds__(SEL_THREADS) void update_digit0_kernel(UpdBatch B) 
     if (chunk == 0 && t == 0 && L.stats) L.stats[0] = L.stats[1] = L.stats[2] = L.stats[3] = 0;
     for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
     __syncthreads();
-    for_each_live_key(L.live, L.gnorm, L.n, chunk, [&](uint32_t kj) { atomicAdd(&hist[kj >> 21], 1u); });
+    for_each_live_key(L.live, L.gnorm, upd_count(L), chunk, [&](uint32_t kj) { atomicAdd(&hist[kj >> 21], 1u); });
     __syncthreads();
     for (int b = t; b < SEL_BINS; b += SEL_THREADS)
         if (hist[b]) atomicAdd(&L.sel->hist0[b], hist[b]);
@@ -237,7 +245,7 @@ __global__ __launch_bounds__(SEL_THREADS) void update_digit1_kernel(UpdBatch B) 
     for (int b = t; b < SEL_BINS; b += SEL_THREADS) hist[b] = 0;
     if (t == 0) s_parked = 0;
     __syncthreads();
-    for_each_live_key(L.live, L.gnorm, L.n, chunk, [&](uint32_t kj) {
+    for_each_live_key(L.live, L.gnorm, upd_count(L), chunk, [&](uint32_t kj) {
         if ((kj >> 21) != d0) return;
         atomicAdd(&hist[(kj >> 10) & 2047u], 1u);
         park[atomicAdd(&s_parked, 1u)] = kj;  // a workgroup sees at most SEL_CHUNK keys
@@ -264,12 +272,12 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void classify_update_kernel(UpdBatch
     const int t = threadIdx.x;
     // this thread's element first: the loads are in flight while the selection below runs
     const int j = local * FG_SCAN_BLOCK + t;
-    const bool in = j < L.n;
+    const bool in = j < upd_count(L);
     const int jc = in ? j : 0;
-    const uint8_t live_j = (in && L.n > 0) ? (L.live ? L.live[jc] : (uint8_t)1) : (uint8_t)0;
-    const uint32_t key_j = (in && L.n > 0) ? order_key(L.gnorm[jc]) : 0u;
-    const uint8_t hit_j = (in && L.n > 0) ? L.hit[jc] : (uint8_t)0;
-    const int32_t v = (in && L.n > 0) ? L.ids[jc] : -1;
+    const uint8_t live_j = in ? (L.live ? L.live[jc] : (uint8_t)1) : (uint8_t)0;
+    const uint32_t key_j = in ? order_key(L.gnorm[jc]) : 0u;
+    const uint8_t hit_j = in ? L.hit[jc] : (uint8_t)0;
+    const int32_t v = in ? L.ids[jc] : -1;
     // the rest of the selection, the same in every workgroup of the layer
     uint32_t d0, tau_key = 0;
     long long m;
@@ -707,7 +715,8 @@ namespace {
 fg_status_t prepare_update_layer(fg_cache_t* cache, const char* who, int32_t layer, int64_t iter, const int32_t* ids_dev,
                                  int32_t n, const uint8_t* live_dev, const uint8_t* hit_dev, const float* gnorm_dev,
                                  float p_grad, const void* h_dev, int64_t h_stride, int64_t* stats_dev, char* ws,
-                                 UpdLayer* out, const int32_t* saving_dev = nullptr, int64_t max_admit = 0) {
+                                 UpdLayer* out, const int32_t* saving_dev = nullptr, int64_t max_admit = 0,
+                                 const int64_t* n_dev = nullptr) {
     const fg_layer* lc;
     fg_status_t rc = layer_of(cache, layer, who, &lc);
     if (rc != FG_OK) return rc;
@@ -743,6 +752,7 @@ fg_status_t prepare_update_layer(fg_cache_t* cache, const char* who, int32_t lay
     u.table = (char*)l->table;
     u.row_bytes = row_bytes;
     u.n = n;
+    u.n_dev = n_dev;
     u.p_grad = iter < cache->stabilization ? 0.0f : p_grad;  // stabilization period: nothing is admitted (k = 0)
     return FG_OK;
 }
@@ -838,7 +848,7 @@ fg_status_t update_all(const char* who, int phase, fg_cache_t* cache, int64_t it
             FG_FAIL(FG_ERR_STATE, "%s: layer %d still waits for fg_cache_update_commit", who, a.layer);
         fg_status_t rc = prepare_update_layer(cache, who, a.layer, phase == 2 ? cache->layers[a.layer - 1].last_iter : iter, a.ids_dev, a.n,
                                               a.live_dev, a.hit_dev, a.gnorm_dev, p_grad, a.h_dev, a.h_stride, a.stats_dev,
-                                              (char*)ws_dev + off, &B.l[i], a.saving_dev, a.max_admit);
+                                              (char*)ws_dev + off, &B.l[i], a.saving_dev, a.max_admit, a.n_dev);
         if (rc != FG_OK) return rc;
         off += upd_layout(a.n).total;
     }

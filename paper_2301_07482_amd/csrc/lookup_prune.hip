@@ -180,7 +180,8 @@ struct TdLayer {
     CacheView cv;
     int has_cache;
     const int32_t* ids;
-    int n;
+    int n;                 // positions of the layer: the caller's bound (every array holds this many) ...
+    const int64_t* n_dev;  // ... and, if non-null, the count in device memory: positions at or beyond it are dead
     const uint8_t* live;   // liveness given by the caller (seed layer, or a layer whose upper neighbour marks nothing); may be null = all live
     uint8_t* mark;         // workspace, one byte per position, zero between calls: set by the layer above (or the walk)
     uint8_t* live_out;     // non-null: liveness = mark, written here in full (the caller's live_src array of the layer above)
@@ -209,6 +210,13 @@ struct TdArgs {
     int count;
 };
 
+// positions of the layer that exist: the device-side count where the caller gave one, never above the bound
+__device__ __forceinline__ int td_count(const TdLayer& L) {
+    if (!L.n_dev) return L.n;
+    const int64_t c = *L.n_dev;
+    return c < 0 ? 0 : (c < (int64_t)L.n ? (int)c : L.n);
+}
+
 // Marks the neighbours of one row, eight loads in flight (a slot past the end re-reads the last one).
 __device__ __forceinline__ void td_mark_row(const int32_t* __restrict__ col, int32_t s, int32_t e, uint8_t* __restrict__ mark,
                                             int n_mark) {
@@ -229,7 +237,8 @@ __device__ __forceinline__ void td_walk_rows(const TdArgs& a, int hops, int bloc
     const TdLayer& B = a.layer[1];
     const int lane = threadIdx.x & 63;
     const int n_waves = n_blocks * (TD_WALK_THREADS / 64);
-    for (int r = (block * TD_WALK_THREADS + (int)threadIdx.x) >> 6; r < A.n; r += n_waves) {
+    const int n_seed = td_count(A);
+    for (int r = (block * TD_WALK_THREADS + (int)threadIdx.x) >> 6; r < n_seed; r += n_waves) {
         const uint8_t live_r = A.live ? A.live[r] : (uint8_t)1;
         const int32_t s0 = A.row_start[r], e0 = A.row_end[r];
         const int32_t id_r = A.has_cache ? A.ids[r] : -1;
@@ -266,8 +275,10 @@ __global__ __launch_bounds__(TD_WALK_THREADS) void td_walk_kernel(TdArgs a, int 
     const int64_t gsize = (int64_t)(gridDim.x - walk_blocks) * blockDim.x;
     for (int i = 0; i < a.count; ++i) {
         const TdLayer& L = a.layer[i];
-        if (L.has_cache)
-            for (int64_t j = gtid; j < L.n; j += gsize) L.slot[j] = cache_lookup(L.cv, L.ids[j]);
+        if (L.has_cache) {
+            const int n_i = td_count(L);
+            for (int64_t j = gtid; j < n_i; j += gsize) L.slot[j] = cache_lookup(L.cv, L.ids[j]);
+        }
         uint8_t* p = L.clear_below;
         if (!p) continue;
         const int64_t n = L.n_src;
@@ -283,28 +294,30 @@ __global__ __launch_bounds__(TD_WALK_THREADS) void td_walk_kernel(TdArgs a, int 
 // class, row cut, and, if `mark`, the marks of a normal row in the layer below.
 __device__ __forceinline__ void td_classify_chunk(const TdLayer& L, int chunk, bool mark) {
     const int j = chunk * FG_SCAN_BLOCK + threadIdx.x;
-    const bool in = j < L.n;
+    const bool in = j < L.n;                // within the arrays: flags and class are written
+    const bool there = j < td_count(L);     // a position of this mini-batch
     uint8_t live_j = 0;
-    if (in) live_j = L.live_out ? L.mark[j] : (L.live ? L.live[j] : (uint8_t)1);
+    if (in) live_j = L.live_out ? L.mark[j] : ((there && L.live) ? L.live[j] : (uint8_t)1);
     int32_t s0 = 0, e0 = 0, slot_j = -1;
-    if (in && L.row_start) {
+    if (there && L.row_start) {
         s0 = L.row_start[j];
         e0 = L.row_end[j];
     }
-    if (in && L.has_cache) slot_j = L.slot[j];   // the node's usable slot or -1, looked up for every position by launch 1
-    const bool is_live = live_j != 0;
+    if (there && L.has_cache) slot_j = L.slot[j];   // the node's usable slot or -1, looked up for every position by launch 1
+    const bool marked = live_j != 0;        // (a mark beyond the count can only come from a column out of range: cleared, ignored)
+    const bool is_live = marked && there;
     const bool hit = is_live && L.has_cache && slot_j >= 0;
     const int32_t slot = hit ? slot_j : -1;
     const bool normal = is_live && !hit;
     if (in) {
         if (L.live_out) {
             L.live_out[j] = is_live ? 1 : 0;
-            if (is_live) L.mark[j] = 0;
+            if (marked) L.mark[j] = 0;
         }
         L.cls[j] = is_live ? (hit ? CLS_HIT : CLS_NORMAL) : CLS_DEAD;
         L.slot[j] = slot;
         if (L.hit) L.hit[j] = hit ? 1 : 0;
-        if (L.row_start) {
+        if (L.row_start && there) {
             if (!normal) {
                 L.row_end[j] = s0;
             } else if (mark && L.mark_below) {
@@ -553,6 +566,7 @@ extern "C" fg_status_t fg_top_down(const fg_cache_t* cache, int64_t iter, int32_
         const WsLayout w = ws_layout(in.n);
         L.ids = in.ids_dev;
         L.n = in.n;
+        L.n_dev = in.n_dev;
         L.live = in.live_dev;
         L.row_start = has_block ? in.row_start_dev : nullptr;
         L.row_end = in.row_end_dev;

@@ -35,6 +35,7 @@ class DeviceBatch:
         self.num_layers = L
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
         self.n = [len(x) for x in mb.ids]
+        self.n_dev = [None] * (L + 1)       # the layer sizes are host integers
         self.ids = [up(x) for x in mb.ids]
         self.start = [None] + [up(mb.start[l]) for l in range(1, L + 1)]
         self.end = [None] + [up(mb.end[l]) for l in range(1, L + 1)]
@@ -59,11 +60,16 @@ class DeviceBatch:
 
 class SampledBatch:
     """A mini-batch sampled on the device (`DeviceSampler.sample`): the same fields as `DeviceBatch`; the transposed blocks
-    only if the sampler was asked for them, `labels` (the seeds' classes) for the caller to set."""
+    only if the sampler was asked for them, `labels` (the seeds' classes) for the caller to set.
+
+    Until `finish()` the layer sizes exist only in device memory: `n[l]` and `nnz[l]` are the sampler's bounds (the arrays
+    hold that many entries; rows at and beyond the count are empty) and `n_dev[l]` is the address of layer l's count, which
+    `HotPath.run` hands to the calls that walk whole layers. Nothing then waits for the sampler on the host."""
 
     def __init__(self, L):
         self.num_layers = L
         self.n, self.nnz = [0] * (L + 1), [0] * (L + 1)
+        self.n_dev = [None] * (L + 1)
         self.ids = [None] * (L + 1)
         self.start, self.end, self.col = [None] * (L + 1), [None] * (L + 1), [None] * (L + 1)
         self.col_ids1 = None
@@ -80,6 +86,7 @@ class SampledBatch:
         host[L][0] = self._n_seeds
         for l in range(L + 1):
             self.n[l] = int(host[l][0])
+            self.n_dev[l] = None
             assert self.n[l] <= self._bound[l], "a layer outgrew its bound"
             if l < L:
                 self.ids[l] = self.ids[l][:max(self.n[l], 1)]
@@ -91,8 +98,8 @@ class SampledBatch:
 
 class DeviceSampler:
     """Samples whole mini-batches with fg_sample_block over an in-neighbour CSR in HBM: one call per block, each layer's
-    device-side count feeding the next call, one read-back of the counts at the end (the rest of the path takes the
-    layer sizes as host integers)."""
+    device-side count feeding the next call. `sample(..., finish=False)` returns at once with the sizes still on the device
+    (the path takes them from there); `finish()` reads them back for callers that want host integers."""
 
     def __init__(self, indptr, indices, num_nodes, fanouts, batch, device="cuda", transposes=False):
         """transposes: also build the transposed blocks of layers 2..L (fg_transpose_block), which the backward pass walks."""
@@ -157,6 +164,12 @@ class DeviceSampler:
                 B.fg_transpose_block(bt.start[l], bt.end[l], bt.col[l], None if l == L else cp + 16 * l, rows, cp + 16 * (l - 1), nb,
                                      rows * f, bt.t_start[l], bt.t_end[l], bt.t_row[l], self.ws, self.ws_bytes, st)
         bt._counts, bt._bound, bt._n_seeds = counts, self.bound, n_seeds
+        # until the sizes are read back: the bounds, and where each layer's count lives
+        for l in range(L + 1):
+            bt.n[l] = self.bound[l] if l < L else n_seeds
+            bt.n_dev[l] = cp + 16 * l if l < L else None
+        for l in range(1, L + 1):
+            bt.nnz[l] = (self.bound[l] if l < L else n_seeds) * self.fanouts[l - 1]
         return bt.finish() if finish else bt
 
 
@@ -330,7 +343,7 @@ class HotPath:
                                      gnorm_dev=gnorm[l], h_dev=self.H[l], h_stride=self.dims[l] * esz[self.h_code[l]],
                                      stats_dev=self.stats.data_ptr() + l * 32,
                                      saving_dev=self.saving[l] if self.admit_budget else None,
-                                     max_admit=int(self.admit_budget.get(l, 0)) if self.admit_budget else 0)
+                                     max_admit=int(self.admit_budget.get(l, 0)) if self.admit_budget else 0, n_dev=bt.n_dev[l])
                                 for l in range(1, self.L)])
 
     def _cnt(self, l, k):
@@ -353,7 +366,7 @@ class HotPath:
                         hit_dev=self.hit[l], hit_pos_dev=self.hit_pos[l], hit_slot_dev=self.hit_slot[l],
                         normal_pos_dev=self.normal_pos[l],
                         normal_ids_dev=self.input_ids if l == 0 else (self.self_ids if (fused and l == 1) else None),
-                        counts_dev=self._cnt(l, 0))
+                        counts_dev=self._cnt(l, 0), n_dev=bt.n_dev[l])
 
         if self.one_launch_top_down:
             tick("top_down")
@@ -400,7 +413,12 @@ class HotPath:
         esz = B.DTYPE_SIZE
         st = torch.cuda.current_stream().cuda_stream
         do_update = update and self.use_cache and self.cache is not None
-        assert all(bt.n[l] <= self.n_max[l] for l in range(L + 1)), "mini-batch larger than the static bounds"
+        # sizes still on the device: the host integers are bounds, and a layer cannot outgrow the node count
+        assert all(bt.n[l] <= self.n_max[l] or bt.n_dev[l] is not None for l in range(L + 1)), "mini-batch larger than the static bounds"
+        assert all(d is None for d in bt.n_dev) or (self.one_launch_top_down and (self.update_all or not self.use_cache)), \
+            "layer sizes in device memory go through fg_top_down and fg_cache_update_all"
+        if any(bt.n[l] > self.n_max[l] for l in range(L + 1)):
+            bt.n = [min(bt.n[l], self.n_max[l]) for l in range(L + 1)]
         fused = self.fused_input
         promised = self._td_for is not None
         pruned_ahead = promised and self._td_for[0] == it and self._td_for[1] is bt

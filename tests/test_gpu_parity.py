@@ -1021,7 +1021,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
                         backward=False, stabilization=0, model="sage", conditioned=False, col_ids=False,
                         fetch_with_loader=True, admit_budget=None, device_sampler=False, overlap_update=True,
-                        lookahead=False):
+                        lookahead=False, device_counts=False):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
@@ -1030,6 +1030,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
     conditioned: for narrow layers. The bar is 1e-5 of max(|ref|, rowmax/16); where a row's largest output is small next to
     the terms it is summed from, one fp32 rounding of those terms already exceeds that, whatever the kernel. The bound
     used is then max(1e-5, 4 fp32 half-ulps of sum |terms| over the same denominator), computed from the oracle's values.
+    device_counts (with device_sampler): the sampled mini-batch is run with its layer sizes still in device memory (bounds on
+    the host); they are read back, and the sample compared with the oracle's, only after the iteration has been launched.
     backward: the gradient norms come from the backward pass of a softmax cross-entropy loss on the seeds' synthetic
     labels. The embedding gradients and their norms are compared within tolerance; the admission decisions are then taken
     on both sides from the device's norms (the same fp32 values), so that cache state stays comparable bit for bit.
@@ -1090,26 +1092,42 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                 a32 = lambda x: np.asarray(x, dtype=np.int32)
                 mb = MiniBatch(L, [a32(x) for x in o["ids"]], [None] + [a32(x) for x in o["start"][1:]],
                                [None] + [a32(x) for x in o["end"][1:]], [None] + [a32(x) for x in o["col"][1:]])
-                bt = sampler.sample(dev(torch, seeds.astype(np.int32)), key)
-                assert bt.n == [len(x) for x in mb.ids] and bt.nnz[1:] == [len(mb.col[l]) for l in range(1, L + 1)]
-                for l in range(L + 1):
-                    assert np.array_equal(bt.ids[l].cpu().numpy()[:bt.n[l]], mb.ids[l]), f"sampled nodes, iteration {it} layer {l}"
-                for l in range(1, L + 1):
-                    assert np.array_equal(bt.start[l].cpu().numpy()[:bt.n[l]], mb.start[l])
-                    assert np.array_equal(bt.end[l].cpu().numpy()[:bt.n[l]], mb.end[l])
-                    assert np.array_equal(bt.col[l].cpu().numpy()[:bt.nnz[l]], mb.col[l]), f"sampled block, iteration {it} layer {l}"
-                assert np.array_equal(bt.col_ids1.cpu().numpy()[:bt.nnz[1]], a32(o["col_ids"][1]))
+                bt = sampler.sample(dev(torch, seeds.astype(np.int32)), key, finish=not device_counts)
+
+                want_t = {}
+                if backward:      # the transposes of the blocks as sampled (the iteration prunes mb's row ends in place)
+                    from oracle import sampler_oracle as SO
+                    want_t = {l: SO.transpose_block(mb.start[l], mb.end[l], mb.col[l], len(mb.ids[l - 1])) for l in range(2, L + 1)}
+
+                def verify(bt=bt, mb=mb, o=o, it=it, want_t=want_t):
+                    """The device's sample against the oracle's (layer sizes read back first, if they were not yet)."""
+                    if bt.n_dev[0] is not None:
+                        bt.finish()
+                    assert bt.n == [len(x) for x in mb.ids] and bt.nnz[1:] == [len(mb.col[l]) for l in range(1, L + 1)]
+                    for l in range(L + 1):
+                        assert np.array_equal(bt.ids[l].cpu().numpy()[:bt.n[l]], mb.ids[l]), f"sampled nodes, iteration {it} layer {l}"
+                    for l in range(1, L + 1):
+                        assert np.array_equal(bt.start[l].cpu().numpy()[:bt.n[l]], mb.start[l])
+                        assert np.array_equal(bt.col[l].cpu().numpy()[:bt.nnz[l]], mb.col[l]), f"sampled block, iteration {it} layer {l}"
+                    assert np.array_equal(bt.col_ids1.cpu().numpy()[:bt.nnz[1]], a32(o["col_ids"][1]))
+                    if backward:
+                        for l in range(2, L + 1):      # the device's transposed blocks against the oracle's definition
+                            ts, te, tr = want_t[l]
+                            assert bt.t_start[l].cpu().numpy()[:bt.n[l - 1]].tolist() == ts and bt.t_end[l].cpu().numpy()[:bt.n[l - 1]].tolist() == te
+                            assert bt.t_row[l].cpu().numpy()[:bt.nnz[l]].tolist() == tr, f"transposed block, iteration {it} layer {l}"
+
+                if device_counts:      # the sizes stay on the device until the iteration has run; the row ends are pruned by then
+                    bt.verify_sample = verify
+                else:
+                    for l in range(1, L + 1):
+                        assert np.array_equal(bt.end[l].cpu().numpy()[:bt.n[l]], mb.end[l])
+                    verify()
                 gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
                 bt.gnorm = {l: dev(torch, x) for l, x in gn.items()}
                 labels = None
                 if backward:
-                    from oracle import sampler_oracle as SO
                     labels = wl.node_labels(w, mb.ids[L])
                     bt.labels = dev(torch, labels.astype(np.int32))
-                    for l in range(2, L + 1):      # the device's transposed blocks against the oracle's definition
-                        ts, te, tr = SO.transpose_block(mb.start[l], mb.end[l], mb.col[l], len(mb.ids[l - 1]))
-                        assert bt.t_start[l].cpu().numpy()[:bt.n[l - 1]].tolist() == ts and bt.t_end[l].cpu().numpy()[:bt.n[l - 1]].tolist() == te
-                        assert bt.t_row[l].cpu().numpy()[:bt.nnz[l]].tolist() == tr, f"transposed block, iteration {it} layer {l}"
             else:
                 mb = wl.minibatch(w, g, it)
                 gn = {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}
@@ -1137,6 +1155,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
             # device cache rows at the slots about to be hit, read before this iteration's update recycles slots
             pre_rows = {l: hp.cache_rows(l, rec["look"][l]["hit_slot"]) for l in range(1, L) if len(rec["look"][l]["hit_pos"])}
             hp.run(bt, it, next_bt=ahead[1] if ahead is not None else None)
+            if getattr(bt, "verify_sample", None) is not None:
+                bt.verify_sample()
             snap = hp.snapshot(bt)
             if backward:
                 # (a) every call against the oracle on the SAME inputs (the device's own H and dH of the layer above), so
@@ -1732,6 +1752,23 @@ def test_iterations_on_device_sampled_minibatches(env):
     w3 = dataclasses.replace(wl.WORKLOADS["large_hbm"], name="large_hbm/small", num_nodes=200_000, num_edges=4_000_000, batch=128,
                              train_nodes=20_000, cache_capacity=20_000, t_stale=6)
     assert run_workload_parity(torch, w3, 8, p_grad=0.7, fused=True, device_sampler=True, backward=True)[0] > 0
+
+
+def test_iterations_with_layer_sizes_left_on_the_device(env):
+    """Device-sampled mini-batches run without their sizes ever reaching the host beforehand: every call gets the sampler's
+    bounds and, where it walks a whole layer, the address of the layer's count. Same results as with host sizes."""
+    torch, B = env
+    w = wl.WORKLOADS["tiny"]
+    assert run_workload_parity(torch, w, w.iterations, fused=True, device_sampler=True, device_counts=True)[0] > 0
+    assert run_workload_parity(torch, w, 6, device_sampler=True, device_counts=True)[0] > 0      # input layer bounded by the node count
+    assert run_workload_parity(torch, w, 6, fused=True, device_sampler=True, device_counts=True, lookahead=True)[0] > 0
+    import dataclasses
+    w3 = dataclasses.replace(wl.WORKLOADS["large_hbm"], name="large_hbm/small", num_nodes=200_000, num_edges=4_000_000, batch=128,
+                             train_nodes=20_000, cache_capacity=20_000, t_stale=6)
+    assert run_workload_parity(torch, w3, 8, p_grad=0.7, fused=True, device_sampler=True, device_counts=True, backward=True)[0] > 0
+    assert run_workload_parity(torch, w3, 6, p_grad=0.7, fused=True, device_sampler=True, device_counts=True, model="gcn")[0] > 0
+    assert run_workload_parity(torch, w3, 6, p_grad=0.7, fused=True, device_sampler=True, device_counts=True,
+                               admit_budget={1: 300, 2: 40})[0] > 0
 
 
 def test_iterations_medium_fused_input(env):
