@@ -146,7 +146,7 @@ fg_status_t fg_cache_export(const fg_cache_t* cache, int32_t layer, int64_t iter
 /*
  * Launch-shape overrides for measurements (defaults are tuned for MI355X and need no call). Keys:
  * "gather_wg_per_cu", "gather_host_wg_per_cu", "gather_unroll" (1, 2, 4, 8), "gather_nontemporal" (0/1),
- * "aggregate_wg_per_cu", "top_down_walk" (fg_top_down: 1 = its first launch walks the first two blocks down from the seeds, 0 = one layer per launch), "linear_tile" (fp32 GEMM variant: 0 = default, 8 = one task per workgroup with K split over its wavefronts, 32 = panel kernel, 64 / 128 = LDS-tiled kernel with that many rows). Process-wide, not thread-safe against concurrent launches. Results never depend on them.
+ * "aggregate_wg_per_cu", "top_down_walk" (fg_top_down: 1 = its first launch walks the first two blocks down from the seeds, 0 = one layer per launch), "linear_tile" (fp32 GEMM variant: 0 = default, 8 = one task per workgroup with K split over its wavefronts, 32 = panel kernel, 64 / 128 = LDS-tiled kernel with that many rows; bf16 weights: 1064 / 1128 = the 64 x 64 or the 128 x 128 tile). Process-wide, not thread-safe against concurrent launches. Results never depend on them.
  */
 fg_status_t fg_set_tuning(const char* key, int64_t value);
 
@@ -392,6 +392,18 @@ fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_stride, fg_d
                       int64_t agg_stride, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
                       int32_t d_in, int32_t d_out, const void* W, fg_dtype_t w_dtype, const float* bias, int32_t relu,
                       void* h_out, int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, void* stream);
+
+/*
+ * fg_linear with the weights given transposed: Wt is [d_out x 2*d_in] row-major (the weights of one output column are
+ * contiguous), bf16 only (FG_ERR_DTYPE otherwise). Same result as fg_linear on the untransposed matrix. This is the layout
+ * the bf16 matrix-core kernel reads 16 bytes at a time with nothing to reshuffle on the way into LDS; a caller that keeps
+ * its weights across many mini-batches transposes them once (and the backward product dz . W^T takes W itself this way).
+ */
+fg_status_t fg_linear_wt(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype, const void* agg,
+                         int64_t agg_stride, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in,
+                         int32_t d_out, const void* Wt, fg_dtype_t w_dtype, const float* bias, int32_t relu, void* h_out,
+                         int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, void* stream);
+
 
 /*
  * fg_aggregate followed by fg_linear for one fp32 GraphSAGE-mean layer (Eq. 1 in one call; same results as the two

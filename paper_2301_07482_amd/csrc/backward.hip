@@ -228,7 +228,7 @@ BwWs bw_layout(int64_t n, int64_t max_rows, int64_t cols, int64_t d_out, int64_t
 fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype, const void* agg,
                                   int64_t agg_stride, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
                                   int32_t d_in, int32_t d_out, const void* W, const float* bias, int32_t relu, void* h_out,
-                                  int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, hipStream_t st);
+                                  int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, hipStream_t st, bool w_nk);
 
 extern "C" fg_status_t fg_softmax_xent_grad(const float* h_dev, int64_t h_stride, const int32_t* labels_dev, int32_t n, int32_t d,
                                             float* dh_dev, int64_t dh_stride, void* stream) {
@@ -327,12 +327,10 @@ static fg_status_t layer_backward_launch(const char* who, int kind, const float*
             hipLaunchKernelGGL(relu_backward_kernel<true>, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dh_dev, dh_stride,
                                (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_out, dz_pos, dz_cmp);
             FG_LAUNCH_CHECK("relu_backward_kernel");
-            hipLaunchKernelGGL(transpose_kernel<unsigned short>, tgrid, dim3(BW_THREADS), 0, st, (const unsigned short*)W, cols, d_out,
-                               (unsigned short*)wt);
-            FG_LAUNCH_CHECK("transpose_kernel");
-            // dx[r, :] = [dz_pos[r, :] ‖ dz_cmp[k, :]] . W^T, bf16 operands, fp32 sums and result
+            // dx[r, :] = [dz_pos[r, :] ‖ dz_cmp[k, :]] . W^T, bf16 operands, fp32 sums and result. The weights of this product are
+            // W^T; the matrix-core kernel takes them transposed, which is W as the caller holds it: nothing to transpose
             fg_status_t rc = fg_launch_linear_bf16(dz_pos, n, (int64_t)half * 2, FG_BF16, dz_cmp, (int64_t)half * 2, rows_dev, n_rows_dev,
-                                                   max_rows, half, cols, wt, nullptr, 0, dx, n, (int64_t)cols * 4, FG_F32, st);
+                                                   max_rows, half, cols, W, nullptr, 0, dx, n, (int64_t)cols * 4, FG_F32, st, true);
             if (rc != FG_OK) return rc;
         } else {
             hipLaunchKernelGGL(relu_backward_kernel<false>, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dh_dev, dh_stride,

@@ -108,7 +108,7 @@ enum fg_tune_id {
     FG_TUNE_GATHER_UNROLL,
     FG_TUNE_GATHER_NONTEMPORAL,
     FG_TUNE_AGG_WG_PER_CU,
-    FG_TUNE_LINEAR_TILE,  // 0: choose by problem size; 8: split-K kernel, 32: panel kernel, 64 or 128: LDS-tiled kernel
+    FG_TUNE_LINEAR_TILE,  // 0: choose by problem size; 8: split-K kernel, 32: panel kernel, 64 or 128: LDS-tiled kernel; bf16: 1064, 1128
     FG_TUNE_TOP_DOWN_WALK,  // 1: fg_top_down walks the first two blocks from the seeds in its first launch; 0: one layer per launch
     FG_TUNE_COUNT
 };

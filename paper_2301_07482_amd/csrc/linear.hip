@@ -714,7 +714,7 @@ fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_
                                   const void* agg, int64_t agg_stride, const int32_t* rows_dev,
                                   const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
                                   const float* bias, int32_t relu, void* h_out, int32_t n_out, int64_t out_stride,
-                                  fg_dtype_t out_dtype, hipStream_t st);
+                                  fg_dtype_t out_dtype, hipStream_t st, bool w_nk);
 
 extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype,
                                  const void* agg, int64_t agg_stride, const int32_t* rows_dev,
@@ -814,8 +814,23 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
     }
     if (w_dtype == FG_BF16)
         return fg_launch_linear_bf16(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows_dev, n_rows_dev, max_rows,
-                                     d_in, d_out, W, bias, relu, h_out, n_out, out_stride, out_dtype, st);
+                                     d_in, d_out, W, bias, relu, h_out, n_out, out_stride, out_dtype, st, false);
     FG_FAIL(FG_ERR_DTYPE, "fg_linear: weights must be F32 or BF16");
+}
+
+// fg_linear with the bf16 weights given transposed ([d_out x 2*d_in], one output column's weights contiguous): the layout
+// the matrix-core kernel reads 16 bytes at a time, with no reshuffling on the way into LDS.
+extern "C" fg_status_t fg_linear_wt(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype, const void* agg,
+                                    int64_t agg_stride, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
+                                    int32_t d_in, int32_t d_out, const void* Wt, fg_dtype_t w_dtype, const float* bias, int32_t relu,
+                                    void* h_out, int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, void* stream) {
+    if (max_rows < 0 || n_src < 0 || n_out < 0 || d_in <= 0 || d_out <= 0)
+        FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear_wt: bad size (max_rows %lld, n_src %d, n_out %d, d_in %d, d_out %d)",
+                (long long)max_rows, n_src, n_out, d_in, d_out);
+    if (w_dtype != FG_BF16) FG_FAIL(FG_ERR_DTYPE, "fg_linear_wt: transposed weights are taken in bf16 only");
+    if (max_rows > 0 && (!h_src || !agg || !Wt || !h_out)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear_wt: NULL pointer");
+    return fg_launch_linear_bf16(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out,
+                                 Wt, bias, relu, h_out, n_out, out_stride, out_dtype, (hipStream_t)stream, true);
 }
 
 

@@ -272,11 +272,14 @@ class HotPath:
         self.ws_upd_bytes = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L))
         self.ws_upd = torch.zeros(self.ws_upd_bytes + 256, dtype=torch.uint8, device=dev)
         self.W = {}
+        self.Wt = {}
         self.bias = {}
         wt = TORCH_DTYPE[self.comp_code]
         for l in range(1, L + 1):
             W, b = weights[l]
             self.W[l] = torch.from_numpy(np.ascontiguousarray(W)).to(dev).to(wt).contiguous()
+            if self.comp_code == B.FG_BF16:      # the layout the bf16 dense update reads fastest (fg_linear_wt); set up once
+                self.Wt[l] = self.W[l].t().contiguous()
             self.bias[l] = torch.from_numpy(np.ascontiguousarray(b)).to(dev)
         # backward: the gradient norms of the update come from the backward pass (softmax cross-entropy on H[L] against
         # the batch's labels) instead of from the batch. Gradients are fp32 in every setting; the bf16 model rounds the
@@ -531,9 +534,10 @@ class HotPath:
                                bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], in_code, self.AGG_l[l], agg_b,
                                self.agg_code, st)
             tick(f"linear[{l}]")
-            B.fg_linear(self.H[l - 1], bt.n[l - 1], in_b, in_code, self.AGG_l[l], agg_b, self.normal_pos[l], self._cnt(l, 2),
-                        bt.n[l], self.dims[l - 1], self.dims[l], self.W[l], self.comp_code, self.bias[l],
-                        1 if l < L else 0, self.H[l], bt.n[l], out_b, out_code, st)
+            dense, weights = (B.fg_linear_wt, self.Wt[l]) if l in self.Wt else (B.fg_linear, self.W[l])
+            dense(self.H[l - 1], bt.n[l - 1], in_b, in_code, self.AGG_l[l], agg_b, self.normal_pos[l], self._cnt(l, 2),
+                  bt.n[l], self.dims[l - 1], self.dims[l], weights, self.comp_code, self.bias[l],
+                  1 if l < L else 0, self.H[l], bt.n[l], out_b, out_code, st)
         # ---- loss and backward pass down to layer 1: the gradient norms the update admits and checks out by
         gnorm = bt.gnorm
         if self.backward:
