@@ -175,6 +175,9 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void compact_lists_kernel(
 // classification of their layer, so nothing has to be cleared ahead of the marking.
 constexpr int TD_MAX_LAYERS = 8;
 constexpr int TD_WALK_THREADS = 256;
+constexpr uint32_t TD_PUBLISHED = 0x80000000u;   // a chunk's counts as one word: this bit, live count << 12, hit count
+constexpr int TD_FUSED_MAX_BLOCKS = 256;         // workgroups of a launch whose chunks wait for each other: all resident at once
+constexpr int TD_SPIN_LIMIT = 1 << 20;           // polls of a predecessor's word before a chunk gives up (never reached)
 
 struct TdLayer {
     CacheView cv;
@@ -209,6 +212,8 @@ struct TdArgs {
     TdLayer layer[TD_MAX_LAYERS];
     int count;
 };
+
+__device__ __forceinline__ int td_chunks(int n) { return (n + FG_SCAN_BLOCK - 1) / FG_SCAN_BLOCK; }
 
 // positions of the layer that exist: the device-side count where the caller gave one, never above the bound
 __device__ __forceinline__ int td_count(const TdLayer& L) {
@@ -266,7 +271,7 @@ __device__ __forceinline__ void td_walk_rows(const TdArgs& a, int hops, int bloc
 
 // Launch 1: workgroups [0, walk_blocks) walk down from the seeds; the others look every position of every cached layer up
 // and clear the caller's liveness array below the last layer, if that is wanted.
-__global__ __launch_bounds__(TD_WALK_THREADS) void td_walk_kernel(TdArgs a, int hops, int walk_blocks) {
+__global__ __launch_bounds__(TD_WALK_THREADS) void td_walk_kernel(TdArgs a, int hops, int walk_blocks, int clear_published) {
     if ((int)blockIdx.x < walk_blocks) {
         td_walk_rows(a, hops, blockIdx.x, walk_blocks);
         return;
@@ -279,6 +284,8 @@ __global__ __launch_bounds__(TD_WALK_THREADS) void td_walk_kernel(TdArgs a, int 
             const int n_i = td_count(L);
             for (int64_t j = gtid; j < n_i; j += gsize) L.slot[j] = cache_lookup(L.cv, L.ids[j]);
         }
+        if (clear_published)      // the words the chunks of the fused launches publish their counts in
+            for (int64_t q = gtid; q < td_chunks(L.n); q += gsize) L.blk[3 * q] = 0;
         uint8_t* p = L.clear_below;
         if (!p) continue;
         const int64_t n = L.n_src;
@@ -291,8 +298,10 @@ __global__ __launch_bounds__(TD_WALK_THREADS) void td_walk_kernel(TdArgs a, int 
 }
 
 // One chunk of FG_SCAN_BLOCK positions of one layer: liveness (from the caller or from the marks, which are cleared),
-// class, row cut, and, if `mark`, the marks of a normal row in the layer below.
-__device__ __forceinline__ void td_classify_chunk(const TdLayer& L, int chunk, bool mark) {
+// class, row cut, and, if `mark`, the marks of a normal row in the layer below. The class and slot of this thread's position
+// are returned; `publish`: the chunk's counts go out as one word (see td_fused_kernel) instead of three.
+__device__ __forceinline__ void td_classify_chunk(const TdLayer& L, int chunk, bool mark, bool publish, uint8_t& cls_out,
+                                                  int32_t& slot_out, int& live_out, int& hit_out) {
     const int j = chunk * FG_SCAN_BLOCK + threadIdx.x;
     const bool in = j < L.n;                // within the arrays: flags and class are written
     const bool there = j < td_count(L);     // a position of this mini-batch
@@ -309,13 +318,17 @@ __device__ __forceinline__ void td_classify_chunk(const TdLayer& L, int chunk, b
     const bool hit = is_live && L.has_cache && slot_j >= 0;
     const int32_t slot = hit ? slot_j : -1;
     const bool normal = is_live && !hit;
+    cls_out = is_live ? (hit ? CLS_HIT : CLS_NORMAL) : CLS_DEAD;
+    slot_out = slot;
     if (in) {
         if (L.live_out) {
             L.live_out[j] = is_live ? 1 : 0;
             if (marked) L.mark[j] = 0;
         }
-        L.cls[j] = is_live ? (hit ? CLS_HIT : CLS_NORMAL) : CLS_DEAD;
-        L.slot[j] = slot;
+        if (!publish) {
+            L.cls[j] = cls_out;
+            L.slot[j] = slot;
+        }
         if (L.hit) L.hit[j] = hit ? 1 : 0;
         if (L.row_start && there) {
             if (!normal) {
@@ -328,10 +341,17 @@ __device__ __forceinline__ void td_classify_chunk(const TdLayer& L, int chunk, b
     }
     const int c_live = __syncthreads_count(is_live);
     const int c_hit = __syncthreads_count(hit);
+    live_out = c_live;
+    hit_out = c_hit;
     if (threadIdx.x == 0) {
-        L.blk[3 * chunk + 0] = c_live;
-        L.blk[3 * chunk + 1] = c_hit;
-        L.blk[3 * chunk + 2] = c_live - c_hit;
+        if (publish) {
+            __hip_atomic_store((uint32_t*)&L.blk[3 * chunk], TD_PUBLISHED | ((uint32_t)c_live << 12) | (uint32_t)c_hit, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        } else {
+            L.blk[3 * chunk + 0] = c_live;
+            L.blk[3 * chunk + 1] = c_hit;
+            L.blk[3 * chunk + 2] = c_live - c_hit;
+        }
     }
 }
 
@@ -342,8 +362,6 @@ struct TdPhase {
     int cls_blocks;            // workgroups that classify; the rest compact
 };
 
-__device__ __forceinline__ int td_chunks(int n) { return (n + FG_SCAN_BLOCK - 1) / FG_SCAN_BLOCK; }
-
 __global__ __launch_bounds__(FG_SCAN_BLOCK) void td_phase_kernel(TdArgs a, TdPhase p) {
     __shared__ long long red[16];
     __shared__ int sc[17];
@@ -352,7 +370,10 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void td_phase_kernel(TdArgs a, TdPha
         for (int i = p.cls_first; i <= p.cls_last; ++i) {
             const int nc = td_chunks(a.layer[i].n);
             if (b < nc) {
-                td_classify_chunk(a.layer[i], b, i >= p.mark_from);
+                uint8_t c;
+                int32_t slot;
+                int c_live, c_hit;
+                td_classify_chunk(a.layer[i], b, i >= p.mark_from, false, c, slot, c_live, c_hit);
                 return;
             }
             b -= nc;
@@ -377,6 +398,75 @@ __global__ __launch_bounds__(FG_SCAN_BLOCK) void td_phase_kernel(TdArgs a, TdPha
             return;
         }
         b -= nc;
+    }
+}
+
+// Classification and compaction of a group of layers in one launch. A chunk's lists start where those of the chunks before
+// it end, so a chunk publishes its counts as one word (zero before the launch: cleared by launch 1) and then polls the words
+// of its predecessors in the same layer. The launch is small enough for all of its workgroups to be resident at once
+// (the host checks), a chunk waits only for chunks with a smaller index, and the poll is bounded anyway.
+__global__ __launch_bounds__(FG_SCAN_BLOCK) void td_fused_kernel(TdArgs a, TdPhase p) {
+    __shared__ long long red[16];
+    __shared__ int sc[17];
+    int b = blockIdx.x;
+    for (int i = p.cls_first; i <= p.cls_last; ++i) {
+        const TdLayer& L = a.layer[i];
+        const int nc = td_chunks(L.n);
+        if (nc == 0) {      // an empty layer has one workgroup, which writes its counts
+            if (b == 0) {
+                if (threadIdx.x < 3) L.counts[threadIdx.x] = 0;
+                return;
+            }
+            b -= 1;
+            continue;
+        }
+        if (b >= nc) {
+            b -= nc;
+            continue;
+        }
+        const int j = b * FG_SCAN_BLOCK + threadIdx.x;
+        const int32_t id_j = (j < L.n && L.normal_ids) ? L.ids[j] : -1;
+        uint8_t c;
+        int32_t slot_j;
+        int c_live, c_hit;
+        td_classify_chunk(L, b, i >= p.mark_from, true, c, slot_j, c_live, c_hit);
+        long long p_live = 0, p_hit = 0;
+        bool lost = false;
+        for (int q = threadIdx.x; q < b; q += FG_SCAN_BLOCK) {
+            uint32_t w = 0;
+            int polls = 0;
+            do {
+                w = __hip_atomic_load((const uint32_t*)&L.blk[3 * q], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (w & TD_PUBLISHED) break;
+                __builtin_amdgcn_s_sleep(2);
+            } while (++polls < TD_SPIN_LIMIT);
+            lost = lost || !(w & TD_PUBLISHED);
+            p_live += (w >> 12) & 0xFFFu;
+            p_hit += w & 0xFFFu;
+        }
+        p_live = fg_block_sum(p_live, red);
+        p_hit = fg_block_sum(p_hit, red);
+        const long long p_norm = p_live - p_hit;
+        const bool any_lost = __syncthreads_or(lost ? 1 : 0) != 0;
+        int t_hit, t_norm;
+        const int r_hit = fg_block_rank(c == CLS_HIT, t_hit, sc);
+        const int r_norm = fg_block_rank(c == CLS_NORMAL, t_norm, sc);
+        if (!any_lost) {
+            if (c == CLS_HIT && L.has_cache) {
+                L.hit_pos[p_hit + r_hit] = j;
+                L.hit_slot[p_hit + r_hit] = slot_j;
+            }
+            if (c == CLS_NORMAL) {
+                L.normal_pos[p_norm + r_norm] = j;
+                if (L.normal_ids) L.normal_ids[p_norm + r_norm] = id_j;
+            }
+        }
+        if (b == nc - 1 && threadIdx.x == 0) {
+            L.counts[0] = any_lost ? -1 : p_live + t_hit + t_norm;
+            L.counts[1] = any_lost ? -1 : p_hit + t_hit;
+            L.counts[2] = any_lost ? -1 : p_norm + t_norm;
+        }
+        return;
     }
 }
 
@@ -619,37 +709,77 @@ extern "C" fg_status_t fg_top_down(const fg_cache_t* cache, int64_t iter, int32_
         // the caller's liveness array below the last layer is cleared by this launch, however short it is
         if (a.layer[i].clear_below) prep = prep > fg_ceil_div(a.layer[i].n_src, 4) ? prep : fg_ceil_div(a.layer[i].n_src, 4);
     }
+    auto chunks = [&](int i) { return (int)fg_ceil_div(a.layer[i].n, FG_SCAN_BLOCK); };
+    // The layers are classified in groups: first every layer the walk settled, then one layer per group. A group whose
+    // chunks (an empty layer counts as one) all fit on the chip at once is classified and compacted by one launch.
+    const bool fuse = fg_tuning(FG_TUNE_TOP_DOWN_WALK) == 1;
+    auto group_blocks = [&](int first, int last) {
+        int total = 0;
+        for (int i = first; i <= last; ++i) total += chunks(i) > 0 ? chunks(i) : 1;
+        return total;
+    };
+    bool any_fused = false;
+    for (int first = 0; first < n_layers;) {
+        const int last = first == 0 ? hops : first;
+        if (fuse && group_blocks(first, last) <= TD_FUSED_MAX_BLOCKS) any_fused = true;
+        first = last + 1;
+    }
+    if (any_fused)      // the words the chunks publish their counts in are cleared by launch 1
+        for (int i = 0; i < n_layers; ++i) prep = prep > chunks(i) ? prep : chunks(i);
     const int walk_blocks = hops > 0 ? (int)fg_ceil_div(a.layer[0].n, TD_WALK_THREADS / 64) : 0;
     int64_t prep_blocks = fg_ceil_div(prep, TD_WALK_THREADS);
     if (prep_blocks > 2048) prep_blocks = 2048;
+    if (any_fused && prep_blocks < 1) prep_blocks = 1;
     if (walk_blocks + prep_blocks > 0) {
-        hipLaunchKernelGGL(td_walk_kernel, dim3((unsigned)(walk_blocks + prep_blocks)), dim3(TD_WALK_THREADS), 0, st, a, hops, walk_blocks);
+        hipLaunchKernelGGL(td_walk_kernel, dim3((unsigned)(walk_blocks + prep_blocks)), dim3(TD_WALK_THREADS), 0, st, a, hops, walk_blocks,
+                           any_fused ? 1 : 0);
         FG_LAUNCH_CHECK("td_walk_kernel");
     }
-    // classification of the layers [lo, hi], then compaction of those beside the classification of the next layer
-    auto chunks = [&](int i) { return (int)fg_ceil_div(a.layer[i].n, FG_SCAN_BLOCK); };
+    // A group that is not fused is classified by one launch and compacted by the next, beside the classification of the group
+    // that follows it.
     int cmp_first = 0, cmp_last = -1;          // classified, not yet compacted
-    int next = 0;                              // first layer not yet classified
-    while (next < n_layers || cmp_first <= cmp_last) {
+    auto compact_pending_with = [&](int cls_first, int cls_last, int mark_from) -> fg_status_t {
         TdPhase p{};
-        p.cls_first = next;
-        p.cls_last = next - 1;
-        if (next < n_layers) p.cls_last = next == 0 ? hops : next;     // the first classification takes every layer the walk settled
-        p.mark_from = (next == 0) ? hops : next;                         // layers above `hops` were marked from by the walk
+        p.cls_first = cls_first;
+        p.cls_last = cls_last;
+        p.mark_from = mark_from;
         p.cmp_first = cmp_first;
         p.cmp_last = cmp_last;
         p.cls_blocks = 0;
-        for (int i = p.cls_first; i <= p.cls_last; ++i) p.cls_blocks += chunks(i);
-        int cmp_blocks = 0;
-        for (int i = p.cmp_first; i <= p.cmp_last; ++i) cmp_blocks += chunks(i) > 0 ? chunks(i) : 1;
+        for (int i = cls_first; i <= cls_last; ++i) p.cls_blocks += chunks(i);
+        const int cmp_blocks = cmp_first <= cmp_last ? group_blocks(cmp_first, cmp_last) : 0;
         if (p.cls_blocks + cmp_blocks > 0) {
             hipLaunchKernelGGL(td_phase_kernel, dim3((unsigned)(p.cls_blocks + cmp_blocks)), dim3(FG_SCAN_BLOCK), 0, st, a, p);
             FG_LAUNCH_CHECK("td_phase_kernel");
         }
-        cmp_first = p.cls_first;
-        cmp_last = p.cls_last;
-        next = p.cls_last + 1 > next ? p.cls_last + 1 : next;
-        if (p.cls_first > p.cls_last) break;   // that launch only compacted: done
+        cmp_first = cls_first;
+        cmp_last = cls_last;
+        return FG_OK;
+    };
+    for (int first = 0; first < n_layers;) {
+        const int last = first == 0 ? hops : first;
+        const int mark_from = first == 0 ? hops : first;      // layers above `hops` were marked from by the walk
+        if (fuse && group_blocks(first, last) <= TD_FUSED_MAX_BLOCKS) {
+            if (cmp_first <= cmp_last) {      // an earlier group still waits for its compaction
+                fg_status_t rc = compact_pending_with(0, -1, 0);
+                if (rc != FG_OK) return rc;
+                cmp_first = 0, cmp_last = -1;
+            }
+            TdPhase p{};
+            p.cls_first = first;
+            p.cls_last = last;
+            p.mark_from = mark_from;
+            hipLaunchKernelGGL(td_fused_kernel, dim3((unsigned)group_blocks(first, last)), dim3(FG_SCAN_BLOCK), 0, st, a, p);
+            FG_LAUNCH_CHECK("td_fused_kernel");
+        } else {
+            fg_status_t rc = compact_pending_with(first, last, mark_from);
+            if (rc != FG_OK) return rc;
+        }
+        first = last + 1;
+    }
+    if (cmp_first <= cmp_last) {
+        fg_status_t rc = compact_pending_with(0, -1, 0);
+        if (rc != FG_OK) return rc;
     }
     return FG_OK;
 }
