@@ -70,8 +70,10 @@ def main():
     ap.add_argument("--backward", action="store_true",
                     help="take the gradient norms of the cache update from the backward pass (softmax cross-entropy on the seeds' "
                          "synthetic labels, layer backward down to layer 1, row norms) instead of the synthetic norms")
-    ap.add_argument("--one-launch-seed-layer", action="store_true",
-                    help="run the seed layer through fg_aggregate_linear (one launch) instead of fg_aggregate + fg_linear")
+    ap.add_argument("--two-launch-seed-layer", action="store_true",
+                    help="run the seed layer as fg_aggregate + fg_linear instead of through fg_aggregate_linear (one launch, the "
+                         "default where the layer's shape allows it: the two measure the same, the one launch needs no buffer "
+                         "for the means)")
     ap.add_argument("--block-positions", action="store_true",
                     help="give the fused loader block 1 with positions as columns (fg_gather_aggregate) instead of node ids "
                          "(fg_gather_aggregate_ids)")
@@ -163,9 +165,8 @@ def main():
     hp, weights, feat = G.make_hotpath(w, use_cache=not args.no_cache, fused_input=not args.no_fuse, log_ring=total + extra + 32,
                                        hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads, model=args.model,
                                        fetch_with_loader=not args.separate_fetch, admit_budget=admit_budget,
-                                       overlap_update=not args.no_overlap_update, overlap_min_rows=65536)
-    if args.one_launch_seed_layer:
-        hp.fuse_small_layers = hp.model == "sage" and not hp.weight_grads
+                                       overlap_update=not args.no_overlap_update, overlap_min_rows=65536,
+                                       fuse_small_layers=not args.two_launch_seed_layer)
     ids_cols = not args.block_positions and not args.no_fuse
     make_batch = (lambda mb, gn, labels: DeviceBatch(mb, None, labels=labels, col_ids=ids_cols)) if args.backward else \
         (lambda mb, gn, labels: DeviceBatch(mb, gn, col_ids=ids_cols))
@@ -577,7 +578,7 @@ def policy_paper_run(w, feat, sampled, args, ids_cols):
     fused = not args.no_fuse
     hp, _, _ = G.make_hotpath(w, feat_table=feat, fused_input=fused, log_ring=total + 32, model=args.model,
                               fetch_with_loader=not args.separate_fetch, overlap_update=not args.no_overlap_update,
-                              overlap_min_rows=65536)
+                              overlap_min_rows=65536, fuse_small_layers=not args.two_launch_seed_layer)
     try:
         batches = [DeviceBatch(mb, gn, col_ids=ids_cols) for mb, gn, _ in sampled[:total]]
         for it in range(first_timed):

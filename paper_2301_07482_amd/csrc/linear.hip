@@ -554,7 +554,8 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
     }
 }
 
-// Few rows (up to 768 tasks, about three per compute unit; measured crossover with the panel kernel near 1000):
+// Few rows (fg_linear takes it up to 288 tasks: measured crossover with the bf16 x 3 panel kernel at 256 columns between
+// 1024 and 1280 rows; fg_aggregate_linear up to 768):
 // one workgroup per task, the K range split over its
 // 8 wavefronts. A wavefront copies only its own rows of the W panel to LDS, fetches its A values in one round of
 // loads, runs its one or two K chunks and leaves a 32 x 32 partial sum in fp64; the partial sums meet in LDS (in the
@@ -744,7 +745,7 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
         const size_t panel_bytes = (size_t)2 * d_in * PL_BN * sizeof(float);
         if (n_src == 0 || n_out == 0) return FG_OK;  // no row can be in range
         const int64_t n_tasks = fg_ceil_div(max_rows, 32) * fg_ceil_div(d_out, PL_BN);
-        if (d_in % KC == 0 && panel_bytes <= 64 * 1024 && (forced == 8 || (forced == 0 && n_tasks <= 768))) {
+        if (d_in % KC == 0 && panel_bytes <= 64 * 1024 && (forced == 8 || (forced == 0 && n_tasks <= 288))) {
             const int n_panels = (int)fg_ceil_div(d_out, PL_BN);
             const size_t lds = panel_bytes > (size_t)SK_PART_BYTES ? panel_bytes : (size_t)SK_PART_BYTES;
             const unsigned grid = (unsigned)(fg_ceil_div(fg_ceil_div(max_rows, 32), 8) * 8 * n_panels);

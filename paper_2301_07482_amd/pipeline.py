@@ -671,7 +671,7 @@ class HotPath:
 
 def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None, p_grad=None, fused_input=False, one_launch_top_down=True, update_all=True, log_ring=256,
                  hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage",
-                 fetch_with_loader=True, admit_budget=None, overlap_update=True, overlap_min_rows=0):
+                 fetch_with_loader=True, admit_budget=None, overlap_update=True, overlap_min_rows=0, fuse_small_layers=False):
     """HotPath for workload `w` with its feature table resident where the workload says."""
     from fg_inputs import device as fdev, workload as wl
     dims = wl.layer_dims(w)
@@ -686,7 +686,7 @@ def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None
                  use_cache=use_cache, fused_input=fused_input, one_launch_top_down=one_launch_top_down, update_all=update_all,
                  fetch_all=update_all, log_ring=log_ring, hot_ids=hot_ids, buffer_bytes=buffer_bytes, backward=backward, weight_grads=weight_grads, stabilization=stabilization, model=model,
                  fetch_with_loader=fetch_with_loader, admit_budget=admit_budget, overlap_update=overlap_update,
-                 overlap_min_rows=overlap_min_rows)
+                 overlap_min_rows=overlap_min_rows, fuse_small_layers=fuse_small_layers)
     return hp, weights, feat_table
 
 

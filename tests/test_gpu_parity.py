@@ -1021,7 +1021,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
                         backward=False, stabilization=0, model="sage", conditioned=False, col_ids=False,
                         fetch_with_loader=True, admit_budget=None, device_sampler=False, overlap_update=True,
-                        lookahead=False, device_counts=False):
+                        lookahead=False, device_counts=False, fuse_small_layers=False):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
@@ -1045,7 +1045,7 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                                              update_all=one_launch_top_down, hot_ids=hot,
                                              buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward, stabilization=stabilization, model=model,
                                              fetch_with_loader=fetch_with_loader, admit_budget=admit_budget,
-                                             overlap_update=overlap_update)
+                                             overlap_update=overlap_update, fuse_small_layers=fuse_small_layers)
     from paper_2301_07482_amd import binding as FGB
     bc = None
     if fs:
@@ -1788,12 +1788,13 @@ def test_iterations_medium(env):
 
 def test_iterations_large_hbm_full_size(env):
     """The benchmarked workload at its full size (111 M nodes, 57 GB table in HBM, 2 x 11.1 M cache slots) in the launch
-    configuration bench.py times (fused loader, whole-pass top-down, fetch and update calls), more iterations than the
+    configuration bench.py times (fused loader, whole-pass top-down, seed layer in one launch, fetch and update calls), more iterations than the
     staleness bound so that entries age out; index work compared in full every iteration, the layer-1 nodes' own
     feature rows on a sample, numerics every 8th iteration."""
     torch, B = env
     w = wl.WORKLOADS["large_hbm"]
-    hits, worst = run_workload_parity(torch, w, 24, check_numeric_every=8, sample_rows=20000, fused=True, col_ids=True, lookahead=True)
+    hits, worst = run_workload_parity(torch, w, 24, check_numeric_every=8, sample_rows=20000, fused=True, col_ids=True, lookahead=True,
+                                      fuse_small_layers=True)
     print(f"large_hbm: {hits} hits, worst rel err {worst:.3e}")
     assert hits > 1000
 
