@@ -135,6 +135,45 @@ def test_lookup_prune_matches_oracle(env, n, n_src, max_deg, seed):
             assert np.array_equal(t_live_src.cpu().numpy().astype(bool), want["live_src"])
             if use_cache and n >= 1000:
                 assert cnt[1] > 0
+            # the same layer through fg_top_down as a list of one layer: with the size as a host integer, and with the arrays
+            # padded by garbage (ids that may be cached, live flags set, row ranges out of range) behind a count in device memory
+            pad = 1500
+            for counted in (False, True):
+                m = n + pad if counted else n
+                g_ids = np.concatenate([ids, r.permutation(N)[:m - n].astype(np.int32)])
+                g_live = np.concatenate([live if use_live else np.ones(n, bool), np.ones(m - n, bool)]).astype(np.uint8)
+                g_start = np.concatenate([start, r.integers(-5, nnz + 5, m - n).astype(np.int32)])
+                g_end = np.concatenate([end, r.integers(-5, nnz + 5, m - n).astype(np.int32)])
+                t_end = dev(torch, g_end)
+                ns = max(n_src, m)      # the layer below is bounded like this one
+                t_live_src = torch.full((ns,), 7, dtype=torch.uint8, device="cuda")
+                t_hit = torch.full((m,), 9, dtype=torch.uint8, device="cuda")
+                t_hp, t_hs, t_np, t_ni = (torch.full((m,), -7, dtype=torch.int32, device="cuda") for _ in range(4))
+                t_cnt = torch.zeros(3, dtype=torch.int64, device="cuda")
+                t_n = dev(torch, np.asarray([n], dtype=np.int64))
+                # (the descriptors hold addresses only: the tensors must outlive the calls)
+                t_ids, t_glive, t_start, t_col = dev(torch, g_ids), dev(torch, g_live), dev(torch, g_start), dev(torch, col)
+                layers = B.top_down_layers([dict(cache_layer=1 if use_cache else 0, ids_dev=t_ids, n=m,
+                                                 live_dev=t_glive if (use_live or counted) else None,
+                                                 row_start_dev=t_start, row_end_dev=t_end, col_dev=t_col, nnz=nnz,
+                                                 n_src=ns, live_src_dev=t_live_src, hit_dev=t_hit, hit_pos_dev=t_hp, hit_slot_dev=t_hs,
+                                                 normal_pos_dev=t_np, normal_ids_dev=t_ni, counts_dev=t_cnt,
+                                                 n_dev=t_n if counted else None)])
+                wsb2 = B.fg_top_down_workspace_bytes(layers)
+                ws2 = torch.zeros(wsb2, dtype=torch.uint8, device="cuda")
+                for _ in range(2):      # twice into the same workspace: every call must leave its marks cleared
+                    t_end.copy_(dev(torch, g_end))
+                    B.fg_top_down(cache if use_cache else None, it, layers, ws2, wsb2, None)
+                cnt = t_cnt.cpu().numpy()
+                assert tuple(cnt) == want["counts"], f"fg_top_down, counted={counted}"
+                assert np.array_equal(t_hit.cpu().numpy()[:n].astype(bool), want["hit"]) and not t_hit[n:].any().item()
+                assert np.array_equal(t_hp.cpu().numpy()[:cnt[1]], want["hit_pos"])
+                assert np.array_equal(t_hs.cpu().numpy()[:cnt[1]], want["hit_slot"])
+                assert np.array_equal(t_np.cpu().numpy()[:cnt[2]], want["normal_pos"])
+                assert np.array_equal(t_ni.cpu().numpy()[:cnt[2]], ids[want["normal_pos"]])
+                assert np.array_equal(t_end.cpu().numpy()[:n], want_end) and np.array_equal(t_end.cpu().numpy()[n:], g_end[n:])
+                assert np.array_equal(t_live_src.cpu().numpy()[:n_src].astype(bool), want["live_src"]) and not t_live_src[n_src:].any().item()
+                assert not ws2[(wsb2 // 2 + 255) // 256 * 256:].any().item(), "the marks must be all zero between calls"
     finally:
         B.fg_cache_destroy(cache)
 
