@@ -126,6 +126,32 @@ def test_argument_validation_needs_no_gpu(B):
     assert code(B.fg_layer_backward_weights, 4096, 10, 512, 4096, 512, 4096, 1024, None, 0, 10, 4096, None, 10, 128, 256, 4096, None,
                 4096, 64) == B.FG_ERR_SHAPE                                                                 # workspace
     assert B.fg_layer_backward_weights_workspace_bytes(67584, 128, 256) >= 256 * 256 * 4
+    # GCN and mixed-precision forms of the layer backward: the same argument list, their own shape rules
+    assert code(bw, kind="gcn", n_src=5) == B.FG_ERR_SHAPE and code(bw, kind="gcn", dh_src_stride=500) == B.FG_ERR_SHAPE
+    assert code(bw, kind="gcn", ws_bytes=100) == B.FG_ERR_SHAPE
+    assert code(bw, kind="bf16", d_out=248) == B.FG_ERR_SHAPE           # d_out % 16
+    assert code(bw, kind="bf16", d_in=132) == B.FG_ERR_SHAPE            # d_in % 8
+    assert code(bw, kind="bf16", W=4100) == B.FG_ERR_INVALID_ARG        # W 16-byte aligned
+    assert code(bw, kind="bf16", h_stride=256) == B.FG_ERR_SHAPE        # bf16 rows of 256 values need 512 bytes
+    assert B.fg_layer_backward_workspace_bytes(10, 10, 128, 256, kind="gcn") < B.fg_layer_backward_workspace_bytes(10, 10, 128, 256)
+    assert B.fg_layer_backward_workspace_bytes(10, 10, 128, 256, kind="bf16") < B.fg_layer_backward_workspace_bytes(10, 10, 128, 256)
+    assert B.fg_layer_backward_workspace_bytes(10, 10, 128, 256, kind="bf16") >= 10 * 2 * 128 * 4 + 10 * 256 * 2
+    wg16 = lambda **k: B.fg_layer_backward_weights_bf16(**{**dict(h_src=4096, n_src=10, src_stride=256, src_dtype=B.FG_BF16, agg=4096,
+                                                                   agg_stride=256, dh=4096, dh_stride=1024, h=None, h_stride=0, n=10,
+                                                                   rows=4096, n_rows=None, max_rows=10, d_in=128, d_out=256, dw=4096,
+                                                                   db=None, ws=4096, ws_bytes=1 << 30), **k})
+    assert code(wg16, dw=None) == B.FG_ERR_INVALID_ARG and code(wg16, ws_bytes=64) == B.FG_ERR_SHAPE
+    assert code(wg16, src_dtype=9) == B.FG_ERR_DTYPE and code(wg16, d_in=132) == B.FG_ERR_SHAPE
+    assert code(wg16, src_dtype=B.FG_F32) == B.FG_ERR_SHAPE             # fp32 rows of 128 values need a stride of 512 bytes
+    lin_wt = lambda **k: B.fg_linear_wt(**{**dict(h_src=4096, n_src=9, src_stride=256, in_dtype=B.FG_BF16, agg=4096, agg_stride=256,
+                                                   rows=None, n_rows=None, max_rows=5, d_in=128, d_out=64, Wt=4096, w_dtype=B.FG_BF16,
+                                                   bias=None, relu=1, h_out=4096, n_out=9, out_stride=128, out_dtype=B.FG_BF16), **k})
+    assert code(lin_wt, w_dtype=B.FG_F32) == B.FG_ERR_DTYPE             # transposed weights are taken in bf16 only
+    assert code(lin_wt, Wt=None) == B.FG_ERR_INVALID_ARG and code(lin_wt, d_in=124) == B.FG_ERR_SHAPE
+    assert code(lin_wt, in_dtype=B.FG_F32) == B.FG_ERR_DTYPE and code(lin_wt, out_stride=64) == B.FG_ERR_SHAPE
+    # the allocation-free lookup refuses what its built-in scratch memory cannot hold
+    assert code(B.fg_lookup_prune_static, None, 0, 0, 4096, B.FG_LOOKUP_PRUNE_STATIC_MAX_N + 1, None, None, None, None, 0, 0, None, None,
+                None, None, 4096, None, 4096) == B.FG_ERR_SHAPE
     assert code(B.fg_cache_set_stabilization, None, 3) == B.FG_ERR_INVALID_ARG
     assert code(B.fg_aggregate_linear, 4096, 4096, 4096, 5, 5, None, None, 5, None, 9, 512, 128, 64, 4096, None, 0, None, 512, 4096, 5,
                 256) == B.FG_ERR_INVALID_ARG                                                                # no h_src
