@@ -671,8 +671,14 @@ fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t n_src, int
  *
  * fg_layer_backward_weights_bf16: the mixed-precision setting. agg and h are bf16, h_src is fp32, fp16 or bf16 (src_dtype;
  * rounded to bf16 as the forward product rounds it); dz is rounded to bf16 before it enters x^T dz, the bias gradient
- * sums the unrounded dz; products, sums and results as above. d_in and d_out multiples of 8. Same workspace size.
+ * sums the unrounded dz. With both operands bf16 the contraction over the computed rows runs on the bf16 matrix cores:
+ * one launch writes x and dz transposed (the contraction index contiguous) into the workspace, the forward matrix-core
+ * kernel multiplies them with fp32 sums over all rows (its loop stops at the device-side row count), a last launch adds
+ * up the bias gradient's partial sums in fp64. d_in and d_out multiples of 8; pointers and strides 4-byte aligned, dw and
+ * db 16-byte. Deterministic.
+ *   ws_dev, ws_bytes    device workspace >= fg_layer_backward_weights_bf16_workspace_bytes(max_rows, d_in, d_out), 16-byte aligned
  */
+size_t fg_layer_backward_weights_bf16_workspace_bytes(int64_t max_rows, int32_t d_in, int32_t d_out);
 fg_status_t fg_layer_backward_weights_bf16(const void* h_src_dev, int32_t n_src, int64_t src_stride, fg_dtype_t src_dtype,
                                            const void* agg_dev, int64_t agg_stride, const float* dh_dev, int64_t dh_stride,
                                            const void* h_dev, int64_t h_stride, int32_t n, const int32_t* rows_dev,

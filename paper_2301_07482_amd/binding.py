@@ -77,6 +77,7 @@ SIGNATURES = {
     "fg_layer_backward_bf16_workspace_bytes": (_sz, [_i32, _i64, _i32, _i32]),
     "fg_layer_backward_bf16": (_i32, [_p, _i64, _p, _i64, _i32, _p, _p, _i64, _p, _p, _p, _p, _p, _p, _p, _i64, _i32, _i32, _i32, _p, _p,
                                       _i64, _p, _p, _sz, _p]),
+    "fg_layer_backward_weights_bf16_workspace_bytes": (_sz, [_i64, _i32, _i32]),
     "fg_layer_backward_weights_bf16": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _i64, _p, _i64, _i32, _p, _p, _i64, _i32, _i32, _p, _p,
                                               _p, _sz, _p]),
 }
@@ -380,6 +381,10 @@ def fg_layer_backward_weights(h_src, n_src, src_stride, agg, agg_stride, dh, dh_
                               d_out, dw, db, ws, ws_bytes, stream=None):
     _check(_lib.fg_layer_backward_weights(ptr(h_src), n_src, src_stride, ptr(agg), agg_stride, ptr(dh), dh_stride, ptr(h), h_stride, n,
                                           ptr(rows), ptr(n_rows), max_rows, d_in, d_out, ptr(dw), ptr(db), ptr(ws), ws_bytes, stream))
+
+
+def fg_layer_backward_weights_bf16_workspace_bytes(max_rows, d_in, d_out):
+    return _lib.fg_layer_backward_weights_bf16_workspace_bytes(max_rows, d_in, d_out)
 
 
 def fg_layer_backward_weights_bf16(h_src, n_src, src_stride, src_dtype, agg, agg_stride, dh, dh_stride, h, h_stride, n, rows, n_rows,

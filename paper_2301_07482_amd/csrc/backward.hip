@@ -228,7 +228,7 @@ BwWs bw_layout(int64_t n, int64_t max_rows, int64_t cols, int64_t d_out, int64_t
 fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype, const void* agg,
                                   int64_t agg_stride, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
                                   int32_t d_in, int32_t d_out, const void* W, const float* bias, int32_t relu, void* h_out,
-                                  int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, hipStream_t st, bool w_nk);
+                                  int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, hipStream_t st, bool w_nk, const int64_t* k_limit_dev = nullptr);
 
 extern "C" fg_status_t fg_softmax_xent_grad(const float* h_dev, int64_t h_stride, const int32_t* labels_dev, int32_t n, int32_t d,
                                             float* dh_dev, int64_t dh_stride, void* stream) {
@@ -419,12 +419,8 @@ constexpr int WG_PAIRS = 3;  // pairs of rows whose loads are issued together
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-// B16: the bf16 setting. agg and h are bf16, h_src is of type src_code (fp32 and fp16 values are rounded to bf16, as the
-// forward product rounds them), dz is rounded to bf16 before it enters the product and summed unrounded for the bias
-// gradient. The products of two bf16 values are exact in fp32, so the fp32 matrix instruction serves both settings.
-template <bool B16>
 __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
-    const char* __restrict__ h_src, int n_src, int64_t src_stride, int src_code, const char* __restrict__ agg, int64_t agg_stride,
+    const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const char* __restrict__ dh, int64_t dh_stride, const char* __restrict__ h, int64_t h_stride, int n,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     float* __restrict__ part_w, float* __restrict__ part_b) {
@@ -446,14 +442,12 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
 
     // This lane's columns. A wavefront's 64 rows of the result are split over its two row blocks by parity and its 128
     // columns over its four column blocks modulo 4, so that a lane's operands for all blocks are adjacent in memory:
-    // X[k][m_pair], X[k][m_pair + 1] (one load) and dz[k][n_quad .. n_quad + 3] (16-byte loads).
+    // X[k][m_pair], X[k][m_pair + 1] (one 8-byte load) and dz[k][n_quad .. n_quad + 3] (16-byte loads).
     // Row l of result block i is then row m_base + 2*l + i, column l of result block j is column n_base + 4*l + j.
     const int m_pair = m_base + 2 * l32;
     const bool a_ok = m_pair < M;              // M is even: both columns exist or neither
     const bool a_self = m_pair < d_in;         // d_in is even: a pair never straddles the two panels
     const int a_col = a_ok ? (a_self ? m_pair : m_pair - d_in) : 0;
-    const bool a_wide = !B16 || (a_self && src_code == FG_F32);   // this lane's pair of X is two fp32 values
-    const bool a_half = B16 && a_self && src_code == FG_F16;      // ... two fp16 values (otherwise two bf16 values)
     const int n_quad = n_base + 4 * l32;
     const bool b_ok = n_quad < N;              // N is a multiple of 4
     const int b_col = b_ok ? n_quad : 0;
@@ -471,12 +465,12 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
         const int64_t ks = kk < k_end ? kk : k_begin;
         return rows ? rows[ks] : (int32_t)ks;
     };
-    // One batch = WG_PAIRS pairs of rows: the loads of a pair, then 8 matrix instructions per pair. Two batches are
+    // One batch = WG_PAIRS pairs of rows: 11 loads per pair and lane, then 8 matrix instructions per pair. Two batches are
     // kept in registers: while one is multiplied the loads of the next are in flight. The row positions are fetched one
     // batch further ahead so that the row loads do not wait for them.
     struct Batch {
-        f32x2 a[WG_PAIRS];      // B16: the raw bits of the pair (one word where the pair is two 16-bit values)
-        f32x4 g[WG_PAIRS], o[WG_PAIRS];   // B16: o holds the four bf16 outputs in its first two words
+        f32x2 a[WG_PAIRS];
+        f32x4 g[WG_PAIRS], o[WG_PAIRS];
         bool ok[WG_PAIRS];
     };
     int32_t r_next[WG_PAIRS];
@@ -492,62 +486,25 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
             r_next[p] = row_of(kk + 2 * WG_PAIRS);
             B.ok[p] = in && r >= 0 && r < n && r < n_src;
             const int64_t rs = B.ok[p] ? r : 0;
-            const char* xs = h_src + rs * src_stride;
-            const char* xa = agg + ks * agg_stride;
-            const char* gr = dh + rs * dh_stride;
-            if constexpr (B16) {
-                if (a_wide) {
-                    B.a[p] = *(const f32x2*)(xs + (int64_t)a_col * 4);
-                } else {
-                    B.a[p][0] = *(const float*)((a_self ? xs : xa) + (int64_t)a_col * 2);
-                    B.a[p][1] = 0.f;
-                }
-                const f32x2 o2 = *(const f32x2*)(h ? h + rs * h_stride + (int64_t)b_col * 2 : gr);
-                B.o[p][0] = o2[0];
-                B.o[p][1] = o2[1];
-            } else {
-                B.a[p] = *(const f32x2*)((a_self ? xs : xa) + (int64_t)a_col * 4);
-                B.o[p] = *(const f32x4*)((h ? h + rs * h_stride : gr) + (int64_t)b_col * 4);
-            }
-            B.g[p] = *(const f32x4*)(gr + (int64_t)b_col * 4);
+            const float* xs = (const float*)(h_src + rs * src_stride);
+            const float* xa = (const float*)(agg + ks * agg_stride);
+            B.a[p] = *(const f32x2*)((a_self ? xs : xa) + a_col);
+            const float* gr = (const float*)(dh + rs * dh_stride);
+            const float* hr = h ? (const float*)(h + rs * h_stride) : gr;
+            B.g[p] = *(const f32x4*)(gr + b_col);
+            B.o[p] = *(const f32x4*)(hr + b_col);
         }
     };
     auto multiply_batch = [&](Batch& B) {
 #pragma unroll
         for (int p = 0; p < WG_PAIRS; ++p) {
-            if constexpr (B16) {
-                float x0, x1;
-                if (a_wide) {
-                    x0 = bw_bf16_value(bw_bf16_bits(B.a[p][0]));
-                    x1 = bw_bf16_value(bw_bf16_bits(B.a[p][1]));
-                } else {
-                    const unsigned int w = __float_as_uint(B.a[p][0]);
-                    if (a_half) {
-                        x0 = bw_bf16_value(bw_bf16_bits(__half2float(__ushort_as_half((unsigned short)(w & 0xFFFFu)))));
-                        x1 = bw_bf16_value(bw_bf16_bits(__half2float(__ushort_as_half((unsigned short)(w >> 16)))));
-                    } else {
-                        x0 = __uint_as_float(w << 16);
-                        x1 = __uint_as_float(w & 0xFFFF0000u);
-                    }
-                }
-                B.a[p][0] = x0;
-                B.a[p][1] = x1;
-            }
 #pragma unroll
             for (int i = 0; i < 2; ++i) B.a[p][i] = (B.ok[p] && a_ok) ? B.a[p][i] : 0.f;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                float act;
-                if constexpr (B16) {
-                    const unsigned int w = __float_as_uint(B.o[p][j >> 1]);
-                    act = (j & 1) ? __uint_as_float(w & 0xFFFF0000u) : __uint_as_float(w << 16);
-                } else {
-                    act = B.o[p][j];
-                }
-                const bool pass = B.ok[p] && b_ok && (h ? act > 0.f : true);
+                const bool pass = B.ok[p] && b_ok && (h ? B.o[p][j] > 0.f : true);
                 B.g[p][j] = pass ? B.g[p][j] : 0.f;
                 colsum[j] += B.g[p][j];
-                if constexpr (B16) B.g[p][j] = bw_bf16_value(bw_bf16_bits(B.g[p][j]));
             }
         }
 #pragma unroll
@@ -635,6 +592,86 @@ __global__ __launch_bounds__(BW_THREADS) void weight_grad_reduce_kernel(const fl
     }
 }
 
+// Mixed precision: the weight gradients as a product on the bf16 matrix cores. Both operands of dW = X^T . dz are bf16 values
+// (the rows of X as the forward product rounded them, dz rounded after the mask), so the contraction over the computed rows
+// is a plain bf16 matrix product; the matrix instruction wants the contraction index contiguous, which for X^T . dz is the
+// row index. This kernel writes both operands transposed, XT [2*d_in x Kp] and DZT [d_out x Kp] in bf16 (Kp = the bound on
+// the rows rounded up to 64; zeros from the row count to the end of its block of 64), 64 x 64 tiles through LDS, reads and
+// writes coalesced. The dz tiles also leave the column sums of the unrounded dz of their 64 rows (the bias gradient's
+// partial sums; zeros for blocks beyond the rows there are).
+constexpr int ST_TILE = 64;
+__global__ __launch_bounds__(BW_THREADS) void weight_grad_stage_bf16_kernel(
+    const char* __restrict__ h_src, int n_src, int64_t src_stride, int src_code, const char* __restrict__ agg, int64_t agg_stride,
+    const char* __restrict__ dh, int64_t dh_stride, const char* __restrict__ h, int64_t h_stride, int n,
+    const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out, int tiles_x,
+    unsigned short* __restrict__ xt, unsigned short* __restrict__ dzt, int64_t kp, float* __restrict__ part_b) {
+    __shared__ unsigned short tile[ST_TILE][ST_TILE + 2];
+    __shared__ float sums[BW_THREADS / ST_TILE][ST_TILE];
+    int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
+    if (n_rows > max_rows) n_rows = max_rows;
+    const int64_t k0 = (int64_t)blockIdx.x * ST_TILE;
+    const bool is_x = (int)blockIdx.y < tiles_x;
+    const int c0 = (is_x ? (int)blockIdx.y : (int)blockIdx.y - tiles_x) * ST_TILE;   // first column of X (of 2*d_in) or of dz
+    const int n_cols = is_x ? 2 * d_in : d_out;
+    const int tx = threadIdx.x & (ST_TILE - 1), ty = threadIdx.x / ST_TILE;          // 64 x 4
+    const int c = c0 + tx;
+    if (k0 >= n_rows) {      // nothing to stage: only the bias gradient's partial sums need their zeros
+        if (!is_x && ty == 0 && c < d_out) part_b[(int64_t)blockIdx.x * d_out + c] = 0.f;
+        return;
+    }
+    float colsum = 0.f;
+    for (int rr = ty; rr < ST_TILE; rr += BW_THREADS / ST_TILE) {
+        const int64_t k = k0 + rr;
+        float v = 0.f;
+        if (k < n_rows && c < n_cols) {
+            const int32_t r = rows ? rows[k] : (int32_t)k;
+            if (r >= 0 && r < n) {
+                if (is_x) {
+                    if (c < d_in) {
+                        if (r < n_src) {
+                            const char* row = h_src + (int64_t)r * src_stride;
+                            v = src_code == FG_F32 ? ((const float*)row)[c]
+                                : src_code == FG_F16 ? __half2float(__ushort_as_half(((const unsigned short*)row)[c]))
+                                                     : bw_bf16_value(((const unsigned short*)row)[c]);
+                        }
+                    } else {
+                        v = bw_bf16_value(((const unsigned short*)(agg + k * agg_stride))[c - d_in]);
+                    }
+                } else {
+                    v = ((const float*)(dh + (int64_t)r * dh_stride))[c];
+                    if (h && !(bw_bf16_value(((const unsigned short*)(h + (int64_t)r * h_stride))[c]) > 0.f)) v = 0.f;
+                    colsum += v;
+                }
+            }
+        }
+        tile[rr][tx] = bw_bf16_bits(v);
+    }
+    if (!is_x) sums[ty][tx] = colsum;
+    __syncthreads();
+    if (!is_x && ty == 0 && c < d_out) {
+        float t = 0.f;
+#pragma unroll
+        for (int q = 0; q < BW_THREADS / ST_TILE; ++q) t += sums[q][tx];
+        part_b[(int64_t)blockIdx.x * d_out + c] = t;
+    }
+    unsigned short* out = is_x ? xt : dzt;
+    for (int cc = ty; cc < ST_TILE; cc += BW_THREADS / ST_TILE)
+        if (c0 + cc < n_cols) out[(int64_t)(c0 + cc) * kp + k0 + tx] = tile[tx][cc];
+}
+
+struct WgStage {
+    int64_t kp;
+    size_t dzt, part_b, total;
+};
+WgStage wg_stage_plan(int64_t max_rows, int64_t d_in, int64_t d_out) {
+    WgStage p;
+    p.kp = fg_ceil_div(max_rows > 0 ? max_rows : 1, ST_TILE) * ST_TILE;
+    p.dzt = fg_align_up((size_t)(2 * d_in) * p.kp * 2, 256);
+    p.part_b = p.dzt + fg_align_up((size_t)d_out * p.kp * 2, 256);
+    p.total = p.part_b + fg_align_up((size_t)(p.kp / ST_TILE) * d_out * 4, 256);
+    return p;
+}
+
 struct WgPlan {
     int n_chunks, rows_per_chunk, tiles_m, tiles_n;
     size_t part_b, total;
@@ -663,24 +700,21 @@ extern "C" size_t fg_layer_backward_weights_workspace_bytes(int64_t max_rows, in
     return wg_plan(max_rows, d_in, d_out).total;
 }
 
-static fg_status_t weights_backward_launch(const char* who, bool b16, const void* h_src_dev, int32_t n_src, int64_t src_stride,
-                                           fg_dtype_t src_dtype, const void* agg_dev, int64_t agg_stride, const float* dh_dev,
-                                           int64_t dh_stride, const void* h_dev, int64_t h_stride, int32_t n, const int32_t* rows_dev,
-                                           const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, float* dw_dev,
-                                           float* db_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t n_src, int64_t src_stride, const float* agg_dev,
+                                                 int64_t agg_stride, const float* dh_dev, int64_t dh_stride, const float* h_dev,
+                                                 int64_t h_stride, int32_t n, const int32_t* rows_dev, const int64_t* n_rows_dev,
+                                                 int64_t max_rows, int32_t d_in, int32_t d_out, float* dw_dev, float* db_dev,
+                                                 void* ws_dev, size_t ws_bytes, void* stream) {
+    const char* who = "fg_layer_backward_weights";
     if (n < 0 || n_src < 0 || max_rows < 0 || d_in <= 0 || d_out <= 0)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (n %d, n_src %d, max_rows %lld, d_in %d, d_out %d)", who, n, n_src, (long long)max_rows, d_in, d_out);
     if (!dw_dev) FG_FAIL(FG_ERR_INVALID_ARG, "%s: dw_dev is NULL", who);
-    if (src_dtype != FG_F32 && src_dtype != FG_F16 && src_dtype != FG_BF16) FG_FAIL(FG_ERR_DTYPE, "%s: h_src must be fp32, fp16 or bf16", who);
-    if (!b16 && src_dtype != FG_F32) FG_FAIL(FG_ERR_DTYPE, "%s: h_src must be fp32", who);
-    const int64_t src_esz = src_dtype == FG_F32 ? 4 : 2, esz = b16 ? 2 : 4;
-    const int mult = b16 ? 8 : 4;     // a lane's loads stay 4-, 8- or 16-byte aligned
-    if (d_out % mult) FG_FAIL(FG_ERR_SHAPE, "%s: d_out = %d must be a multiple of %d", who, d_out, mult);
+    if (d_out % 4) FG_FAIL(FG_ERR_SHAPE, "%s: d_out = %d must be a multiple of 4", who, d_out);
     if (((uintptr_t)dw_dev | (uintptr_t)db_dev) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: dw_dev and db_dev must be 16-byte aligned", who);
     if (max_rows > 0 && n > 0 && n_src > 0 && (!h_src_dev || !agg_dev || !dh_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
-    if (src_stride < (int64_t)d_in * src_esz || agg_stride < (int64_t)d_in * esz || dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * esz))
+    if (src_stride < (int64_t)d_in * 4 || agg_stride < (int64_t)d_in * 4 || dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * 4))
         FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
-    if (d_in % mult) FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d must be a multiple of %d", who, d_in, mult);
+    if (d_in % 4) FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d must be a multiple of 4", who, d_in);
     if (((uintptr_t)h_src_dev | (uintptr_t)agg_dev | (uintptr_t)dh_dev | (uintptr_t)h_dev | (uintptr_t)src_stride | (uintptr_t)agg_stride |
          (uintptr_t)dh_stride | (uintptr_t)h_stride) & 15)
         FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_src, agg, dh, h and their strides must be 16-byte aligned", who);
@@ -693,15 +727,9 @@ static fg_status_t weights_backward_launch(const char* who, bool b16, const void
     float* part_b = (float*)((char*)ws_dev + P.part_b);
     // without rows (or without anything they could index) every chunk is empty and the partials are zeros
     const int64_t rows_bound = (n > 0 && n_src > 0) ? max_rows : 0;
-    const dim3 grid((unsigned)P.n_chunks, (unsigned)P.tiles_m, (unsigned)P.tiles_n);
-    if (b16)
-        hipLaunchKernelGGL(weight_grad_partial_kernel<true>, grid, dim3(WG_THREADS), 0, st, (const char*)h_src_dev, n_src, src_stride,
-                           (int)src_dtype, (const char*)agg_dev, agg_stride, (const char*)dh_dev, dh_stride, (const char*)h_dev, h_stride, n,
-                           rows_dev, n_rows_dev, rows_bound, d_in, d_out, part_w, part_b);
-    else
-        hipLaunchKernelGGL(weight_grad_partial_kernel<false>, grid, dim3(WG_THREADS), 0, st, (const char*)h_src_dev, n_src, src_stride,
-                           (int)src_dtype, (const char*)agg_dev, agg_stride, (const char*)dh_dev, dh_stride, (const char*)h_dev, h_stride, n,
-                           rows_dev, n_rows_dev, rows_bound, d_in, d_out, part_w, part_b);
+    hipLaunchKernelGGL(weight_grad_partial_kernel, dim3((unsigned)P.n_chunks, (unsigned)P.tiles_m, (unsigned)P.tiles_n), dim3(WG_THREADS), 0, st,
+                       (const char*)h_src_dev, n_src, src_stride, (const char*)agg_dev, agg_stride, (const char*)dh_dev, dh_stride,
+                       (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, rows_bound, d_in, d_out, part_w, part_b);
     FG_LAUNCH_CHECK("weight_grad_partial_kernel");
     const int64_t mn = (int64_t)2 * d_in * d_out;
     const int w_blocks = (int)fg_ceil_div(mn, 128), b_blocks = (int)fg_ceil_div(d_out, 128);
@@ -711,14 +739,9 @@ static fg_status_t weights_backward_launch(const char* who, bool b16, const void
     return FG_OK;
 }
 
-extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t n_src, int64_t src_stride, const float* agg_dev,
-                                                 int64_t agg_stride, const float* dh_dev, int64_t dh_stride, const float* h_dev,
-                                                 int64_t h_stride, int32_t n, const int32_t* rows_dev, const int64_t* n_rows_dev,
-                                                 int64_t max_rows, int32_t d_in, int32_t d_out, float* dw_dev, float* db_dev,
-                                                 void* ws_dev, size_t ws_bytes, void* stream) {
-    return weights_backward_launch("fg_layer_backward_weights", false, h_src_dev, n_src, src_stride, FG_F32, agg_dev, agg_stride, dh_dev,
-                                   dh_stride, h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_in, d_out, dw_dev, db_dev, ws_dev,
-                                   ws_bytes, stream);
+extern "C" size_t fg_layer_backward_weights_bf16_workspace_bytes(int64_t max_rows, int32_t d_in, int32_t d_out) {
+    if (max_rows < 0 || d_in <= 0 || d_out <= 0) return 0;
+    return wg_stage_plan(max_rows, d_in, d_out).total;
 }
 
 extern "C" fg_status_t fg_layer_backward_weights_bf16(const void* h_src_dev, int32_t n_src, int64_t src_stride, fg_dtype_t src_dtype,
@@ -726,7 +749,57 @@ extern "C" fg_status_t fg_layer_backward_weights_bf16(const void* h_src_dev, int
                                                       const void* h_dev, int64_t h_stride, int32_t n, const int32_t* rows_dev,
                                                       const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out,
                                                       float* dw_dev, float* db_dev, void* ws_dev, size_t ws_bytes, void* stream) {
-    return weights_backward_launch("fg_layer_backward_weights_bf16", true, h_src_dev, n_src, src_stride, src_dtype, agg_dev, agg_stride,
-                                   dh_dev, dh_stride, h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_in, d_out, dw_dev, db_dev,
-                                   ws_dev, ws_bytes, stream);
+    const char* who = "fg_layer_backward_weights_bf16";
+    if (n < 0 || n_src < 0 || max_rows < 0 || d_in <= 0 || d_out <= 0)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (n %d, n_src %d, max_rows %lld, d_in %d, d_out %d)", who, n, n_src, (long long)max_rows, d_in, d_out);
+    if (!dw_dev) FG_FAIL(FG_ERR_INVALID_ARG, "%s: dw_dev is NULL", who);
+    if (src_dtype != FG_F32 && src_dtype != FG_F16 && src_dtype != FG_BF16) FG_FAIL(FG_ERR_DTYPE, "%s: h_src must be fp32, fp16 or bf16", who);
+    const int64_t src_esz = src_dtype == FG_F32 ? 4 : 2;
+    if (d_in % 8 || d_out % 8) FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d and d_out = %d must be multiples of 8", who, d_in, d_out);
+    if (((uintptr_t)dw_dev | (uintptr_t)db_dev) & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: dw_dev and db_dev must be 16-byte aligned", who);
+    if (max_rows > 0 && n > 0 && n_src > 0 && (!h_src_dev || !agg_dev || !dh_dev)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
+    if (src_stride < (int64_t)d_in * src_esz || agg_stride < (int64_t)d_in * 2 || dh_stride < (int64_t)d_out * 4 || (h_dev && h_stride < (int64_t)d_out * 2))
+        FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
+    if (((uintptr_t)h_src_dev | (uintptr_t)agg_dev | (uintptr_t)dh_dev | (uintptr_t)h_dev | (uintptr_t)src_stride | (uintptr_t)agg_stride |
+         (uintptr_t)dh_stride | (uintptr_t)h_stride) & 3)
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_src, agg, dh, h and their strides must be 4-byte aligned", who);
+    const WgStage P = wg_stage_plan(max_rows, d_in, d_out);
+    if (!ws_dev || ws_bytes < P.total) FG_FAIL(FG_ERR_SHAPE, "%s: workspace of %zu bytes given, %zu needed", who, ws_bytes, P.total);
+    if ((uintptr_t)ws_dev & 15) FG_FAIL(FG_ERR_INVALID_ARG, "%s: the workspace must be 16-byte aligned", who);
+    fg_clear_error();
+    hipStream_t st = (hipStream_t)stream;
+    unsigned short* xt = (unsigned short*)ws_dev;
+    unsigned short* dzt = (unsigned short*)((char*)ws_dev + P.dzt);
+    float* part_b = (float*)((char*)ws_dev + P.part_b);
+    // without rows (or without anything they could index) nothing is staged and the product below is over nothing
+    const int64_t rows_bound = (n > 0 && n_src > 0) ? max_rows : 0;
+    const int tiles_k = (int)(P.kp / ST_TILE), tiles_x = (int)fg_ceil_div(2 * d_in, ST_TILE), tiles_z = (int)fg_ceil_div(d_out, ST_TILE);
+    hipLaunchKernelGGL(weight_grad_stage_bf16_kernel, dim3((unsigned)tiles_k, (unsigned)(tiles_x + tiles_z)), dim3(BW_THREADS), 0, st,
+                       (const char*)h_src_dev, n_src, src_stride, (int)src_dtype, (const char*)agg_dev, agg_stride, (const char*)dh_dev,
+                       dh_stride, (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, rows_bound, d_in, d_out, tiles_x, xt, dzt, P.kp,
+                       part_b);
+    FG_LAUNCH_CHECK("weight_grad_stage_bf16_kernel");
+    // dW [2*d_in x d_out] = XT . DZT^T: the forward kernel with XT's rows as its rows (both halves of its K from the one
+    // matrix), DZT as the transposed weights, K = the rows there are (a count in device memory, or the bound)
+    const int64_t half_k = P.kp / 2;
+    const int64_t* k_limit = nullptr;
+    // the count the K loop stops at must be min(*n_rows_dev, rows_bound): the staging kernel zero-fills up to the end of
+    // that block of 64; with a host-side bound only, the whole of Kp is valid (zeros beyond the rows)
+    if (n_rows_dev && rows_bound == max_rows) k_limit = n_rows_dev;
+    if (rows_bound == 0) {      // nothing staged: dW = 0 without touching the (unwritten) operands
+        fg_status_t rc = fg_launch_fill_i32((int32_t*)dw_dev, (int64_t)2 * d_in * d_out, 0, st);
+        if (rc != FG_OK) return rc;
+    } else {
+        fg_status_t rc = fg_launch_linear_bf16(xt, 2 * d_in, P.kp * 2, FG_BF16, xt + half_k, P.kp * 2, nullptr, nullptr, 2 * d_in,
+                                               (int32_t)half_k, d_out, dzt, nullptr, 0, dw_dev, 2 * d_in, (int64_t)d_out * 4, FG_F32, st,
+                                               true, k_limit);
+        if (rc != FG_OK) return rc;
+    }
+    if (db_dev) {
+        const int b_blocks = (int)fg_ceil_div(d_out, 128);
+        hipLaunchKernelGGL(weight_grad_reduce_kernel, dim3((unsigned)b_blocks), dim3(BW_THREADS), 0, st, part_b, part_b, tiles_k, (int64_t)0,
+                           d_out, 0, dw_dev, db_dev);
+        FG_LAUNCH_CHECK("weight_grad_reduce_kernel");
+    }
+    return FG_OK;
 }

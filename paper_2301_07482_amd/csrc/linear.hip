@@ -715,7 +715,7 @@ fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_
                                   const void* agg, int64_t agg_stride, const int32_t* rows_dev,
                                   const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
                                   const float* bias, int32_t relu, void* h_out, int32_t n_out, int64_t out_stride,
-                                  fg_dtype_t out_dtype, hipStream_t st, bool w_nk);
+                                  fg_dtype_t out_dtype, hipStream_t st, bool w_nk, const int64_t* k_limit_dev = nullptr);
 
 extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype,
                                  const void* agg, int64_t agg_stride, const int32_t* rows_dev,

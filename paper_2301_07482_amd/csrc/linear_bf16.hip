@@ -62,7 +62,7 @@ __global__ __launch_bounds__(64 * hb_waves(HB_M, HB_N), hb_waves(HB_M, HB_N) == 
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     const unsigned short* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
-    int64_t out_stride, int n_tiles) {
+    int64_t out_stride, int n_tiles, const int64_t* __restrict__ k_limit_dev) {
     extern __shared__ __attribute__((aligned(16))) unsigned short hb_lds[];
     constexpr int HB_WAVES = hb_waves(HB_M, HB_N), HB_THREADS = 64 * HB_WAVES;
     constexpr int STAGE = (HB_M + HB_N) * LDH;    // halfwords per buffer: A rows, then the columns of W
@@ -240,7 +240,14 @@ __global__ __launch_bounds__(64 * hb_waves(HB_M, HB_N), hb_waves(HB_M, HB_N) == 
         }
     };
 
-    const int nk = (K + HB_K - 1) / HB_K;
+    // k_limit_dev (optional): only the first *k_limit_dev values of k count (the caller guarantees zeros from there to the end
+    // of that K step), so the K loop stops there: the contraction length is then a count in device memory
+    int nk = (K + HB_K - 1) / HB_K;
+    if (k_limit_dev) {
+        const int64_t lim = *k_limit_dev;
+        const int64_t steps = lim <= 0 ? 0 : (lim + HB_K - 1) / HB_K;
+        if (steps < nk) nk = (int)steps;
+    }
     Regs R0, R1;
     load_step(0, R0);
     if (nk > 1) load_step(HB_K, R1);
@@ -294,7 +301,7 @@ fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_
                                   const void* agg, int64_t agg_stride, const int32_t* rows_dev,
                                   const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
                                   const float* bias, int32_t relu, void* h_out, int32_t n_out, int64_t out_stride,
-                                  fg_dtype_t out_dtype, hipStream_t st, bool w_nk) {
+                                  fg_dtype_t out_dtype, hipStream_t st, bool w_nk, const int64_t* k_limit_dev) {
     if (in_dtype != FG_F16 && in_dtype != FG_BF16) FG_FAIL(FG_ERR_DTYPE, "fg_linear: bf16 weights need fp16 or bf16 inputs");
     if (out_dtype != FG_BF16 && out_dtype != FG_F32) FG_FAIL(FG_ERR_DTYPE, "fg_linear: bf16 weights give bf16 or fp32 outputs");
     if (d_in % 8 || d_out % 8) FG_FAIL(FG_ERR_SHAPE, "fg_linear: d_in = %d and d_out = %d must be multiples of 8 for 16-bit types", d_in, d_out);
@@ -320,7 +327,7 @@ fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_
 #define FG_LB4(F16, OBF, TM, TN, NK)                                                                                       \
     hipLaunchKernelGGL((linear_bf16_kernel<F16, OBF, TM, TN, NK>), dim3(grid), dim3(64 * hb_waves(TM, TN)), hb_lds_bytes(TM, TN), st, \
                        (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, \
-                       d_in, d_out, (const unsigned short*)W, bias, relu, (char*)h_out, n_out, out_stride, ny)
+                       d_in, d_out, (const unsigned short*)W, bias, relu, (char*)h_out, n_out, out_stride, ny, k_limit_dev)
 #define FG_LB3(F16, OBF, TM, TN)         \
     do {                                 \
         if (w_nk)                        \

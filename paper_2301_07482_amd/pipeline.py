@@ -298,7 +298,8 @@ class HotPath:
                 w_rows = [None] + [(1 if model == "gcn" else 2) * dims[l - 1] for l in range(1, L + 1)]
                 self.dW = [None] + [torch.zeros((w_rows[l], dims[l]), dtype=torch.float32, device=dev) for l in range(1, L + 1)]
                 self.db = [None] + [torch.zeros(dims[l], dtype=torch.float32, device=dev) for l in range(1, L + 1)]
-                self.ws_wg_bytes = max(B.fg_layer_backward_weights_workspace_bytes(n[l], dims[l - 1], dims[l]) for l in range(1, L + 1))
+                wg_bytes = B.fg_layer_backward_weights_bf16_workspace_bytes if self.bw_kind == "bf16" else B.fg_layer_backward_weights_workspace_bytes
+                self.ws_wg_bytes = max(wg_bytes(n[l], dims[l - 1], dims[l]) for l in range(1, L + 1))
                 self.ws_wg = torch.zeros(self.ws_wg_bytes + 256, dtype=torch.uint8, device=dev)
         self.cache = None
         self.feature_side = False

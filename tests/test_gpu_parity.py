@@ -983,8 +983,8 @@ def test_layer_backward_weights_bf16_match_oracle(env, src, d_in, d_out, n, n_ro
     if n_rows:
         rows_dev[:n_rows] = dev(torch, rows)
     cnt = dev(torch, np.asarray([n_rows], dtype=np.int64))
-    wsb = B.fg_layer_backward_weights_workspace_bytes(n, d_in, d_out)
-    ws = torch.full((wsb,), 255, dtype=torch.uint8, device="cuda")
+    wsb = B.fg_layer_backward_weights_bf16_workspace_bytes(n, d_in, d_out)
+    ws = torch.full((wsb,), 255, dtype=torch.uint8, device="cuda")           # NaN patterns: whatever is read must have been written
     t_dw = torch.full((2 * d_in, d_out), 3.0, dtype=torch.float32, device="cuda")
     t_db = torch.full((d_out,), 3.0, dtype=torch.float32, device="cuda")
     ssz = 4 if src == "f32" else 2
