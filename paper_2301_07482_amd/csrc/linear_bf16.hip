@@ -103,27 +103,25 @@ __global__ __launch_bounds__(64 * hb_waves(HB_M, HB_N), hb_waves(HB_M, HB_N) == 
     // (the k pair runs fastest over the lanes: their 32-bit transposed writes then fall on different LDS banks)
     const int b_kp = t % B_PAIRS;    // k pairs b_kp + B_PAIRS * q: rows 2 kp, 2 kp + 1
     const int b_nc = t / B_PAIRS;    // columns 8 b_nc .. 8 b_nc + 7
-    // per thread: the positions of its A rows (32 bits each) and one base address per operand; the rows of a thread lie
-    // A_ROWS apart, so the addresses of its other loads differ from the base by multiples the whole workgroup shares
-    int32_t a_row[A_PASSES];
+    // per thread: the positions of its A rows and, relative to the tile's first mean row / first weight column (which always
+    // exist), the rows of its other loads: 32 bits each; a row or column that does not exist reads the first one instead
+    int32_t a_row[A_PASSES], agg_rel[A_PASSES];
     const int32_t r_first = row_of[0];          // the tile's first row exists (m0 < n_rows), its position may still be out of range
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
-        const int32_t r = row_of[a_m + A_ROWS * i];
+        const int m = a_m + A_ROWS * i;
+        const int32_t r = row_of[m];
         a_row[i] = r >= 0 ? r : (r_first >= 0 ? r_first : 0);
+        agg_rel[i] = m0 + m < n_rows ? m : 0;   // list entries below the count lie within the caller's max_rows
     }
-    // mean rows m0 + a_m + A_ROWS * i: rows beyond the list are only read if they lie within the caller's max_rows
-    const char* agg_base = agg + (m0 + a_m) * agg_stride;
-    bool agg_there[A_PASSES];
-#pragma unroll
-    for (int i = 0; i < A_PASSES; ++i) agg_there[i] = m0 + a_m + A_ROWS * i < max_rows;
+    const char* agg_first = agg + m0 * agg_stride;
     const bool b_col_ok = (n0 + 8 * b_nc) < d_out;
     const unsigned short* w_col = W + (b_col_ok ? n0 + 8 * b_nc : 0);        // [K x N]
-    const unsigned short* w_base = W + (int64_t)(n0 + a_m) * K;              // [N x K]: column n0 + a_m + A_ROWS * i
-    bool w_ok[W_NK ? B_PASSES : 1];
+    const unsigned short* w_first = W + (int64_t)n0 * K;                      // [N x K]: column n0 (n0 < d_out)
+    int32_t w_rel[W_NK ? B_PASSES : 1];
     if constexpr (W_NK) {
 #pragma unroll
-        for (int i = 0; i < B_PASSES; ++i) w_ok[i] = n0 + a_m + A_ROWS * i < d_out;
+        for (int i = 0; i < B_PASSES; ++i) w_rel[i] = n0 + a_m + A_ROWS * i < d_out ? a_m + A_ROWS * i : 0;
     }
 
     struct Regs {
@@ -135,13 +133,13 @@ __global__ __launch_bounds__(64 * hb_waves(HB_M, HB_N), hb_waves(HB_M, HB_N) == 
         const int64_t a_off = (int64_t)(ka < K ? (own ? ka : ka - d_in) : 0) * 2;
 #pragma unroll
         for (int i = 0; i < A_PASSES; ++i) {
-            const char* from = own ? h_src + (int64_t)a_row[i] * src_stride : agg_base + (agg_there[i] ? (int64_t)(A_ROWS * i) * agg_stride : 0);
+            const char* from = own ? h_src + (int64_t)a_row[i] * src_stride : agg_first + (int64_t)agg_rel[i] * agg_stride;
             R.a[i] = *(const u32x4*)(from + a_off);
         }
         if constexpr (W_NK) {
             const int kw = ka < K ? ka : 0;
 #pragma unroll
-            for (int i = 0; i < B_PASSES; ++i) R.b[i] = *(const u32x4*)(w_base + (w_ok[i] ? (int64_t)(A_ROWS * i) * K : 0) + kw);
+            for (int i = 0; i < B_PASSES; ++i) R.b[i] = *(const u32x4*)(w_first + (int64_t)w_rel[i] * K + kw);
         } else {
 #pragma unroll
             for (int q = 0; q < B_PASSES; ++q)
@@ -313,7 +311,7 @@ fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_
     if (((uintptr_t)h_out | (uintptr_t)out_stride) & (uintptr_t)(osz - 1) || ((uintptr_t)bias & 3))
         FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: h_out, its stride and bias must be aligned to their element size");
     fg_clear_error();
-    if (max_rows == 0) return FG_OK;
+    if (max_rows == 0 || n_src == 0 || n_out == 0) return FG_OK;     // no row can be in range
     // tile by the number of workgroups the bound on the rows gives (the rows there are may be a fraction of it): the large
     // tile once it fills most of the chip, else the small one, whose many workgroups hide each other's load latency
     const int64_t t128 = fg_ceil_div(max_rows, 128) * fg_ceil_div(d_out, 128);
