@@ -74,6 +74,9 @@ def main():
                     help="run the seed layer as fg_aggregate + fg_linear instead of through fg_aggregate_linear (one launch, the "
                          "default where the layer's shape allows it: the two measure the same, the one launch needs no buffer "
                          "for the means)")
+    ap.add_argument("--copy-own-rows", action="store_true",
+                    help="let the loader copy the layer-1 nodes' own feature rows out for the dense update (fg_linear) instead of "
+                         "that update reading them from the table by node id (fg_linear_ids, the default for an fp32 table in HBM)")
     ap.add_argument("--block-positions", action="store_true",
                     help="give the fused loader block 1 with positions as columns (fg_gather_aggregate) instead of node ids "
                          "(fg_gather_aggregate_ids)")
@@ -166,7 +169,7 @@ def main():
                                        hot_ids=hot, buffer_bytes=buffer_bytes, backward=args.backward, weight_grads=args.weight_grads, model=args.model,
                                        fetch_with_loader=not args.separate_fetch, admit_budget=admit_budget,
                                        overlap_update=not args.no_overlap_update, overlap_min_rows=65536,
-                                       fuse_small_layers=not args.two_launch_seed_layer)
+                                       fuse_small_layers=not args.two_launch_seed_layer, copy_own_rows=args.copy_own_rows)
     ids_cols = not args.block_positions and not args.no_fuse
     make_batch = (lambda mb, gn, labels: DeviceBatch(mb, None, labels=labels, col_ids=ids_cols)) if args.backward else \
         (lambda mb, gn, labels: DeviceBatch(mb, gn, col_ids=ids_cols))
@@ -280,6 +283,7 @@ def main():
     feat_row = w.feat_dim * esz[w.feat_dtype]
     agg_row = w.feat_dim * (4 if w.compute_dtype == "f32" else 2)
     gather_bytes, n_input, dom_kernel = loader_bytes(hp, w, batches, roof_it, counts, not args.no_fuse, ids_cols, args.model)
+    own_by_linear = hp.own_rows_from_table(batches[roof_it[0]])
     # rows the loader found on the feature side instead of reading them from the table (the placed rows lie beyond the
     # rings, so which nodes are there does not change during the run)
     from_buffer = 0.0
@@ -451,7 +455,9 @@ def main():
                        and not hp.feature_side and hp.one_launch_top_down) else "at the start of the step",
                    "update_selection": "second stream, beside the layers" if (hp.overlap_update and not args.backward and not args.no_cache
                                                                               and not args.per_layer_update and not hp.feature_side) else "after the layers",
-                   "block1_columns": "node ids" if ids_cols else "positions", "seed": w.seed},
+                   "block1_columns": "node ids" if ids_cols else "positions",
+                   "own_rows_layer1": "read from the table by the dense update (fg_linear_ids)" if own_by_linear
+                   else "copied out by the loader", "seed": w.seed},
         "prefill_steps": prefill,
         "roofline": roofline,
         "roofline_2": roofline_2,
@@ -552,9 +558,13 @@ def loader_bytes(hp, w, batches, its, counts, fused, ids_cols, model):
     # not normal have end = start).
     edges = [float((batches[it].end[1] - batches[it].start[1]).sum().item()) for it in its]
     own_row = (4 + feat_row) if model == "gcn" else (4 + 2 * feat_row)   # GCN: the own row enters the mean, no copy
+    own_by_linear = hp.own_rows_from_table(batches[its[0]])               # the dense update reads the own rows itself
+    if own_by_linear:
+        own_row = 0
     per_edge = (4 if ids_cols and not hp.feature_side and model == "sage" else 8) + feat_row   # column (+ position -> id) + row
     gather_bytes = float(np.mean([e * per_edge + c[1][2] * (12 + agg_row + own_row) for e, c in zip(edges, counts)]))
-    n_input = float(np.mean(edges)) + float(np.mean([c[1][2] for c in counts]))   # table rows read (edges + own rows)
+    # table rows read (edges + own rows: the latter by the loader, or by the dense update of layer 1)
+    n_input = float(np.mean(edges)) + float(np.mean([c[1][2] for c in counts]))
     kernel = "aggregate_mean_kernel<.., true> (fg_gather_aggregate: loader fused with the layer-1 mean)"
     fetch_rides = (ids_cols and hp.fetch_with_loader and hp.fetch_all and hp.cache is not None and hp.use_cache
                    and model == "sage" and not hp.feature_side and not hp.one_launch(1, batches[its[0]].n[1]))
@@ -578,7 +588,7 @@ def policy_paper_run(w, feat, sampled, args, ids_cols):
     fused = not args.no_fuse
     hp, _, _ = G.make_hotpath(w, feat_table=feat, fused_input=fused, log_ring=total + 32, model=args.model,
                               fetch_with_loader=not args.separate_fetch, overlap_update=not args.no_overlap_update,
-                              overlap_min_rows=65536, fuse_small_layers=not args.two_launch_seed_layer)
+                              overlap_min_rows=65536, fuse_small_layers=not args.two_launch_seed_layer, copy_own_rows=args.copy_own_rows)
     try:
         batches = [DeviceBatch(mb, gn, col_ids=ids_cols) for mb, gn, _ in sampled[:total]]
         for it in range(first_timed):

@@ -404,6 +404,24 @@ fg_status_t fg_linear_wt(const void* h_src, int32_t n_src, int64_t src_stride, f
                          int32_t d_out, const void* Wt, fg_dtype_t w_dtype, const float* bias, int32_t relu, void* h_out,
                          int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, void* stream);
 
+/*
+ * fg_linear for the input layer with Load_feature (Algorithm 1) of the rows' own features folded into the operand load:
+ * the own features of output position r are row src_ids_dev[r] of `table` (node ids into the raw feature table, as
+ * fg_gather reads them), so that a loader which forms the neighbour means (fg_gather_aggregate* with h_self_out = NULL)
+ * need not copy those rows out and this call need not read the copy back:
+ *   h_out[r, :] = act( table[src_ids[r], :] . W[0:d_in, :] + agg[k, :] . W[d_in:2*d_in, :] + bias ),  r = rows[k]
+ *   table, table_rows, src_stride   device memory (every own row is read once per 32 or 64 output columns: a table
+ *                                   in mapped host memory works but is not what this call is for)
+ *   src_ids_dev[n_out]              int32, device; entries whose id is outside [0, table_rows) are skipped like
+ *                                   positions outside [0, n_out)
+ * Everything else, and the result, as for fg_linear on the gathered rows (same kernels, same arithmetic).
+ */
+fg_status_t fg_linear_ids(const void* table, int32_t table_rows, int64_t src_stride, fg_dtype_t in_dtype,
+                          const int32_t* src_ids_dev, const void* agg, int64_t agg_stride, const int32_t* rows_dev,
+                          const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
+                          fg_dtype_t w_dtype, const float* bias, int32_t relu, void* h_out, int32_t n_out, int64_t out_stride,
+                          fg_dtype_t out_dtype, void* stream);
+
 
 /*
  * fg_aggregate followed by fg_linear for one fp32 GraphSAGE-mean layer (Eq. 1 in one call; same results as the two

@@ -61,6 +61,7 @@ SIGNATURES = {
                                        _i32, _p, _i32, _p, _p]),
     "fg_linear": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _p, _i64, _i32, _i32, _p, _i32, _p, _i32, _p, _i32, _i64, _i32, _p]),
     "fg_linear_wt": (_i32, [_p, _i32, _i64, _i32, _p, _i64, _p, _p, _i64, _i32, _i32, _p, _i32, _p, _i32, _p, _i32, _i64, _i32, _p]),
+    "fg_linear_ids": (_i32, [_p, _i32, _i64, _i32, _p, _p, _i64, _p, _p, _i64, _i32, _i32, _p, _i32, _p, _i32, _p, _i32, _i64, _i32, _p]),
     "fg_aggregate_linear": (_i32, [_p, _p, _p, _i64, _i32, _p, _p, _i64, _p, _i32, _i64, _i32, _i32, _p, _p, _i32, _p, _i64, _p, _i32,
                                    _i64, _p]),
     "fg_cache_update": (_i32, [_p, _i32, _i64, _p, _i32, _p, _p, _p, _f, _p, _i64, _p, _p, _sz, _p]),
@@ -322,6 +323,12 @@ def fg_linear_wt(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows, n_ro
                  h_out, n_out, out_stride, out_dtype, stream=None):
     _check(_lib.fg_linear_wt(ptr(h_src), n_src, src_stride, in_dtype, ptr(agg), agg_stride, ptr(rows), ptr(n_rows), max_rows,
                              d_in, d_out, ptr(Wt), w_dtype, ptr(bias), relu, ptr(h_out), n_out, out_stride, out_dtype, stream))
+
+
+def fg_linear_ids(table, table_rows, src_stride, in_dtype, src_ids, agg, agg_stride, rows, n_rows, max_rows, d_in, d_out, W, w_dtype, bias,
+                  relu, h_out, n_out, out_stride, out_dtype, stream=None):
+    _check(_lib.fg_linear_ids(ptr(table), table_rows, src_stride, in_dtype, ptr(src_ids), ptr(agg), agg_stride, ptr(rows), ptr(n_rows),
+                              max_rows, d_in, d_out, ptr(W), w_dtype, ptr(bias), relu, ptr(h_out), n_out, out_stride, out_dtype, stream))
 
 
 def fg_aggregate_linear(row_start, row_end, col, nnz, n_block_rows, rows, n_rows, max_rows, h_src, n_src, src_stride, d_in, d_out, W,

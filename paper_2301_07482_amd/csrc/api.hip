@@ -42,7 +42,7 @@ extern "C" fg_status_t fg_set_tuning(const char* key, int64_t value) {
 
 extern "C" const char* fg_last_error(void) { return g_err; }
 
-extern "C" int32_t fg_version(void) { return 300; }  // 0.3.0: device-side layer sizes (two structs grew a field), backward for GCN and mixed precision, fg_linear_wt, fg_lookup_prune_static
+extern "C" int32_t fg_version(void) { return 301; }  // 0.3.1: fg_linear_ids; 0.3.0: device-side layer sizes (two structs grew a field), backward for GCN and mixed precision, fg_linear_wt, fg_lookup_prune_static
 
 extern "C" size_t fg_workspace_bytes(fg_ws_kind_t kind, int64_t n, int64_t reserved) {
     (void)reserved;

@@ -228,7 +228,8 @@ BwWs bw_layout(int64_t n, int64_t max_rows, int64_t cols, int64_t d_out, int64_t
 fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype, const void* agg,
                                   int64_t agg_stride, const int32_t* rows_dev, const int64_t* n_rows_dev, int64_t max_rows,
                                   int32_t d_in, int32_t d_out, const void* W, const float* bias, int32_t relu, void* h_out,
-                                  int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, hipStream_t st, bool w_nk, const int64_t* k_limit_dev = nullptr);
+                                  int32_t n_out, int64_t out_stride, fg_dtype_t out_dtype, hipStream_t st, bool w_nk, const int64_t* k_limit_dev = nullptr,
+                                  const int32_t* src_ids_dev = nullptr);
 
 extern "C" fg_status_t fg_softmax_xent_grad(const float* h_dev, int64_t h_stride, const int32_t* labels_dev, int32_t n, int32_t d,
                                             float* dh_dev, int64_t dh_stride, void* stream) {

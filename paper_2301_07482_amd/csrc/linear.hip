@@ -28,12 +28,20 @@ constexpr int KC = 32;  // k values per fp32 accumulation chunk (one fp64 fold p
 constexpr int LDB = BN + 4;
 constexpr int LIN_THREADS = 256;
 
+// The row of h_src that holds the own features of position r: r itself, or src_ids[r] where the caller reads them straight
+// from a table by row number (fg_linear_ids). -1 where there is no such row.
+__device__ __forceinline__ int32_t own_row(const int32_t* __restrict__ src_ids, int32_t r, int n_src) {
+    if (r < 0) return -1;
+    const int32_t s = src_ids ? src_ids[r] : r;
+    return (s < 0 || s >= n_src) ? -1 : s;
+}
+
 template <int WM, int BK>
 __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
-    int64_t out_stride, int n_tiles) {
+    int64_t out_stride, int n_tiles, const int32_t* __restrict__ src_ids) {
     constexpr int BM = 32 * WM;
     constexpr int WN = 4 / WM;          // wavefronts along N
     constexpr int NB = BN / (32 * WN);  // 32-wide MFMA blocks per wavefront
@@ -45,7 +53,7 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
     constexpr int B_ROWS = LIN_THREADS / 16;         // k rows covered by one pass of the workgroup
     __shared__ __attribute__((aligned(16))) float As[BM * LDA];
     __shared__ __attribute__((aligned(16))) float Bs[BK * LDB];
-    __shared__ int32_t row_of[BM];
+    __shared__ int32_t row_of[BM], src_of[BM];
 
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
     if (n_rows > max_rows) n_rows = max_rows;
@@ -62,12 +70,15 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
 
     if (t < BM) {
         const int64_t g = m0 + t;
-        int32_t r = -1;
+        int32_t r = -1, s = -1;
         if (g < n_rows) {
             r = rows ? rows[g] : (int32_t)g;
-            if (r < 0 || r >= n_src || r >= n_out) r = -1;
+            if (r < 0 || r >= n_out) r = -1;
+            s = own_row(src_ids, r, n_src);
+            if (s < 0) r = -1;
         }
         row_of[t] = r;
+        src_of[t] = s;
     }
     __syncthreads();
 
@@ -85,7 +96,7 @@ __global__ __launch_bounds__(LIN_THREADS, 3) void linear_f32_kernel(
         const int m = a_m + A_ROWS * i;
         const int32_t r = row_of[m];
         a_ok[i] = r >= 0;
-        a_self[i] = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0));
+        a_self[i] = (const float*)(h_src + (r >= 0 ? (int64_t)src_of[m] * src_stride : 0));
         a_agg[i] = (const float*)(agg + (r >= 0 ? (m0 + m) * agg_stride : 0));
     }
     const bool b_col_ok = (n0 + 4 * b_nc) < d_out;
@@ -204,7 +215,7 @@ __global__ __launch_bounds__(PL_THREADS, 4) void linear_f32_panel_kernel(
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
-    int64_t out_stride, int n_panels, int n_groups) {
+    int64_t out_stride, int n_panels, int n_groups, const int32_t* __restrict__ src_ids) {
     extern __shared__ __attribute__((aligned(16))) float panel[];  // [K][32]
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
     if (n_rows > max_rows) n_rows = max_rows;
@@ -232,22 +243,26 @@ __global__ __launch_bounds__(PL_THREADS, 4) void linear_f32_panel_kernel(
     const double bv = (bias && c < d_out) ? (double)bias[c] : 0.0;
     const float* bcol = panel + 16 * half * PL_BN + l32;
 
-    // destination / source row of this lane in row block rb (-1: past the end or out of range)
-    auto row_of_block = [&](int64_t rb) -> int32_t {
+    // destination row of this lane in row block rb (-1: past the end or out of range) and, in s, the row of its own features
+    auto row_of_block = [&](int64_t rb, int32_t& s) -> int32_t {
         const int64_t g = rb * 32 + l32;
         int32_t r = -1;
+        s = -1;
         if (rb < n_blocks && g < n_rows) {
             r = rows ? rows[g] : (int32_t)g;
-            if (r < 0 || r >= n_src || r >= n_out) r = -1;
+            if (r < 0 || r >= n_out) r = -1;
+            s = own_row(src_ids, r, n_src);
+            if (s < 0) r = -1;
         }
         return r;
     };
     const int64_t stride = (int64_t)n_groups * PL_WAVES;
     int64_t rb = group + (int64_t)n_groups * wave;
     if (rb >= n_blocks) return;
-    int32_t r = row_of_block(rb);
-    int32_t r_next = row_of_block(rb + stride);
-    const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+    int32_t s, s_next;
+    int32_t r = row_of_block(rb, s);
+    int32_t r_next = row_of_block(rb + stride, s_next);
+    const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)s * src_stride : 0)) + 16 * half;
     const float* a_agg = (const float*)(agg + (r >= 0 ? (rb * 32 + l32) * agg_stride : 0)) + 16 * half;
     f32x4 a0[4], a1[4];
 #pragma unroll
@@ -255,7 +270,8 @@ __global__ __launch_bounds__(PL_THREADS, 4) void linear_f32_panel_kernel(
     for (; rb < n_blocks; rb += stride) {
         // the row of the task after next is fetched now, and the next task's first K step during this task's last
         // one, so that the matrix instructions of consecutive tasks follow each other without a memory round trip
-        const int32_t r_after = row_of_block(rb + 2 * stride);
+        int32_t s_after;
+        const int32_t r_after = row_of_block(rb + 2 * stride, s_after);
         double sum[16];
 #pragma unroll
         for (int i = 0; i < 16; ++i) sum[i] = 0.0;
@@ -283,7 +299,7 @@ __global__ __launch_bounds__(PL_THREADS, 4) void linear_f32_panel_kernel(
             compute(step, a0);
             {
                 const int s2 = step + 2;
-                const float* nxt = (const float*)(h_src + (r_next >= 0 ? (int64_t)r_next * src_stride : 0)) + 16 * half;
+                const float* nxt = (const float*)(h_src + (r_next >= 0 ? (int64_t)s_next * src_stride : 0)) + 16 * half;
                 const float* cur = s2 < nk_self ? a_self + s2 * KC : a_agg + (s2 < nk ? s2 - nk_self : 0) * KC;
                 const float* p = s2 < nk ? cur : nxt;  // after the last step: step 0 of the next task (or a valid dummy)
 #pragma unroll
@@ -303,8 +319,10 @@ __global__ __launch_bounds__(PL_THREADS, 4) void linear_f32_panel_kernel(
             *(float*)(h_out + (int64_t)rr * out_stride + (int64_t)c * 4) = v;
         }
         r = r_next;
+        s = s_next;
         r_next = r_after;
-        a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+        s_next = s_after;
+        a_self = (const float*)(h_src + (r >= 0 ? (int64_t)s * src_stride : 0)) + 16 * half;
         a_agg = (const float*)(agg + (r >= 0 ? ((rb + stride) * 32 + l32) * agg_stride : 0)) + 16 * half;
     }
 }
@@ -323,7 +341,7 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 constexpr int X3_LIST = 8;                                  // tasks whose rows a wavefront lists ahead in LDS
-constexpr int X3_LIST_BYTES = PL_WAVES * X3_LIST * 32 * 4;  // the lists of a workgroup
+constexpr int X3_LIST_BYTES = PL_WAVES * X3_LIST * 32 * 4;  // the lists of a workgroup (twice that with src_ids)
 
 // v[0..7] -> three fragments of eight bf16 (element j in half j % 2 of word j / 2)
 __device__ __forceinline__ void split8(const float* v, u32x4& t1, u32x4& t2, u32x4& t3) {
@@ -348,7 +366,7 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
-    int64_t out_stride, int n_panels, int n_groups, int near_out) {
+    int64_t out_stride, int n_panels, int n_groups, int near_out, const int32_t* __restrict__ src_ids) {
     constexpr int BNW = PL_BN * NB;
     extern __shared__ __attribute__((aligned(16))) u32x4 bfrag[];  // [3 terms][K / 8 groups of k][BNW columns]
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
@@ -402,7 +420,9 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
     // row of task t at rowlist[t * 32 + l32], -1 for a row past the end or out of range. Reading them costs no wait on
     // global memory: a global load of a row index in the middle of a task would make the wavefront wait for everything
     // it has in flight (the A values fetched ahead, the previous task's stores), since those complete in order.
+    // With src_ids a second list holds the rows of h_src the own features come from (without: the same rows, one list).
     int32_t* rowlist = (int32_t*)(bfrag + 3 * ngr * BNW) + wave * (X3_LIST * 32);
+    int32_t* srclist = src_ids ? rowlist + PL_WAVES * (X3_LIST * 32) : rowlist;
     auto row_raw = [&](int64_t rbx) -> int32_t {      // unconditional load: clamped index, a valid dummy address without a list
         int64_t g = rbx * 32 + l32;
         g = g < n_rows ? g : n_rows - 1;  // n_rows >= 1 here
@@ -412,7 +432,7 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
     auto row_decode = [&](int32_t raw, int64_t rbx) -> int32_t {
         const int64_t g = rbx * 32 + l32;
         int32_t r = rows ? raw : (int32_t)g;
-        if (rbx >= n_blocks || g >= n_rows || r < 0 || r >= n_src || r >= n_out) r = -1;
+        if (rbx >= n_blocks || g >= n_rows || r < 0 || r >= n_out || (!src_ids && r >= n_src)) r = -1;
         return r;
     };
     const int64_t stride = (int64_t)n_groups * PL_WAVES;
@@ -422,10 +442,22 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
 #pragma unroll
             for (int q = 0; q < X3_LIST; ++q) raw[q] = row_raw(rb0 + q * stride);
 #pragma unroll
-            for (int q = 0; q < X3_LIST; ++q) rowlist[q * 32 + l32] = row_decode(raw[q], rb0 + q * stride);   // both halves write the same value
+            for (int q = 0; q < X3_LIST; ++q) raw[q] = row_decode(raw[q], rb0 + q * stride);
+            if (src_ids) {      // second round: the table rows of those positions (position 0 exists: n_out >= 1)
+                int32_t sraw[X3_LIST];
+#pragma unroll
+                for (int q = 0; q < X3_LIST; ++q) sraw[q] = src_ids[raw[q] >= 0 ? raw[q] : 0];
+#pragma unroll
+                for (int q = 0; q < X3_LIST; ++q) {
+                    if (raw[q] < 0 || sraw[q] < 0 || sraw[q] >= n_src) raw[q] = sraw[q] = -1;
+                    srclist[q * 32 + l32] = sraw[q];
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < X3_LIST; ++q) rowlist[q * 32 + l32] = raw[q];   // both halves write the same value
         }
-        int32_t r = rowlist[l32];
-        const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+        int32_t r = rowlist[l32], s = srclist[l32];
+        const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)s * src_stride : 0)) + 16 * half;
         const float* a_agg = (const float*)(agg + (r >= 0 ? (rb0 * 32 + l32) * agg_stride : 0)) + 16 * half;
         f32x4 a0[4], a1[4];
 #pragma unroll
@@ -436,6 +468,7 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
             // the row of the next task: its first K step is fetched during this task's last one (the last task of a
             // list fetches row 0 instead, and the next list starts with a fetch of its own)
             const int32_t r_next = tk + 1 < X3_LIST ? rowlist[(tk + 1) * 32 + l32] : -1;
+            const int32_t s_next = tk + 1 < X3_LIST ? srclist[(tk + 1) * 32 + l32] : -1;
             // Two fp32 accumulators per column block, kept across the whole K range: `big` takes the products of the two
             // leading bf16 terms, `small` the five products that are 2^-8 and 2^-16 of those. What limits an fp32
             // running sum is the rounding of the sum itself at every accumulation step; with the leading term alone
@@ -489,7 +522,7 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
                 compute(step, a0);
                 {
                     const int s2 = step + 2;
-                    const float* nxt = (const float*)(h_src + (r_next >= 0 ? (int64_t)r_next * src_stride : 0)) + 16 * half;
+                    const float* nxt = (const float*)(h_src + (r_next >= 0 ? (int64_t)s_next * src_stride : 0)) + 16 * half;
                     const float* cur = s2 < nk_self ? a_self + s2 * KC : a_agg + (s2 < nk ? s2 - nk_self : 0) * KC;
                     const float* p = s2 < nk ? cur : nxt;
 #pragma unroll
@@ -548,7 +581,8 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
                 }
             }
             r = r_next;
-            a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+            s = s_next;
+            a_self = (const float*)(h_src + (r >= 0 ? (int64_t)s * src_stride : 0)) + 16 * half;
             a_agg = (const float*)(agg + (r >= 0 ? ((rb + stride) * 32 + l32) * agg_stride : 0)) + 16 * half;
         }
     }
@@ -572,7 +606,7 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32_splitk_kernel(
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     const float* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
     int64_t out_stride, int n_panels, const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end,
-    const int32_t* __restrict__ col, int64_t nnz, int n_block_rows) {
+    const int32_t* __restrict__ col, int64_t nnz, int n_block_rows, const int32_t* __restrict__ src_ids) {
     extern __shared__ __attribute__((aligned(16))) float panel[];  // [K][32], later the partial sums
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
     if (n_rows > max_rows) n_rows = max_rows;
@@ -596,12 +630,14 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32_splitk_kernel(
 
     // destination / source row of this lane (-1: past the end or out of range; such a lane reads row 0)
     const int64_t g = rb * 32 + l32;
-    int32_t r = -1;
+    int32_t r = -1, s_own = -1;
     if (g < n_rows) {
         r = rows ? rows[g] : (int32_t)g;
-        if (r < 0 || r >= n_src || r >= n_out) r = -1;
+        if (r < 0 || r >= n_out) r = -1;
+        s_own = own_row(src_ids, r, n_src);
+        if (s_own < 0) r = -1;
     }
-    const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)r * src_stride : 0)) + 16 * half;
+    const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)s_own * src_stride : 0)) + 16 * half;
     const float* a_agg = (const float*)(agg + (r >= 0 ? g * agg_stride : 0)) + 16 * half;
     auto a_ptr = [&](int s) { return s < nk_self ? a_self + s * KC : a_agg + (s - nk_self) * KC; };
     // this lane's row of the block (FUSE): its sampled neighbours are col[e0 .. e1)
@@ -715,30 +751,32 @@ fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_
                                   const void* agg, int64_t agg_stride, const int32_t* rows_dev,
                                   const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
                                   const float* bias, int32_t relu, void* h_out, int32_t n_out, int64_t out_stride,
-                                  fg_dtype_t out_dtype, hipStream_t st, bool w_nk, const int64_t* k_limit_dev = nullptr);
+                                  fg_dtype_t out_dtype, hipStream_t st, bool w_nk, const int64_t* k_limit_dev = nullptr,
+                                  const int32_t* src_ids_dev = nullptr);
 
-extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype,
-                                 const void* agg, int64_t agg_stride, const int32_t* rows_dev,
+// fg_linear (src_ids_dev == NULL: the own features of position r are row r of h_src) and fg_linear_ids (row src_ids_dev[r])
+static fg_status_t linear_launch(const char* who, const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype,
+                                 const int32_t* src_ids_dev, const void* agg, int64_t agg_stride, const int32_t* rows_dev,
                                  const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
                                  fg_dtype_t w_dtype, const float* bias, int32_t relu, void* h_out, int32_t n_out,
                                  int64_t out_stride, fg_dtype_t out_dtype, void* stream) {
     if (max_rows < 0 || n_src < 0 || n_out < 0 || d_in <= 0 || d_out <= 0)
-        FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: bad size (max_rows %lld, n_src %d, n_out %d, d_in %d, d_out %d)",
+        FG_FAIL(FG_ERR_INVALID_ARG, "%s: bad size (max_rows %lld, n_src %d, n_out %d, d_in %d, d_out %d)", who,
                 (long long)max_rows, n_src, n_out, d_in, d_out);
     if (!fg_dtype_size(in_dtype) || !fg_dtype_size(w_dtype) || !fg_dtype_size(out_dtype))
-        FG_FAIL(FG_ERR_DTYPE, "fg_linear: unknown element type");
-    if (max_rows > 0 && (!h_src || !agg || !W || !h_out)) FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: NULL pointer");
+        FG_FAIL(FG_ERR_DTYPE, "%s: unknown element type", who);
+    if (max_rows > 0 && (!h_src || !agg || !W || !h_out)) FG_FAIL(FG_ERR_INVALID_ARG, "%s: NULL pointer", who);
     hipStream_t st = (hipStream_t)stream;
     if (w_dtype == FG_F32) {
         if (in_dtype != FG_F32 || out_dtype != FG_F32)
-            FG_FAIL(FG_ERR_DTYPE, "fg_linear: fp32 weights need fp32 inputs and outputs");
-        if (d_in % 4 || d_out % 4) FG_FAIL(FG_ERR_SHAPE, "fg_linear: d_in = %d and d_out = %d must be multiples of 4", d_in, d_out);
+            FG_FAIL(FG_ERR_DTYPE, "%s: fp32 weights need fp32 inputs and outputs", who);
+        if (d_in % 4 || d_out % 4) FG_FAIL(FG_ERR_SHAPE, "%s: d_in = %d and d_out = %d must be multiples of 4", who, d_in, d_out);
         if (src_stride < (int64_t)d_in * 4 || agg_stride < (int64_t)d_in * 4 || out_stride < (int64_t)d_out * 4)
-            FG_FAIL(FG_ERR_SHAPE, "fg_linear: a row stride is smaller than its row");
+            FG_FAIL(FG_ERR_SHAPE, "%s: a row stride is smaller than its row", who);
         if (((uintptr_t)h_src | (uintptr_t)agg | (uintptr_t)W | (uintptr_t)src_stride | (uintptr_t)agg_stride) & 15)
-            FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: h_src, agg, W and the input strides must be 16-byte aligned");
+            FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_src, agg, W and the input strides must be 16-byte aligned", who);
         if (((uintptr_t)h_out | (uintptr_t)out_stride | (uintptr_t)bias) & 3)
-            FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear: h_out, its stride and bias must be 4-byte aligned");
+            FG_FAIL(FG_ERR_INVALID_ARG, "%s: h_out, its stride and bias must be 4-byte aligned", who);
         fg_clear_error();
         if (max_rows == 0) return FG_OK;
         const int64_t forced = fg_tuning(FG_TUNE_LINEAR_TILE);
@@ -752,15 +790,16 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
             hipLaunchKernelGGL(linear_f32_splitk_kernel<false>, dim3(grid), dim3(PL_THREADS), lds, st, (const char*)h_src, n_src,
                                src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out,
                                (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels, nullptr, nullptr, nullptr,
-                               (int64_t)0, 0);
+                               (int64_t)0, 0, src_ids_dev);
             FG_LAUNCH_CHECK("linear_f32_splitk_kernel");
             return FG_OK;
         }
         // bf16 x 3 panel kernel: two 32-column blocks per wavefront if the split panel fits in LDS, else one
         const size_t x3_bytes = (size_t)2 * d_in * 192;
-        if (d_in % KC == 0 && x3_bytes <= 144 * 1024 && (forced == 0 || forced == 301 || forced == 302)) {
+        const size_t x3_lists = (size_t)X3_LIST_BYTES * (src_ids_dev ? 2 : 1);
+        if (d_in % KC == 0 && x3_bytes + x3_lists <= 160 * 1024 && x3_bytes <= 144 * 1024 && (forced == 0 || forced == 301 || forced == 302)) {
             const int nb = (forced != 301 && 2 * x3_bytes <= 144 * 1024) ? 2 : 1;
-            const size_t lds = x3_bytes * nb + X3_LIST_BYTES;     // fragments of the panel, then the wavefronts' row lists
+            const size_t lds = x3_bytes * nb + x3_lists;          // fragments of the panel, then the wavefronts' row lists
             const int n_panels = (int)fg_ceil_div(d_out, PL_BN * nb);
             int q = 256 / (8 * n_panels);  // register use allows one workgroup per compute unit
             if (q < 1) q = 1;
@@ -773,12 +812,12 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
                 hipLaunchKernelGGL(linear_f32x3_panel_kernel<2>, dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), lds, st,
                                    (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev,
                                    max_rows, d_in, d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels,
-                                   n_groups, near_out);
+                                   n_groups, near_out, src_ids_dev);
             else
                 hipLaunchKernelGGL(linear_f32x3_panel_kernel<1>, dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), lds, st,
                                    (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev,
                                    max_rows, d_in, d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels,
-                                   n_groups, near_out);
+                                   n_groups, near_out, src_ids_dev);
             FG_LAUNCH_CHECK("linear_f32x3_panel_kernel");
             return FG_OK;
         }
@@ -793,7 +832,7 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
             hipLaunchKernelGGL(linear_f32_panel_kernel, dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), panel_bytes, st,
                                (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev,
                                max_rows, d_in, d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels,
-                               n_groups);
+                               n_groups, src_ids_dev);
             FG_LAUNCH_CHECK("linear_f32_panel_kernel");
             return FG_OK;
         }
@@ -805,18 +844,38 @@ extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_s
         if (big)
             hipLaunchKernelGGL((linear_f32_kernel<4, 32>), dim3(grid), dim3(LIN_THREADS), 0, st, (const char*)h_src, n_src, src_stride,
                                (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, (const float*)W,
-                               bias, relu, (char*)h_out, n_out, out_stride, ny);
+                               bias, relu, (char*)h_out, n_out, out_stride, ny, src_ids_dev);
         else
             hipLaunchKernelGGL((linear_f32_kernel<2, 32>), dim3(grid), dim3(LIN_THREADS), 0, st, (const char*)h_src, n_src, src_stride,
                                (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, (const float*)W,
-                               bias, relu, (char*)h_out, n_out, out_stride, ny);
+                               bias, relu, (char*)h_out, n_out, out_stride, ny, src_ids_dev);
         FG_LAUNCH_CHECK("linear_f32_kernel");
         return FG_OK;
     }
     if (w_dtype == FG_BF16)
         return fg_launch_linear_bf16(h_src, n_src, src_stride, in_dtype, agg, agg_stride, rows_dev, n_rows_dev, max_rows,
-                                     d_in, d_out, W, bias, relu, h_out, n_out, out_stride, out_dtype, st, false);
-    FG_FAIL(FG_ERR_DTYPE, "fg_linear: weights must be F32 or BF16");
+                                     d_in, d_out, W, bias, relu, h_out, n_out, out_stride, out_dtype, st, false, nullptr, src_ids_dev);
+    FG_FAIL(FG_ERR_DTYPE, "%s: weights must be F32 or BF16", who);
+}
+
+extern "C" fg_status_t fg_linear(const void* h_src, int32_t n_src, int64_t src_stride, fg_dtype_t in_dtype,
+                                 const void* agg, int64_t agg_stride, const int32_t* rows_dev,
+                                 const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
+                                 fg_dtype_t w_dtype, const float* bias, int32_t relu, void* h_out, int32_t n_out,
+                                 int64_t out_stride, fg_dtype_t out_dtype, void* stream) {
+    return linear_launch("fg_linear", h_src, n_src, src_stride, in_dtype, nullptr, agg, agg_stride, rows_dev, n_rows_dev, max_rows,
+                         d_in, d_out, W, w_dtype, bias, relu, h_out, n_out, out_stride, out_dtype, stream);
+}
+
+// fg_linear with the own features read straight from a table: row src_ids_dev[r] of `table` for output position r
+extern "C" fg_status_t fg_linear_ids(const void* table, int32_t table_rows, int64_t src_stride, fg_dtype_t in_dtype,
+                                     const int32_t* src_ids_dev, const void* agg, int64_t agg_stride, const int32_t* rows_dev,
+                                     const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
+                                     fg_dtype_t w_dtype, const float* bias, int32_t relu, void* h_out, int32_t n_out,
+                                     int64_t out_stride, fg_dtype_t out_dtype, void* stream) {
+    if (max_rows > 0 && n_out > 0 && !src_ids_dev) FG_FAIL(FG_ERR_INVALID_ARG, "fg_linear_ids: src_ids_dev is NULL");
+    return linear_launch("fg_linear_ids", table, table_rows, src_stride, in_dtype, src_ids_dev, agg, agg_stride, rows_dev, n_rows_dev,
+                         max_rows, d_in, d_out, W, w_dtype, bias, relu, h_out, n_out, out_stride, out_dtype, stream);
 }
 
 // fg_linear with the bf16 weights given transposed ([d_out x 2*d_in], one output column's weights contiguous): the layout
@@ -862,7 +921,7 @@ extern "C" fg_status_t fg_aggregate_linear(const int32_t* row_start_dev, const i
         const unsigned grid = (unsigned)(fg_ceil_div(fg_ceil_div(max_rows, 32), 8) * 8 * n_panels);
         hipLaunchKernelGGL(linear_f32_splitk_kernel<true>, dim3(grid), dim3(PL_THREADS), lds, (hipStream_t)stream, (const char*)h_src,
                            n_src, src_stride, (const char*)h_src, src_stride, rows_dev, n_rows_dev, max_rows, d_in, d_out, W, bias, relu,
-                           (char*)h_out, n_out, out_stride, n_panels, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows);
+                           (char*)h_out, n_out, out_stride, n_panels, row_start_dev, row_end_dev, col_dev, nnz, n_block_rows, nullptr);
         FG_LAUNCH_CHECK("linear_f32_splitk_kernel (fused aggregation)");
         return FG_OK;
     }

@@ -53,7 +53,7 @@ __device__ __forceinline__ u32x4 f16x8_to_bf16x8(u32x4 v) {
 // exist reads the tile's first row, a k beyond K reads k = 0). Rows and columns that do not exist need no zeroing: an
 // output depends on its own row of A and its own column of W only, and theirs are never written. Only the k values
 // beyond K of a last, partial step are written to LDS as zeros (both operands, so that nothing non-finite meets a zero).
-constexpr size_t hb_lds_bytes(int hb_m, int hb_n) { return (size_t)2 * (hb_m + hb_n) * LDH * 2 + (size_t)hb_m * 4; }
+constexpr size_t hb_lds_bytes(int hb_m, int hb_n) { return (size_t)2 * (hb_m + hb_n) * LDH * 2 + (size_t)hb_m * 8; }
 
 constexpr int hb_waves(int hb_m, int hb_n) { return hb_m * hb_n >= 128 * 128 ? 8 : 4; }
 
@@ -62,11 +62,12 @@ __global__ __launch_bounds__(64 * hb_waves(HB_M, HB_N), hb_waves(HB_M, HB_N) == 
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
     const unsigned short* __restrict__ W, const float* __restrict__ bias, int relu, char* __restrict__ h_out, int n_out,
-    int64_t out_stride, int n_tiles, const int64_t* __restrict__ k_limit_dev) {
+    int64_t out_stride, int n_tiles, const int64_t* __restrict__ k_limit_dev, const int32_t* __restrict__ src_ids) {
     extern __shared__ __attribute__((aligned(16))) unsigned short hb_lds[];
     constexpr int HB_WAVES = hb_waves(HB_M, HB_N), HB_THREADS = 64 * HB_WAVES;
     constexpr int STAGE = (HB_M + HB_N) * LDH;    // halfwords per buffer: A rows, then the columns of W
-    int32_t* row_of = (int32_t*)(hb_lds + 2 * STAGE);
+    int32_t* row_of = (int32_t*)(hb_lds + 2 * STAGE);   // output position of each row of the tile, -1: none
+    int32_t* src_of = row_of + HB_M;                     // the row of h_src with its own features: the position, or src_ids[position]
 
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
     if (n_rows > max_rows) n_rows = max_rows;
@@ -81,12 +82,15 @@ __global__ __launch_bounds__(64 * hb_waves(HB_M, HB_N), hb_waves(HB_M, HB_N) == 
 
     if (t < HB_M) {
         const int64_t g = m0 + t;
-        int32_t r = -1;
+        int32_t r = -1, s = -1;
         if (g < n_rows) {
             r = rows ? rows[g] : (int32_t)g;
-            if (r < 0 || r >= n_src || r >= n_out) r = -1;
+            if (r < 0 || r >= n_out) r = -1;
+            if (r >= 0) s = src_ids ? src_ids[r] : r;
+            if (s < 0 || s >= n_src) r = s = -1;
         }
         row_of[t] = r;
+        src_of[t] = s;
     }
     __syncthreads();
 
@@ -106,11 +110,11 @@ __global__ __launch_bounds__(64 * hb_waves(HB_M, HB_N), hb_waves(HB_M, HB_N) == 
     // per thread: the positions of its A rows and, relative to the tile's first mean row / first weight column (which always
     // exist), the rows of its other loads: 32 bits each; a row or column that does not exist reads the first one instead
     int32_t a_row[A_PASSES], agg_rel[A_PASSES];
-    const int32_t r_first = row_of[0];          // the tile's first row exists (m0 < n_rows), its position may still be out of range
+    const int32_t r_first = src_of[0];          // the tile's first row exists (m0 < n_rows), its position may still be out of range
 #pragma unroll
     for (int i = 0; i < A_PASSES; ++i) {
         const int m = a_m + A_ROWS * i;
-        const int32_t r = row_of[m];
+        const int32_t r = src_of[m];
         a_row[i] = r >= 0 ? r : (r_first >= 0 ? r_first : 0);
         agg_rel[i] = m0 + m < n_rows ? m : 0;   // list entries below the count lie within the caller's max_rows
     }
@@ -299,7 +303,8 @@ fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_
                                   const void* agg, int64_t agg_stride, const int32_t* rows_dev,
                                   const int64_t* n_rows_dev, int64_t max_rows, int32_t d_in, int32_t d_out, const void* W,
                                   const float* bias, int32_t relu, void* h_out, int32_t n_out, int64_t out_stride,
-                                  fg_dtype_t out_dtype, hipStream_t st, bool w_nk, const int64_t* k_limit_dev) {
+                                  fg_dtype_t out_dtype, hipStream_t st, bool w_nk, const int64_t* k_limit_dev,
+                                  const int32_t* src_ids_dev) {
     if (in_dtype != FG_F16 && in_dtype != FG_BF16) FG_FAIL(FG_ERR_DTYPE, "fg_linear: bf16 weights need fp16 or bf16 inputs");
     if (out_dtype != FG_BF16 && out_dtype != FG_F32) FG_FAIL(FG_ERR_DTYPE, "fg_linear: bf16 weights give bf16 or fp32 outputs");
     if (d_in % 8 || d_out % 8) FG_FAIL(FG_ERR_SHAPE, "fg_linear: d_in = %d and d_out = %d must be multiples of 8 for 16-bit types", d_in, d_out);
@@ -325,7 +330,7 @@ fg_status_t fg_launch_linear_bf16(const void* h_src, int32_t n_src, int64_t src_
 #define FG_LB4(F16, OBF, TM, TN, NK)                                                                                       \
     hipLaunchKernelGGL((linear_bf16_kernel<F16, OBF, TM, TN, NK>), dim3(grid), dim3(64 * hb_waves(TM, TN)), hb_lds_bytes(TM, TN), st, \
                        (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, \
-                       d_in, d_out, (const unsigned short*)W, bias, relu, (char*)h_out, n_out, out_stride, ny, k_limit_dev)
+                       d_in, d_out, (const unsigned short*)W, bias, relu, (char*)h_out, n_out, out_stride, ny, k_limit_dev, src_ids_dev)
 #define FG_LB3(F16, OBF, TM, TN)         \
     do {                                 \
         if (w_nk)                        \

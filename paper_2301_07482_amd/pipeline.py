@@ -179,7 +179,7 @@ class HotPath:
     def __init__(self, num_nodes, dims, fanouts, batch, capacity, t_stale, p_grad, features, feat_dtype, compute_dtype,
                  weights, features_on_host=False, device="cuda", use_cache=True, update_all=True, fetch_all=True, fused_input=False,
                  one_launch_top_down=True, log_ring=256, hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage", fuse_small_layers=False,
-                 fetch_with_loader=True, admit_budget=None, overlap_update=True, overlap_min_rows=0):
+                 fetch_with_loader=True, admit_budget=None, overlap_update=True, overlap_min_rows=0, copy_own_rows=False):
         self.device = device
         self.L = L = len(fanouts)
         self.dims = list(dims)
@@ -193,6 +193,9 @@ class HotPath:
         # fused_input: layer 1 aggregates straight from the feature table (fg_gather_aggregate); only the layer-1
         # nodes' own rows are gathered into H[0] and the top-down pass stops at layer 1
         self.fused_input = fused_input
+        # copy_own_rows: the loader also copies the layer-1 nodes' own rows into H[0] for the dense update. Off: the dense
+        # update of layer 1 reads them from the table itself by node id (fg_linear_ids), where `own_rows_from_table` allows
+        self.copy_own_rows = bool(copy_own_rows)
         # one_launch_top_down: the whole top-down pass as one call (fg_top_down) instead of one fg_lookup_prune call per layer
         self.one_launch_top_down = one_launch_top_down
         self.n_max, self.nnz_max = layer_bounds(batch, fanouts, num_nodes)
@@ -525,7 +528,8 @@ class HotPath:
                 elif getattr(bt, "col_ids1", None) is not None:
                     B.fg_gather_aggregate_ids(bt.start[1], bt.end[1], bt.col_ids1, bt.nnz[1], bt.n[1], self.normal_pos[1],
                                               self._cnt(1, 2), bt.n[1], bt.ids[1], self.feat, self.num_nodes, d0b, self.dims[0],
-                                              in_code, self.AGG_l[1], agg_b, self.agg_code, self.H[0], d0b, bt.n[0],
+                                              in_code, self.AGG_l[1], agg_b, self.agg_code,
+                                              None if self.own_rows_from_table(bt) else self.H[0], d0b, bt.n[0],
                                               self.cache if fetch_specs is not None else None, fetch_specs, st)
                 else:
                     B.fg_gather_aggregate(*args)
@@ -535,6 +539,11 @@ class HotPath:
                                bt.n[l], self.H[l - 1], bt.n[l - 1], in_b, self.dims[l - 1], in_code, self.AGG_l[l], agg_b,
                                self.agg_code, st)
             tick(f"linear[{l}]")
+            if l == 1 and fused and self.own_rows_from_table(bt):
+                B.fg_linear_ids(self.feat, self.num_nodes, in_b, in_code, bt.ids[1], self.AGG_l[1], agg_b, self.normal_pos[1],
+                                self._cnt(1, 2), bt.n[1], self.dims[0], self.dims[1], self.W[1], self.comp_code, self.bias[1],
+                                1 if L > 1 else 0, self.H[1], bt.n[1], out_b, out_code, st)
+                continue
             dense, weights = (B.fg_linear_wt, self.Wt[l]) if l in self.Wt else (B.fg_linear, self.W[l])
             dense(self.H[l - 1], bt.n[l - 1], in_b, in_code, self.AGG_l[l], agg_b, self.normal_pos[l], self._cnt(l, 2),
                   bt.n[l], self.dims[l - 1], self.dims[l], weights, self.comp_code, self.bias[l],
@@ -612,6 +621,13 @@ class HotPath:
             torch.cuda.current_stream().wait_event(self.ev_bw[0])
         tick(None)
 
+    def own_rows_from_table(self, bt):
+        """Whether layer 1's dense update of this mini-batch reads the nodes' own features from the table itself (fp32 table
+        in HBM, id-column loader) instead of from a copy the loader makes."""
+        return (not self.copy_own_rows and self.fused_input and self.model == "sage" and not self.feature_side and not self.on_host
+                and self.comp_code == B.FG_F32 and self.feat_code == B.FG_F32 and not self.weight_grads
+                and getattr(bt, "col_ids1", None) is not None and not self.one_launch(1, bt.n[1]))
+
     # ---- read-back helpers for tests and reports (synchronising) -------------------------------------------
     def snapshot(self, bt):
         """Host copies of what one `run` produced (lists cut to their device-side counts)."""
@@ -670,7 +686,7 @@ class HotPath:
 
 # ---- set-up shared by the tests and bench.py (workload -> HotPath); no arithmetic of the method
 
-def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None, p_grad=None, fused_input=False, one_launch_top_down=True, update_all=True, log_ring=256,
+def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None, p_grad=None, fused_input=False, one_launch_top_down=True, update_all=True, log_ring=256, copy_own_rows=False,
                  hot_ids=None, buffer_bytes=None, backward=False, weight_grads=False, stabilization=0, model="sage",
                  fetch_with_loader=True, admit_budget=None, overlap_update=True, overlap_min_rows=0, fuse_small_layers=False):
     """HotPath for workload `w` with its feature table resident where the workload says."""
@@ -687,7 +703,7 @@ def make_hotpath(w, feat_table=None, use_cache=True, capacity=None, t_stale=None
                  use_cache=use_cache, fused_input=fused_input, one_launch_top_down=one_launch_top_down, update_all=update_all,
                  fetch_all=update_all, log_ring=log_ring, hot_ids=hot_ids, buffer_bytes=buffer_bytes, backward=backward, weight_grads=weight_grads, stabilization=stabilization, model=model,
                  fetch_with_loader=fetch_with_loader, admit_budget=admit_budget, overlap_update=overlap_update,
-                 overlap_min_rows=overlap_min_rows, fuse_small_layers=fuse_small_layers)
+                 overlap_min_rows=overlap_min_rows, fuse_small_layers=fuse_small_layers, copy_own_rows=copy_own_rows)
     return hp, weights, feat_table
 
 

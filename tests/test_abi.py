@@ -149,6 +149,14 @@ def test_argument_validation_needs_no_gpu(B):
     assert code(lin_wt, w_dtype=B.FG_F32) == B.FG_ERR_DTYPE             # transposed weights are taken in bf16 only
     assert code(lin_wt, Wt=None) == B.FG_ERR_INVALID_ARG and code(lin_wt, d_in=124) == B.FG_ERR_SHAPE
     assert code(lin_wt, in_dtype=B.FG_F32) == B.FG_ERR_DTYPE and code(lin_wt, out_stride=64) == B.FG_ERR_SHAPE
+    lin_ids = lambda **k: B.fg_linear_ids(**{**dict(table=4096, table_rows=90, src_stride=512, in_dtype=B.FG_F32, src_ids=4096,
+                                                     agg=4096, agg_stride=512, rows=None, n_rows=None, max_rows=5, d_in=128, d_out=64,
+                                                     W=4096, w_dtype=B.FG_F32, bias=None, relu=1, h_out=4096, n_out=9,
+                                                     out_stride=256, out_dtype=B.FG_F32), **k})
+    assert code(lin_ids, src_ids=None) == B.FG_ERR_INVALID_ARG and code(lin_ids, table=None) == B.FG_ERR_INVALID_ARG
+    assert code(lin_ids, src_stride=256) == B.FG_ERR_SHAPE and code(lin_ids, in_dtype=B.FG_F16) == B.FG_ERR_DTYPE
+    assert code(lin_ids, table_rows=-1) == B.FG_ERR_INVALID_ARG
+    lin_ids(max_rows=0, src_ids=None)                                   # nothing to do: no launch, no error
     # the allocation-free lookup refuses what its built-in scratch memory cannot hold
     assert code(B.fg_lookup_prune_static, None, 0, 0, 4096, B.FG_LOOKUP_PRUNE_STATIC_MAX_N + 1, None, None, None, None, 0, 0, None, None,
                 None, None, 4096, None, 4096) == B.FG_ERR_SHAPE

@@ -362,6 +362,67 @@ def test_linear_matches_oracle(env, d_in, d_out, n_rows, max_rows, relu, variant
     assert err <= REL_TOL_F32
 
 
+@pytest.mark.parametrize("variant", [0, 8, 32, 64, 301, 302, "bf16", "f16"])
+@pytest.mark.parametrize("d_in,d_out,n_rows,max_rows", [(128, 256, 4097, 5000), (256, 256, 700, 700), (100, 64, 333, 400),
+                                                        (64, 64, 0, 128), (128, 256, 20000, 20000)])
+def test_linear_ids_reads_own_rows_from_the_table(env, d_in, d_out, n_rows, max_rows, variant):
+    """fg_linear_ids (own features straight from the table by node id) against the oracle on the gathered rows, and bit for
+    bit against fg_linear on a gathered copy; positions whose id is out of range are left alone."""
+    torch, B = env
+    r = np.random.default_rng(d_in * 13 + d_out + max_rows)
+    n_out, table_rows = max_rows + 300, 50_000
+    sixteen = variant in ("bf16", "f16")
+    if sixteen and d_in % 8:
+        pytest.skip("16-bit rows need d_in % 8 == 0")
+    src = variant if sixteen else "f32"
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16, "f32": torch.float32}
+    code = {"f16": B.FG_F16, "bf16": B.FG_BF16, "f32": B.FG_F32}
+    esz = 2 if sixteen else 4
+    table = O.round_to(r.standard_normal((table_rows, d_in)), src).astype(np.float32)
+    agg = r.standard_normal((max_rows, d_in)) * 0.3
+    agg = O.round_bf16(agg) if sixteen else agg.astype(np.float32)
+    W = r.standard_normal((2 * d_in, d_out)) / np.sqrt(2 * d_in)
+    W = O.round_bf16(W) if sixteen else W.astype(np.float32)
+    bias = (0.1 * r.standard_normal(d_out)).astype(np.float32)
+    ids = r.integers(0, table_rows, n_out).astype(np.int32)
+    rows = np.sort(r.permutation(n_out)[:max_rows]).astype(np.int32)
+    bad = rows[:n_rows][::97]                      # some listed positions carry ids outside the table
+    ids[bad[0::2]] = -1
+    ids[bad[1::2]] = table_rows
+    up = lambda a, dt: torch.from_numpy(np.ascontiguousarray(a)).cuda().to(tdt[dt])
+    t_table, t_agg, t_W = up(table, src), up(agg, "bf16" if sixteen else "f32"), up(W, "bf16" if sixteen else "f32")
+    t_cnt = torch.tensor([n_rows], dtype=torch.int64, device="cuda")
+    t_out = torch.full((n_out, d_out), -3.0, dtype=torch.float32, device="cuda")
+    t_ref = torch.full((n_out, d_out), -3.0, dtype=torch.float32, device="cuda")
+    gathered = np.zeros((n_out, d_in), np.float32)
+    ok = (ids >= 0) & (ids < table_rows)
+    gathered[ok] = table[ids[ok]]
+    rows_ok = rows.copy()
+    rows_ok[:n_rows][~ok[rows[:n_rows]]] = -1      # what fg_linear needs to be told to skip the same positions
+    wcode = B.FG_BF16 if sixteen else B.FG_F32
+    B.fg_set_tuning("linear_tile", 0 if sixteen else variant)
+    try:
+        B.fg_linear_ids(t_table, table_rows, d_in * esz, code[src], dev(torch, ids), t_agg, d_in * esz, dev(torch, rows), t_cnt,
+                        max_rows, d_in, d_out, t_W, wcode, dev(torch, bias), 1, t_out, n_out, d_out * 4, B.FG_F32, None)
+        B.fg_linear(up(gathered, src), n_out, d_in * esz, code[src], t_agg, d_in * esz, dev(torch, rows_ok), t_cnt,
+                    max_rows, d_in, d_out, t_W, wcode, dev(torch, bias), 1, t_ref, n_out, d_out * 4, B.FG_F32, None)
+    finally:
+        B.fg_set_tuning("linear_tile", 0)
+    got, ref = t_out.cpu().numpy(), t_ref.cpu().numpy()
+    assert np.array_equal(got, ref)
+    sel = rows[:n_rows][ok[rows[:n_rows]]]
+    keep = ok[rows[:n_rows]]
+    untouched = np.ones(n_out, bool)
+    untouched[sel] = False
+    assert np.all(got[untouched] == -3.0)
+    own = table[ids[sel]]
+    want = O.round_to(O.linear(O.round_bf16(own) if sixteen else own, agg[:n_rows][keep], W, bias, True), "f32")
+    if len(sel):
+        err = T.rel_err_rows(got[sel], want)
+        print(f"linear_ids {src} {d_in}x{d_out} rows {n_rows} variant {variant}: rel err {err:.3e}")
+        assert err <= (2e-2 if sixteen else REL_TOL_F32)
+
+
 @pytest.mark.parametrize("variant", [0, 301, 302, 32, 64])
 @pytest.mark.parametrize("case", ["rows scaled", "mixed within a row", "columns of W scaled", "near the upper limit", "near the lower limit"])
 def test_linear_operands_of_mixed_and_extreme_magnitude(env, case, variant):
@@ -1060,8 +1121,11 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                         sample_rows=None, feat_table=None, fused=False, one_launch_top_down=True, feature_side=None,
                         backward=False, stabilization=0, model="sage", conditioned=False, col_ids=False,
                         fetch_with_loader=True, admit_budget=None, device_sampler=False, overlap_update=True,
-                        lookahead=False, device_counts=False, fuse_small_layers=False):
+                        lookahead=False, device_counts=False, fuse_small_layers=False, copy_own_rows=False):
     """Run `iterations` iterations on both sides from an empty cache; compare everything after every call sequence.
+
+    copy_own_rows: the loader copies the layer-1 nodes' own feature rows out for the dense update (compared bit for bit
+    here); otherwise, where the pipeline can, that update reads them from the table itself and no copy exists to compare.
 
     feature_side = dict(n_hot, buffer_bytes[, poison]): both sides share the cache's buffer with the raw features of the
     graph's n_hot hottest nodes (Section 4.2). poison: once the rows are placed, the table rows of those nodes are
@@ -1084,7 +1148,8 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
                                              update_all=one_launch_top_down, hot_ids=hot,
                                              buffer_bytes=fs["buffer_bytes"] if fs else None, backward=backward, weight_grads=backward, stabilization=stabilization, model=model,
                                              fetch_with_loader=fetch_with_loader, admit_budget=admit_budget,
-                                             overlap_update=overlap_update, fuse_small_layers=fuse_small_layers)
+                                             overlap_update=overlap_update, fuse_small_layers=fuse_small_layers,
+                                             copy_own_rows=copy_own_rows)
     from paper_2301_07482_amd import binding as FGB
     bc = None
     if fs:
@@ -1273,7 +1338,9 @@ def run_workload_parity(torch, w, iterations, check_numeric_every=1, t_stale=Non
             # gathered raw features: bit-exact
             rows_chk = ipos if sample_rows is None or len(ipos) <= sample_rows else np.sort(
                 np.random.default_rng(it).choice(ipos, sample_rows, replace=False))
-            if not (fused and model == "gcn"):      # there the own rows enter the mean directly and are never stored
+            # (GCN: the own rows enter the mean directly and are never stored; nor are they where layer 1's dense update
+            #  reads them from the table itself)
+            if not (fused and model == "gcn") and not hp.own_rows_from_table(bt):
                 got0 = hp.H[0][torch.as_tensor(rows_chk.astype(np.int64), device="cuda")].cpu().numpy()
                 want0 = rec["H"][0][rows_chk]
                 differ = np.flatnonzero((got0.view(np.uint8) != want0.view(np.uint8)).any(axis=1))
@@ -1680,6 +1747,10 @@ def test_iterations_fused_input_with_node_ids_as_block_columns(env):
         assert run_workload_parity(torch, wl.WORKLOADS["tiny"], 10, fused=True, col_ids=True, fetch_with_loader=ride)[0] > 0
         assert run_workload_parity(torch, wl.WORKLOADS["medium"], 4, check_numeric_every=2, sample_rows=20000, fused=True, col_ids=True,
                                    fetch_with_loader=ride)[0] > 0
+    # the loader's copy of the layer-1 nodes' own rows (what the dense update reads where it cannot take them from the table)
+    assert run_workload_parity(torch, wl.WORKLOADS["tiny"], 10, fused=True, col_ids=True, copy_own_rows=True)[0] > 0
+    assert run_workload_parity(torch, wl.WORKLOADS["medium"], 4, check_numeric_every=2, sample_rows=20000, fused=True, col_ids=True,
+                               copy_own_rows=True)[0] > 0
 
 
 def test_iterations_access_aware_admission(env):
@@ -1831,8 +1902,10 @@ def test_iterations_medium(env):
 def test_iterations_large_hbm_full_size(env):
     """The benchmarked workload at its full size (111 M nodes, 57 GB table in HBM, 2 x 11.1 M cache slots) in the launch
     configuration bench.py times (fused loader, whole-pass top-down, seed layer in one launch, fetch and update calls), more iterations than the
-    staleness bound so that entries age out; index work compared in full every iteration, the layer-1 nodes' own
-    feature rows on a sample, numerics every 8th iteration."""
+    staleness bound so that entries age out; index work compared in full every iteration, numerics on a row sample every
+    iteration and in full every 8th. (The layer-1 dense update reads the nodes' own rows from the table here; the loader's
+    copy of them is compared bit for bit in the tests that ask for it with copy_own_rows, and at this size in the test
+    with the backward pass, whose weight gradients need it.)"""
     torch, B = env
     w = wl.WORKLOADS["large_hbm"]
     hits, worst = run_workload_parity(torch, w, 24, check_numeric_every=8, sample_rows=20000, fused=True, col_ids=True, lookahead=True,
