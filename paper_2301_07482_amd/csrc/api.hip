@@ -20,7 +20,7 @@ size_t fg_ws_lookup_prune_bytes(int64_t n);
 size_t fg_ws_cache_update_bytes(int64_t n);
 size_t fg_ws_export_bytes(int64_t capacity);
 
-static int64_t g_tune[FG_TUNE_COUNT] = {16, 4, 1, 1, 16, 0, 1};
+static int64_t g_tune[FG_TUNE_COUNT] = {16, 4, 1, 1, 32, 0, 1};
 static const char* const g_tune_names[FG_TUNE_COUNT] = {"gather_wg_per_cu", "gather_host_wg_per_cu", "gather_unroll",
                                                         "gather_nontemporal", "aggregate_wg_per_cu", "linear_tile",
                                                         "top_down_walk"};
