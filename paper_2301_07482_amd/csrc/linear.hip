@@ -361,7 +361,12 @@ __device__ __forceinline__ void split8(const float* v, u32x4& t1, u32x4& t2, u32
     }
 }
 
-template <int NB>
+// RAGGED: d_in is a multiple of 4 but not of 32. Each half of the operand is then walked as if it were d_pad = d_in rounded
+// up to 32 wide: the k values from d_in to d_pad have zero weights in the panel, and the 16-byte pieces of a row that would
+// lie there are read from 16 bytes of zeros instead (a piece lies wholly inside or wholly outside the row's d_in values).
+__device__ __attribute__((aligned(16))) float x3_zero[4];
+
+template <int NB, bool RAGGED>
 __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
     const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
     const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
@@ -371,8 +376,9 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
     extern __shared__ __attribute__((aligned(16))) u32x4 bfrag[];  // [3 terms][K / 8 groups of k][BNW columns]
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
     if (n_rows > max_rows) n_rows = max_rows;
-    const int K = 2 * d_in;
-    const int nk = K / KC, nk_self = d_in / KC;
+    const int d_pad = RAGGED ? (d_in + KC - 1) / KC * KC : d_in;
+    const int K = 2 * d_pad;      // the contraction length as it is walked
+    const int nk = K / KC, nk_self = d_pad / KC;
     const int ngr = K / 8;
     const int t = threadIdx.x;
     const int xcd = blockIdx.x & 7;
@@ -390,15 +396,21 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
         const int c4 = (q % (BNW / 4)) * 4, gi = q / (BNW / 4);
         const int k0 = 32 * (gi >> 2) + 16 * (gi & 1) + 8 * ((gi >> 1) & 1);
         const bool in = n0 + c4 < d_out;      // d_out is a multiple of 4: the four columns exist together
-        const float* wp = W + (int64_t)k0 * d_out + (in ? n0 + c4 : 0);
+        const float* wp = W + (in ? n0 + c4 : 0);
         f32x4 w4[8];
+        bool k_in[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) w4[e] = *(const f32x4*)(wp + (int64_t)e * d_out);
+        for (int e = 0; e < 8; ++e) {     // walked k -> row of W: the second half starts at d_in; padding rows read row 0
+            const int kp = k0 + e, hf = (RAGGED && kp >= d_pad) ? 1 : 0, kk = kp - hf * d_pad;
+            k_in[e] = !RAGGED || kk < d_in;
+            const int wrow = RAGGED ? (k_in[e] ? hf * d_in + kk : 0) : kp;
+            w4[e] = *(const f32x4*)(wp + (int64_t)wrow * d_out);
+        }
 #pragma unroll
         for (int cc = 0; cc < 4; ++cc) {
             float v[8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) v[e] = in ? w4[e][cc] : 0.f;
+            for (int e = 0; e < 8; ++e) v[e] = (in && k_in[e]) ? w4[e][cc] : 0.f;
             u32x4 t1, t2, t3;
             split8(v, t1, t2, t3);
             bfrag[(0 * ngr + gi) * BNW + c4 + cc] = t1;
@@ -459,9 +471,17 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
         int32_t r = rowlist[l32], s = srclist[l32];
         const float* a_self = (const float*)(h_src + (r >= 0 ? (int64_t)s * src_stride : 0)) + 16 * half;
         const float* a_agg = (const float*)(agg + (r >= 0 ? (rb0 * 32 + l32) * agg_stride : 0)) + 16 * half;
-        f32x4 a0[4], a1[4];
+        // the four 16-byte pieces of chunk `c` of one half of a row (base = that half's first value + 16 * half)
+        auto load_chunk = [&](const float* base, int c, f32x4* a) {
+            const float* p = base + c * KC;
 #pragma unroll
-        for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(a_self + 4 * q);  // step 0 of the first task of the list
+            for (int q = 0; q < 4; ++q) {
+                const bool there = !RAGGED || c * KC + 16 * half + 4 * q < d_in;
+                a[q] = *(const f32x4*)(there ? p + 4 * q : (const float*)x3_zero);
+            }
+        };
+        f32x4 a0[4], a1[4];
+        load_chunk(a_self, 0, a0);  // step 0 of the first task of the list
         for (int tk = 0; tk < X3_LIST; ++tk) {
             const int64_t rb = rb0 + tk * stride;
             if (rb >= n_blocks) break;
@@ -514,19 +534,18 @@ __global__ __launch_bounds__(PL_THREADS, 2) void linear_f32x3_panel_kernel(
             for (int step = 0; step < nk; step += 2) {
                 {
                     const int s1 = step + 1;
-                    const float* p = s1 < nk_self ? a_self + s1 * KC : a_agg + (s1 - nk_self) * KC;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) a1[q] = *(const f32x4*)(p + 4 * q);
+                    const bool own = s1 < nk_self;
+                    load_chunk(own ? a_self : a_agg, own ? s1 : s1 - nk_self, a1);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 compute(step, a0);
                 {
                     const int s2 = step + 2;
                     const float* nxt = (const float*)(h_src + (r_next >= 0 ? (int64_t)s_next * src_stride : 0)) + 16 * half;
-                    const float* cur = s2 < nk_self ? a_self + s2 * KC : a_agg + (s2 < nk ? s2 - nk_self : 0) * KC;
-                    const float* p = s2 < nk ? cur : nxt;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) a0[q] = *(const f32x4*)(p + 4 * q);
+                    // past the last step: step 0 of the next task's own half
+                    const float* base = s2 < nk_self ? a_self : (s2 < nk ? a_agg : nxt);
+                    const int c = s2 < nk_self ? s2 : (s2 < nk ? s2 - nk_self : 0);
+                    load_chunk(base, c, a0);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 compute(step + 1, a1);
@@ -794,10 +813,13 @@ static fg_status_t linear_launch(const char* who, const void* h_src, int32_t n_s
             FG_LAUNCH_CHECK("linear_f32_splitk_kernel");
             return FG_OK;
         }
-        // bf16 x 3 panel kernel: two 32-column blocks per wavefront if the split panel fits in LDS, else one
-        const size_t x3_bytes = (size_t)2 * d_in * 192;
+        // bf16 x 3 panel kernel: two 32-column blocks per wavefront if the split panel fits in LDS, else one. A d_in that is
+        // not a multiple of 32 is walked as the next multiple (zero weights, zero pieces: the RAGGED variant).
+        const int d_pad = (int)(fg_ceil_div(d_in, KC) * KC);
+        const bool ragged = d_pad != d_in;
+        const size_t x3_bytes = (size_t)2 * d_pad * 192;
         const size_t x3_lists = (size_t)X3_LIST_BYTES * (src_ids_dev ? 2 : 1);
-        if (d_in % KC == 0 && x3_bytes + x3_lists <= 160 * 1024 && x3_bytes <= 144 * 1024 && (forced == 0 || forced == 301 || forced == 302)) {
+        if (x3_bytes + x3_lists <= 160 * 1024 && x3_bytes <= 144 * 1024 && (forced == 0 || forced == 301 || forced == 302)) {
             const int nb = (forced != 301 && 2 * x3_bytes <= 144 * 1024) ? 2 : 1;
             const size_t lds = x3_bytes * nb + x3_lists;          // fragments of the panel, then the wavefronts' row lists
             const int n_panels = (int)fg_ceil_div(d_out, PL_BN * nb);
@@ -808,16 +830,16 @@ static fg_status_t linear_launch(const char* who, const void* h_src, int32_t n_s
             const int n_groups = 8 * q;
             // output offsets in 32 bits: every byte of h_out below 2^31, rows and stride below 2^24
             const int near_out = ((int64_t)n_out * out_stride < (1ll << 31) && n_out < (1 << 24) && out_stride < (1 << 24)) ? 1 : 0;
-            if (nb == 2)
-                hipLaunchKernelGGL(linear_f32x3_panel_kernel<2>, dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), lds, st,
-                                   (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev,
-                                   max_rows, d_in, d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels,
-                                   n_groups, near_out, src_ids_dev);
-            else
-                hipLaunchKernelGGL(linear_f32x3_panel_kernel<1>, dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), lds, st,
-                                   (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev,
-                                   max_rows, d_in, d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels,
-                                   n_groups, near_out, src_ids_dev);
+#define FG_X3(NBV, RAG)                                                                                                        \
+    hipLaunchKernelGGL((linear_f32x3_panel_kernel<NBV, RAG>), dim3((unsigned)(n_groups * n_panels)), dim3(PL_THREADS), lds, st,  \
+                       (const char*)h_src, n_src, src_stride, (const char*)agg, agg_stride, rows_dev, n_rows_dev, max_rows, d_in, \
+                       d_out, (const float*)W, bias, relu, (char*)h_out, n_out, out_stride, n_panels, n_groups, near_out, src_ids_dev)
+            if (nb == 2) {
+                if (ragged) FG_X3(2, true); else FG_X3(2, false);
+            } else {
+                if (ragged) FG_X3(1, true); else FG_X3(1, false);
+            }
+#undef FG_X3
             FG_LAUNCH_CHECK("linear_f32x3_panel_kernel");
             return FG_OK;
         }

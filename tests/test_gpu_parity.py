@@ -362,6 +362,38 @@ def test_linear_matches_oracle(env, d_in, d_out, n_rows, max_rows, relu, variant
     assert err <= REL_TOL_F32
 
 
+@pytest.mark.parametrize("variant", [0, 301, 302, 32, 64])
+@pytest.mark.parametrize("d_in,d_out", [(100, 256), (36, 64), (4, 32), (28, 96)])
+def test_linear_width_not_a_multiple_of_32_ignores_what_follows_a_row(env, d_in, d_out, variant):
+    """Rows wider apart than d_in values, with NaN in the gap (own rows and means alike), and NaN rows around the listed
+    ones: a kernel that walks such a width as the next multiple of 32 must not let anything beyond a row's d_in values
+    into a product, zero weight or not."""
+    torch, B = env
+    r = np.random.default_rng(d_in * 5 + d_out + variant)
+    n_src, n_rows, pad = 1500, 1100, 12
+    h = np.full((n_src, d_in + pad), np.nan, np.float32)
+    agg = np.full((n_rows, d_in + pad), np.nan, np.float32)
+    rows = np.sort(r.permutation(n_src)[:n_rows]).astype(np.int32)
+    h[rows, :d_in] = r.standard_normal((n_rows, d_in)).astype(np.float32)
+    agg[:, :d_in] = (r.standard_normal((n_rows, d_in)) * 0.3).astype(np.float32)
+    W = (r.standard_normal((2 * d_in, d_out)) / np.sqrt(2 * d_in)).astype(np.float32)
+    bias = (0.1 * r.standard_normal(d_out)).astype(np.float32)
+    t_out = torch.full((n_src, d_out), -3.0, dtype=torch.float32, device="cuda")
+    t_cnt = torch.tensor([n_rows], dtype=torch.int64, device="cuda")
+    B.fg_set_tuning("linear_tile", variant)
+    try:
+        B.fg_linear(dev(torch, h), n_src, (d_in + pad) * 4, B.FG_F32, dev(torch, agg), (d_in + pad) * 4, dev(torch, rows), t_cnt,
+                    n_rows, d_in, d_out, dev(torch, W), B.FG_F32, dev(torch, bias), 1, t_out, n_src, d_out * 4, B.FG_F32, None)
+    finally:
+        B.fg_set_tuning("linear_tile", 0)
+    got = t_out.cpu().numpy()
+    want = O.round_to(O.linear(h[rows, :d_in], agg[:, :d_in], W, bias, True), "f32")
+    assert np.all(np.isfinite(got))
+    err = T.rel_err_rows(got[rows], want)
+    print(f"linear {d_in}x{d_out} with gaps, variant {variant}: rel err {err:.3e}")
+    assert err <= REL_TOL_F32
+
+
 @pytest.mark.parametrize("variant", [0, 8, 32, 64, 301, 302, "bf16", "f16"])
 @pytest.mark.parametrize("d_in,d_out,n_rows,max_rows", [(128, 256, 4097, 5000), (256, 256, 700, 700), (100, 64, 333, 400),
                                                         (64, 64, 0, 128), (128, 256, 20000, 20000)])
