@@ -533,6 +533,7 @@ def timed_region(hp, batches, first_timed, steps, total, bracket_every, lookahea
         hp.overlap_update = overlapped and not alone
         hp.run(batches[it], it, timer=timer_for(step_events, only=bracketed) if (alone or beside) else None, next_bt=ahead)
         (ev if alone else ev_ovl).append(step_events)
+    hp.flush()      # the last step's row copy (left to the next call when that call's top-down pass is already queued) belongs to it
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     hp.overlap_update = overlapped
