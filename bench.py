@@ -275,7 +275,7 @@ def main():
     stats_log = hp.stats_log.cpu().numpy()
     steps_it = [first_timed + k for k in range(args.steps)]
     # the roofline figures price the launches that were bracketed: the same steps' counts
-    roof_it = [first_timed + k for k in range(args.steps) if k % args.bracket_every == 0]
+    roof_it = [first_timed + k for k in range(args.steps) if alone_step(k, args.steps, args.bracket_every)]
     counts = [counts_log[it % hp.ring] for it in roof_it]
     counts_all = [counts_log[it % hp.ring] for it in steps_it]
     esz = {"f32": 4, "f16": 2, "bf16": 2}
@@ -511,13 +511,22 @@ def spans(event_log):
     return {k: float(np.mean(v)) for k, v in out.items()}
 
 
+def alone_step(k, steps, bracket_every):
+    """Whether timed step k is one whose bracketed launches have the chip to themselves: every `bracket_every`-th step,
+    starting half a period in (the first step after the opening synchronisation finds an idle device and is no sample
+    of the steady state); step 0 where the region is shorter than that."""
+    first = bracket_every // 2 if steps > bracket_every // 2 else 0
+    return k >= first and (k - first) % bracket_every == 0
+
+
 def timed_region(hp, batches, first_timed, steps, total, bracket_every, lookahead, bracketed):
     """Exactly `steps` iterations (mini-batches first_timed ..) between two device synchronisations. HIP events on the
     launch stream bracket only the calls named in `bracketed`, and only on every `bracket_every`-th step, so that the
     region is not perturbed (an event record costs about 3 us of stream time). Two kinds of bracketed steps: every
     `bracket_every`-th step runs with every call on the one stream, so that the bracketed launches have the chip to
-    themselves (the durations `roofline` is priced on, comparable with a kernel trace); half way between them a step is
-    bracketed as it normally runs, with the bookkeeping launches of the second stream beside it.
+    themselves (the durations `roofline` is priced on, comparable with a kernel trace; the first of these steps comes half
+    a period into the region, see alone_step); half way between them a step is bracketed as it normally runs, with the
+    bookkeeping launches of the second stream beside it.
     Returns (seconds, {call: ms} of the one-stream steps, {call: ms} of the overlapped steps)."""
     import torch
     ev, ev_ovl = [], []
@@ -527,8 +536,8 @@ def timed_region(hp, batches, first_timed, steps, total, bracket_every, lookahea
     for k in range(steps):
         it = first_timed + k
         step_events = {}
-        alone = k % bracket_every == 0
-        beside = overlapped and k % bracket_every == bracket_every // 2
+        alone = alone_step(k, steps, bracket_every)
+        beside = overlapped and k > 0 and k % bracket_every == 0
         ahead = batches[it + 1] if (it + 1 < total and lookahead and not alone) else None   # its top-down pass runs beside this step's layers
         hp.overlap_update = overlapped and not alone
         hp.run(batches[it], it, timer=timer_for(step_events, only=bracketed) if (alone or beside) else None, next_bt=ahead)
@@ -598,7 +607,7 @@ def policy_paper_run(w, feat, sampled, args, ids_cols):
         elapsed, timed_ms, _ = timed_region(hp, batches, first_timed, args.steps, total, args.bracket_every, not args.no_lookahead,
                                             (loader, "linear[1]"))
         counts_log = hp.counts_log.cpu().numpy()
-        roof_it = [first_timed + k for k in range(args.steps) if k % args.bracket_every == 0]
+        roof_it = [first_timed + k for k in range(args.steps) if alone_step(k, args.steps, args.bracket_every)]
         steps_it = [first_timed + k for k in range(args.steps)]
         counts = [counts_log[it % hp.ring] for it in roof_it]
         counts_all = [counts_log[it % hp.ring] for it in steps_it]
