@@ -407,9 +407,11 @@ extern "C" fg_status_t fg_layer_backward_bf16(const float* dh_dev, int64_t dh_st
 //
 // dW = X^T . dz and db = column sums of dz over the computed rows, X[k, :] = [h_src[rows[k], :] ‖ agg[k, :]],
 // dz[k, :] = dh[rows[k], :] * (h[rows[k], :] > 0). A contraction over the rows (K = tens of thousands) with a small
-// result (2*d_in x d_out), so K is split over the workgroups: workgroup `chunk` multiplies its rows on the fp32
-// matrix cores and leaves a partial result, a second launch adds the partials up in fp64.
-// Both operands are read straight from global memory in the layout v_mfma_f32_32x32x2_f32 wants (for the two rows k, k+1 a
+// result (2*d_in x d_out), so K is split over the workgroups: workgroup `chunk` multiplies its rows on the matrix
+// cores and leaves a partial result, a second launch adds the partials up in fp64. Two kernels for the partial
+// products: weight_grad_partial_x3_kernel (further down, the default: bf16 matrix instructions on three-way splits of
+// both operands) and this one on the fp32 matrix instructions (operands beyond 4 GB, or asked for through the tuning key).
+// Here both operands are read straight from global memory in the layout v_mfma_f32_32x32x2_f32 wants (for the two rows k, k+1 a
 // lane supplies one element of row k + lane/32 per block), with no transposition and no LDS.
 // A workgroup of 8 wavefronts (4 along M x 2 along N) owns a 256 x 256 tile of the result, a wavefront 64 x 128 of it as
 // 2 x 4 blocks of 32 x 32. The blocks interleave: a lane's elements for the two row blocks are adjacent columns of X and
@@ -549,6 +551,215 @@ __global__ __launch_bounds__(WG_THREADS) void weight_grad_partial_kernel(
             const int c = n_quad + j;
             if (kh == 0 && c < N) part_b[(int64_t)chunk * N + c] = s;
         }
+    }
+}
+
+// The same partial products on the bf16 matrix cores. Every fp32 value is the exact sum of three bf16 values
+// (x1 = bf16(x), x2 = bf16(x - x1), x3 = bf16(x - x1 - x2), nearest even), and the six products a_i * b_j with i + j <= 4
+// (1-based; each exact in fp32) are kept: the dropped three are below 2^-24 of the product. v_mfma_f32_32x32x16_bf16 wants
+// its contraction index contiguous in a lane, which for X^T . dz is the row index, so both operands go through LDS
+// transposed: a step is 16 rows; thread (column c, group g) of the workgroup loads the 8 values X[k0 + 8g .. + 7][c] (each
+// load coalesced over the columns), splits them and writes the three 16-byte fragments where the lane that needs them
+// for (column c, k half g) reads them back with one LDS load: [term][g][column], conflict-free both ways. The same thread
+// does the same for dz (mask applied to the loaded values, column sums for db kept in a register). Splitting is shared by
+// the whole workgroup: 16 values per thread and step next to 48 matrix instructions per wavefront. Two LDS buffers, one
+// barrier per step; the values of step s + 1 and the row positions of step s + 2 are in flight while step s is multiplied.
+// A wavefront owns 64 x 128 of the 256 x 256 tile as before; fp32 sums within a slice, fp64 across the slices.
+typedef unsigned int wu32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 wbf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 wbf16x2 __attribute__((ext_vector_type(2)));
+
+constexpr int WX_STEP = 16;                          // rows per step: the K of one matrix instruction
+constexpr int WX_FRAGS = 3 * 2 * WG_TILE;            // 16-byte fragments of one operand per step
+constexpr size_t WX_LDS_BYTES = (size_t)2 * 2 * WX_FRAGS * 16;  // two operands, two buffers: 96 KB
+
+// v[0..7] -> three fragments of eight bf16 (element j in half j % 2 of word j / 2)
+__device__ __forceinline__ void wx_split8(const float* v, wu32x4& t1, wu32x4& t2, wu32x4& t3) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        const f32x2 x = {v[2 * p], v[2 * p + 1]};
+        const wbf16x2 b1 = __builtin_convertvector(x, wbf16x2);
+        const unsigned int u1 = __builtin_bit_cast(unsigned int, b1);
+        const f32x2 r1 = {x[0] - __uint_as_float(u1 << 16), x[1] - __uint_as_float(u1 & 0xFFFF0000u)};
+        const wbf16x2 b2 = __builtin_convertvector(r1, wbf16x2);
+        const unsigned int u2 = __builtin_bit_cast(unsigned int, b2);
+        const f32x2 r2 = {r1[0] - __uint_as_float(u2 << 16), r1[1] - __uint_as_float(u2 & 0xFFFF0000u)};
+        const wbf16x2 b3 = __builtin_convertvector(r2, wbf16x2);
+        t1[p] = u1;
+        t2[p] = u2;
+        t3[p] = __builtin_bit_cast(unsigned int, b3);
+    }
+}
+
+__global__ __launch_bounds__(WG_THREADS, 2) void weight_grad_partial_x3_kernel(
+    const char* __restrict__ h_src, int n_src, int64_t src_stride, const char* __restrict__ agg, int64_t agg_stride,
+    const char* __restrict__ dh, int64_t dh_stride, const char* __restrict__ h, int64_t h_stride, int n,
+    const int32_t* __restrict__ rows, const int64_t* __restrict__ n_rows_dev, int64_t max_rows, int d_in, int d_out,
+    float* __restrict__ part_w, float* __restrict__ part_b) {
+    extern __shared__ __attribute__((aligned(16))) wu32x4 wx_lds[];   // [buffer][operand][term][group][column]
+    int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
+    if (n_rows > max_rows) n_rows = max_rows;
+    const int M = 2 * d_in, N = d_out;
+    const int chunk = blockIdx.x;
+    const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+    const int l32 = lane & 31, half = lane >> 5;
+    const int wm = wave & 3, wn = wave >> 2;
+    const int m_tile = blockIdx.y * WG_TILE, n_tile = blockIdx.z * WG_TILE;
+    // the rows there are, split evenly over the chunks of the launch (whole steps per chunk)
+    const int64_t per = (n_rows + gridDim.x - 1) / gridDim.x;
+    const int64_t per_b = (per + WX_STEP - 1) / WX_STEP * WX_STEP;
+    const int64_t k_begin = (int64_t)chunk * per_b < n_rows ? (int64_t)chunk * per_b : n_rows;
+    int64_t k_end = k_begin + per_b;
+    if (k_end > n_rows) k_end = n_rows;
+    const int n_steps = (int)((k_end - k_begin + WX_STEP - 1) / WX_STEP);
+
+    // staging role of this thread: column pc of both tiles, rows 8 * pg .. 8 * pg + 7 of a step
+    const int pc = t & (WG_TILE - 1), pg = t >> 8;
+    const int xc = m_tile + pc;
+    const bool x_ok = xc < M, x_self = xc < d_in;
+    const int x_col = x_ok ? (x_self ? xc : xc - d_in) : 0;
+    const int zc = n_tile + pc;
+    const bool z_ok = zc < N;
+    const int z_col = z_ok ? zc : 0;
+
+    // The loaded values of one step wait in registers: they are requested a whole step (its matrix instructions, its
+    // barrier) before they are split and written to LDS, the row positions one step earlier still.
+    struct Vals {
+        float xv[8], gv[8], ov[8];
+        unsigned ok;     // bit e: row e exists
+    };
+    int32_t pos_next[8];
+    float colsum = 0.f;
+    // positions of the rows of step s (list entries k_begin + 16 s + 8 pg + e); an entry past the chunk reads entry k_begin
+    auto load_positions = [&](int s) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t kk = k_begin + (int64_t)s * WX_STEP + 8 * pg + e;
+            const int64_t ks = kk < k_end ? kk : k_begin;
+            pos_next[e] = rows ? rows[ks] : (int32_t)ks;
+        }
+    };
+    // values of step s from the positions loaded for it; rows that do not exist read row 0 / entry k_begin and count as zero
+    auto load_values = [&](int s, Vals& V) {
+        V.ok = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int64_t kk = k_begin + (int64_t)s * WX_STEP + 8 * pg + e;
+            const bool in = kk < k_end;
+            const int64_t ks = in ? kk : k_begin;
+            const int32_t r = pos_next[e];
+            const bool ok = in && r >= 0 && r < n && r < n_src;
+            V.ok |= ok ? (1u << e) : 0u;
+            // byte offsets in 32 bits (the host checks that every operand is below 4 GB): one register per address
+            const uint32_t rs = ok ? (uint32_t)r : 0u;
+            const uint32_t x_off = x_self ? rs * (uint32_t)src_stride + 4u * (uint32_t)x_col
+                                          : (uint32_t)ks * (uint32_t)agg_stride + 4u * (uint32_t)x_col;
+            V.xv[e] = *(const float*)((x_self ? h_src : agg) + x_off);
+            V.gv[e] = *(const float*)(dh + (rs * (uint32_t)dh_stride + 4u * (uint32_t)z_col));
+            V.ov[e] = h ? *(const float*)(h + (rs * (uint32_t)h_stride + 4u * (uint32_t)z_col)) : 1.f;
+        }
+    };
+    // mask, split and write the loaded step to buffer b
+    auto stage = [&](int b, const Vals& V) {
+        float xs8[8], zs8[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const bool ok = (V.ok >> e) & 1u;
+            xs8[e] = (ok && x_ok) ? V.xv[e] : 0.f;
+            zs8[e] = (ok && z_ok && V.ov[e] > 0.f) ? V.gv[e] : 0.f;
+            colsum += zs8[e];
+        }
+        wu32x4 a1, a2, a3, b1, b2, b3;
+        wx_split8(xs8, a1, a2, a3);
+        wx_split8(zs8, b1, b2, b3);
+        wu32x4* X = wx_lds + (size_t)b * 2 * WX_FRAGS;
+        wu32x4* Z = X + WX_FRAGS;
+        X[(0 * 2 + pg) * WG_TILE + pc] = a1;
+        X[(1 * 2 + pg) * WG_TILE + pc] = a2;
+        X[(2 * 2 + pg) * WG_TILE + pc] = a3;
+        Z[(0 * 2 + pg) * WG_TILE + pc] = b1;
+        Z[(1 * 2 + pg) * WG_TILE + pc] = b2;
+        Z[(2 * 2 + pg) * WG_TILE + pc] = b3;
+    };
+
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    // one step out of buffer b: 48 matrix instructions per wavefront
+    auto multiply = [&](int b) {
+        const wu32x4* X = wx_lds + (size_t)b * 2 * WX_FRAGS;
+        const wu32x4* Z = X + WX_FRAGS;
+        wu32x4 ax[2][3];
+#pragma unroll
+        for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+            for (int term = 0; term < 3; ++term) ax[mb][term] = X[(term * 2 + half) * WG_TILE + wm * 64 + mb * 32 + l32];
+        // (X term, dz term) pairs, smallest products first
+        constexpr int TA[6] = {2, 0, 1, 1, 0, 0};
+        constexpr int TZ[6] = {0, 2, 1, 0, 1, 0};
+#pragma unroll
+        for (int nb = 0; nb < 4; ++nb) {
+            wu32x4 bz[3];
+#pragma unroll
+            for (int term = 0; term < 3; ++term) bz[term] = Z[(term * 2 + half) * WG_TILE + wn * 128 + nb * 32 + l32];
+#pragma unroll
+            for (int e = 0; e < 6; ++e)
+#pragma unroll
+                for (int mb = 0; mb < 2; ++mb)
+                    acc[mb][nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(wbf16x8, ax[mb][TA[e]]),
+                                                                          __builtin_bit_cast(wbf16x8, bz[TZ[e]]), acc[mb][nb], 0, 0, 0);
+        }
+    };
+
+    if (n_steps > 0) {      // uniform over the workgroup
+        Vals V;
+        load_positions(0);
+        load_values(0, V);
+        if (n_steps > 1) load_positions(1);
+        stage(0, V);
+        if (n_steps > 1) {
+            load_values(1, V);
+            if (n_steps > 2) load_positions(2);
+        }
+        __syncthreads();
+        for (int s = 0; s < n_steps; ++s) {
+            const int b = s & 1;
+            // step s + 1 goes to the other buffer (last read a step ago, before the previous barrier), then the registers take
+            // step s + 2, and step s is multiplied with those loads in flight
+            if (s + 1 < n_steps) stage(b ^ 1, V);
+            if (s + 2 < n_steps) {
+                load_values(s + 2, V);
+                if (s + 3 < n_steps) load_positions(s + 3);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            multiply(b);
+            __syncthreads();
+        }
+    }
+    // partial result of this chunk (zeros if the chunk lies beyond the rows there are): accumulator element e of a block is
+    // its row 8 * (e / 4) + 4 * half + e % 4, column l32
+    float* pw = part_w + (int64_t)chunk * M * N;
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int m = m_tile + wm * 64 + mb * 32 + 8 * (e >> 2) + 4 * half + (e & 3);
+#pragma unroll
+            for (int nb = 0; nb < 4; ++nb) {
+                const int c = n_tile + wn * 128 + nb * 32 + l32;
+                if (m < M && c < N) pw[(int64_t)m * N + c] = acc[mb][nb][e];
+            }
+        }
+    if (blockIdx.y == 0) {      // column sums of dz: the two row groups of a column meet in LDS
+        float* red = (float*)wx_lds;
+        red[t] = colsum;
+        __syncthreads();
+        if (t < WG_TILE && z_ok) part_b[(int64_t)chunk * N + zc] = red[t] + red[t + WG_TILE];
     }
 }
 
@@ -732,9 +943,20 @@ extern "C" fg_status_t fg_layer_backward_weights(const float* h_src_dev, int32_t
     float* part_b = (float*)((char*)ws_dev + P.part_b);
     // without rows (or without anything they could index) every chunk is empty and the partials are zeros
     const int64_t rows_bound = (n > 0 && n_src > 0) ? max_rows : 0;
-    hipLaunchKernelGGL(weight_grad_partial_kernel, dim3((unsigned)P.n_chunks, (unsigned)P.tiles_m, (unsigned)P.tiles_n), dim3(WG_THREADS), 0, st,
-                       (const char*)h_src_dev, n_src, src_stride, (const char*)agg_dev, agg_stride, (const char*)dh_dev, dh_stride,
-                       (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, rows_bound, d_in, d_out, part_w, part_b);
+    // the products on the bf16 matrix cores (three-way split of both operands) unless the fp32 instructions are asked for
+    const int64_t forced = fg_tuning(FG_TUNE_LINEAR_TILE);
+    // (its byte offsets are 32-bit: every operand has to end below 4 GB)
+    const int64_t lim = (int64_t)1 << 32;
+    const bool near = (int64_t)n_src * src_stride < lim && max_rows * agg_stride < lim && (int64_t)n * dh_stride < lim &&
+                      (!h_dev || (int64_t)n * h_stride < lim);
+    if (forced == 32 || forced == 64 || forced == 128 || !near)
+        hipLaunchKernelGGL(weight_grad_partial_kernel, dim3((unsigned)P.n_chunks, (unsigned)P.tiles_m, (unsigned)P.tiles_n), dim3(WG_THREADS), 0, st,
+                           (const char*)h_src_dev, n_src, src_stride, (const char*)agg_dev, agg_stride, (const char*)dh_dev, dh_stride,
+                           (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, rows_bound, d_in, d_out, part_w, part_b);
+    else
+        hipLaunchKernelGGL(weight_grad_partial_x3_kernel, dim3((unsigned)P.n_chunks, (unsigned)P.tiles_m, (unsigned)P.tiles_n), dim3(WG_THREADS),
+                           WX_LDS_BYTES, st, (const char*)h_src_dev, n_src, src_stride, (const char*)agg_dev, agg_stride, (const char*)dh_dev,
+                           dh_stride, (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, rows_bound, d_in, d_out, part_w, part_b);
     FG_LAUNCH_CHECK("weight_grad_partial_kernel");
     const int64_t mn = (int64_t)2 * d_in * d_out;
     const int w_blocks = (int)fg_ceil_div(mn, 128), b_blocks = (int)fg_ceil_div(d_out, 128);

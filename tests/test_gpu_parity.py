@@ -939,11 +939,22 @@ def test_layer_backward_matches_oracle(env, d_in, d_out, n, n_src, max_deg, relu
     assert (np.abs(want).sum(axis=1) == 0).sum() == (np.abs(got).sum(axis=1) == 0).sum()
 
 
+@pytest.mark.parametrize("variant", [0, 32])
 @pytest.mark.parametrize("d_in,d_out,n,n_rows,relu,seed", [(128, 256, 5000, 4100, True, 0), (256, 256, 700, 700, True, 1),
                                                          (64, 64, 300, 250, False, 2), (24, 72, 130, 77, True, 3),
-                                                         (8, 8, 9, 1, True, 4), (128, 256, 40, 0, True, 5)])
-def test_layer_backward_weights_match_oracle(env, d_in, d_out, n, n_rows, relu, seed):
+                                                         (8, 8, 9, 1, True, 4), (128, 256, 40, 0, True, 5),
+                                                         (128, 256, 30000, 29001, True, 6), (200, 300, 3000, 2999, True, 7)])
+def test_layer_backward_weights_match_oracle(env, d_in, d_out, n, n_rows, relu, seed, variant):
+    """variant 0: the partial products on the bf16 matrix cores (three-way split of both operands); 32: on the fp32 ones."""
     torch, B = env
+    B.fg_set_tuning("linear_tile", variant)
+    try:
+        _layer_backward_weights_case(torch, B, d_in, d_out, n, n_rows, relu, seed)
+    finally:
+        B.fg_set_tuning("linear_tile", 0)
+
+
+def _layer_backward_weights_case(torch, B, d_in, d_out, n, n_rows, relu, seed):
     r = np.random.default_rng(seed)
     n_src = n + 50
     rows = np.sort(r.permutation(n)[:n_rows]).astype(np.int32)
