@@ -204,7 +204,8 @@ __device__ __forceinline__ void aggregate_backward_row(
 
 // Groups of 2^lanes_log2 lanes take the source positions in turn. Where a group is smaller than a wavefront (several rows,
 // several chains of index reads, per wavefront: what a layer with many rows wants), a position with more than `many`
-// incoming edges is left out of that sweep and taken by a whole wavefront in a second one: a small group walks the edge list
+// incoming edges is left out of that sweep and taken by a whole wavefront in a second one (by other workgroups of the same
+// launch): a small group walks the edge list
 // once per piece it holds, which for the hubs of a power-law graph was the whole launch (measured: 166 us against 84 us
 // with one row per wavefront on the workload with average degree 50). Every position is written by exactly one group.
 template <bool GCN>
@@ -212,36 +213,40 @@ __global__ __launch_bounds__(BW_THREADS) void aggregate_backward_kernel(
     const char* __restrict__ dx, int n, int d_in, const uint8_t* __restrict__ live, const uint8_t* __restrict__ hit,
     const int32_t* __restrict__ row_start, const int32_t* __restrict__ row_end, const int32_t* __restrict__ t_start,
     const int32_t* __restrict__ t_end, const int32_t* __restrict__ t_row, int64_t nnz, int n_src, char* __restrict__ out,
-    int64_t out_stride, int lanes_log2, float* __restrict__ norms, int many) {
+    int64_t out_stride, int lanes_log2, float* __restrict__ norms, int many, int sweep2_blocks) {
     const int lanes = 1 << lanes_log2;
     const int lane = threadIdx.x & (lanes - 1);
     const int gpb = BW_THREADS >> lanes_log2;
     const bool two_sweeps = lanes < 64;
-    for (int64_t j = (int64_t)blockIdx.x * gpb + (threadIdx.x >> lanes_log2); j < n_src; j += (int64_t)gridDim.x * gpb) {
+    if ((int)blockIdx.x < sweep2_blocks) {
+        // second sweep, by workgroups of its own at the front of the grid (the long rows start first): a wavefront looks
+        // at 64 positions at once (one coalesced read of their ranges) and takes those with many incoming edges one after the
+        // other, all 64 lanes on each
+        const int wl = threadIdx.x & 63;
+        const int64_t n_waves = (int64_t)sweep2_blocks * (BW_THREADS >> 6);
+        for (int64_t j0 = ((int64_t)blockIdx.x * (BW_THREADS >> 6) + (threadIdx.x >> 6)) * 64; j0 < n_src; j0 += n_waves * 64) {
+            int32_t s = 0, e = 0;
+            if (j0 + wl < n_src) {
+                s = t_start[j0 + wl];
+                e = t_end[j0 + wl];
+                if (s < 0 || e < s || (int64_t)e > nnz) s = e = 0;
+            }
+            unsigned long long big = __ballot(e - s > many);
+            while (big) {      // uniform over the wavefront
+                const int b = __ffsll((long long)big) - 1;
+                big &= big - 1;
+                const int32_t s0 = __shfl(s, b, 64), e0 = __shfl(e, b, 64);
+                aggregate_backward_row<GCN>(j0 + b, s0, e0, wl, 64, dx, n, d_in, live, hit, row_start, row_end, t_row, out, out_stride, norms);
+            }
+        }
+        return;
+    }
+    const int64_t block = (int64_t)blockIdx.x - sweep2_blocks, n_blocks = (int64_t)gridDim.x - sweep2_blocks;
+    for (int64_t j = block * gpb + (threadIdx.x >> lanes_log2); j < n_src; j += n_blocks * gpb) {
         int32_t s0 = t_start[j], e0 = t_end[j];
         if (s0 < 0 || e0 < s0 || (int64_t)e0 > nnz) s0 = e0 = 0;
         if (two_sweeps && e0 - s0 > many) continue;
         aggregate_backward_row<GCN>(j, s0, e0, lane, lanes, dx, n, d_in, live, hit, row_start, row_end, t_row, out, out_stride, norms);
-    }
-    if (!two_sweeps) return;
-    // second sweep: a wavefront looks at 64 positions at once (one coalesced read of their ranges) and takes those with many
-    // incoming edges one after the other, all 64 lanes on each
-    const int wl = threadIdx.x & 63;
-    const int64_t n_waves = (int64_t)gridDim.x * (BW_THREADS >> 6);
-    for (int64_t j0 = ((int64_t)blockIdx.x * (BW_THREADS >> 6) + (threadIdx.x >> 6)) * 64; j0 < n_src; j0 += n_waves * 64) {
-        int32_t s = 0, e = 0;
-        if (j0 + wl < n_src) {
-            s = t_start[j0 + wl];
-            e = t_end[j0 + wl];
-            if (s < 0 || e < s || (int64_t)e > nnz) s = e = 0;
-        }
-        unsigned long long big = __ballot(e - s > many);
-        while (big) {      // uniform over the wavefront
-            const int b = __ffsll((long long)big) - 1;
-            big &= big - 1;
-            const int32_t s0 = __shfl(s, b, 64), e0 = __shfl(e, b, 64);
-            aggregate_backward_row<GCN>(j0 + b, s0, e0, wl, 64, dx, n, d_in, live, hit, row_start, row_end, t_row, out, out_stride, norms);
-        }
     }
 }
 
@@ -393,14 +398,17 @@ static fg_status_t layer_backward_launch(const char* who, int kind, const float*
     const int gpb = BW_THREADS >> lg;
     int64_t blocks = fg_ceil_div(n_src, gpb);
     if (blocks > 256 * 16) blocks = 256 * 16;
+    // with groups smaller than a wavefront: workgroups of their own for the positions with many incoming edges (one pass of
+    // 64 positions per wavefront)
+    const int sweep2 = lg < 6 ? (int)fg_ceil_div(n_src, 64 * (BW_THREADS / 64)) : 0;
     if (gcn)
-        hipLaunchKernelGGL(aggregate_backward_kernel<true>, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dx, n, d_in, live_dev,
-                           hit_dev, row_start_dev, row_end_dev, t_start_dev, t_end_dev, t_row_dev, nnz, n_src, (char*)dh_src_dev, dh_src_stride,
-                           lg, norms_src_dev, 16);
+        hipLaunchKernelGGL(aggregate_backward_kernel<true>, dim3((unsigned)(blocks + sweep2)), dim3(BW_THREADS), 0, st, (const char*)dx, n, d_in,
+                           live_dev, hit_dev, row_start_dev, row_end_dev, t_start_dev, t_end_dev, t_row_dev, nnz, n_src, (char*)dh_src_dev,
+                           dh_src_stride, lg, norms_src_dev, 16, sweep2);
     else
-        hipLaunchKernelGGL(aggregate_backward_kernel<false>, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dx, n, d_in, live_dev,
-                           hit_dev, row_start_dev, row_end_dev, t_start_dev, t_end_dev, t_row_dev, nnz, n_src, (char*)dh_src_dev, dh_src_stride,
-                           lg, norms_src_dev, 16);
+        hipLaunchKernelGGL(aggregate_backward_kernel<false>, dim3((unsigned)(blocks + sweep2)), dim3(BW_THREADS), 0, st, (const char*)dx, n, d_in,
+                           live_dev, hit_dev, row_start_dev, row_end_dev, t_start_dev, t_end_dev, t_row_dev, nnz, n_src, (char*)dh_src_dev,
+                           dh_src_stride, lg, norms_src_dev, 16, sweep2);
     FG_LAUNCH_CHECK("aggregate_backward_kernel");
     return FG_OK;
 }
