@@ -671,8 +671,10 @@ fg_status_t fg_layer_backward_bf16(const float* dh_dev, int64_t dh_stride, const
  *   dw[a, c] = sum_k x[k, a] * dz[k, c],  x[k, :] = [h_src[rows[k], :] ‖ agg[k, :]]   ([2*d_in x d_out], the layout of W)
  *   db[c]    = sum_k dz[k, c]                                                          (db_dev may be NULL)
  * h_src, agg, rows as given to fg_linear for this layer in the forward pass; dh, h (NULL = no activation) by position,
- * n rows. Products on the fp32 matrix cores, fp32 sums within a slice of the rows, fp64 across slices; the slicing
- * depends only on max_rows and the number of rows, so results do not depend on scheduling.
+ * n rows. Every fp32 product is formed exactly, on the bf16 matrix cores from three-way splits of both operands as in
+ * fg_linear (or on the fp32 matrix instructions where an operand ends beyond 4 GB); fp32 sums within a slice of the rows,
+ * fp64 across slices; the slicing depends only on max_rows and the number of rows, so results do not depend on
+ * scheduling. Input domain as for fg_linear.
  *   ws_dev, ws_bytes    device workspace >= fg_layer_backward_weights_workspace_bytes(max_rows, d_in, d_out), 16-byte aligned
  */
 size_t fg_layer_backward_weights_workspace_bytes(int64_t max_rows, int32_t d_in, int32_t d_out);
