@@ -84,18 +84,39 @@ __device__ __forceinline__ float bw_bf16_value(unsigned short b) { return __uint
 // matrix indexed by position and the other K/2 from one indexed by list order, so dz is written in that form:
 // columns [0, half) to dz_pos[r, :], columns [half, d) to dz_cmp[k, :].
 // BF16: the layer's output h is bf16 and dz is rounded to bf16 (the operand type of the bf16 matrix product that follows).
+// one 32 x 32 tile of wt[c, a] = w[a, c]; w is [rows x cols]
+template <typename T>
+__device__ __forceinline__ void transpose_tile(const T* __restrict__ w, int rows, int cols, T* __restrict__ wt, int bx, int by) {
+    __shared__ T tile[32][33];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
+    const int c0 = bx * 32, a0 = by * 32;
+    for (int i = ty; i < 32; i += 8)
+        if (a0 + i < rows && c0 + tx < cols) tile[i][tx] = w[(int64_t)(a0 + i) * cols + c0 + tx];
+    __syncthreads();
+    for (int i = ty; i < 32; i += 8)
+        if (c0 + i < cols && a0 + tx < rows) wt[(int64_t)(c0 + i) * rows + a0 + tx] = tile[tx][i];
+}
+
+// The first t_blocks workgroups (t_gx of them per row of tiles) transpose the layer's fp32 weights for the product that
+// follows, an independent job that would otherwise be a launch of its own; the others mask the gradient.
 template <bool BF16>
 __global__ __launch_bounds__(BW_THREADS) void relu_backward_kernel(const char* __restrict__ dh, int64_t dh_stride,
                                                                    const char* __restrict__ h, int64_t h_stride, int n,
                                                                    const int32_t* __restrict__ rows,
                                                                    const int64_t* __restrict__ n_rows_dev, int64_t max_rows,
-                                                                   int d, void* __restrict__ dz_pos_v, void* __restrict__ dz_cmp_v) {
+                                                                   int d, void* __restrict__ dz_pos_v, void* __restrict__ dz_cmp_v,
+                                                                   int t_blocks, int t_gx, const float* __restrict__ w, int w_rows,
+                                                                   int w_cols, float* __restrict__ wt) {
+    if ((int)blockIdx.x < t_blocks) {      // uniform over the workgroup
+        transpose_tile<float>(w, w_rows, w_cols, wt, (int)blockIdx.x % t_gx, (int)blockIdx.x / t_gx);
+        return;
+    }
     int64_t n_rows = n_rows_dev ? *n_rows_dev : max_rows;
     if (n_rows > max_rows) n_rows = max_rows;
     const int half = d >> 1;
     const int lane = threadIdx.x & 63;
-    const int64_t n_waves = ((int64_t)gridDim.x * BW_THREADS) >> 6;
-    for (int64_t k = ((int64_t)blockIdx.x * BW_THREADS + threadIdx.x) >> 6; k < n_rows; k += n_waves) {
+    const int64_t n_waves = ((int64_t)(gridDim.x - t_blocks) * BW_THREADS) >> 6;
+    for (int64_t k = ((int64_t)(blockIdx.x - t_blocks) * BW_THREADS + threadIdx.x) >> 6; k < n_rows; k += n_waves) {
         const int32_t r = rows ? rows[k] : (int32_t)k;
         if (r < 0 || r >= n) continue;
         const float* g = (const float*)(dh + (int64_t)r * dh_stride);
@@ -120,19 +141,6 @@ __global__ __launch_bounds__(BW_THREADS) void relu_backward_kernel(const char* _
             }
         }
     }
-}
-
-// wt[c, a] = w[a, c]; w is [rows x cols]
-template <typename T>
-__global__ __launch_bounds__(BW_THREADS) void transpose_kernel(const T* __restrict__ w, int rows, int cols, T* __restrict__ wt) {
-    __shared__ T tile[32][33];
-    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;  // 32 x 8
-    const int c0 = blockIdx.x * 32, a0 = blockIdx.y * 32;
-    for (int i = ty; i < 32; i += 8)
-        if (a0 + i < rows && c0 + tx < cols) tile[i][tx] = w[(int64_t)(a0 + i) * cols + c0 + tx];
-    __syncthreads();
-    for (int i = ty; i < 32; i += 8)
-        if (c0 + i < cols && a0 + tx < rows) wt[(int64_t)(c0 + i) * rows + a0 + tx] = tile[tx][i];
 }
 
 // Transposed mean aggregation. A group of 2^g lanes owns source position j and 16 bytes of the row per lane:
@@ -368,7 +376,8 @@ static fg_status_t layer_backward_launch(const char* who, int kind, const float*
         const dim3 tgrid((unsigned)fg_ceil_div(d_out, 32), (unsigned)fg_ceil_div(cols, 32));
         if (b16) {
             hipLaunchKernelGGL(relu_backward_kernel<true>, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dh_dev, dh_stride,
-                               (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_out, dz_pos, dz_cmp);
+                               (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_out, dz_pos, dz_cmp, 0, 1,
+                               (const float*)nullptr, 0, 0, (float*)nullptr);
             FG_LAUNCH_CHECK("relu_backward_kernel");
             // dx[r, :] = [dz_pos[r, :] ‖ dz_cmp[k, :]] . W^T, bf16 operands, fp32 sums and result. The weights of this product are
             // W^T; the matrix-core kernel takes them transposed, which is W as the caller holds it: nothing to transpose
@@ -376,11 +385,12 @@ static fg_status_t layer_backward_launch(const char* who, int kind, const float*
                                                    max_rows, half, cols, W, nullptr, 0, dx, n, (int64_t)cols * 4, FG_F32, st, true);
             if (rc != FG_OK) return rc;
         } else {
-            hipLaunchKernelGGL(relu_backward_kernel<false>, dim3((unsigned)blocks), dim3(BW_THREADS), 0, st, (const char*)dh_dev, dh_stride,
-                               (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_out, dz_pos, dz_cmp);
+            // (the transposition of W rides in the same launch: tgrid.x * tgrid.y workgroups in front of the others)
+            const int t_blocks = (int)(tgrid.x * tgrid.y);
+            hipLaunchKernelGGL(relu_backward_kernel<false>, dim3((unsigned)(blocks + t_blocks)), dim3(BW_THREADS), 0, st, (const char*)dh_dev,
+                               dh_stride, (const char*)h_dev, h_stride, n, rows_dev, n_rows_dev, max_rows, d_out, dz_pos, dz_cmp, t_blocks,
+                               (int)tgrid.x, (const float*)W, cols, d_out, (float*)wt);
             FG_LAUNCH_CHECK("relu_backward_kernel");
-            hipLaunchKernelGGL(transpose_kernel<float>, tgrid, dim3(BW_THREADS), 0, st, (const float*)W, cols, d_out, (float*)wt);
-            FG_LAUNCH_CHECK("transpose_kernel");
             // dx[r, :] = [dz_pos[r, :] ‖ dz_cmp[k, :]] . W^T for r = rows[k]: the forward GEMM with K = d_out, N = cols
             fg_status_t rc = fg_linear(dz_pos, n, (int64_t)half * 4, FG_F32, dz_cmp, (int64_t)half * 4, rows_dev, n_rows_dev, max_rows, half,
                                        cols, wt, FG_F32, nullptr, 0, dx, n, (int64_t)cols * 4, FG_F32, stream);
