@@ -235,7 +235,8 @@ def _device_update(torch, B, cache, i, ids, live, gn, p, rows, misalign=False):
 
 @pytest.mark.parametrize("dim,dtype,max_deg,n", [(64, "f32", 10, 700), (100, "f32", 15, 3000), (128, "f32", 15, 5000),
                                                  (256, "f32", 10, 900), (128, "f32", 150, 300), (768, "f16", 25, 400),
-                                                 (1024, "bf16", 15, 300), (4, "f32", 3, 50)])
+                                                 (1024, "bf16", 15, 300), (4, "f32", 3, 50),
+                                                 (320, "f32", 12, 500), (544, "f32", 8, 300)])   # 80 and 136 pieces: 32-lane groups
 def test_aggregate_matches_oracle(env, dim, dtype, max_deg, n):
     torch, B = env
     r = np.random.default_rng(dim + max_deg)
@@ -266,7 +267,8 @@ def test_aggregate_matches_oracle(env, dim, dtype, max_deg, n):
         assert empty.any() and np.all(got[:len(rows)][empty] == 0)
 
 
-@pytest.mark.parametrize("dim,dtype,max_deg,n", [(128, "f32", 15, 3000), (100, "f32", 70, 500), (768, "f16", 25, 300)])
+@pytest.mark.parametrize("dim,dtype,max_deg,n", [(128, "f32", 15, 3000), (100, "f32", 70, 500), (768, "f16", 25, 300),
+                                                 (320, "f32", 12, 400)])
 def test_gather_aggregate_equals_gather_then_aggregate(env, dim, dtype, max_deg, n):
     torch, B = env
     r = np.random.default_rng(dim + n)
