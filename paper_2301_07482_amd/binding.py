@@ -238,12 +238,7 @@ def fg_lookup_prune_static(cache, layer, it, ids, n, live, row_start, row_end, c
 
 def top_down_layers(specs):
     """ctypes array of fg_top_down_layer_t from dicts (tensors or addresses; missing keys are NULL / 0)."""
-    arr = (TopDownLayer * len(specs))()
-    for e, d in zip(arr, specs):
-        for name, ctype in TopDownLayer._fields_:
-            v = d.get(name)
-            setattr(e, name, (ptr(v) if ctype is _p else (v or 0)))
-    return arr
+    return _struct_array(TopDownLayer, specs)
 
 
 def fg_top_down_workspace_bytes(layers):
@@ -401,12 +396,23 @@ def fg_layer_backward_weights_bf16(h_src, n_src, src_stride, src_dtype, agg, agg
                                                ws_bytes, stream))
 
 
+_POINTER_FIELDS = {}
+
+
 def _struct_array(struct, specs):
+    """ctypes array of `struct` from dicts keyed by its field names. A new array is all zero bytes, so a key that is
+    missing or None stays NULL / 0; only what a dict holds is written."""
+    is_ptr = _POINTER_FIELDS.get(struct)
+    if is_ptr is None:
+        is_ptr = _POINTER_FIELDS[struct] = {name: ctype is _p for name, ctype in struct._fields_}
     arr = (struct * len(specs))()
     for a, spec in zip(arr, specs):
-        for name, ctype in struct._fields_:
-            v = spec.get(name)
-            setattr(a, name, ptr(v) if ctype is _p else (0 if v is None else v))
+        for name, v in spec.items():
+            if v is None:
+                continue
+            if is_ptr[name] and not isinstance(v, int):
+                v = v.data_ptr()
+            setattr(a, name, v)
     return arr
 
 

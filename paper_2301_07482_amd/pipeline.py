@@ -173,6 +173,10 @@ class DeviceSampler:
         return bt.finish() if finish else bt
 
 
+def _no_tick(name, stream=None):
+    return None
+
+
 class HotPath:
     """Work buffers, cache and weights of one model; `run(batch, it)` executes one iteration."""
 
@@ -236,13 +240,15 @@ class HotPath:
         self.normal_pos = [torch.zeros(n[l], dtype=torch.int32, device=dev) for l in range(L + 1)]
         self.input_ids = torch.zeros(n[0], dtype=torch.int32, device=dev)
         self.self_ids = torch.zeros(n[1], dtype=torch.int32, device=dev)
-        # what the top-down pass writes exists twice (iterations alternate), so that the pass for the next mini-batch can
-        # run while this one's layers are computed (`run(..., next_bt=...)`)
+        # what the top-down pass writes exists three times (iteration it uses set it % 3), so that the pass for the next
+        # mini-batch can run while this one's layers are computed (`run(..., next_bt=...)`) and the previous one's
+        # admitted rows are still being copied: the second stream then waits for nothing younger than the row copy of
+        # two iterations ago, and its chain selection -> next top-down pass can start before this iteration's loader
         mk = lambda dt: [torch.zeros(n[l], dtype=dt, device=dev) for l in range(L + 1)]
+        more = lambda: dict(live=mk(torch.uint8), hit=mk(torch.uint8), hit_pos=mk(torch.int32), hit_slot=mk(torch.int32),
+                            normal_pos=mk(torch.int32), input_ids=torch.zeros_like(self.input_ids), self_ids=torch.zeros_like(self.self_ids))
         self._lists = [dict(live=self.live, hit=self.hit, hit_pos=self.hit_pos, hit_slot=self.hit_slot, normal_pos=self.normal_pos,
-                            input_ids=self.input_ids, self_ids=self.self_ids),
-                       dict(live=mk(torch.uint8), hit=mk(torch.uint8), hit_pos=mk(torch.int32), hit_slot=mk(torch.int32),
-                            normal_pos=mk(torch.int32), input_ids=torch.zeros_like(self.input_ids), self_ids=torch.zeros_like(self.self_ids))]
+                            input_ids=self.input_ids, self_ids=self.self_ids), more(), more()]
         self._td_for = None      # (iteration, mini-batch) whose top-down pass has already been launched on the second stream
         self._row_copy_due = None  # (iteration, descriptors) of a selection whose rows are not copied yet
         # device-side counts/stats are kept per iteration in a ring, so a timed loop can be read back afterwards
@@ -268,12 +274,16 @@ class HotPath:
         overlap_update = overlap_update and self.n_max[0] >= overlap_min_rows
         self.overlap_update = overlap_update
         self.side = torch.cuda.Stream(device=device) if overlap_update else None
-        self.ev_pruned, self.ev_selected, self.ev_next_pruned, self.ev_done = (torch.cuda.Event() for _ in range(4))
+        self.ev_pruned, self.ev_selected, self.ev_next_pruned = (torch.cuda.Event() for _ in range(3))
+        self.ev_done = [torch.cuda.Event(), torch.cuda.Event()]     # row copy of iteration it: ev_done[it % 2]
         self.ev_bw = [torch.cuda.Event() for _ in range(L + 1)]
         self.admit_budget = dict(admit_budget) if admit_budget else None   # {layer: rows per update}: access-aware admission
         assert not (self.admit_budget and not update_all), "the access-aware admission needs fg_cache_update_all"
         self.ws_upd_bytes = sum(B.fg_workspace_bytes(B.FG_WS_CACHE_UPDATE, n[l]) for l in range(1, L))
-        self.ws_upd = torch.zeros(self.ws_upd_bytes + 256, dtype=torch.uint8, device=dev)
+        # the update's workspace exists twice (iteration it uses half it % 2): the selection of an iteration writes what
+        # that iteration's row copy reads, and the next selection may run before that copy
+        self.ws_upd_stride = -(-self.ws_upd_bytes // 256) * 256
+        self.ws_upd = torch.zeros(2 * self.ws_upd_stride + 256, dtype=torch.uint8, device=dev)
         self.W = {}
         self.Wt = {}
         self.bias = {}
@@ -353,6 +363,9 @@ class HotPath:
                                      max_admit=int(self.admit_budget.get(l, 0)) if self.admit_budget else 0, n_dev=bt.n_dev[l])
                                 for l in range(1, self.L)])
 
+    def _ws_upd(self, it):
+        return self.ws_upd.data_ptr() + (it % 2) * self.ws_upd_stride
+
     def _cnt(self, l, k):
         return self.counts.data_ptr() + (l * 3 + k) * 8
 
@@ -388,23 +401,23 @@ class HotPath:
                                   a["hit_dev"], a["hit_pos_dev"], a["hit_slot_dev"], a["normal_pos_dev"], a["normal_ids_dev"],
                                   a["counts_dev"], self.ws, self.ws_bytes, st)
 
-    def flush(self, selection_done=False):
+    def flush(self, selection_done=False, main=None):
         """Copy the rows admitted by the last iteration into the cache, if that is still due (`run` leaves it to the next
         call when that call's top-down pass is already on the second stream). Called by everything that reads the cache."""
         if self._row_copy_due is None:
             return
         it, specs = self._row_copy_due
         self._row_copy_due = None
-        main = torch.cuda.current_stream()
+        if main is None:
+            main = torch.cuda.current_stream()
         if not selection_done:
             main.wait_event(self.ev_selected)
-        B.fg_cache_update_commit(self.cache, it, specs, self.ws_upd, self.ws_upd_bytes, main.cuda_stream)
-        self.ev_done.record(main)
+        B.fg_cache_update_commit(self.cache, it, specs, self._ws_upd(it), self.ws_upd_bytes, main.cuda_stream)
+        self.ev_done[it % 2].record(main)
 
     def _bind(self, it):
         """Point the per-iteration state (lists of the top-down pass, counters, statistics) at iteration `it`'s copies."""
-        for k, v in self._lists[it % 2].items():
-            setattr(self, k, v)
+        self.__dict__.update(self._lists[it % 3])
         self.counts = self.counts_log[it % self.ring]
         self.stats = self.stats_log[it % self.ring]
 
@@ -416,9 +429,10 @@ class HotPath:
         the next call (which must be for that mini-batch and iteration) finds it done."""
         L = self.L
         self._bind(it)
-        tick = timer if timer is not None else (lambda name, stream=None: None)
+        tick = timer if timer is not None else _no_tick
         esz = B.DTYPE_SIZE
-        st = torch.cuda.current_stream().cuda_stream
+        main = torch.cuda.current_stream()      # asked for once: the query costs several microseconds of host time
+        st = main.cuda_stream
         do_update = update and self.use_cache and self.cache is not None
         # sizes still on the device: the host integers are bounds, and a layer cannot outgrow the node count
         assert all(bt.n[l] <= self.n_max[l] or bt.n_dev[l] is not None for l in range(L + 1)), "mini-batch larger than the static bounds"
@@ -431,8 +445,8 @@ class HotPath:
         pruned_ahead = promised and self._td_for[0] == it and self._td_for[1] is bt
         self._td_for = None
         if promised:      # (also when the promise was not kept: that pass writes the lists this call is about to use)
-            torch.cuda.current_stream().wait_event(self.ev_next_pruned)   # behind the previous selection on that stream
-        self.flush(selection_done=promised)
+            main.wait_event(self.ev_next_pruned)   # behind the previous selection on that stream
+        self.flush(selection_done=promised, main=main)
         if not pruned_ahead:
             self._top_down(bt, it, st, tick)
 
@@ -443,26 +457,28 @@ class HotPath:
         # advances. Copying the admitted rows over there too, beside the seed layer, measured slower than on this stream.)
         early_select = None
         if do_update and self.update_all and self.overlap_update and not self.backward and cached_layers and not self.feature_side:
-            main = torch.cuda.current_stream()
+            # (every call below names the second stream itself: torch's current stream stays the caller's)
+            side, side_st = self.side, self.side.cuda_stream
             if not pruned_ahead:
                 self.ev_pruned.record(main)
-            with torch.cuda.stream(self.side):
-                if not pruned_ahead:
-                    self.side.wait_event(self.ev_pruned)
-                self.side.wait_event(self.ev_done)     # the previous iteration's row copy has read the update's workspace
-                if self.admit_budget:
-                    self._estimates(bt, self.side.cuda_stream)
-                early_select = self._update_specs(bt, bt.gnorm)
-                B.fg_cache_update_select(self.cache, it, self.p_grad, early_select, self.ws_upd, self.ws_upd_bytes, self.side.cuda_stream)
-                self.ev_selected.record(self.side)
-                if next_bt is not None and self.one_launch_top_down:
-                    # the cache's index is final for this iteration: the next mini-batch can be looked up and pruned now,
-                    # into the other set of lists (free since the previous iteration's row copy: ev_done above)
-                    self._bind(it + 1)
-                    self._top_down(next_bt, it + 1, self.side.cuda_stream, lambda name, stream=None: None)
-                    self.ev_next_pruned.record(self.side)
-                    self._td_for = (it + 1, next_bt)
-                    self._bind(it)
+                side.wait_event(self.ev_pruned)
+            # What this selection and the top-down pass behind it overwrite (half it % 2 of the workspace, set (it + 1) % 3
+            # of the lists) was last read by iteration it - 2 and its row copy, which recorded this event (the copy of
+            # iteration it - 1, just queued, recorded the other one).
+            side.wait_event(self.ev_done[it % 2])
+            if self.admit_budget:
+                self._estimates(bt, side_st)
+            early_select = self._update_specs(bt, bt.gnorm)
+            B.fg_cache_update_select(self.cache, it, self.p_grad, early_select, self._ws_upd(it), self.ws_upd_bytes, side_st)
+            self.ev_selected.record(side)
+            if next_bt is not None and self.one_launch_top_down:
+                # the cache's index is final for this iteration: the next mini-batch can be looked up and pruned now,
+                # into the next set of lists (free since the row copy of two iterations ago: ev_done above)
+                self._bind(it + 1)
+                self._top_down(next_bt, it + 1, side_st, _no_tick)
+                self.ev_next_pruned.record(side)
+                self._td_for = (it + 1, next_bt)
+                self._bind(it)
         fetch_specs = None
         if self.fetch_all and cached_layers:
             fetch_specs = B.fetch_layers([dict(layer=l, hit_slot_dev=self.hit_slot[l], hit_pos_dev=self.hit_pos[l],
@@ -609,7 +625,7 @@ class HotPath:
                 tick("access_estimate")
                 self._estimates(bt, st)
             tick("cache_update_all")
-            B.fg_cache_update_all(self.cache, it, self.p_grad, self._update_specs(bt, gnorm), self.ws_upd, self.ws_upd_bytes, st)
+            B.fg_cache_update_all(self.cache, it, self.p_grad, self._update_specs(bt, gnorm), self._ws_upd(it), self.ws_upd_bytes, st)
         elif do_update:
             for l in range(1, L):
                 out_b = self.dims[l] * esz[self.h_code[l]]
