@@ -522,15 +522,17 @@ def alone_step(k, steps, bracket_every):
 def timed_region(hp, batches, first_timed, steps, total, bracket_every, lookahead, bracketed):
     """Exactly `steps` iterations (mini-batches first_timed ..) between two device synchronisations. HIP events on the
     launch stream bracket only the calls named in `bracketed`, and only on every `bracket_every`-th step, so that the
-    region is not perturbed (an event record costs about 3 us of stream time). Two kinds of bracketed steps: every
-    `bracket_every`-th step runs with every call on the one stream, so that the bracketed launches have the chip to
-    themselves (the durations `roofline` is priced on, comparable with a kernel trace; the first of these steps comes half
-    a period into the region, see alone_step); half way between them a step is bracketed as it normally runs, with the
-    bookkeeping launches of the second stream beside it.
+    region is not perturbed (an event record costs about 3 us of stream time). Two kinds of bracketed steps: in every
+    `bracket_every`-th step the bracketed launches have the chip to themselves (the durations `roofline` is priced on,
+    comparable with a kernel trace; the first of these steps comes half a period into the region, see alone_step): the
+    second stream's bookkeeping of that step is held back until layer 1 is done, or, where the pipeline has nothing to
+    hold (backward pass, feature side), every call of the step runs on the one stream; half way between them a step is
+    bracketed as it normally runs, with the bookkeeping launches of the second stream beside it.
     Returns (seconds, {call: ms} of the one-stream steps, {call: ms} of the overlapped steps)."""
     import torch
     ev, ev_ovl = [], []
     overlapped = hp.overlap_update
+    can_hold = hp.holds_second_stream()
     torch.cuda.synchronize()
     t_start = time.perf_counter()
     for k in range(steps):
@@ -538,9 +540,11 @@ def timed_region(hp, batches, first_timed, steps, total, bracket_every, lookahea
         step_events = {}
         alone = alone_step(k, steps, bracket_every)
         beside = overlapped and k > 0 and k % bracket_every == 0
-        ahead = batches[it + 1] if (it + 1 < total and lookahead and not alone) else None   # its top-down pass runs beside this step's layers
-        hp.overlap_update = overlapped and not alone
-        hp.run(batches[it], it, timer=timer_for(step_events, only=bracketed) if (alone or beside) else None, next_bt=ahead)
+        ahead = batches[it + 1] if (it + 1 < total and lookahead and (can_hold or not alone)) else None   # its top-down pass runs beside this step's layers
+        if not can_hold:
+            hp.overlap_update = overlapped and not alone
+        hp.run(batches[it], it, timer=timer_for(step_events, only=bracketed) if (alone or beside) else None, next_bt=ahead,
+               hold_second_stream=alone and can_hold)
         (ev if alone else ev_ovl).append(step_events)
     hp.flush()      # the last step's row copy (left to the next call when that call's top-down pass is already queued) belongs to it
     torch.cuda.synchronize()

@@ -421,12 +421,14 @@ class HotPath:
         self.counts = self.counts_log[it % self.ring]
         self.stats = self.stats_log[it % self.ring]
 
-    def run(self, bt, it, update=True, timer=None, next_bt=None):
+    def run(self, bt, it, update=True, timer=None, next_bt=None, hold_second_stream=False):
         """One iteration on torch's current stream. `timer(name, stream)` (optional) is called before each C-ABI call
         and with name None after the last call of a stream (stream None = the current stream).
         next_bt: the mini-batch of iteration it + 1, if the caller has it: where the update's selection runs on the second
         stream (see below), the top-down pass of that mini-batch follows it there, beside this iteration's layers, and
-        the next call (which must be for that mini-batch and iteration) finds it done."""
+        the next call (which must be for that mini-batch and iteration) finds it done.
+        hold_second_stream: what this call puts on the second stream starts only when layer 1 is done, so that the loader and
+        the layer-1 dense update have the chip to themselves (for a caller that times these two launches)."""
         L = self.L
         self._bind(it)
         tick = timer if timer is not None else _no_tick
@@ -456,10 +458,11 @@ class HotPath:
         # (Not with raw features in the cache's buffer: the loader reads the rings' written extents, which the selection
         # advances. Copying the admitted rows over there too, beside the seed layer, measured slower than on this stream.)
         early_select = None
-        if do_update and self.update_all and self.overlap_update and not self.backward and cached_layers and not self.feature_side:
+
+        def second_stream():
             # (every call below names the second stream itself: torch's current stream stays the caller's)
             side, side_st = self.side, self.side.cuda_stream
-            if not pruned_ahead:
+            if not pruned_ahead or hold_second_stream:
                 self.ev_pruned.record(main)
                 side.wait_event(self.ev_pruned)
             # What this selection and the top-down pass behind it overwrite (half it % 2 of the workspace, set (it + 1) % 3
@@ -468,8 +471,8 @@ class HotPath:
             side.wait_event(self.ev_done[it % 2])
             if self.admit_budget:
                 self._estimates(bt, side_st)
-            early_select = self._update_specs(bt, bt.gnorm)
-            B.fg_cache_update_select(self.cache, it, self.p_grad, early_select, self._ws_upd(it), self.ws_upd_bytes, side_st)
+            specs = self._update_specs(bt, bt.gnorm)
+            B.fg_cache_update_select(self.cache, it, self.p_grad, specs, self._ws_upd(it), self.ws_upd_bytes, side_st)
             self.ev_selected.record(side)
             if next_bt is not None and self.one_launch_top_down:
                 # the cache's index is final for this iteration: the next mini-batch can be looked up and pruned now,
@@ -479,6 +482,11 @@ class HotPath:
                 self.ev_next_pruned.record(side)
                 self._td_for = (it + 1, next_bt)
                 self._bind(it)
+            return specs
+
+        beside = do_update and self.update_all and self.overlap_update and not self.backward and bool(cached_layers) and not self.feature_side
+        if beside and not hold_second_stream:
+            early_select = second_stream()
         fetch_specs = None
         if self.fetch_all and cached_layers:
             fetch_specs = B.fetch_layers([dict(layer=l, hit_slot_dev=self.hit_slot[l], hit_pos_dev=self.hit_pos[l],
@@ -504,6 +512,8 @@ class HotPath:
                             self.H[0], bt.n[0], d0b, self.on_host, st)
         # ---- bottom-up: cached rows, mean aggregation, dense update
         for l in range(1, L + 1):
+            if beside and hold_second_stream and l == 2:     # (a cache has layers, so L >= 2 here)
+                early_select = second_stream()
             in_code, out_code = self.h_code[l - 1], self.h_code[l]
             in_b = self.dims[l - 1] * esz[in_code]
             out_b = self.dims[l] * esz[out_code]
@@ -636,6 +646,11 @@ class HotPath:
             self.ev_bw[0].record(self.side)       # the next iteration overwrites what the weight gradients read
             torch.cuda.current_stream().wait_event(self.ev_bw[0])
         tick(None)
+
+    def holds_second_stream(self):
+        """Whether `run(..., hold_second_stream=True)` has work on a second stream to hold back."""
+        return bool(self.overlap_update and self.update_all and self.use_cache and self.cache is not None and self.L > 1
+                    and not self.backward and not self.feature_side)
 
     def own_rows_from_table(self, bt):
         """Whether layer 1's dense update of this mini-batch reads the nodes' own features from the table itself (fp32 table

@@ -1533,6 +1533,49 @@ def test_lookahead_promise_not_kept(env):
         ref.close()
 
 
+def test_iterations_queued_back_to_back_match_one_at_a_time(env):
+    """Fourteen iterations of the medium workload queued without a synchronisation in between, each mini-batch announced
+    to the iteration before it (so the second stream runs up to a step ahead, over three sets of lists and two halves of
+    the update's workspace; in two of the iterations it is held back until layer 1 is done), leave the same outputs,
+    counters, statistics and caches as the same iterations run one at a time on one stream."""
+    torch, B = env
+    from paper_2301_07482_amd.pipeline import DeviceBatch
+    w = wl.WORKLOADS["medium"]
+    g = wl.make_graph(w)
+    L, K = w.num_layers, 14
+    hp, weights, _ = G.make_hotpath(w, fused_input=True, fuse_small_layers=True, log_ring=K + 2)
+    ref, _, _ = G.make_hotpath(w, fused_input=True, fuse_small_layers=True, overlap_update=False, log_ring=K + 2)
+    try:
+        assert hp.holds_second_stream() and not ref.holds_second_stream()
+        mbs = [wl.minibatch(w, g, it) for it in range(K)]
+        batches = [DeviceBatch(mb, {l: wl.grad_norms(w, it, l, mb.ids[l]) for l in range(1, L)}, col_ids=True) for it, mb in enumerate(mbs)]
+        n_out = [len(mb.ids[L]) for mb in mbs]
+        torch.cuda.synchronize()
+        outs = []
+        for it in range(K):
+            hp.run(batches[it], it, next_bt=batches[it + 1] if it + 1 < K else None, hold_second_stream=it in (4, 9))
+            outs.append(hp.H[L][:n_out[it]].clone())      # a copy on the same stream, in order: no synchronisation
+        hp.flush()
+        torch.cuda.synchronize()
+        hits = 0
+        for it in range(K):
+            ref.run(batches[it], it)
+            torch.cuda.synchronize()
+            assert torch.equal(outs[it], ref.H[L][:n_out[it]]), f"outputs, iteration {it}"
+            assert torch.equal(hp.counts_log[it], ref.counts_log[it]), f"counters, iteration {it}"
+            assert torch.equal(hp.stats_log[it], ref.stats_log[it]), f"update statistics, iteration {it}"
+            hits += int(ref.counts_log[it][1:L, 1].sum().item())
+        assert hits > 1000, f"only {hits} cache hits: the caches were hardly used"
+        for l in range(1, L):
+            ea, eb = hp.export_cache(l, K), ref.export_cache(l, K)
+            assert ea["head"] == eb["head"] and np.array_equal(ea["nodes"], eb["nodes"]) and np.array_equal(ea["slots"], eb["slots"]) \
+                and np.array_equal(ea["stamps"], eb["stamps"])
+            assert np.array_equal(hp.cache_rows(l, ea["slots"][:4000]), ref.cache_rows(l, eb["slots"][:4000])), f"cached rows, layer {l}"
+    finally:
+        hp.close()
+        ref.close()
+
+
 def test_iterations_tiny_layer_by_layer_top_down(env):
     """The same iterations with one fg_lookup_prune and one fg_cache_update call per layer instead of fg_top_down and
     fg_cache_update_all."""
