@@ -250,6 +250,7 @@ def main():
     elapsed, timed_ms, timed_ovl_ms = timed_region(hp, batches, first_timed, args.steps, total, args.bracket_every,
                                                    not args.no_lookahead, BRACKETED)
     ms_per_step = 1e3 * elapsed / args.steps
+    host_ms_per_step = 1e3 * timed_region.host_seconds / args.steps      # host time to queue a step's launches (below ms_per_step: the device is the bound)
     value = args.steps / elapsed
 
     # breakdown pass (not part of `value`): the iterations that follow the timed ones, on their own mini-batches, with
@@ -476,7 +477,7 @@ def main():
                      "hits": hits, "gather_bytes": gather_bytes, "linear_flops": lin_flops},
         "admit_budget": admit_budget,
         "sampler": sampler_report,
-        "host": {"sampling_s": t_sample, "setup_s": t_setup},
+        "host": {"sampling_s": t_sample, "setup_s": t_setup, "queueing_ms_per_step": host_ms_per_step},
     }
     print(json.dumps(out))
 
@@ -547,9 +548,11 @@ def timed_region(hp, batches, first_timed, steps, total, bracket_every, lookahea
                hold_second_stream=alone and can_hold)
         (ev if alone else ev_ovl).append(step_events)
     hp.flush()      # the last step's row copy (left to the next call when that call's top-down pass is already queued) belongs to it
+    t_queued = time.perf_counter()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     hp.overlap_update = overlapped
+    timed_region.host_seconds = t_queued - t_start      # the host's own share: every launch of the region is queued by then
     return elapsed, spans(ev), spans(ev_ovl)
 
 
@@ -707,9 +710,11 @@ def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False, lookahead=T
         hp.run(cur, first_it + t, next_bt=nxt if lookahead else None)
         consumed_ev[t % K].record(main)
         cur = nxt
+    t_queued = time.time()      # everything is queued: the host's own share of the loop
     torch.cuda.synchronize()
     dt = time.time() - t_start
     return {"steps": steps, "warmup": warmup, "ms_per_step": 1e3 * dt / steps, "minibatches_per_s": steps / dt,
+            "host_ms_per_step": 1e3 * (t_queued - t_start) / steps,
             "host_synchronisations_per_minibatch": 1 if host_sizes else 0,
             "note": "sampling (a stream of its own, two mini-batches ahead), gradient norms and the whole path inside the timed loop; "
                     + ("layer sizes read back through a pinned copy" if host_sizes else "layer sizes never leave the device")}
