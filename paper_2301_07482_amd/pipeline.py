@@ -485,8 +485,19 @@ class HotPath:
             return specs
 
         beside = do_update and self.update_all and self.overlap_update and not self.backward and bool(cached_layers) and not self.feature_side
+        held = {"due": False, "specs": None}
         if beside and not hold_second_stream:
             early_select = second_stream()
+        elif beside:
+            # released at the first call of layer 2, right behind the caller's timer: an event the timer records there closes
+            # the span of layer 1's dense update before the release's own event is queued
+            timer_tick = tick
+
+            def tick(name, stream=None):
+                timer_tick(name, stream)
+                if held["due"]:
+                    held["due"] = False
+                    held["specs"] = second_stream()
         fetch_specs = None
         if self.fetch_all and cached_layers:
             fetch_specs = B.fetch_layers([dict(layer=l, hit_slot_dev=self.hit_slot[l], hit_pos_dev=self.hit_pos[l],
@@ -513,7 +524,7 @@ class HotPath:
         # ---- bottom-up: cached rows, mean aggregation, dense update
         for l in range(1, L + 1):
             if beside and hold_second_stream and l == 2:     # (a cache has layers, so L >= 2 here)
-                early_select = second_stream()
+                held["due"] = True
             in_code, out_code = self.h_code[l - 1], self.h_code[l]
             in_b = self.dims[l - 1] * esz[in_code]
             out_b = self.dims[l] * esz[out_code]
@@ -625,6 +636,8 @@ class HotPath:
                     tick(f"weight_grads[{l}]")
                     weight_grads(l, st)
         # ---- update of the caches
+        if held["specs"] is not None:
+            early_select = held["specs"]
         if early_select is not None:      # the selection ran beside the layers: only the admitted rows are left to copy
             self._row_copy_due = (it, early_select)
             if self._td_for is None:      # otherwise the next call does it, behind the wait it has anyway (one wait less per step)
