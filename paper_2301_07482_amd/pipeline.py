@@ -636,6 +636,9 @@ class HotPath:
                     tick(f"weight_grads[{l}]")
                     weight_grads(l, st)
         # ---- update of the caches
+        if held["due"]:           # no timed call came after layer 1
+            held["due"] = False
+            held["specs"] = second_stream()
         if held["specs"] is not None:
             early_select = held["specs"]
         if early_select is not None:      # the selection ran beside the layers: only the admitted rows are left to copy
