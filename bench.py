@@ -672,7 +672,7 @@ def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False, lookahead=T
         with torch.cuda.stream(side):
             if t >= K:
                 side.wait_event(consumed_ev[k])        # the path is done with this set of buffers
-            bt = ds.sample(seeds[t], keys[t], finish=False, out=outs[k])
+            bt = ds.sample(seeds[t], keys[t], finish=False, out=outs[k], ready=False)
             if backward:          # the norms come from the backward pass; it needs the seeds' classes
                 bt.labels = labels[t]
             else:
@@ -682,16 +682,16 @@ def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False, lookahead=T
             if host_sizes:
                 host_counts[k].copy_(bt._counts, non_blocking=True)
             sampled_ev[k].record(side)
+            bt.ready = sampled_ev[k]       # behind the norms as well: what the path's second stream waits for
         return bt
 
     def ready(t, bt):
-        """Mini-batch t with the path's stream behind its sampling (host_sizes: and its layer sizes on the host)."""
+        """Mini-batch t as the path takes it (host_sizes: with its layer sizes on the host)."""
         k = t % K
         if host_sizes:
             sampled_ev[k].synchronize()
             bt.finish(host_counts[k])
-        main.wait_event(sampled_ev[k])
-        return bt
+        return bt      # (its `ready` event orders the path's streams behind the sampling: HotPath.run)
 
     # the sampler works two mini-batches ahead, so that the next one is complete (sizes known) when this one is run and
     # its top-down pass can go to the second stream beside this one's layers
@@ -708,7 +708,10 @@ def sampled_loop(w, hp, ds, first_it, steps, warmup, backward=False, lookahead=T
             queue[t + 2] = launch(t + 2)
         nxt = ready(t + 1, queue.pop(t + 1)) if t + 1 < n_it else None
         hp.run(cur, first_it + t, next_bt=nxt if lookahead else None)
-        consumed_ev[t % K].record(main)
+        # the buffers of mini-batch t - 1 are free once this call's launches are through: the call started behind the second
+        # stream's last reads of that mini-batch (its update's selection), and its own launches follow the row copy
+        if t >= 1:
+            consumed_ev[(t - 1) % K].record(main)
         cur = nxt
     t_queued = time.time()      # everything is queued: the host's own share of the loop
     torch.cuda.synchronize()

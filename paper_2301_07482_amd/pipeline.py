@@ -33,6 +33,7 @@ class DeviceBatch:
         the norms come from the backward pass; the blocks' transposes are then uploaded too."""
         L = mb.num_layers
         self.num_layers = L
+        self.ready = None      # the uploads below are complete when they return: nothing for `HotPath.run` to wait for
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(device)
         self.n = [len(x) for x in mb.ids]
         self.n_dev = [None] * (L + 1)       # the layer sizes are host integers
@@ -77,6 +78,9 @@ class SampledBatch:
         self.labels = None
         self.t_start, self.t_end, self.t_row = [None] * (L + 1), [None] * (L + 1), [None] * (L + 1)
         self._counts = self._bound = self._n_seeds = None
+        # recorded behind the sampling launches (`DeviceSampler.sample`); a caller that adds to the mini-batch on the device
+        # afterwards (norms, labels) records its own event behind that work and puts it here
+        self.ready = None
 
     def finish(self, host_counts=None):
         """Read the layer sizes back (synchronises with the sampling launches) and cut the arrays to them. host_counts: the
@@ -134,10 +138,11 @@ class DeviceSampler:
         return (torch.empty(self.out_elems, dtype=torch.int32, device=self.device),
                 torch.empty((self.L + 1, 2), dtype=torch.int64, device=self.device))
 
-    def sample(self, seeds, key, finish=True, out=None):
+    def sample(self, seeds, key, finish=True, out=None, ready=True):
         """seeds: int32 device tensor of distinct node ids (at most `batch`); key: the mini-batch's 64-bit key.
         finish=False: only the launches; `SampledBatch.finish()` later reads the counts back (sampling ahead of the
-        consumer needs no synchronisation per mini-batch that way)."""
+        consumer needs no synchronisation per mini-batch that way). ready=False: no event is recorded behind the launches
+        (the caller sets the mini-batch's `ready` itself, behind whatever it adds on the device)."""
         L, dev = self.L, self.device
         st = torch.cuda.current_stream().cuda_stream
         bt = SampledBatch(L)
@@ -170,6 +175,9 @@ class DeviceSampler:
             bt.n_dev[l] = cp + 16 * l if l < L else None
         for l in range(1, L + 1):
             bt.nnz[l] = (self.bound[l] if l < L else n_seeds) * self.fanouts[l - 1]
+        if ready:
+            bt.ready = torch.cuda.Event()
+            bt.ready.record(torch.cuda.current_stream())
         return bt.finish() if finish else bt
 
 
@@ -250,6 +258,7 @@ class HotPath:
         self._lists = [dict(live=self.live, hit=self.hit, hit_pos=self.hit_pos, hit_slot=self.hit_slot, normal_pos=self.normal_pos,
                             input_ids=self.input_ids, self_ids=self.self_ids), more(), more()]
         self._td_for = None      # (iteration, mini-batch) whose top-down pass has already been launched on the second stream
+        self._ready_waited = None  # the mini-batch whose `ready` event the second stream waited for in the previous call
         self._row_copy_due = None  # (iteration, descriptors) of a selection whose rows are not copied yet
         # device-side counts/stats are kept per iteration in a ring, so a timed loop can be read back afterwards
         self.ring = int(log_ring)
@@ -428,7 +437,14 @@ class HotPath:
         stream (see below), the top-down pass of that mini-batch follows it there, beside this iteration's layers, and
         the next call (which must be for that mini-batch and iteration) finds it done.
         hold_second_stream: what this call puts on the second stream starts only when layer 1 is done, so that the loader and
-        the layer-1 dense update have the chip to themselves (for a caller that times these two launches)."""
+        the layer-1 dense update have the chip to themselves (for a caller that times these two launches).
+        Ordering of the inputs: the arrays of `bt` and `next_bt` (norms and labels included) are read on torch's current
+        stream and, where the update's selection and the next top-down pass run there, on the second stream, which does not
+        follow the current stream call by call (it runs up to an iteration ahead). Arrays that are complete when `run` is
+        called need nothing (`DeviceBatch`); a mini-batch still being written on the device carries an event recorded behind
+        its last write in `ready` (`DeviceSampler.sample` sets it), and both streams are ordered behind it here (the
+        current stream directly when this call runs the top-down pass itself, else through the second stream, which waited
+        for it in the call that announced the mini-batch)."""
         L = self.L
         self._bind(it)
         tick = timer if timer is not None else _no_tick
@@ -446,6 +462,8 @@ class HotPath:
         promised = self._td_for is not None
         pruned_ahead = promised and self._td_for[0] == it and self._td_for[1] is bt
         self._td_for = None
+        if not pruned_ahead and getattr(bt, "ready", None) is not None:
+            main.wait_event(bt.ready)      # this call's own launches are the first to read the mini-batch
         if promised:      # (also when the promise was not kept: that pass writes the lists this call is about to use)
             main.wait_event(self.ev_next_pruned)   # behind the previous selection on that stream
         self.flush(selection_done=promised, main=main)
@@ -462,6 +480,10 @@ class HotPath:
         def second_stream():
             # (every call below names the second stream itself: torch's current stream stays the caller's)
             side, side_st = self.side, self.side.cuda_stream
+            for b in (bt, next_bt):      # mini-batches still being written on the device when this call was made
+                if b is not None and b is not self._ready_waited and getattr(b, "ready", None) is not None:
+                    side.wait_event(b.ready)
+            self._ready_waited = next_bt      # (the next call's `bt`: already waited for)
             if not pruned_ahead or hold_second_stream:
                 self.ev_pruned.record(main)
                 side.wait_event(self.ev_pruned)

@@ -1576,6 +1576,60 @@ def test_iterations_queued_back_to_back_match_one_at_a_time(env):
         ref.close()
 
 
+def test_device_sampled_iterations_queued_back_to_back(env):
+    """Mini-batches sampled on the device (and their norms made there) on the current stream right before the call that
+    announces them, twelve iterations queued without a synchronisation: the second stream, which runs ahead of the current
+    one, must still read each mini-batch only after it is complete (the `ready` event). Same outputs, counters and
+    statistics as the same iterations one at a time on one stream."""
+    torch, B = env
+    import dataclasses
+    from fg_inputs import device as fdev, rng
+    from paper_2301_07482_amd.pipeline import DeviceSampler
+    w = dataclasses.replace(wl.WORKLOADS["large_hbm"], name="large_hbm/small", num_nodes=200_000, num_edges=4_000_000, batch=128,
+                            train_nodes=20_000, cache_capacity=20_000, t_stale=6)
+    indptr, indices = fdev.chunglu_csr(wl.make_graph(w))
+    L, K = w.num_layers, 12
+
+    def sample(ds, it):
+        seeds = torch.from_numpy(wl.seed_nodes(w, it).astype(np.int32)).cuda()
+        bt = ds.sample(seeds, int(rng.make_key(w.seed, 0x5A3, it)), finish=False, ready=False)
+        st = torch.cuda.current_stream()
+        for l in range(1, L):
+            bt.gnorm[l] = torch.empty(ds.bound[l], dtype=torch.float32, device="cuda")
+            fdev.grad_norms(bt.ids[l], bt._counts.data_ptr() + 16 * l, ds.bound[l], int(rng.make_key(w.seed, 0x6AD, it, l)),
+                            bt.gnorm[l], st.cuda_stream)
+        bt.ready = torch.cuda.Event()
+        bt.ready.record(st)
+        return bt
+
+    hp, _, feat = G.make_hotpath(w, fused_input=True, fuse_small_layers=True, p_grad=0.7, log_ring=K + 2)
+    ref, _, _ = G.make_hotpath(w, feat_table=feat, fused_input=True, fuse_small_layers=True, p_grad=0.7, overlap_update=False, log_ring=K + 2)
+    try:
+        assert hp.holds_second_stream()
+        ds = DeviceSampler(indptr, indices, w.num_nodes, w.fanouts, w.batch)
+        torch.cuda.synchronize()
+        outs, nxt = [], sample(ds, 0)
+        for it in range(K):
+            cur = nxt
+            nxt = sample(ds, it + 1) if it + 1 < K else None
+            hp.run(cur, it, next_bt=nxt)
+            outs.append(hp.H[L][:w.batch].clone())
+        hp.flush()
+        torch.cuda.synchronize()
+        hits = 0
+        for it in range(K):
+            ref.run(sample(ds, it), it)
+            torch.cuda.synchronize()
+            assert torch.equal(outs[it], ref.H[L][:w.batch]), f"outputs, iteration {it}"
+            assert torch.equal(hp.counts_log[it], ref.counts_log[it]), f"counters, iteration {it}"
+            assert torch.equal(hp.stats_log[it], ref.stats_log[it]), f"update statistics, iteration {it}"
+            hits += int(ref.counts_log[it][1:L, 1].sum().item())
+        assert hits > 0
+    finally:
+        hp.close()
+        ref.close()
+
+
 def test_iterations_tiny_layer_by_layer_top_down(env):
     """The same iterations with one fg_lookup_prune and one fg_cache_update call per layer instead of fg_top_down and
     fg_cache_update_all."""
